@@ -1,0 +1,355 @@
+/*
+ * CPU oracle for the masked full-neighbourhood GNN layer path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain loops, double precision, written from the
+ * paper's definitions; it shares no code with the HIP library and must never
+ * be called from the product path (only tests, the smoke check and the CPU
+ * baseline leg of the benchmark use it).
+ *
+ * What it follows:
+ *   - layer equation of section 2.1:  h_N(v) = AGGREGATE({h_u : u in N(v)}),
+ *     h_v = F(h_v, h_N(v)), AGGREGATE a (scaled) sum, F = weights then sigma;
+ *   - one-hop graph masking of section 6 (figure 7c, steps 1-5): ONE one-hop
+ *     graph is reused by every layer, and layer l only produces the vertices
+ *     that the targets' exact dependency still needs;
+ *   - expansion-aware sampling of section 5.3: inner dependencies are kept
+ *     whole, only edges that leave the target set are thinned, at most
+ *     `fanout` per boundary vertex.
+ *
+ * Conventions.  L layers numbered l = 1..L.  T = target (inner) vertices.
+ * Row v of the CSR lists the vertices u that v aggregates.  dist(v) = number
+ * of hops from T to v following rows (dist = 0 on T).  Layer l computes the
+ * rows R_l = {v : dist(v) <= L - l}; R_L = T.
+ *
+ * Every pin of this file (dense brute force, finite differences, closed forms,
+ * the published splitmix64 vector) lives in tests/test_oracle_*.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------------- */
+/* Active sets: breadth-first levels from T over rows, capped at L.        */
+/* Section 6, step 1 ("extract the multi-hop dependency starting from the  */
+/* inner vertices") and step 4 (per-layer mask).                           */
+/*   dist[v]      hop distance, -1 if v is farther than L hops or unreachable */
+/*   ring_ids     vertices sorted by (dist, id); ring j = vertices at dist j  */
+/*   hop_offsets  [L+2]; ring j is ring_ids[hop_offsets[j] .. hop_offsets[j+1]) */
+/* ---------------------------------------------------------------------- */
+int orc_active_sets(int32_t n, const int32_t *row_ptr, const int32_t *col_idx,
+                    const int32_t *targets, int32_t n_targets, int32_t L,
+                    int32_t *dist, int32_t *ring_ids, int64_t *hop_offsets)
+{
+    for (int32_t v = 0; v < n; ++v) dist[v] = -1;
+    for (int32_t i = 0; i < n_targets; ++i) {
+        if (targets[i] < 0 || targets[i] >= n) return 1;
+        dist[targets[i]] = 0;                 /* duplicates: set semantics */
+    }
+    for (int32_t j = 0; j < L; ++j) {
+        /* every vertex at distance j opens its row; unseen entries get j+1 */
+        for (int32_t v = 0; v < n; ++v) {
+            if (dist[v] != j) continue;
+            for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                int32_t u = col_idx[e];
+                if (dist[u] < 0) dist[u] = j + 1;
+            }
+        }
+    }
+    int64_t pos = 0;
+    for (int32_t j = 0; j <= L; ++j) {
+        hop_offsets[j] = pos;
+        for (int32_t v = 0; v < n; ++v)
+            if (dist[v] == j) ring_ids[pos++] = v;
+    }
+    hop_offsets[L + 1] = pos;
+    return 0;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Normalisation factors (reading of "AGGREGATE ... usually the summation" */
+/* for the two named models).  mode 1: mean, 1/len (0 for an empty row).   */
+/* mode 2: symmetric GCN, len^-1/2 (len counts the self loop in the graph).*/
+/* ---------------------------------------------------------------------- */
+void orc_norm_scales(int32_t mode, const int32_t *len, int32_t n, double *out)
+{
+    for (int32_t v = 0; v < n; ++v) {
+        if (len[v] <= 0) out[v] = 0.0;
+        else if (mode == 1) out[v] = 1.0 / (double)len[v];
+        else out[v] = 1.0 / sqrt((double)len[v]);
+    }
+}
+
+/* ---------------------------------------------------------------------- */
+/* Masked aggregation, forward (section 2.1 equation, first half):         */
+/*   Y[v,:] = rs[v] * sum_{u in row(v)} cs[u] * X[u,:]   for v in rows     */
+/* rows == NULL means 0..n_active-1.  rs/cs NULL means 1.  Rows outside    */
+/* the list are not touched (masked vertices are never read afterwards).   */
+/* ---------------------------------------------------------------------- */
+void orc_spmm_fwd(const int32_t *row_ptr, const int32_t *col_idx,
+                  const int32_t *rows, int32_t n_active,
+                  const double *X, int64_t ldx, double *Y, int64_t ldy, int32_t F,
+                  const double *rs, const double *cs)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int32_t i = 0; i < n_active; ++i) {
+        int32_t v = rows ? rows[i] : i;
+        double *y = Y + (int64_t)v * ldy;
+        for (int32_t f = 0; f < F; ++f) y[f] = 0.0;
+        for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+            int32_t u = col_idx[e];
+            double w = cs ? cs[u] : 1.0;
+            const double *x = X + (int64_t)u * ldx;
+            for (int32_t f = 0; f < F; ++f) y[f] += w * x[f];
+        }
+        if (rs)
+            for (int32_t f = 0; f < F; ++f) y[f] *= rs[v];
+    }
+}
+
+/* ---------------------------------------------------------------------- */
+/* Masked aggregation, backward = adjoint of the forward map, written as   */
+/* the scatter the chain rule gives over the SAME (forward) CSR:           */
+/*   for v in rows, u in row(v):  dX[u,:] += cs[u] * rs[v] * dY[v,:]       */
+/* dX is accumulated into (caller zeroes it).  Threads split the feature   */
+/* columns, so no two threads touch the same element.                      */
+/* ---------------------------------------------------------------------- */
+void orc_spmm_bwd(const int32_t *row_ptr, const int32_t *col_idx,
+                  const int32_t *rows, int32_t n_active,
+                  const double *dY, int64_t lddy, double *dX, int64_t lddx, int32_t F,
+                  const double *rs, const double *cs)
+{
+    const int32_t CB = 16;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t f0 = 0; f0 < F; f0 += CB) {
+        int32_t f1 = f0 + CB < F ? f0 + CB : F;
+        for (int32_t i = 0; i < n_active; ++i) {
+            int32_t v = rows ? rows[i] : i;
+            const double *dy = dY + (int64_t)v * lddy;
+            double wv = rs ? rs[v] : 1.0;
+            for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                int32_t u = col_idx[e];
+                double w = wv * (cs ? cs[u] : 1.0);
+                double *dx = dX + (int64_t)u * lddx;
+                for (int32_t f = f0; f < f1; ++f) dx[f] += w * dy[f];
+            }
+        }
+    }
+}
+
+/* ---------------------------------------------------------------------- */
+/* Feature transform, forward (section 2.1 equation, second half):         */
+/*   Z[v,:] = A[v,:] W_neigh (+ X_self[v,:] W_self) + bias                 */
+/*   H[v,:] = relu ? max(Z,0) : Z          for v in rows                   */
+/* A, X_self: [*, K] with leading dimension ld_in; W: [K, N] row-major.    */
+/* ---------------------------------------------------------------------- */
+void orc_linear_fwd(const int32_t *rows, int32_t n_active,
+                    const double *A, const double *X_self, int64_t ld_in, int32_t K,
+                    const double *W_neigh, const double *W_self, const double *bias, int32_t N,
+                    double *H, int64_t ld_out, int32_t relu)
+{
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < n_active; ++i) {
+        int32_t v = rows ? rows[i] : i;
+        double *h = H + (int64_t)v * ld_out;
+        for (int32_t j = 0; j < N; ++j) h[j] = bias ? bias[j] : 0.0;
+        const double *a = A + (int64_t)v * ld_in;
+        for (int32_t k = 0; k < K; ++k)
+            for (int32_t j = 0; j < N; ++j) h[j] += a[k] * W_neigh[(int64_t)k * N + j];
+        if (X_self) {
+            const double *x = X_self + (int64_t)v * ld_in;
+            for (int32_t k = 0; k < K; ++k)
+                for (int32_t j = 0; j < N; ++j) h[j] += x[k] * W_self[(int64_t)k * N + j];
+        }
+        if (relu)
+            for (int32_t j = 0; j < N; ++j) h[j] = h[j] > 0.0 ? h[j] : 0.0;
+    }
+}
+
+/* ---------------------------------------------------------------------- */
+/* Feature transform, backward (chain rule of the above):                  */
+/*   dZ = relu ? dH * [H > 0] : dH                                          */
+/*   dW_neigh = A[rows]^T dZ,  dW_self = X_self[rows]^T dZ,  dbias = sum dZ */
+/*   dA[v,:] = dZ W_neigh^T,   dX_self[v,:] = dZ W_self^T   (v in rows)     */
+/* dW_*, dbias are overwritten.  dA / dX_self rows in the list are         */
+/* overwritten; either may be NULL to skip.  H may be NULL when relu == 0.  */
+/* ---------------------------------------------------------------------- */
+void orc_linear_bwd(const int32_t *rows, int32_t n_active,
+                    const double *dH, int64_t ld_dh, const double *H, int64_t ld_h, int32_t relu,
+                    const double *A, const double *X_self, int64_t ld_in, int32_t K,
+                    const double *W_neigh, const double *W_self, int32_t N,
+                    double *dW_neigh, double *dW_self, double *dbias,
+                    double *dA, double *dX_self, int64_t ld_din)
+{
+    double *dz = (double *)malloc(sizeof(double) * (size_t)N);
+    memset(dW_neigh, 0, sizeof(double) * (size_t)K * N);
+    if (dW_self) memset(dW_self, 0, sizeof(double) * (size_t)K * N);
+    memset(dbias, 0, sizeof(double) * (size_t)N);
+    for (int32_t i = 0; i < n_active; ++i) {
+        int32_t v = rows ? rows[i] : i;
+        const double *dh = dH + (int64_t)v * ld_dh;
+        for (int32_t j = 0; j < N; ++j) {
+            double g = dh[j];
+            if (relu && !(H[(int64_t)v * ld_h + j] > 0.0)) g = 0.0;
+            dz[j] = g;
+            dbias[j] += g;
+        }
+        const double *a = A + (int64_t)v * ld_in;
+        for (int32_t k = 0; k < K; ++k)
+            for (int32_t j = 0; j < N; ++j) dW_neigh[(int64_t)k * N + j] += a[k] * dz[j];
+        if (X_self && dW_self) {
+            const double *x = X_self + (int64_t)v * ld_in;
+            for (int32_t k = 0; k < K; ++k)
+                for (int32_t j = 0; j < N; ++j) dW_self[(int64_t)k * N + j] += x[k] * dz[j];
+        }
+        if (dA) {
+            double *da = dA + (int64_t)v * ld_din;
+            for (int32_t k = 0; k < K; ++k) {
+                double s = 0.0;
+                for (int32_t j = 0; j < N; ++j) s += dz[j] * W_neigh[(int64_t)k * N + j];
+                da[k] = s;
+            }
+        }
+        if (dX_self && W_self) {
+            double *dx = dX_self + (int64_t)v * ld_din;
+            for (int32_t k = 0; k < K; ++k) {
+                double s = 0.0;
+                for (int32_t j = 0; j < N; ++j) s += dz[j] * W_self[(int64_t)k * N + j];
+                dx[k] = s;
+            }
+        }
+    }
+    free(dz);
+}
+
+/* ---------------------------------------------------------------------- */
+/* Node-classification loss on the targets (section 8.1, task):            */
+/*   loss = mean_{v in T} -log softmax(Z[v])[y_v];  dZ = (softmax - onehot)/|T| */
+/* labels[i] belongs to rows[i].  Rows outside the list are not written.   */
+/* ---------------------------------------------------------------------- */
+double orc_softmax_ce(const int32_t *rows, int32_t n_active,
+                      const double *Z, int64_t ldz, int32_t C, const int32_t *labels,
+                      double *dZ, int64_t lddz)
+{
+    double loss = 0.0;
+    for (int32_t i = 0; i < n_active; ++i) {
+        int32_t v = rows ? rows[i] : i;
+        const double *z = Z + (int64_t)v * ldz;
+        double m = z[0];
+        for (int32_t c = 1; c < C; ++c) if (z[c] > m) m = z[c];
+        double s = 0.0;
+        for (int32_t c = 0; c < C; ++c) s += exp(z[c] - m);
+        loss += -(z[labels[i]] - m - log(s));
+        if (dZ) {
+            double *d = dZ + (int64_t)v * lddz;
+            for (int32_t c = 0; c < C; ++c)
+                d[c] = (exp(z[c] - m) / s - (c == labels[i] ? 1.0 : 0.0)) / (double)n_active;
+        }
+    }
+    return n_active > 0 ? loss / (double)n_active : 0.0;
+}
+
+/* ---------------------------------------------------------------------- */
+/* bf16 storage: round a value to the nearest bfloat16 (ties to even),     */
+/* taken from its float32 value.  NaN stays NaN.                           */
+/* ---------------------------------------------------------------------- */
+void orc_round_bf16(double *x, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float f = (float)x[i];
+        uint32_t b;
+        memcpy(&b, &f, 4);
+        if ((b & 0x7fffffffu) > 0x7f800000u) { x[i] = NAN; continue; }
+        uint32_t lsb = (b >> 16) & 1u;
+        b += 0x7fffu + lsb;
+        b &= 0xffff0000u;
+        memcpy(&f, &b, 4);
+        x[i] = (double)f;
+    }
+}
+
+/* ---------------------------------------------------------------------- */
+/* Expansion-aware sampling, one hop (section 5.3.1 with the selection     */
+/* rule replaced by a seeded counter-based hash: every edge (v,u) gets a   */
+/* 64-bit key that depends on (seed, v, u, hop) only).                     */
+/*                                                                         */
+/* mix64 is the splitmix64 output function (Steele, Lea, Flood 2014;       */
+/* Vigna's public-domain constants): add the golden-ratio increment, then  */
+/* two xor-shift-multiply rounds and a final xor-shift.                    */
+/* ---------------------------------------------------------------------- */
+uint64_t orc_mix64(uint64_t x)
+{
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+
+uint64_t orc_edge_key(uint64_t seed, uint64_t v, uint64_t u, uint64_t hop)
+{
+    return orc_mix64(orc_mix64(orc_mix64(seed + hop) ^ v) ^ u);
+}
+
+typedef struct { uint64_t key; int32_t u; } orc_cand;
+
+static int orc_cand_cmp(const void *a, const void *b)
+{
+    const orc_cand *x = (const orc_cand *)a, *y = (const orc_cand *)b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    return (x->u > y->u) - (x->u < y->u);
+}
+
+static int orc_i32_cmp(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * For every target v (in the order given): keep every neighbour that is a
+ * target ("all other dependencies untouched"); of the neighbours outside T
+ * keep the min(fanout, count) with the smallest (key, id).  The kept row is
+ * emitted in ascending id order.  Two-call use: out_col_idx == NULL only
+ * fills out_row_ptr[0..n_targets] (so the caller can size the second call).
+ * Returns the number of kept entries, or -1 on a bad argument.
+ */
+int64_t orc_sample_boundary(int32_t n, const int32_t *row_ptr, const int32_t *col_idx,
+                            const uint8_t *is_target, const int32_t *targets, int32_t n_targets,
+                            int32_t fanout, uint64_t seed,
+                            int32_t *out_row_ptr, int32_t *out_col_idx)
+{
+    if (fanout < 0) return -1;
+    int64_t pos = 0;
+    orc_cand *cand = NULL;
+    int32_t cap = 0;
+    for (int32_t i = 0; i < n_targets; ++i) {
+        int32_t v = targets[i];
+        if (v < 0 || v >= n) { free(cand); return -1; }
+        int32_t len = row_ptr[v + 1] - row_ptr[v];
+        if (len > cap) { cap = len; cand = (orc_cand *)realloc(cand, sizeof(orc_cand) * (size_t)cap); }
+        out_row_ptr[i] = (int32_t)pos;
+        int32_t n_ext = 0;
+        int64_t row_start = pos;
+        for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+            int32_t u = col_idx[e];
+            if (is_target[u]) {
+                if (out_col_idx) out_col_idx[pos] = u;
+                ++pos;
+            } else {
+                cand[n_ext].key = orc_edge_key(seed, (uint64_t)v, (uint64_t)u, 1);
+                cand[n_ext].u = u;
+                ++n_ext;
+            }
+        }
+        qsort(cand, (size_t)n_ext, sizeof(orc_cand), orc_cand_cmp);
+        int32_t keep = n_ext < fanout ? n_ext : fanout;
+        for (int32_t k = 0; k < keep; ++k) {
+            if (out_col_idx) out_col_idx[pos] = cand[k].u;
+            ++pos;
+        }
+        if (out_col_idx) qsort(out_col_idx + row_start, (size_t)(pos - row_start), sizeof(int32_t), orc_i32_cmp);
+    }
+    out_row_ptr[n_targets] = (int32_t)pos;
+    free(cand);
+    return pos;
+}
