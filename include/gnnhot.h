@@ -1,0 +1,204 @@
+/*
+ * gnnhot - one GPU's share of a full-neighbourhood GNN training step under one-hop graph
+ * masking, for AMD MI355X (gfx950).  C ABI; every kernel behind it is hand-written HIP.
+ *
+ * The problem (paper sections 2.1, 5.3 and 6).  A partition holds its target ("inner")
+ * vertices T and a preloaded multi-hop halo.  ONE one-hop graph is reused by all L layers;
+ * row v of its CSR lists the vertices u whose hidden vectors v aggregates.  With
+ * dist(v) = hops from T to v along rows, layer l (l = 1..L) only produces the rows
+ *     R_l = { v : dist(v) <= L - l },       R_L = T,
+ * because nothing else can reach the targets' outputs (the per-layer mask of section 6,
+ * figure 7c steps 4-5).  Every layer is the two halves of the equation of section 2.1:
+ *     A_l[v]  = rs[v] * sum_{u in row(v)} cs[u] * H_{l-1}[u]          (aggregation)
+ *     H_l[v]  = sigma( A_l[v] W_neigh [+ H_{l-1}[v] W_self] + b )     (feature transform)
+ * followed, for training, by the matching backward pass.
+ *
+ * General rules of this interface
+ *   - Pointers are DEVICE pointers unless the name ends in _host.  The gnn_csr struct itself
+ *     is read on the host; the arrays it points to are on the device.
+ *   - The caller owns every buffer.  The library allocates nothing and keeps no state
+ *     between calls.  Calls that need scratch take (ws, ws_bytes): with ws == NULL the call
+ *     only writes the number of bytes it needs to *ws_bytes and returns GNN_OK; otherwise
+ *     *ws_bytes is the size of ws, which must be 256-byte aligned.  ws contents are
+ *     meaningless between calls.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  All work is enqueued on it and
+ *     nothing synchronises, except where a *_host output is requested (documented below).
+ *   - Matrices are row-major with an explicit leading dimension in ELEMENTS (int64).
+ *     dtype GNN_F32: float storage and arithmetic.  dtype GNN_BF16: bfloat16 storage,
+ *     float accumulation; weight and bias gradients are float in both cases.
+ *   - Rows that a call is not asked to produce are neither read nor written.
+ *   - Every function returns a gnn_status.  Nothing throws, aborts or prints.
+ *     gnn_last_error() gives a message for the calling thread's last failure.
+ *   - Index type is int32; nnz must be < 2^31.  Addresses are formed in 64 bits.
+ */
+#ifndef GNNHOT_H
+#define GNNHOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gnn_status {
+    GNN_OK = 0,
+    GNN_ERR_INVALID_ARG = 1, /* null where not allowed, negative size, misaligned ws, L < 1, fanout < 0 */
+    GNN_ERR_SHAPE = 2,       /* leading dimension smaller than the width, inconsistent sizes */
+    GNN_ERR_WORKSPACE = 3,   /* *ws_bytes smaller than required */
+    GNN_ERR_UNSUPPORTED = 4, /* unknown dtype, nnz >= 2^31, hops != 1, width over the limit */
+    GNN_ERR_HIP = 5          /* a HIP runtime call or kernel launch failed */
+} gnn_status;
+
+typedef enum gnn_dtype { GNN_F32 = 0, GNN_BF16 = 1 } gnn_dtype;
+
+typedef enum gnn_norm { GNN_NORM_MEAN = 1, GNN_NORM_SYM = 2 } gnn_norm;
+
+/* One-hop graph in CSR form.  Columns of a row may be in any order; a repeated column counts
+ * as often as it appears. */
+typedef struct gnn_csr {
+    int32_t n_rows;
+    int32_t n_cols;
+    int64_t nnz;
+    const int32_t *row_ptr; /* device, [n_rows + 1], row_ptr[0] = 0, row_ptr[n_rows] = nnz */
+    const int32_t *col_idx; /* device, [nnz], each in [0, n_cols) */
+} gnn_csr;
+
+int32_t gnn_version(void);
+const char *gnn_last_error(void);
+
+/*
+ * Per-layer active vertex sets (section 6: step 1 extracts the multi-hop dependency starting
+ * from the inner vertices; step 4 generates the per-layer mask).  Level-synchronous frontier
+ * expansion from T over CSR rows, L levels deep.
+ *   targets          [n_targets] vertex ids; repeats are allowed (set semantics);
+ *                    ids outside [0, n_rows) are ignored
+ *   dist             out [n_rows]: hop distance, -1 if farther than L hops or unreachable
+ *   ring_ids         out [n_rows] capacity: vertices ordered by (dist, id); only the first
+ *                    hop_offsets[L+1] entries are written
+ *   hop_offsets      out [L+2], device: ring j = ring_ids[hop_offsets[j] .. hop_offsets[j+1]);
+ *                    the rows of layer l are the prefix ring_ids[0 .. hop_offsets[L-l+1])
+ *   hop_offsets_host optional host copy of hop_offsets; when non-NULL the call waits for the
+ *                    stream before returning
+ * Requires g->n_rows == g->n_cols.  All outputs are bit-exact functions of the inputs.
+ */
+int32_t gnn_build_active_sets(const gnn_csr *g, const int32_t *targets, int32_t n_targets, int32_t L,
+                              int32_t *dist, int32_t *ring_ids, int64_t *hop_offsets,
+                              int64_t *hop_offsets_host, void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Normalisation factors for the aggregation of the two models the paper trains (section 8.1):
+ * GNN_NORM_MEAN  out[v] = 1 / len[v], 0 for an empty row   (GraphSAGE mean aggregator)
+ * GNN_NORM_SYM   out[v] = len[v]^(-1/2), 0 if len[v] = 0   (GCN; len counts the self loop)
+ * len[v] is taken from `len` when non-NULL, else row_ptr[v+1] - row_ptr[v].
+ */
+int32_t gnn_norm_scales(int32_t norm, const int32_t *len, const int32_t *row_ptr, int32_t n, float *out,
+                        void *stream);
+
+/*
+ * Masked aggregation, forward (section 2.1, first half of the layer equation; section 6 mask):
+ *     Y[v, 0:F] = row_scale[v] * sum_{u in row(v)} col_scale[u] * X[u, 0:F]     for v in rows
+ *   rows        [n_active] row ids, or NULL for rows 0 .. n_active-1
+ *   X           [g->n_cols, ldx], Y [g->n_rows, ldy]; X and Y must not overlap
+ *   row_scale, col_scale   float vectors or NULL (= 1)
+ * An empty row gives 0.  Columns F..ldy of Y are not written.  Results do not depend on launch
+ * order (no floating-point atomics): the same call gives the same bits.
+ * ws: hub queue for long rows (query the size with ws == NULL).
+ */
+int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_active,
+                            const void *X, int64_t ldx, void *Y, int64_t ldy, int32_t F, int32_t dtype,
+                            const float *row_scale, const float *col_scale,
+                            void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Masked aggregation, backward = the adjoint of the forward map, in gather form over the
+ * TRANSPOSED graph gT (row u of gT lists every v that aggregates u; for a symmetric graph pass
+ * the same arrays):
+ *     dX[u, 0:F] (+)= col_scale[u] * sum_{v in rowT(u), active(v)} row_scale[v] * dY[v, 0:F]   for u in out_rows
+ *   active(v)   dist == NULL: always; else 0 <= dist[v] <= max_active_dist  (v was a row of the forward call)
+ *   accumulate  0: overwrite dX rows, 1: add to them
+ * Same determinism and ws rules as the forward call.
+ */
+int32_t gnn_masked_spmm_bwd(const gnn_csr *gT, const int32_t *out_rows, int32_t n_out,
+                            const int32_t *dist, int32_t max_active_dist,
+                            const void *dY, int64_t lddy, void *dX, int64_t lddx, int32_t F, int32_t dtype,
+                            const float *row_scale, const float *col_scale, int32_t accumulate,
+                            void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Feature transform, forward (section 2.1, second half: weights, then the activation):
+ *     Z[v] = A_neigh[v, 0:K] W_neigh (+ X_self[v, 0:K] W_self) + bias,   H_out[v, 0:N] = relu ? max(Z, 0) : Z
+ * for v in rows (NULL = 0 .. n_active-1).
+ *   A_neigh, X_self  [*, ld_in]; X_self and W_self both NULL for a GCN layer
+ *   W_neigh, W_self  [K, N] dense row-major, same dtype as the activations
+ *   bias             float [N] or NULL
+ * MFMA GEMM (fp32 or bf16 inputs, float accumulation).  K, N <= 4096.
+ */
+int32_t gnn_linear_fwd(const int32_t *rows, int32_t n_active,
+                       const void *A_neigh, const void *X_self, int64_t ld_in, int32_t K,
+                       const void *W_neigh, const void *W_self, const float *bias, int32_t N,
+                       void *H_out, int64_t ld_out, int32_t relu, int32_t dtype,
+                       void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Feature transform, backward (chain rule of the above), for v in rows:
+ *     dZ[v]    = relu ? dH_out[v] * [H_out[v] > 0] : dH_out[v]
+ *     dW_neigh = sum_v A_neigh[v]^T dZ[v]      dW_self = sum_v X_self[v]^T dZ[v]      dbias = sum_v dZ[v]
+ *     dA_neigh[v, 0:K] = dZ[v] W_neigh^T       dX_self[v, 0:K] = dZ[v] W_self^T
+ *   dH_out, H_out     [*, ld_out]; H_out may be NULL when relu == 0
+ *   dW_neigh, dW_self float [K, N], overwritten; dbias float [N], overwritten
+ *   dA_neigh, dX_self [*, ld_din], rows in the list overwritten; either may be NULL to skip it
+ *                     (the first layer needs no input gradient)
+ * Reductions over rows use a fixed split and order (no atomics).
+ */
+int32_t gnn_linear_bwd(const int32_t *rows, int32_t n_active,
+                       const void *dH_out, const void *H_out, int64_t ld_out, int32_t relu,
+                       const void *A_neigh, const void *X_self, int64_t ld_in, int32_t K,
+                       const void *W_neigh, const void *W_self, int32_t N,
+                       float *dW_neigh, float *dW_self, float *dbias,
+                       void *dA_neigh, void *dX_self, int64_t ld_din, int32_t dtype,
+                       void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Node-classification loss on the targets (section 8.1): mean softmax cross-entropy.
+ *     loss = mean_i -log softmax(Z[rows[i]])[labels[i]],   dZ[rows[i]] = (softmax - onehot) / n_active
+ *   Z, dZ   [*, ldz] / [*, lddz] of `dtype`; dZ may be NULL; C <= 1024 classes
+ *   loss    float, device, overwritten
+ */
+int32_t gnn_softmax_ce(const int32_t *rows, int32_t n_active, const void *Z, int64_t ldz, int32_t C,
+                       const int32_t *labels, void *dZ, int64_t lddz, int32_t dtype, float *loss,
+                       void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Bitmap of a vertex set: bit (v & 31) of word v >> 5 is set iff v is in `ids`.
+ * bitmap has (n + 31) / 32 words and is overwritten.
+ */
+int32_t gnn_make_bitmap(const int32_t *ids, int32_t n_ids, int32_t n, uint32_t *bitmap, void *stream);
+
+/*
+ * Expansion-aware sampling, boundary only (section 5.3): dependencies between targets are kept
+ * whole; of the neighbours OUTSIDE the target set each target keeps at most `fanout`, chosen
+ * by a seeded counter-based hash so that the result depends on (seed, v, u) alone:
+ *     key(v, u) = mix64(mix64(mix64(seed + hop) ^ v) ^ u),  hop = 1,
+ *     mix64 = splitmix64's output function; keep the `fanout` smallest (key, u).
+ * For targets[i] the kept neighbours (global ids, ascending) are
+ * out_col_idx[out_row_ptr[i] .. out_row_ptr[i+1]).
+ * Two calls:
+ *   count pass  out_col_idx == NULL: writes out_row_ptr[0..n_targets] and *out_nnz (device);
+ *               out_nnz_host, if non-NULL, receives the same number (the call then waits).
+ *   fill pass   out_col_idx != NULL: reads out_row_ptr as written by the count pass with the
+ *               same arguments and writes the kept ids; entries at or beyond out_capacity
+ *               are not written.
+ * hops must be 1.  Bit-exact and independent of the order of `targets`.
+ */
+int32_t gnn_sample_boundary(const gnn_csr *g, const uint32_t *target_bitmap,
+                            const int32_t *targets, int32_t n_targets,
+                            int32_t fanout, int32_t hops, uint64_t seed,
+                            int32_t *out_row_ptr, int32_t *out_col_idx, int64_t out_capacity,
+                            int64_t *out_nnz, int64_t *out_nnz_host,
+                            void *ws, size_t *ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNNHOT_H */

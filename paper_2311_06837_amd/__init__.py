@@ -1,0 +1,14 @@
+"""gnnhot: one GPU's share of a full-neighbourhood GNN training step under one-hop graph
+masking (GraNNDis, arXiv 2311.06837) as hand-written HIP kernels for MI355X behind a C ABI.
+
+``binding`` mirrors include/gnnhot.h with torch tensors; ``model`` sequences the calls for one
+partition; ``build`` compiles the library.  There is no CPU fallback.
+"""
+from .binding import (GNN_BF16, GNN_F32, GNN_NORM_MEAN, GNN_NORM_SYM, GnnError, Graph, Workspace, gnn_build_active_sets,
+                      gnn_linear_bwd, gnn_linear_fwd, gnn_make_bitmap, gnn_masked_spmm_bwd, gnn_masked_spmm_fwd,
+                      gnn_norm_scales, gnn_sample_boundary, gnn_softmax_ce, gnn_version)
+from .model import MaskedGNN
+
+__all__ = ["GNN_BF16", "GNN_F32", "GNN_NORM_MEAN", "GNN_NORM_SYM", "GnnError", "Graph", "Workspace", "MaskedGNN",
+           "gnn_build_active_sets", "gnn_linear_bwd", "gnn_linear_fwd", "gnn_make_bitmap", "gnn_masked_spmm_bwd",
+           "gnn_masked_spmm_fwd", "gnn_norm_scales", "gnn_sample_boundary", "gnn_softmax_ce", "gnn_version"]

@@ -1,0 +1,261 @@
+"""ctypes binding of libgnnhot.so: the same entry points as include/gnnhot.h, taking torch
+tensors.  Argument marshalling and host-side shape checks only - every step of the path runs
+in the HIP kernels behind the C ABI.  torch supplies device memory and the current stream.
+
+There is no CPU fallback: importing works without a GPU (so that the symbols can be
+inspected), but every call needs the built library and CUDA/HIP tensors.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgnnhot.so")
+
+GNN_F32, GNN_BF16 = 0, 1
+GNN_NORM_MEAN, GNN_NORM_SYM = 1, 2
+STATUS = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_SHAPE", 3: "GNN_ERR_WORKSPACE",
+          4: "GNN_ERR_UNSUPPORTED", 5: "GNN_ERR_HIP"}
+
+EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_scales", "gnn_masked_spmm_fwd",
+           "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
+           "gnn_sample_boundary"]
+
+
+class GnnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class gnn_csr(C.Structure):
+    _fields_ = [("n_rows", C.c_int32), ("n_cols", C.c_int32), ("nnz", C.c_int64),
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_2311_06837_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with paper_2311_06837_amd.build.build_library(); "
+                               "there is no fallback path")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.gnn_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if name not in ("gnn_last_error",):
+                getattr(_lib, name).restype = C.c_int32
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise GnnError(status, lib().gnn_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert isinstance(t, torch.Tensor) and t.is_cuda, "device tensor expected"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GNN_F32
+    if t.dtype == torch.bfloat16:
+        return GNN_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _i32(t, name):
+    assert t is None or (t.dtype == torch.int32 and t.is_contiguous()), f"{name}: contiguous int32 expected"
+    return t
+
+
+def _mat(t, name):
+    assert t.dim() == 2 and t.stride(1) == 1, f"{name}: row-major 2-D tensor expected"
+    return t
+
+
+class Graph:
+    """Device CSR (int32) of a one-hop graph plus the host struct handed to the C ABI."""
+
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, n_cols: int | None = None):
+        _i32(row_ptr, "row_ptr"), _i32(col_idx, "col_idx")
+        assert row_ptr.is_cuda and col_idx.is_cuda
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.n_rows = row_ptr.numel() - 1
+        self.n_cols = self.n_rows if n_cols is None else n_cols
+        self.nnz = col_idx.numel()
+        self.c = gnn_csr(self.n_rows, self.n_cols, self.nnz, row_ptr.data_ptr(), col_idx.data_ptr() if self.nnz else None)
+
+    @staticmethod
+    def from_numpy(row_ptr, col_idx, device="cuda", n_cols=None) -> "Graph":
+        return Graph(torch.from_numpy(row_ptr).to(device), torch.from_numpy(col_idx).to(device), n_cols)
+
+
+class Workspace:
+    """Grow-only scratch buffer handed to the calls that take (ws, ws_bytes)."""
+
+    def __init__(self):
+        self.buf = None
+
+    def get(self, nbytes: int) -> torch.Tensor:
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        return self.buf
+
+
+_default_ws = Workspace()
+
+
+def _with_ws(fn, args_before, args_after, ws: Workspace | None):
+    """Run the (ws, ws_bytes) protocol: query the size, then call with a buffer of that size."""
+    ws = ws or _default_ws
+    need = C.c_size_t(0)
+    _check(fn(*args_before, None, C.byref(need), *args_after))
+    buf = ws.get(need.value)
+    have = C.c_size_t(buf.numel())
+    _check(fn(*args_before, _ptr(buf), C.byref(have), *args_after))
+
+
+def gnn_version() -> int:
+    return int(lib().gnn_version())
+
+
+def gnn_build_active_sets(g: Graph, targets: torch.Tensor, L: int, sync: bool = True, ws: Workspace | None = None):
+    """-> dist int32[n], ring_ids int32[n] (first hop_offsets[L+1] valid), hop_offsets int64[L+2] (device),
+    and the host copy of hop_offsets as a list (None when sync is False)."""
+    _i32(targets, "targets")
+    dev = g.row_ptr.device
+    dist = torch.empty(g.n_rows, dtype=torch.int32, device=dev)
+    ring = torch.empty(max(g.n_rows, 1), dtype=torch.int32, device=dev)
+    off = torch.empty(L + 2, dtype=torch.int64, device=dev)
+    host = (C.c_int64 * (L + 2))() if sync else None
+    _with_ws(lib().gnn_build_active_sets,
+             (C.byref(g.c), _ptr(targets) if targets.numel() else None, C.c_int32(targets.numel()), C.c_int32(L),
+              _ptr(dist) if g.n_rows else None, _ptr(ring), _ptr(off), host),
+             (_stream(),), ws)
+    return dist, ring, off, (list(host) if sync else None)
+
+
+def gnn_norm_scales(norm: int, n: int, length: torch.Tensor | None = None, row_ptr: torch.Tensor | None = None) -> torch.Tensor:
+    src = length if length is not None else row_ptr
+    out = torch.empty(n, dtype=torch.float32, device=src.device)
+    _check(lib().gnn_norm_scales(C.c_int32(norm), _ptr(_i32(length, "len")), _ptr(_i32(row_ptr, "row_ptr")), C.c_int32(n),
+                                 _ptr(out), _stream()))
+    return out
+
+
+def gnn_masked_spmm_fwd(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int,
+                        row_scale=None, col_scale=None, ws: Workspace | None = None):
+    _mat(X, "X"), _mat(Y, "Y")
+    assert X.dtype == Y.dtype and X.shape[0] >= g.n_cols and Y.shape[0] >= g.n_rows
+    assert rows is None or rows.numel() >= n_active
+    _with_ws(lib().gnn_masked_spmm_fwd,
+             (C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
+              C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale)),
+             (_stream(),), ws)
+
+
+def gnn_masked_spmm_bwd(gT: Graph, out_rows, n_out: int, dist, max_active_dist: int, dY: torch.Tensor, dX: torch.Tensor,
+                        F: int, row_scale=None, col_scale=None, accumulate: bool = False, ws: Workspace | None = None):
+    _mat(dY, "dY"), _mat(dX, "dX")
+    assert dY.dtype == dX.dtype and dY.shape[0] >= gT.n_cols and dX.shape[0] >= gT.n_rows
+    assert out_rows is None or out_rows.numel() >= n_out
+    _with_ws(lib().gnn_masked_spmm_bwd,
+             (C.byref(gT.c), _ptr(_i32(out_rows, "out_rows")), C.c_int32(n_out), _ptr(_i32(dist, "dist")),
+              C.c_int32(max_active_dist), _ptr(dY), C.c_int64(dY.stride(0)), _ptr(dX), C.c_int64(dX.stride(0)), C.c_int32(F),
+              C.c_int32(_dtype_code(dY)), _ptr(row_scale), _ptr(col_scale), C.c_int32(1 if accumulate else 0)),
+             (_stream(),), ws)
+
+
+def gnn_linear_fwd(rows, n_active: int, A_neigh: torch.Tensor, X_self, K: int, W_neigh: torch.Tensor, W_self, bias,
+                   H_out: torch.Tensor, relu: bool, ws: Workspace | None = None):
+    _mat(A_neigh, "A_neigh"), _mat(H_out, "H_out")
+    N = W_neigh.shape[1]
+    assert W_neigh.shape == (K, N) and W_neigh.is_contiguous() and W_neigh.dtype == A_neigh.dtype == H_out.dtype
+    if X_self is not None:
+        _mat(X_self, "X_self")
+        assert X_self.stride(0) == A_neigh.stride(0) and X_self.dtype == A_neigh.dtype
+        assert W_self.shape == (K, N) and W_self.is_contiguous() and W_self.dtype == W_neigh.dtype
+    assert bias is None or (bias.dtype == torch.float32 and bias.numel() == N)
+    _with_ws(lib().gnn_linear_fwd,
+             (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(A_neigh), _ptr(X_self), C.c_int64(A_neigh.stride(0)),
+              C.c_int32(K), _ptr(W_neigh), _ptr(W_self), _ptr(bias), C.c_int32(N), _ptr(H_out), C.c_int64(H_out.stride(0)),
+              C.c_int32(1 if relu else 0), C.c_int32(_dtype_code(A_neigh))),
+             (_stream(),), ws)
+
+
+def gnn_linear_bwd(rows, n_active: int, dH_out: torch.Tensor, H_out, relu: bool, A_neigh: torch.Tensor, X_self, K: int,
+                   W_neigh: torch.Tensor, W_self, dW_neigh: torch.Tensor, dW_self, dbias: torch.Tensor,
+                   dA_neigh=None, dX_self=None, ws: Workspace | None = None):
+    _mat(dH_out, "dH_out"), _mat(A_neigh, "A_neigh")
+    N = W_neigh.shape[1]
+    assert W_neigh.shape == (K, N) and W_neigh.is_contiguous()
+    assert dW_neigh.dtype == torch.float32 and dW_neigh.shape == (K, N) and dW_neigh.is_contiguous()
+    assert dbias.dtype == torch.float32 and dbias.numel() == N
+    if H_out is not None:
+        assert H_out.stride(0) == dH_out.stride(0) and H_out.dtype == dH_out.dtype
+    if X_self is not None:
+        assert X_self.stride(0) == A_neigh.stride(0)
+        assert dW_self is not None and dW_self.dtype == torch.float32 and dW_self.shape == (K, N) and dW_self.is_contiguous()
+    ld_din = 0
+    for t in (dA_neigh, dX_self):
+        if t is not None:
+            _mat(t, "dA/dX")
+            assert ld_din in (0, t.stride(0)) and t.dtype == A_neigh.dtype
+            ld_din = t.stride(0)
+    _with_ws(lib().gnn_linear_bwd,
+             (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(dH_out), _ptr(H_out), C.c_int64(dH_out.stride(0)),
+              C.c_int32(1 if relu else 0), _ptr(A_neigh), _ptr(X_self), C.c_int64(A_neigh.stride(0)), C.c_int32(K),
+              _ptr(W_neigh), _ptr(W_self), C.c_int32(N), _ptr(dW_neigh), _ptr(dW_self), _ptr(dbias), _ptr(dA_neigh),
+              _ptr(dX_self), C.c_int64(ld_din), C.c_int32(_dtype_code(A_neigh))),
+             (_stream(),), ws)
+
+
+def gnn_softmax_ce(rows, n_active: int, Z: torch.Tensor, n_classes: int, labels: torch.Tensor, dZ, loss: torch.Tensor,
+                   ws: Workspace | None = None):
+    _mat(Z, "Z")
+    assert loss.dtype == torch.float32 and loss.numel() == 1 and labels.numel() >= n_active
+    _with_ws(lib().gnn_softmax_ce,
+             (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(Z), C.c_int64(Z.stride(0)), C.c_int32(n_classes),
+              _ptr(_i32(labels, "labels")), _ptr(dZ), C.c_int64(dZ.stride(0) if dZ is not None else 0),
+              C.c_int32(_dtype_code(Z)), _ptr(loss)),
+             (_stream(),), ws)
+
+
+def gnn_make_bitmap(ids: torch.Tensor, n: int) -> torch.Tensor:
+    bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=ids.device)
+    _check(lib().gnn_make_bitmap(_ptr(_i32(ids, "ids")) if ids.numel() else None, C.c_int32(ids.numel()), C.c_int32(n),
+                                 _ptr(bitmap) if n else None, _stream()))
+    return bitmap
+
+
+def gnn_sample_boundary(g: Graph, target_bitmap: torch.Tensor, targets: torch.Tensor, fanout: int, seed: int, hops: int = 1,
+                        ws: Workspace | None = None):
+    """Count pass + fill pass.  -> out_row_ptr int32[n_targets+1], out_col_idx int32[kept] (global ids)."""
+    _i32(targets, "targets")
+    nt = targets.numel()
+    dev = g.row_ptr.device
+    out_rp = torch.empty(nt + 1, dtype=torch.int32, device=dev)
+    nnz_dev = torch.empty(1, dtype=torch.int64, device=dev)
+    nnz_host = C.c_int64(0)
+    common = (C.byref(g.c), _ptr(target_bitmap), _ptr(targets) if nt else None, C.c_int32(nt), C.c_int32(fanout),
+              C.c_int32(hops), C.c_uint64(seed & (2**64 - 1)), _ptr(out_rp))
+    _with_ws(lib().gnn_sample_boundary, common + (None, C.c_int64(0), _ptr(nnz_dev), C.byref(nnz_host)), (_stream(),), ws)
+    kept = int(nnz_host.value)
+    out_ci = torch.empty(max(kept, 1), dtype=torch.int32, device=dev)
+    _with_ws(lib().gnn_sample_boundary, common + (_ptr(out_ci), C.c_int64(kept), _ptr(nnz_dev), None), (_stream(),), ws)
+    return out_rp, out_ci[:kept]

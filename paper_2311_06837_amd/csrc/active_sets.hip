@@ -1,0 +1,208 @@
+// Per-layer active vertex sets: level-synchronous frontier expansion from the targets
+// (paper section 6, figure 7c: step 1 extracts the multi-hop dependency from the inner
+// vertices, step 4 generates the per-layer mask).
+//
+// Data layout.  Two bitmaps of n bits live in the workspace: `visited` (everything reached
+// so far, read-only while a level expands) and `next` (candidates found by the level being
+// expanded).  A level is: expand (edge gather + bit probes) -> count / scan / emit, a
+// bitmap compaction that lists the new ring in ascending id order without any sort, so the
+// output does not depend on which wave found a vertex first.  Ring sizes stay on the
+// device (hop_offsets); every kernel has a fixed grid and reads its bounds from there, so
+// the whole construction is enqueued without a host round trip.
+//
+// Bound: HBM bandwidth.  Per level the algorithm reads each edge of the frontier once
+// (4 B) and writes 8 B per newly reached vertex; the bit probes hit a bitmap of n/8 bytes
+// that stays in L2.
+#include "common.h"
+#include "scan.h"
+
+namespace gnnhot {
+
+constexpr int kAsWordsPerBlock = 256;   // one bitmap word per thread: 8192 vertices per block
+constexpr int kAsHubDegree = 4096;      // longer rows are expanded by the whole grid
+constexpr int kAsHubChunk = 1024;       // edges per block-iteration in the hub kernel
+
+struct AsCtrl {
+    int32_t n_hubs;
+    int32_t pad[7];
+};
+
+__global__ __launch_bounds__(256) void as_init_kernel(int32_t* __restrict__ dist, int32_t n, uint32_t* __restrict__ visited,
+                                                      uint32_t* __restrict__ next, int64_t nw, AsCtrl* ctrl,
+                                                      int64_t* __restrict__ hop_offsets, int32_t L) {
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = tid; v < n; v += stride) dist[v] = -1;
+    for (int64_t w = tid; w < nw; w += stride) {
+        visited[w] = 0u;
+        next[w] = 0u;
+    }
+    if (tid == 0) ctrl->n_hubs = 0;
+    if (tid <= L + 1) hop_offsets[tid] = 0;
+}
+
+__global__ __launch_bounds__(256) void as_seed_kernel(const int32_t* __restrict__ targets, int32_t n_targets, int32_t n,
+                                                      uint32_t* __restrict__ next) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_targets; i += (int64_t)gridDim.x * blockDim.x) {
+        int32_t v = targets[i];
+        if (v >= 0 && v < n) atomicOr(&next[v >> 5], 1u << (v & 31));
+    }
+}
+
+// One wave per frontier vertex, lanes across its row.
+__global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                        const int32_t* __restrict__ ring_ids,
+                                                        const int64_t* __restrict__ hop_offsets, int32_t ring,
+                                                        const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
+                                                        int32_t* __restrict__ hubq, AsCtrl* ctrl) {
+    const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
+    const int lane = lane_id();
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t i = begin + wave; i < end; i += n_waves) {
+        const int32_t v = ring_ids[i];
+        const int32_t s = row_ptr[v], e = row_ptr[v + 1];
+        if (e - s > kAsHubDegree) {
+            if (lane == 0) hubq[atomicAdd(&ctrl->n_hubs, 1)] = v;
+            continue;
+        }
+        for (int32_t p = s + lane; p < e; p += kWave) {
+            const int32_t u = col_idx[p];
+            const uint32_t bit = 1u << (u & 31);
+            if (!(visited[u >> 5] & bit) && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
+        }
+    }
+}
+
+// Hub rows: every block takes chunks of every hub row.
+__global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                             const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
+                                                             const int32_t* __restrict__ hubq, const AsCtrl* ctrl) {
+    const int32_t n_hubs = ctrl->n_hubs;
+    for (int32_t h = 0; h < n_hubs; ++h) {
+        const int32_t v = hubq[h];
+        const int32_t s = row_ptr[v], e = row_ptr[v + 1];
+        for (int64_t c = (int64_t)s + (int64_t)blockIdx.x * kAsHubChunk; c < e; c += (int64_t)gridDim.x * kAsHubChunk) {
+#pragma unroll
+            for (int k = 0; k < kAsHubChunk / 256; ++k) {
+                const int64_t p = c + k * 256 + threadIdx.x;
+                if (p < e) {
+                    const int32_t u = col_idx[p];
+                    const uint32_t bit = 1u << (u & 31);
+                    if (!(visited[u >> 5] & bit) && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kAsWordsPerBlock) void as_count_kernel(const uint32_t* __restrict__ next,
+                                                                    const uint32_t* __restrict__ visited, int64_t nw,
+                                                                    int32_t* __restrict__ blk_cnt) {
+    __shared__ int s_part[kAsWordsPerBlock / kWave];
+    const int64_t w = (int64_t)blockIdx.x * kAsWordsPerBlock + threadIdx.x;
+    int c = 0;
+    if (w < nw) c = __popc(next[w] & ~visited[w]);
+    int total;
+    block_exclusive_scan<kAsWordsPerBlock>(c, s_part, &total);
+    if (threadIdx.x == 0) blk_cnt[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(1024) void as_scan_kernel(int32_t* __restrict__ blk_cnt, int64_t n_blocks,
+                                                       int64_t* __restrict__ hop_offsets, int32_t ring, AsCtrl* ctrl) {
+    __shared__ int s_part[1024 / kWave];
+    const int64_t total = single_block_exclusive_scan(blk_cnt, n_blocks, s_part);
+    if (threadIdx.x == 0) {
+        hop_offsets[ring + 1] = hop_offsets[ring] + total;
+        ctrl->n_hubs = 0;
+    }
+}
+
+__global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(uint32_t* __restrict__ next, uint32_t* __restrict__ visited,
+                                                                   int64_t nw, const int32_t* __restrict__ blk_cnt,
+                                                                   const int64_t* __restrict__ hop_offsets, int32_t ring,
+                                                                   int32_t* __restrict__ ring_ids, int32_t* __restrict__ dist) {
+    __shared__ int s_part[kAsWordsPerBlock / kWave];
+    const int64_t w = (int64_t)blockIdx.x * kAsWordsPerBlock + threadIdx.x;
+    uint32_t fresh = 0u;
+    if (w < nw) {
+        const uint32_t nx = next[w];
+        if (nx) {
+            const uint32_t vis = visited[w];
+            fresh = nx & ~vis;
+            visited[w] = vis | fresh;
+            next[w] = 0u;
+        }
+    }
+    int total;
+    const int before = block_exclusive_scan<kAsWordsPerBlock>(__popc(fresh), s_part, &total);
+    int64_t pos = hop_offsets[ring] + blk_cnt[blockIdx.x] + before;
+    while (fresh) {
+        const int b = __ffs(fresh) - 1;
+        fresh &= fresh - 1;
+        const int32_t v = (int32_t)(w * 32 + b);
+        ring_ids[pos++] = v;
+        dist[v] = ring;
+    }
+}
+
+}  // namespace gnnhot
+
+using namespace gnnhot;
+
+extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* targets, int32_t n_targets, int32_t L,
+                                         int32_t* dist, int32_t* ring_ids, int64_t* hop_offsets, int64_t* hop_offsets_host,
+                                         void* ws, size_t* ws_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_csr(g, "g"));
+    GNN_REQUIRE(g->n_rows == g->n_cols, GNN_ERR_SHAPE, "active sets need a square graph (%d x %d)", g->n_rows, g->n_cols);
+    GNN_REQUIRE(L >= 1 && L <= 1024, GNN_ERR_INVALID_ARG, "L = %d out of range [1, 1024]", L);
+    GNN_REQUIRE(n_targets >= 0, GNN_ERR_INVALID_ARG, "n_targets < 0");
+    const int32_t n = g->n_rows;
+    const int64_t nw = ((int64_t)n + 31) / 32;
+    const int64_t nb = nw > 0 ? (nw + kAsWordsPerBlock - 1) / kAsWordsPerBlock : 1;
+
+    WsCarver carve(ws);
+    uint32_t* visited = carve.take<uint32_t>((size_t)nw + 1);
+    uint32_t* next = carve.take<uint32_t>((size_t)nw + 1);
+    int32_t* blk_cnt = carve.take<int32_t>((size_t)nb + 1);
+    int32_t* hubq = carve.take<int32_t>((size_t)n + 1);
+    AsCtrl* ctrl = carve.take<AsCtrl>(1);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+
+    GNN_REQUIRE(hop_offsets != nullptr, GNN_ERR_INVALID_ARG, "hop_offsets is NULL");
+    GNN_REQUIRE(n == 0 || (dist != nullptr && ring_ids != nullptr), GNN_ERR_INVALID_ARG, "dist / ring_ids is NULL");
+    GNN_REQUIRE(n_targets == 0 || targets != nullptr, GNN_ERR_INVALID_ARG, "targets is NULL");
+
+    as_init_kernel<<<grid_for(n > L + 2 ? n : L + 2, 256, 2048), 256, 0, stream>>>(dist, n, visited, next, nw, ctrl, hop_offsets, L);
+    GNN_LAUNCH_CHECK("as_init_kernel");
+    if (n > 0) {
+        if (n_targets > 0) {
+            as_seed_kernel<<<grid_for(n_targets, 256, 2048), 256, 0, stream>>>(targets, n_targets, n, next);
+            GNN_LAUNCH_CHECK("as_seed_kernel");
+        }
+        const int expand_grid = 2048;  // 8 waves per CU-slot; bounds are read on the device
+        for (int32_t ring = 0; ring <= L; ++ring) {
+            if (ring > 0) {
+                as_expand_kernel<<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited,
+                                                                  next, hubq, ctrl);
+                GNN_LAUNCH_CHECK("as_expand_kernel");
+                as_expand_hubs_kernel<<<1024, 256, 0, stream>>>(g->row_ptr, g->col_idx, visited, next, hubq, ctrl);
+                GNN_LAUNCH_CHECK("as_expand_hubs_kernel");
+            }
+            as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt);
+            GNN_LAUNCH_CHECK("as_count_kernel");
+            as_scan_kernel<<<1, 1024, 0, stream>>>(blk_cnt, nb, hop_offsets, ring, ctrl);
+            GNN_LAUNCH_CHECK("as_scan_kernel");
+            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
+            GNN_LAUNCH_CHECK("as_emit_kernel");
+        }
+    }
+    if (hop_offsets_host != nullptr) {
+        GNN_HIP(hipMemcpyAsync(hop_offsets_host, hop_offsets, sizeof(int64_t) * (size_t)(L + 2), hipMemcpyDeviceToHost, stream));
+        GNN_HIP(hipStreamSynchronize(stream));
+    }
+    return GNN_OK;
+}

@@ -1,0 +1,665 @@
+// Dense feature transform of a GNN layer and its backward pass (paper section 2.1: the
+// aggregated vector, optionally combined with the vertex's own previous vector, is
+// multiplied by the layer's weights and passed through the activation).
+//
+// Two MFMA GEMM kernels for gfx950 carry all of it:
+//   gemm_nt   C[m, n] = epilogue( sum_src sum_k A_src[row(m), k] * Bt_src[n, k] )
+//             forward  (Bt = W^T, made once per call in the workspace; bias + ReLU epilogue)
+//             dA / dX_self = dZ W^T  (Bt = W as stored; rows scattered back through `rows`)
+//   gemm_tn   P[split][k, n] = sum_{m in split} A_src[row(m), k] * D[m, n]
+//             dW_neigh / dW_self = A^T dZ, reduced over fixed row splits, then summed in
+//             split order by reduce_partials (deterministic, no atomics).
+// fp32 uses v_mfma_f32_32x32x2_f32, bf16 uses v_mfma_f32_32x32x16_bf16 (fp32 accumulate).
+//
+// Tiling.  256 threads = 4 wavefronts per workgroup; every LDS tile row is 128 bytes of the
+// reduction (gemm_nt) so one global row read is a full cache line, padded to 144 bytes so
+// that 16-byte LDS reads of 32 consecutive rows are conflict-free.  The reduction index of a
+// tile is permuted between the two halves of the wavefront (half g owns elements
+// [g*BK/2, (g+1)*BK/2)) so that each lane fetches its whole operand strip with four
+// ds_read_b128; both operands use the same permutation, which leaves the product unchanged.
+// The next tile is prefetched into registers while the current one feeds the MFMAs.
+// Workgroup ids are remapped so that consecutive tiles share an XCD (and its L2).
+#include "common.h"
+
+namespace gnnhot {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kMaxDim = 4096;
+constexpr int kLdsRowWords = 36;  // 128 B of data + 16 B pad
+
+template <int DT>
+struct DTy {
+    static constexpr int ES = DT == GNN_F32 ? 4 : 2;  // bytes per element
+    static constexpr int EPV = 16 / ES;               // elements per 16-byte vector
+};
+
+// 16 bytes from row-major storage with element-granular bounds; `n_valid` elements from
+// `p` are in range (<= 0: none).  Falls back to element loads at a ragged edge or when the
+// address is not 16-byte aligned.
+template <int DT>
+__device__ __forceinline__ uint4 load16(const void* base, int64_t elem_off, int n_valid, bool vec_ok) {
+    constexpr int EPV = DTy<DT>::EPV;
+    uint4 r = make_uint4(0u, 0u, 0u, 0u);
+    if (n_valid <= 0) return r;
+    if (n_valid >= EPV && vec_ok) {
+        if (DT == GNN_F32) return *(const uint4*)((const float*)base + elem_off);
+        return *(const uint4*)((const uint16_t*)base + elem_off);
+    }
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (DT == GNN_F32) {
+        const uint32_t* p = (const uint32_t*)base + elem_off;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (e < n_valid) w[e] = p[e];
+    } else {
+        const uint16_t* p = (const uint16_t*)base + elem_off;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < n_valid) w[e >> 1] |= (uint32_t)p[e] << ((e & 1) * 16);
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int DT>
+__device__ __forceinline__ void store_elem(void* base, int64_t off, float v) {
+    if (DT == GNN_F32) ((float*)base)[off] = v;
+    else ((uint16_t*)base)[off] = f32_to_bf16(v);
+}
+
+template <int DT>
+__device__ __forceinline__ float load_elem(const void* base, int64_t off) {
+    if (DT == GNN_F32) return ((const float*)base)[off];
+    return bf16_to_f32(((const uint16_t*)base)[off]);
+}
+
+// Workgroup id -> logical tile so that consecutive logical tiles run on the same XCD
+// (ids are dealt round-robin over the 8 XCDs).  Grid must be 8 * ceil(total / 8).
+__device__ __forceinline__ int64_t xcd_remap(int64_t id, int64_t total) {
+    const int64_t per = (total + 7) / 8;
+    return (id % 8) * per + id / 8;
+}
+
+// ------------------------------------------------------------------------------------------
+// gemm_nt
+// ------------------------------------------------------------------------------------------
+struct GemmNT {
+    const void* A[2];
+    const void* Bt[2];
+    int32_t n_src;
+    int64_t lda, ldb;
+    int32_t a_vec, b_vec;      // 16-byte loads allowed
+    const int32_t* a_rows;     // nullable
+    const int32_t* c_rows;     // nullable
+    int32_t M, N, K;
+    const float* bias;         // nullable
+    int32_t relu;
+    void* C;
+    int64_t ldc;
+};
+
+template <int DT, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT a) {
+    constexpr int BM = 128;
+    constexpr int EPV = DTy<DT>::EPV;
+    constexpr int BK = 8 * EPV;  // elements per 128-byte tile row
+    constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 32, NT = WTN / 32;
+    constexpr int A_CH = BM / 32, B_CH = BN / 32;  // 16-byte chunks per thread
+    static_assert(WM * WN == 4 && MT >= 1 && NT >= 1, "bad wave layout");
+    __shared__ uint32_t sA[BM * kLdsRowWords];
+    __shared__ uint32_t sB[BN * kLdsRowWords];
+
+    const int tiles_n = (a.N + BN - 1) / BN, tiles_m = (a.M + BM - 1) / BM;
+    const int64_t total = (int64_t)tiles_m * tiles_n;
+    const int64_t tile = xcd_remap(blockIdx.x, total);
+    if (tile >= total) return;
+    const int m0 = (int)(tile / tiles_n) * BM, n0 = (int)(tile % tiles_n) * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, g = lane >> 5;
+    const int ld_row = tid >> 3, ld_kc = tid & 7;  // loader: row within a 32-row band, 16-byte column
+
+    int64_t a_off[A_CH];
+    bool a_ok[A_CH];
+#pragma unroll
+    for (int c = 0; c < A_CH; ++c) {
+        const int m = m0 + ld_row + 32 * c;
+        a_ok[c] = m < a.M;
+        const int64_t r = a_ok[c] ? (a.a_rows ? (int64_t)a.a_rows[m] : (int64_t)m) : 0;
+        a_off[c] = r * a.lda;
+    }
+    int64_t b_off[B_CH];
+    bool b_ok[B_CH];
+#pragma unroll
+    for (int c = 0; c < B_CH; ++c) {
+        const int n = n0 + ld_row + 32 * c;
+        b_ok[c] = n < a.N;
+        b_off[c] = (int64_t)(b_ok[c] ? n : 0) * a.ldb;
+    }
+
+    v16f acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int k_tiles = (a.K + BK - 1) / BK;
+    const int n_steps = k_tiles * a.n_src;
+    uint4 ra[A_CH], rb[B_CH];
+
+    auto fetch = [&](int step) {
+        const int src = step / k_tiles;
+        const int ke = (step % k_tiles) * BK + ld_kc * EPV;
+        const int nv = a.K - ke;
+        const void* Ab = a.A[src];
+        const void* Bb = a.Bt[src];
+#pragma unroll
+        for (int c = 0; c < A_CH; ++c) ra[c] = load16<DT>(Ab, a_off[c] + ke, a_ok[c] ? nv : 0, a.a_vec != 0);
+#pragma unroll
+        for (int c = 0; c < B_CH; ++c) rb[c] = load16<DT>(Bb, b_off[c] + ke, b_ok[c] ? nv : 0, a.b_vec != 0);
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int c = 0; c < A_CH; ++c) *(uint4*)&sA[(ld_row + 32 * c) * kLdsRowWords + ld_kc * 4] = ra[c];
+#pragma unroll
+        for (int c = 0; c < B_CH; ++c) *(uint4*)&sB[(ld_row + 32 * c) * kLdsRowWords + ld_kc * 4] = rb[c];
+    };
+
+    if (n_steps > 0) {
+        fetch(0);
+        stash();
+    }
+    __syncthreads();
+    for (int step = 0; step < n_steps; ++step) {
+        if (step + 1 < n_steps) fetch(step + 1);
+        uint4 fa[MT][4], fb[NT][4];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                fa[i][q] = *(const uint4*)&sA[(wm * WTM + i * 32 + li) * kLdsRowWords + g * 16 + q * 4];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                fb[j][q] = *(const uint4*)&sB[(wn * WTN + j * 32 + li) * kLdsRowWords + g * 16 + q * 4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (DT == GNN_F32) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < NT; ++j) {
+                            const uint32_t av = t == 0 ? fa[i][q].x : (t == 1 ? fa[i][q].y : (t == 2 ? fa[i][q].z : fa[i][q].w));
+                            const uint32_t bv = t == 0 ? fb[j][q].x : (t == 1 ? fb[j][q].y : (t == 2 ? fb[j][q].z : fb[j][q].w));
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av), __uint_as_float(bv), acc[i][j], 0, 0, 0);
+                        }
+            } else {
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fa[i][q]),
+                                                                             __builtin_bit_cast(v8bf, fb[j][q]), acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+        if (step + 1 < n_steps) {
+            stash();
+            __syncthreads();
+        }
+    }
+
+    // epilogue: acc[i][j][r] is C[row = (r/4)*8 + g*4 + r%4][col = li] of its 32x32 block
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+            if (m >= a.M) continue;
+            const int64_t crow = a.c_rows ? (int64_t)a.c_rows[m] : (int64_t)m;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int n = n0 + wn * WTN + j * 32 + li;
+                if (n < a.N) {
+                    float v = acc[i][j][r];
+                    if (a.bias) v += a.bias[n];
+                    if (a.relu) v = v > 0.f ? v : 0.f;
+                    store_elem<DT>(a.C, crow * a.ldc + n, v);
+                }
+            }
+        }
+    }
+}
+
+template <int DT>
+static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
+    if (a.M <= 0 || a.N <= 0) return GNN_OK;
+    const int64_t tiles_m = ((int64_t)a.M + 127) / 128;
+    if (a.N > 64) {
+        const int64_t total = tiles_m * ((a.N + 127) / 128);
+        gemm_nt_kernel<DT, 128, 2, 2><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(a);
+    } else if (a.N > 32) {
+        const int64_t total = tiles_m * ((a.N + 63) / 64);
+        gemm_nt_kernel<DT, 64, 2, 2><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(a);
+    } else {
+        const int64_t total = tiles_m;
+        gemm_nt_kernel<DT, 32, 4, 1><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(a);
+    }
+    GNN_LAUNCH_CHECK("gemm_nt_kernel");
+    return GNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// gemm_tn : P[split][src*K + k][n] = sum_{m in split} A_src[row(m)][k] * D[m][n]
+// ------------------------------------------------------------------------------------------
+struct GemmTN {
+    const void* A[2];
+    int32_t n_src;
+    int64_t lda;
+    int32_t a_vec;
+    const int32_t* a_rows;  // nullable
+    const void* D;          // [M, ldd], rows compact
+    int64_t ldd;
+    int32_t d_vec;
+    int32_t M, N, K;
+    int32_t rows_per_split; // multiple of 32
+    float* P;               // [splits][n_src*K][N]
+};
+
+template <int DT, int BN>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN a) {
+    constexpr int BKO = 128, BMR = 32;
+    constexpr int EPV = DTy<DT>::EPV;
+    constexpr int WKO = BN == 128 ? 2 : 4, WNN = 4 / WKO;      // waves along k-out and n
+    constexpr int WTK = BKO / WKO, WTN = BN / WNN, MT = WTK / 32, NT = WTN / 32;
+    constexpr int A_VPR = BKO / EPV;                 // 16-byte vectors per tile row
+    constexpr int D_VPR = BN / EPV;
+    constexpr int A_CH = BMR * A_VPR / 256;          // vectors per thread
+    constexpr int D_CH = (BMR * D_VPR + 255) / 256;
+    constexpr int A_LDW = BKO * DTy<DT>::ES / 4, D_LDW = BN * DTy<DT>::ES / 4;  // LDS row strides in words
+    __shared__ uint32_t sA[BMR * A_LDW];
+    __shared__ uint32_t sD[BMR * D_LDW];
+
+    const int ko_tiles = (a.K + BKO - 1) / BKO;
+    const int n_tiles = (a.N + BN - 1) / BN;
+    const int t = blockIdx.x;
+    const int tn = t % n_tiles, tk = (t / n_tiles) % ko_tiles, src = t / (n_tiles * ko_tiles);
+    const int ko0 = tk * BKO, n0 = tn * BN;
+    const int split = blockIdx.y;
+    const int64_t m_begin = (int64_t)split * a.rows_per_split;
+    const int64_t m_end = m_begin + a.rows_per_split < a.M ? m_begin + a.rows_per_split : a.M;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wk = wave / WNN, wn = wave % WNN;
+    const int li = lane & 31, g = lane >> 5;
+    const void* Ab = a.A[src];
+
+    v16f acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    uint4 ra[A_CH], rd[D_CH];
+    auto fetch = [&](int64_t mb) {
+#pragma unroll
+        for (int c = 0; c < A_CH; ++c) {
+            const int v = tid + 256 * c;
+            const int row = v / A_VPR, kc = v % A_VPR;
+            const int64_t m = mb + row;
+            const int ke = ko0 + kc * EPV;
+            int64_t r = 0;
+            if (m < m_end) r = a.a_rows ? (int64_t)a.a_rows[m] : m;
+            ra[c] = load16<DT>(Ab, r * a.lda + ke, m < m_end ? a.K - ke : 0, a.a_vec != 0);
+        }
+#pragma unroll
+        for (int c = 0; c < D_CH; ++c) {
+            const int v = tid + 256 * c;
+            const int row = v / D_VPR, nc = v % D_VPR;
+            const int64_t m = mb + row;
+            const int ne = n0 + nc * EPV;
+            const bool ok = row < BMR && m < m_end;
+            rd[c] = load16<DT>(a.D, (ok ? m : 0) * a.ldd + ne, ok ? a.N - ne : 0, a.d_vec != 0);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int c = 0; c < A_CH; ++c) {
+            const int v = tid + 256 * c;
+            *(uint4*)&sA[(v / A_VPR) * A_LDW + (v % A_VPR) * 4] = ra[c];
+        }
+#pragma unroll
+        for (int c = 0; c < D_CH; ++c) {
+            const int v = tid + 256 * c;
+            if (v / D_VPR < BMR) *(uint4*)&sD[(v / D_VPR) * D_LDW + (v % D_VPR) * 4] = rd[c];
+        }
+    };
+
+    if (m_begin < m_end) {
+        fetch(m_begin);
+        stash();
+    }
+    __syncthreads();
+    for (int64_t mb = m_begin; mb < m_end; mb += BMR) {
+        if (mb + BMR < m_end) fetch(mb + BMR);
+        if (DT == GNN_F32) {
+            // half g of the wave owns tile rows g*16 .. g*16+15; step s multiplies row g*16+s
+            const float* fA = (const float*)sA;
+            const float* fD = (const float*)sD;
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                float av[MT], dv[NT];
+#pragma unroll
+                for (int i = 0; i < MT; ++i) av[i] = fA[(g * 16 + s) * A_LDW + wk * WTK + i * 32 + li];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) dv[j] = fD[(g * 16 + s) * D_LDW + wn * WTN + j * 32 + li];
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], dv[j], acc[i][j], 0, 0, 0);
+            }
+        } else {
+            // step s (0, 1) multiplies tile rows s*16 + g*8 + e, e = 0..7, gathered down a column
+            const uint16_t* hA = (const uint16_t*)sA;
+            const uint16_t* hD = (const uint16_t*)sD;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                uint4 av[MT], dv[NT];
+#pragma unroll
+                for (int i = 0; i < MT; ++i) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int r0 = s * 16 + g * 8 + 2 * e;
+                        const int col = wk * WTK + i * 32 + li;
+                        w[e] = (uint32_t)hA[r0 * (A_LDW * 2) + col] | ((uint32_t)hA[(r0 + 1) * (A_LDW * 2) + col] << 16);
+                    }
+                    av[i] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int r0 = s * 16 + g * 8 + 2 * e;
+                        const int col = wn * WTN + j * 32 + li;
+                        w[e] = (uint32_t)hD[r0 * (D_LDW * 2) + col] | ((uint32_t)hD[(r0 + 1) * (D_LDW * 2) + col] << 16);
+                    }
+                    dv[j] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av[i]),
+                                                                             __builtin_bit_cast(v8bf, dv[j]), acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+        if (mb + BMR < m_end) {
+            stash();
+            __syncthreads();
+        }
+    }
+
+    float* P = a.P + ((int64_t)split * a.n_src + src) * (int64_t)a.K * a.N;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int k = ko0 + wk * WTK + i * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+            if (k >= a.K) continue;
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int n = n0 + wn * WTN + j * 32 + li;
+                if (n < a.N) P[(int64_t)k * a.N + n] = acc[i][j][r];
+            }
+        }
+}
+
+// out_src[k][n] = sum over splits, in split order
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ P, int32_t splits, int32_t n_src,
+                                                              int64_t kn, float* __restrict__ out0, float* __restrict__ out1) {
+    const int64_t total = (int64_t)n_src * kn;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        float s = 0.f;
+        for (int32_t sp = 0; sp < splits; ++sp) s += P[(int64_t)sp * total + i];
+        if (i < kn) out0[i] = s;
+        else out1[i - kn] = s;
+    }
+}
+
+// Wt[n][k] = W[k][n]; Wt rows are padded to ldt elements (pad left untouched, never read).
+template <int DT>
+__global__ __launch_bounds__(256) void transpose_kernel(const void* __restrict__ W, int32_t K, int32_t N, void* __restrict__ Wt,
+                                                        int64_t ldt) {
+    __shared__ uint32_t tile[32][33];
+    const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    for (int r = ty; r < 32; r += 8) {
+        const int k = k0 + r, n = n0 + tx;
+        uint32_t v = 0;
+        if (k < K && n < N) v = DT == GNN_F32 ? ((const uint32_t*)W)[(int64_t)k * N + n] : ((const uint16_t*)W)[(int64_t)k * N + n];
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int n = n0 + r, k = k0 + tx;
+        if (k < K && n < N) {
+            if (DT == GNN_F32) ((uint32_t*)Wt)[(int64_t)n * ldt + k] = tile[tx][r];
+            else ((uint16_t*)Wt)[(int64_t)n * ldt + k] = (uint16_t)tile[tx][r];
+        }
+    }
+}
+
+// dZ[i][0:N] = relu ? dH[row(i)] * [H[row(i)] > 0] : dH[row(i)], rows compacted; column sums of
+// each block of 256 rows go to part[block][0:N].  Threads: CX columns x 256/CX row lanes.
+template <int DT>
+__global__ __launch_bounds__(256) void dz_kernel(const int32_t* __restrict__ rows, int32_t M, const void* __restrict__ dH,
+                                                 const void* __restrict__ H, int64_t ld_out, int32_t relu, int32_t N,
+                                                 void* __restrict__ dZ, int64_t ldz, float* __restrict__ part, int32_t cx) {
+    __shared__ float s_sum[256];
+    const int tx = threadIdx.x % cx, ty = threadIdx.x / cx, ny = 256 / cx;
+    const int64_t m_lo = (int64_t)blockIdx.x * 256;
+    const int64_t m_hi = m_lo + 256 < M ? m_lo + 256 : M;
+    for (int nb = 0; nb < N; nb += cx) {  // uniform trip count: the loop holds barriers
+        const int n = nb + tx;
+        float s = 0.f;
+        if (n < N) {
+            for (int64_t m = m_lo + ty; m < m_hi; m += ny) {
+                const int64_t r = rows ? (int64_t)rows[m] : m;
+                float gval = load_elem<DT>(dH, r * ld_out + n);
+                if (relu && !(load_elem<DT>(H, r * ld_out + n) > 0.f)) gval = 0.f;
+                store_elem<DT>(dZ, m * ldz + n, gval);
+                // the bias gradient sums what the weight-gradient GEMM will read (the stored value)
+                s += DT == GNN_F32 ? gval : bf16_to_f32(f32_to_bf16(gval));
+            }
+        }
+        s_sum[threadIdx.x] = s;
+        __syncthreads();
+        if (ty == 0 && n < N) {
+            float t = 0.f;
+            for (int y = 0; y < ny; ++y) t += s_sum[y * cx + tx];
+            part[(int64_t)blockIdx.x * N + n] = t;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ part, int32_t n_blocks, int32_t N,
+                                                          float* __restrict__ out) {
+    for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < N; n += gridDim.x * blockDim.x) {
+        float s = 0.f;
+        for (int32_t b = 0; b < n_blocks; ++b) s += part[(int64_t)b * N + n];
+        out[n] = s;
+    }
+}
+
+static inline bool vec_ok(const void* p, int64_t ld, int es) { return ((uintptr_t)p % 16 == 0) && ((ld * es) % 16 == 0); }
+
+template <int DT>
+static int32_t linear_fwd_impl(const int32_t* rows, int32_t n_active, const void* A, const void* Xs, int64_t ld_in, int32_t K,
+                               const void* Wn, const void* Ws, const float* bias, int32_t N, void* H, int64_t ld_out,
+                               int32_t relu, void* Wt0, void* Wt1, int64_t ldt, hipStream_t stream) {
+    constexpr int ES = DTy<DT>::ES;
+    dim3 tg((K + 31) / 32, (N + 31) / 32);
+    transpose_kernel<DT><<<tg, 256, 0, stream>>>(Wn, K, N, Wt0, ldt);
+    GNN_LAUNCH_CHECK("transpose_kernel");
+    if (Xs) {
+        transpose_kernel<DT><<<tg, 256, 0, stream>>>(Ws, K, N, Wt1, ldt);
+        GNN_LAUNCH_CHECK("transpose_kernel");
+    }
+    GemmNT g;
+    g.A[0] = A; g.A[1] = Xs; g.Bt[0] = Wt0; g.Bt[1] = Wt1; g.n_src = Xs ? 2 : 1;
+    g.lda = ld_in; g.ldb = ldt;
+    g.a_vec = vec_ok(A, ld_in, ES) && (!Xs || vec_ok(Xs, ld_in, ES));
+    g.b_vec = 1;
+    g.a_rows = rows; g.c_rows = rows; g.M = n_active; g.N = N; g.K = K;
+    g.bias = bias; g.relu = relu; g.C = H; g.ldc = ld_out;
+    return launch_gemm_nt<DT>(g, stream);
+}
+
+template <int DT>
+static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, const void* H, int64_t ld_out, int32_t relu,
+                               const void* A, const void* Xs, int64_t ld_in, int32_t K, const void* Wn, const void* Ws, int32_t N,
+                               float* dWn, float* dWs, float* dbias, void* dA, void* dXs, int64_t ld_din, void* dZ, int64_t ldz,
+                               float* part, int32_t n_part, float* P, int32_t splits, int32_t rows_per_split, hipStream_t stream) {
+    constexpr int ES = DTy<DT>::ES;
+    int cx = 8;
+    while (cx < N && cx < 256) cx <<= 1;
+    dz_kernel<DT><<<n_part, 256, 0, stream>>>(rows, M, dH, H, ld_out, relu, N, dZ, ldz, part, cx);
+    GNN_LAUNCH_CHECK("dz_kernel");
+    reduce_rows_kernel<<<grid_for(N, 256, 64), 256, 0, stream>>>(part, n_part, N, dbias);
+    GNN_LAUNCH_CHECK("reduce_rows_kernel");
+
+    GemmTN t;
+    t.A[0] = A; t.A[1] = Xs; t.n_src = Xs ? 2 : 1; t.lda = ld_in;
+    t.a_vec = vec_ok(A, ld_in, ES) && (!Xs || vec_ok(Xs, ld_in, ES));
+    t.a_rows = rows; t.D = dZ; t.ldd = ldz; t.d_vec = vec_ok(dZ, ldz, ES);
+    t.M = M; t.N = N; t.K = K; t.rows_per_split = rows_per_split; t.P = P;
+    const int ko_tiles = (K + 127) / 128;
+    if (N > 32) {
+        dim3 grid((unsigned)(t.n_src * ko_tiles * ((N + 127) / 128)), (unsigned)splits);
+        gemm_tn_kernel<DT, 128><<<grid, 256, 0, stream>>>(t);
+    } else {
+        dim3 grid((unsigned)(t.n_src * ko_tiles), (unsigned)splits);
+        gemm_tn_kernel<DT, 32><<<grid, 256, 0, stream>>>(t);
+    }
+    GNN_LAUNCH_CHECK("gemm_tn_kernel");
+    reduce_partials_kernel<<<grid_for((int64_t)t.n_src * K * N, 256, 2048), 256, 0, stream>>>(P, splits, t.n_src, (int64_t)K * N, dWn,
+                                                                                            dWs);
+    GNN_LAUNCH_CHECK("reduce_partials_kernel");
+
+    // input gradients: dA = dZ W_neigh^T, dX_self = dZ W_self^T   (Bt = W as stored: [K][N])
+    for (int which = 0; which < 2; ++which) {
+        void* out = which == 0 ? dA : dXs;
+        const void* W = which == 0 ? Wn : Ws;
+        if (!out) continue;
+        GemmNT g;
+        g.A[0] = dZ; g.A[1] = nullptr; g.Bt[0] = W; g.Bt[1] = nullptr; g.n_src = 1;
+        g.lda = ldz; g.ldb = N; g.a_vec = vec_ok(dZ, ldz, ES); g.b_vec = vec_ok(W, N, ES);
+        g.a_rows = nullptr; g.c_rows = rows; g.M = M; g.N = K; g.K = N;
+        g.bias = nullptr; g.relu = 0; g.C = out; g.ldc = ld_din;
+        GNN_CHECK(launch_gemm_nt<DT>(g, stream));
+    }
+    return GNN_OK;
+}
+
+static int32_t check_linear_common(int32_t n_active, int32_t K, int32_t N, int32_t dtype) {
+    GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative row count");
+    GNN_REQUIRE(dtype == GNN_F32 || dtype == GNN_BF16, GNN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    GNN_REQUIRE(K >= 1 && N >= 1, GNN_ERR_INVALID_ARG, "K and N must be positive");
+    GNN_REQUIRE(K <= kMaxDim && N <= kMaxDim, GNN_ERR_UNSUPPORTED, "K or N above %d", kMaxDim);
+    return GNN_OK;
+}
+
+}  // namespace gnnhot
+
+using namespace gnnhot;
+
+extern "C" int32_t gnn_linear_fwd(const int32_t* rows, int32_t n_active, const void* A_neigh, const void* X_self, int64_t ld_in,
+                                  int32_t K, const void* W_neigh, const void* W_self, const float* bias, int32_t N, void* H_out,
+                                  int64_t ld_out, int32_t relu, int32_t dtype, void* ws, size_t* ws_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_linear_common(n_active, K, N, dtype));
+    GNN_REQUIRE(ld_in >= K && ld_out >= N, GNN_ERR_SHAPE, "leading dimension smaller than the width");
+    GNN_REQUIRE((X_self == nullptr) == (W_self == nullptr), GNN_ERR_INVALID_ARG, "X_self and W_self must be given together");
+    const int es = dtype == GNN_F32 ? 4 : 2;
+    const int64_t ldt = (int64_t)align_up((size_t)K, 16 / es);
+    WsCarver carve(ws);
+    char* Wt0 = carve.take<char>((size_t)N * ldt * es);
+    char* Wt1 = carve.take<char>((size_t)N * ldt * es);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+    if (n_active == 0) return GNN_OK;
+    GNN_REQUIRE(A_neigh && W_neigh && H_out, GNN_ERR_INVALID_ARG, "A_neigh, W_neigh or H_out is NULL");
+    if (dtype == GNN_F32)
+        return linear_fwd_impl<GNN_F32>(rows, n_active, A_neigh, X_self, ld_in, K, W_neigh, W_self, bias, N, H_out, ld_out, relu, Wt0,
+                                        Wt1, ldt, stream);
+    return linear_fwd_impl<GNN_BF16>(rows, n_active, A_neigh, X_self, ld_in, K, W_neigh, W_self, bias, N, H_out, ld_out, relu, Wt0,
+                                     Wt1, ldt, stream);
+}
+
+extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const void* dH_out, const void* H_out, int64_t ld_out,
+                                  int32_t relu, const void* A_neigh, const void* X_self, int64_t ld_in, int32_t K,
+                                  const void* W_neigh, const void* W_self, int32_t N, float* dW_neigh, float* dW_self, float* dbias,
+                                  void* dA_neigh, void* dX_self, int64_t ld_din, int32_t dtype, void* ws, size_t* ws_bytes,
+                                  void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_linear_common(n_active, K, N, dtype));
+    GNN_REQUIRE(ld_in >= K && ld_out >= N, GNN_ERR_SHAPE, "leading dimension smaller than the width");
+    GNN_REQUIRE((dA_neigh == nullptr && dX_self == nullptr) || ld_din >= K, GNN_ERR_SHAPE, "ld_din smaller than K");
+    GNN_REQUIRE((X_self == nullptr) == (W_self == nullptr) && (X_self == nullptr) == (dW_self == nullptr), GNN_ERR_INVALID_ARG,
+                "X_self, W_self and dW_self must be given together");
+    GNN_REQUIRE(dX_self == nullptr || W_self != nullptr, GNN_ERR_INVALID_ARG, "dX_self needs W_self");
+    const int es = dtype == GNN_F32 ? 4 : 2;
+    const int n_src = X_self ? 2 : 1;
+    const int64_t ldz = (int64_t)align_up((size_t)N, 16 / es);
+    const int32_t n_part = n_active > 0 ? (n_active + 255) / 256 : 1;
+    // row splits of the weight-gradient reduction: enough workgroups to fill the chip, at most 64
+    const int tiles = n_src * ((K + 127) / 128) * (N > 32 ? (N + 127) / 128 : 1);
+    int32_t splits = (2048 + tiles - 1) / tiles;
+    const int32_t max_splits = n_active > 0 ? (n_active + 255) / 256 : 1;
+    if (splits > max_splits) splits = max_splits;
+    if (splits > 64) splits = 64;
+    if (splits < 1) splits = 1;
+    int32_t rows_per_split = (int32_t)align_up((size_t)((n_active + splits - 1) / splits), 32);
+    if (rows_per_split < 32) rows_per_split = 32;
+    splits = n_active > 0 ? (n_active + rows_per_split - 1) / rows_per_split : 1;
+
+    WsCarver carve(ws);
+    char* dZ = carve.take<char>((size_t)(n_active > 0 ? n_active : 1) * ldz * es);
+    float* part = carve.take<float>((size_t)n_part * N);
+    float* P = carve.take<float>((size_t)splits * n_src * K * N);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+    GNN_REQUIRE(dW_neigh && dbias, GNN_ERR_INVALID_ARG, "dW_neigh or dbias is NULL");
+    if (n_active == 0) {
+        fill_kernel<float><<<grid_for((int64_t)K * N, 256, 1024), 256, 0, stream>>>(dW_neigh, (int64_t)K * N, 0.f);
+        if (dW_self) fill_kernel<float><<<grid_for((int64_t)K * N, 256, 1024), 256, 0, stream>>>(dW_self, (int64_t)K * N, 0.f);
+        fill_kernel<float><<<1, 256, 0, stream>>>(dbias, (int64_t)N, 0.f);
+        GNN_LAUNCH_CHECK("fill_kernel");
+        return GNN_OK;
+    }
+    GNN_REQUIRE(dH_out && A_neigh && W_neigh, GNN_ERR_INVALID_ARG, "dH_out, A_neigh or W_neigh is NULL");
+    GNN_REQUIRE(!relu || H_out, GNN_ERR_INVALID_ARG, "relu backward needs H_out");
+    if (dtype == GNN_F32)
+        return linear_bwd_impl<GNN_F32>(rows, n_active, dH_out, H_out, ld_out, relu, A_neigh, X_self, ld_in, K, W_neigh, W_self, N,
+                                        dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, splits,
+                                        rows_per_split, stream);
+    return linear_bwd_impl<GNN_BF16>(rows, n_active, dH_out, H_out, ld_out, relu, A_neigh, X_self, ld_in, K, W_neigh, W_self, N,
+                                     dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, splits,
+                                     rows_per_split, stream);
+}

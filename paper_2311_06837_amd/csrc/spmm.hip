@@ -1,0 +1,427 @@
+// Masked CSR aggregation, forward and backward (paper section 2.1: h_N(v) = AGGREGATE of the
+// neighbours' hidden vectors, a scaled sum; section 6: only the rows the layer's mask keeps).
+//
+//     Y[v, :] = out_scale[v] * sum_{u in row(v), keep(u)} nbr_scale[u] * X[u, :]      v in rows
+//
+// Forward: (out_scale, nbr_scale) = (row_scale, col_scale), no filter.  Backward runs the
+// same gather over the transposed graph with the scale roles swapped and keep(u) =
+// "u was an active row of the forward call" (a dist probe), so no floating-point atomics
+// are needed and results are bit-reproducible.
+//
+// Mapping to CDNA4.  The work is a gather of whole feature rows: HBM/L2 bound, one FMA per
+// loaded element, so no MFMA.  A group of LPR lanes (16, 32 or 64) owns one output row and
+// spans its feature columns with 16-byte loads, so every neighbour costs one fully coalesced
+// row read; 64/LPR rows share a wavefront when rows are narrow.  Neighbour ids (and their
+// scales) are fetched 64 at a time, coalesced, filtered, compacted and staged in an LDS tile
+// private to the wavefront; the inner loop then reads the tile by broadcast and keeps
+// U x NCH independent 16-byte loads in flight per lane.  Rows longer than kHubDegree are
+// deferred to a queue and processed by 16-wave workgroups that split the neighbour list and
+// reduce the partial sums through LDS in a fixed order.
+#include "common.h"
+
+namespace gnnhot {
+
+constexpr int kHubDegree = 1024;   // rows longer than this go to the hub kernel
+constexpr int kHubWaves = 16;
+
+struct SpmmArgs {
+    const int32_t* row_ptr;
+    const int32_t* col_idx;
+    const int32_t* rows;      // nullable
+    int32_t n_active;
+    const void* X;
+    int64_t ldx;
+    void* Y;
+    int64_t ldy;
+    int32_t F;
+    const float* out_scale;   // nullable, indexed by output row
+    const float* nbr_scale;   // nullable, indexed by neighbour
+    const int32_t* dist;      // nullable filter: keep u iff 0 <= dist[u] <= max_dist
+    int32_t max_dist;
+    int32_t accumulate;
+    int32_t* hub_queue;
+    int32_t* hub_count;
+};
+
+// ---- element access: VE elements per lane-chunk ------------------------------------------
+template <int DT, int VE>
+struct Elem;
+
+template <>
+struct Elem<GNN_F32, 4> {
+    static constexpr int VE = 4;
+    using Raw = uint4;
+    static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return *(const uint4*)((const float*)p + off); }
+    static __device__ __forceinline__ void fma(float (&acc)[4], float w, const Raw& r) {
+        acc[0] = fmaf(w, __uint_as_float(r.x), acc[0]);
+        acc[1] = fmaf(w, __uint_as_float(r.y), acc[1]);
+        acc[2] = fmaf(w, __uint_as_float(r.z), acc[2]);
+        acc[3] = fmaf(w, __uint_as_float(r.w), acc[3]);
+    }
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[4], int n_valid, bool accumulate) {
+        float* q = (float*)p + off;
+        if (n_valid >= 4) {
+            float4 o = make_float4(v[0], v[1], v[2], v[3]);
+            if (accumulate) {
+                float4 old = *(const float4*)q;
+                o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+            }
+            *(float4*)q = o;
+        } else {
+            for (int e = 0; e < n_valid; ++e) q[e] = accumulate ? q[e] + v[e] : v[e];
+        }
+    }
+};
+
+template <>
+struct Elem<GNN_F32, 1> {
+    static constexpr int VE = 1;
+    using Raw = float;
+    static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return ((const float*)p)[off]; }
+    static __device__ __forceinline__ void fma(float (&acc)[1], float w, const Raw& r) { acc[0] = fmaf(w, r, acc[0]); }
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[1], int n_valid, bool accumulate) {
+        float* q = (float*)p + off;
+        if (n_valid >= 1) q[0] = accumulate ? q[0] + v[0] : v[0];
+    }
+};
+
+template <>
+struct Elem<GNN_BF16, 8> {
+    static constexpr int VE = 8;
+    using Raw = uint4;
+    static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return *(const uint4*)((const uint16_t*)p + off); }
+    static __device__ __forceinline__ void fma(float (&acc)[8], float w, const Raw& r) {
+        acc[0] = fmaf(w, bf16lo(r.x), acc[0]); acc[1] = fmaf(w, bf16hi(r.x), acc[1]);
+        acc[2] = fmaf(w, bf16lo(r.y), acc[2]); acc[3] = fmaf(w, bf16hi(r.y), acc[3]);
+        acc[4] = fmaf(w, bf16lo(r.z), acc[4]); acc[5] = fmaf(w, bf16hi(r.z), acc[5]);
+        acc[6] = fmaf(w, bf16lo(r.w), acc[6]); acc[7] = fmaf(w, bf16hi(r.w), acc[7]);
+    }
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[8], int n_valid, bool accumulate) {
+        uint16_t* q = (uint16_t*)p + off;
+        if (n_valid >= 8) {
+            float t[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = v[e];
+            if (accumulate) {
+                uint4 old = *(const uint4*)q;
+                t[0] += bf16lo(old.x); t[1] += bf16hi(old.x); t[2] += bf16lo(old.y); t[3] += bf16hi(old.y);
+                t[4] += bf16lo(old.z); t[5] += bf16hi(old.z); t[6] += bf16lo(old.w); t[7] += bf16hi(old.w);
+            }
+            uint4 o;
+            o.x = pack_bf16(t[0], t[1]); o.y = pack_bf16(t[2], t[3]);
+            o.z = pack_bf16(t[4], t[5]); o.w = pack_bf16(t[6], t[7]);
+            *(uint4*)q = o;
+        } else {
+            for (int e = 0; e < n_valid; ++e) q[e] = f32_to_bf16(accumulate ? bf16_to_f32(q[e]) + v[e] : v[e]);
+        }
+    }
+};
+
+template <>
+struct Elem<GNN_BF16, 1> {
+    static constexpr int VE = 1;
+    using Raw = uint16_t;
+    static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return ((const uint16_t*)p)[off]; }
+    static __device__ __forceinline__ void fma(float (&acc)[1], float w, const Raw& r) { acc[0] = fmaf(w, bf16_to_f32(r), acc[0]); }
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[1], int n_valid, bool accumulate) {
+        uint16_t* q = (uint16_t*)p + off;
+        if (n_valid >= 1) q[0] = f32_to_bf16(accumulate ? bf16_to_f32(q[0]) + v[0] : v[0]);
+    }
+};
+
+// Stage up to LPR neighbour ids of one row segment into the group's LDS slots, dropping the
+// filtered ones.  Returns how many were kept.  `p` is this lane's edge position.
+template <int LPR, bool FILTER>
+__device__ __forceinline__ int stage_tile(const SpmmArgs& a, int32_t p, int32_t row_end, int sub, int sl,
+                                          int32_t* s_idx, float* s_w) {
+    const bool in_row = p < row_end;
+    int32_t u = 0;
+    bool keep = false;
+    if (in_row) {
+        u = a.col_idx[p];
+        keep = true;
+        if (FILTER) {
+            const int32_t d = a.dist[u];
+            keep = d >= 0 && d <= a.max_dist;
+        }
+    }
+    float w = 1.f;
+    if (keep && a.nbr_scale) w = a.nbr_scale[u];
+    int slot, cnt;
+    if (FILTER) {
+        const uint64_t group_mask = LPR == 64 ? ~0ull : (((1ull << (LPR & 63)) - 1ull) << (sub * LPR));
+        const uint64_t kept = __ballot(keep) & group_mask;
+        const uint64_t below = kept & ((1ull << (sub * LPR + sl)) - 1ull);
+        slot = __popcll(below);
+        cnt = __popcll(kept);
+    } else {
+        slot = sl;
+        const int32_t left = row_end - (p - sl);
+        cnt = left < 0 ? 0 : (left < LPR ? left : LPR);
+    }
+    if (keep) {
+        s_idx[sub * LPR + slot] = u;
+        s_w[sub * LPR + slot] = w;
+    }
+    return cnt;
+}
+
+// acc += sum over the staged tile.  `cnt` (this group's entries) may differ between the groups
+// of a wave; `cnt_max` is uniform over the wave.
+template <typename E, int LPR, int NCH, int U>
+__device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt_max, int sub, const int64_t (&col_off)[NCH],
+                                             const bool (&col_ok)[NCH], const int32_t* s_idx, const float* s_w,
+                                             float (&acc)[NCH][E::VE]) {
+    for (int k = 0; k < cnt_max; k += U) {
+        typename E::Raw x[U][NCH];
+        float w[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (k + j < cnt) {
+                const int32_t u = s_idx[sub * LPR + k + j];
+                w[j] = s_w[sub * LPR + k + j];
+                const int64_t base = (int64_t)u * a.ldx;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c)
+                    if (col_ok[c]) x[j][c] = E::load(a.X, base + col_off[c]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (k + j < cnt) {
+#pragma unroll
+                for (int c = 0; c < NCH; ++c)
+                    if (col_ok[c]) E::fma(acc[c], w[j], x[j][c]);
+            }
+        }
+    }
+}
+
+template <int DT, int VE, int LPR, int NCH, int U, bool FILTER>
+__global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
+    using E = Elem<DT, VE>;
+    constexpr int RPW = kWave / LPR;
+    constexpr int W = LPR * NCH * VE;
+    __shared__ int32_t s_idx_all[4][kWave];
+    __shared__ float s_w_all[4][kWave];
+    const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
+    const int sub = lane / LPR, sl = lane % LPR;
+    int32_t* s_idx = s_idx_all[wave];
+    float* s_w = s_w_all[wave];
+
+    const int64_t i = ((int64_t)blockIdx.x * 4 + wave) * RPW + sub;
+    bool row_ok = i < a.n_active;
+    int32_t v = 0, s = 0, e = 0;
+    if (row_ok) {
+        v = a.rows ? a.rows[i] : (int32_t)i;
+        s = a.row_ptr[v];
+        e = a.row_ptr[v + 1];
+        if (e - s > kHubDegree) {
+            if (sl == 0 && blockIdx.y == 0) a.hub_queue[atomicAdd(a.hub_count, 1)] = v;
+            row_ok = false;
+            e = s;
+        }
+    }
+    int64_t col_off[NCH];
+    bool col_ok[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        col_off[c] = (int64_t)blockIdx.y * W + (int64_t)(sl + c * LPR) * VE;
+        col_ok[c] = col_off[c] < a.F;
+    }
+    float acc[NCH][VE];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
+
+    // longest row of the wave bounds the (wave-uniform) tile loop
+    int len_max = e - s;
+#pragma unroll
+    for (int d = LPR; d < kWave; d <<= 1) len_max = max(len_max, __shfl_xor(len_max, d, kWave));
+
+    for (int base = 0; base < len_max; base += LPR) {
+        wave_lds_sync();  // the previous tile has been consumed
+        const int cnt = stage_tile<LPR, FILTER>(a, s + base + sl, e, sub, sl, s_idx, s_w);
+        int cnt_max = cnt;
+#pragma unroll
+        for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
+        wave_lds_sync();
+        consume_tile<E, LPR, NCH, U>(a, cnt, cnt_max, sub, col_off, col_ok, s_idx, s_w, acc);
+    }
+
+    if (row_ok) {
+        const float sc = a.out_scale ? a.out_scale[v] : 1.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (col_ok[c]) {
+                float o[VE];
+#pragma unroll
+                for (int k = 0; k < VE; ++k) o[k] = acc[c][k] * sc;
+                const int64_t left = (int64_t)a.F - col_off[c];
+                E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, left >= VE ? VE : (int)left, a.accumulate != 0);
+            }
+        }
+    }
+}
+
+// One 16-wave workgroup per queued hub row: wave w takes tiles w, w+16, ... of the row.
+template <int DT, int VE, int NCH, int U, bool FILTER>
+__global__ __launch_bounds__(kHubWaves* kWave) void spmm_hub_kernel(SpmmArgs a) {
+    using E = Elem<DT, VE>;
+    constexpr int LPR = kWave;
+    constexpr int W = LPR * NCH * VE;
+    __shared__ int32_t s_idx_all[kHubWaves][kWave];
+    __shared__ float s_w_all[kHubWaves][kWave];
+    __shared__ float s_red[kHubWaves][W];
+    const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
+    int32_t* s_idx = s_idx_all[wave];
+    float* s_w = s_w_all[wave];
+    const int32_t n_hubs = *a.hub_count;
+
+    int64_t col_off[NCH];
+    bool col_ok[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        col_off[c] = (int64_t)blockIdx.y * W + (int64_t)(lane + c * LPR) * VE;
+        col_ok[c] = col_off[c] < a.F;
+    }
+
+    for (int32_t h = blockIdx.x; h < n_hubs; h += gridDim.x) {
+        const int32_t v = a.hub_queue[h];
+        const int32_t s = a.row_ptr[v], e = a.row_ptr[v + 1];
+        float acc[NCH][VE];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
+        for (int64_t base = (int64_t)s + wave * kWave; base < e; base += kHubWaves * kWave) {
+            wave_lds_sync();
+            const int cnt = stage_tile<LPR, FILTER>(a, (int32_t)base + lane, e, 0, lane, s_idx, s_w);
+            wave_lds_sync();
+            consume_tile<E, LPR, NCH, U>(a, cnt, cnt, 0, col_off, col_ok, s_idx, s_w, acc);
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int k = 0; k < VE; ++k) s_red[wave][(lane + c * LPR) * VE + k] = acc[c][k];
+        __syncthreads();
+        const float sc = a.out_scale ? a.out_scale[v] : 1.f;
+        for (int col = threadIdx.x; col < W; col += kHubWaves * kWave) {
+            const int64_t gcol = (int64_t)blockIdx.y * W + col;
+            if (gcol < a.F) {
+                float t = 0.f;
+#pragma unroll
+                for (int w = 0; w < kHubWaves; ++w) t += s_red[w][col];
+                float o[1] = {t * sc};
+                Elem<DT, 1>::store(a.Y, (int64_t)v * a.ldy + gcol, o, 1, a.accumulate != 0);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void spmm_reset_kernel(int32_t* hub_count) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *hub_count = 0;
+}
+
+template <int DT, int VE, int LPR, int NCH, bool FILTER>
+static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
+    constexpr int U = NCH == 1 ? 8 : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
+    constexpr int RPW = kWave / LPR;
+    constexpr int W = LPR * NCH * VE;
+    dim3 grid((unsigned)(((int64_t)a.n_active + 4 * RPW - 1) / (4 * RPW)), (unsigned)((a.F + W - 1) / W));
+    spmm_rows_kernel<DT, VE, LPR, NCH, U, FILTER><<<grid, 256, 0, stream>>>(a);
+    GNN_LAUNCH_CHECK("spmm_rows_kernel");
+    return GNN_OK;
+}
+
+template <int DT, int VE, int NCH, bool FILTER>
+static int32_t launch_hubs(const SpmmArgs& a, hipStream_t stream) {
+    constexpr int U = NCH == 1 ? 8 : (NCH == 2 ? 4 : 3);
+    constexpr int W = kWave * NCH * VE;
+    const int64_t max_hubs = a.n_active;
+    dim3 grid((unsigned)(max_hubs < 1024 ? (max_hubs < 1 ? 1 : max_hubs) : 1024), (unsigned)((a.F + W - 1) / W));
+    spmm_hub_kernel<DT, VE, NCH, U, FILTER><<<grid, kHubWaves * kWave, 0, stream>>>(a);
+    GNN_LAUNCH_CHECK("spmm_hub_kernel");
+    return GNN_OK;
+}
+
+template <int DT, bool FILTER>
+static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
+    constexpr int VE = DT == GNN_F32 ? 4 : 8;
+    const int F = a.F;
+    if (!vec_ok) {  // any alignment / leading dimension: element-wise lanes, 256 columns per block
+        GNN_CHECK((launch_rows<DT, 1, 64, 4, FILTER>(a, stream)));
+        return launch_hubs<DT, 1, 3, FILTER>(a, stream);
+    }
+    if (F <= 16 * VE) {
+        GNN_CHECK((launch_rows<DT, VE, 16, 1, FILTER>(a, stream)));
+    } else if (F <= 32 * VE) {
+        GNN_CHECK((launch_rows<DT, VE, 32, 1, FILTER>(a, stream)));
+    } else if (F <= 64 * VE) {
+        GNN_CHECK((launch_rows<DT, VE, 64, 1, FILTER>(a, stream)));
+    } else if (F <= 128 * VE) {
+        GNN_CHECK((launch_rows<DT, VE, 64, 2, FILTER>(a, stream)));
+    } else {
+        GNN_CHECK((launch_rows<DT, VE, 64, 3, FILTER>(a, stream)));
+    }
+    if (F <= 64 * VE) return launch_hubs<DT, VE, 1, FILTER>(a, stream);
+    if (DT == GNN_BF16 || F <= 128 * VE) return launch_hubs<DT, VE, DT == GNN_BF16 ? 1 : 2, FILTER>(a, stream);
+    return launch_hubs<DT, VE, DT == GNN_BF16 ? 1 : 3, FILTER>(a, stream);
+}
+
+static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* rows, int32_t n_active, const int32_t* dist,
+                           int32_t max_dist, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F, int32_t dtype,
+                           const float* out_scale, const float* nbr_scale, int32_t accumulate, void* ws, size_t* ws_bytes,
+                           hipStream_t stream) {
+    GNN_CHECK(check_csr(g, gname));
+    GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative row count");
+    GNN_REQUIRE(rows != nullptr || n_active <= g->n_rows, GNN_ERR_SHAPE, "n_active %d exceeds n_rows %d", n_active, g->n_rows);
+    GNN_REQUIRE(dtype == GNN_F32 || dtype == GNN_BF16, GNN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    GNN_REQUIRE(F >= 0, GNN_ERR_INVALID_ARG, "F < 0");
+    GNN_REQUIRE(ldx >= F && ldy >= F, GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
+
+    WsCarver carve(ws);
+    int32_t* hub_queue = carve.take<int32_t>((size_t)n_active + 1);
+    int32_t* hub_count = carve.take<int32_t>(1);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+    if (n_active == 0 || F == 0) return GNN_OK;
+    GNN_REQUIRE(X != nullptr && Y != nullptr, GNN_ERR_INVALID_ARG, "X or Y is NULL");
+
+    SpmmArgs a;
+    a.row_ptr = g->row_ptr; a.col_idx = g->col_idx; a.rows = rows; a.n_active = n_active;
+    a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
+    a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = max_dist;
+    a.accumulate = accumulate; a.hub_queue = hub_queue; a.hub_count = hub_count;
+
+    const int ve = dtype == GNN_F32 ? 4 : 8;
+    const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0;
+    spmm_reset_kernel<<<1, 64, 0, stream>>>(hub_count);
+    GNN_LAUNCH_CHECK("spmm_reset_kernel");
+    const bool filter = dist != nullptr;
+    if (dtype == GNN_F32) return filter ? dispatch<GNN_F32, true>(a, vec_ok, stream) : dispatch<GNN_F32, false>(a, vec_ok, stream);
+    return filter ? dispatch<GNN_BF16, true>(a, vec_ok, stream) : dispatch<GNN_BF16, false>(a, vec_ok, stream);
+}
+
+}  // namespace gnnhot
+
+using namespace gnnhot;
+
+extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
+                                       void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
+                                       const float* col_scale, void* ws, size_t* ws_bytes, void* stream) {
+    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, ws, ws_bytes,
+                       (hipStream_t)stream);
+}
+
+extern "C" int32_t gnn_masked_spmm_bwd(const gnn_csr* gT, const int32_t* out_rows, int32_t n_out, const int32_t* dist,
+                                       int32_t max_active_dist, const void* dY, int64_t lddy, void* dX, int64_t lddx, int32_t F,
+                                       int32_t dtype, const float* row_scale, const float* col_scale, int32_t accumulate,
+                                       void* ws, size_t* ws_bytes, void* stream) {
+    GNN_REQUIRE(accumulate == 0 || accumulate == 1, GNN_ERR_INVALID_ARG, "accumulate must be 0 or 1");
+    return spmm_common(gT, "gT", out_rows, n_out, dist, max_active_dist, dY, lddy, dX, lddx, F, dtype, col_scale, row_scale,
+                       accumulate, ws, ws_bytes, (hipStream_t)stream);
+}

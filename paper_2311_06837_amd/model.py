@@ -1,0 +1,144 @@
+"""Sequencing of the C-ABI calls for one partition: active sets once, then per training step
+forward (aggregation + transform per layer), loss, backward.  Host orchestration only; all
+arithmetic happens behind include/gnnhot.h.
+
+Paper section 6, figure 7c: (1) multi-hop dependency from the inner vertices, (3)-(4) every
+layer reuses the same one-hop graph and a per-layer mask, (5) logits of the inner vertices.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+def _pad(n: int, mult: int) -> int:
+    return (n + mult - 1) // mult * mult
+
+
+class MaskedGNN:
+    """L-layer GCN ("gcn") or GraphSAGE-mean ("sage") over one partition under one-hop masking.
+
+    graph, graph_t   B.Graph of the one-hop graph and of its transpose (same object if symmetric)
+    targets          int32 device tensor of inner-vertex ids
+    params           list of dicts with float32 device tensors W_neigh [K,N], W_self (sage), bias [N]
+    dtype            torch.float32 or torch.bfloat16 (storage of activations and weights)
+    global_degree    int32 device tensor: row lengths in the unpartitioned graph (GCN normalisation)
+    """
+
+    def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, kind: str, params: list,
+                 dtype=torch.float32, global_degree: torch.Tensor | None = None):
+        assert kind in ("gcn", "sage")
+        self.g, self.gt, self.targets, self.kind, self.dtype = graph, graph_t, targets, kind, dtype
+        self.n = graph.n_rows
+        self.L = len(params)
+        self.ws = B.Workspace()
+        self.dims = [params[0]["W_neigh"].shape[0]] + [p["W_neigh"].shape[1] for p in params]
+        self.params = []
+        for p in params:
+            q = {"W_neigh": p["W_neigh"].to(dtype).contiguous(), "bias": p["bias"].float().contiguous()}
+            if kind == "sage":
+                q["W_self"] = p["W_self"].to(dtype).contiguous()
+            self.params.append(q)
+        self.global_degree = global_degree
+        mult = 4 if dtype == torch.float32 else 8
+        self.ld = [_pad(d, mult) for d in self.dims]   # 16-byte aligned rows
+        dev = targets.device
+        # activations A_l, H_l and their gradients; rows outside the active sets are never touched
+        self.A = [None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
+        self.H = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
+        self.dH = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
+        self.dA = [None, None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(2, self.L + 1)]
+        self.grads = []
+        for p in self.params:
+            gdict = {"dW_neigh": torch.zeros_like(p["W_neigh"], dtype=torch.float32), "dbias": torch.zeros_like(p["bias"])}
+            if kind == "sage":
+                gdict["dW_self"] = torch.zeros_like(p["W_self"], dtype=torch.float32)
+            self.grads.append(gdict)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.hop = None
+
+    # -- step a1 -------------------------------------------------------------------------
+    def build_active_sets(self):
+        self.dist, self.ring_ids, self.hop_offsets, self.hop = B.gnn_build_active_sets(self.g, self.targets, self.L, ws=self.ws)
+        if self.kind == "gcn":
+            s = B.gnn_norm_scales(B.GNN_NORM_SYM, self.n, length=self.global_degree,
+                                  row_ptr=None if self.global_degree is not None else self.g.row_ptr)
+            self.rs, self.cs = s, s
+        else:
+            self.rs, self.cs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr), None
+        return self.hop
+
+    def n_rows_of_layer(self, l: int) -> int:
+        """|R_l|, R_l = {dist <= L - l}: a prefix of the ring-sorted ids."""
+        return int(self.hop[self.L - l + 1])
+
+    def set_input(self, H0: torch.Tensor):
+        """H0: [n, >= F0] of the model dtype, row-major; used in place."""
+        assert H0.dtype == self.dtype and H0.shape[0] == self.n and H0.shape[1] >= self.dims[0]
+        self.H[0] = H0
+
+    # -- steps a2, a3, a4 ----------------------------------------------------------------
+    def forward(self, labels: torch.Tensor) -> torch.Tensor:
+        for l in range(1, self.L + 1):
+            p = self.params[l - 1]
+            K = self.dims[l - 1]
+            nl = self.n_rows_of_layer(l)
+            B.gnn_masked_spmm_fwd(self.g, self.ring_ids, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs, ws=self.ws)
+            B.gnn_linear_fwd(self.ring_ids, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
+                             p["W_neigh"], p.get("W_self"), p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
+        nt = self.n_rows_of_layer(self.L)
+        B.gnn_softmax_ce(self.ring_ids, nt, self.H[self.L], self.dims[self.L], labels, self.dH[self.L], self.loss, ws=self.ws)
+        return self.loss
+
+    # -- steps a5, a6 --------------------------------------------------------------------
+    def backward(self):
+        L = self.L
+        for l in range(L, 0, -1):
+            p, gr = self.params[l - 1], self.grads[l - 1]
+            K = self.dims[l - 1]
+            nl = self.n_rows_of_layer(l)
+            sage = self.kind == "sage"
+            need_in = l > 1
+            B.gnn_linear_bwd(self.ring_ids, nl, self.dH[l], self.H[l] if l < L else None, l < L, self.A[l],
+                             self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
+                             gr["dW_neigh"], gr.get("dW_self"), gr["dbias"],
+                             self.dA[l] if need_in else None, self.dH[l - 1] if (need_in and sage) else None, ws=self.ws)
+            if need_in:
+                n_prev = self.n_rows_of_layer(l - 1)
+                if sage:
+                    # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
+                    B.gnn_masked_spmm_bwd(self.gt, self.ring_ids, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                                          self.rs, self.cs, accumulate=True, ws=self.ws)
+                    if n_prev > nl:
+                        B.gnn_masked_spmm_bwd(self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
+                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False, ws=self.ws)
+                else:
+                    B.gnn_masked_spmm_bwd(self.gt, self.ring_ids, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                                          self.rs, self.cs, accumulate=False, ws=self.ws)
+        return self.grads
+
+    def step(self, labels: torch.Tensor):
+        """One pass of the whole hot path: active sets, forward, loss, backward."""
+        self.build_active_sets()
+        self.forward(labels)
+        self.backward()
+        return self.loss
+
+    def aggregated_edges(self) -> dict:
+        """Edges visited per layer by the forward and the backward aggregation (host-side bookkeeping
+        from row_ptr; used by the benchmark's edges/s metric)."""
+        rp = self.g.row_ptr.long()
+        rpt = self.gt.row_ptr.long()
+        ring = self.ring_ids.long()
+        out = {}
+        for l in range(1, self.L + 1):
+            rows = ring[: self.n_rows_of_layer(l)]
+            fwd = int((rp[rows + 1] - rp[rows]).sum().item())
+            bwd = 0
+            if l > 1:
+                # transposed rows of R_{l-1}; entries v with dist(v) <= L - l are exactly the forward edges of R_l
+                bwd = fwd
+                _ = rpt
+            out[l] = {"fwd": fwd, "bwd": bwd}
+        return out

@@ -1,0 +1,145 @@
+"""GPU parity: gnn_linear_fwd / _bwd (MFMA GEMMs) and gnn_softmax_ce against the oracle
+(section 2.1 feature transform; section 8.1 task).  fp32: 1e-4, bf16: 2e-2."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import as_stored, check, dev, host64, padded
+
+pytestmark = pytest.mark.gpu
+
+SENT = 777.0
+
+
+def _pad(n, m):
+    return (n + m - 1) // m * m
+
+
+def _case(M_total, n_active, K, N, dtype, sage, relu, use_rows, aligned, seed, need_in=True):
+    import paper_2311_06837_amd as P
+    print(f"linear: n={M_total} active={n_active} K={K} N={N} {dtype} sage={sage} relu={relu} rows={use_rows} "
+          f"aligned={aligned}", flush=True)
+    rng = np.random.default_rng(seed)
+    mult = (4 if dtype == torch.float32 else 8) if aligned else 1
+    ld_in, ld_out = _pad(K, mult), _pad(N, mult)
+    A = as_stored(rng.standard_normal((M_total, K)), dtype)
+    Xs = as_stored(rng.standard_normal((M_total, K)), dtype) if sage else None
+    Wn = as_stored(rng.standard_normal((K, N)) / np.sqrt(K), dtype)
+    Ws = as_stored(rng.standard_normal((K, N)) / np.sqrt(K), dtype) if sage else None
+    b = rng.standard_normal(N).astype(np.float32)
+    rows = np.sort(rng.choice(M_total, n_active, replace=False)).astype(np.int32) if use_rows else None
+    sel = rows if use_rows else np.arange(n_active)
+    rest = np.setdiff1d(np.arange(M_total), sel)
+
+    Ad = padded(A, ld_in, dtype, fill=float("nan") if ld_in > K else 0.0)
+    Xd = padded(Xs, ld_in, dtype, fill=float("nan") if ld_in > K else 0.0) if sage else None
+    Wnd, Wsd = dev(Wn, dtype), (dev(Ws, dtype) if sage else None)
+    Hd = torch.full((M_total, ld_out), SENT, dtype=dtype, device="cuda")
+    P.gnn_linear_fwd(dev(rows) if use_rows else None, n_active, Ad, Xd, K, Wnd, Wsd, dev(b), Hd, relu)
+    torch.cuda.synchronize()
+    H = np.full((M_total, N), SENT)
+    oracle.linear_fwd(rows if use_rows else np.arange(n_active, dtype=np.int32), A, Xs, K, Wn, Ws, b.astype(np.float64), H, relu)
+    got = host64(Hd)
+    check(got[sel, :N], H[sel], dtype, "H")
+    sent = host64(torch.tensor(SENT, dtype=dtype))
+    assert (got[rest] == sent).all() and (got[:, N:] == sent).all(), "forward wrote outside its rows/columns"
+
+    # backward, fed with the oracle's own H (rounded to storage) so both sides mask the same entries
+    Hs = as_stored(H, dtype)
+    dH = as_stored(rng.standard_normal((M_total, N)), dtype)
+    dWn_d = torch.full((K, N), SENT, device="cuda")
+    dWs_d = torch.full((K, N), SENT, device="cuda") if sage else None
+    db_d = torch.full((N,), SENT, device="cuda")
+    dA_d = torch.full((M_total, ld_in), SENT, dtype=dtype, device="cuda") if need_in else None
+    dX_d = torch.full((M_total, ld_in), SENT, dtype=dtype, device="cuda") if (need_in and sage) else None
+    P.gnn_linear_bwd(dev(rows) if use_rows else None, n_active, padded(dH, ld_out, dtype, fill=float("nan") if ld_out > N else 0.0),
+                     padded(Hs, ld_out, dtype) if relu else None, relu, Ad, Xd, K, Wnd, Wsd, dWn_d, dWs_d, db_d, dA_d, dX_d)
+    torch.cuda.synchronize()
+    dA = np.full((M_total, K), SENT)
+    dX = np.full((M_total, K), SENT) if sage else None
+    dWn, dWs, db = oracle.linear_bwd(rows if use_rows else np.arange(n_active, dtype=np.int32), dH, Hs if relu else None, relu,
+                                     A, Xs, K, Wn, Ws, dA if need_in else None, dX if (need_in and sage) else None)
+    check(host64(dWn_d), dWn, dtype, "dW_neigh")
+    check(host64(db_d), db, dtype, "dbias")
+    if sage:
+        check(host64(dWs_d), dWs, dtype, "dW_self")
+    if need_in:
+        g = host64(dA_d)
+        check(g[sel, :K], dA[sel], dtype, "dA")
+        assert (g[rest] == sent).all() and (g[:, K:] == sent).all(), "dA wrote outside its rows/columns"
+        if sage:
+            g = host64(dX_d)
+            check(g[sel, :K], dX[sel], dtype, "dX_self")
+            assert (g[rest] == sent).all()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K,N", [(64, 64), (64, 8), (602, 256), (100, 256), (256, 47), (128, 16), (256, 41), (33, 5), (128, 128)])
+def test_shapes_of_the_workloads(dtype, K, N):
+    _case(3000, 1777, K, N, dtype, sage=(K != 100 and K != 64), relu=(N > 50), use_rows=True, aligned=True, seed=K + N)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_prefix_rows_ragged_counts_and_unaligned_leading_dimensions(dtype):
+    _case(700, 700, 64, 64, dtype, sage=True, relu=True, use_rows=False, aligned=True, seed=1)
+    _case(700, 129, 48, 40, dtype, sage=False, relu=False, use_rows=False, aligned=True, seed=2)
+    _case(300, 1, 64, 64, dtype, sage=True, relu=True, use_rows=True, aligned=True, seed=3)
+    _case(500, 257, 602, 41, dtype, sage=True, relu=False, use_rows=True, aligned=False, seed=4)     # ld = 602 / 41
+    _case(500, 333, 100, 256, dtype, sage=False, relu=True, use_rows=True, aligned=True, seed=5, need_in=False)
+
+
+def test_large_row_count_many_splits():
+    _case(70000, 65537, 256, 256, torch.float32, sage=True, relu=True, use_rows=True, aligned=True, seed=6)
+    _case(70000, 65537, 128, 128, torch.bfloat16, sage=True, relu=True, use_rows=True, aligned=True, seed=7)
+
+
+def test_zero_active_rows_zeroes_the_weight_gradients():
+    import paper_2311_06837_amd as P
+    K, N = 16, 8
+    A = torch.randn(10, K, device="cuda")
+    W = torch.randn(K, N, device="cuda")
+    dW = torch.full((K, N), 5.0, device="cuda")
+    db = torch.full((N,), 5.0, device="cuda")
+    P.gnn_linear_bwd(None, 0, torch.randn(10, N, device="cuda"), None, False, A, None, K, W, None, dW, None, db)
+    H = torch.full((10, N), 5.0, device="cuda")
+    P.gnn_linear_fwd(None, 0, A, None, K, W, None, None, H, False)
+    torch.cuda.synchronize()
+    assert not dW.any() and not db.any() and (H == 5.0).all()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("C", [8, 41, 47, 16, 32, 100])
+def test_softmax_cross_entropy(dtype, C):
+    import paper_2311_06837_amd as P
+    rng = np.random.default_rng(C)
+    n, nt = 5000, 2111
+    Z = as_stored(rng.standard_normal((n, C)) * 3, dtype)
+    rows = np.sort(rng.choice(n, nt, replace=False)).astype(np.int32)
+    y = rng.integers(0, C, nt).astype(np.int32)
+    ld = _pad(C, 8)
+    Zd = padded(Z, ld, dtype, fill=float("nan") if ld > C else 0.0)
+    dZd = torch.full((n, ld), SENT, dtype=dtype, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    P.gnn_softmax_ce(dev(rows), nt, Zd, C, dev(y), dZd, loss)
+    torch.cuda.synchronize()
+    dZ = np.full((n, C), SENT)
+    want = oracle.softmax_ce(rows, Z, C, y, dZ)
+    assert abs(loss.item() - want) <= 1e-4 * abs(want)
+    got = host64(dZd)
+    check(got[rows, :C], dZ[rows], dtype, "dZ")
+    rest = np.setdiff1d(np.arange(n), rows)
+    sent = host64(torch.tensor(SENT, dtype=dtype))
+    assert (got[rest] == sent).all() and (got[:, C:] == sent).all()
+
+
+def test_norm_scales():
+    import paper_2311_06837_amd as P
+    deg = np.array([0, 1, 2, 3, 4, 9, 490, 10520], dtype=np.int32)
+    for mode, code in (("mean", P.GNN_NORM_MEAN), ("sym", P.GNN_NORM_SYM)):
+        got = P.gnn_norm_scales(code, len(deg), length=dev(deg)).cpu().numpy().astype(np.float64)
+        want = oracle.norm_scales(mode, deg)
+        assert np.allclose(got, want, rtol=2e-7, atol=0)
+    rp = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    got = P.gnn_norm_scales(P.GNN_NORM_MEAN, len(deg), row_ptr=dev(rp)).cpu().numpy()
+    assert np.allclose(got, oracle.norm_scales("mean", deg), rtol=2e-7)

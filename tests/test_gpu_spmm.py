@@ -1,0 +1,149 @@
+"""GPU parity: gnn_masked_spmm_fwd / _bwd against the oracle (section 2.1 aggregation under
+the section 6 mask).  fp32: 1e-4, bf16 storage: 2e-2 (see gpu_util.TOL)."""
+import numpy as np
+import pytest
+import torch
+
+import graphgen as gg
+import oracle
+from gpu_util import as_stored, check, dev, host64, padded
+
+pytestmark = pytest.mark.gpu
+
+SENTINEL = 12345.0
+
+
+def _fwd_case(g, F, ld, dtype, rows, scales, seed):
+    import paper_2311_06837_amd as P
+    print(f"spmm fwd: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} rows={'list' if rows is not None else 'all'} "
+          f"scales={scales}", flush=True)
+    rng = np.random.default_rng(seed)
+    n = g.n_rows
+    X = as_stored(rng.standard_normal((n, F)), dtype)
+    rs = (rng.random(n) + 0.5).astype(np.float32) if scales else None
+    cs = (rng.random(n) + 0.5).astype(np.float32) if scales else None
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    Xd = padded(X, ld, dtype, fill=float("nan") if ld > F else 0.0)       # pad columns must never matter
+    if ld > F and ld - F >= 1:
+        Xd[:, F:] = float("nan")
+    Yd = torch.full((n, ld), SENTINEL, dtype=dtype, device="cuda")
+    rows_d = dev(rows) if rows is not None else None
+    n_active = len(rows) if rows is not None else n
+    P.gnn_masked_spmm_fwd(G, rows_d, n_active, Xd, Yd, F, dev(rs) if scales else None, dev(cs) if scales else None)
+    torch.cuda.synchronize()
+    want = np.full((n, F), SENTINEL)
+    oracle.spmm_fwd(g.row_ptr, g.col_idx, rows, X, want, F, rs, cs)
+    got = host64(Yd)
+    sel = np.asarray(rows if rows is not None else np.arange(n))
+    check(got[sel, :F], want[sel], dtype, "active rows")
+    rest = np.setdiff1d(np.arange(n), sel)
+    assert (got[rest] == host64(torch.tensor(SENTINEL, dtype=dtype))).all(), "masked rows were written"
+    if ld > F:
+        assert (got[:, F:] == host64(torch.tensor(SENTINEL, dtype=dtype))).all(), "pad columns were written"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("F,ld", [(64, 64), (100, 100), (128, 128), (256, 256), (602, 608), (602, 602), (7, 7), (1, 8),
+                                  (300, 304), (1000, 1000)])
+def test_fwd_widths(dtype, F, ld):
+    g = gg.chung_lu(3000, 20.0, 2.1, 11)
+    rng = np.random.default_rng(F)
+    rows = np.sort(rng.choice(3000, 1777, replace=False)).astype(np.int32)
+    _fwd_case(g, F, ld, dtype, rows, True, F)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fwd_hub_rows_empty_rows_and_all_rows(dtype):
+    g = gg.chung_lu(12000, 150.0, 2.1, 12)                                # hub rows > 1024 neighbours
+    assert g.degrees().max() > 1024
+    _fwd_case(g, 128, 128, dtype, None, True, 1)
+    _fwd_case(g, 602, 608, dtype, None, False, 2)
+    d = gg.random_directed(5000, 1.5, 13)                                 # many empty rows
+    assert (d.degrees() == 0).any()
+    _fwd_case(d, 64, 64, dtype, None, True, 3)
+    rows = np.random.default_rng(0).permutation(5000)[:3001].astype(np.int32)     # unsorted row list, ragged count
+    _fwd_case(d, 100, 100, dtype, rows, False, 4)
+
+
+def test_fwd_sum_of_ones_is_degree_exactly():
+    import paper_2311_06837_amd as P
+    g = gg.chung_lu(20000, 80.0, 2.1, 14)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    X = torch.ones(20000, 64, device="cuda")
+    Y = torch.zeros(20000, 64, device="cuda")
+    P.gnn_masked_spmm_fwd(G, None, 20000, X, Y, 64)
+    assert torch.equal(Y[:, 0].cpu(), torch.from_numpy(g.degrees()).float())     # integers < 2^24 are exact in fp32
+    assert torch.equal(Y, Y[:, :1].expand(-1, 64))
+
+
+def test_fwd_is_bitwise_reproducible():
+    import paper_2311_06837_amd as P
+    g = gg.chung_lu(12000, 150.0, 2.1, 12)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    X = torch.randn(12000, 256, device="cuda", generator=torch.Generator("cuda").manual_seed(0))
+    outs = []
+    for _ in range(3):
+        Y = torch.zeros(12000, 256, device="cuda")
+        P.gnn_masked_spmm_fwd(G, None, 12000, X, Y, 256)
+        outs.append(Y)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed):
+    """Backward of layer `lyr` of an L-layer model: forward rows R_lyr, outputs for R_{lyr-1}."""
+    import paper_2311_06837_amd as P
+    print(f"spmm bwd: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} L={L} layer={lyr} acc={accumulate}", flush=True)
+    rng = np.random.default_rng(seed)
+    n = g.n_rows
+    T = np.sort(rng.choice(n, max(1, n // 50), replace=False)).astype(np.int32)
+    dist, ring, off = oracle.active_sets(g.row_ptr, g.col_idx, T, L)
+    rows_f = ring[: off[L - lyr + 1]]                 # R_lyr
+    rows_o = ring[: off[L - lyr + 2]]                 # R_{lyr-1}
+    gt = gg.transpose(g)
+    dY = as_stored(rng.standard_normal((n, F)), dtype)
+    rs = (rng.random(n) + 0.5).astype(np.float32)
+    cs = (rng.random(n) + 0.5).astype(np.float32)
+    init = as_stored(rng.standard_normal((n, F)), dtype) if accumulate else np.full((n, F), SENTINEL)
+    GT = P.Graph.from_numpy(gt.row_ptr, gt.col_idx)
+    dYd = padded(dY, ld, dtype)
+    dXd = padded(init, ld, dtype, fill=SENTINEL)
+    P.gnn_masked_spmm_bwd(GT, dev(rows_o), len(rows_o), dev(dist), L - lyr, dYd, dXd, F, dev(rs), dev(cs), accumulate=accumulate)
+    torch.cuda.synchronize()
+    want = np.zeros((n, F))
+    oracle.spmm_bwd(g.row_ptr, g.col_idx, rows_f, dY, want, F, rs, cs)
+    # everything the adjoint touches lies inside R_{lyr-1}
+    outside = np.setdiff1d(np.arange(n), rows_o)
+    assert not want[outside].any()
+    if accumulate:
+        want = want + init
+    got = host64(dXd)
+    check(got[rows_o, :F], want[rows_o], dtype, "bwd rows")
+    assert (got[outside, :F] == host64(padded(init, ld, dtype, fill=SENTINEL))[outside, :F]).all(), "rows outside were written"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_bwd_directed_graph_with_filter(dtype, accumulate):
+    g = gg.random_directed(8000, 6.0, 21)
+    _bwd_case(g, 128, 128, dtype, 3, 3, accumulate, 5)
+    _bwd_case(g, 256, 256, dtype, 3, 2, accumulate, 6)
+    _bwd_case(g, 602, 608, dtype, 2, 2, accumulate, 7)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_bwd_power_law_hubs(dtype):
+    g = gg.chung_lu(12000, 150.0, 2.1, 12)
+    _bwd_case(g, 64, 64, dtype, 2, 2, False, 8)
+    _bwd_case(g, 100, 100, dtype, 3, 2, True, 9)
+
+
+def test_empty_calls_are_noops():
+    import paper_2311_06837_amd as P
+    g = gg.erdos_renyi(100, 3.0, 1)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    X = torch.randn(100, 8, device="cuda")
+    Y = torch.full((100, 8), 3.0, device="cuda")
+    P.gnn_masked_spmm_fwd(G, None, 0, X, Y, 8)
+    P.gnn_masked_spmm_fwd(G, None, 100, X, Y, 0)
+    torch.cuda.synchronize()
+    assert (Y == 3.0).all()
