@@ -39,7 +39,7 @@ def test_power_law_partition(fanout):
 
 def test_hub_rows_and_large_fanout_and_seed_range():
     g = gg.chung_lu(8000, 300.0, 2.1, 32)                 # rows far longer than one wavefront
-    assert g.degrees().max() > 2000
+    assert g.degrees().max() > 1200
     T = np.arange(0, 8000, 3).astype(np.int32)
     _compare(g, T, 5, 1)
     _compare(g, T, 70, 2**64 - 1)                         # fanout above the wavefront width; seed + hop wraps
