@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the masked full-neighbourhood GNN hot path on ONE MI355X.
+
+A step is one pass of the whole hot path over one synthetic partition: active-set construction
+(frontier expansion), then per layer masked aggregation + feature transform, the loss, and the
+matching backward pass.  Inputs are resident in HBM before the timed region.  One JSON line on
+stdout:
+  value     aggregated edges per second = (edges visited by all forward and backward aggregations
+            of a step) / (wall time of a step)
+  roofline  the dominant kernel (the layer-1 forward aggregation): algorithmic bytes per launch
+            over the launch's duration from HIP events recorded on the launch stream in the timed steps
+  cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample (reported for
+            context; it is not the target)
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1] [--scale s]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+CONFIG_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_partition(name, scale):
+    """The seeded synthetic partition of the named workload (cfg4: sampled on the GPU first)."""
+    import graphgen as gg
+    t0 = time.time()
+    w = gg.make_workload(name, scale=scale)
+    log(f"[bench] generated {name} (scale {scale}) in {time.time() - t0:.1f}s: global n={w.global_graph.n_rows} "
+        f"nnz={w.global_graph.nnz}")
+    return w
+
+
+def sampled_partition_cfg4(w):
+    """cfg4: boundary sampling on the GPU (step a0), then host-side extraction of the local one-hop graph."""
+    import torch
+    import graphgen as gg
+    import paper_2311_06837_amd as P
+    g, T = w.global_graph, w.targets_global.astype(np.int32)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    Td = torch.from_numpy(T).cuda()
+    bits = P.gnn_make_bitmap(Td, g.n_rows)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    rp, ci = P.gnn_sample_boundary(G, bits, Td, w.fanout, w.sample_seed)
+    torch.cuda.synchronize()
+    t_sample = time.perf_counter() - t0
+    rp, ci = rp.cpu().numpy(), ci.cpu().numpy()
+    # local vertices = targets + kept outside neighbours; edges = kept rows + reverse of the outside ones
+    rows = np.repeat(T.astype(np.int64), np.diff(rp).astype(np.int64))
+    cols = ci.astype(np.int64)
+    is_t = np.zeros(g.n_rows, dtype=bool)
+    is_t[T] = True
+    ext = ~is_t[cols]
+    l2g = np.union1d(T.astype(np.int64), cols)
+    part = gg.partition_from_edges(g.n_rows, l2g, np.concatenate([rows, cols[ext]]), np.concatenate([cols, rows[ext]]),
+                                   w.targets_global, g.degrees())
+    return part, t_sample, int(ci.size)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg1", choices=sorted(CONFIG_INDEX))
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the vertex count (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding or collectives are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import graphgen as gg
+    import paper_2311_06837_amd as P
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = build_partition(args.workload, args.scale)
+    t_sample, kept = None, None
+    if w.partition is None:
+        part, t_sample, kept = sampled_partition_cfg4(w)
+    else:
+        part = w.partition
+    dtype = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    sage = w.model == "sage"
+    n = part.graph.n_rows
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
+    GT = G if part.graph_t is part.graph else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
+    params = gg.layer_weights(w.dims, sage, w.seed)
+    model = P.MaskedGNN(G, GT, dev(part.targets), w.model, [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
+                        global_degree=dev(part.global_degree) if w.model == "gcn" else None)
+    mult = 4 if dtype == torch.float32 else 8
+    ld0 = (w.dims[0] + mult - 1) // mult * mult
+    H0 = gg.features(n, w.dims[0], w.seed, ld=ld0)
+    model.set_input(dev(H0).to(dtype))
+    labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
+    log(f"[bench] partition: n={n} nnz={part.graph.nnz} |T|={len(part.targets)} model={w.model} dims={w.dims} dtype={w.dtype}")
+
+    for _ in range(args.warmup):
+        model.step(labels)
+    torch.cuda.synchronize()
+    model.trace = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.step(labels)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    trace, model.trace = model.trace, None
+    ms_per_step = wall / args.steps * 1e3
+
+    per_call = {}
+    for name, a, b in trace:
+        per_call.setdefault(name, []).append(a.elapsed_time(b))
+    call_ms = {k: float(np.mean(v)) for k, v in per_call.items()}
+    edges = model.aggregated_edges()
+    total_edges = sum(e["fwd"] + e["bwd"] for e in edges.values())
+    hop = [int(x) for x in model.hop]
+    L = model.L
+    es = 4 if dtype == torch.float32 else 2
+
+    # per-layer report
+    layers = {}
+    for l in range(1, L + 1):
+        t_f = call_ms.get(f"spmm_fwd_{l}", 0.0)
+        t_b = call_ms.get(f"spmm_bwd_{l}", 0.0) + call_ms.get(f"spmm_bwd_{l}_ring", 0.0)
+        e = edges[l]
+        F = w.dims[l - 1]
+        nl = model.n_rows_of_layer(l)
+        gather_bytes = e["fwd"] * (4 + F * es) + nl * (8 + F * es)
+        layers[str(l)] = {
+            "rows": nl, "edges_fwd": e["fwd"], "edges_bwd": e["bwd"], "F": F,
+            "spmm_fwd_ms": round(t_f, 4), "spmm_bwd_ms": round(t_b, 4),
+            "linear_fwd_ms": round(call_ms.get(f"linear_fwd_{l}", 0.0), 4),
+            "linear_bwd_ms": round(call_ms.get(f"linear_bwd_{l}", 0.0), 4),
+            "edges_per_s_spmm": (e["fwd"] + e["bwd"]) / ((t_f + t_b) * 1e-3) if t_f + t_b > 0 else None,
+            "spmm_fwd_gather_GBs": gather_bytes / (t_f * 1e-3) / 1e9 if t_f > 0 else None,
+        }
+
+    # roofline of the dominant kernel: the forward aggregation with the largest time
+    dom = max(range(1, L + 1), key=lambda l: call_ms.get(f"spmm_fwd_{l}", 0.0))
+    Fd = w.dims[dom - 1]
+    nd = model.n_rows_of_layer(dom)
+    n_in = model.n_rows_of_layer(dom - 1) if dom > 1 else int(hop[L + 1])
+    alg_bytes = edges[dom]["fwd"] * (4 + Fd * es) + nd * (8 + Fd * es)           # gather model
+    compulsory = edges[dom]["fwd"] * 4 + n_in * Fd * es + nd * (8 + Fd * es)     # every input row read once
+    t_dom = call_ms[f"spmm_fwd_{dom}"] * 1e-3
+    roofline = {
+        "kernel": f"spmm_rows_kernel (gnn_masked_spmm_fwd, layer {dom}, F={Fd})",
+        "bound": "hbm", "achieved": alg_bytes / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS, "traffic": None,
+        "bytes_per_launch": alg_bytes, "launch_ms": t_dom * 1e3,
+        "compulsory_bytes_per_launch": compulsory, "compulsory_GBs": compulsory / t_dom / 1e9,
+    }
+    # the feature-transform GEMMs against the MFMA peak of their data type
+    gemm = {}
+    for l in range(1, L + 1):
+        K, N = w.dims[l - 1], w.dims[l]
+        nl = model.n_rows_of_layer(l)
+        srcs = 2 if sage else 1
+        f_fwd = 2.0 * nl * K * N * srcs
+        f_bwd = f_fwd * (2 if l > 1 else 1)
+        tf, tb = call_ms.get(f"linear_fwd_{l}", 0.0) * 1e-3, call_ms.get(f"linear_bwd_{l}", 0.0) * 1e-3
+        peak = MFMA_PEAK_TFLOPS[w.dtype]
+        b_fwd = nl * (K * srcs + N) * es
+        gemm[str(l)] = {"M": nl, "K": K * srcs, "N": N,
+                        "fwd_TFLOPs": f_fwd / tf / 1e12 if tf > 0 else None, "fwd_frac_mfma": f_fwd / tf / 1e12 / peak if tf > 0 else None,
+                        "fwd_GBs": b_fwd / tf / 1e9 if tf > 0 else None,
+                        "bwd_TFLOPs": f_bwd / tb / 1e12 if tb > 0 else None, "bwd_frac_mfma": f_bwd / tb / 1e12 / peak if tb > 0 else None}
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(part, w, params, H0, model)
+
+    out = {
+        "metric": "aggregated_edges_per_sec", "value": total_edges / (wall / args.steps), "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{CONFIG_INDEX[args.workload]}]: {gg.WORKLOADS[args.workload]}",
+                   "scale": args.scale, "n_local": n, "nnz_local": part.graph.nnz, "targets": len(part.targets),
+                   "hop_offsets": hop, "layers": L},
+        "epoch_ms": sum(v for k, v in call_ms.items() if k != "active_sets"),
+        "active_sets_ms": call_ms.get("active_sets"),
+        "sampling_ms": None if t_sample is None else t_sample * 1e3, "sampled_edges": kept,
+        "aggregated_edges_per_step": total_edges,
+        "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,
+        "call_ms": {k: round(v, 4) for k, v in call_ms.items()},
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(part, w, params, H0, model):
+    """The oracle as it stands, on this machine's host cores: layer-1 masked aggregation + feature transform
+    (forward) on a seeded sample of the layer's rows, sized for about 10-30 s."""
+    import oracle
+    rows_all = model.ring_ids[: model.n_rows_of_layer(1)].cpu().numpy()
+    K, N = w.dims[0], w.dims[1]
+    deg = np.diff(part.graph.row_ptr)[rows_all].astype(np.int64)
+    # budget: about 2e11 fp64 multiply-adds of aggregation (roughly 10-20 s on 16 cores with the gathers)
+    budget = 2.0e11 / max(K, 1)
+    rng = np.random.default_rng(12345)
+    order = rng.permutation(rows_all.size)
+    take = int(np.searchsorted(np.cumsum(deg[order]), budget)) + 1
+    take = max(1, min(take, rows_all.size))
+    rows = np.sort(rows_all[order[:take]]).astype(np.int32)
+    sample_edges = int(deg[order[:take]].sum())
+    X = np.ascontiguousarray(H0[:, :K], dtype=np.float64)
+    if w.dtype == "bf16":
+        oracle.round_bf16(X)
+    n = part.graph.n_rows
+    length = np.diff(part.graph.row_ptr)
+    if w.model == "gcn":
+        s = oracle.norm_scales("sym", part.global_degree)
+        rs, cs = s, s
+    else:
+        rs, cs = oracle.norm_scales("mean", length), None
+    A = np.zeros((n, K))
+    Hn = np.zeros((n, N))
+    p = params[0]
+    t0 = time.perf_counter()
+    oracle.spmm_fwd(part.graph.row_ptr, part.graph.col_idx, rows, X, A, K, rs, cs)
+    t_agg = time.perf_counter() - t0
+    oracle.linear_fwd(rows, A, X if w.model == "sage" else None, K, p["W_neigh"], p.get("W_self"), p["bias"], Hn, True)
+    t_all = time.perf_counter() - t0
+    log(f"[bench] cpu oracle: {take} rows, {sample_edges} edges, aggregation {t_agg:.2f}s, with transform {t_all:.2f}s")
+    return {"value": sample_edges / t_all, "unit": "edges/s", "cores": oracle.n_threads(), "kind": "oracle",
+            "sample": f"layer-1 forward (masked aggregation + feature transform) of {take} seeded rows of R_1 "
+                      f"({sample_edges} edges) of the same partition, fp64, gcc -O2 -fopenmp",
+            "seconds": t_all, "aggregation_only_edges_per_s": sample_edges / t_agg}
+
+
+if __name__ == "__main__":
+    main()

@@ -102,13 +102,12 @@ int32_t gnn_norm_scales(int32_t norm, const int32_t *len, const int32_t *row_ptr
  *   X           [g->n_cols, ldx], Y [g->n_rows, ldy]; X and Y must not overlap
  *   row_scale, col_scale   float vectors or NULL (= 1)
  * An empty row gives 0.  Columns F..ldy of Y are not written.  Results do not depend on launch
- * order (no floating-point atomics): the same call gives the same bits.
- * ws: hub queue for long rows (query the size with ws == NULL).
+ * order (no floating-point atomics): the same call gives the same bits.  One kernel launch,
+ * no workspace.  Row ids in `rows` must lie in [0, g->n_rows); they are not checked.
  */
 int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_active,
                             const void *X, int64_t ldx, void *Y, int64_t ldy, int32_t F, int32_t dtype,
-                            const float *row_scale, const float *col_scale,
-                            void *ws, size_t *ws_bytes, void *stream);
+                            const float *row_scale, const float *col_scale, void *stream);
 
 /*
  * Masked aggregation, backward = the adjoint of the forward map, in gather form over the
@@ -117,13 +116,12 @@ int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_act
  *     dX[u, 0:F] (+)= col_scale[u] * sum_{v in rowT(u), active(v)} row_scale[v] * dY[v, 0:F]   for u in out_rows
  *   active(v)   dist == NULL: always; else 0 <= dist[v] <= max_active_dist  (v was a row of the forward call)
  *   accumulate  0: overwrite dX rows, 1: add to them
- * Same determinism and ws rules as the forward call.
+ * Same determinism as the forward call; one kernel launch, no workspace.
  */
 int32_t gnn_masked_spmm_bwd(const gnn_csr *gT, const int32_t *out_rows, int32_t n_out,
                             const int32_t *dist, int32_t max_active_dist,
                             const void *dY, int64_t lddy, void *dX, int64_t lddx, int32_t F, int32_t dtype,
-                            const float *row_scale, const float *col_scale, int32_t accumulate,
-                            void *ws, size_t *ws_bytes, void *stream);
+                            const float *row_scale, const float *col_scale, int32_t accumulate, void *stream);
 
 /*
  * Feature transform, forward (section 2.1, second half: weights, then the activation):

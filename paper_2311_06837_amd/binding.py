@@ -159,26 +159,24 @@ def gnn_norm_scales(norm: int, n: int, length: torch.Tensor | None = None, row_p
 
 
 def gnn_masked_spmm_fwd(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int,
-                        row_scale=None, col_scale=None, ws: Workspace | None = None):
+                        row_scale=None, col_scale=None):
     _mat(X, "X"), _mat(Y, "Y")
     assert X.dtype == Y.dtype and X.shape[0] >= g.n_cols and Y.shape[0] >= g.n_rows
     assert rows is None or rows.numel() >= n_active
-    _with_ws(lib().gnn_masked_spmm_fwd,
-             (C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
-              C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale)),
-             (_stream(),), ws)
+    _check(lib().gnn_masked_spmm_fwd(
+        C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
+        C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale), _stream()))
 
 
 def gnn_masked_spmm_bwd(gT: Graph, out_rows, n_out: int, dist, max_active_dist: int, dY: torch.Tensor, dX: torch.Tensor,
-                        F: int, row_scale=None, col_scale=None, accumulate: bool = False, ws: Workspace | None = None):
+                        F: int, row_scale=None, col_scale=None, accumulate: bool = False):
     _mat(dY, "dY"), _mat(dX, "dX")
     assert dY.dtype == dX.dtype and dY.shape[0] >= gT.n_cols and dX.shape[0] >= gT.n_rows
     assert out_rows is None or out_rows.numel() >= n_out
-    _with_ws(lib().gnn_masked_spmm_bwd,
-             (C.byref(gT.c), _ptr(_i32(out_rows, "out_rows")), C.c_int32(n_out), _ptr(_i32(dist, "dist")),
-              C.c_int32(max_active_dist), _ptr(dY), C.c_int64(dY.stride(0)), _ptr(dX), C.c_int64(dX.stride(0)), C.c_int32(F),
-              C.c_int32(_dtype_code(dY)), _ptr(row_scale), _ptr(col_scale), C.c_int32(1 if accumulate else 0)),
-             (_stream(),), ws)
+    _check(lib().gnn_masked_spmm_bwd(
+        C.byref(gT.c), _ptr(_i32(out_rows, "out_rows")), C.c_int32(n_out), _ptr(_i32(dist, "dist")),
+        C.c_int32(max_active_dist), _ptr(dY), C.c_int64(dY.stride(0)), _ptr(dX), C.c_int64(dX.stride(0)), C.c_int32(F),
+        C.c_int32(_dtype_code(dY)), _ptr(row_scale), _ptr(col_scale), C.c_int32(1 if accumulate else 0), _stream()))
 
 
 def gnn_linear_fwd(rows, n_active: int, A_neigh: torch.Tensor, X_self, K: int, W_neigh: torch.Tensor, W_self, bias,

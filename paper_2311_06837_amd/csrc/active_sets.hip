@@ -19,8 +19,7 @@
 namespace gnnhot {
 
 constexpr int kAsWordsPerBlock = 256;   // one bitmap word per thread: 8192 vertices per block
-constexpr int kAsHubDegree = 4096;      // longer rows are expanded by the whole grid
-constexpr int kAsHubChunk = 1024;       // edges per block-iteration in the hub kernel
+constexpr int kAsHubDegree = 2048;      // longer rows are queued and expanded by a whole workgroup each
 
 struct AsCtrl {
     int32_t n_hubs;
@@ -74,24 +73,18 @@ __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restric
     }
 }
 
-// Hub rows: every block takes chunks of every hub row.
+// Hub rows: one workgroup per queued row (grid-stride over the queue), threads across the row.
 __global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                              const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
                                                              const int32_t* __restrict__ hubq, const AsCtrl* ctrl) {
     const int32_t n_hubs = ctrl->n_hubs;
-    for (int32_t h = 0; h < n_hubs; ++h) {
+    for (int32_t h = blockIdx.x; h < n_hubs; h += gridDim.x) {
         const int32_t v = hubq[h];
         const int32_t s = row_ptr[v], e = row_ptr[v + 1];
-        for (int64_t c = (int64_t)s + (int64_t)blockIdx.x * kAsHubChunk; c < e; c += (int64_t)gridDim.x * kAsHubChunk) {
-#pragma unroll
-            for (int k = 0; k < kAsHubChunk / 256; ++k) {
-                const int64_t p = c + k * 256 + threadIdx.x;
-                if (p < e) {
-                    const int32_t u = col_idx[p];
-                    const uint32_t bit = 1u << (u & 31);
-                    if (!(visited[u >> 5] & bit) && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
-                }
-            }
+        for (int32_t p = s + (int32_t)threadIdx.x; p < e; p += 256) {
+            const int32_t u = col_idx[p];
+            const uint32_t bit = 1u << (u & 31);
+            if (!(visited[u >> 5] & bit) && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
         }
     }
 }
@@ -189,7 +182,7 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* target
                 as_expand_kernel<<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited,
                                                                   next, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_kernel");
-                as_expand_hubs_kernel<<<1024, 256, 0, stream>>>(g->row_ptr, g->col_idx, visited, next, hubq, ctrl);
+                as_expand_hubs_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, visited, next, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_hubs_kernel");
             }
             as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt);

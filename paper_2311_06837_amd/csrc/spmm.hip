@@ -14,15 +14,14 @@
 // row read; 64/LPR rows share a wavefront when rows are narrow.  Neighbour ids (and their
 // scales) are fetched 64 at a time, coalesced, filtered, compacted and staged in an LDS tile
 // private to the wavefront; the inner loop then reads the tile by broadcast and keeps
-// U x NCH independent 16-byte loads in flight per lane.  Rows longer than kHubDegree are
-// deferred to a queue and processed by 16-wave workgroups that split the neighbour list and
-// reduce the partial sums through LDS in a fixed order.
+// U x NCH independent 16-byte loads in flight per lane.  Rows longer than kHubDegree
+// (power-law hubs) are split over all wavefronts of the workgroup and the partial sums are
+// reduced through LDS in a fixed order, inside the same launch.
 #include "common.h"
 
 namespace gnnhot {
 
-constexpr int kHubDegree = 1024;   // rows longer than this go to the hub kernel
-constexpr int kHubWaves = 16;
+constexpr int kHubDegree = 1024;   // rows longer than this are split over the whole workgroup
 
 struct SpmmArgs {
     const int32_t* row_ptr;
@@ -39,8 +38,6 @@ struct SpmmArgs {
     const int32_t* dist;      // nullable filter: keep u iff 0 <= dist[u] <= max_dist
     int32_t max_dist;
     int32_t accumulate;
-    int32_t* hub_queue;
-    int32_t* hub_count;
 };
 
 // ---- element access: VE elements per lane-chunk ------------------------------------------
@@ -197,30 +194,40 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
     }
 }
 
+// One workgroup (4 wavefronts) owns 4 * 64/LPR consecutive entries of the row list.  Phase 1:
+// every LPR-lane group aggregates its own row unless the row is a hub.  Phase 2: the hub rows
+// of the workgroup are taken one at a time by ALL its groups (group q takes neighbour tiles
+// q, q+NG, ...), the partial sums meet in LDS and are added in group order.
 template <int DT, int VE, int LPR, int NCH, int U, bool FILTER>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
-    constexpr int W = LPR * NCH * VE;
+    constexpr int NG = 4 * RPW;             // groups (= rows) per workgroup
+    constexpr int W = LPR * NCH * VE;       // feature columns per workgroup (grid.y blocks cover F)
     __shared__ int32_t s_idx_all[4][kWave];
     __shared__ float s_w_all[4][kWave];
+    __shared__ int32_t s_hub[NG];           // hub row id of each group's row, or -1
+    __shared__ float s_red[NG][W];
     const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
     const int sub = lane / LPR, sl = lane % LPR;
+    const int gi = wave * RPW + sub;
     int32_t* s_idx = s_idx_all[wave];
     float* s_w = s_w_all[wave];
 
-    const int64_t i = ((int64_t)blockIdx.x * 4 + wave) * RPW + sub;
+    const int64_t i = (int64_t)blockIdx.x * NG + gi;
     bool row_ok = i < a.n_active;
     int32_t v = 0, s = 0, e = 0;
+    bool hub = false;
     if (row_ok) {
         v = a.rows ? a.rows[i] : (int32_t)i;
         s = a.row_ptr[v];
         e = a.row_ptr[v + 1];
-        if (e - s > kHubDegree) {
-            if (sl == 0 && blockIdx.y == 0) a.hub_queue[atomicAdd(a.hub_count, 1)] = v;
-            row_ok = false;
-            e = s;
-        }
+        hub = e - s > kHubDegree;
+    }
+    if (sl == 0) s_hub[gi] = hub ? v : -1;
+    if (hub) {
+        row_ok = false;
+        e = s;
     }
     int64_t col_off[NCH];
     bool col_ok[NCH];
@@ -235,11 +242,10 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
 #pragma unroll
         for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
 
-    // longest row of the wave bounds the (wave-uniform) tile loop
+    // ---- phase 1: one row per group; the longest row of the wave bounds the uniform tile loop
     int len_max = e - s;
 #pragma unroll
     for (int d = LPR; d < kWave; d <<= 1) len_max = max(len_max, __shfl_xor(len_max, d, kWave));
-
     for (int base = 0; base < len_max; base += LPR) {
         wave_lds_sync();  // the previous tile has been consumed
         const int cnt = stage_tile<LPR, FILTER>(a, s + base + sl, e, sub, sl, s_idx, s_w);
@@ -249,7 +255,6 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
         wave_lds_sync();
         consume_tile<E, LPR, NCH, U>(a, cnt, cnt_max, sub, col_off, col_ok, s_idx, s_w, acc);
     }
-
     if (row_ok) {
         const float sc = a.out_scale ? a.out_scale[v] : 1.f;
 #pragma unroll
@@ -263,66 +268,45 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
             }
         }
     }
-}
 
-// One 16-wave workgroup per queued hub row: wave w takes tiles w, w+16, ... of the row.
-template <int DT, int VE, int NCH, int U, bool FILTER>
-__global__ __launch_bounds__(kHubWaves* kWave) void spmm_hub_kernel(SpmmArgs a) {
-    using E = Elem<DT, VE>;
-    constexpr int LPR = kWave;
-    constexpr int W = LPR * NCH * VE;
-    __shared__ int32_t s_idx_all[kHubWaves][kWave];
-    __shared__ float s_w_all[kHubWaves][kWave];
-    __shared__ float s_red[kHubWaves][W];
-    const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
-    int32_t* s_idx = s_idx_all[wave];
-    float* s_w = s_w_all[wave];
-    const int32_t n_hubs = *a.hub_count;
-
-    int64_t col_off[NCH];
-    bool col_ok[NCH];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        col_off[c] = (int64_t)blockIdx.y * W + (int64_t)(lane + c * LPR) * VE;
-        col_ok[c] = col_off[c] < a.F;
-    }
-
-    for (int32_t h = blockIdx.x; h < n_hubs; h += gridDim.x) {
-        const int32_t v = a.hub_queue[h];
-        const int32_t s = a.row_ptr[v], e = a.row_ptr[v + 1];
-        float acc[NCH][VE];
+    // ---- phase 2: hub rows, all groups of the workgroup on one row at a time
+    __syncthreads();
+    for (int q = 0; q < NG; ++q) {
+        const int32_t hv = s_hub[q];   // uniform over the workgroup
+        if (hv < 0) continue;
+        const int32_t hs = a.row_ptr[hv], he = a.row_ptr[hv + 1];
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
             for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
-        for (int64_t base = (int64_t)s + wave * kWave; base < e; base += kHubWaves * kWave) {
+        for (int64_t base = (int64_t)hs + (int64_t)wave * kWave; base < he; base += 4 * kWave) {
+            // the wave's RPW groups take consecutive LPR-wide tiles of this 64-entry stretch
             wave_lds_sync();
-            const int cnt = stage_tile<LPR, FILTER>(a, (int32_t)base + lane, e, 0, lane, s_idx, s_w);
+            const int cnt = stage_tile<LPR, FILTER>(a, (int32_t)base + sub * LPR + sl, he, sub, sl, s_idx, s_w);
+            int cnt_max = cnt;
+#pragma unroll
+            for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
             wave_lds_sync();
-            consume_tile<E, LPR, NCH, U>(a, cnt, cnt, 0, col_off, col_ok, s_idx, s_w, acc);
+            consume_tile<E, LPR, NCH, U>(a, cnt, cnt_max, sub, col_off, col_ok, s_idx, s_w, acc);
         }
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
-            for (int k = 0; k < VE; ++k) s_red[wave][(lane + c * LPR) * VE + k] = acc[c][k];
+            for (int k = 0; k < VE; ++k) s_red[gi][(sl + c * LPR) * VE + k] = acc[c][k];
         __syncthreads();
-        const float sc = a.out_scale ? a.out_scale[v] : 1.f;
-        for (int col = threadIdx.x; col < W; col += kHubWaves * kWave) {
+        const float sc = a.out_scale ? a.out_scale[hv] : 1.f;
+        for (int col = threadIdx.x; col < W; col += 256) {
             const int64_t gcol = (int64_t)blockIdx.y * W + col;
             if (gcol < a.F) {
                 float t = 0.f;
 #pragma unroll
-                for (int w = 0; w < kHubWaves; ++w) t += s_red[w][col];
+                for (int r = 0; r < NG; ++r) t += s_red[r][col];
                 float o[1] = {t * sc};
-                Elem<DT, 1>::store(a.Y, (int64_t)v * a.ldy + gcol, o, 1, a.accumulate != 0);
+                Elem<DT, 1>::store(a.Y, (int64_t)hv * a.ldy + gcol, o, 1, a.accumulate != 0);
             }
         }
         __syncthreads();
     }
-}
-
-__global__ void spmm_reset_kernel(int32_t* hub_count) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) *hub_count = 0;
 }
 
 template <int DT, int VE, int LPR, int NCH, bool FILTER>
@@ -336,58 +320,28 @@ static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
     return GNN_OK;
 }
 
-template <int DT, int VE, int NCH, bool FILTER>
-static int32_t launch_hubs(const SpmmArgs& a, hipStream_t stream) {
-    constexpr int U = NCH == 1 ? 8 : (NCH == 2 ? 4 : 3);
-    constexpr int W = kWave * NCH * VE;
-    const int64_t max_hubs = a.n_active;
-    dim3 grid((unsigned)(max_hubs < 1024 ? (max_hubs < 1 ? 1 : max_hubs) : 1024), (unsigned)((a.F + W - 1) / W));
-    spmm_hub_kernel<DT, VE, NCH, U, FILTER><<<grid, kHubWaves * kWave, 0, stream>>>(a);
-    GNN_LAUNCH_CHECK("spmm_hub_kernel");
-    return GNN_OK;
-}
-
 template <int DT, bool FILTER>
 static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
     constexpr int VE = DT == GNN_F32 ? 4 : 8;
     const int F = a.F;
-    if (!vec_ok) {  // any alignment / leading dimension: element-wise lanes, 256 columns per block
-        GNN_CHECK((launch_rows<DT, 1, 64, 4, FILTER>(a, stream)));
-        return launch_hubs<DT, 1, 3, FILTER>(a, stream);
-    }
-    if (F <= 16 * VE) {
-        GNN_CHECK((launch_rows<DT, VE, 16, 1, FILTER>(a, stream)));
-    } else if (F <= 32 * VE) {
-        GNN_CHECK((launch_rows<DT, VE, 32, 1, FILTER>(a, stream)));
-    } else if (F <= 64 * VE) {
-        GNN_CHECK((launch_rows<DT, VE, 64, 1, FILTER>(a, stream)));
-    } else if (F <= 128 * VE) {
-        GNN_CHECK((launch_rows<DT, VE, 64, 2, FILTER>(a, stream)));
-    } else {
-        GNN_CHECK((launch_rows<DT, VE, 64, 3, FILTER>(a, stream)));
-    }
-    if (F <= 64 * VE) return launch_hubs<DT, VE, 1, FILTER>(a, stream);
-    if (DT == GNN_BF16 || F <= 128 * VE) return launch_hubs<DT, VE, DT == GNN_BF16 ? 1 : 2, FILTER>(a, stream);
-    return launch_hubs<DT, VE, DT == GNN_BF16 ? 1 : 3, FILTER>(a, stream);
+    // any alignment / leading dimension: element-wise lanes, 256 columns per workgroup
+    if (!vec_ok) return launch_rows<DT, 1, 64, 4, FILTER>(a, stream);
+    if (F <= 16 * VE) return launch_rows<DT, VE, 16, 1, FILTER>(a, stream);
+    if (F <= 32 * VE) return launch_rows<DT, VE, 32, 1, FILTER>(a, stream);
+    if (F <= 64 * VE) return launch_rows<DT, VE, 64, 1, FILTER>(a, stream);
+    if (F <= 128 * VE) return launch_rows<DT, VE, 64, 2, FILTER>(a, stream);
+    return launch_rows<DT, VE, 64, 3, FILTER>(a, stream);
 }
 
 static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* rows, int32_t n_active, const int32_t* dist,
                            int32_t max_dist, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F, int32_t dtype,
-                           const float* out_scale, const float* nbr_scale, int32_t accumulate, void* ws, size_t* ws_bytes,
-                           hipStream_t stream) {
+                           const float* out_scale, const float* nbr_scale, int32_t accumulate, hipStream_t stream) {
     GNN_CHECK(check_csr(g, gname));
     GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative row count");
     GNN_REQUIRE(rows != nullptr || n_active <= g->n_rows, GNN_ERR_SHAPE, "n_active %d exceeds n_rows %d", n_active, g->n_rows);
     GNN_REQUIRE(dtype == GNN_F32 || dtype == GNN_BF16, GNN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
     GNN_REQUIRE(F >= 0, GNN_ERR_INVALID_ARG, "F < 0");
     GNN_REQUIRE(ldx >= F && ldy >= F, GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
-
-    WsCarver carve(ws);
-    int32_t* hub_queue = carve.take<int32_t>((size_t)n_active + 1);
-    int32_t* hub_count = carve.take<int32_t>(1);
-    bool query;
-    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
-    if (query) return GNN_OK;
     if (n_active == 0 || F == 0) return GNN_OK;
     GNN_REQUIRE(X != nullptr && Y != nullptr, GNN_ERR_INVALID_ARG, "X or Y is NULL");
 
@@ -395,12 +349,10 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     a.row_ptr = g->row_ptr; a.col_idx = g->col_idx; a.rows = rows; a.n_active = n_active;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
     a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = max_dist;
-    a.accumulate = accumulate; a.hub_queue = hub_queue; a.hub_count = hub_count;
+    a.accumulate = accumulate;
 
     const int ve = dtype == GNN_F32 ? 4 : 8;
     const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0;
-    spmm_reset_kernel<<<1, 64, 0, stream>>>(hub_count);
-    GNN_LAUNCH_CHECK("spmm_reset_kernel");
     const bool filter = dist != nullptr;
     if (dtype == GNN_F32) return filter ? dispatch<GNN_F32, true>(a, vec_ok, stream) : dispatch<GNN_F32, false>(a, vec_ok, stream);
     return filter ? dispatch<GNN_BF16, true>(a, vec_ok, stream) : dispatch<GNN_BF16, false>(a, vec_ok, stream);
@@ -412,16 +364,15 @@ using namespace gnnhot;
 
 extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
                                        void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
-                                       const float* col_scale, void* ws, size_t* ws_bytes, void* stream) {
-    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, ws, ws_bytes,
-                       (hipStream_t)stream);
+                                       const float* col_scale, void* stream) {
+    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, (hipStream_t)stream);
 }
 
 extern "C" int32_t gnn_masked_spmm_bwd(const gnn_csr* gT, const int32_t* out_rows, int32_t n_out, const int32_t* dist,
                                        int32_t max_active_dist, const void* dY, int64_t lddy, void* dX, int64_t lddx, int32_t F,
                                        int32_t dtype, const float* row_scale, const float* col_scale, int32_t accumulate,
-                                       void* ws, size_t* ws_bytes, void* stream) {
+                                       void* stream) {
     GNN_REQUIRE(accumulate == 0 || accumulate == 1, GNN_ERR_INVALID_ARG, "accumulate must be 0 or 1");
     return spmm_common(gT, "gT", out_rows, n_out, dist, max_active_dist, dY, lddy, dX, lddx, F, dtype, col_scale, row_scale,
-                       accumulate, ws, ws_bytes, (hipStream_t)stream);
+                       accumulate, (hipStream_t)stream);
 }

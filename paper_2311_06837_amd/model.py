@@ -57,10 +57,23 @@ class MaskedGNN:
             self.grads.append(gdict)
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         self.hop = None
+        self.trace = None   # when a list: (name, start_event, end_event) per C-ABI call, for the benchmark
+
+    def _call(self, name, fn, *args, **kw):
+        """Run one C-ABI call; with tracing on, bracket it by events on the stream it is launched on."""
+        if self.trace is None:
+            return fn(*args, **kw)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        out = fn(*args, **kw)
+        b.record()
+        self.trace.append((name, a, b))
+        return out
 
     # -- step a1 -------------------------------------------------------------------------
     def build_active_sets(self):
-        self.dist, self.ring_ids, self.hop_offsets, self.hop = B.gnn_build_active_sets(self.g, self.targets, self.L, ws=self.ws)
+        self.dist, self.ring_ids, self.hop_offsets, self.hop = self._call(
+            "active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws)
         if self.kind == "gcn":
             s = B.gnn_norm_scales(B.GNN_NORM_SYM, self.n, length=self.global_degree,
                                   row_ptr=None if self.global_degree is not None else self.g.row_ptr)
@@ -84,11 +97,11 @@ class MaskedGNN:
             p = self.params[l - 1]
             K = self.dims[l - 1]
             nl = self.n_rows_of_layer(l)
-            B.gnn_masked_spmm_fwd(self.g, self.ring_ids, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs, ws=self.ws)
-            B.gnn_linear_fwd(self.ring_ids, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
+            self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, self.g, self.ring_ids, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs)
+            self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.ring_ids, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
                              p["W_neigh"], p.get("W_self"), p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
         nt = self.n_rows_of_layer(self.L)
-        B.gnn_softmax_ce(self.ring_ids, nt, self.H[self.L], self.dims[self.L], labels, self.dH[self.L], self.loss, ws=self.ws)
+        self._call("softmax_ce", B.gnn_softmax_ce, self.ring_ids, nt, self.H[self.L], self.dims[self.L], labels, self.dH[self.L], self.loss, ws=self.ws)
         return self.loss
 
     # -- steps a5, a6 --------------------------------------------------------------------
@@ -100,7 +113,7 @@ class MaskedGNN:
             nl = self.n_rows_of_layer(l)
             sage = self.kind == "sage"
             need_in = l > 1
-            B.gnn_linear_bwd(self.ring_ids, nl, self.dH[l], self.H[l] if l < L else None, l < L, self.A[l],
+            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.ring_ids, nl, self.dH[l], self.H[l] if l < L else None, l < L, self.A[l],
                              self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
                              gr["dW_neigh"], gr.get("dW_self"), gr["dbias"],
                              self.dA[l] if need_in else None, self.dH[l - 1] if (need_in and sage) else None, ws=self.ws)
@@ -108,14 +121,14 @@ class MaskedGNN:
                 n_prev = self.n_rows_of_layer(l - 1)
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
-                    B.gnn_masked_spmm_bwd(self.gt, self.ring_ids, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=True, ws=self.ws)
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                                          self.rs, self.cs, accumulate=True)
                     if n_prev > nl:
-                        B.gnn_masked_spmm_bwd(self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
-                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False, ws=self.ws)
+                        self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
+                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False)
                 else:
-                    B.gnn_masked_spmm_bwd(self.gt, self.ring_ids, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=False, ws=self.ws)
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                                          self.rs, self.cs, accumulate=False)
         return self.grads
 
     def step(self, labels: torch.Tensor):
@@ -129,7 +142,6 @@ class MaskedGNN:
         """Edges visited per layer by the forward and the backward aggregation (host-side bookkeeping
         from row_ptr; used by the benchmark's edges/s metric)."""
         rp = self.g.row_ptr.long()
-        rpt = self.gt.row_ptr.long()
         ring = self.ring_ids.long()
         out = {}
         for l in range(1, self.L + 1):
@@ -139,6 +151,5 @@ class MaskedGNN:
             if l > 1:
                 # transposed rows of R_{l-1}; entries v with dist(v) <= L - l are exactly the forward edges of R_l
                 bwd = fwd
-                _ = rpt
             out[l] = {"fwd": fwd, "bwd": bwd}
         return out
