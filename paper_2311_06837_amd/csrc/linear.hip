@@ -462,46 +462,94 @@ __global__ __launch_bounds__(256) void transpose_kernel(const void* __restrict__
     }
 }
 
-// dZ[i][0:N] = relu ? dH[row(i)] * [H[row(i)] > 0] : dH[row(i)], rows compacted; column sums of
-// each block of 256 rows go to part[block][0:N].  Threads: CX columns x 256/CX row lanes.
+// dZ[i][0:N] = relu ? dH[row(i)] * [H[row(i)] > 0] : dH[row(i)], rows compacted (pad columns of dZ
+// are written as zero); column sums of each block of kDzRows rows go to part[block][0:N].
+// Threads: cx 16-byte column vectors x 256/cx row lanes.
+constexpr int kDzRows = 1024;
+
 template <int DT>
 __global__ __launch_bounds__(256) void dz_kernel(const int32_t* __restrict__ rows, int32_t M, const void* __restrict__ dH,
-                                                 const void* __restrict__ H, int64_t ld_out, int32_t relu, int32_t N,
-                                                 void* __restrict__ dZ, int64_t ldz, float* __restrict__ part, int32_t cx) {
-    __shared__ float s_sum[256];
+                                                 const void* __restrict__ H, int64_t ld_out, int32_t io_vec, int32_t relu,
+                                                 int32_t N, void* __restrict__ dZ, int64_t ldz, float* __restrict__ part,
+                                                 int32_t cx) {
+    constexpr int EPV = DTy<DT>::EPV;
+    __shared__ float s_sum[256 * EPV];
     const int tx = threadIdx.x % cx, ty = threadIdx.x / cx, ny = 256 / cx;
-    const int64_t m_lo = (int64_t)blockIdx.x * 256;
-    const int64_t m_hi = m_lo + 256 < M ? m_lo + 256 : M;
-    for (int nb = 0; nb < N; nb += cx) {  // uniform trip count: the loop holds barriers
-        const int n = nb + tx;
-        float s = 0.f;
-        if (n < N) {
+    const int64_t m_lo = (int64_t)blockIdx.x * kDzRows;
+    const int64_t m_hi = m_lo + kDzRows < M ? m_lo + kDzRows : M;
+    const int n_vec = (N + EPV - 1) / EPV;
+    for (int vb = 0; vb < n_vec; vb += cx) {  // uniform trip count: the loop holds barriers
+        const int n0 = (vb + tx) * EPV;
+        float s[EPV];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) s[e] = 0.f;
+        if (n0 < N) {
             for (int64_t m = m_lo + ty; m < m_hi; m += ny) {
                 const int64_t r = rows ? (int64_t)rows[m] : m;
-                float gval = load_elem<DT>(dH, r * ld_out + n);
-                if (relu && !(load_elem<DT>(H, r * ld_out + n) > 0.f)) gval = 0.f;
-                store_elem<DT>(dZ, m * ldz + n, gval);
-                // the bias gradient sums what the weight-gradient GEMM will read (the stored value)
-                s += DT == GNN_F32 ? gval : bf16_to_f32(f32_to_bf16(gval));
+                const uint4 g4 = load16<DT>(dH, r * ld_out + n0, N - n0, io_vec != 0);
+                uint4 h4 = make_uint4(0u, 0u, 0u, 0u);
+                if (relu) h4 = load16<DT>(H, r * ld_out + n0, N - n0, io_vec != 0);
+                uint4 o;
+                if (DT == GNN_F32) {
+                    float gv[4] = {__uint_as_float(g4.x), __uint_as_float(g4.y), __uint_as_float(g4.z), __uint_as_float(g4.w)};
+                    const float hv[4] = {__uint_as_float(h4.x), __uint_as_float(h4.y), __uint_as_float(h4.z), __uint_as_float(h4.w)};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (relu && !(hv[e] > 0.f)) gv[e] = 0.f;
+                        s[e] += gv[e];
+                    }
+                    o = make_uint4(__float_as_uint(gv[0]), __float_as_uint(gv[1]), __float_as_uint(gv[2]), __float_as_uint(gv[3]));
+                } else {
+                    // bf16 values pass through unchanged (or become 0), so the sum is over the stored values
+                    const uint32_t gw[4] = {g4.x, g4.y, g4.z, g4.w};
+                    const uint32_t hw[4] = {h4.x, h4.y, h4.z, h4.w};
+                    uint32_t ow[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        uint32_t lo = gw[e] & 0xffffu, hi = gw[e] & 0xffff0000u;
+                        if (relu && !(bf16lo(hw[e]) > 0.f)) lo = 0u;
+                        if (relu && !(bf16hi(hw[e]) > 0.f)) hi = 0u;
+                        s[2 * e] += __uint_as_float(lo << 16);
+                        s[2 * e + 1] += __uint_as_float(hi);
+                        ow[e] = lo | hi;
+                    }
+                    o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+                }
+                if (DT == GNN_F32) *(uint4*)((float*)dZ + m * ldz + n0) = o;
+                else *(uint4*)((uint16_t*)dZ + m * ldz + n0) = o;
             }
         }
-        s_sum[threadIdx.x] = s;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) s_sum[(ty * cx + tx) * EPV + e] = s[e];
         __syncthreads();
-        if (ty == 0 && n < N) {
-            float t = 0.f;
-            for (int y = 0; y < ny; ++y) t += s_sum[y * cx + tx];
-            part[(int64_t)blockIdx.x * N + n] = t;
+        if (ty == 0 && n0 < N) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                float t = 0.f;
+                for (int y = 0; y < ny; ++y) t += s_sum[(y * cx + tx) * EPV + e];
+                if (n0 + e < N) part[(int64_t)blockIdx.x * N + n0 + e] = t;
+            }
         }
         __syncthreads();
     }
 }
 
+// out[n] = sum over the partial rows, in a fixed order: 8 row lanes x 32 columns per workgroup.
 __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ part, int32_t n_blocks, int32_t N,
                                                           float* __restrict__ out) {
-    for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < N; n += gridDim.x * blockDim.x) {
-        float s = 0.f;
-        for (int32_t b = 0; b < n_blocks; ++b) s += part[(int64_t)b * N + n];
-        out[n] = s;
+    __shared__ float s_sum[8][32];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int n = blockIdx.x * 32 + tx;
+    float s = 0.f;
+    if (n < N)
+        for (int32_t b = ty; b < n_blocks; b += 8) s += part[(int64_t)b * N + n];
+    s_sum[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && n < N) {
+        float t = 0.f;
+#pragma unroll
+        for (int y = 0; y < 8; ++y) t += s_sum[y][tx];
+        out[n] = t;
     }
 }
 
@@ -535,11 +583,13 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
                                float* dWn, float* dWs, float* dbias, void* dA, void* dXs, int64_t ld_din, void* dZ, int64_t ldz,
                                float* part, int32_t n_part, float* P, int32_t splits, int32_t rows_per_split, hipStream_t stream) {
     constexpr int ES = DTy<DT>::ES;
-    int cx = 8;
-    while (cx < N && cx < 256) cx <<= 1;
-    dz_kernel<DT><<<n_part, 256, 0, stream>>>(rows, M, dH, H, ld_out, relu, N, dZ, ldz, part, cx);
+    const int n_vec = (N + DTy<DT>::EPV - 1) / DTy<DT>::EPV;
+    int cx = 4;
+    while (cx < n_vec && cx < 256) cx <<= 1;
+    const int io_vec = vec_ok(dH, ld_out, ES) && (!relu || vec_ok(H, ld_out, ES));
+    dz_kernel<DT><<<n_part, 256, 0, stream>>>(rows, M, dH, H, ld_out, io_vec, relu, N, dZ, ldz, part, cx);
     GNN_LAUNCH_CHECK("dz_kernel");
-    reduce_rows_kernel<<<grid_for(N, 256, 64), 256, 0, stream>>>(part, n_part, N, dbias);
+    reduce_rows_kernel<<<(N + 31) / 32, 256, 0, stream>>>(part, n_part, N, dbias);
     GNN_LAUNCH_CHECK("reduce_rows_kernel");
 
     GemmTN t;
@@ -626,13 +676,16 @@ extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const v
     const int es = dtype == GNN_F32 ? 4 : 2;
     const int n_src = X_self ? 2 : 1;
     const int64_t ldz = (int64_t)align_up((size_t)N, 16 / es);
-    const int32_t n_part = n_active > 0 ? (n_active + 255) / 256 : 1;
-    // row splits of the weight-gradient reduction: enough workgroups to fill the chip, at most 64
+    const int32_t n_part = n_active > 0 ? (n_active + kDzRows - 1) / kDzRows : 1;
+    // row splits of the weight-gradient reduction: about four workgroups per CU, at least 256 rows each,
+    // at most 256 splits and 128 MB of partial tiles
     const int tiles = n_src * ((K + 127) / 128) * (N > 32 ? (N + 127) / 128 : 1);
-    int32_t splits = (2048 + tiles - 1) / tiles;
+    int32_t splits = (1024 + tiles - 1) / tiles;
     const int32_t max_splits = n_active > 0 ? (n_active + 255) / 256 : 1;
+    const int64_t split_bytes = (int64_t)n_src * K * N * 4;
     if (splits > max_splits) splits = max_splits;
-    if (splits > 64) splits = 64;
+    if (splits > 256) splits = 256;
+    if ((int64_t)splits * split_bytes > ((int64_t)128 << 20)) splits = (int32_t)(((int64_t)128 << 20) / split_bytes);
     if (splits < 1) splits = 1;
     int32_t rows_per_split = (int32_t)align_up((size_t)((n_active + splits - 1) / splits), 32);
     if (rows_per_split < 32) rows_per_split = 32;

@@ -11,10 +11,10 @@
 // Mapping to CDNA4.  The work is a gather of whole feature rows: HBM/L2 bound, one FMA per
 // loaded element, so no MFMA.  A group of LPR lanes (16, 32 or 64) owns one output row and
 // spans its feature columns with 16-byte loads, so every neighbour costs one fully coalesced
-// row read; 64/LPR rows share a wavefront when rows are narrow.  Neighbour ids (and their
-// scales) are fetched 64 at a time, coalesced, filtered, compacted and staged in an LDS tile
-// private to the wavefront; the inner loop then reads the tile by broadcast and keeps
-// U x NCH independent 16-byte loads in flight per lane.  Rows longer than kHubDegree
+// row read; 64/LPR rows share a wavefront when rows are narrow.  Neighbour ids are fetched one
+// tile ahead, coalesced, filtered, compacted and staged in an LDS tile private to the
+// wavefront; the inner loop then reads the tile by broadcast and keeps U x NCH independent
+// 16-byte loads in flight per lane.  Groups claim rows dynamically inside a workgroup's chunk.  Rows longer than kHubDegree
 // (power-law hubs) are split over all wavefronts of the workgroup and the partial sums are
 // reduced through LDS in a fixed order, inside the same launch.
 #include "common.h"
@@ -126,57 +126,42 @@ struct Elem<GNN_BF16, 1> {
     }
 };
 
-// Stage up to LPR neighbour ids of one row segment into the group's LDS slots, dropping the
-// filtered ones.  Returns how many were kept.  `p` is this lane's edge position.
+// Filter (backward: "was u an active row of the forward call"), compact and stage one tile of
+// neighbour ids (already in registers: `u`, valid where `in_row`) into the group's LDS slots.
+// Returns how many were kept.
 template <int LPR, bool FILTER>
-__device__ __forceinline__ int stage_tile(const SpmmArgs& a, int32_t p, int32_t row_end, int sub, int sl,
-                                          int32_t* s_idx, float* s_w) {
-    const bool in_row = p < row_end;
-    int32_t u = 0;
+__device__ __forceinline__ int commit_tile(const SpmmArgs& a, bool in_row, int32_t u, int n_in_row, int sub, int sl, int32_t* s_idx) {
+    if (!FILTER) {
+        if (in_row) s_idx[sub * LPR + sl] = u;
+        return n_in_row;
+    }
     bool keep = false;
     if (in_row) {
-        u = a.col_idx[p];
-        keep = true;
-        if (FILTER) {
-            const int32_t d = a.dist[u];
-            keep = d >= 0 && d <= a.max_dist;
-        }
+        const int32_t d = a.dist[u];
+        keep = d >= 0 && d <= a.max_dist;
     }
-    float w = 1.f;
-    if (keep && a.nbr_scale) w = a.nbr_scale[u];
-    int slot, cnt;
-    if (FILTER) {
-        const uint64_t group_mask = LPR == 64 ? ~0ull : (((1ull << (LPR & 63)) - 1ull) << (sub * LPR));
-        const uint64_t kept = __ballot(keep) & group_mask;
-        const uint64_t below = kept & ((1ull << (sub * LPR + sl)) - 1ull);
-        slot = __popcll(below);
-        cnt = __popcll(kept);
-    } else {
-        slot = sl;
-        const int32_t left = row_end - (p - sl);
-        cnt = left < 0 ? 0 : (left < LPR ? left : LPR);
-    }
-    if (keep) {
-        s_idx[sub * LPR + slot] = u;
-        s_w[sub * LPR + slot] = w;
-    }
-    return cnt;
+    const uint64_t group_mask = LPR == 64 ? ~0ull : (((1ull << (LPR & 63)) - 1ull) << (sub * LPR));
+    const uint64_t kept = __ballot(keep) & group_mask;
+    const uint64_t below = kept & ((1ull << (sub * LPR + sl)) - 1ull);
+    if (keep) s_idx[sub * LPR + __popcll(below)] = u;
+    return __popcll(kept);
 }
 
 // acc += sum over the staged tile.  `cnt` (this group's entries) may differ between the groups
-// of a wave; `cnt_max` is uniform over the wave.
+// of a wave; `cnt_max` is uniform over the wave.  Each round issues U x NCH independent row loads
+// (plus U broadcast loads of the neighbour scale) before the first multiply-add.
 template <typename E, int LPR, int NCH, int U>
 __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt_max, int sub, const int64_t (&col_off)[NCH],
-                                             const bool (&col_ok)[NCH], const int32_t* s_idx, const float* s_w,
-                                             float (&acc)[NCH][E::VE]) {
+                                             const bool (&col_ok)[NCH], const int32_t* s_idx, float (&acc)[NCH][E::VE]) {
     for (int k = 0; k < cnt_max; k += U) {
         typename E::Raw x[U][NCH];
         float w[U];
 #pragma unroll
         for (int j = 0; j < U; ++j) {
+            w[j] = 1.f;
             if (k + j < cnt) {
                 const int32_t u = s_idx[sub * LPR + k + j];
-                w[j] = s_w[sub * LPR + k + j];
+                if (a.nbr_scale) w[j] = a.nbr_scale[u];
                 const int64_t base = (int64_t)u * a.ldx;
 #pragma unroll
                 for (int c = 0; c < NCH; ++c)
@@ -194,41 +179,53 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
     }
 }
 
-// One workgroup (4 wavefronts) owns 4 * 64/LPR consecutive entries of the row list.  Phase 1:
-// every LPR-lane group aggregates its own row unless the row is a hub.  Phase 2: the hub rows
-// of the workgroup are taken one at a time by ALL its groups (group q takes neighbour tiles
-// q, q+NG, ...), the partial sums meet in LDS and are added in group order.
+constexpr int kRowsPerGroup = 8;
+
+// One workgroup (4 wavefronts = NG groups of LPR lanes) owns NG * kRowsPerGroup consecutive
+// entries of the row list.
+//   phase 0  the row descriptors (id, start, end, output scale) of the chunk go to LDS in one
+//            coalesced sweep;
+//   phase 1  every group streams through rows of the chunk, one LPR-wide tile of neighbours per
+//            step; a group that finishes a row claims the next unclaimed one from an LDS counter,
+//            so short and long rows mix without idle groups, and the ids of the NEXT tile are
+//            fetched while the current tile's rows are being gathered;
+//   phase 2  hub rows (longer than kHubDegree) are taken one at a time by ALL groups (group q takes
+//            tiles q, q+NG, ...); the partial sums meet in LDS and are added in group order.
+// Which group handles a row does not change the order of its additions: results are bit-reproducible.
 template <int DT, int VE, int LPR, int NCH, int U, bool FILTER>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
-    constexpr int NG = 4 * RPW;             // groups (= rows) per workgroup
-    constexpr int W = LPR * NCH * VE;       // feature columns per workgroup (grid.y blocks cover F)
+    constexpr int NG = 4 * RPW;
+    constexpr int RPB = NG * kRowsPerGroup;  // <= 128
+    constexpr int W = LPR * NCH * VE;        // feature columns per workgroup (grid.y blocks cover F)
     __shared__ int32_t s_idx_all[4][kWave];
-    __shared__ float s_w_all[4][kWave];
-    __shared__ int32_t s_hub[NG];           // hub row id of each group's row, or -1
+    __shared__ int32_t s_row_v[RPB], s_row_s[RPB], s_row_e[RPB], s_row_hub[RPB];
+    __shared__ float s_row_sc[RPB];
+    __shared__ int32_t s_next;
     __shared__ float s_red[NG][W];
     const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
     const int sub = lane / LPR, sl = lane % LPR;
     const int gi = wave * RPW + sub;
     int32_t* s_idx = s_idx_all[wave];
-    float* s_w = s_w_all[wave];
 
-    const int64_t i = (int64_t)blockIdx.x * NG + gi;
-    bool row_ok = i < a.n_active;
-    int32_t v = 0, s = 0, e = 0;
-    bool hub = false;
-    if (row_ok) {
-        v = a.rows ? a.rows[i] : (int32_t)i;
-        s = a.row_ptr[v];
-        e = a.row_ptr[v + 1];
-        hub = e - s > kHubDegree;
+    // ---- phase 0
+    const int64_t chunk0 = (int64_t)blockIdx.x * RPB;
+    const int n_chunk = (int)(((int64_t)a.n_active - chunk0) < RPB ? ((int64_t)a.n_active - chunk0) : RPB);
+    if ((int)threadIdx.x < n_chunk) {
+        const int r = threadIdx.x;
+        const int32_t v = a.rows ? a.rows[chunk0 + r] : (int32_t)(chunk0 + r);
+        const int32_t s = a.row_ptr[v], e = a.row_ptr[v + 1];
+        const bool hub = e - s > kHubDegree;
+        s_row_v[r] = v;
+        s_row_s[r] = s;
+        s_row_e[r] = hub ? s : e;
+        s_row_hub[r] = hub ? 1 : 0;
+        s_row_sc[r] = a.out_scale ? a.out_scale[v] : 1.f;
     }
-    if (sl == 0) s_hub[gi] = hub ? v : -1;
-    if (hub) {
-        row_ok = false;
-        e = s;
-    }
+    if (threadIdx.x == 0) s_next = NG;
+    __syncthreads();
+
     int64_t col_off[NCH];
     bool col_ok[NCH];
 #pragma unroll
@@ -242,59 +239,98 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
 #pragma unroll
         for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
 
-    // ---- phase 1: one row per group; the longest row of the wave bounds the uniform tile loop
-    int len_max = e - s;
-#pragma unroll
-    for (int d = LPR; d < kWave; d <<= 1) len_max = max(len_max, __shfl_xor(len_max, d, kWave));
-    for (int base = 0; base < len_max; base += LPR) {
+    // ---- phase 1
+    int jc = gi;
+    bool have = jc < n_chunk;
+    int32_t pc = 0, ec = 0;
+    if (have) {
+        pc = s_row_s[jc];
+        ec = s_row_e[jc];
+    }
+    int32_t u_c = (have && pc + sl < ec) ? a.col_idx[pc + sl] : 0;
+    while (__ballot(have) != 0ull) {  // uniform over the wave
+        // descriptor of the group's next tile: same row, or the next unclaimed row of the chunk
+        const bool row_done = have && pc + LPR >= ec;
+        int got = 0;
+        if (row_done && sl == 0) got = atomicAdd(&s_next, 1);
+        got = __shfl(got, sub * LPR, kWave);
+        int jn = jc;
+        int32_t pn = pc + LPR, en = ec;
+        bool have_n = have;
+        if (row_done) {
+            jn = got;
+            have_n = jn < n_chunk;
+            pn = have_n ? s_row_s[jn] : 0;
+            en = have_n ? s_row_e[jn] : 0;
+        }
+        const int32_t u_n = (have_n && pn + sl < en) ? a.col_idx[pn + sl] : 0;  // in flight during the gathers below
+
+        int left = have ? ec - pc : 0;
+        left = left < 0 ? 0 : (left < LPR ? left : LPR);
         wave_lds_sync();  // the previous tile has been consumed
-        const int cnt = stage_tile<LPR, FILTER>(a, s + base + sl, e, sub, sl, s_idx, s_w);
+        const int cnt = commit_tile<LPR, FILTER>(a, sl < left, u_c, left, sub, sl, s_idx);
         int cnt_max = cnt;
 #pragma unroll
         for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
         wave_lds_sync();
-        consume_tile<E, LPR, NCH, U>(a, cnt, cnt_max, sub, col_off, col_ok, s_idx, s_w, acc);
-    }
-    if (row_ok) {
-        const float sc = a.out_scale ? a.out_scale[v] : 1.f;
+        consume_tile<E, LPR, NCH, U>(a, cnt, cnt_max, sub, col_off, col_ok, s_idx, acc);
+
+        if (row_done) {
+            if (!s_row_hub[jc]) {
+                const int32_t v = s_row_v[jc];
+                const float sc = s_row_sc[jc];
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            if (col_ok[c]) {
-                float o[VE];
+                for (int c = 0; c < NCH; ++c) {
+                    if (col_ok[c]) {
+                        float o[VE];
 #pragma unroll
-                for (int k = 0; k < VE; ++k) o[k] = acc[c][k] * sc;
-                const int64_t left = (int64_t)a.F - col_off[c];
-                E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, left >= VE ? VE : (int)left, a.accumulate != 0);
+                        for (int k = 0; k < VE; ++k) o[k] = acc[c][k] * sc;
+                        const int64_t rest = (int64_t)a.F - col_off[c];
+                        E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, rest >= VE ? VE : (int)rest, a.accumulate != 0);
+                    }
+                }
             }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
         }
+        jc = jn;
+        pc = pn;
+        ec = en;
+        have = have_n;
+        u_c = u_n;
     }
 
-    // ---- phase 2: hub rows, all groups of the workgroup on one row at a time
+    // ---- phase 2
     __syncthreads();
-    for (int q = 0; q < NG; ++q) {
-        const int32_t hv = s_hub[q];   // uniform over the workgroup
-        if (hv < 0) continue;
-        const int32_t hs = a.row_ptr[hv], he = a.row_ptr[hv + 1];
+    for (int q = 0; q < n_chunk; ++q) {
+        if (!s_row_hub[q]) continue;  // uniform over the workgroup
+        const int32_t hv = s_row_v[q];
+        const int32_t hs = s_row_s[q], he = a.row_ptr[hv + 1];
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
             for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
         for (int64_t base = (int64_t)hs + (int64_t)wave * kWave; base < he; base += 4 * kWave) {
             // the wave's RPW groups take consecutive LPR-wide tiles of this 64-entry stretch
+            const int64_t p0 = base + sub * LPR;
+            int left = (int)((int64_t)he - p0 < 0 ? 0 : ((int64_t)he - p0 < LPR ? (int64_t)he - p0 : LPR));
+            const int32_t u = sl < left ? a.col_idx[p0 + sl] : 0;
             wave_lds_sync();
-            const int cnt = stage_tile<LPR, FILTER>(a, (int32_t)base + sub * LPR + sl, he, sub, sl, s_idx, s_w);
+            const int cnt = commit_tile<LPR, FILTER>(a, sl < left, u, left, sub, sl, s_idx);
             int cnt_max = cnt;
 #pragma unroll
             for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
             wave_lds_sync();
-            consume_tile<E, LPR, NCH, U>(a, cnt, cnt_max, sub, col_off, col_ok, s_idx, s_w, acc);
+            consume_tile<E, LPR, NCH, U>(a, cnt, cnt_max, sub, col_off, col_ok, s_idx, acc);
         }
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
             for (int k = 0; k < VE; ++k) s_red[gi][(sl + c * LPR) * VE + k] = acc[c][k];
         __syncthreads();
-        const float sc = a.out_scale ? a.out_scale[hv] : 1.f;
+        const float sc = s_row_sc[q];
         for (int col = threadIdx.x; col < W; col += 256) {
             const int64_t gcol = (int64_t)blockIdx.y * W + col;
             if (gcol < a.F) {
@@ -312,9 +348,9 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
 template <int DT, int VE, int LPR, int NCH, bool FILTER>
 static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
     constexpr int U = NCH == 1 ? 8 : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
-    constexpr int RPW = kWave / LPR;
+    constexpr int RPB = 4 * (kWave / LPR) * kRowsPerGroup;
     constexpr int W = LPR * NCH * VE;
-    dim3 grid((unsigned)(((int64_t)a.n_active + 4 * RPW - 1) / (4 * RPW)), (unsigned)((a.F + W - 1) / W));
+    dim3 grid((unsigned)(((int64_t)a.n_active + RPB - 1) / RPB), (unsigned)((a.F + W - 1) / W));
     spmm_rows_kernel<DT, VE, LPR, NCH, U, FILTER><<<grid, 256, 0, stream>>>(a);
     GNN_LAUNCH_CHECK("spmm_rows_kernel");
     return GNN_OK;
