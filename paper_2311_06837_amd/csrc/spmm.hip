@@ -21,6 +21,18 @@
 
 namespace gnnhot {
 
+// independent row loads in flight per lane-chunk when a lane owns one 16-byte chunk of the row
+#ifndef GNN_SPMM_U_NARROW
+#define GNN_SPMM_U_NARROW 16
+#endif
+#ifndef GNN_SPMM_U_WIDE
+#define GNN_SPMM_U_WIDE 8
+#endif
+
+#ifndef GNN_SPMM_RPG
+#define GNN_SPMM_RPG 4
+#endif
+constexpr int kRowsPerGroup = GNN_SPMM_RPG;   // largest chunk: this many rows of the list per group
 constexpr int kHubDegree = 1024;   // rows longer than this are split over the whole workgroup
 
 struct SpmmArgs {
@@ -38,6 +50,7 @@ struct SpmmArgs {
     const int32_t* dist;      // nullable filter: keep u iff 0 <= dist[u] <= max_dist
     int32_t max_dist;
     int32_t accumulate;
+    int32_t rows_per_group;   // 1..kRowsPerGroup: rows of the list per LPR-lane group in one workgroup
 };
 
 // ---- element access: VE elements per lane-chunk ------------------------------------------
@@ -179,7 +192,6 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
     }
 }
 
-constexpr int kRowsPerGroup = 8;
 
 // One workgroup (4 wavefronts = NG groups of LPR lanes) owns NG * kRowsPerGroup consecutive
 // entries of the row list.
@@ -197,7 +209,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
     constexpr int NG = 4 * RPW;
-    constexpr int RPB = NG * kRowsPerGroup;  // <= 128
+    constexpr int RPB = NG * kRowsPerGroup;  // largest chunk, <= 128
     constexpr int W = LPR * NCH * VE;        // feature columns per workgroup (grid.y blocks cover F)
     __shared__ int32_t s_idx_all[4][kWave];
     __shared__ int32_t s_row_v[RPB], s_row_s[RPB], s_row_e[RPB], s_row_hub[RPB];
@@ -210,8 +222,9 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
     int32_t* s_idx = s_idx_all[wave];
 
     // ---- phase 0
-    const int64_t chunk0 = (int64_t)blockIdx.x * RPB;
-    const int n_chunk = (int)(((int64_t)a.n_active - chunk0) < RPB ? ((int64_t)a.n_active - chunk0) : RPB);
+    const int rpb = NG * a.rows_per_group;
+    const int64_t chunk0 = (int64_t)blockIdx.x * rpb;
+    const int n_chunk = (int)(((int64_t)a.n_active - chunk0) < rpb ? ((int64_t)a.n_active - chunk0) : rpb);
     if ((int)threadIdx.x < n_chunk) {
         const int r = threadIdx.x;
         const int32_t v = a.rows ? a.rows[chunk0 + r] : (int32_t)(chunk0 + r);
@@ -347,11 +360,17 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
 
 template <int DT, int VE, int LPR, int NCH, bool FILTER>
 static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
-    constexpr int U = NCH == 1 ? 8 : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
-    constexpr int RPB = 4 * (kWave / LPR) * kRowsPerGroup;
+    constexpr int U = NCH == 1 ? (LPR < 64 ? GNN_SPMM_U_NARROW : GNN_SPMM_U_WIDE) : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
+    constexpr int NG = 4 * (kWave / LPR);
     constexpr int W = LPR * NCH * VE;
-    dim3 grid((unsigned)(((int64_t)a.n_active + RPB - 1) / RPB), (unsigned)((a.F + W - 1) / W));
-    spmm_rows_kernel<DT, VE, LPR, NCH, U, FILTER><<<grid, 256, 0, stream>>>(a);
+    // chunk size: as large as possible (better balance inside a workgroup) while the launch still
+    // has about 16 workgroups per CU
+    SpmmArgs b = a;
+    int rpg = (int)((int64_t)a.n_active / ((int64_t)NG * 4096));
+    b.rows_per_group = rpg < 1 ? 1 : (rpg > kRowsPerGroup ? kRowsPerGroup : rpg);
+    const int rpb = NG * b.rows_per_group;
+    dim3 grid((unsigned)(((int64_t)a.n_active + rpb - 1) / rpb), (unsigned)((a.F + W - 1) / W));
+    spmm_rows_kernel<DT, VE, LPR, NCH, U, FILTER><<<grid, 256, 0, stream>>>(b);
     GNN_LAUNCH_CHECK("spmm_rows_kernel");
     return GNN_OK;
 }
@@ -386,6 +405,7 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
     a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = max_dist;
     a.accumulate = accumulate;
+    a.rows_per_group = 1;
 
     const int ve = dtype == GNN_F32 ? 4 : 8;
     const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0;
