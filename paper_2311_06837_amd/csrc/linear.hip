@@ -26,6 +26,16 @@ namespace gnnhot {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+#ifndef GNN_NT_PF_BF16
+#define GNN_NT_PF_BF16 2
+#endif
+#ifndef GNN_NT_PF_F32
+#define GNN_NT_PF_F32 1
+#endif
+#ifndef GNN_NT_MINB
+#define GNN_NT_MINB 3
+#endif
+
 constexpr int kMaxDim = 4096;
 constexpr int kLdsRowWords = 36;  // 128 B of data + 16 B pad
 
@@ -60,6 +70,35 @@ __device__ __forceinline__ uint4 load16(const void* base, int64_t elem_off, int 
             if (e < n_valid) w[e >> 1] |= (uint32_t)p[e] << ((e & 1) * 16);
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Fast path used when every row of the operand is 16-byte aligned and its leading dimension is a
+// multiple of the vector.  load_raw issues ONE unconditional 16-byte load (an out-of-range chunk reads
+// element 0 of the matrix instead, which is always addressable), so a whole tile's loads form a
+// straight line that can stay in flight across the MFMAs; fix_chunk, applied when the data is moved
+// to LDS, zeroes what was out of range and, on a ragged last tile, the elements at or beyond
+// n_valid, so padding can never reach the MFMAs.
+template <int DT>
+__device__ __forceinline__ uint4 load_raw(const void* base, int64_t elem_off, bool in_range) {
+    const int64_t off = in_range ? elem_off : 0;
+    if (DT == GNN_F32) return *(const uint4*)((const float*)base + off);
+    return *(const uint4*)((const uint16_t*)base + off);
+}
+
+template <int DT>
+__device__ __forceinline__ uint4 fix_chunk(uint4 r, int n_valid) {
+    if (DT == GNN_F32) {
+        r.x = n_valid > 0 ? r.x : 0u;
+        r.y = n_valid > 1 ? r.y : 0u;
+        r.z = n_valid > 2 ? r.z : 0u;
+        r.w = n_valid > 3 ? r.w : 0u;
+    } else {
+        r.x &= (n_valid > 0 ? 0xffffu : 0u) | (n_valid > 1 ? 0xffff0000u : 0u);
+        r.y &= (n_valid > 2 ? 0xffffu : 0u) | (n_valid > 3 ? 0xffff0000u : 0u);
+        r.z &= (n_valid > 4 ? 0xffffu : 0u) | (n_valid > 5 ? 0xffff0000u : 0u);
+        r.w &= (n_valid > 6 ? 0xffffu : 0u) | (n_valid > 7 ? 0xffff0000u : 0u);
+    }
+    return r;
 }
 
 template <int DT>
@@ -97,18 +136,21 @@ struct GemmNT {
     int32_t relu;
     void* C;
     int64_t ldc;
+    int32_t c_vec;             // 16-byte stores to C rows allowed
 };
 
-template <int DT, int BN, int WM, int WN>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT a) {
+template <int DT, int BN, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(256, GNN_NT_MINB) void gemm_nt_kernel(GemmNT a) {
     constexpr int BM = 128;
     constexpr int EPV = DTy<DT>::EPV;
     constexpr int BK = 8 * EPV;  // elements per 128-byte tile row
     constexpr int WTM = BM / WM, WTN = BN / WN, MT = WTM / 32, NT = WTN / 32;
     constexpr int A_CH = BM / 32, B_CH = BN / 32;  // 16-byte chunks per thread
     static_assert(WM * WN == 4 && MT >= 1 && NT >= 1, "bad wave layout");
-    __shared__ uint32_t sA[BM * kLdsRowWords];
-    __shared__ uint32_t sB[BN * kLdsRowWords];
+    constexpr int PF = DT == GNN_BF16 ? GNN_NT_PF_BF16 : GNN_NT_PF_F32;  // register prefetch depth (bf16 steps are too short to hide a load)
+    __shared__ __attribute__((aligned(16))) uint32_t smem[(BM + BN) * kLdsRowWords];
+    uint32_t* sA = smem;
+    uint32_t* sB = smem + BM * kLdsRowWords;
 
     const int tiles_n = (a.N + BN - 1) / BN, tiles_m = (a.M + BM - 1) / BM;
     const int64_t total = (int64_t)tiles_m * tiles_n;
@@ -149,33 +191,42 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT a) {
 
     const int k_tiles = (a.K + BK - 1) / BK;
     const int n_steps = k_tiles * a.n_src;
-    uint4 ra[A_CH], rb[B_CH];
+    uint4 ra0[A_CH], rb0[B_CH], ra1[A_CH], rb1[B_CH];
 
-    auto fetch = [&](int step) {
+    auto fetch = [&](int step, uint4 (&ra)[A_CH], uint4 (&rb)[B_CH]) {
         const int src = step / k_tiles;
         const int ke = (step % k_tiles) * BK + ld_kc * EPV;
         const int nv = a.K - ke;
         const void* Ab = a.A[src];
         const void* Bb = a.Bt[src];
+        if (VEC) {
 #pragma unroll
-        for (int c = 0; c < A_CH; ++c) ra[c] = load16<DT>(Ab, a_off[c] + ke, a_ok[c] ? nv : 0, a.a_vec != 0);
+            for (int c = 0; c < A_CH; ++c) ra[c] = load_raw<DT>(Ab, a_off[c] + ke, a_ok[c] && nv > 0);
 #pragma unroll
-        for (int c = 0; c < B_CH; ++c) rb[c] = load16<DT>(Bb, b_off[c] + ke, b_ok[c] ? nv : 0, a.b_vec != 0);
+            for (int c = 0; c < B_CH; ++c) rb[c] = load_raw<DT>(Bb, b_off[c] + ke, b_ok[c] && nv > 0);
+        } else {
+#pragma unroll
+            for (int c = 0; c < A_CH; ++c) ra[c] = load16<DT>(Ab, a_off[c] + ke, a_ok[c] ? nv : 0, a.a_vec != 0);
+#pragma unroll
+            for (int c = 0; c < B_CH; ++c) rb[c] = load16<DT>(Bb, b_off[c] + ke, b_ok[c] ? nv : 0, a.b_vec != 0);
+        }
     };
-    auto stash = [&]() {
+    // edge: this workgroup's tile touches the end of M or N, or K is not a multiple of the tile row (uniform)
+    const bool edge = m0 + BM > a.M || n0 + BN > a.N || a.K % BK != 0;
+    auto stash = [&](int step, uint4 (&ra)[A_CH], uint4 (&rb)[B_CH]) {
+        if (VEC && edge) {
+            const int nv = a.K - ((step % k_tiles) * BK + ld_kc * EPV);
+#pragma unroll
+            for (int c = 0; c < A_CH; ++c) ra[c] = fix_chunk<DT>(ra[c], a_ok[c] ? nv : 0);
+#pragma unroll
+            for (int c = 0; c < B_CH; ++c) rb[c] = fix_chunk<DT>(rb[c], b_ok[c] ? nv : 0);
+        }
 #pragma unroll
         for (int c = 0; c < A_CH; ++c) *(uint4*)&sA[(ld_row + 32 * c) * kLdsRowWords + ld_kc * 4] = ra[c];
 #pragma unroll
         for (int c = 0; c < B_CH; ++c) *(uint4*)&sB[(ld_row + 32 * c) * kLdsRowWords + ld_kc * 4] = rb[c];
     };
-
-    if (n_steps > 0) {
-        fetch(0);
-        stash();
-    }
-    __syncthreads();
-    for (int step = 0; step < n_steps; ++step) {
-        if (step + 1 < n_steps) fetch(step + 1);
+    auto compute = [&]() {
         uint4 fa[MT][4], fb[NT][4];
 #pragma unroll
         for (int i = 0; i < MT; ++i)
@@ -209,11 +260,80 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT a) {
                                                                              __builtin_bit_cast(v8bf, fb[j][q]), acc[i][j], 0, 0, 0);
             }
         }
+    };
+
+    // Pipeline: LDS holds step s; register set (s+1)%2 holds step s+1 and, with PF == 2, the other set
+    // is refilled with step s+2 before the MFMAs of step s start, so two tile loads overlap.
+    if (n_steps > 0) fetch(0, ra0, rb0);
+    if (PF == 2 && n_steps > 1) fetch(1, ra1, rb1);
+    if (n_steps > 0) stash(0, ra0, rb0);
+    __syncthreads();
+    for (int step = 0; step < n_steps; step += 2) {
+        if (PF == 2) {
+            if (step + 2 < n_steps) fetch(step + 2, ra0, rb0);
+        } else {
+            if (step + 1 < n_steps) fetch(step + 1, ra1, rb1);
+        }
+        compute();
         __syncthreads();
         if (step + 1 < n_steps) {
-            stash();
+            stash(step + 1, ra1, rb1);
             __syncthreads();
+            if (PF == 2) {
+                if (step + 3 < n_steps) fetch(step + 3, ra1, rb1);
+            } else {
+                if (step + 2 < n_steps) fetch(step + 2, ra0, rb0);
+            }
+            compute();
+            __syncthreads();
+            if (step + 2 < n_steps) {
+                stash(step + 2, ra0, rb0);
+                __syncthreads();
+            }
         }
+    }
+
+    if (DT == GNN_BF16) {
+        // bf16 epilogue through LDS: the accumulator layout gives 2-byte column-strided stores, so the
+        // tile is first laid out row-major in LDS (bias + ReLU + rounding applied) and then written
+        // with 16-byte stores, one 256-byte row segment per 16 lanes.
+        constexpr int RS = BN / 2 + 4;  // words per LDS row of the C tile
+        static_assert(BM * RS <= (BM + BN) * kLdsRowWords, "C tile does not fit the operand buffers");
+        uint16_t* sC = (uint16_t*)smem;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = wm * WTM + i * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    const int col = wn * WTN + j * 32 + li;
+                    float v = acc[i][j][r];
+                    if (a.bias && n0 + col < a.N) v += a.bias[n0 + col];
+                    if (a.relu) v = v > 0.f ? v : 0.f;
+                    sC[row * (RS * 2) + col] = f32_to_bf16(v);
+                }
+            }
+        __syncthreads();
+        constexpr int CPR = BN / 8;  // 16-byte chunks per tile row
+#pragma unroll
+        for (int k = 0; k < BM * CPR / 256; ++k) {
+            const int idx = tid + 256 * k;
+            const int row = idx / CPR, ch = idx % CPR;
+            const int m = m0 + row, n = n0 + ch * 8;
+            if (m < a.M && n < a.N) {
+                const int64_t crow = a.c_rows ? (int64_t)a.c_rows[m] : (int64_t)m;
+                const uint4 v = *(const uint4*)&smem[row * RS + ch * 4];
+                uint16_t* dst = (uint16_t*)a.C + crow * a.ldc + n;
+                if (n + 8 <= a.N && a.c_vec) {
+                    *(uint4*)dst = v;
+                } else {
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                    for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                }
+            }
+        }
+        return;
     }
 
     // epilogue: acc[i][j][r] is C[row = (r/4)*8 + g*4 + r%4][col = li] of its 32x32 block
@@ -242,15 +362,19 @@ template <int DT>
 static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
     if (a.M <= 0 || a.N <= 0) return GNN_OK;
     const int64_t tiles_m = ((int64_t)a.M + 127) / 128;
+    const bool vec = a.a_vec && a.b_vec;  // both operands aligned: the branch-free loader
     if (a.N > 64) {
-        const int64_t total = tiles_m * ((a.N + 127) / 128);
-        gemm_nt_kernel<DT, 128, 2, 2><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(a);
+        const unsigned grid = (unsigned)((tiles_m * ((a.N + 127) / 128) + 7) / 8 * 8);
+        if (vec) gemm_nt_kernel<DT, 128, 2, 2, true><<<grid, 256, 0, stream>>>(a);
+        else gemm_nt_kernel<DT, 128, 2, 2, false><<<grid, 256, 0, stream>>>(a);
     } else if (a.N > 32) {
-        const int64_t total = tiles_m * ((a.N + 63) / 64);
-        gemm_nt_kernel<DT, 64, 2, 2><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(a);
+        const unsigned grid = (unsigned)((tiles_m * ((a.N + 63) / 64) + 7) / 8 * 8);
+        if (vec) gemm_nt_kernel<DT, 64, 2, 2, true><<<grid, 256, 0, stream>>>(a);
+        else gemm_nt_kernel<DT, 64, 2, 2, false><<<grid, 256, 0, stream>>>(a);
     } else {
-        const int64_t total = tiles_m;
-        gemm_nt_kernel<DT, 32, 4, 1><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(a);
+        const unsigned grid = (unsigned)((tiles_m + 7) / 8 * 8);
+        if (vec) gemm_nt_kernel<DT, 32, 4, 1, true><<<grid, 256, 0, stream>>>(a);
+        else gemm_nt_kernel<DT, 32, 4, 1, false><<<grid, 256, 0, stream>>>(a);
     }
     GNN_LAUNCH_CHECK("gemm_nt_kernel");
     return GNN_OK;
@@ -270,11 +394,12 @@ struct GemmTN {
     int32_t d_vec;
     int32_t M, N, K;
     int32_t rows_per_split; // multiple of 32
+    int32_t n_splits;
     float* P;               // [splits][n_src*K][N]
 };
 
-template <int DT, int BN>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN a) {
+template <int DT, int BN, bool VEC>
+__global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
     constexpr int BKO = 128, BMR = 32;
     constexpr int EPV = DTy<DT>::EPV;
     constexpr int WKO = BN == 128 ? 2 : 4, WNN = 4 / WKO;      // waves along k-out and n
@@ -289,10 +414,15 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN a) {
 
     const int ko_tiles = (a.K + BKO - 1) / BKO;
     const int n_tiles = (a.N + BN - 1) / BN;
-    const int t = blockIdx.x;
+    // all tiles of one row split are consecutive logical ids, hence on one XCD: its L2 serves the re-reads
+    const int tiles = a.n_src * ko_tiles * n_tiles;
+    const int64_t total = (int64_t)tiles * a.n_splits;
+    const int64_t logical = xcd_remap(blockIdx.x, total);
+    if (logical >= total) return;
+    const int t = (int)(logical % tiles);
+    const int split = (int)(logical / tiles);
     const int tn = t % n_tiles, tk = (t / n_tiles) % ko_tiles, src = t / (n_tiles * ko_tiles);
     const int ko0 = tk * BKO, n0 = tn * BN;
-    const int split = blockIdx.y;
     const int64_t m_begin = (int64_t)split * a.rows_per_split;
     const int64_t m_end = m_begin + a.rows_per_split < a.M ? m_begin + a.rows_per_split : a.M;
 
@@ -319,7 +449,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN a) {
             const int ke = ko0 + kc * EPV;
             int64_t r = 0;
             if (m < m_end) r = a.a_rows ? (int64_t)a.a_rows[m] : m;
-            ra[c] = load16<DT>(Ab, r * a.lda + ke, m < m_end ? a.K - ke : 0, a.a_vec != 0);
+            if (VEC) ra[c] = load_raw<DT>(Ab, r * a.lda + ke, m < m_end && ke < a.K);
+            else ra[c] = load16<DT>(Ab, r * a.lda + ke, m < m_end ? a.K - ke : 0, a.a_vec != 0);
         }
 #pragma unroll
         for (int c = 0; c < D_CH; ++c) {
@@ -328,25 +459,30 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN a) {
             const int64_t m = mb + row;
             const int ne = n0 + nc * EPV;
             const bool ok = row < BMR && m < m_end;
-            rd[c] = load16<DT>(a.D, (ok ? m : 0) * a.ldd + ne, ok ? a.N - ne : 0, a.d_vec != 0);
+            if (VEC) rd[c] = load_raw<DT>(a.D, m * a.ldd + ne, ok && ne < a.N);
+            else rd[c] = load16<DT>(a.D, (ok ? m : 0) * a.ldd + ne, ok ? a.N - ne : 0, a.d_vec != 0);
         }
     };
-    auto stash = [&]() {
+    // `mb` is the first row of the tile being moved to LDS; out-of-range parts are zeroed here (VEC path)
+    auto stash = [&](int64_t mb) {
+        const bool edge = mb + BMR > m_end || ko0 + BKO > a.K || n0 + BN > a.N;  // uniform
 #pragma unroll
         for (int c = 0; c < A_CH; ++c) {
             const int v = tid + 256 * c;
+            if (VEC && edge) ra[c] = fix_chunk<DT>(ra[c], mb + v / A_VPR < m_end ? a.K - (ko0 + (v % A_VPR) * EPV) : 0);
             *(uint4*)&sA[(v / A_VPR) * A_LDW + (v % A_VPR) * 4] = ra[c];
         }
 #pragma unroll
         for (int c = 0; c < D_CH; ++c) {
             const int v = tid + 256 * c;
+            if (VEC && edge) rd[c] = fix_chunk<DT>(rd[c], mb + v / D_VPR < m_end ? a.N - (n0 + (v % D_VPR) * EPV) : 0);
             if (v / D_VPR < BMR) *(uint4*)&sD[(v / D_VPR) * D_LDW + (v % D_VPR) * 4] = rd[c];
         }
     };
 
     if (m_begin < m_end) {
         fetch(m_begin);
-        stash();
+        stash(m_begin);
     }
     __syncthreads();
     for (int64_t mb = m_begin; mb < m_end; mb += BMR) {
@@ -407,7 +543,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN a) {
         }
         __syncthreads();
         if (mb + BMR < m_end) {
-            stash();
+            stash(mb + BMR);
             __syncthreads();
         }
     }
@@ -573,7 +709,7 @@ static int32_t linear_fwd_impl(const int32_t* rows, int32_t n_active, const void
     g.a_vec = vec_ok(A, ld_in, ES) && (!Xs || vec_ok(Xs, ld_in, ES));
     g.b_vec = 1;
     g.a_rows = rows; g.c_rows = rows; g.M = n_active; g.N = N; g.K = K;
-    g.bias = bias; g.relu = relu; g.C = H; g.ldc = ld_out;
+    g.bias = bias; g.relu = relu; g.C = H; g.ldc = ld_out; g.c_vec = vec_ok(H, ld_out, ES);
     return launch_gemm_nt<DT>(g, stream);
 }
 
@@ -596,14 +732,16 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
     t.A[0] = A; t.A[1] = Xs; t.n_src = Xs ? 2 : 1; t.lda = ld_in;
     t.a_vec = vec_ok(A, ld_in, ES) && (!Xs || vec_ok(Xs, ld_in, ES));
     t.a_rows = rows; t.D = dZ; t.ldd = ldz; t.d_vec = vec_ok(dZ, ldz, ES);
-    t.M = M; t.N = N; t.K = K; t.rows_per_split = rows_per_split; t.P = P;
+    t.M = M; t.N = N; t.K = K; t.rows_per_split = rows_per_split; t.n_splits = splits; t.P = P;
     const int ko_tiles = (K + 127) / 128;
     if (N > 32) {
-        dim3 grid((unsigned)(t.n_src * ko_tiles * ((N + 127) / 128)), (unsigned)splits);
-        gemm_tn_kernel<DT, 128><<<grid, 256, 0, stream>>>(t);
+        const int64_t total = (int64_t)t.n_src * ko_tiles * ((N + 127) / 128) * splits;
+        if (t.a_vec && t.d_vec) gemm_tn_kernel<DT, 128, true><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
+        else gemm_tn_kernel<DT, 128, false><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
     } else {
-        dim3 grid((unsigned)(t.n_src * ko_tiles), (unsigned)splits);
-        gemm_tn_kernel<DT, 32><<<grid, 256, 0, stream>>>(t);
+        const int64_t total = (int64_t)t.n_src * ko_tiles * splits;
+        if (t.a_vec && t.d_vec) gemm_tn_kernel<DT, 32, true><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
+        else gemm_tn_kernel<DT, 32, false><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
     }
     GNN_LAUNCH_CHECK("gemm_tn_kernel");
     reduce_partials_kernel<<<grid_for((int64_t)t.n_src * K * N, 256, 2048), 256, 0, stream>>>(P, splits, t.n_src, (int64_t)K * N, dWn,
@@ -619,7 +757,7 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
         g.A[0] = dZ; g.A[1] = nullptr; g.Bt[0] = W; g.Bt[1] = nullptr; g.n_src = 1;
         g.lda = ldz; g.ldb = N; g.a_vec = vec_ok(dZ, ldz, ES); g.b_vec = vec_ok(W, N, ES);
         g.a_rows = nullptr; g.c_rows = rows; g.M = M; g.N = K; g.K = N;
-        g.bias = nullptr; g.relu = 0; g.C = out; g.ldc = ld_din;
+        g.bias = nullptr; g.relu = 0; g.C = out; g.ldc = ld_din; g.c_vec = vec_ok(out, ld_din, ES);
         GNN_CHECK(launch_gemm_nt<DT>(g, stream));
     }
     return GNN_OK;
