@@ -33,6 +33,11 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 
 CONFIG_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}
 
+# HBM-side traffic of the dominant kernel per launch, from the two rocprofv3 --pmc runs summarised in
+# profiles/spmm_rows_fwd_cfg1.md (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, scaled by what the same
+# counters read for a 1 GiB copy: 2.0 and 1.0).  Only known for the default workload at full scale.
+MEASURED_TRAFFIC_BYTES = {"cfg1": 135105540 * 1024 * 2.0 + 554357 * 1024 * 1.0}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -171,7 +176,8 @@ def main():
     roofline = {
         "kernel": f"spmm_rows_kernel (gnn_masked_spmm_fwd, layer {dom}, F={Fd})",
         "bound": "hbm", "achieved": alg_bytes / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS, "traffic": None,
+        "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if (args.scale == 1.0 and dom == 1) else None,
         "bytes_per_launch": alg_bytes, "launch_ms": t_dom * 1e3,
         "compulsory_bytes_per_launch": compulsory, "compulsory_GBs": compulsory / t_dom / 1e9,
     }
