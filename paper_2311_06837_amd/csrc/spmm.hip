@@ -140,19 +140,16 @@ struct Elem<GNN_BF16, 1> {
 };
 
 // Filter (backward: "was u an active row of the forward call"), compact and stage one tile of
-// neighbour ids (already in registers: `u`, valid where `in_row`) into the group's LDS slots.
+// neighbour ids (already in registers: `u` and its `d` = dist[u], valid where `in_row`) into the group's LDS slots.
 // Returns how many were kept.
 template <int LPR, bool FILTER>
-__device__ __forceinline__ int commit_tile(const SpmmArgs& a, bool in_row, int32_t u, int n_in_row, int sub, int sl, int32_t* s_idx) {
+__device__ __forceinline__ int commit_tile(const SpmmArgs& a, bool in_row, int32_t u, int32_t d, int n_in_row, int sub, int sl,
+                                           int32_t* s_idx) {
     if (!FILTER) {
         if (in_row) s_idx[sub * LPR + sl] = u;
         return n_in_row;
     }
-    bool keep = false;
-    if (in_row) {
-        const int32_t d = a.dist[u];
-        keep = d >= 0 && d <= a.max_dist;
-    }
+    const bool keep = in_row && d >= 0 && d <= a.max_dist;  // d = dist[u], fetched by the caller
     const uint64_t group_mask = LPR == 64 ? ~0ull : (((1ull << (LPR & 63)) - 1ull) << (sub * LPR));
     const uint64_t kept = __ballot(keep) & group_mask;
     const uint64_t below = kept & ((1ull << (sub * LPR + sl)) - 1ull);
@@ -204,8 +201,10 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
 //   phase 2  hub rows (longer than kHubDegree) are taken one at a time by ALL groups (group q takes
 //            tiles q, q+NG, ...); the partial sums meet in LDS and are added in group order.
 // Which group handles a row does not change the order of its additions: results are bit-reproducible.
+// At least four workgroups per CU (six when a lane holds a single chunk and eight loads): the gather is
+// latency-bound, so resident wavefronts matter more than a few registers.
 template <int DT, int VE, int LPR, int NCH, int U, bool FILTER>
-__global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_kernel(SpmmArgs a) {
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
     constexpr int NG = 4 * RPW;
@@ -253,6 +252,22 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
         for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
 
     // ---- phase 1
+    // Tile descriptors (row slot j, position p, row end e, valid flag) of the current tile and of the
+    // two tiles after it: ids are fetched two tiles ahead and their dist values (backward filter) one
+    // tile ahead, so neither latency is paid between two gathers.
+    auto advance = [&](int j, int32_t p, int32_t e, bool hv, int& jo, int32_t& po, int32_t& eo, bool& ho) {
+        const bool done = hv && p + LPR >= e;
+        int got = 0;
+        if (done && sl == 0) got = atomicAdd(&s_next, 1);
+        got = __shfl(got, sub * LPR, kWave);  // executed by every lane of the wave
+        jo = j; po = p + LPR; eo = e; ho = hv;
+        if (done) {
+            jo = got;
+            ho = jo < n_chunk;
+            po = ho ? s_row_s[jo] : 0;
+            eo = ho ? s_row_e[jo] : 0;
+        }
+    };
     int jc = gi;
     bool have = jc < n_chunk;
     int32_t pc = 0, ec = 0;
@@ -260,28 +275,28 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
         pc = s_row_s[jc];
         ec = s_row_e[jc];
     }
+    int jn;
+    int32_t pn, en;
+    bool have_n;
+    advance(jc, pc, ec, have, jn, pn, en, have_n);
     int32_t u_c = (have && pc + sl < ec) ? a.col_idx[pc + sl] : 0;
+    int32_t u_n = (have_n && pn + sl < en) ? a.col_idx[pn + sl] : 0;
+    int32_t d_c = 0;
+    if (FILTER) d_c = (have && pc + sl < ec) ? a.dist[u_c] : -1;
     while (__ballot(have) != 0ull) {  // uniform over the wave
-        // descriptor of the group's next tile: same row, or the next unclaimed row of the chunk
         const bool row_done = have && pc + LPR >= ec;
-        int got = 0;
-        if (row_done && sl == 0) got = atomicAdd(&s_next, 1);
-        got = __shfl(got, sub * LPR, kWave);
-        int jn = jc;
-        int32_t pn = pc + LPR, en = ec;
-        bool have_n = have;
-        if (row_done) {
-            jn = got;
-            have_n = jn < n_chunk;
-            pn = have_n ? s_row_s[jn] : 0;
-            en = have_n ? s_row_e[jn] : 0;
-        }
-        const int32_t u_n = (have_n && pn + sl < en) ? a.col_idx[pn + sl] : 0;  // in flight during the gathers below
+        int jnn;
+        int32_t pnn, enn;
+        bool have_nn;
+        advance(jn, pn, en, have_n, jnn, pnn, enn, have_nn);
+        const int32_t u_nn = (have_nn && pnn + sl < enn) ? a.col_idx[pnn + sl] : 0;  // two tiles ahead
+        int32_t d_n = 0;
+        if (FILTER) d_n = (have_n && pn + sl < en) ? a.dist[u_n] : -1;               // one tile ahead
 
         int left = have ? ec - pc : 0;
         left = left < 0 ? 0 : (left < LPR ? left : LPR);
         wave_lds_sync();  // the previous tile has been consumed
-        const int cnt = commit_tile<LPR, FILTER>(a, sl < left, u_c, left, sub, sl, s_idx);
+        const int cnt = commit_tile<LPR, FILTER>(a, sl < left, u_c, d_c, left, sub, sl, s_idx);
         int cnt_max = cnt;
 #pragma unroll
         for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
@@ -308,11 +323,9 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
 #pragma unroll
                 for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
         }
-        jc = jn;
-        pc = pn;
-        ec = en;
-        have = have_n;
-        u_c = u_n;
+        jc = jn; pc = pn; ec = en; have = have_n;
+        jn = jnn; pn = pnn; en = enn; have_n = have_nn;
+        u_c = u_n; u_n = u_nn; d_c = d_n;
     }
 
     // ---- phase 2
@@ -330,8 +343,10 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(SpmmArgs a) {
             const int64_t p0 = base + sub * LPR;
             int left = (int)((int64_t)he - p0 < 0 ? 0 : ((int64_t)he - p0 < LPR ? (int64_t)he - p0 : LPR));
             const int32_t u = sl < left ? a.col_idx[p0 + sl] : 0;
+            int32_t d = 0;
+            if (FILTER) d = sl < left ? a.dist[u] : -1;
             wave_lds_sync();
-            const int cnt = commit_tile<LPR, FILTER>(a, sl < left, u, left, sub, sl, s_idx);
+            const int cnt = commit_tile<LPR, FILTER>(a, sl < left, u, d, left, sub, sl, s_idx);
             int cnt_max = cnt;
 #pragma unroll
             for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
