@@ -32,6 +32,9 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 #ifndef GNN_NT_PF_F32
 #define GNN_NT_PF_F32 1
 #endif
+#ifndef GNN_NT_MINB_NARROW
+#define GNN_NT_MINB_NARROW 3
+#endif
 #ifndef GNN_NT_MINB
 #define GNN_NT_MINB 3
 #endif
@@ -140,7 +143,7 @@ struct GemmNT {
 };
 
 template <int DT, int BN, int WM, int WN, bool VEC>
-__global__ __launch_bounds__(256, GNN_NT_MINB) void gemm_nt_kernel(GemmNT a) {
+__global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) void gemm_nt_kernel(GemmNT a) {
     constexpr int BM = 128;
     constexpr int EPV = DTy<DT>::EPV;
     constexpr int BK = 8 * EPV;  // elements per 128-byte tile row
