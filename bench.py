@@ -118,8 +118,7 @@ def main():
     params = gg.layer_weights(w.dims, sage, w.seed)
     model = P.MaskedGNN(G, GT, dev(part.targets), w.model, [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
                         global_degree=dev(part.global_degree) if w.model == "gcn" else None)
-    mult = 4 if dtype == torch.float32 else 8
-    ld0 = (w.dims[0] + mult - 1) // mult * mult
+    ld0 = P.row_stride(w.dims[0], dtype)
     H0 = gg.features(n, w.dims[0], w.seed, ld=ld0)
     model.set_input(dev(H0).to(dtype))
     labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))

@@ -54,14 +54,21 @@ typedef enum gnn_dtype { GNN_F32 = 0, GNN_BF16 = 1 } gnn_dtype;
 
 typedef enum gnn_norm { GNN_NORM_MEAN = 1, GNN_NORM_SYM = 2 } gnn_norm;
 
-/* One-hop graph in CSR form.  Columns of a row may be in any order; a repeated column counts
- * as often as it appears. */
+/* Properties of a graph that the caller guarantees (gnn_csr.flags). */
+typedef enum gnn_csr_flags {
+    GNN_CSR_SORTED_COLUMNS = 1 /* within every row the columns are in ascending order (repeats allowed) */
+} gnn_csr_flags;
+
+/* One-hop graph in CSR form.  Columns of a row may be in any order unless flags says otherwise;
+ * a repeated column counts as often as it appears. */
 typedef struct gnn_csr {
     int32_t n_rows;
     int32_t n_cols;
     int64_t nnz;
     const int32_t *row_ptr; /* device, [n_rows + 1], row_ptr[0] = 0, row_ptr[n_rows] = nnz */
     const int32_t *col_idx; /* device, [nnz], each in [0, n_cols) */
+    int32_t flags;          /* OR of gnn_csr_flags; 0 promises nothing.  A promise that does not hold
+                               gives wrong sums (never an out-of-bounds access). */
 } gnn_csr;
 
 int32_t gnn_version(void);
@@ -102,12 +109,22 @@ int32_t gnn_norm_scales(int32_t norm, const int32_t *len, const int32_t *row_ptr
  *   X           [g->n_cols, ldx], Y [g->n_rows, ldy]; X and Y must not overlap
  *   row_scale, col_scale   float vectors or NULL (= 1)
  * An empty row gives 0.  Columns F..ldy of Y are not written.  Results do not depend on launch
- * order (no floating-point atomics): the same call gives the same bits.  One kernel launch,
- * no workspace.  Row ids in `rows` must lie in [0, g->n_rows); they are not checked.
+ * order (no floating-point atomics): the same call gives the same bits.  Row ids in `rows` must
+ * lie in [0, g->n_rows); they are not checked.
+ *
+ * Workspace (optional).  ws_bytes == NULL: no workspace, one kernel launch that gathers whole rows.
+ * With a workspace the call may take the column-blocked route for dense graphs whose gathered
+ * matrix is far larger than a cache (average row length >= 64 per column block, columns sorted:
+ * GNN_CSR_SORTED_COLUMNS, 16-byte aligned operands): the neighbour-id range is cut into 8 blocks
+ * per pass, workgroup i works on block i mod 8 (the compute die it runs on), so each die's L2
+ * only ever holds one eighth of a 256-byte-wide feature slab; the per-block partial sums (float)
+ * go to ws and are added in block order.  The size query (ws == NULL) reports 0 when the route
+ * does not apply; the sums of the two routes differ by float rounding only.
  */
 int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_active,
                             const void *X, int64_t ldx, void *Y, int64_t ldy, int32_t F, int32_t dtype,
-                            const float *row_scale, const float *col_scale, void *stream);
+                            const float *row_scale, const float *col_scale,
+                            void *ws, size_t *ws_bytes, void *stream);
 
 /*
  * Masked aggregation, backward = the adjoint of the forward map, in gather form over the
@@ -116,12 +133,13 @@ int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_act
  *     dX[u, 0:F] (+)= col_scale[u] * sum_{v in rowT(u), active(v)} row_scale[v] * dY[v, 0:F]   for u in out_rows
  *   active(v)   dist == NULL: always; else 0 <= dist[v] <= max_active_dist  (v was a row of the forward call)
  *   accumulate  0: overwrite dX rows, 1: add to them
- * Same determinism as the forward call; one kernel launch, no workspace.
+ * Same determinism and the same optional workspace as the forward call.
  */
 int32_t gnn_masked_spmm_bwd(const gnn_csr *gT, const int32_t *out_rows, int32_t n_out,
                             const int32_t *dist, int32_t max_active_dist,
                             const void *dY, int64_t lddy, void *dX, int64_t lddx, int32_t F, int32_t dtype,
-                            const float *row_scale, const float *col_scale, int32_t accumulate, void *stream);
+                            const float *row_scale, const float *col_scale, int32_t accumulate,
+                            void *ws, size_t *ws_bytes, void *stream);
 
 /*
  * Feature transform, forward (section 2.1, second half: weights, then the activation):

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgnnhot.so")
 
 GNN_F32, GNN_BF16 = 0, 1
 GNN_NORM_MEAN, GNN_NORM_SYM = 1, 2
+GNN_CSR_SORTED_COLUMNS = 1
 STATUS = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_SHAPE", 3: "GNN_ERR_WORKSPACE",
           4: "GNN_ERR_UNSUPPORTED", 5: "GNN_ERR_HIP"}
 
@@ -33,7 +34,7 @@ class GnnError(RuntimeError):
 
 class gnn_csr(C.Structure):
     _fields_ = [("n_rows", C.c_int32), ("n_cols", C.c_int32), ("nnz", C.c_int64),
-                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p)]
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("flags", C.c_int32)]
 
 
 _lib = None
@@ -91,18 +92,27 @@ def _mat(t, name):
 class Graph:
     """Device CSR (int32) of a one-hop graph plus the host struct handed to the C ABI."""
 
-    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, n_cols: int | None = None):
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, n_cols: int | None = None, sorted_columns: bool = False):
+        """sorted_columns: the caller's promise that every row lists its columns in ascending order."""
         _i32(row_ptr, "row_ptr"), _i32(col_idx, "col_idx")
         assert row_ptr.is_cuda and col_idx.is_cuda
         self.row_ptr, self.col_idx = row_ptr, col_idx
         self.n_rows = row_ptr.numel() - 1
         self.n_cols = self.n_rows if n_cols is None else n_cols
         self.nnz = col_idx.numel()
-        self.c = gnn_csr(self.n_rows, self.n_cols, self.nnz, row_ptr.data_ptr(), col_idx.data_ptr() if self.nnz else None)
+        self.sorted_columns = bool(sorted_columns)
+        self.c = gnn_csr(self.n_rows, self.n_cols, self.nnz, row_ptr.data_ptr(), col_idx.data_ptr() if self.nnz else None,
+                         GNN_CSR_SORTED_COLUMNS if sorted_columns else 0)
 
     @staticmethod
     def from_numpy(row_ptr, col_idx, device="cuda", n_cols=None) -> "Graph":
-        return Graph(torch.from_numpy(row_ptr).to(device), torch.from_numpy(col_idx).to(device), n_cols)
+        """Copies host arrays to the device; whether the rows are column-sorted is checked here, on the host."""
+        import numpy as np
+        ok = True
+        if col_idx.size > 1:
+            falls = np.flatnonzero(col_idx[1:] < col_idx[:-1]) + 1          # positions lower than their predecessor
+            ok = bool(np.isin(falls, row_ptr[:-1]).all())                   # fine only where a new row starts
+        return Graph(torch.from_numpy(row_ptr).to(device), torch.from_numpy(col_idx).to(device), n_cols, sorted_columns=ok)
 
 
 class Workspace:
@@ -158,25 +168,33 @@ def gnn_norm_scales(norm: int, n: int, length: torch.Tensor | None = None, row_p
     return out
 
 
+def _with_optional_ws(fn, args_before, args_after, ws: Workspace | None):
+    """ws None: the call runs without a workspace (ws_bytes = NULL); else the usual size query + call."""
+    if ws is None:
+        _check(fn(*args_before, None, None, *args_after))
+    else:
+        _with_ws(fn, args_before, args_after, ws)
+
+
 def gnn_masked_spmm_fwd(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int,
-                        row_scale=None, col_scale=None):
+                        row_scale=None, col_scale=None, ws: Workspace | None = None):
     _mat(X, "X"), _mat(Y, "Y")
     assert X.dtype == Y.dtype and X.shape[0] >= g.n_cols and Y.shape[0] >= g.n_rows
     assert rows is None or rows.numel() >= n_active
-    _check(lib().gnn_masked_spmm_fwd(
+    _with_optional_ws(lib().gnn_masked_spmm_fwd, (
         C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
-        C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale), _stream()))
+        C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale)), (_stream(),), ws)
 
 
 def gnn_masked_spmm_bwd(gT: Graph, out_rows, n_out: int, dist, max_active_dist: int, dY: torch.Tensor, dX: torch.Tensor,
-                        F: int, row_scale=None, col_scale=None, accumulate: bool = False):
+                        F: int, row_scale=None, col_scale=None, accumulate: bool = False, ws: Workspace | None = None):
     _mat(dY, "dY"), _mat(dX, "dX")
     assert dY.dtype == dX.dtype and dY.shape[0] >= gT.n_cols and dX.shape[0] >= gT.n_rows
     assert out_rows is None or out_rows.numel() >= n_out
-    _check(lib().gnn_masked_spmm_bwd(
+    _with_optional_ws(lib().gnn_masked_spmm_bwd, (
         C.byref(gT.c), _ptr(_i32(out_rows, "out_rows")), C.c_int32(n_out), _ptr(_i32(dist, "dist")),
         C.c_int32(max_active_dist), _ptr(dY), C.c_int64(dY.stride(0)), _ptr(dX), C.c_int64(dX.stride(0)), C.c_int32(F),
-        C.c_int32(_dtype_code(dY)), _ptr(row_scale), _ptr(col_scale), C.c_int32(1 if accumulate else 0), _stream()))
+        C.c_int32(_dtype_code(dY)), _ptr(row_scale), _ptr(col_scale), C.c_int32(1 if accumulate else 0)), (_stream(),), ws)
 
 
 def gnn_linear_fwd(rows, n_active: int, A_neigh: torch.Tensor, X_self, K: int, W_neigh: torch.Tensor, W_self, bias,

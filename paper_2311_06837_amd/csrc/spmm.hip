@@ -18,6 +18,7 @@
 // (power-law hubs) are split over all wavefronts of the workgroup and the partial sums are
 // reduced through LDS in a fixed order, inside the same launch.
 #include "common.h"
+#include "scan.h"
 
 namespace gnnhot {
 
@@ -35,6 +36,25 @@ namespace gnnhot {
 constexpr int kRowsPerGroup = GNN_SPMM_RPG;   // largest chunk: this many rows of the list per group
 constexpr int kHubDegree = 1024;   // rows longer than this are split over the whole workgroup
 
+// Column-blocked route (dense graphs, gathered matrix far larger than an L2).  The neighbour-id
+// range [0, n_cols) is cut into 8 * passes equal blocks; in pass p workgroup i gathers, for its
+// rows, only the neighbours inside block 8p + (i mod 8).  Workgroups are dealt round-robin to the 8
+// compute dies, so every die's L2 sees one eighth of the matrix - and with the feature axis walked
+// in slabs of 256 bytes per row (grid.y, the slow grid axis) that eighth fits: the gathers then
+// run at L2 rather than at fabric speed (measured about 2x).  Each die leaves a plane of float
+// partial sums; a second kernel adds the planes in block order and applies the output scale.
+constexpr int kDies = 8;
+#ifndef GNN_SPMM_DIE_BYTES
+#define GNN_SPMM_DIE_BYTES (8ll << 20)      // target size of one die's share of one slab
+#endif
+#ifndef GNN_SPMM_BLOCKED_MIN_SLAB
+#define GNN_SPMM_BLOCKED_MIN_SLAB (16ll << 20)   // below this slab size the plain route is already cache-resident
+#endif
+#ifndef GNN_SPMM_BLOCKED_MIN_SEG
+#define GNN_SPMM_BLOCKED_MIN_SEG 8          // average neighbours of a row inside one column block
+#endif
+constexpr int kSlabBytes = 256;
+
 struct SpmmArgs {
     const int32_t* row_ptr;
     const int32_t* col_idx;
@@ -51,6 +71,11 @@ struct SpmmArgs {
     int32_t max_dist;
     int32_t accumulate;
     int32_t rows_per_group;   // 1..kRowsPerGroup: rows of the list per LPR-lane group in one workgroup
+    // column-blocked route only
+    const int32_t* seg;       // [n_active][n_blocks + 1] cut points of every listed row: block j = [seg[j], seg[j+1])
+    const int32_t* seg_end;   // nullable, [n_active][n_blocks]: block j ends here instead (filtered, compacted copy of the ids)
+    int32_t n_blocks;
+    int32_t block0;           // first column block of this pass
 };
 
 // ---- element access: VE elements per lane-chunk ------------------------------------------
@@ -138,6 +163,25 @@ struct Elem<GNN_BF16, 1> {
         if (n_valid >= 1) q[0] = f32_to_bf16(accumulate ? bf16_to_f32(q[0]) + v[0] : v[0]);
     }
 };
+
+// Float partial sums of the column-blocked route: VE consecutive floats at p[off] (16-byte aligned when VE >= 4).
+template <int VE>
+__device__ __forceinline__ void store_part(float* p, int64_t off, const float (&v)[VE], int n_valid, bool accumulate) {
+    if (VE >= 4 && n_valid == VE) {
+#pragma unroll
+        for (int q = 0; q < VE / 4; ++q) {
+            float4* dst = (float4*)(p + off) + q;
+            float4 o = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+            if (accumulate) {
+                const float4 old = *dst;
+                o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+            }
+            *dst = o;
+        }
+    } else {
+        for (int k = 0; k < n_valid; ++k) p[off + k] = accumulate ? p[off + k] + v[k] : v[k];
+    }
+}
 
 // Filter (backward: "was u an active row of the forward call"), compact and stage one tile of
 // neighbour ids (already in registers: `u` and its `d` = dist[u], valid where `in_row`) into the group's LDS slots.
@@ -373,6 +417,283 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
     }
 }
 
+
+// ---- edge-balanced kernel ------------------------------------------------------------------
+// One workgroup owns up to kStreamMaxRows consecutive entries of the row list, but the work is split
+// by EDGES, not by rows: the rows' neighbour lists are treated as one concatenated stream of E edges and
+// each of the NG lane groups takes a contiguous E/NG stretch of it, LPR edges (one tile) per step.  A row
+// that lies inside one stretch is summed and stored by that group; a row cut by a stretch boundary leaves
+// its pieces in LDS ("carry" slots: at most a head piece and a tail piece per group), and after a barrier the
+// pieces are added in stream order and stored.  So power-law rows cost no imbalance inside the workgroup,
+// tiles are always full, and the result is a fixed-order sum (bit-reproducible).
+//   PART (column-blocked route): the workgroup id carries (chunk, die) = (id / 8, id % 8); every row is cut to
+//   the die's column block through `seg`, and the unscaled float sums go to plane `die` of the partial buffer
+//   (a.Y, row index = position in the row list) instead of the output matrix.
+constexpr int kStreamMaxRows = 256;
+#ifndef GNN_SPMM_STREAM_U
+#define GNN_SPMM_STREAM_U 4        // row loads in flight per lane when a lane owns one 16-byte chunk of the row
+#endif
+#ifndef GNN_SPMM_STREAM_MINB
+#define GNN_SPMM_STREAM_MINB 6     // workgroups per CU the register budget is cut for (L2-resident gathers
+                                   // want resident wavefronts more than loads in flight: measured 4/6 > 8/4 > 16/3)
+#endif
+#ifndef GNN_SPMM_WG_EDGES
+#define GNN_SPMM_WG_EDGES 8192     // edges one workgroup aims for when the host picks its row count
+#endif
+
+template <int DT, int VE, int LPR, int NCH, int U, bool FILTER, bool PART>
+__global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm_stream_kernel(SpmmArgs a) {
+    using E = Elem<DT, VE>;
+    constexpr int RPW = kWave / LPR;
+    constexpr int NG = 4 * RPW;
+    constexpr int W = LPR * NCH * VE;  // feature columns per workgroup (grid.y blocks cover F)
+    __shared__ int32_t s_start[kStreamMaxRows], s_voff[kStreamMaxRows + 1], s_v[kStreamMaxRows];
+    __shared__ float s_sc[kStreamMaxRows];
+    __shared__ int2 s_tile_all[4][kWave];   // (neighbour id or -1 if filtered out, row slot) per staged edge
+    __shared__ float s_carry[NG * 2][W];
+    __shared__ int32_t s_ctag[NG * 2];
+    __shared__ int s_scan[4];
+    const int tid = (int)threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int sub = lane / LPR, sl = lane % LPR;
+    const int gi = wave * RPW + sub;
+    int2* s_tile = s_tile_all[wave];
+
+    // ---- phase 0: row descriptors and the exclusive prefix of the row lengths
+    const int rpw = a.rows_per_group;  // rows of the list per workgroup, <= kStreamMaxRows
+    const int die = PART ? (int)(blockIdx.x % kDies) : 0;
+    const int64_t chunk0 = (int64_t)(PART ? blockIdx.x / kDies : blockIdx.x) * rpw;
+    const int n_chunk = (int)(((int64_t)a.n_active - chunk0) < rpw ? ((int64_t)a.n_active - chunk0) : rpw);
+    float* const part = PART ? (float*)a.Y + (int64_t)die * a.n_active * a.ldy : nullptr;
+    int len = 0;
+    if (tid < n_chunk) {
+        int32_t v, s, e;
+        float sc = 1.f;
+        if (PART) {
+            v = (int32_t)(chunk0 + tid);
+            const int32_t* cut = a.seg + (int64_t)v * (a.n_blocks + 1) + a.block0 + die;
+            s = cut[0];
+            e = a.seg_end ? a.seg_end[(int64_t)v * a.n_blocks + a.block0 + die] : cut[1];
+        } else {
+            v = a.rows ? a.rows[chunk0 + tid] : (int32_t)(chunk0 + tid);
+            s = a.row_ptr[v];
+            e = a.row_ptr[v + 1];
+            if (a.out_scale) sc = a.out_scale[v];
+        }
+        s_v[tid] = v;
+        s_start[tid] = s;
+        s_sc[tid] = sc;
+        len = e - s;
+    }
+    if (tid < NG * 2) s_ctag[tid] = -1;
+    int n_edges;
+    const int voff = block_exclusive_scan<256>(len, s_scan, &n_edges);
+    if (tid < n_chunk) s_voff[tid] = voff;
+    if (tid == 0) s_voff[n_chunk] = n_edges;
+    __syncthreads();
+
+    int per = (n_edges + NG - 1) / NG;
+    per = (per + LPR - 1) / LPR * LPR;
+    const int64_t lo64 = (int64_t)gi * per < n_edges ? (int64_t)gi * per : n_edges;
+    const int lo = (int)lo64, hi = (int)(lo64 + per < n_edges ? lo64 + per : n_edges);  // this group's stretch of the stream
+
+    int64_t col_off[NCH];
+    bool col_ok[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        col_off[c] = (int64_t)blockIdx.y * W + (int64_t)(sl + c * LPR) * VE;
+        col_ok[c] = col_off[c] < a.F;
+    }
+    float acc[NCH][VE];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
+
+    // Row slot and position in col_idx of stream position t0 + sl (rows only move forward: r_hint).
+    int r_hint = 0;
+    auto locate = [&](int t0, int& r, int32_t& p) -> bool {
+        const int t = t0 + sl;
+        r = 0;
+        p = 0;
+        if (t >= hi) return false;
+        int x = r_hint, y = n_chunk;  // s_voff[x] <= t < s_voff[y]
+        while (y - x > 1) {
+            const int m = (x + y) >> 1;
+            if (s_voff[m] <= t) x = m;
+            else y = m;
+        }
+        r_hint = x;
+        r = x;
+        p = s_start[x] + (t - s_voff[x]);
+        return true;
+    };
+
+    int cur = -1;  // row slot the accumulators belong to (uniform over the group)
+    auto flush = [&]() {
+        const int b0 = s_voff[cur], b1 = s_voff[cur + 1];
+        if (b0 >= lo && b1 <= hi) {  // the whole row lies in this stretch
+            const int32_t v = s_v[cur];
+            const float sc = s_sc[cur];
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                if (col_ok[c]) {
+                    float o[VE];
+#pragma unroll
+                    for (int k = 0; k < VE; ++k) o[k] = acc[c][k] * sc;
+                    const int64_t rest = (int64_t)a.F - col_off[c];
+                    const int n_valid = rest >= VE ? VE : (int)rest;
+                    if (PART) store_part<VE>(part, (int64_t)v * a.ldy + col_off[c], o, n_valid, a.accumulate != 0);
+                    else E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, n_valid, a.accumulate != 0);
+                }
+            }
+        } else {  // a piece: head (the row began in an earlier stretch) or tail (it goes on in the next one)
+            const int slot = gi * 2 + (b0 < lo ? 0 : 1);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int k = 0; k < VE; ++k) s_carry[slot][(sl + c * LPR) * VE + k] = acc[c][k];
+            if (sl == 0) s_ctag[slot] = cur;
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
+    };
+
+    // ---- phase 1: ids are fetched two tiles ahead and their dist values (backward filter) one tile ahead
+    int t_c = lo;
+    int r_c, r_n;
+    int32_t p_c, p_n;
+    const bool v_c0 = locate(t_c, r_c, p_c);
+    bool v_n = locate(t_c + LPR, r_n, p_n);
+    bool v_c = v_c0;
+    int32_t u_c = v_c ? a.col_idx[p_c] : 0;
+    int32_t u_n = v_n ? a.col_idx[p_n] : 0;
+    int32_t d_c = 0;
+    if (FILTER) d_c = v_c ? a.dist[u_c] : -1;
+    while (__ballot(t_c < hi) != 0ull) {  // uniform over the wave
+        int r_nn;
+        int32_t p_nn;
+        const bool v_nn = locate(t_c + 2 * LPR, r_nn, p_nn);
+        const int32_t u_nn = v_nn ? a.col_idx[p_nn] : 0;
+        int32_t d_n = 0;
+        if (FILTER) d_n = v_n ? a.dist[u_n] : -1;
+
+        wave_lds_sync();  // the previous tile has been consumed
+        const bool keep = v_c && (!FILTER || (d_c >= 0 && d_c <= a.max_dist));
+        s_tile[lane] = make_int2(keep ? u_c : -1, r_c);
+        int cnt = hi - t_c;
+        cnt = cnt < 0 ? 0 : (cnt < LPR ? cnt : LPR);
+        int cnt_max = cnt;
+#pragma unroll
+        for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
+        wave_lds_sync();
+
+        for (int k0 = 0; k0 < cnt_max; k0 += U) {
+            typename E::Raw x[U][NCH];
+            float w[U];
+            int rr[U];
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                rr[j] = -1;
+                w[j] = 0.f;
+                if (k0 + j < cnt) {
+                    const int2 e = s_tile[sub * LPR + k0 + j];
+                    rr[j] = e.y;
+                    if (!FILTER || e.x >= 0) {
+                        w[j] = a.nbr_scale ? a.nbr_scale[e.x] : 1.f;
+                        const int64_t base = (int64_t)e.x * a.ldx;
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c)
+                            if (col_ok[c]) x[j][c] = E::load(a.X, base + col_off[c]);
+                    } else {
+                        rr[j] |= 1 << 30;  // filtered out: the row still has to appear, the edge adds nothing
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                if (rr[j] >= 0) {
+                    const int row = rr[j] & ~(1 << 30);
+                    if (row != cur) {
+                        if (cur >= 0) flush();
+                        cur = row;
+                    }
+                    if (!FILTER || !(rr[j] & (1 << 30))) {
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c)
+                            if (col_ok[c]) E::fma(acc[c], w[j], x[j][c]);
+                    }
+                }
+            }
+        }
+        t_c += LPR;
+        r_c = r_n; p_c = p_n; v_c = v_n; u_c = u_n; d_c = d_n;
+        r_n = r_nn; p_n = p_nn; v_n = v_nn; u_n = u_nn;
+    }
+    if (cur >= 0) flush();
+    __syncthreads();
+
+    // ---- phase 2: rows cut by stretch boundaries - their pieces sit in consecutive carry slots
+    for (int col = tid; col < W; col += 256) {
+        const int64_t gcol = (int64_t)blockIdx.y * W + col;
+        if (gcol >= a.F) continue;
+        int tag = -1;
+        float sum = 0.f;
+        for (int q = 0; q <= NG * 2; ++q) {
+            const int tq = q < NG * 2 ? s_ctag[q] : -2;
+            if (tq == -1) continue;
+            if (tq != tag) {
+                if (tag >= 0) {
+                    float o[1] = {sum * s_sc[tag]};
+                    const int64_t off = (int64_t)s_v[tag] * a.ldy + gcol;
+                    if (PART) store_part<1>(part, off, o, 1, a.accumulate != 0);
+                    else Elem<DT, 1>::store(a.Y, off, o, 1, a.accumulate != 0);
+                }
+                tag = tq;
+                sum = 0.f;
+            }
+            if (tq >= 0) sum += s_carry[q][col];
+        }
+    }
+    // ---- phase 3: rows without any edge are zero (they never show up in the stream)
+    if (!a.accumulate) {
+        for (int r = gi; r < n_chunk; r += NG) {
+            if (s_voff[r + 1] != s_voff[r]) continue;
+            const int32_t v = s_v[r];
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                if (col_ok[c]) {
+                    float o[VE];
+#pragma unroll
+                    for (int k = 0; k < VE; ++k) o[k] = 0.f;
+                    const int64_t rest = (int64_t)a.F - col_off[c];
+                    const int n_valid = rest >= VE ? VE : (int)rest;
+                    if (PART) store_part<VE>(part, (int64_t)v * a.ldy + col_off[c], o, n_valid, false);
+                    else E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, n_valid, false);
+                }
+            }
+        }
+    }
+}
+
+template <int DT, int VE, int LPR, int NCH, bool FILTER, bool PART>
+static int32_t launch_stream(const SpmmArgs& a, int64_t avg_row, hipStream_t stream) {
+    constexpr int U = NCH == 1 ? GNN_SPMM_STREAM_U : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
+    constexpr int W = LPR * NCH * VE;
+    // rows per workgroup: about GNN_SPMM_WG_EDGES edges, while the launch keeps a few thousand workgroups
+    SpmmArgs b = a;
+    int64_t rows = (int64_t)GNN_SPMM_WG_EDGES / (avg_row < 1 ? 1 : avg_row);
+    const int64_t cap = (int64_t)a.n_active * (PART ? kDies : 1) / 4096;
+    if (rows > cap) rows = cap;
+    b.rows_per_group = (int32_t)(rows < 16 ? 16 : (rows > kStreamMaxRows ? kStreamMaxRows : rows));
+    const int64_t n_chunks = ((int64_t)a.n_active + b.rows_per_group - 1) / b.rows_per_group;
+    dim3 grid((unsigned)(n_chunks * (PART ? kDies : 1)), (unsigned)((a.F + W - 1) / W));
+    spmm_stream_kernel<DT, VE, LPR, NCH, U, FILTER, PART><<<grid, 256, 0, stream>>>(b);
+    GNN_LAUNCH_CHECK("spmm_stream_kernel");
+    return GNN_OK;
+}
+
 template <int DT, int VE, int LPR, int NCH, bool FILTER>
 static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
     constexpr int U = NCH == 1 ? (LPR < 64 ? GNN_SPMM_U_NARROW : GNN_SPMM_U_WIDE) : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
@@ -387,6 +708,176 @@ static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)(((int64_t)a.n_active + rpb - 1) / rpb), (unsigned)((a.F + W - 1) / W));
     spmm_rows_kernel<DT, VE, LPR, NCH, U, FILTER><<<grid, 256, 0, stream>>>(b);
     GNN_LAUNCH_CHECK("spmm_rows_kernel");
+    return GNN_OK;
+}
+
+// Cut points of every listed row at the column-block boundaries j * block_size (rows sorted by column):
+// seg[r][j] = first position of row r whose column is >= j * block_size; seg[r][0] = start, seg[r][n_blocks] = end.
+__global__ __launch_bounds__(256) void spmm_seg_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                        const int32_t* __restrict__ rows, int32_t n_active, int32_t n_blocks,
+                                                        int32_t block_size, int32_t* __restrict__ seg) {
+    const int64_t total = (int64_t)n_active * (n_blocks + 1);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t r = (int32_t)(i / (n_blocks + 1)), j = (int32_t)(i % (n_blocks + 1));
+        const int32_t v = rows ? rows[r] : r;
+        int32_t lo = row_ptr[v], hi = row_ptr[v + 1];
+        if (j == n_blocks) {
+            lo = hi;
+        } else if (j > 0) {
+            const int64_t bound = (int64_t)j * block_size;
+            while (lo < hi) {  // lower bound
+                const int32_t mid = lo + ((hi - lo) >> 1);
+                if ((int64_t)col_idx[mid] < bound) lo = mid + 1;
+                else hi = mid;
+            }
+        }
+        seg[i] = lo;
+    }
+}
+
+// Backward filter of the column-blocked route, applied once instead of once per feature slab: every (row, block)
+// segment is copied to `ids` at its own position with the neighbours that fail the dist test squeezed out;
+// seg_end[r][j] = where the kept ones end.  One group of 16 lanes per segment.
+__global__ __launch_bounds__(256) void spmm_filter_kernel(const int32_t* __restrict__ col_idx, const int32_t* __restrict__ seg,
+                                                           const int32_t* __restrict__ dist, int32_t max_dist, int64_t n_segments,
+                                                           int32_t n_blocks, int32_t* __restrict__ ids, int32_t* __restrict__ seg_end) {
+    constexpr int LPG = 16;
+    const int lane = lane_id(), sub = lane / LPG, sl = lane % LPG;
+    const int64_t groups = (int64_t)gridDim.x * (blockDim.x / LPG);
+    for (int64_t sgm = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPG; sgm < n_segments; sgm += groups) {
+        const int64_t r = sgm / n_blocks;
+        const int32_t j = (int32_t)(sgm % n_blocks);
+        const int32_t lo = seg[r * (n_blocks + 1) + j], hi = seg[r * (n_blocks + 1) + j + 1];
+        int32_t out = lo;
+        for (int32_t p = lo; p < hi; p += LPG) {
+            const bool valid = p + sl < hi;
+            const int32_t u = valid ? col_idx[p + sl] : 0;
+            const int32_t d = valid ? dist[u] : -1;
+            const bool keep = valid && d >= 0 && d <= max_dist;
+            const uint64_t kept = (__ballot(keep) >> (sub * LPG)) & 0xffffull;
+            if (keep) ids[out + __popcll(kept & ((1ull << sl) - 1ull))] = u;
+            out += __popcll(kept);
+        }
+        if (sl == 0) seg_end[sgm] = out;
+    }
+}
+
+// Y[v, c] (+)= out_scale[v] * (plane 0 + plane 1 + ... + plane 7)[r, c], v = rows[r]: planes added in die order.
+// One thread per four columns; part rows are 16-byte aligned, and so are the rows of Y (vector route only).
+template <int DT>
+__global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __restrict__ part, int64_t ldp, const int32_t* __restrict__ rows,
+                                                              int32_t n_active, int32_t F, void* __restrict__ Y, int64_t ldy,
+                                                              const float* __restrict__ out_scale, int32_t accumulate) {
+    const int32_t f4 = (F + 3) / 4;
+    const int64_t total = (int64_t)n_active * f4;
+    const int64_t plane = (int64_t)n_active * ldp;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t r = (int32_t)(i / f4), c = (int32_t)(i % f4) * 4;
+        const int32_t v = rows ? rows[r] : r;
+        float4 t = *(const float4*)(part + (int64_t)r * ldp + c);
+#pragma unroll
+        for (int d = 1; d < kDies; ++d) {
+            const float4 q = *(const float4*)(part + d * plane + (int64_t)r * ldp + c);
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+        }
+        const float sc = out_scale ? out_scale[v] : 1.f;
+        float o[4] = {t.x * sc, t.y * sc, t.z * sc, t.w * sc};
+        const int n_valid = F - c >= 4 ? 4 : F - c;
+        const int64_t off = (int64_t)v * ldy + c;
+        if (DT == GNN_F32) {
+            float* y = (float*)Y + off;
+            if (n_valid == 4) {
+                float4 w = make_float4(o[0], o[1], o[2], o[3]);
+                if (accumulate) {
+                    const float4 old = *(const float4*)y;
+                    w.x += old.x; w.y += old.y; w.z += old.z; w.w += old.w;
+                }
+                *(float4*)y = w;
+            } else {
+                for (int k = 0; k < n_valid; ++k) y[k] = accumulate ? y[k] + o[k] : o[k];
+            }
+        } else {
+            uint16_t* y = (uint16_t*)Y + off;
+            if (n_valid == 4) {
+                if (accumulate) {
+                    const uint2 old = *(const uint2*)y;
+                    o[0] += bf16lo(old.x); o[1] += bf16hi(old.x); o[2] += bf16lo(old.y); o[3] += bf16hi(old.y);
+                }
+                *(uint2*)y = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
+            } else {
+                for (int k = 0; k < n_valid; ++k) y[k] = f32_to_bf16(accumulate ? bf16_to_f32(y[k]) + o[k] : o[k]);
+            }
+        }
+    }
+}
+
+// The column-blocked route's shape for one call; passes == 0: the route does not apply.
+struct BlockedPlan {
+    int passes = 0;
+    int n_blocks = 0;
+    int32_t block_size = 0;
+    int64_t ldp = 0;          // leading dimension of a partial plane, in floats
+    size_t seg_bytes = 0, part_bytes = 0;
+    size_t end_bytes = 0, ids_bytes = 0;   // backward filter only: segment ends and the compacted copy of the ids
+    int64_t avg_seg = 0;      // average neighbours of a row inside one column block
+};
+
+static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, bool vec_ok, bool filter) {
+    BlockedPlan p;
+    if (!vec_ok || !(g->flags & GNN_CSR_SORTED_COLUMNS) || g->n_rows <= 0 || n_active < 4096) return p;
+    const int64_t slab = (int64_t)g->n_cols * kSlabBytes;
+    if (slab < (int64_t)GNN_SPMM_BLOCKED_MIN_SLAB) return p;
+    const int passes = (int)((slab + kDies * (int64_t)GNN_SPMM_DIE_BYTES - 1) / (kDies * (int64_t)GNN_SPMM_DIE_BYTES));
+    const int n_blocks = kDies * passes;
+    if (g->nnz / g->n_rows < (int64_t)GNN_SPMM_BLOCKED_MIN_SEG * n_blocks) return p;
+    p.passes = passes;
+    p.n_blocks = n_blocks;
+    p.avg_seg = g->nnz / g->n_rows / n_blocks;
+    p.block_size = (int32_t)(((int64_t)g->n_cols + n_blocks - 1) / n_blocks);
+    p.ldp = ((int64_t)F + 7) / 8 * 8;
+    p.seg_bytes = (size_t)n_active * (n_blocks + 1) * sizeof(int32_t);
+    p.part_bytes = (size_t)kDies * n_active * p.ldp * sizeof(float);
+    if (filter) {
+        p.end_bytes = (size_t)n_active * n_blocks * sizeof(int32_t);
+        p.ids_bytes = (size_t)g->nnz * sizeof(int32_t);
+    }
+    return p;
+}
+
+template <int DT, bool FILTER>
+static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hipStream_t stream) {
+    constexpr int VE = DT == GNN_F32 ? 4 : 8;
+    WsCarver carve(ws);
+    int32_t* seg = carve.take<int32_t>(p.seg_bytes / sizeof(int32_t));
+    float* part = carve.take<float>(p.part_bytes / sizeof(float));
+    int32_t* seg_end = FILTER ? carve.take<int32_t>(p.end_bytes / sizeof(int32_t)) : nullptr;
+    int32_t* ids = FILTER ? carve.take<int32_t>(p.ids_bytes / sizeof(int32_t)) : nullptr;
+    spmm_seg_kernel<<<grid_for((int64_t)a.n_active * (p.n_blocks + 1), 256, 1 << 16), 256, 0, stream>>>(
+        a.row_ptr, a.col_idx, a.rows, a.n_active, p.n_blocks, p.block_size, seg);
+    GNN_LAUNCH_CHECK("spmm_seg_kernel");
+    SpmmArgs b = a;
+    if (FILTER) {
+        const int64_t n_segments = (int64_t)a.n_active * p.n_blocks;
+        spmm_filter_kernel<<<grid_for(n_segments * 16, 256, 1 << 18), 256, 0, stream>>>(a.col_idx, seg, a.dist, a.max_dist, n_segments,
+                                                                                     p.n_blocks, ids, seg_end);
+        GNN_LAUNCH_CHECK("spmm_filter_kernel");
+        b.col_idx = ids;
+        b.seg_end = seg_end;
+        b.dist = nullptr;
+    }
+    b.seg = seg;
+    b.n_blocks = p.n_blocks;
+    b.Y = part;
+    b.ldy = p.ldp;
+    b.out_scale = nullptr;
+    for (int pass = 0; pass < p.passes; ++pass) {
+        b.block0 = pass * kDies;
+        b.accumulate = pass > 0;
+        GNN_CHECK((launch_stream<DT, VE, 16, 1, false, true>(b, p.avg_seg, stream)));
+    }
+    spmm_sum_parts_kernel<DT><<<grid_for((int64_t)a.n_active * ((a.F + 3) / 4), 256, 1 << 16), 256, 0, stream>>>(
+        part, p.ldp, a.rows, a.n_active, a.F, a.Y, a.ldy, a.out_scale, a.accumulate);
+    GNN_LAUNCH_CHECK("spmm_sum_parts_kernel");
     return GNN_OK;
 }
 
@@ -405,13 +896,33 @@ static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
 
 static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* rows, int32_t n_active, const int32_t* dist,
                            int32_t max_dist, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F, int32_t dtype,
-                           const float* out_scale, const float* nbr_scale, int32_t accumulate, hipStream_t stream) {
+                           const float* out_scale, const float* nbr_scale, int32_t accumulate, void* ws, size_t* ws_bytes,
+                           hipStream_t stream) {
     GNN_CHECK(check_csr(g, gname));
     GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative row count");
     GNN_REQUIRE(rows != nullptr || n_active <= g->n_rows, GNN_ERR_SHAPE, "n_active %d exceeds n_rows %d", n_active, g->n_rows);
     GNN_REQUIRE(dtype == GNN_F32 || dtype == GNN_BF16, GNN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
     GNN_REQUIRE(F >= 0, GNN_ERR_INVALID_ARG, "F < 0");
     GNN_REQUIRE(ldx >= F && ldy >= F, GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
+    const int ve = dtype == GNN_F32 ? 4 : 8;
+    const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0;
+    const bool filter = dist != nullptr;
+    BlockedPlan plan;
+    if (ws_bytes != nullptr) {
+        if (n_active > 0 && F > 0) plan = plan_blocked(g, n_active, F, vec_ok, filter);
+        WsCarver measure(nullptr);
+        if (plan.passes > 0) {
+            measure.take<char>(plan.seg_bytes);
+            measure.take<char>(plan.part_bytes);
+            if (filter) {
+                measure.take<char>(plan.end_bytes);
+                measure.take<char>(plan.ids_bytes);
+            }
+        }
+        bool query_only = false;
+        GNN_CHECK(ws_protocol(ws, ws_bytes, measure.used, &query_only));
+        if (query_only) return GNN_OK;
+    }
     if (n_active == 0 || F == 0) return GNN_OK;
     GNN_REQUIRE(X != nullptr && Y != nullptr, GNN_ERR_INVALID_ARG, "X or Y is NULL");
 
@@ -421,10 +932,12 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = max_dist;
     a.accumulate = accumulate;
     a.rows_per_group = 1;
+    a.seg = nullptr; a.seg_end = nullptr; a.n_blocks = 0; a.block0 = 0;
 
-    const int ve = dtype == GNN_F32 ? 4 : 8;
-    const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0;
-    const bool filter = dist != nullptr;
+    if (plan.passes > 0) {
+        if (dtype == GNN_F32) return filter ? run_blocked<GNN_F32, true>(a, plan, ws, stream) : run_blocked<GNN_F32, false>(a, plan, ws, stream);
+        return filter ? run_blocked<GNN_BF16, true>(a, plan, ws, stream) : run_blocked<GNN_BF16, false>(a, plan, ws, stream);
+    }
     if (dtype == GNN_F32) return filter ? dispatch<GNN_F32, true>(a, vec_ok, stream) : dispatch<GNN_F32, false>(a, vec_ok, stream);
     return filter ? dispatch<GNN_BF16, true>(a, vec_ok, stream) : dispatch<GNN_BF16, false>(a, vec_ok, stream);
 }
@@ -435,15 +948,16 @@ using namespace gnnhot;
 
 extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
                                        void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
-                                       const float* col_scale, void* stream) {
-    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, (hipStream_t)stream);
+                                       const float* col_scale, void* ws, size_t* ws_bytes, void* stream) {
+    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, ws, ws_bytes,
+                       (hipStream_t)stream);
 }
 
 extern "C" int32_t gnn_masked_spmm_bwd(const gnn_csr* gT, const int32_t* out_rows, int32_t n_out, const int32_t* dist,
                                        int32_t max_active_dist, const void* dY, int64_t lddy, void* dX, int64_t lddx, int32_t F,
                                        int32_t dtype, const float* row_scale, const float* col_scale, int32_t accumulate,
-                                       void* stream) {
+                                       void* ws, size_t* ws_bytes, void* stream) {
     GNN_REQUIRE(accumulate == 0 || accumulate == 1, GNN_ERR_INVALID_ARG, "accumulate must be 0 or 1");
     return spmm_common(gT, "gT", out_rows, n_out, dist, max_active_dist, dY, lddy, dX, lddx, F, dtype, col_scale, row_scale,
-                       accumulate, (hipStream_t)stream);
+                       accumulate, ws, ws_bytes, (hipStream_t)stream);
 }

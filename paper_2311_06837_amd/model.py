@@ -12,8 +12,11 @@ import torch
 from . import binding as B
 
 
-def _pad(n: int, mult: int) -> int:
-    return (n + mult - 1) // mult * mult
+def row_stride(width: int, dtype) -> int:
+    """Leading dimension (in elements) the model gives a matrix of `width` columns: rows start on 128-byte
+    boundaries, so a 256-byte stretch of a gathered row touches two cache lines, never three."""
+    mult = 128 // torch.empty(0, dtype=dtype).element_size()
+    return (width + mult - 1) // mult * mult
 
 
 class MaskedGNN:
@@ -41,8 +44,7 @@ class MaskedGNN:
                 q["W_self"] = p["W_self"].to(dtype).contiguous()
             self.params.append(q)
         self.global_degree = global_degree
-        mult = 4 if dtype == torch.float32 else 8
-        self.ld = [_pad(d, mult) for d in self.dims]   # 16-byte aligned rows
+        self.ld = [row_stride(d, dtype) for d in self.dims]
         dev = targets.device
         # activations A_l, H_l and their gradients; rows outside the active sets are never touched
         self.A = [None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
@@ -87,8 +89,8 @@ class MaskedGNN:
         return int(self.hop[self.L - l + 1])
 
     def set_input(self, H0: torch.Tensor):
-        """H0: [n, >= F0] of the model dtype, row-major; used in place."""
-        assert H0.dtype == self.dtype and H0.shape[0] == self.n and H0.shape[1] >= self.dims[0]
+        """H0: [n, row_stride(F0, dtype)] of the model dtype, row-major; used in place."""
+        assert H0.dtype == self.dtype and H0.shape[0] == self.n and H0.stride(0) == self.ld[0]
         self.H[0] = H0
 
     # -- steps a2, a3, a4 ----------------------------------------------------------------
@@ -97,7 +99,7 @@ class MaskedGNN:
             p = self.params[l - 1]
             K = self.dims[l - 1]
             nl = self.n_rows_of_layer(l)
-            self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, self.g, self.ring_ids, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs)
+            self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, self.g, self.ring_ids, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs, ws=self.ws)
             self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.ring_ids, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
                              p["W_neigh"], p.get("W_self"), p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
         nt = self.n_rows_of_layer(self.L)
@@ -122,13 +124,13 @@ class MaskedGNN:
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=True)
+                                          self.rs, self.cs, accumulate=True, ws=self.ws)
                     if n_prev > nl:
                         self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
-                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False)
+                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False, ws=self.ws)
                 else:
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=False)
+                                          self.rs, self.cs, accumulate=False, ws=self.ws)
         return self.grads
 
     def step(self, labels: torch.Tensor):

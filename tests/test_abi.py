@@ -51,13 +51,17 @@ def test_bad_arguments_return_codes_without_touching_the_gpu(lib):
     assert lib.gnn_build_active_sets(C.byref(g2), None, 0, 2, None, None, None, None, None, C.byref(need), None) == 2
     # nnz >= 2^31
     g3 = _csr(nnz=2**31, ci=1)
-    assert lib.gnn_masked_spmm_fwd(C.byref(g3), None, 0, None, C.c_int64(4), None, C.c_int64(4), 4, 0, None, None, None) == 4
+    assert lib.gnn_masked_spmm_fwd(C.byref(g3), None, 0, None, C.c_int64(4), None, C.c_int64(4), 4, 0, None, None, None, None, None) == 4
     # ws_bytes NULL
     assert lib.gnn_build_active_sets(C.byref(g), None, 0, 2, None, None, None, None, None, None, None) == 1
     # leading dimension smaller than F
-    assert lib.gnn_masked_spmm_fwd(C.byref(g), None, 0, None, C.c_int64(3), None, C.c_int64(4), 4, 0, None, None, None) == 2
+    assert lib.gnn_masked_spmm_fwd(C.byref(g), None, 0, None, C.c_int64(3), None, C.c_int64(4), 4, 0, None, None, None, None, None) == 2
     # unknown dtype
-    assert lib.gnn_masked_spmm_fwd(C.byref(g), None, 0, None, C.c_int64(4), None, C.c_int64(4), 4, 7, None, None, None) == 4
+    assert lib.gnn_masked_spmm_fwd(C.byref(g), None, 0, None, C.c_int64(4), None, C.c_int64(4), 4, 7, None, None, None, None, None) == 4
+    # aggregation: the size query of a call the column-blocked route does not apply to reports 0 bytes
+    need.value = 77
+    assert lib.gnn_masked_spmm_fwd(C.byref(g), None, 4, None, C.c_int64(4), None, C.c_int64(4), 4, 0, None, None, None,
+                                   C.byref(need), None) == 0 and need.value == 0
     # linear: K = 0, X_self without W_self, dims over the limit
     assert lib.gnn_linear_fwd(None, 0, None, None, C.c_int64(4), 0, None, None, None, 4, None, C.c_int64(4), 0, 0, None,
                               C.byref(need), None) == 1

@@ -15,8 +15,15 @@ from gpu_util import as_stored, check, dev, host64, padded
 pytestmark = pytest.mark.gpu
 
 
-def _pad(n, m):
-    return (n + m - 1) // m * m
+_WS = {}
+
+
+def _ws():
+    """One workspace for the aggregation calls, as the model passes one (on cfg1 that selects the column-blocked route)."""
+    import paper_2311_06837_amd as P
+    if "ws" not in _WS:
+        _WS["ws"] = P.Workspace()
+    return _WS["ws"]
 
 
 @pytest.fixture(scope="module")
@@ -63,8 +70,7 @@ def _spmm_fwd_sampled(w, G, rows_all, F, dtype, kind, seed, n_sample=1500):
     import paper_2311_06837_amd as P
     part = w.partition
     n = part.graph.n_rows
-    mult = 4 if dtype == torch.float32 else 8
-    ld = _pad(F, mult)
+    ld = P.row_stride(F, dtype)                       # the layout the model (and so bench.py) uses
     print(f"{w.name}: spmm fwd rows={rows_all.size} F={F} {dtype} {kind}", flush=True)
     X = as_stored(gg.features(n, F, seed), dtype)
     length = np.diff(part.graph.row_ptr).astype(np.int32)
@@ -79,7 +85,7 @@ def _spmm_fwd_sampled(w, G, rows_all, F, dtype, kind, seed, n_sample=1500):
         cs_d = rs_d
     Xd = padded(X, ld, dtype)
     Yd = torch.zeros(n, ld, dtype=dtype, device="cuda")
-    P.gnn_masked_spmm_fwd(G, dev(rows_all), rows_all.size, Xd, Yd, F, rs_d, cs_d)
+    P.gnn_masked_spmm_fwd(G, dev(rows_all), rows_all.size, Xd, Yd, F, rs_d, cs_d, ws=_ws())
     torch.cuda.synchronize()
     sample = _sample_rows(part, rows_all, n_sample, seed)
     want = np.zeros((n, F))
@@ -96,13 +102,12 @@ def _spmm_bwd_sampled(w, G, dist, rows_out, max_dist, F, dtype, scales, seed, n_
     part = w.partition
     n = part.graph.n_rows
     rs, cs, rs_d, cs_d = scales
-    mult = 4 if dtype == torch.float32 else 8
-    ld = _pad(F, mult)
+    ld = P.row_stride(F, dtype)                       # the layout the model (and so bench.py) uses
     print(f"{w.name}: spmm bwd rows={rows_out.size} F={F} {dtype} max_dist={max_dist}", flush=True)
     dY = as_stored(gg.features(n, F, seed + 100), dtype)
     dYd = padded(dY, ld, dtype)
     dXd = torch.zeros(n, ld, dtype=dtype, device="cuda")
-    P.gnn_masked_spmm_bwd(G, dev(rows_out), rows_out.size, dev(dist), max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False)
+    P.gnn_masked_spmm_bwd(G, dev(rows_out), rows_out.size, dev(dist), max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False, ws=_ws())
     torch.cuda.synchronize()
     sample = _sample_rows(part, rows_out, n_sample, seed + 1)
     active = ((dist >= 0) & (dist <= max_dist)).astype(np.float64)
@@ -119,8 +124,7 @@ def _linear_sampled(w, rows_all, K, N, dtype, sage, seed, n_sample=2000, n_cols=
     (a column of dW depends on that column of dZ only)."""
     import paper_2311_06837_amd as P
     n = w.partition.graph.n_rows
-    mult = 4 if dtype == torch.float32 else 8
-    ld_in, ld_out = _pad(K, mult), _pad(N, mult)
+    ld_in, ld_out = P.row_stride(K, dtype), P.row_stride(N, dtype)
     print(f"{w.name}: linear rows={rows_all.size} K={K} N={N} {dtype} sage={sage}", flush=True)
     params = gg.layer_weights([K, N], sage, seed)[0]
     A = as_stored(gg.features(n, K, seed + 1), dtype)
@@ -189,7 +193,8 @@ def test_cfg1_sum_of_ones_is_degree_at_full_size(cfg1):
     G = _graph(part)
     X = torch.ones(n, 64, device="cuda")
     Y = torch.zeros(n, 64, device="cuda")
-    P.gnn_masked_spmm_fwd(G, None, n, X, Y, 64)
+    P.gnn_masked_spmm_fwd(G, None, n, X, Y, 64, ws=_ws())
+    assert _ws().buf.numel() > 256                        # the column-blocked route: sums of ones stay exact
     assert torch.equal(Y[:, 0].cpu(), torch.from_numpy(part.graph.degrees()).float())
     assert torch.equal(Y, Y[:, :1].expand(-1, 64))
 

@@ -24,6 +24,7 @@ def _gpu_model(part, kind, params, dtype):
 def _parity(name, part, kind, dims, dtype, seed):
     print(f"model {name}: n={part.graph.n_rows} nnz={part.graph.nnz} |T|={len(part.targets)} {kind} dims={dims} {dtype}",
           flush=True)
+    import paper_2311_06837_amd as P
     L = len(dims) - 1
     params = gg.layer_weights(dims, kind == "sage", seed)
     n = part.graph.n_rows
@@ -41,8 +42,7 @@ def _parity(name, part, kind, dims, dtype, seed):
     assert list(hop) == list(om.hop_offsets)
     assert np.array_equal(m.dist.cpu().numpy(), om.dist)
     assert np.array_equal(m.ring_ids.cpu().numpy()[: hop[-1]], om.ring_ids)
-    mult = 4 if dtype == torch.float32 else 8
-    m.set_input(padded(H0, (dims[0] + mult - 1) // mult * mult, dtype))
+    m.set_input(padded(H0, P.row_stride(dims[0], dtype), dtype))
     loss = m.forward(dev(y))
     m.backward()
     torch.cuda.synchronize()

@@ -13,7 +13,12 @@ pytestmark = pytest.mark.gpu
 SENTINEL = 12345.0
 
 
-def _fwd_case(g, F, ld, dtype, rows, scales, seed):
+def _used_blocked_route(ws):
+    """The size query reports 0 bytes when the column-blocked route does not apply, so the workspace stays minimal."""
+    return ws is not None and ws.buf is not None and ws.buf.numel() > 256
+
+
+def _fwd_case(g, F, ld, dtype, rows, scales, seed, ws=None):
     import paper_2311_06837_amd as P
     print(f"spmm fwd: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} rows={'list' if rows is not None else 'all'} "
           f"scales={scales}", flush=True)
@@ -29,7 +34,7 @@ def _fwd_case(g, F, ld, dtype, rows, scales, seed):
     Yd = torch.full((n, ld), SENTINEL, dtype=dtype, device="cuda")
     rows_d = dev(rows) if rows is not None else None
     n_active = len(rows) if rows is not None else n
-    P.gnn_masked_spmm_fwd(G, rows_d, n_active, Xd, Yd, F, dev(rs) if scales else None, dev(cs) if scales else None)
+    P.gnn_masked_spmm_fwd(G, rows_d, n_active, Xd, Yd, F, dev(rs) if scales else None, dev(cs) if scales else None, ws=ws)
     torch.cuda.synchronize()
     want = np.full((n, F), SENTINEL)
     oracle.spmm_fwd(g.row_ptr, g.col_idx, rows, X, want, F, rs, cs)
@@ -89,7 +94,7 @@ def test_fwd_is_bitwise_reproducible():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
-def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed):
+def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed, ws=None):
     """Backward of layer `lyr` of an L-layer model: forward rows R_lyr, outputs for R_{lyr-1}."""
     import paper_2311_06837_amd as P
     print(f"spmm bwd: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} L={L} layer={lyr} acc={accumulate}", flush=True)
@@ -107,7 +112,8 @@ def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed):
     GT = P.Graph.from_numpy(gt.row_ptr, gt.col_idx)
     dYd = padded(dY, ld, dtype)
     dXd = padded(init, ld, dtype, fill=SENTINEL)
-    P.gnn_masked_spmm_bwd(GT, dev(rows_o), len(rows_o), dev(dist), L - lyr, dYd, dXd, F, dev(rs), dev(cs), accumulate=accumulate)
+    P.gnn_masked_spmm_bwd(GT, dev(rows_o), len(rows_o), dev(dist), L - lyr, dYd, dXd, F, dev(rs), dev(cs), accumulate=accumulate,
+                          ws=ws)
     torch.cuda.synchronize()
     want = np.zeros((n, F))
     oracle.spmm_bwd(g.row_ptr, g.col_idx, rows_f, dY, want, F, rs, cs)
@@ -147,3 +153,70 @@ def test_empty_calls_are_noops():
     P.gnn_masked_spmm_fwd(G, None, 100, X, Y, 0)
     torch.cuda.synchronize()
     assert (Y == 3.0).all()
+
+
+# ---- column-blocked route (dense graph + workspace) ------------------------------------------
+
+_DENSE = {}
+
+
+def _dense_graph():
+    """70k vertices (a 256-byte feature slab of 17.9 MB), average row length 90, plus one vertex adjacent to
+    20k others, so that one of its column blocks alone is longer than the hub threshold."""
+    if "g" not in _DENSE:
+        n = 70000
+        base = gg.erdos_renyi(n, 88.0, 31)
+        rng = np.random.default_rng(32)
+        nb = rng.choice(n - 1, 20000, replace=False).astype(np.int64) + 1      # neighbours of vertex 0
+        r = np.repeat(np.arange(n, dtype=np.int64), np.diff(base.row_ptr))
+        c = base.col_idx.astype(np.int64)
+        z = np.zeros_like(nb)
+        _DENSE["g"] = gg.csr_from_edges(n, n, np.concatenate([r, z, nb]), np.concatenate([c, nb, z]))
+    return _DENSE["g"]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_blocked_route_forward(dtype):
+    import paper_2311_06837_amd as P
+    g = _dense_graph()
+    assert g.nnz / g.n_rows >= 64 and g.degrees()[0] > 8 * 1024
+    ws = P.Workspace()
+    _fwd_case(g, 200, 200, dtype, None, True, 41, ws=ws)                  # 4 (fp32) / 2 (bf16) slabs, ragged last slab
+    assert _used_blocked_route(ws)
+    rows = np.random.default_rng(5).permutation(g.n_rows)[:40001].astype(np.int32)   # unsorted list, ragged count
+    if 0 not in rows:
+        rows[17] = 0
+    _fwd_case(g, 602, 608, dtype, rows, False, 42, ws=ws)
+    _fwd_case(g, 64, 64, dtype, rows, True, 43, ws=ws)                    # a single slab
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_blocked_route_backward_with_filter(dtype, accumulate):
+    import paper_2311_06837_amd as P
+    g = _dense_graph()
+    ws = P.Workspace()
+    _bwd_case(g, 136, 136, dtype, 2, 2, accumulate, 44, ws=ws)            # forward rows = targets only: most neighbours filtered out
+    assert _used_blocked_route(ws)
+
+
+def test_blocked_route_falls_back_without_promise_or_density():
+    """Unsorted columns (no GNN_CSR_SORTED_COLUMNS promise) or a sparse graph: the size query reports 0 and the
+    call gathers whole rows."""
+    import paper_2311_06837_amd as P
+    g = _dense_graph()
+    ws = P.Workspace()
+    G = P.Graph(dev(g.row_ptr), dev(g.col_idx), sorted_columns=False)
+    X = torch.randn(g.n_rows, 64, device="cuda")
+    Y1, Y2 = torch.zeros_like(X), torch.zeros_like(X)
+    P.gnn_masked_spmm_fwd(G, None, g.n_rows, X, Y1, 64, ws=ws)
+    assert not _used_blocked_route(ws)
+    Gs = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    assert Gs.sorted_columns
+    P.gnn_masked_spmm_fwd(Gs, None, g.n_rows, X, Y2, 64, ws=ws)
+    assert _used_blocked_route(ws)
+    assert (Y1 - Y2).abs().max() <= 1e-4 * Y1.abs().max()                 # the two routes differ by rounding order only
+    sparse = gg.chung_lu(80000, 12.0, 2.1, 33)
+    ws2 = P.Workspace()
+    _fwd_case(sparse, 128, 128, torch.float32, None, True, 45, ws=ws2)
+    assert not _used_blocked_route(ws2)
