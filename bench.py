@@ -33,10 +33,13 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 
 CONFIG_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}
 
-# HBM-side traffic of the dominant kernel per launch, from the two rocprofv3 --pmc runs summarised in
-# profiles/spmm_rows_fwd_cfg1.md (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, scaled by what the same
-# counters read for a 1 GiB copy: 2.0 and 1.0).  Only known for the default workload at full scale.
-MEASURED_TRAFFIC_BYTES = {"cfg1": 135105540 * 1024 * 2.0 + 554357 * 1024 * 1.0}
+# Traffic between L2 and the memory fabric of the dominant call per launch, from the two rocprofv3 --pmc runs
+# summarised in profiles/spmm_fwd_layer1_cfg1.md (FETCH_SIZE and WRITE_SIZE in KiB, summed over the call's
+# three kernels, scaled by what the same counters read for a 1 GiB copy: 2.0 and 1.0).  Only known for the
+# default workload at full scale.
+MEASURED_TRAFFIC_KIB = {"cfg1": {"fetch": 40634700 + 2297583 + 230172,     # stream + sum_parts + seg kernels
+                                 "write": 4427011 + 562655 + 8192}}
+FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 
 
 def log(*a):
@@ -172,11 +175,21 @@ def main():
     alg_bytes = edges[dom]["fwd"] * (4 + Fd * es) + nd * (8 + Fd * es)           # gather model
     compulsory = edges[dom]["fwd"] * 4 + n_in * Fd * es + nd * (8 + Fd * es)     # every input row read once
     t_dom = call_ms[f"spmm_fwd_{dom}"] * 1e-3
+    blocked = P.binding.spmm_workspace_bytes(G, nd, model.H[dom - 1], model.A[dom], Fd) > 0
+    kernels = ("spmm_stream_kernel (+ spmm_seg_kernel before and spmm_sum_parts_kernel after it: column-blocked route)"
+               if blocked else "spmm_rows_kernel")
+    kib = MEASURED_TRAFFIC_KIB.get(args.workload) if (args.scale == 1.0 and dom == 1) else None
+    traffic = None
+    if kib and kib["fetch"] is not None:
+        traffic = (kib["fetch"] * FETCH_SCALE + kib["write"] * WRITE_SCALE) * 1024
+    # `achieved` counts the ALGORITHMIC bytes of the gather model (every neighbour row of every edge); on the
+    # column-blocked route most of them are served by the L2 of the compute die, so it can exceed the HBM peak.
+    # `traffic` is what actually crossed from L2 to the memory fabric, `traffic_GBs` the same per second.
     roofline = {
-        "kernel": f"spmm_rows_kernel (gnn_masked_spmm_fwd, layer {dom}, F={Fd})",
+        "kernel": f"{kernels}; gnn_masked_spmm_fwd, layer {dom}, F={Fd}",
         "bound": "hbm", "achieved": alg_bytes / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if (args.scale == 1.0 and dom == 1) else None,
+        "traffic": traffic, "traffic_GBs": None if traffic is None else traffic / t_dom / 1e9,
         "bytes_per_launch": alg_bytes, "launch_ms": t_dom * 1e3,
         "compulsory_bytes_per_launch": compulsory, "compulsory_GBs": compulsory / t_dom / 1e9,
     }

@@ -186,6 +186,16 @@ def gnn_masked_spmm_fwd(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch
         C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale)), (_stream(),), ws)
 
 
+def spmm_workspace_bytes(g: Graph, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int) -> int:
+    """Size query of gnn_masked_spmm_fwd: what a workspace would have to hold; 0 = the call gathers whole rows
+    in one launch, > 0 = it takes the column-blocked route."""
+    need = C.c_size_t(0)
+    _check(lib().gnn_masked_spmm_fwd(
+        C.byref(g.c), None, C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y), C.c_int64(Y.stride(0)), C.c_int32(F),
+        C.c_int32(_dtype_code(X)), None, None, None, C.byref(need), None))
+    return int(need.value)
+
+
 def gnn_masked_spmm_bwd(gT: Graph, out_rows, n_out: int, dist, max_active_dist: int, dY: torch.Tensor, dX: torch.Tensor,
                         F: int, row_scale=None, col_scale=None, accumulate: bool = False, ws: Workspace | None = None):
     _mat(dY, "dY"), _mat(dX, "dX")

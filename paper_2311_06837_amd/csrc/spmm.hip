@@ -441,7 +441,7 @@ constexpr int kStreamMaxRows = 256;
 #define GNN_SPMM_WG_EDGES 8192     // edges one workgroup aims for when the host picks its row count
 #endif
 
-template <int DT, int VE, int LPR, int NCH, int U, bool FILTER, bool PART>
+template <int DT, int VE, int LPR, int NCH, int U, bool PART, bool SCALED>
 __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm_stream_kernel(SpmmArgs a) {
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
@@ -449,14 +449,17 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
     constexpr int W = LPR * NCH * VE;  // feature columns per workgroup (grid.y blocks cover F)
     __shared__ int32_t s_start[kStreamMaxRows], s_voff[kStreamMaxRows + 1], s_v[kStreamMaxRows];
     __shared__ float s_sc[kStreamMaxRows];
-    __shared__ int2 s_tile_all[4][kWave];   // (neighbour id or -1 if filtered out, row slot) per staged edge
+    __shared__ int32_t s_u_all[4][kWave], s_r_all[4][kWave];   // neighbour id and row slot of every staged edge
+    __shared__ float s_w_all[4][kWave];                        // its scale factor (only with a neighbour scale)
     __shared__ float s_carry[NG * 2][W];
     __shared__ int32_t s_ctag[NG * 2];
     __shared__ int s_scan[4];
     const int tid = (int)threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int sub = lane / LPR, sl = lane % LPR;
     const int gi = wave * RPW + sub;
-    int2* s_tile = s_tile_all[wave];
+    int32_t* s_u = s_u_all[wave];
+    int32_t* s_r = s_r_all[wave];
+    float* s_w = s_w_all[wave];
 
     // ---- phase 0: row descriptors and the exclusive prefix of the row lengths
     const int rpw = a.rows_per_group;  // rows of the list per workgroup, <= kStreamMaxRows
@@ -503,6 +506,9 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
         col_off[c] = (int64_t)blockIdx.y * W + (int64_t)(sl + c * LPR) * VE;
         col_ok[c] = col_off[c] < a.F;
     }
+    int64_t col_ld[NCH];  // column to load from: col_off, or 0 for the lanes past F (whose sums are never stored)
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) col_ld[c] = col_ok[c] ? col_off[c] : 0;
     float acc[NCH][VE];
 #pragma unroll
     for (int c = 0; c < NCH; ++c)
@@ -560,76 +566,77 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
             for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
     };
 
-    // ---- phase 1: ids are fetched two tiles ahead and their dist values (backward filter) one tile ahead
+    // ---- phase 1: ids are fetched two tiles ahead and their scale factors one tile ahead, each lane for its own
+    // edge, so the gather loop below touches global memory for feature rows only
     int t_c = lo;
     int r_c, r_n;
     int32_t p_c, p_n;
-    const bool v_c0 = locate(t_c, r_c, p_c);
+    // (a lane without an edge reads position 0 / vertex 0: the prefetches stay unconditional, see below)
+    bool v_c = locate(t_c, r_c, p_c);
     bool v_n = locate(t_c + LPR, r_n, p_n);
-    bool v_c = v_c0;
-    int32_t u_c = v_c ? a.col_idx[p_c] : 0;
-    int32_t u_n = v_n ? a.col_idx[p_n] : 0;
-    int32_t d_c = 0;
-    if (FILTER) d_c = v_c ? a.dist[u_c] : -1;
+    int32_t u_c = a.col_idx[p_c];
+    int32_t u_n = a.col_idx[p_n];
+    if (!v_c) u_c = 0;
+    if (!v_n) u_n = 0;
+    float w_c = 1.f;
+    if (SCALED) w_c = a.nbr_scale[u_c];
     while (__ballot(t_c < hi) != 0ull) {  // uniform over the wave
-        int r_nn;
-        int32_t p_nn;
-        const bool v_nn = locate(t_c + 2 * LPR, r_nn, p_nn);
-        const int32_t u_nn = v_nn ? a.col_idx[p_nn] : 0;
-        int32_t d_n = 0;
-        if (FILTER) d_n = v_n ? a.dist[u_n] : -1;
-
         wave_lds_sync();  // the previous tile has been consumed
-        const bool keep = v_c && (!FILTER || (d_c >= 0 && d_c <= a.max_dist));
-        s_tile[lane] = make_int2(keep ? u_c : -1, r_c);
+        s_u[lane] = u_c;  // 0 where the lane has no edge: still a valid row of X for the clamped loads below
+        s_r[lane] = r_c;
+        s_w[lane] = w_c;
         int cnt = hi - t_c;
         cnt = cnt < 0 ? 0 : (cnt < LPR ? cnt : LPR);
         int cnt_max = cnt;
 #pragma unroll
         for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
+        // bit k of `starts`: edge k of this group's tile belongs to another row than the edge before it
+        // (edge 0: than the accumulators); the gather loop reads one dword per edge (the id) and looks up
+        // the row slot only where a row starts
+        const int r_before = __shfl_up(r_c, 1, kWave);
+        const bool start = v_c && r_c != (sl == 0 ? cur : r_before);
+        const uint64_t starts = (__ballot(start) >> (sub * LPR)) & (LPR == 64 ? ~0ull : (1ull << (LPR & 63)) - 1ull);
         wave_lds_sync();
+        // the prefetches go out right before this tile's gathers (everything older has been waited for by now)
+        int r_nn;
+        int32_t p_nn;
+        const bool v_nn = locate(t_c + 2 * LPR, r_nn, p_nn);
+        int32_t u_nn = a.col_idx[p_nn];
+        float w_n = 1.f;
+        if (SCALED) w_n = a.nbr_scale[u_n];
 
-        for (int k0 = 0; k0 < cnt_max; k0 += U) {
+#pragma unroll
+        for (int k0 = 0; k0 < LPR; k0 += U) {
+            if (k0 >= cnt_max) break;  // uniform over the wave
+            // The loads are unconditional (a slot past the group's count repeats slot 0, a column past F repeats
+            // column 0: both valid addresses, the values are never used): with branches around them the compiler
+            // waits for every load before issuing the next one.
             typename E::Raw x[U][NCH];
             float w[U];
-            int rr[U];
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                rr[j] = -1;
-                w[j] = 0.f;
-                if (k0 + j < cnt) {
-                    const int2 e = s_tile[sub * LPR + k0 + j];
-                    rr[j] = e.y;
-                    if (!FILTER || e.x >= 0) {
-                        w[j] = a.nbr_scale ? a.nbr_scale[e.x] : 1.f;
-                        const int64_t base = (int64_t)e.x * a.ldx;
+                const int k = k0 + j < cnt ? k0 + j : 0;
+                const int32_t u = s_u[sub * LPR + k];
+                w[j] = s_w[sub * LPR + k];
+                const int64_t base = (int64_t)u * a.ldx;
 #pragma unroll
-                        for (int c = 0; c < NCH; ++c)
-                            if (col_ok[c]) x[j][c] = E::load(a.X, base + col_off[c]);
-                    } else {
-                        rr[j] |= 1 << 30;  // filtered out: the row still has to appear, the edge adds nothing
-                    }
-                }
+                for (int c = 0; c < NCH; ++c) x[j][c] = E::load(a.X, base + col_ld[c]);
             }
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                if (rr[j] >= 0) {
-                    const int row = rr[j] & ~(1 << 30);
-                    if (row != cur) {
+                if (k0 + j < cnt) {
+                    if ((starts >> (k0 + j)) & 1ull) {
                         if (cur >= 0) flush();
-                        cur = row;
+                        cur = s_r[sub * LPR + k0 + j];
                     }
-                    if (!FILTER || !(rr[j] & (1 << 30))) {
 #pragma unroll
-                        for (int c = 0; c < NCH; ++c)
-                            if (col_ok[c]) E::fma(acc[c], w[j], x[j][c]);
-                    }
+                    for (int c = 0; c < NCH; ++c) E::fma(acc[c], w[j], x[j][c]);
                 }
             }
         }
         t_c += LPR;
-        r_c = r_n; p_c = p_n; v_c = v_n; u_c = u_n; d_c = d_n;
-        r_n = r_nn; p_n = p_nn; v_n = v_nn; u_n = u_nn;
+        r_c = r_n; p_c = p_n; v_c = v_n; u_c = u_n; w_c = w_n;
+        r_n = r_nn; p_n = p_nn; v_n = v_nn; u_n = v_nn ? u_nn : 0;
     }
     if (cur >= 0) flush();
     __syncthreads();
@@ -677,7 +684,7 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
     }
 }
 
-template <int DT, int VE, int LPR, int NCH, bool FILTER, bool PART>
+template <int DT, int VE, int LPR, int NCH, bool PART>
 static int32_t launch_stream(const SpmmArgs& a, int64_t avg_row, hipStream_t stream) {
     constexpr int U = NCH == 1 ? GNN_SPMM_STREAM_U : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
     constexpr int W = LPR * NCH * VE;
@@ -689,7 +696,8 @@ static int32_t launch_stream(const SpmmArgs& a, int64_t avg_row, hipStream_t str
     b.rows_per_group = (int32_t)(rows < 16 ? 16 : (rows > kStreamMaxRows ? kStreamMaxRows : rows));
     const int64_t n_chunks = ((int64_t)a.n_active + b.rows_per_group - 1) / b.rows_per_group;
     dim3 grid((unsigned)(n_chunks * (PART ? kDies : 1)), (unsigned)((a.F + W - 1) / W));
-    spmm_stream_kernel<DT, VE, LPR, NCH, U, FILTER, PART><<<grid, 256, 0, stream>>>(b);
+    if (a.nbr_scale) spmm_stream_kernel<DT, VE, LPR, NCH, U, PART, true><<<grid, 256, 0, stream>>>(b);
+    else spmm_stream_kernel<DT, VE, LPR, NCH, U, PART, false><<<grid, 256, 0, stream>>>(b);
     GNN_LAUNCH_CHECK("spmm_stream_kernel");
     return GNN_OK;
 }
@@ -873,7 +881,7 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
     for (int pass = 0; pass < p.passes; ++pass) {
         b.block0 = pass * kDies;
         b.accumulate = pass > 0;
-        GNN_CHECK((launch_stream<DT, VE, 16, 1, false, true>(b, p.avg_seg, stream)));
+        GNN_CHECK((launch_stream<DT, VE, 16, 1, true>(b, p.avg_seg, stream)));
     }
     spmm_sum_parts_kernel<DT><<<grid_for((int64_t)a.n_active * ((a.F + 3) / 4), 256, 1 << 16), 256, 0, stream>>>(
         part, p.ldp, a.rows, a.n_active, a.F, a.Y, a.ldy, a.out_scale, a.accumulate);
