@@ -74,6 +74,7 @@ struct SpmmArgs {
     // column-blocked route only
     const int32_t* seg;       // [n_active][n_blocks + 1] cut points of every listed row: block j = [seg[j], seg[j+1])
     const int32_t* seg_end;   // nullable, [n_active][n_blocks]: block j ends here instead (filtered, compacted copy of the ids)
+    const float* edge_w;      // with a neighbour scale: the factor of every entry of col_idx, at the same position
     int32_t n_blocks;
     int32_t block0;           // first column block of this pass
 };
@@ -506,9 +507,13 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
         col_off[c] = (int64_t)blockIdx.y * W + (int64_t)(sl + c * LPR) * VE;
         col_ok[c] = col_off[c] < a.F;
     }
-    int64_t col_ld[NCH];  // column to load from: col_off, or 0 for the lanes past F (whose sums are never stored)
+    // per-lane base address of its 16-byte chunk(s) of a row of X: column col_off, or column 0 for the lanes past
+    // F (whose sums are never stored); a neighbour's row then adds its offset, staged in 16-byte units
+    constexpr int ES = DT == GNN_F32 ? 4 : 2;
+    const char* x_lane[NCH];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) col_ld[c] = col_ok[c] ? col_off[c] : 0;
+    for (int c = 0; c < NCH; ++c) x_lane[c] = (const char*)a.X + (col_ok[c] ? col_off[c] : 0) * ES;
+    const uint32_t row16 = (uint32_t)(a.ldx * ES / 16);
     float acc[NCH][VE];
 #pragma unroll
     for (int c = 0; c < NCH; ++c)
@@ -566,8 +571,8 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
             for (int k = 0; k < VE; ++k) acc[c][k] = 0.f;
     };
 
-    // ---- phase 1: ids are fetched two tiles ahead and their scale factors one tile ahead, each lane for its own
-    // edge, so the gather loop below touches global memory for feature rows only
+    // ---- phase 1: ids (and their scale factors, stored per edge by the prepare pass) are fetched two tiles ahead,
+    // coalesced, each lane for its own edge, so the gather loop below touches global memory for feature rows only
     int t_c = lo;
     int r_c, r_n;
     int32_t p_c, p_n;
@@ -578,18 +583,26 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
     int32_t u_n = a.col_idx[p_n];
     if (!v_c) u_c = 0;
     if (!v_n) u_n = 0;
-    float w_c = 1.f;
-    if (SCALED) w_c = a.nbr_scale[u_c];
+    float w_c = 1.f, w_n = 1.f;
+    if (SCALED) {
+        w_c = a.edge_w[p_c];
+        w_n = a.edge_w[p_n];
+    }
     while (__ballot(t_c < hi) != 0ull) {  // uniform over the wave
         wave_lds_sync();  // the previous tile has been consumed
-        s_u[lane] = u_c;  // 0 where the lane has no edge: still a valid row of X for the clamped loads below
+        // what is staged is the neighbour's row offset in 16-byte units (one multiply per lane and tile instead of
+        // a 64-bit multiply per edge in the gather loop); 0 where the lane has no edge: a valid row all the same
+        s_u[lane] = (int32_t)((uint32_t)u_c * row16);
         s_r[lane] = r_c;
-        s_w[lane] = w_c;
+        if (SCALED) s_w[lane] = w_c;
         int cnt = hi - t_c;
         cnt = cnt < 0 ? 0 : (cnt < LPR ? cnt : LPR);
-        int cnt_max = cnt;
+        int cnt_max = cnt, cnt_min = cnt;
 #pragma unroll
-        for (int d = LPR; d < kWave; d <<= 1) cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
+        for (int d = LPR; d < kWave; d <<= 1) {
+            cnt_max = max(cnt_max, __shfl_xor(cnt_max, d, kWave));
+            cnt_min = min(cnt_min, __shfl_xor(cnt_min, d, kWave));
+        }
         // bit k of `starts`: edge k of this group's tile belongs to another row than the edge before it
         // (edge 0: than the accumulators); the gather loop reads one dword per edge (the id) and looks up
         // the row slot only where a row starts
@@ -602,41 +615,49 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
         int32_t p_nn;
         const bool v_nn = locate(t_c + 2 * LPR, r_nn, p_nn);
         int32_t u_nn = a.col_idx[p_nn];
-        float w_n = 1.f;
-        if (SCALED) w_n = a.nbr_scale[u_n];
+        float w_nn = 1.f;
+        if (SCALED) w_nn = a.edge_w[p_nn];
 
 #pragma unroll
         for (int k0 = 0; k0 < LPR; k0 += U) {
             if (k0 >= cnt_max) break;  // uniform over the wave
-            // The loads are unconditional (a slot past the group's count repeats slot 0, a column past F repeats
+            // The loads are unconditional (a slot past the group's count holds row 0, a column past F reads
             // column 0: both valid addresses, the values are never used): with branches around them the compiler
             // waits for every load before issuing the next one.
             typename E::Raw x[U][NCH];
             float w[U];
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                const int k = k0 + j < cnt ? k0 + j : 0;
-                const int32_t u = s_u[sub * LPR + k];
-                w[j] = s_w[sub * LPR + k];
-                const int64_t base = (int64_t)u * a.ldx;
+                const uint64_t row_bytes = (uint64_t)(uint32_t)s_u[sub * LPR + k0 + j] << 4;
+                w[j] = SCALED ? s_w[sub * LPR + k0 + j] : 1.f;
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) x[j][c] = E::load(a.X, base + col_ld[c]);
+                for (int c = 0; c < NCH; ++c) x[j][c] = *(const typename E::Raw*)(x_lane[c] + row_bytes);
             }
+            // common case, decided for the whole wave: every group has a full tile and no row starts inside this
+            // round -> plain multiply-adds; else each edge checks its count and its row-start bit
+            const bool round_has_start = ((starts >> k0) & ((1ull << U) - 1ull)) != 0ull;
+            if (cnt_min == LPR && __ballot(round_has_start) == 0ull) {
 #pragma unroll
-            for (int j = 0; j < U; ++j) {
-                if (k0 + j < cnt) {
-                    if ((starts >> (k0 + j)) & 1ull) {
-                        if (cur >= 0) flush();
-                        cur = s_r[sub * LPR + k0 + j];
-                    }
+                for (int j = 0; j < U; ++j)
 #pragma unroll
                     for (int c = 0; c < NCH; ++c) E::fma(acc[c], w[j], x[j][c]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < U; ++j) {
+                    if (k0 + j < cnt) {
+                        if ((starts >> (k0 + j)) & 1ull) {
+                            if (cur >= 0) flush();
+                            cur = s_r[sub * LPR + k0 + j];
+                        }
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c) E::fma(acc[c], w[j], x[j][c]);
+                    }
                 }
             }
         }
         t_c += LPR;
         r_c = r_n; p_c = p_n; v_c = v_n; u_c = u_n; w_c = w_n;
-        r_n = r_nn; p_n = p_nn; v_n = v_nn; u_n = v_nn ? u_nn : 0;
+        r_n = r_nn; p_n = p_nn; v_n = v_nn; u_n = v_nn ? u_nn : 0; w_n = w_nn;
     }
     if (cur >= 0) flush();
     __syncthreads();
@@ -696,7 +717,7 @@ static int32_t launch_stream(const SpmmArgs& a, int64_t avg_row, hipStream_t str
     b.rows_per_group = (int32_t)(rows < 16 ? 16 : (rows > kStreamMaxRows ? kStreamMaxRows : rows));
     const int64_t n_chunks = ((int64_t)a.n_active + b.rows_per_group - 1) / b.rows_per_group;
     dim3 grid((unsigned)(n_chunks * (PART ? kDies : 1)), (unsigned)((a.F + W - 1) / W));
-    if (a.nbr_scale) spmm_stream_kernel<DT, VE, LPR, NCH, U, PART, true><<<grid, 256, 0, stream>>>(b);
+    if (a.edge_w) spmm_stream_kernel<DT, VE, LPR, NCH, U, PART, true><<<grid, 256, 0, stream>>>(b);
     else spmm_stream_kernel<DT, VE, LPR, NCH, U, PART, false><<<grid, 256, 0, stream>>>(b);
     GNN_LAUNCH_CHECK("spmm_stream_kernel");
     return GNN_OK;
@@ -743,12 +764,15 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(const int32_t* __restrict
     }
 }
 
-// Backward filter of the column-blocked route, applied once instead of once per feature slab: every (row, block)
-// segment is copied to `ids` at its own position with the neighbours that fail the dist test squeezed out;
-// seg_end[r][j] = where the kept ones end.  One group of 16 lanes per segment.
-__global__ __launch_bounds__(256) void spmm_filter_kernel(const int32_t* __restrict__ col_idx, const int32_t* __restrict__ seg,
-                                                           const int32_t* __restrict__ dist, int32_t max_dist, int64_t n_segments,
-                                                           int32_t n_blocks, int32_t* __restrict__ ids, int32_t* __restrict__ seg_end) {
+// Per-edge preparation of the column-blocked route, done once per call instead of once per feature slab: every
+// (row, block) segment is copied to `ids` at its own position - with a dist filter (backward) the neighbours that
+// fail the test are squeezed out, seg_end[r][j] = where the kept ones end - and with a neighbour scale the factor of
+// every kept neighbour goes to `w` at the same position (the random 4-byte gathers of the scale vector happen here,
+// once; the stream kernel then reads ids and factors coalesced).  One group of 16 lanes per segment.
+__global__ __launch_bounds__(256) void spmm_prepare_kernel(const int32_t* __restrict__ col_idx, const int32_t* __restrict__ seg,
+                                                            const int32_t* __restrict__ dist, int32_t max_dist,
+                                                            const float* __restrict__ nbr_scale, int64_t n_segments, int32_t n_blocks,
+                                                            int32_t* __restrict__ ids, float* __restrict__ w, int32_t* __restrict__ seg_end) {
     constexpr int LPG = 16;
     const int lane = lane_id(), sub = lane / LPG, sl = lane % LPG;
     const int64_t groups = (int64_t)gridDim.x * (blockDim.x / LPG);
@@ -757,14 +781,34 @@ __global__ __launch_bounds__(256) void spmm_filter_kernel(const int32_t* __restr
         const int32_t j = (int32_t)(sgm % n_blocks);
         const int32_t lo = seg[r * (n_blocks + 1) + j], hi = seg[r * (n_blocks + 1) + j + 1];
         int32_t out = lo;
-        for (int32_t p = lo; p < hi; p += LPG) {
-            const bool valid = p + sl < hi;
-            const int32_t u = valid ? col_idx[p + sl] : 0;
-            const int32_t d = valid ? dist[u] : -1;
-            const bool keep = valid && d >= 0 && d <= max_dist;
-            const uint64_t kept = (__ballot(keep) >> (sub * LPG)) & 0xffffull;
-            if (keep) ids[out + __popcll(kept & ((1ull << sl) - 1ull))] = u;
-            out += __popcll(kept);
+        // kT tiles of 16 entries per step: all their id loads go out together, then all dist / scale loads, so a
+        // typical segment (a few tiles) pays each memory latency once instead of once per tile
+        constexpr int kT = 4;
+        for (int32_t p = lo; p < hi; p += kT * LPG) {
+            int32_t u[kT], d[kT];
+            float f[kT];
+            bool valid[kT];
+#pragma unroll
+            for (int t = 0; t < kT; ++t) {
+                valid[t] = p + t * LPG + sl < hi;
+                u[t] = valid[t] ? col_idx[p + t * LPG + sl] : 0;
+            }
+#pragma unroll
+            for (int t = 0; t < kT; ++t) {
+                d[t] = dist ? dist[u[t]] : 0;          // u = 0 where the lane has no entry: a valid index
+                f[t] = nbr_scale ? nbr_scale[u[t]] : 1.f;
+            }
+#pragma unroll
+            for (int t = 0; t < kT; ++t) {
+                const bool keep = valid[t] && d[t] >= 0 && d[t] <= (dist ? max_dist : 0);
+                const uint64_t kept = (__ballot(keep) >> (sub * LPG)) & 0xffffull;
+                if (keep) {
+                    const int32_t q = out + __popcll(kept & ((1ull << sl) - 1ull));
+                    ids[q] = u[t];
+                    if (nbr_scale) w[q] = f[t];
+                }
+                out += __popcll(kept);
+            }
         }
         if (sl == 0) seg_end[sgm] = out;
     }
@@ -826,12 +870,16 @@ struct BlockedPlan {
     int32_t block_size = 0;
     int64_t ldp = 0;          // leading dimension of a partial plane, in floats
     size_t seg_bytes = 0, part_bytes = 0;
-    size_t end_bytes = 0, ids_bytes = 0;   // backward filter only: segment ends and the compacted copy of the ids
+    size_t end_bytes = 0, ids_bytes = 0;   // with a filter or a neighbour scale: segment ends and the (compacted) copy of the ids
+    size_t w_bytes = 0;                    // with a neighbour scale: the factor of every copied id
     int64_t avg_seg = 0;      // average neighbours of a row inside one column block
 };
 
-static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, bool vec_ok, bool filter) {
+static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, int64_t row_bytes, bool vec_ok, bool filter,
+                                bool scaled) {
     BlockedPlan p;
+    // the stream kernel addresses the gathered matrix with 32-bit offsets in 16-byte units: 64 GB at most
+    if ((int64_t)g->n_cols * row_bytes >= ((int64_t)1 << 36)) return p;
     if (!vec_ok || !(g->flags & GNN_CSR_SORTED_COLUMNS) || g->n_rows <= 0 || n_active < 4096) return p;
     const int64_t slab = (int64_t)g->n_cols * kSlabBytes;
     if (slab < (int64_t)GNN_SPMM_BLOCKED_MIN_SLAB) return p;
@@ -845,10 +893,11 @@ static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, b
     p.ldp = ((int64_t)F + 7) / 8 * 8;
     p.seg_bytes = (size_t)n_active * (n_blocks + 1) * sizeof(int32_t);
     p.part_bytes = (size_t)kDies * n_active * p.ldp * sizeof(float);
-    if (filter) {
+    if (filter || scaled) {
         p.end_bytes = (size_t)n_active * n_blocks * sizeof(int32_t);
         p.ids_bytes = (size_t)g->nnz * sizeof(int32_t);
     }
+    if (scaled) p.w_bytes = (size_t)g->nnz * sizeof(float);
     return p;
 }
 
@@ -858,19 +907,22 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
     WsCarver carve(ws);
     int32_t* seg = carve.take<int32_t>(p.seg_bytes / sizeof(int32_t));
     float* part = carve.take<float>(p.part_bytes / sizeof(float));
-    int32_t* seg_end = FILTER ? carve.take<int32_t>(p.end_bytes / sizeof(int32_t)) : nullptr;
-    int32_t* ids = FILTER ? carve.take<int32_t>(p.ids_bytes / sizeof(int32_t)) : nullptr;
+    const bool prepare = FILTER || a.nbr_scale != nullptr;
+    int32_t* seg_end = prepare ? carve.take<int32_t>(p.end_bytes / sizeof(int32_t)) : nullptr;
+    int32_t* ids = prepare ? carve.take<int32_t>(p.ids_bytes / sizeof(int32_t)) : nullptr;
+    float* edge_w = a.nbr_scale ? carve.take<float>(p.w_bytes / sizeof(float)) : nullptr;
     spmm_seg_kernel<<<grid_for((int64_t)a.n_active * (p.n_blocks + 1), 256, 1 << 16), 256, 0, stream>>>(
         a.row_ptr, a.col_idx, a.rows, a.n_active, p.n_blocks, p.block_size, seg);
     GNN_LAUNCH_CHECK("spmm_seg_kernel");
     SpmmArgs b = a;
-    if (FILTER) {
+    if (prepare) {
         const int64_t n_segments = (int64_t)a.n_active * p.n_blocks;
-        spmm_filter_kernel<<<grid_for(n_segments * 16, 256, 1 << 18), 256, 0, stream>>>(a.col_idx, seg, a.dist, a.max_dist, n_segments,
-                                                                                     p.n_blocks, ids, seg_end);
-        GNN_LAUNCH_CHECK("spmm_filter_kernel");
+        spmm_prepare_kernel<<<grid_for(n_segments * 16, 256, 1 << 18), 256, 0, stream>>>(
+            a.col_idx, seg, FILTER ? a.dist : nullptr, a.max_dist, a.nbr_scale, n_segments, p.n_blocks, ids, edge_w, seg_end);
+        GNN_LAUNCH_CHECK("spmm_prepare_kernel");
         b.col_idx = ids;
         b.seg_end = seg_end;
+        b.edge_w = edge_w;
         b.dist = nullptr;
     }
     b.seg = seg;
@@ -917,15 +969,16 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     const bool filter = dist != nullptr;
     BlockedPlan plan;
     if (ws_bytes != nullptr) {
-        if (n_active > 0 && F > 0) plan = plan_blocked(g, n_active, F, vec_ok, filter);
+        if (n_active > 0 && F > 0) plan = plan_blocked(g, n_active, F, ldx * (dtype == GNN_F32 ? 4 : 2), vec_ok, filter, nbr_scale != nullptr);
         WsCarver measure(nullptr);
         if (plan.passes > 0) {
             measure.take<char>(plan.seg_bytes);
             measure.take<char>(plan.part_bytes);
-            if (filter) {
+            if (plan.end_bytes) {
                 measure.take<char>(plan.end_bytes);
                 measure.take<char>(plan.ids_bytes);
             }
+            if (plan.w_bytes) measure.take<char>(plan.w_bytes);
         }
         bool query_only = false;
         GNN_CHECK(ws_protocol(ws, ws_bytes, measure.used, &query_only));
@@ -940,7 +993,7 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = max_dist;
     a.accumulate = accumulate;
     a.rows_per_group = 1;
-    a.seg = nullptr; a.seg_end = nullptr; a.n_blocks = 0; a.block0 = 0;
+    a.seg = nullptr; a.seg_end = nullptr; a.edge_w = nullptr; a.n_blocks = 0; a.block0 = 0;
 
     if (plan.passes > 0) {
         if (dtype == GNN_F32) return filter ? run_blocked<GNN_F32, true>(a, plan, ws, stream) : run_blocked<GNN_F32, false>(a, plan, ws, stream);
