@@ -201,6 +201,25 @@ def sampled_local_edges(targets, out_row_ptr, out_col_idx):
     return l2g, er, ec
 
 
+def extract_partition(row_ptr, col_idx, targets, L):
+    """Section 6 step 1: the one-hop graph of everything within L hops of the targets, vertices renumbered by
+    (distance, id).  -> (local_row_ptr, local_col_idx, local_to_global, hop_offsets, dist_local);
+    layer l's rows are the local ids 0 .. hop_offsets[L-l+1]-1."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    n = row_ptr.shape[0] - 1
+    _, ring, off = active_sets(row_ptr, col_idx, targets, L)
+    n_local = ring.shape[0]
+    new_id = np.empty(n, dtype=np.int32)
+    rp = np.empty(n_local + 1, dtype=np.int32)
+    f = lib().orc_extract_partition
+    f.restype = C.c_int64
+    nnz = f(C.c_int32(n), _p(row_ptr), _p(col_idx), _p(ring), C.c_int32(n_local), _p(new_id), _p(rp), None)
+    ci = np.empty(max(int(nnz), 1), dtype=np.int32)
+    f(C.c_int32(n), _p(row_ptr), _p(col_idx), _p(ring), C.c_int32(n_local), _p(new_id), _p(rp), _p(ci))
+    dist_local = np.repeat(np.arange(L + 1, dtype=np.int32), np.diff(off).astype(np.int64))
+    return rp, ci[: int(nnz)], ring, off, dist_local
+
+
 def _row_entries(row_ptr, col_idx, rows):
     """All column entries of the listed rows, concatenated."""
     start = row_ptr[rows].astype(np.int64)

@@ -14,7 +14,10 @@
  *     that the targets' exact dependency still needs;
  *   - expansion-aware sampling of section 5.3: inner dependencies are kept
  *     whole, only edges that leave the target set are thinned, at most
- *     `fanout` per boundary vertex.
+ *     `fanout` per boundary vertex;
+ *   - extraction of the partition (section 6, step 1; section 5.3.1 "a
+ *     subgraph is generated from the traversed vertices"): the vertices the
+ *     traversal reached and every edge of the graph between two of them.
  *
  * Conventions.  L layers numbered l = 1..L.  T = target (inner) vertices.
  * Row v of the CSR lists the vertices u that v aggregates.  dist(v) = number
@@ -351,5 +354,41 @@ int64_t orc_sample_boundary(int32_t n, const int32_t *row_ptr, const int32_t *co
     }
     out_row_ptr[n_targets] = (int32_t)pos;
     free(cand);
+    return pos;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Extraction of the partition's one-hop graph (section 6, step 1; section  */
+/* 5.3.1): the traversed vertices = ring_ids (all vertices within L hops of */
+/* the targets, sorted by (distance, id), as orc_active_sets returns them)  */
+/* become the local vertices 0 .. n_local-1 in that order, so that every    */
+/* per-layer active set is a prefix of the local numbering; the local graph */
+/* keeps exactly the edges of the graph whose two ends were both traversed  */
+/* (vertex-induced sub-graph).  Local rows list their columns in ascending  */
+/* local id.                                                                */
+/*   new_id       scratch [n]: local id of every vertex, -1 if not traversed */
+/*   out_col_idx  NULL: only count (out_row_ptr is still written)            */
+/* Returns the number of local edges.                                       */
+/* ---------------------------------------------------------------------- */
+int64_t orc_extract_partition(int32_t n, const int32_t *row_ptr, const int32_t *col_idx,
+                              const int32_t *ring_ids, int32_t n_local, int32_t *new_id,
+                              int32_t *out_row_ptr, int32_t *out_col_idx)
+{
+    for (int32_t v = 0; v < n; ++v) new_id[v] = -1;
+    for (int32_t i = 0; i < n_local; ++i) new_id[ring_ids[i]] = i;
+    int64_t pos = 0;
+    for (int32_t i = 0; i < n_local; ++i) {
+        const int32_t v = ring_ids[i];
+        out_row_ptr[i] = (int32_t)pos;
+        const int64_t first = pos;
+        for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+            const int32_t u = new_id[col_idx[e]];
+            if (u < 0) continue;              /* the other end was not traversed */
+            if (out_col_idx) out_col_idx[pos] = u;
+            ++pos;
+        }
+        if (out_col_idx) qsort(out_col_idx + first, (size_t)(pos - first), sizeof(int32_t), orc_i32_cmp);
+    }
+    out_row_ptr[n_local] = (int32_t)pos;
     return pos;
 }
