@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--workload", default="cfg1", choices=sorted(CONFIG_INDEX))
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the vertex count (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extract-on-gpu", action="store_true",
+                    help="build the partition on the GPU from the unpartitioned graph (active sets, extraction with "
+                         "(distance, id) numbering, feature gather) instead of on the host; full-halo workloads only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -116,14 +119,54 @@ def main():
     n = part.graph.n_rows
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
-    G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
-    GT = G if part.graph_t is part.graph else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
     params = gg.layer_weights(w.dims, sage, w.seed)
-    model = P.MaskedGNN(G, GT, dev(part.targets), w.model, [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
-                        global_degree=dev(part.global_degree) if w.model == "gcn" else None)
+    dparams = [{k: dev(v) for k, v in p.items()} for p in params]
     ld0 = P.row_stride(w.dims[0], dtype)
     H0 = gg.features(n, w.dims[0], w.seed, ld=ld0)
-    model.set_input(dev(H0).to(dtype))
+    n_layers = len(w.dims) - 1
+
+    # Step (a-1) of the path, outside the timed step like the sampling: the partition's one-hop graph extracted on
+    # the GPU from the unpartitioned graph, vertices renumbered by (distance, id).  Timed always (full-halo
+    # workloads); used for the run with --extract-on-gpu.
+    t_extract, gpu_part = None, None
+    if w.partition is not None:
+        Gg = P.Graph.from_numpy(w.global_graph.row_ptr, w.global_graph.col_idx)
+        Tg = dev(w.targets_global.astype(np.int32))
+        ews = P.Workspace()
+        for rep_i in range(2):       # first pass warms the allocator, second is timed
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            gdist, gring, _, ghop = P.gnn_build_active_sets(Gg, Tg, n_layers, ws=ews)
+            local, new_id = P.gnn_extract_partition(Gg, gring, int(ghop[-1]), gdist, n_layers, ws=ews)
+            torch.cuda.synchronize()
+            t_extract = time.perf_counter() - t0
+        assert local.n_rows == n and local.nnz == part.graph.nnz, "GPU extraction disagrees with the host-built partition"
+        log(f"[bench] GPU extraction of the partition (active sets of the unpartitioned graph + sub-graph): {t_extract * 1e3:.2f} ms")
+        if args.extract_on_gpu:
+            gpu_part = (local, gring[:n].clone())
+        del Gg, gdist, new_id
+        if not args.extract_on_gpu:
+            del local, gring
+
+    if gpu_part is not None:
+        G, l2g = gpu_part
+        GT = G                                   # the workloads' graphs are symmetric
+        t_dev = torch.arange(len(part.targets), dtype=torch.int32, device="cuda")
+        gdeg = None
+        if w.model == "gcn":
+            gdeg = dev(w.global_graph.degrees().astype(np.int32))[l2g.long()]
+        model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg)
+        # the host partition numbers its vertices by ascending id; its feature rows are permuted into ring order
+        pos = torch.from_numpy(np.searchsorted(part.local_to_global, l2g.cpu().numpy().astype(np.int64)).astype(np.int32)).cuda()
+        H0d = torch.zeros(n, ld0, dtype=dtype, device="cuda")
+        P.gnn_gather_rows(dev(H0).to(dtype), pos, w.dims[0], H0d)
+        model.set_input(H0d)
+    else:
+        G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
+        GT = G if part.graph_t is part.graph else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
+        model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=dtype,
+                            global_degree=dev(part.global_degree) if w.model == "gcn" else None)
+        model.set_input(dev(H0).to(dtype))
     labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
     log(f"[bench] partition: n={n} nnz={part.graph.nnz} |T|={len(part.targets)} model={w.model} dims={w.dims} dtype={w.dtype}")
 
@@ -219,7 +262,10 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(part, w, params, H0, model)
+        rows1 = model.ring_ids[: model.n_rows_of_layer(1)]
+        if gpu_part is not None:     # same vertices in the host partition's numbering (H0 and part.graph use it)
+            rows1 = pos[rows1.long()]
+        cpu = cpu_baseline(part, w, params, H0, rows1.cpu().numpy())
 
     out = {
         "metric": "aggregated_edges_per_sec", "value": total_edges / (wall / args.steps), "unit": "edges/s",
@@ -231,6 +277,8 @@ def main():
         "epoch_ms": sum(v for k, v in call_ms.items() if k != "active_sets"),
         "active_sets_ms": call_ms.get("active_sets"),
         "sampling_ms": None if t_sample is None else t_sample * 1e3, "sampled_edges": kept,
+        "extract_ms": None if t_extract is None else t_extract * 1e3,
+        "partition_built_on": "gpu ((distance, id) numbering)" if gpu_part is not None else "host (ascending-id numbering)",
         "aggregated_edges_per_step": total_edges,
         "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,
         "call_ms": {k: round(v, 4) for k, v in call_ms.items()},
@@ -238,11 +286,11 @@ def main():
     print(json.dumps(out))
 
 
-def cpu_baseline(part, w, params, H0, model):
+def cpu_baseline(part, w, params, H0, rows_all):
     """The oracle as it stands, on this machine's host cores: layer-1 masked aggregation + feature transform
-    (forward) on a seeded sample of the layer's rows, sized for about 10-30 s."""
+    (forward) on a seeded sample of the layer's rows (rows_all, local ids of the host partition), sized for
+    about 10-30 s."""
     import oracle
-    rows_all = model.ring_ids[: model.n_rows_of_layer(1)].cpu().numpy()
     K, N = w.dims[0], w.dims[1]
     deg = np.diff(part.graph.row_ptr)[rows_all].astype(np.int64)
     # budget: about 2e11 fp64 multiply-adds of aggregation (roughly 10-20 s on 16 cores with the gathers)

@@ -214,6 +214,38 @@ int32_t gnn_sample_boundary(const gnn_csr *g, const uint32_t *target_bitmap,
                             int64_t *out_nnz, int64_t *out_nnz_host,
                             void *ws, size_t *ws_bytes, void *stream);
 
+/*
+ * Extraction of the partition's one-hop graph (section 6, figure 7c step 1: extract the multi-hop
+ * dependency starting from the inner vertices; section 5.3.1: a subgraph is generated from the
+ * traversed vertices).  g is the UNPARTITIONED graph (square); ring_ids[0 .. n_local) and dist are
+ * what gnn_build_active_sets wrote for it (traversed vertices sorted by (distance, id)).  The
+ * traversed vertices become the local vertices 0 .. n_local-1 in that order - so the rows of layer l
+ * are the PREFIX 0 .. hop_offsets[L-l+1]-1 of the local numbering, targets first - and the local
+ * graph keeps every edge of g between two traversed vertices, in local ids, each row ascending
+ * (the result satisfies GNN_CSR_SORTED_COLUMNS if g does).
+ *   new_id       out [g->n_rows]: local id of every vertex, -1 if not traversed (written by the
+ *                count pass, read by the fill pass)
+ * Two calls, as for gnn_sample_boundary:
+ *   count pass   out_col_idx == NULL: writes new_id, out_row_ptr[0 .. n_local] and *out_nnz (device);
+ *                out_nnz_host, if non-NULL, receives the same number (the call then waits)
+ *   fill pass    out_col_idx != NULL: writes the local column ids; entries at or beyond out_capacity
+ *                are not written
+ * Ids in ring_ids outside [0, g->n_rows) give empty rows.  L <= 30.  Bit-exact.
+ */
+int32_t gnn_extract_partition(const gnn_csr *g, const int32_t *ring_ids, int32_t n_local,
+                              const int32_t *dist, int32_t L, int32_t *new_id,
+                              int32_t *out_row_ptr, int32_t *out_col_idx, int64_t out_capacity,
+                              int64_t *out_nnz, int64_t *out_nnz_host,
+                              void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Row gather (the features of the extracted vertices, in local order):
+ *     dst[i, 0:F] = src[ids[i], 0:F]    for i in [0, n);  rows with ids[i] outside [0, n_src) are skipped
+ * src [n_src, ld_src], dst [n, ld_dst] of `dtype`; columns F..ld_dst of dst are not written.
+ */
+int32_t gnn_gather_rows(const void *src, int64_t ld_src, int32_t n_src, const int32_t *ids, int32_t n,
+                        int32_t F, int32_t dtype, void *dst, int64_t ld_dst, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ STATUS = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_SHAPE", 3: "GNN_ERR
 
 EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_scales", "gnn_masked_spmm_fwd",
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
-           "gnn_sample_boundary"]
+           "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows"]
 
 
 class GnnError(RuntimeError):
@@ -285,3 +285,28 @@ def gnn_sample_boundary(g: Graph, target_bitmap: torch.Tensor, targets: torch.Te
     out_ci = torch.empty(max(kept, 1), dtype=torch.int32, device=dev)
     _with_ws(lib().gnn_sample_boundary, common + (_ptr(out_ci), C.c_int64(kept), _ptr(nnz_dev), None), (_stream(),), ws)
     return out_rp, out_ci[:kept]
+
+
+def gnn_extract_partition(g: Graph, ring_ids: torch.Tensor, n_local: int, dist: torch.Tensor, L: int, ws: Workspace | None = None):
+    """Count pass + fill pass.  -> (local Graph with sorted columns if g has them, new_id int32[g.n_rows])."""
+    _i32(ring_ids, "ring_ids"), _i32(dist, "dist")
+    assert ring_ids.numel() >= n_local and dist.numel() >= g.n_rows
+    dev = g.row_ptr.device
+    new_id = torch.empty(max(g.n_rows, 1), dtype=torch.int32, device=dev)
+    out_rp = torch.empty(n_local + 1, dtype=torch.int32, device=dev)
+    nnz_dev = torch.empty(1, dtype=torch.int64, device=dev)
+    nnz_host = C.c_int64(0)
+    common = (C.byref(g.c), _ptr(ring_ids) if n_local else None, C.c_int32(n_local), _ptr(dist), C.c_int32(L), _ptr(new_id), _ptr(out_rp))
+    _with_ws(lib().gnn_extract_partition, common + (None, C.c_int64(0), _ptr(nnz_dev), C.byref(nnz_host)), (_stream(),), ws)
+    nnz = int(nnz_host.value)
+    out_ci = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    _with_ws(lib().gnn_extract_partition, common + (_ptr(out_ci), C.c_int64(nnz), _ptr(nnz_dev), None), (_stream(),), ws)
+    return Graph(out_rp, out_ci[:nnz], n_cols=n_local, sorted_columns=g.sorted_columns), new_id[: g.n_rows]
+
+
+def gnn_gather_rows(src: torch.Tensor, ids: torch.Tensor, F: int, dst: torch.Tensor):
+    """dst[i, :F] = src[ids[i], :F]."""
+    _mat(src, "src"), _mat(dst, "dst"), _i32(ids, "ids")
+    assert src.dtype == dst.dtype and dst.shape[0] >= ids.numel()
+    _check(lib().gnn_gather_rows(_ptr(src), C.c_int64(src.stride(0)), C.c_int32(src.shape[0]), _ptr(ids), C.c_int32(ids.numel()),
+                                 C.c_int32(F), C.c_int32(_dtype_code(src)), _ptr(dst), C.c_int64(dst.stride(0)), _stream()))

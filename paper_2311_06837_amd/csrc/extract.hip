@@ -1,0 +1,183 @@
+// Extraction of the partition's one-hop graph (paper section 6, figure 7c step 1: "extract the selected
+// neighbours from the multi-hop dependency starting from the inner vertices"; section 5.3.1: "a subgraph is
+// generated from the traversed vertices"), and the matching gather of the feature rows.
+//
+// Input is what gnn_build_active_sets leaves for the UNPARTITIONED graph: the traversed vertices in ring order
+// (sorted by (distance from the targets, id)) and dist[].  They become the local vertices 0 .. n_local-1 in that
+// order, so every per-layer active set R_l of the local graph is a prefix of the numbering (targets first), and the
+// local graph keeps every edge of the graph between two traversed vertices (vertex-induced sub-graph).
+//
+// Mapping to CDNA4.  Integer work, HBM-bound: each local row reads its global row once per pass (4 bytes per entry)
+// and probes new_id[] / dist[] (4 bytes, random; both arrays are L2-resident for the partition sizes in question).
+// A group of 16 lanes owns a row.  Because the numbering is (distance, id) and a global row is ascending in id, the
+// row in ascending LOCAL id is the stable partition of its kept entries by distance: one ballot-compaction pass per
+// distance class (at most three classes can occur in a symmetric graph - distance d-1, d, d+1 - and the passes
+// re-read a row that is already in cache), no sort, bit-exact.
+#include "common.h"
+#include "scan.h"
+
+namespace gnnhot {
+
+constexpr int kExLanes = 16;  // lanes per local row
+
+__global__ __launch_bounds__(256) void ex_number_kernel(const int32_t* __restrict__ ring_ids, int32_t n_local, int32_t n,
+                                                         int32_t* __restrict__ new_id) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_local) {
+        const int32_t v = ring_ids[i];
+        if (v >= 0 && v < n) new_id[v] = (int32_t)i;
+    }
+}
+
+// counts[i] = entries of global row ring_ids[i] whose other end was traversed
+__global__ __launch_bounds__(256) void ex_count_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                        const int32_t* __restrict__ ring_ids, int32_t n_local, int32_t n,
+                                                        const int32_t* __restrict__ new_id, int32_t* __restrict__ counts) {
+    const int lane = lane_id(), sub = lane / kExLanes, sl = lane % kExLanes;
+    const int64_t groups = (int64_t)gridDim.x * (blockDim.x / kExLanes);
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kExLanes; i < n_local; i += groups) {
+        const int32_t v = ring_ids[i];
+        int32_t s = 0, e = 0;
+        if (v >= 0 && v < n) {
+            s = row_ptr[v];
+            e = row_ptr[v + 1];
+        }
+        int32_t c = 0;
+        for (int32_t p = s; p < e; p += kExLanes) {
+            const bool keep = p + sl < e && new_id[col_idx[p + sl]] >= 0;
+            c += __popcll((__ballot(keep) >> (sub * kExLanes)) & 0xffffull);
+        }
+        if (sl == 0) counts[i] = c;
+    }
+}
+
+// out_col_idx[out_row_ptr[i] ..] = local ids of the kept entries of global row ring_ids[i], ascending
+__global__ __launch_bounds__(256) void ex_fill_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                       const int32_t* __restrict__ ring_ids, int32_t n_local, int32_t n,
+                                                       const int32_t* __restrict__ new_id, const int32_t* __restrict__ dist, int32_t L,
+                                                       const int32_t* __restrict__ out_row_ptr, int32_t* __restrict__ out_col_idx,
+                                                       int64_t capacity) {
+    const int lane = lane_id(), sub = lane / kExLanes, sl = lane % kExLanes;
+    const int64_t groups = (int64_t)gridDim.x * (blockDim.x / kExLanes);
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kExLanes; i < n_local; i += groups) {
+        const int32_t v = ring_ids[i];
+        int32_t s = 0, e = 0;
+        if (v >= 0 && v < n) {
+            s = row_ptr[v];
+            e = row_ptr[v + 1];
+        }
+        int64_t out = out_row_ptr[i];
+        // which distance classes occur in this row (bit d), so that empty classes cost no pass
+        uint32_t classes = 0;
+        for (int32_t p = s; p < e; p += kExLanes) {
+            if (p + sl < e) {
+                const int32_t u = col_idx[p + sl];
+                if (new_id[u] >= 0) classes |= 1u << dist[u];
+            }
+        }
+#pragma unroll
+        for (int d = 1; d < kExLanes; d <<= 1) classes |= __shfl_xor(classes, d, kWave);
+        for (int d = 0; d <= L; ++d) {
+            if (!((classes >> d) & 1u)) continue;  // uniform over the group
+            for (int32_t p = s; p < e; p += kExLanes) {
+                int32_t id = -1;
+                if (p + sl < e) {
+                    const int32_t u = col_idx[p + sl];
+                    if (dist[u] == d) id = new_id[u];
+                }
+                const bool keep = id >= 0;
+                const uint64_t kept = (__ballot(keep) >> (sub * kExLanes)) & 0xffffull;
+                const int64_t q = out + __popcll(kept & ((1ull << sl) - 1ull));
+                if (keep && q < capacity) out_col_idx[q] = id;
+                out += __popcll(kept);
+            }
+        }
+    }
+}
+
+// dst[i, 0:row_bytes) = src[ids[i], 0:row_bytes): 16 lanes per row, 16 bytes per lane and step
+__global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ src, int64_t src_stride, const int32_t* __restrict__ ids,
+                                                           int32_t n, int32_t n_src, int64_t row_bytes, char* __restrict__ dst,
+                                                           int64_t dst_stride, int vec) {
+    const int sl = (int)(threadIdx.x % 16);
+    const int64_t groups = (int64_t)gridDim.x * (blockDim.x / 16);
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 16; i < n; i += groups) {
+        const int32_t v = ids[i];
+        if (v < 0 || v >= n_src) continue;
+        const char* s = src + (int64_t)v * src_stride;
+        char* d = dst + i * dst_stride;
+        if (vec) {
+            for (int64_t b = (int64_t)sl * 16; b < row_bytes; b += 256) *(uint4*)(d + b) = *(const uint4*)(s + b);
+        } else {
+            for (int64_t b = (int64_t)sl * 2; b < row_bytes; b += 32) *(uint16_t*)(d + b) = *(const uint16_t*)(s + b);
+        }
+    }
+}
+
+}  // namespace gnnhot
+
+using namespace gnnhot;
+
+extern "C" int32_t gnn_extract_partition(const gnn_csr* g, const int32_t* ring_ids, int32_t n_local, const int32_t* dist, int32_t L,
+                                         int32_t* new_id, int32_t* out_row_ptr, int32_t* out_col_idx, int64_t out_capacity,
+                                         int64_t* out_nnz, int64_t* out_nnz_host, void* ws, size_t* ws_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_csr(g, "g"));
+    GNN_REQUIRE(g->n_rows == g->n_cols, GNN_ERR_SHAPE, "g must be square (%d x %d)", g->n_rows, g->n_cols);
+    GNN_REQUIRE(n_local >= 0 && n_local <= g->n_rows, GNN_ERR_INVALID_ARG, "n_local %d outside [0, %d]", n_local, g->n_rows);
+    GNN_REQUIRE(L >= 1 && L <= 30, GNN_ERR_INVALID_ARG, "L = %d outside [1, 30]", L);
+    WsCarver carve(ws);
+    int32_t* counts = carve.take<int32_t>((size_t)n_local + 1);
+    int32_t* sums = carve.take<int32_t>((size_t)offsets_scan_blocks(n_local) + 1);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+    GNN_REQUIRE(new_id != nullptr && out_row_ptr != nullptr, GNN_ERR_INVALID_ARG, "new_id / out_row_ptr is NULL");
+    GNN_REQUIRE(n_local == 0 || (ring_ids != nullptr && dist != nullptr), GNN_ERR_INVALID_ARG, "ring_ids / dist is NULL");
+    const int group_grid = grid_for((int64_t)n_local * kExLanes, 256, 1 << 20);
+
+    if (out_col_idx == nullptr) {  // count pass
+        GNN_REQUIRE(out_nnz != nullptr, GNN_ERR_INVALID_ARG, "out_nnz is NULL");
+        if (g->n_rows > 0) {
+            fill_kernel<int32_t><<<grid_for(g->n_rows, 256, 1 << 16), 256, 0, stream>>>(new_id, g->n_rows, -1);
+            GNN_LAUNCH_CHECK("fill_kernel");
+        }
+        if (n_local > 0) {
+            ex_number_kernel<<<grid_for(n_local, 256), 256, 0, stream>>>(ring_ids, n_local, g->n_rows, new_id);
+            GNN_LAUNCH_CHECK("ex_number_kernel");
+            ex_count_kernel<<<group_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, n_local, g->n_rows, new_id, counts);
+            GNN_LAUNCH_CHECK("ex_count_kernel");
+        }
+        GNN_CHECK(counts_to_offsets(counts, n_local, sums, out_row_ptr, out_nnz, stream));
+        if (out_nnz_host != nullptr) {
+            GNN_HIP(hipMemcpyAsync(out_nnz_host, out_nnz, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+            GNN_HIP(hipStreamSynchronize(stream));
+        }
+        return GNN_OK;
+    }
+    GNN_REQUIRE(out_capacity >= 0, GNN_ERR_INVALID_ARG, "out_capacity < 0");
+    if (n_local > 0) {
+        ex_fill_kernel<<<group_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, n_local, g->n_rows, new_id, dist, L,
+                                                       out_row_ptr, out_col_idx, out_capacity);
+        GNN_LAUNCH_CHECK("ex_fill_kernel");
+    }
+    return GNN_OK;
+}
+
+extern "C" int32_t gnn_gather_rows(const void* src, int64_t ld_src, int32_t n_src, const int32_t* ids, int32_t n, int32_t F,
+                                   int32_t dtype, void* dst, int64_t ld_dst, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_REQUIRE(dtype == GNN_F32 || dtype == GNN_BF16, GNN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    GNN_REQUIRE(n >= 0 && F >= 0 && n_src >= 0, GNN_ERR_INVALID_ARG, "negative size");
+    GNN_REQUIRE(ld_src >= F && ld_dst >= F, GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
+    if (n == 0 || F == 0) return GNN_OK;
+    GNN_REQUIRE(src != nullptr && dst != nullptr && ids != nullptr, GNN_ERR_INVALID_ARG, "src / dst / ids is NULL");
+    const int64_t es = dtype == GNN_F32 ? 4 : 2;
+    const int64_t row_bytes = (int64_t)F * es;
+    const int vec = ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0) && (ld_src * es) % 16 == 0 && (ld_dst * es) % 16 == 0 &&
+                    row_bytes % 16 == 0;
+    gather_rows_kernel<<<grid_for((int64_t)n * 16, 256, 1 << 20), 256, 0, stream>>>((const char*)src, ld_src * es, ids, n, n_src, row_bytes,
+                                                                                 (char*)dst, ld_dst * es, vec);
+    GNN_LAUNCH_CHECK("gather_rows_kernel");
+    return GNN_OK;
+}

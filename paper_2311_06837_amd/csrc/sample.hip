@@ -90,45 +90,6 @@ __global__ __launch_bounds__(256) void sb_count_kernel(const int32_t* __restrict
     if (sl == 0 && i < n_targets) counts[i] = n_in + (n_ext < fanout ? n_ext : fanout);
 }
 
-constexpr int kScanBlock = 1024;  // counts per block in the offset scan (256 threads x 4)
-
-__global__ __launch_bounds__(256) void sb_block_sums_kernel(const int32_t* __restrict__ counts, int32_t n, int32_t* __restrict__ sums) {
-    __shared__ int s_part[4];
-    const int64_t base = (int64_t)blockIdx.x * kScanBlock + threadIdx.x * 4;
-    int c = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-        if (base + k < n) c += counts[base + k];
-    int total;
-    block_exclusive_scan<256>(c, s_part, &total);
-    if (threadIdx.x == 0) sums[blockIdx.x] = total;
-}
-
-__global__ __launch_bounds__(1024) void sb_scan_sums_kernel(int32_t* __restrict__ sums, int32_t n_blocks, int64_t* __restrict__ out_nnz) {
-    __shared__ int s_part[16];
-    const int64_t total = single_block_exclusive_scan(sums, n_blocks, s_part);
-    if (threadIdx.x == 0) *out_nnz = total;
-}
-
-__global__ __launch_bounds__(256) void sb_offsets_kernel(const int32_t* __restrict__ counts, int32_t n, const int32_t* __restrict__ sums,
-                                                         int32_t n_blocks, int32_t* __restrict__ out_row_ptr) {
-    __shared__ int s_part[4];
-    const int64_t base = (int64_t)blockIdx.x * kScanBlock + threadIdx.x * 4;
-    int c[4], tot = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        c[k] = base + k < n ? counts[base + k] : 0;
-        tot += c[k];
-    }
-    int total;
-    int run = block_exclusive_scan<256>(tot, s_part, &total) + sums[blockIdx.x];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        if (base + k < n) out_row_ptr[base + k] = run;
-        run += c[k];
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) out_row_ptr[n] = sums[n_blocks];
-}
 
 __global__ __launch_bounds__(256) void sb_fill_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                       int32_t n, const uint32_t* __restrict__ tbits,
@@ -297,7 +258,7 @@ extern "C" int32_t gnn_sample_boundary(const gnn_csr* g, const uint32_t* target_
     GNN_REQUIRE(fanout >= 0, GNN_ERR_INVALID_ARG, "fanout < 0");
     GNN_REQUIRE(hops == 1, GNN_ERR_UNSUPPORTED, "only hops = 1 is implemented (got %d)", hops);
     GNN_REQUIRE(n_targets >= 0, GNN_ERR_INVALID_ARG, "n_targets < 0");
-    const int32_t n_blocks = n_targets > 0 ? (n_targets + kScanBlock - 1) / kScanBlock : 1;
+    const int32_t n_blocks = offsets_scan_blocks(n_targets);
     WsCarver carve(ws);
     int32_t* counts = carve.take<int32_t>((size_t)n_targets + 1);
     int32_t* sums = carve.take<int32_t>((size_t)n_blocks + 1);
@@ -314,13 +275,8 @@ extern "C" int32_t gnn_sample_boundary(const gnn_csr* g, const uint32_t* target_
             sb_count_kernel<<<wave_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, g->n_rows, target_bitmap, targets, n_targets, fanout,
                                                            counts);
             GNN_LAUNCH_CHECK("sb_count_kernel");
-            sb_block_sums_kernel<<<n_blocks, 256, 0, stream>>>(counts, n_targets, sums);
-            GNN_LAUNCH_CHECK("sb_block_sums_kernel");
         }
-        sb_scan_sums_kernel<<<1, 1024, 0, stream>>>(sums, n_targets > 0 ? n_blocks : 0, out_nnz);
-        GNN_LAUNCH_CHECK("sb_scan_sums_kernel");
-        sb_offsets_kernel<<<n_blocks, 256, 0, stream>>>(counts, n_targets, sums, n_targets > 0 ? n_blocks : 0, out_row_ptr);
-        GNN_LAUNCH_CHECK("sb_offsets_kernel");
+        GNN_CHECK(counts_to_offsets(counts, n_targets, sums, out_row_ptr, out_nnz, stream));
         if (out_nnz_host != nullptr) {
             GNN_HIP(hipMemcpyAsync(out_nnz_host, out_nnz, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
             GNN_HIP(hipStreamSynchronize(stream));

@@ -740,11 +740,57 @@ static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
     return GNN_OK;
 }
 
-// Cut points of every listed row at the column-block boundaries j * block_size (rows sorted by column):
-// seg[r][j] = first position of row r whose column is >= j * block_size; seg[r][0] = start, seg[r][n_blocks] = end.
+// Column-block boundaries of a FILTERED call: bounds[j], j = 0 .. n_blocks, split the neighbour-id range so that
+// every block holds the same number of ACTIVE vertices (0 <= dist <= max_dist) - only those are ever gathered, and
+// they need not be spread evenly over the id range (after a (distance, id) renumbering they are a prefix).
+// One workgroup of 1024 threads: per-thread counts over contiguous id chunks, a block scan, then the thread whose
+// chunk contains the j-th quantile walks it to the exact id.
+__global__ __launch_bounds__(1024) void spmm_bounds_kernel(const int32_t* __restrict__ dist, int32_t max_dist, int32_t n_cols,
+                                                            int32_t n_blocks, int32_t* __restrict__ bounds) {
+    __shared__ int s_part[16];
+    const int64_t chunk = ((int64_t)n_cols + 1023) / 1024;
+    const int64_t lo = (int64_t)threadIdx.x * chunk, hi = lo + chunk < n_cols ? lo + chunk : n_cols;
+    int cnt = 0;
+    for (int64_t u = lo; u < hi; ++u) {
+        const int32_t d = dist[u];
+        cnt += d >= 0 && d <= max_dist;
+    }
+    int total;
+    const int before = block_exclusive_scan<1024>(cnt, s_part, &total);
+    if (threadIdx.x == 0) {
+        bounds[0] = 0;
+        bounds[n_blocks] = n_cols;
+    }
+    // boundary j sits before the active vertex of rank ceil(j * total / n_blocks) (ranks from 0)
+    for (int j = 1; j < n_blocks; ++j) {
+        const int64_t want = ((int64_t)j * total + n_blocks - 1) / n_blocks;
+        if (total == 0) {
+            if (threadIdx.x == 0) bounds[j] = (int32_t)((int64_t)j * n_cols / n_blocks);
+        } else if (want >= before && want < (int64_t)before + cnt) {
+            int64_t rank = before;
+            for (int64_t u = lo; u < hi; ++u) {
+                const int32_t d = dist[u];
+                if (d >= 0 && d <= max_dist) {
+                    if (rank == want) {
+                        bounds[j] = (int32_t)u;
+                        break;
+                    }
+                    ++rank;
+                }
+            }
+        } else if (want >= total && threadIdx.x == 0) {
+            bounds[j] = n_cols;
+        }
+    }
+}
+
+// Cut points of every listed row at the column-block boundaries (rows sorted by column): seg[r][j] = first position
+// of row r whose column is >= the j-th boundary (bounds[j] if given, else j * block_size); seg[r][0] = start,
+// seg[r][n_blocks] = end.
 __global__ __launch_bounds__(256) void spmm_seg_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                         const int32_t* __restrict__ rows, int32_t n_active, int32_t n_blocks,
-                                                        int32_t block_size, int32_t* __restrict__ seg) {
+                                                        int32_t block_size, const int32_t* __restrict__ bounds,
+                                                        int32_t* __restrict__ seg) {
     const int64_t total = (int64_t)n_active * (n_blocks + 1);
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
         const int32_t r = (int32_t)(i / (n_blocks + 1)), j = (int32_t)(i % (n_blocks + 1));
@@ -753,7 +799,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(const int32_t* __restrict
         if (j == n_blocks) {
             lo = hi;
         } else if (j > 0) {
-            const int64_t bound = (int64_t)j * block_size;
+            const int64_t bound = bounds ? (int64_t)bounds[j] : (int64_t)j * block_size;
             while (lo < hi) {  // lower bound
                 const int32_t mid = lo + ((hi - lo) >> 1);
                 if ((int64_t)col_idx[mid] < bound) lo = mid + 1;
@@ -873,6 +919,8 @@ struct BlockedPlan {
     size_t end_bytes = 0, ids_bytes = 0;   // with a filter or a neighbour scale: segment ends and the (compacted) copy of the ids
     size_t w_bytes = 0;                    // with a neighbour scale: the factor of every copied id
     int64_t avg_seg = 0;      // average neighbours of a row inside one column block
+    int32_t n_cols = 0;
+    size_t bounds_bytes = 0;  // with a filter: the column-block boundaries (balanced over the active vertices)
 };
 
 static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, int64_t row_bytes, bool vec_ok, bool filter,
@@ -898,6 +946,8 @@ static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, i
         p.ids_bytes = (size_t)g->nnz * sizeof(int32_t);
     }
     if (scaled) p.w_bytes = (size_t)g->nnz * sizeof(float);
+    if (filter) p.bounds_bytes = ((size_t)n_blocks + 1) * sizeof(int32_t);
+    p.n_cols = g->n_cols;
     return p;
 }
 
@@ -911,8 +961,13 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
     int32_t* seg_end = prepare ? carve.take<int32_t>(p.end_bytes / sizeof(int32_t)) : nullptr;
     int32_t* ids = prepare ? carve.take<int32_t>(p.ids_bytes / sizeof(int32_t)) : nullptr;
     float* edge_w = a.nbr_scale ? carve.take<float>(p.w_bytes / sizeof(float)) : nullptr;
+    int32_t* bounds = FILTER ? carve.take<int32_t>((size_t)p.n_blocks + 1) : nullptr;
+    if (FILTER) {
+        spmm_bounds_kernel<<<1, 1024, 0, stream>>>(a.dist, a.max_dist, p.n_cols, p.n_blocks, bounds);
+        GNN_LAUNCH_CHECK("spmm_bounds_kernel");
+    }
     spmm_seg_kernel<<<grid_for((int64_t)a.n_active * (p.n_blocks + 1), 256, 1 << 16), 256, 0, stream>>>(
-        a.row_ptr, a.col_idx, a.rows, a.n_active, p.n_blocks, p.block_size, seg);
+        a.row_ptr, a.col_idx, a.rows, a.n_active, p.n_blocks, p.block_size, bounds, seg);
     GNN_LAUNCH_CHECK("spmm_seg_kernel");
     SpmmArgs b = a;
     if (prepare) {
@@ -979,6 +1034,7 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
                 measure.take<char>(plan.ids_bytes);
             }
             if (plan.w_bytes) measure.take<char>(plan.w_bytes);
+            if (plan.bounds_bytes) measure.take<char>(plan.bounds_bytes);
         }
         bool query_only = false;
         GNN_CHECK(ws_protocol(ws, ws_bytes, measure.used, &query_only));

@@ -121,16 +121,20 @@ class MaskedGNN:
                              self.dA[l] if need_in else None, self.dH[l - 1] if (need_in and sage) else None, ws=self.ws)
             if need_in:
                 n_prev = self.n_rows_of_layer(l - 1)
+                # The backward gather only keeps the neighbours that were rows of the forward call.  When those are
+                # few (the last layers: R_l is close to T), the column-blocked route would spend more on preparing
+                # every edge than the gathers cost: no workspace -> the one-launch route.
+                ws_bwd = self.ws if 4 * nl >= self.n else None
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=True, ws=self.ws)
+                                          self.rs, self.cs, accumulate=True, ws=ws_bwd)
                     if n_prev > nl:
                         self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
-                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False, ws=self.ws)
+                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False, ws=ws_bwd)
                 else:
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=False, ws=self.ws)
+                                          self.rs, self.cs, accumulate=False, ws=ws_bwd)
         return self.grads
 
     def step(self, labels: torch.Tensor):

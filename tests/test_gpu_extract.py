@@ -1,0 +1,119 @@
+"""GPU parity: gnn_extract_partition and gnn_gather_rows against the oracle (section 6 step 1: the one-hop graph
+of the traversed vertices, renumbered by (distance, id)).  Integer outputs are compared bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import graphgen as gg
+import oracle
+from gpu_util import TOL, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _extract_case(g, T, L, what):
+    import paper_2311_06837_amd as P
+    print(f"extract: {what} n={g.n_rows} nnz={g.nnz} |T|={len(T)} L={L}", flush=True)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    ws = P.Workspace()
+    dist, ring, hop_d, hop = P.gnn_build_active_sets(G, dev(np.asarray(T, dtype=np.int32)), L, ws=ws)
+    n_local = int(hop[-1])
+    local, new_id = P.gnn_extract_partition(G, ring, n_local, dist, L, ws=ws)
+    torch.cuda.synchronize()
+    rp, ci, l2g, off, dl = oracle.extract_partition(g.row_ptr, g.col_idx, T, L)
+    assert n_local == l2g.size and list(hop) == list(off)
+    assert np.array_equal(ring.cpu().numpy()[:n_local], l2g)
+    assert np.array_equal(local.row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(local.col_idx.cpu().numpy(), ci)
+    want_new = np.full(g.n_rows, -1, dtype=np.int32)
+    want_new[l2g] = np.arange(l2g.size, dtype=np.int32)
+    assert np.array_equal(new_id.cpu().numpy(), want_new)
+    assert local.sorted_columns and local.n_rows == n_local and local.nnz == ci.size
+    return local, ring, hop, (rp, ci, l2g, off, dl)
+
+
+@pytest.mark.parametrize("L", [1, 2, 3])
+def test_power_law_graph_with_hubs(L):
+    g = gg.chung_lu(30000, 40.0, 2.1, 51)                     # hub rows of > 1000 entries
+    T = np.sort(np.random.default_rng(L).choice(30000, 300, replace=False))
+    _extract_case(g, T, L, "chung-lu")
+
+
+def test_directed_graph_deep_and_unreached_vertices():
+    g = gg.random_directed(20000, 1.5, 52)                    # many empty rows, most vertices never reached
+    T = np.sort(np.random.default_rng(2).choice(20000, 50, replace=False))
+    local, ring, hop, (rp, ci, l2g, off, dl) = _extract_case(g, T, 8, "directed")
+    assert l2g.size < 20000
+
+
+def test_whole_graph_is_traversed_and_degenerate_sizes():
+    import paper_2311_06837_amd as P
+    g = gg.erdos_renyi(5000, 12.0, 53)
+    _extract_case(g, np.arange(0, 5000, 7), 4, "everything reached")
+    _extract_case(g, np.array([17]), 1, "one target")
+    # n_local = 0: an empty graph comes back
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    dist = torch.full((5000,), -1, dtype=torch.int32, device="cuda")
+    ring = torch.zeros(1, dtype=torch.int32, device="cuda")
+    local, new_id = P.gnn_extract_partition(G, ring, 0, dist, 2)
+    assert local.n_rows == 0 and local.nnz == 0 and int(local.row_ptr[0]) == 0 and bool((new_id == -1).all())
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("F,ld_src,ld_dst", [(64, 64, 64), (602, 608, 608), (100, 100, 128), (7, 7, 9)])
+def test_gather_rows(dtype, F, ld_src, ld_dst):
+    import paper_2311_06837_amd as P
+    rng = np.random.default_rng(F)
+    n_src, n = 4000, 2501
+    src = torch.randn(n_src, ld_src, device="cuda").to(dtype)
+    ids = rng.integers(0, n_src, size=n).astype(np.int32)
+    dst = torch.full((n, ld_dst), 7.0, dtype=dtype, device="cuda")
+    P.gnn_gather_rows(src, dev(ids), F, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:, :F], src[torch.from_numpy(ids).cuda().long(), :F])
+    if ld_dst > F:
+        assert bool((dst[:, F:] == 7.0).all()), "pad columns were written"
+
+
+@pytest.mark.parametrize("kind,dtype", [("sage", torch.float32), ("gcn", torch.float32), ("sage", torch.bfloat16)])
+def test_training_step_on_the_extracted_graph(kind, dtype):
+    """The whole chain on the GPU - active sets of the unpartitioned graph, extraction, feature gather, one training
+    step with prefix row sets - against the oracle's model on the oracle's extraction."""
+    import paper_2311_06837_amd as P
+    n, L, dims = 20000, 3, [48, 32, 32, 7]
+    g = gg.chung_lu(n, 14.0, 2.1, 61)
+    if kind == "gcn":
+        g = gg.add_self_loops(g)
+    rng = np.random.default_rng(61)
+    T = np.sort(rng.choice(n, 150, replace=False))
+    local, ring, hop, (rp, ci, l2g, off, dl) = _extract_case(g, T, L, f"model {kind}")
+    n_local = l2g.size
+    assert n_local < n
+    params = gg.layer_weights(dims, kind == "sage", 61)
+    H0g = gg.features(n, dims[0], 61)
+    y = gg.labels(len(T), dims[-1], 61)
+
+    bf16 = dtype == torch.bfloat16
+    H0o = oracle.round_bf16(H0g.astype(np.float64)) if bf16 else H0g.astype(np.float64)
+    om = oracle.Model(rp, ci, np.arange(len(T), dtype=np.int32), kind, params, g.degrees()[l2g] if kind == "gcn" else None, bf16=bf16)
+    loss_o = om.forward(H0o[l2g], y)
+    grads_o = om.backward()
+
+    ld0 = P.row_stride(dims[0], dtype)
+    H0d = torch.zeros(n_local, ld0, dtype=dtype, device="cuda")
+    P.gnn_gather_rows(dev(H0g).to(dtype), ring[:n_local], dims[0], H0d)
+    m = P.MaskedGNN(local, local, torch.arange(len(T), dtype=torch.int32, device="cuda"), kind,
+                    [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
+                    global_degree=dev(g.degrees()[l2g].astype(np.int32)) if kind == "gcn" else None)
+    m.set_input(H0d)
+    loss = m.step(dev(y))
+    torch.cuda.synchronize()
+    assert list(m.hop) == list(off)
+    assert torch.equal(m.ring_ids[:n_local].cpu(), torch.arange(n_local, dtype=torch.int32))   # the numbering IS the ring order
+    tol = TOL[dtype] * 2 * L
+    assert abs(loss.item() - loss_o) <= tol * abs(loss_o), (loss.item(), loss_o)
+    for l, gr in enumerate(grads_o):
+        for k, want in gr.items():
+            got = m.grads[l][k].double().cpu().numpy()
+            err = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+            assert err <= tol, (l, k, err)

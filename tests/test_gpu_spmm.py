@@ -220,3 +220,26 @@ def test_blocked_route_falls_back_without_promise_or_density():
     ws2 = P.Workspace()
     _fwd_case(sparse, 128, 128, torch.float32, None, True, 45, ws=ws2)
     assert not _used_blocked_route(ws2)
+
+
+def test_blocked_route_backward_with_prefix_active_sources():
+    """After a (distance, id) renumbering the forward rows are a PREFIX of the id range: every kept neighbour falls
+    into the first stretch of ids.  The route balances its column blocks over the active vertices; results as ever."""
+    import paper_2311_06837_amd as P
+    g = _dense_graph()
+    n, F = g.n_rows, 96
+    rng = np.random.default_rng(77)
+    n_fwd = 9000                                                          # forward rows 0 .. 8999
+    dist = np.where(np.arange(n) < n_fwd, 0, 1).astype(np.int32)
+    dY = as_stored(rng.standard_normal((n, F)), torch.float32)
+    rs = (rng.random(n) + 0.5).astype(np.float32)
+    cs = (rng.random(n) + 0.5).astype(np.float32)
+    GT = P.Graph.from_numpy(g.row_ptr, g.col_idx)                         # symmetric
+    ws = P.Workspace()
+    dX = torch.full((n, F), SENTINEL, device="cuda")
+    P.gnn_masked_spmm_bwd(GT, None, n, dev(dist), 0, dev(dY).float(), dX, F, dev(rs), dev(cs), accumulate=False, ws=ws)
+    torch.cuda.synchronize()
+    assert _used_blocked_route(ws)
+    want = np.zeros((n, F))
+    oracle.spmm_bwd(g.row_ptr, g.col_idx, np.arange(n_fwd, dtype=np.int32), dY, want, F, rs, cs)
+    check(host64(dX), want, torch.float32, "prefix-active backward")
