@@ -192,7 +192,7 @@ def sampled_local_edges(targets, out_row_ptr, out_col_idx):
     targets = np.asarray(targets, dtype=np.int64)
     rows = np.repeat(targets, np.diff(out_row_ptr).astype(np.int64))
     cols = out_col_idx.astype(np.int64)
-    is_t = np.zeros(max(int(rows.max(initial=0)), int(cols.max(initial=0))) + 1, dtype=bool)
+    is_t = np.zeros(max(int(targets.max(initial=0)), int(cols.max(initial=0))) + 1, dtype=bool)
     is_t[targets] = True
     ext = ~is_t[cols]
     l2g = np.union1d(targets, cols)
@@ -218,6 +218,29 @@ def extract_partition(row_ptr, col_idx, targets, L):
     f(C.c_int32(n), _p(row_ptr), _p(col_idx), _p(ring), C.c_int32(n_local), _p(new_id), _p(rp), _p(ci))
     dist_local = np.repeat(np.arange(L + 1, dtype=np.int32), np.diff(off).astype(np.int64))
     return rp, ci[: int(nnz)], ring, off, dist_local
+
+
+def extract_sampled(n, targets, s_row_ptr, s_col_idx):
+    """Section 5.3.1: the one-hop graph of the targets and the outside vertices they kept, renumbered by
+    (distance, id).  targets ascending.  -> (local_row_ptr, local_col_idx, local_to_global, hop_offsets, dist_local)."""
+    targets, s_row_ptr, s_col_idx = _i32(targets), _i32(s_row_ptr), _i32(s_col_idx)
+    nt = targets.shape[0]
+    new_id = np.empty(n, dtype=np.int32)
+    l2g = np.empty(max(n, 1), dtype=np.int32)
+    rp = np.empty(n + 1, dtype=np.int32)
+    n_local = C.c_int32(0)
+    f = lib().orc_extract_sampled
+    f.restype = C.c_int64
+    args = [C.c_int32(n), _p(targets), C.c_int32(nt), _p(s_row_ptr), _p(s_col_idx), _p(new_id), _p(l2g), C.byref(n_local), _p(rp)]
+    nnz = f(*args, None)
+    if nnz < 0:
+        raise ValueError("targets must be ascending, without repeats, inside [0, n)")
+    ci = np.empty(max(int(nnz), 1), dtype=np.int32)
+    f(*args, _p(ci))
+    nl = int(n_local.value)
+    off = np.array([0, nt, nl], dtype=np.int64)
+    dist_local = np.repeat(np.arange(2, dtype=np.int32), np.diff(off))
+    return rp[: nl + 1].copy(), ci[: int(nnz)], l2g[:nl].copy(), off, dist_local
 
 
 def _row_entries(row_ptr, col_idx, rows):

@@ -392,3 +392,65 @@ int64_t orc_extract_partition(int32_t n, const int32_t *row_ptr, const int32_t *
     out_row_ptr[n_local] = (int32_t)pos;
     return pos;
 }
+
+/* ---------------------------------------------------------------------- */
+/* Extraction after boundary sampling (section 5.3.1: "when the traversal   */
+/* is finished, a subgraph is generated from the traversed vertices, and    */
+/* the internal dependencies of the inner vertices remain unsampled").      */
+/* Traversed vertices = the targets (distance 0) and every outside vertex   */
+/* that some target kept (distance 1); local numbering by (distance, id):   */
+/* targets first.  Edges: the kept row of every target, plus the reverse    */
+/* (u, v) of every kept edge (v, u) that leaves the target set, so that the */
+/* local one-hop graph stays symmetric; no edges between two outside        */
+/* vertices.  Local rows list their columns in ascending local id.          */
+/*   targets        ascending, no repeats (else -1 is returned)             */
+/*   s_row_ptr/s_col_idx  kept rows as orc_sample_boundary writes them      */
+/*   new_id         scratch [n]                                             */
+/*   local_to_global  out, room for n                                       */
+/*   out_row_ptr    out, room for n + 1;  out_col_idx NULL: only count      */
+/* Returns the number of local edges; *n_local_out = local vertices.        */
+/* ---------------------------------------------------------------------- */
+int64_t orc_extract_sampled(int32_t n, const int32_t *targets, int32_t n_targets,
+                            const int32_t *s_row_ptr, const int32_t *s_col_idx,
+                            int32_t *new_id, int32_t *local_to_global, int32_t *n_local_out,
+                            int32_t *out_row_ptr, int32_t *out_col_idx)
+{
+    for (int32_t v = 0; v < n; ++v) new_id[v] = -1;
+    for (int32_t i = 0; i < n_targets; ++i) {
+        if (targets[i] < 0 || targets[i] >= n) return -1;
+        if (i > 0 && targets[i] <= targets[i - 1]) return -1;
+        new_id[targets[i]] = i;
+        local_to_global[i] = targets[i];
+    }
+    /* outside vertices that were kept by somebody, in ascending id */
+    for (int32_t e = 0; e < s_row_ptr[n_targets]; ++e)
+        if (new_id[s_col_idx[e]] == -1) new_id[s_col_idx[e]] = -2;
+    int32_t n_local = n_targets;
+    for (int32_t v = 0; v < n; ++v)
+        if (new_id[v] == -2) { new_id[v] = n_local; local_to_global[n_local] = v; ++n_local; }
+    *n_local_out = n_local;
+    /* row lengths: a target keeps its sampled row; an outside vertex gets one entry per target that kept it */
+    for (int32_t i = 0; i <= n_local; ++i) out_row_ptr[i] = 0;
+    for (int32_t i = 0; i < n_targets; ++i) {
+        out_row_ptr[i + 1] += s_row_ptr[i + 1] - s_row_ptr[i];
+        for (int32_t e = s_row_ptr[i]; e < s_row_ptr[i + 1]; ++e) {
+            int32_t u = new_id[s_col_idx[e]];
+            if (u >= n_targets) out_row_ptr[u + 1] += 1;
+        }
+    }
+    for (int32_t i = 0; i < n_local; ++i) out_row_ptr[i + 1] += out_row_ptr[i];
+    const int64_t nnz = out_row_ptr[n_local];
+    if (!out_col_idx) return nnz;
+    int32_t *cursor = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_local + 1));
+    for (int32_t i = 0; i < n_local; ++i) cursor[i] = out_row_ptr[i];
+    for (int32_t i = 0; i < n_targets; ++i) {              /* ascending i: reverse rows come out ascending */
+        for (int32_t e = s_row_ptr[i]; e < s_row_ptr[i + 1]; ++e) {
+            int32_t u = new_id[s_col_idx[e]];
+            out_col_idx[cursor[i]++] = u;
+            if (u >= n_targets) out_col_idx[cursor[u]++] = i;
+        }
+        qsort(out_col_idx + out_row_ptr[i], (size_t)(out_row_ptr[i + 1] - out_row_ptr[i]), sizeof(int32_t), orc_i32_cmp);
+    }
+    free(cursor);
+    return nnz;
+}

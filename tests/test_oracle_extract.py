@@ -103,3 +103,62 @@ def test_training_on_the_extracted_graph_equals_the_unpartitioned_result(kind):
     for a, b in zip(full.backward(), m.backward()):
         for k in a:
             assert np.allclose(a[k], b[k], rtol=1e-10, atol=1e-13), k
+
+
+# ---- extraction after boundary sampling (section 5.3.1) ------------------------------------------------------
+
+def _sampled(g, T, fanout, seed):
+    is_t = np.zeros(g.n_rows, dtype=np.uint8)
+    is_t[T] = 1
+    return oracle.sample_boundary(g.row_ptr, g.col_idx, is_t, T, fanout, seed)
+
+
+def test_sampled_extraction_closed_form():
+    """Path 0-1-2-3-4-5 plus the chord 2-5, targets {2, 3}, everything kept (fanout 9): outside vertices 1, 4, 5;
+    local order 2 3 | 1 4 5 -> ids 0 1 | 2 3 4; kept edges 2-3, 2-1, 2-5, 3-4 and their reverses; no 4-5 edge."""
+    g = _sym(6, [(0, 1), (1, 2), (2, 3), (3, 4), (4, 5), (2, 5)])
+    T = np.array([2, 3])
+    srp, sci = _sampled(g, T, 9, 1)
+    rp, ci, l2g, off, dl = oracle.extract_sampled(6, T, srp, sci)
+    assert list(l2g) == [2, 3, 1, 4, 5] and list(off) == [0, 2, 5] and list(dl) == [0, 0, 1, 1, 1]
+    rows = [list(ci[rp[i]:rp[i + 1]]) for i in range(5)]
+    assert rows == [[1, 2, 4], [0, 3], [0], [1], [0]]
+
+
+@pytest.mark.parametrize("fanout", [0, 2, 5, 1000])
+def test_sampled_extraction_equals_edge_list_construction(fanout):
+    """Against the edge-list construction used since the first sampler tests (oracle.sampled_local_edges + scipy
+    assembly in graphgen.partition_from_edges, ascending-id numbering), compared in global ids."""
+    n = 4000
+    g = gg.chung_lu(n, 12.0, 2.1, 71)
+    T = np.sort(np.random.default_rng(fanout).choice(n, 400, replace=False)).astype(np.int64)
+    srp, sci = _sampled(g, T, fanout, 99)
+    rp, ci, l2g, off, dl = oracle.extract_sampled(n, T, srp, sci)
+    l2g_ref, er, ec = oracle.sampled_local_edges(T, srp, sci)
+    assert np.array_equal(np.sort(l2g), l2g_ref) and np.array_equal(l2g[: len(T)], T)
+    rows = np.repeat(np.arange(rp.size - 1), np.diff(rp))
+    mine = set(zip(l2g[rows].tolist(), l2g[ci].tolist()))
+    assert len(mine) == ci.size and mine == set(zip(er.tolist(), ec.tolist()))
+    part = gg.partition_from_edges(n, l2g_ref, er, ec, T, g.degrees())
+    assert part.graph.nnz == ci.size
+    # structure: symmetric, target rows = kept rows, outside rows only reach targets, columns ascending
+    assert mine == {(b, a) for a, b in mine}
+    assert np.array_equal(np.diff(rp)[: len(T)], np.diff(srp))
+    assert np.all(ci[rp[len(T)]:] < len(T))
+    for i in range(rp.size - 1):
+        assert np.all(np.diff(ci[rp[i]:rp[i + 1]]) > 0)
+    if fanout == 0:
+        assert l2g.size == len(T)                                          # nothing outside survives
+    if fanout == 1000:                                                     # nothing is dropped: the one-hop halo, minus outside-outside edges
+        rp1, ci1, l2g1, off1, _ = oracle.extract_partition(g.row_ptr, g.col_idx, T, 1)
+        assert np.array_equal(l2g1, l2g)
+        r1 = np.repeat(np.arange(rp1.size - 1), np.diff(rp1))
+        keep = (r1 < len(T)) | (ci1 < len(T))
+        assert np.array_equal(r1[keep], rows) and np.array_equal(ci1[keep], ci)
+
+
+def test_sampled_extraction_rejects_unsorted_targets():
+    g = _sym(4, [(0, 1), (1, 2), (2, 3)])
+    srp, sci = _sampled(g, np.array([1, 2]), 3, 0)
+    with pytest.raises(ValueError):
+        oracle.extract_sampled(4, np.array([2, 1]), srp, sci)
