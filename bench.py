@@ -57,30 +57,30 @@ def build_partition(name, scale):
 
 
 def sampled_partition_cfg4(w):
-    """cfg4: boundary sampling on the GPU (step a0), then host-side extraction of the local one-hop graph."""
+    """configs[4], steps a0 and a-1 on the GPU: boundary sampling, then extraction of the local one-hop graph with
+    (distance, id) numbering.  Returns a host-side Partition (for the CPU baseline), the device graph and the two times."""
     import torch
     import graphgen as gg
     import paper_2311_06837_amd as P
-    g, T = w.global_graph, w.targets_global.astype(np.int32)
+    g, T = w.global_graph, w.targets_global.astype(np.int32)          # targets ascending
     G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
     Td = torch.from_numpy(T).cuda()
+    ws = P.Workspace()
     bits = P.gnn_make_bitmap(Td, g.n_rows)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    rp, ci = P.gnn_sample_boundary(G, bits, Td, w.fanout, w.sample_seed)
-    torch.cuda.synchronize()
-    t_sample = time.perf_counter() - t0
-    rp, ci = rp.cpu().numpy(), ci.cpu().numpy()
-    # local vertices = targets + kept outside neighbours; edges = kept rows + reverse of the outside ones
-    rows = np.repeat(T.astype(np.int64), np.diff(rp).astype(np.int64))
-    cols = ci.astype(np.int64)
-    is_t = np.zeros(g.n_rows, dtype=bool)
-    is_t[T] = True
-    ext = ~is_t[cols]
-    l2g = np.union1d(T.astype(np.int64), cols)
-    part = gg.partition_from_edges(g.n_rows, l2g, np.concatenate([rows, cols[ext]]), np.concatenate([cols, rows[ext]]),
-                                   w.targets_global, g.degrees())
-    return part, t_sample, int(ci.size)
+    for _ in range(2):                                                 # first pass warms the allocator, second is timed
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rp, ci = P.gnn_sample_boundary(G, bits, Td, w.fanout, w.sample_seed, ws=ws)
+        torch.cuda.synchronize()
+        t_sample = time.perf_counter() - t0
+        local, l2g, hop = P.gnn_extract_sampled_partition(G, Td, rp, ci, ws=ws)     # symmetric graph: gT = g
+        torch.cuda.synchronize()
+        t_extract = time.perf_counter() - t0 - t_sample
+    kept = int(ci.numel())
+    l2g_h = l2g.cpu().numpy().astype(np.int64)
+    lg = gg.CSR(local.n_rows, local.n_rows, local.row_ptr.cpu().numpy(), local.col_idx.cpu().numpy())
+    part = gg.Partition(lg, lg, l2g_h, np.arange(T.size, dtype=np.int32), g.degrees()[l2g_h].astype(np.int32))
+    return part, local, t_sample, t_extract, kept
 
 
 def main():
@@ -109,9 +109,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = build_partition(args.workload, args.scale)
-    t_sample, kept = None, None
+    t_sample, kept, t_extract, sampled_graph = None, None, None, None
     if w.partition is None:
-        part, t_sample, kept = sampled_partition_cfg4(w)
+        part, sampled_graph, t_sample, t_extract, kept = sampled_partition_cfg4(w)
+        log(f"[bench] GPU sampling {t_sample * 1e3:.2f} ms, GPU extraction of the sampled partition {t_extract * 1e3:.2f} ms")
     else:
         part = w.partition
     dtype = torch.float32 if w.dtype == "f32" else torch.bfloat16
@@ -128,7 +129,7 @@ def main():
     # Step (a-1) of the path, outside the timed step like the sampling: the partition's one-hop graph extracted on
     # the GPU from the unpartitioned graph, vertices renumbered by (distance, id).  Timed always (full-halo
     # workloads); used for the run with --extract-on-gpu.
-    t_extract, gpu_part = None, None
+    gpu_part = None
     if w.partition is not None:
         Gg = P.Graph.from_numpy(w.global_graph.row_ptr, w.global_graph.col_idx)
         Tg = dev(w.targets_global.astype(np.int32))
@@ -162,7 +163,7 @@ def main():
         P.gnn_gather_rows(dev(H0).to(dtype), pos, w.dims[0], H0d)
         model.set_input(H0d)
     else:
-        G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
+        G = sampled_graph if sampled_graph is not None else P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
         GT = G if part.graph_t is part.graph else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
         model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=dtype,
                             global_degree=dev(part.global_degree) if w.model == "gcn" else None)
@@ -278,7 +279,8 @@ def main():
         "active_sets_ms": call_ms.get("active_sets"),
         "sampling_ms": None if t_sample is None else t_sample * 1e3, "sampled_edges": kept,
         "extract_ms": None if t_extract is None else t_extract * 1e3,
-        "partition_built_on": "gpu ((distance, id) numbering)" if gpu_part is not None else "host (ascending-id numbering)",
+        "partition_built_on": "gpu ((distance, id) numbering)" if (gpu_part is not None or sampled_graph is not None)
+                              else "host (ascending-id numbering)",
         "aggregated_edges_per_step": total_edges,
         "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,
         "call_ms": {k: round(v, 4) for k, v in call_ms.items()},

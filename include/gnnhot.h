@@ -239,6 +239,33 @@ int32_t gnn_extract_partition(const gnn_csr *g, const int32_t *ring_ids, int32_t
                               void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * out_row_ptr[0 .. n] over the full id range from a row list: row ids[i] gets the length
+ * list_row_ptr[i+1] - list_row_ptr[i] of listed row i, every other row is empty.  With ids ascending,
+ * (out_row_ptr, the list's col_idx) is the row list as an n-row CSR - this is how the kept rows of
+ * gnn_sample_boundary become the graph `gs` below.  Ids outside [0, n) are ignored.
+ */
+int32_t gnn_expand_row_ptr(int32_t n, const int32_t *ids, int32_t n_ids, const int32_t *list_row_ptr,
+                           int32_t *out_row_ptr, void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Extraction after boundary sampling (section 5.3.1: when the traversal is finished a subgraph is
+ * generated from the traversed vertices; the dependencies between inner vertices stay whole).
+ *   gs   the kept rows as an n-row CSR (rows of non-targets empty, columns ascending)
+ *   gT   the transposed unpartitioned graph (the same arrays as the graph itself if it is symmetric)
+ *   ring_ids, dist   gnn_build_active_sets(gs, targets, L = 1): targets (distance 0), then every
+ *        outside vertex some target kept (distance 1), each group ascending
+ * Local vertices = ring order (targets first).  Local rows: a target keeps its kept row; an outside
+ * vertex u gets the reverse of the kept edges that reach it, { v target : u in kept row of v } (so the
+ * local graph is symmetric); there are no edges between two outside vertices.  Rows ascending in
+ * local id.  new_id and the two passes are as for gnn_extract_partition.  Bit-exact.
+ */
+int32_t gnn_extract_sampled_partition(const gnn_csr *gT, const gnn_csr *gs, const int32_t *ring_ids,
+                                      int32_t n_local, const int32_t *dist, int32_t *new_id,
+                                      int32_t *out_row_ptr, int32_t *out_col_idx, int64_t out_capacity,
+                                      int64_t *out_nnz, int64_t *out_nnz_host,
+                                      void *ws, size_t *ws_bytes, void *stream);
+
+/*
  * Row gather (the features of the extracted vertices, in local order):
  *     dst[i, 0:F] = src[ids[i], 0:F]    for i in [0, n);  rows with ids[i] outside [0, n_src) are skipped
  * src [n_src, ld_src], dst [n, ld_dst] of `dtype`; columns F..ld_dst of dst are not written.

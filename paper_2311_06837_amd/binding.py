@@ -23,7 +23,8 @@ STATUS = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_SHAPE", 3: "GNN_ERR
 
 EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_scales", "gnn_masked_spmm_fwd",
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
-           "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows"]
+           "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
+           "gnn_extract_sampled_partition"]
 
 
 class GnnError(RuntimeError):
@@ -302,6 +303,38 @@ def gnn_extract_partition(g: Graph, ring_ids: torch.Tensor, n_local: int, dist: 
     out_ci = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
     _with_ws(lib().gnn_extract_partition, common + (_ptr(out_ci), C.c_int64(nnz), _ptr(nnz_dev), None), (_stream(),), ws)
     return Graph(out_rp, out_ci[:nnz], n_cols=n_local, sorted_columns=g.sorted_columns), new_id[: g.n_rows]
+
+
+def gnn_expand_row_ptr(n: int, ids: torch.Tensor, list_row_ptr: torch.Tensor, ws: Workspace | None = None) -> torch.Tensor:
+    """-> int32[n + 1]: row ids[i] has the length of listed row i, all other rows are empty."""
+    _i32(ids, "ids"), _i32(list_row_ptr, "list_row_ptr")
+    assert list_row_ptr.numel() == ids.numel() + 1
+    out = torch.empty(n + 1, dtype=torch.int32, device=ids.device)
+    _with_ws(lib().gnn_expand_row_ptr, (C.c_int32(n), _ptr(ids) if ids.numel() else None, C.c_int32(ids.numel()), _ptr(list_row_ptr),
+                                        _ptr(out)), (_stream(),), ws)
+    return out
+
+
+def gnn_extract_sampled_partition(gT: Graph, targets: torch.Tensor, kept_row_ptr: torch.Tensor, kept_col_idx: torch.Tensor,
+                                  ws: Workspace | None = None):
+    """The whole chain after gnn_sample_boundary (targets ASCENDING, as they were given to the sampler): kept rows as a
+    CSR over the full id range, its two rings, extraction.  -> (local Graph, local_to_global int32[n_local], hop)."""
+    n = gT.n_rows
+    gs_rp = gnn_expand_row_ptr(n, targets, kept_row_ptr, ws=ws)
+    gs = Graph(gs_rp, kept_col_idx.contiguous(), n_cols=n, sorted_columns=True)
+    dist, ring, _, hop = gnn_build_active_sets(gs, targets, 1, ws=ws)
+    n_local = int(hop[-1])
+    dev = gT.row_ptr.device
+    new_id = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    out_rp = torch.empty(n_local + 1, dtype=torch.int32, device=dev)
+    nnz_dev = torch.empty(1, dtype=torch.int64, device=dev)
+    nnz_host = C.c_int64(0)
+    common = (C.byref(gT.c), C.byref(gs.c), _ptr(ring) if n_local else None, C.c_int32(n_local), _ptr(dist), _ptr(new_id), _ptr(out_rp))
+    _with_ws(lib().gnn_extract_sampled_partition, common + (None, C.c_int64(0), _ptr(nnz_dev), C.byref(nnz_host)), (_stream(),), ws)
+    nnz = int(nnz_host.value)
+    out_ci = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    _with_ws(lib().gnn_extract_sampled_partition, common + (_ptr(out_ci), C.c_int64(nnz), _ptr(nnz_dev), None), (_stream(),), ws)
+    return Graph(out_rp, out_ci[:nnz], n_cols=n_local, sorted_columns=True), ring[:n_local], hop
 
 
 def gnn_gather_rows(src: torch.Tensor, ids: torch.Tensor, F: int, dst: torch.Tensor):

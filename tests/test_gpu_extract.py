@@ -117,3 +117,82 @@ def test_training_step_on_the_extracted_graph(kind, dtype):
             got = m.grads[l][k].double().cpu().numpy()
             err = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
             assert err <= tol, (l, k, err)
+
+
+# ---- extraction after boundary sampling ----------------------------------------------------------------------
+
+def _sampled_case(g, T, fanout, seed, what):
+    import paper_2311_06837_amd as P
+    print(f"extract sampled: {what} n={g.n_rows} nnz={g.nnz} |T|={len(T)} fanout={fanout}", flush=True)
+    n = g.n_rows
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    Td = dev(np.asarray(T, dtype=np.int32))
+    bits = P.gnn_make_bitmap(Td, n)
+    ws = P.Workspace()
+    srp, sci = P.gnn_sample_boundary(G, bits, Td, fanout, seed, ws=ws)
+    local, l2g_d, hop = P.gnn_extract_sampled_partition(G, Td, srp, sci, ws=ws)      # symmetric graph: gT = g
+    torch.cuda.synchronize()
+    is_t = np.zeros(n, dtype=np.uint8)
+    is_t[T] = 1
+    osrp, osci = oracle.sample_boundary(g.row_ptr, g.col_idx, is_t, T, fanout, seed)
+    rp, ci, l2g, off, dl = oracle.extract_sampled(n, T, osrp, osci)
+    assert list(hop) == list(off)
+    assert np.array_equal(l2g_d.cpu().numpy(), l2g)
+    assert np.array_equal(local.row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(local.col_idx.cpu().numpy(), ci)
+    return local, l2g_d, (rp, ci, l2g, off, dl)
+
+
+@pytest.mark.parametrize("fanout", [0, 3, 5, 100000])
+def test_sampled_extraction_power_law(fanout):
+    g = gg.chung_lu(40000, 15.0, 2.1, 81)
+    pid = gg.bfs_partition(g, 8, 81)
+    T = np.flatnonzero(pid == 0)
+    _sampled_case(g, T, fanout, 0x5EED, "one of 8 parts")
+
+
+def test_sampled_extraction_hub_outside_vertex_and_tiny_sets():
+    n = 30000
+    base = gg.erdos_renyi(n, 6.0, 82)
+    rng = np.random.default_rng(82)
+    T = np.sort(rng.choice(np.arange(1, n), 6000, replace=False))
+    r = np.repeat(np.arange(n, dtype=np.int64), np.diff(base.row_ptr))
+    c = base.col_idx.astype(np.int64)
+    z = np.zeros(T.size, dtype=np.int64)
+    g = gg.csr_from_edges(n, n, np.concatenate([r, z, T]), np.concatenate([c, T, z]))   # vertex 0 (outside) adjacent to every target
+    local, l2g, (rp, ci, l2g_o, off, dl) = _sampled_case(g, T, 4, 7, "outside hub")
+    k = int(np.searchsorted(l2g_o[len(T):], 0)) + len(T)
+    assert l2g_o[k] == 0 and rp[k + 1] - rp[k] > 1024                     # a long reverse row
+    _sampled_case(g, np.array([5]), 2, 1, "one target")
+
+
+def test_training_step_after_sampling_and_extraction():
+    """configs[4]'s chain at small size, all on the GPU: sample, extract, gather features, one bf16 training step."""
+    import paper_2311_06837_amd as P
+    n, dims, dtype = 40000, [64, 48, 48, 5], torch.bfloat16
+    g = gg.chung_lu(n, 15.0, 2.1, 83)
+    T = np.flatnonzero(gg.bfs_partition(g, 8, 83) == 0)
+    local, l2g_d, (rp, ci, l2g, off, dl) = _sampled_case(g, T, 5, 0xABC, "model")
+    n_local, L = l2g.size, 3
+    params = gg.layer_weights(dims, True, 83)
+    H0g = gg.features(n, dims[0], 83)
+    y = gg.labels(len(T), dims[-1], 83)
+    H0o = oracle.round_bf16(H0g.astype(np.float64))
+    om = oracle.Model(rp, ci, np.arange(len(T), dtype=np.int32), "sage", params, bf16=True)
+    loss_o = om.forward(H0o[l2g], y)
+    grads_o = om.backward()
+    H0d = torch.zeros(n_local, P.row_stride(dims[0], dtype), dtype=dtype, device="cuda")
+    P.gnn_gather_rows(dev(H0g).to(dtype), l2g_d, dims[0], H0d)
+    m = P.MaskedGNN(local, local, torch.arange(len(T), dtype=torch.int32, device="cuda"), "sage",
+                    [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype)
+    m.set_input(H0d)
+    loss = m.step(dev(y))
+    torch.cuda.synchronize()
+    assert [int(x) for x in m.hop] == [0, len(T), n_local, n_local, n_local]      # dist is 0 or 1: every later ring is empty
+    tol = TOL[dtype] * 2 * L
+    assert abs(loss.item() - loss_o) <= tol * abs(loss_o), (loss.item(), loss_o)
+    for l, gr in enumerate(grads_o):
+        for k, want in gr.items():
+            got = m.grads[l][k].double().cpu().numpy()
+            err = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+            assert err <= tol, (l, k, err)

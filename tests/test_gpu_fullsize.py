@@ -214,8 +214,8 @@ def test_cfg3_full_size_bf16(cfg3):
 
 
 def test_cfg4_sampling_and_active_sets_full_size():
-    """configs[4]: boundary sampling over the 10M-vertex graph, bit-exact in full; then the active sets of the
-    sampled partition."""
+    """configs[4]: boundary sampling over the 10M-vertex graph and the extraction of the sampled partition, both
+    bit-exact in full; then the active sets of the sampled partition."""
     import paper_2311_06837_amd as P
     print("generating cfg4 at full size", flush=True)
     w = gg.make_workload("cfg4")
@@ -230,7 +230,15 @@ def test_cfg4_sampling_and_active_sets_full_size():
     orp, oci = oracle.sample_boundary(g.row_ptr, g.col_idx, is_t, T, w.fanout, w.sample_seed)
     assert np.array_equal(rp.cpu().numpy(), orp)
     assert np.array_equal(ci.cpu().numpy(), oci)
-    del G
+    print("cfg4: extraction of the sampled partition", flush=True)
+    local, l2g_d, hop = P.gnn_extract_sampled_partition(G, Td, rp, ci)
+    torch.cuda.synchronize()
+    xrp, xci, xl2g, xoff, _ = oracle.extract_sampled(g.n_rows, T, orp, oci)
+    assert [int(x) for x in hop] == [int(x) for x in xoff]
+    assert np.array_equal(l2g_d.cpu().numpy(), xl2g)
+    assert np.array_equal(local.row_ptr.cpu().numpy(), xrp)
+    assert np.array_equal(local.col_idx.cpu().numpy(), xci)
+    del G, local
     l2g, er, ec = oracle.sampled_local_edges(T, orp, oci)
     part = gg.partition_from_edges(g.n_rows, l2g, er, ec, T, g.degrees())
     w.partition = part
