@@ -201,6 +201,22 @@ def sampled_local_edges(targets, out_row_ptr, out_col_idx):
     return l2g, er, ec
 
 
+def eas_traverse(row_ptr, col_idx, targets, hops, fanout, rule, seed=0):
+    """Section 5.3.1 traversal.  rule: "degree" (the paper's: many connections to unselected vertices first) or
+    "hash" (seeded).  -> dist int32[n] (hop of selection or -1), ring_ids, hop_offsets int64[hops+2]."""
+    row_ptr, col_idx, targets = _i32(row_ptr), _i32(col_idx), _i32(targets)
+    n = row_ptr.shape[0] - 1
+    dist = np.empty(n, dtype=np.int32)
+    ring = np.empty(max(n, 1), dtype=np.int32)
+    off = np.empty(hops + 2, dtype=np.int64)
+    rc = lib().orc_eas_traverse(C.c_int32(n), _p(row_ptr), _p(col_idx), _p(targets), C.c_int32(targets.shape[0]), C.c_int32(hops),
+                                C.c_int32(fanout), C.c_int32({"hash": 0, "degree": 1}[rule]), C.c_uint64(seed & (2**64 - 1)),
+                                _p(dist), _p(ring), _p(off))
+    if rc != 0:
+        raise ValueError("bad argument")
+    return dist, ring[: off[-1]].copy(), off
+
+
 def extract_partition(row_ptr, col_idx, targets, L):
     """Section 6 step 1: the one-hop graph of everything within L hops of the targets, vertices renumbered by
     (distance, id).  -> (local_row_ptr, local_col_idx, local_to_global, hop_offsets, dist_local);

@@ -15,6 +15,10 @@
  *   - expansion-aware sampling of section 5.3: inner dependencies are kept
  *     whole, only edges that leave the target set are thinned, at most
  *     `fanout` per boundary vertex;
+ *   - the traversal of expansion-aware sampling itself (section 5.3.1): from
+ *     the inner vertices, at most h hops outwards, at most f new vertices per
+ *     traversed vertex and hop, preferring vertices with many connections to
+ *     the vertices not selected so far;
  *   - extraction of the partition (section 6, step 1; section 5.3.1 "a
  *     subgraph is generated from the traversed vertices"): the vertices the
  *     traversal reached and every edge of the graph between two of them.
@@ -453,4 +457,81 @@ int64_t orc_extract_sampled(int32_t n, const int32_t *targets, int32_t n_targets
     }
     free(cursor);
     return nnz;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Traversal of expansion-aware sampling (section 5.3.1).  From the inner   */
+/* vertices (targets, hop 0) go at most `hops` hops outwards; in hop j      */
+/* every vertex v selected in hop j-1 looks at its neighbours that have not */
+/* been selected before this hop started and keeps at most `fanout` of them */
+/* - those with the smallest (key, id):                                     */
+/*   rule 1 (the paper's): key = -(connections of u to vertices that were   */
+/*           unselected when the hop started), i.e. many connections first; */
+/*   rule 0 (seeded hash, as in orc_sample_boundary): key = orc_edge_key(   */
+/*           seed, v, u, j).                                                */
+/* A vertex is selected in hop j if some v kept it.  Outputs are those of   */
+/* orc_active_sets with "distance" = the hop of selection:                  */
+/*   dist[v]      hop in which v was selected, -1 if never                  */
+/*   ring_ids     selected vertices sorted by (hop, id)                     */
+/*   hop_offsets  [hops+2]                                                  */
+/* ---------------------------------------------------------------------- */
+typedef struct { uint64_t key; int32_t u; } orc_eas_cand;
+
+static int orc_eas_cmp(const void *a, const void *b)
+{
+    const orc_eas_cand *x = (const orc_eas_cand *)a, *y = (const orc_eas_cand *)b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    return (x->u > y->u) - (x->u < y->u);
+}
+
+int orc_eas_traverse(int32_t n, const int32_t *row_ptr, const int32_t *col_idx,
+                     const int32_t *targets, int32_t n_targets, int32_t hops, int32_t fanout,
+                     int32_t rule, uint64_t seed,
+                     int32_t *dist, int32_t *ring_ids, int64_t *hop_offsets)
+{
+    if (fanout < 0 || hops < 1 || (rule != 0 && rule != 1)) return 1;
+    for (int32_t v = 0; v < n; ++v) dist[v] = -1;
+    for (int32_t i = 0; i < n_targets; ++i) {
+        if (targets[i] < 0 || targets[i] >= n) return 1;
+        dist[targets[i]] = 0;
+    }
+    int64_t pos = 0;
+    hop_offsets[0] = 0;
+    for (int32_t v = 0; v < n; ++v) if (dist[v] == 0) ring_ids[pos++] = v;
+    hop_offsets[1] = pos;
+    uint8_t *was_selected = (uint8_t *)malloc((size_t)n + 1);
+    int32_t *conn = (int32_t *)malloc(sizeof(int32_t) * ((size_t)n + 1));
+    orc_eas_cand *cand = NULL;
+    int32_t cap = 0;
+    for (int32_t j = 1; j <= hops; ++j) {
+        /* state when the hop starts */
+        for (int32_t v = 0; v < n; ++v) was_selected[v] = dist[v] >= 0;
+        for (int32_t u = 0; u < n; ++u) {
+            int32_t c = 0;
+            for (int32_t e = row_ptr[u]; e < row_ptr[u + 1]; ++e) c += !was_selected[col_idx[e]];
+            conn[u] = c;
+        }
+        for (int64_t q = hop_offsets[j - 1]; q < hop_offsets[j]; ++q) {
+            const int32_t v = ring_ids[q];
+            const int32_t len = row_ptr[v + 1] - row_ptr[v];
+            if (len > cap) { cap = len; cand = (orc_eas_cand *)realloc(cand, sizeof(orc_eas_cand) * (size_t)cap); }
+            int32_t nc = 0;
+            for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                const int32_t u = col_idx[e];
+                if (was_selected[u]) continue;
+                cand[nc].u = u;
+                cand[nc].key = rule == 1 ? (uint64_t)(0xffffffffu - (uint32_t)conn[u])
+                                         : orc_edge_key(seed, (uint64_t)v, (uint64_t)u, (uint64_t)j);
+                ++nc;
+            }
+            qsort(cand, (size_t)nc, sizeof(orc_eas_cand), orc_eas_cmp);
+            const int32_t keep = nc < fanout ? nc : fanout;
+            for (int32_t k = 0; k < keep; ++k)
+                if (dist[cand[k].u] < 0) dist[cand[k].u] = j;
+        }
+        for (int32_t v = 0; v < n; ++v) if (dist[v] == j) ring_ids[pos++] = v;
+        hop_offsets[j + 1] = pos;
+    }
+    free(cand); free(conn); free(was_selected);
+    return 0;
 }
