@@ -215,6 +215,26 @@ int32_t gnn_sample_boundary(const gnn_csr *g, const uint32_t *target_bitmap,
                             void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * Traversal of expansion-aware sampling (section 5.3.1): from the inner vertices (targets, hop 0) at
+ * most `hops` hops outwards; in hop j every vertex selected in hop j-1 keeps at most `fanout` of its
+ * neighbours that had not been selected when the hop started - those with the smallest (key, id):
+ *   GNN_EAS_DEGREE  the paper's rule, vertices with many connections to unselected vertices first:
+ *                   key(u) = -(entries of row u that were unselected when the hop started)
+ *   GNN_EAS_HASH    key(v, u) = mix64(mix64(mix64(seed + j) ^ v) ^ u), as in gnn_sample_boundary
+ * A vertex is selected in hop j if some vertex of hop j-1 kept it.  Outputs as for
+ * gnn_build_active_sets with L = hops ("distance" = hop of selection): dist, ring_ids (selected
+ * vertices sorted by (hop, id)), hop_offsets [hops+2] (device), hop_offsets_host (optional; waits).
+ * gnn_extract_partition(g, ring_ids, n, dist, hops) then gives the sub-graph of the traversed
+ * vertices.  Rows must not repeat a column.  Bit-exact, independent of the order of `targets`.
+ */
+typedef enum gnn_eas_rule { GNN_EAS_HASH = 0, GNN_EAS_DEGREE = 1 } gnn_eas_rule;
+
+int32_t gnn_eas_traverse(const gnn_csr *g, const int32_t *targets, int32_t n_targets, int32_t hops,
+                         int32_t fanout, int32_t rule, uint64_t seed,
+                         int32_t *dist, int32_t *ring_ids, int64_t *hop_offsets, int64_t *hop_offsets_host,
+                         void *ws, size_t *ws_bytes, void *stream);
+
+/*
  * Extraction of the partition's one-hop graph (section 6, figure 7c step 1: extract the multi-hop
  * dependency starting from the inner vertices; section 5.3.1: a subgraph is generated from the
  * traversed vertices).  g is the UNPARTITIONED graph (square); ring_ids[0 .. n_local) and dist are

@@ -217,23 +217,30 @@ def eas_traverse(row_ptr, col_idx, targets, hops, fanout, rule, seed=0):
     return dist, ring[: off[-1]].copy(), off
 
 
-def extract_partition(row_ptr, col_idx, targets, L):
-    """Section 6 step 1: the one-hop graph of everything within L hops of the targets, vertices renumbered by
-    (distance, id).  -> (local_row_ptr, local_col_idx, local_to_global, hop_offsets, dist_local);
-    layer l's rows are the local ids 0 .. hop_offsets[L-l+1]-1."""
-    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+def extract_from_ring(row_ptr, col_idx, ring):
+    """The sub-graph induced by the listed vertices, renumbered in list order (section 5.3.1: a sub-graph is
+    generated from the traversed vertices).  -> (local_row_ptr, local_col_idx)."""
+    row_ptr, col_idx, ring = _i32(row_ptr), _i32(col_idx), _i32(ring)
     n = row_ptr.shape[0] - 1
-    _, ring, off = active_sets(row_ptr, col_idx, targets, L)
     n_local = ring.shape[0]
-    new_id = np.empty(n, dtype=np.int32)
+    new_id = np.empty(max(n, 1), dtype=np.int32)
     rp = np.empty(n_local + 1, dtype=np.int32)
     f = lib().orc_extract_partition
     f.restype = C.c_int64
     nnz = f(C.c_int32(n), _p(row_ptr), _p(col_idx), _p(ring), C.c_int32(n_local), _p(new_id), _p(rp), None)
     ci = np.empty(max(int(nnz), 1), dtype=np.int32)
     f(C.c_int32(n), _p(row_ptr), _p(col_idx), _p(ring), C.c_int32(n_local), _p(new_id), _p(rp), _p(ci))
+    return rp, ci[: int(nnz)]
+
+
+def extract_partition(row_ptr, col_idx, targets, L):
+    """Section 6 step 1: the one-hop graph of everything within L hops of the targets, vertices renumbered by
+    (distance, id).  -> (local_row_ptr, local_col_idx, local_to_global, hop_offsets, dist_local);
+    layer l's rows are the local ids 0 .. hop_offsets[L-l+1]-1."""
+    _, ring, off = active_sets(row_ptr, col_idx, targets, L)
+    rp, ci = extract_from_ring(row_ptr, col_idx, ring)
     dist_local = np.repeat(np.arange(L + 1, dtype=np.int32), np.diff(off).astype(np.int64))
-    return rp, ci[: int(nnz)], ring, off, dist_local
+    return rp, ci, ring, off, dist_local
 
 
 def extract_sampled(n, targets, s_row_ptr, s_col_idx):

@@ -24,7 +24,7 @@ STATUS = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_SHAPE", 3: "GNN_ERR
 EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_scales", "gnn_masked_spmm_fwd",
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
-           "gnn_extract_sampled_partition"]
+           "gnn_extract_sampled_partition", "gnn_eas_traverse"]
 
 
 class GnnError(RuntimeError):
@@ -156,6 +156,24 @@ def gnn_build_active_sets(g: Graph, targets: torch.Tensor, L: int, sync: bool = 
     host = (C.c_int64 * (L + 2))() if sync else None
     _with_ws(lib().gnn_build_active_sets,
              (C.byref(g.c), _ptr(targets) if targets.numel() else None, C.c_int32(targets.numel()), C.c_int32(L),
+              _ptr(dist) if g.n_rows else None, _ptr(ring), _ptr(off), host),
+             (_stream(),), ws)
+    return dist, ring, off, (list(host) if sync else None)
+
+
+def gnn_eas_traverse(g: Graph, targets: torch.Tensor, hops: int, fanout: int, rule: str = "degree", seed: int = 0,
+                     sync: bool = True, ws: Workspace | None = None):
+    """rule: "degree" (many connections to unselected vertices first) or "hash" (seeded).  Outputs as for
+    gnn_build_active_sets with L = hops."""
+    _i32(targets, "targets")
+    dev = g.row_ptr.device
+    dist = torch.empty(g.n_rows, dtype=torch.int32, device=dev)
+    ring = torch.empty(max(g.n_rows, 1), dtype=torch.int32, device=dev)
+    off = torch.empty(hops + 2, dtype=torch.int64, device=dev)
+    host = (C.c_int64 * (hops + 2))() if sync else None
+    _with_ws(lib().gnn_eas_traverse,
+             (C.byref(g.c), _ptr(targets) if targets.numel() else None, C.c_int32(targets.numel()), C.c_int32(hops),
+              C.c_int32(fanout), C.c_int32({"hash": 0, "degree": 1}[rule]), C.c_uint64(seed & (2 ** 64 - 1)),
               _ptr(dist) if g.n_rows else None, _ptr(ring), _ptr(off), host),
              (_stream(),), ws)
     return dist, ring, off, (list(host) if sync else None)

@@ -14,6 +14,7 @@
 // (4 B) and writes 8 B per newly reached vertex; the bit probes hit a bitmap of n/8 bytes
 // that stays in L2.
 #include "common.h"
+#include "hashkey.h"
 #include "scan.h"
 
 namespace gnnhot {
@@ -139,6 +140,116 @@ __global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(uint32_t* __r
     }
 }
 
+// ---- expansion-aware traversal (paper section 5.3.1) -----------------------------------------------------------
+// The same level-synchronous scheme with a thinned expansion: a traversed vertex keeps at most `fanout` of its
+// not-yet-selected neighbours, those with the smallest (key, id).  `visited` is read-only while a hop expands, so
+// "not yet selected" means "when the hop started" for every row, and the result does not depend on the order in
+// which rows are processed.  Keys: the seeded edge hash of the boundary sampler, or (the paper's rule) the negated
+// number of connections of the candidate to vertices that were unselected when the hop started.
+
+// conn[u] = number of entries of row u that are not in `visited`; sixteen lanes per row
+__global__ __launch_bounds__(256) void eas_connections_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                               int32_t n, const uint32_t* __restrict__ visited,
+                                                               int32_t* __restrict__ conn) {
+    const int lane = lane_id(), sub = lane / 16, sl = lane % 16;
+    const int64_t groups = (int64_t)gridDim.x * (blockDim.x / 16);
+    for (int64_t u = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 16; u < n; u += groups) {
+        const int32_t s = row_ptr[u], e = row_ptr[u + 1];
+        int32_t c = 0;
+        for (int32_t p = s; p < e; p += 16) {
+            const bool open = p + sl < e && !in_set(visited, col_idx[p + sl]);
+            c += __popcll((__ballot(open) >> (sub * 16)) & 0xffffull);
+        }
+        if (sl == 0) conn[u] = c;
+    }
+}
+
+__device__ __forceinline__ uint64_t eas_key(int32_t rule, uint64_t seed_hop_mixed, const int32_t* __restrict__ conn, int32_t v, int32_t u) {
+    return rule == 1 ? (uint64_t)(0xffffffffu - (uint32_t)conn[u]) : edge_key(seed_hop_mixed, (uint64_t)v, (uint64_t)u);
+}
+
+// Sixteen lanes per frontier vertex, four vertices per wavefront; loops run to the longest row of the wavefront so
+// that ballots and shuffles stay convergent.  A row with more than `fanout` candidates finds the fanout-th smallest
+// (key, id) by `fanout` rounds of "smallest pair above the previous one" (the row is re-read from cache).
+__global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                          const int32_t* __restrict__ ring_ids, const int64_t* __restrict__ hop_offsets,
+                                                          int32_t ring, const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
+                                                          int32_t fanout, int32_t rule, uint64_t seed_hop_mixed,
+                                                          const int32_t* __restrict__ conn) {
+    const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
+    const int lane = lane_id(), sub = lane / 16, sl = lane % 16;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t base = begin + 4 * (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6); base < end; base += 4 * waves) {  // uniform over the wave
+        const int64_t i = base + sub;
+        int32_t v = 0, s = 0, e = 0;
+        if (i < end) {
+            v = ring_ids[i];
+            s = row_ptr[v];
+            e = row_ptr[v + 1];
+        }
+        int len_max = e - s;
+        len_max = max(len_max, __shfl_xor(len_max, 16, kWave));
+        len_max = max(len_max, __shfl_xor(len_max, 32, kWave));
+        int32_t n_cand = 0;
+        for (int32_t off = 0; off < len_max; off += 16) {
+            const int32_t p = s + off + sl;
+            const bool cand = p < e && !in_set(visited, col_idx[p]);
+            n_cand += __popcll((__ballot(cand) >> (sub * 16)) & 0xffffull);
+        }
+        // threshold pair: candidates with (key, id) <= (thr_k, thr_u) are kept
+        uint64_t thr_k = ~0ull;
+        int32_t thr_u = 0x7fffffff;
+        if (fanout == 0) {
+            thr_k = 0ull;
+            thr_u = -1;  // nothing is <= (0, -1): ids are non-negative
+        }
+        const bool need = fanout > 0 && n_cand > fanout;  // uniform over the 16-lane group
+        if (__ballot(need) != 0ull) {                      // uniform over the wavefront
+            uint64_t prev_k = 0ull;
+            int32_t prev_u = -1;
+            for (int32_t round = 0; round < fanout; ++round) {
+                uint64_t best_k = ~0ull;
+                int32_t best_u = 0x7fffffff;
+                if (need) {
+                    for (int32_t p = s + sl; p < e; p += 16) {
+                        const int32_t u = col_idx[p];
+                        if (in_set(visited, u)) continue;
+                        const uint64_t k = eas_key(rule, seed_hop_mixed, conn, v, u);
+                        if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
+                            best_k = k;
+                            best_u = u;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int d = 8; d >= 1; d >>= 1) {
+                    const uint64_t ok = __shfl_xor(best_k, d, kWave);
+                    const int32_t ou = __shfl_xor(best_u, d, kWave);
+                    if (pair_less(ok, ou, best_k, best_u)) {
+                        best_k = ok;
+                        best_u = ou;
+                    }
+                }
+                prev_k = best_k;
+                prev_u = best_u;
+            }
+            if (need) {
+                thr_k = prev_k;
+                thr_u = prev_u;
+            }
+        }
+        for (int32_t p = s + sl; p < e; p += 16) {
+            const int32_t u = col_idx[p];
+            if (in_set(visited, u)) continue;
+            bool keep = !need;
+            if (need) keep = !pair_less(thr_k, thr_u, eas_key(rule, seed_hop_mixed, conn, v, u), u);
+            if (fanout == 0) keep = false;
+            const uint32_t bit = 1u << (u & 31);
+            if (keep && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
+        }
+    }
+}
+
 }  // namespace gnnhot
 
 using namespace gnnhot;
@@ -195,6 +306,66 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* target
     }
     if (hop_offsets_host != nullptr) {
         GNN_HIP(hipMemcpyAsync(hop_offsets_host, hop_offsets, sizeof(int64_t) * (size_t)(L + 2), hipMemcpyDeviceToHost, stream));
+        GNN_HIP(hipStreamSynchronize(stream));
+    }
+    return GNN_OK;
+}
+
+extern "C" int32_t gnn_eas_traverse(const gnn_csr* g, const int32_t* targets, int32_t n_targets, int32_t hops, int32_t fanout,
+                                    int32_t rule, uint64_t seed, int32_t* dist, int32_t* ring_ids, int64_t* hop_offsets,
+                                    int64_t* hop_offsets_host, void* ws, size_t* ws_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_csr(g, "g"));
+    GNN_REQUIRE(g->n_rows == g->n_cols, GNN_ERR_SHAPE, "the traversal needs a square graph (%d x %d)", g->n_rows, g->n_cols);
+    GNN_REQUIRE(hops >= 1 && hops <= 1024, GNN_ERR_INVALID_ARG, "hops = %d out of range [1, 1024]", hops);
+    GNN_REQUIRE(fanout >= 0, GNN_ERR_INVALID_ARG, "fanout < 0");
+    GNN_REQUIRE(rule == GNN_EAS_HASH || rule == GNN_EAS_DEGREE, GNN_ERR_INVALID_ARG, "unknown selection rule %d", rule);
+    GNN_REQUIRE(n_targets >= 0, GNN_ERR_INVALID_ARG, "n_targets < 0");
+    const int32_t n = g->n_rows;
+    const int64_t nw = ((int64_t)n + 31) / 32;
+    const int64_t nb = nw > 0 ? (nw + kAsWordsPerBlock - 1) / kAsWordsPerBlock : 1;
+
+    WsCarver carve(ws);
+    uint32_t* visited = carve.take<uint32_t>((size_t)nw + 1);
+    uint32_t* next = carve.take<uint32_t>((size_t)nw + 1);
+    int32_t* blk_cnt = carve.take<int32_t>((size_t)nb + 1);
+    int32_t* conn = carve.take<int32_t>(rule == GNN_EAS_DEGREE ? (size_t)n + 1 : 1);
+    AsCtrl* ctrl = carve.take<AsCtrl>(1);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+
+    GNN_REQUIRE(hop_offsets != nullptr, GNN_ERR_INVALID_ARG, "hop_offsets is NULL");
+    GNN_REQUIRE(n == 0 || (dist != nullptr && ring_ids != nullptr), GNN_ERR_INVALID_ARG, "dist / ring_ids is NULL");
+    GNN_REQUIRE(n_targets == 0 || targets != nullptr, GNN_ERR_INVALID_ARG, "targets is NULL");
+
+    as_init_kernel<<<grid_for(n > hops + 2 ? n : hops + 2, 256, 2048), 256, 0, stream>>>(dist, n, visited, next, nw, ctrl, hop_offsets, hops);
+    GNN_LAUNCH_CHECK("as_init_kernel");
+    if (n > 0) {
+        if (n_targets > 0) {
+            as_seed_kernel<<<grid_for(n_targets, 256, 2048), 256, 0, stream>>>(targets, n_targets, n, next);
+            GNN_LAUNCH_CHECK("as_seed_kernel");
+        }
+        for (int32_t ring = 0; ring <= hops; ++ring) {
+            if (ring > 0) {
+                if (rule == GNN_EAS_DEGREE) {
+                    eas_connections_kernel<<<grid_for((int64_t)n * 16, 256, 1 << 16), 256, 0, stream>>>(g->row_ptr, g->col_idx, n, visited, conn);
+                    GNN_LAUNCH_CHECK("eas_connections_kernel");
+                }
+                eas_expand_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited, next, fanout,
+                                                            rule, mix64(seed + (uint64_t)ring), conn);
+                GNN_LAUNCH_CHECK("eas_expand_kernel");
+            }
+            as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt);
+            GNN_LAUNCH_CHECK("as_count_kernel");
+            as_scan_kernel<<<1, 1024, 0, stream>>>(blk_cnt, nb, hop_offsets, ring, ctrl);
+            GNN_LAUNCH_CHECK("as_scan_kernel");
+            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
+            GNN_LAUNCH_CHECK("as_emit_kernel");
+        }
+    }
+    if (hop_offsets_host != nullptr) {
+        GNN_HIP(hipMemcpyAsync(hop_offsets_host, hop_offsets, sizeof(int64_t) * (size_t)(hops + 2), hipMemcpyDeviceToHost, stream));
         GNN_HIP(hipStreamSynchronize(stream));
     }
     return GNN_OK;

@@ -10,30 +10,10 @@
 // is re-read from cache each round), then emit the row in its original ascending order
 // through a ballot-prefix compaction.  Bound: HBM (one streaming read of the target rows).
 #include "common.h"
+#include "hashkey.h"
 #include "scan.h"
 
 namespace gnnhot {
-
-// splitmix64 output function: golden-ratio increment, two xor-shift-multiply rounds, xor-shift.
-__device__ __forceinline__ uint64_t mix64(uint64_t x) {
-    x += 0x9E3779B97F4A7C15ull;
-    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
-    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
-    return x ^ (x >> 31);
-}
-
-__device__ __forceinline__ uint64_t edge_key(uint64_t seed_hop_mixed, uint64_t v, uint64_t u) {
-    return mix64(mix64(seed_hop_mixed ^ v) ^ u);
-}
-
-__device__ __forceinline__ bool in_set(const uint32_t* __restrict__ bitmap, int32_t u) {
-    return (bitmap[u >> 5] >> (u & 31)) & 1u;
-}
-
-// (key, id) pairs ordered lexicographically
-__device__ __forceinline__ bool pair_less(uint64_t ka, int32_t ua, uint64_t kb, int32_t ub) {
-    return ka < kb || (ka == kb && ua < ub);
-}
 
 // Sixteen lanes per target row, four rows per wavefront (the paper's graphs have 15-50 neighbours
 // per vertex).  Loops run to the longest row of the wavefront so that ballots and shuffles stay
@@ -286,11 +266,7 @@ extern "C" int32_t gnn_sample_boundary(const gnn_csr* g, const uint32_t* target_
     GNN_REQUIRE(out_capacity >= 0, GNN_ERR_INVALID_ARG, "out_capacity < 0");
     if (n_targets > 0) {
         // seed + hop is mixed once on the host side of the launch (same function as on the device)
-        uint64_t x = seed + (uint64_t)hops;
-        x += 0x9E3779B97F4A7C15ull;
-        x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
-        x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
-        x = x ^ (x >> 31);
+        const uint64_t x = mix64(seed + (uint64_t)hops);
         sb_fill_kernel<<<wave_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, g->n_rows, target_bitmap, targets, n_targets, fanout, x,
                                                       out_row_ptr, out_col_idx, out_capacity);
         GNN_LAUNCH_CHECK("sb_fill_kernel");
