@@ -25,6 +25,7 @@ namespace gnnhot {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 #ifndef GNN_NT_PF_BF16
 #define GNN_NT_PF_BF16 2
@@ -361,11 +362,218 @@ __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) 
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// gemm_nt, wide tile.  The layer widths of the paper's models (128 .. 602) make these products
+// "skinny": the reduction and the output width are both a few hundred, the row count is millions,
+// so at bf16 the operand rows come from HBM faster than a small tile can turn them over.  This
+// variant gives one workgroup 128 rows x the WHOLE output width (up to 256 columns: each operand
+// row is read once), a wave 64 x 32*NTW, and moves 64-byte row slices through a double-buffered LDS
+// ring with ONE barrier per slice: while slice s feeds the MFMAs, slice s+1 waits in registers and
+// slice s+2 is in flight.  LDS rows are 64 bytes without padding; the 16-byte chunk c of row r sits
+// at slot c ^ ((r >> 1) & 3), so that eight consecutive rows read with the same c touch eight
+// different 16-byte bank groups.  Preconditions (checked by the launcher): 16-byte aligned operand
+// rows and a reduction length that is a multiple of the slice; rows beyond M and columns beyond N
+// are computed from clamped addresses and discarded.
+// ------------------------------------------------------------------------------------------
+template <int DT, int NTW>
+__global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
+    constexpr int BM = 128, BN = 64 * NTW, MT = 2, NT = NTW, WTN = 32 * NTW;
+    constexpr int ES = DTy<DT>::ES, EPV = DTy<DT>::EPV;
+    constexpr int EPS = 64 / ES;                  // reduction elements per slice
+    constexpr int A_CH = BM / 64, B_CH = BN / 64;  // 16-byte chunks per thread and slice
+    constexpr int BUF = (BM + BN) * 16;            // words per ring buffer
+    constexpr int CW = (256 / ES) < WTN ? (256 / ES) : WTN;  // columns of one staged output piece (<= 256 bytes)
+    constexpr int CROW = CW * ES / 4 + 4;          // words per staged row (16 bytes of padding)
+    constexpr int STAGE = 32 * CROW;               // words per wave
+    constexpr int SMEM = 2 * BUF > 4 * STAGE ? 2 * BUF : 4 * STAGE;
+    __shared__ __attribute__((aligned(16))) uint32_t smem[SMEM];
+
+    const int tiles_n = (a.N + BN - 1) / BN;
+    const int m0 = (int)(blockIdx.x / tiles_n) * BM, n0 = (int)(blockIdx.x % tiles_n) * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, g = lane >> 5;
+    const int ld_row = tid >> 2, ld_c = tid & 3;   // loader: row within a 64-row band, 16-byte chunk of the slice
+    const int st_off = ld_row * 16 + ((ld_c ^ ((ld_row >> 1) & 3)) << 2);  // word offset of that chunk inside a band
+
+    // per-thread operand rows as byte offsets (scalars, not arrays: everything here must stay in registers)
+    auto a_row = [&](int c) -> int64_t {
+        const int m = m0 + ld_row + 64 * c;
+        const int64_t r = m < a.M ? (a.a_rows ? (int64_t)a.a_rows[m] : (int64_t)m) : (a.a_rows ? (int64_t)a.a_rows[0] : 0);
+        return (r * a.lda + ld_c * EPV) * ES;
+    };
+    auto b_row = [&](int c) -> int64_t {
+        const int n = n0 + ld_row + 64 * c;
+        return ((int64_t)(n < a.N ? n : 0) * a.ldb + ld_c * EPV) * ES;
+    };
+    const int64_t ao0 = a_row(0), ao1 = a_row(1);
+    const int64_t bo0 = b_row(0), bo1 = B_CH > 1 ? b_row(1) : 0, bo2 = B_CH > 2 ? b_row(2) : 0, bo3 = B_CH > 2 ? b_row(3) : 0;
+
+    v16f acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int k_slices = a.K / EPS;
+    const int n_steps = k_slices * a.n_src;
+    // two register sets (p, q) of one slice each; plain variables, filled and drained by macros
+    u32x4 pa0, pa1, pb0, pb1, pb2, pb3, qa0, qa1, qb0, qb1, qb2, qb3;
+#define GNN_FETCH(S, step_)                                                        \
+    {                                                                              \
+        const int st_ = (step_);                                                   \
+        const int src_ = st_ >= k_slices ? 1 : 0;                                  \
+        const int64_t kb_ = (int64_t)(st_ - src_ * k_slices) * 64;                 \
+        const char* Ab_ = (const char*)(src_ ? a.A[1] : a.A[0]) + kb_;             \
+        const char* Bb_ = (const char*)(src_ ? a.Bt[1] : a.Bt[0]) + kb_;           \
+        S##a0 = *(const u32x4*)(Ab_ + ao0);                                        \
+        S##a1 = *(const u32x4*)(Ab_ + ao1);                                        \
+        S##b0 = *(const u32x4*)(Bb_ + bo0);                                        \
+        if (B_CH > 1) S##b1 = *(const u32x4*)(Bb_ + bo1);                          \
+        if (B_CH > 2) {                                                            \
+            S##b2 = *(const u32x4*)(Bb_ + bo2);                                    \
+            S##b3 = *(const u32x4*)(Bb_ + bo3);                                    \
+        }                                                                          \
+    }
+#define GNN_STASH(buf_, S)                                                         \
+    {                                                                              \
+        *(u32x4*)&(buf_)[st_off] = S##a0;                                          \
+        *(u32x4*)&(buf_)[1024 + st_off] = S##a1;                                   \
+        *(u32x4*)&(buf_)[BM * 16 + st_off] = S##b0;                                \
+        if (B_CH > 1) *(u32x4*)&(buf_)[BM * 16 + 1024 + st_off] = S##b1;           \
+        if (B_CH > 2) {                                                            \
+            *(u32x4*)&(buf_)[BM * 16 + 2048 + st_off] = S##b2;                     \
+            *(u32x4*)&(buf_)[BM * 16 + 3072 + st_off] = S##b3;                     \
+        }                                                                          \
+    }
+    // fragment addresses: row (.. + li), chunk g*2+q
+    const int sw = (li >> 1) & 3;
+    const int fa_off = (wm * 64 + li) * 16, fb_off = BM * 16 + (wn * WTN + li) * 16;
+    auto compute = [&](const uint32_t* buf) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int slot = ((g * 2 + q) ^ sw) << 2;
+            uint4 fa[MT], fb[NT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa[i] = *(const uint4*)&buf[fa_off + i * 512 + slot];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) fb[j] = *(const uint4*)&buf[fb_off + j * 512 + slot];
+            if (DT == GNN_F32) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < NT; ++j) {
+                            const uint32_t av = t == 0 ? fa[i].x : (t == 1 ? fa[i].y : (t == 2 ? fa[i].z : fa[i].w));
+                            const uint32_t bv = t == 0 ? fb[j].x : (t == 1 ? fb[j].y : (t == 2 ? fb[j].z : fb[j].w));
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av), __uint_as_float(bv), acc[i][j], 0, 0, 0);
+                        }
+            } else {
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fa[i]), __builtin_bit_cast(v8bf, fb[j]),
+                                                                             acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+
+    uint32_t* buf0 = smem;
+    uint32_t* buf1 = smem + BUF;
+    // invariant at the top of an iteration for slice s: ring buffer s%2 holds slice s (visible to all waves),
+    // register set (s+1)%2 holds slice s+1 (possibly still in flight), register set s%2 is free
+    GNN_FETCH(p, 0);
+    if (n_steps > 1) GNN_FETCH(q, 1);
+    GNN_STASH(buf0, p);
+    __syncthreads();
+    for (int step = 0; step < n_steps; step += 2) {
+        if (step + 2 < n_steps) GNN_FETCH(p, step + 2);
+        compute(buf0);
+        if (step + 1 < n_steps) GNN_STASH(buf1, q);
+        __syncthreads();
+        if (step + 1 < n_steps) {
+            if (step + 3 < n_steps) GNN_FETCH(q, step + 3);
+            compute(buf1);
+            if (step + 2 < n_steps) GNN_STASH(buf0, p);
+            __syncthreads();
+        }
+    }
+#undef GNN_FETCH
+#undef GNN_STASH
+
+    // Epilogue.  acc[i][j][r] is C[row (r/4)*8 + g*4 + r%4][column li] of its 32x32 block: a piece of 32 rows x CW
+    // columns is laid out row-major in the wave's part of LDS (bias, ReLU and rounding applied) and written with
+    // 16-byte stores, up to 256 contiguous bytes per row.
+    uint32_t* stg = smem + wave * STAGE;
+    constexpr int JP = CW / 32;            // 32-column blocks per piece
+    constexpr int CPR = CW * ES / 16;      // 16-byte chunks per staged row
+    constexpr int RPP = 64 / CPR;          // rows written per pass of the wave
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int p = 0; p < NT / JP; ++p) {
+#pragma unroll
+            for (int jj = 0; jj < JP; ++jj) {
+                const int j = p * JP + jj;
+                const int n = n0 + wn * WTN + j * 32 + li;
+                const float bv = (a.bias && n < a.N) ? a.bias[n] : 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = (r >> 2) * 8 + g * 4 + (r & 3);
+                    float v = acc[i][j][r] + bv;
+                    if (a.relu) v = v > 0.f ? v : 0.f;
+                    if (DT == GNN_F32) stg[row * CROW + jj * 32 + li] = __float_as_uint(v);
+                    else ((uint16_t*)stg)[row * (CROW * 2) + jj * 32 + li] = f32_to_bf16(v);
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int pass = 0; pass < 32 / RPP; ++pass) {
+                const int row = pass * RPP + lane / CPR, ch = lane % CPR;
+                const int m = m0 + wm * 64 + i * 32 + row;
+                const int n = n0 + wn * WTN + p * CW + ch * EPV;
+                if (m < a.M && n < a.N) {
+                    const int64_t crow = a.c_rows ? (int64_t)a.c_rows[m] : (int64_t)m;
+                    const uint4 v = *(const uint4*)&stg[row * CROW + ch * 4];
+                    char* dst = (char*)a.C + (crow * a.ldc + n) * ES;
+                    if (n + EPV <= a.N && a.c_vec) {
+                        *(uint4*)dst = v;
+                    } else {
+                        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                        if (DT == GNN_F32) {
+                            for (int e = 0; e < 4 && n + e < a.N; ++e) ((uint32_t*)dst)[e] = w[e];
+                        } else {
+                            for (int e = 0; e < 8 && n + e < a.N; ++e) ((uint16_t*)dst)[e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
 template <int DT>
 static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
     if (a.M <= 0 || a.N <= 0) return GNN_OK;
     const int64_t tiles_m = ((int64_t)a.M + 127) / 128;
     const bool vec = a.a_vec && a.b_vec;  // both operands aligned: the branch-free loader
+    if (vec && a.N > 32 && a.K % (64 / DTy<DT>::ES) == 0 && a.K > 0) {
+        // wide tile: the tile width that pads the output width least (256 on a tie)
+        const int64_t p256 = ((int64_t)a.N + 255) / 256 * 256, p128 = ((int64_t)a.N + 127) / 128 * 128, p64 = ((int64_t)a.N + 63) / 64 * 64;
+        if (p256 <= p128 && p256 <= p64)
+            gemm_nt_wide_kernel<DT, 4><<<(unsigned)(tiles_m * (p256 / 256)), 256, 0, stream>>>(a);
+        else if (p128 <= p64)
+            gemm_nt_wide_kernel<DT, 2><<<(unsigned)(tiles_m * (p128 / 128)), 256, 0, stream>>>(a);
+        else
+            gemm_nt_wide_kernel<DT, 1><<<(unsigned)(tiles_m * (p64 / 64)), 256, 0, stream>>>(a);
+        GNN_LAUNCH_CHECK("gemm_nt_wide_kernel");
+        return GNN_OK;
+    }
     if (a.N > 64) {
         const unsigned grid = (unsigned)((tiles_m * ((a.N + 127) / 128) + 7) / 8 * 8);
         if (vec) gemm_nt_kernel<DT, 128, 2, 2, true><<<grid, 256, 0, stream>>>(a);
