@@ -419,91 +419,118 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
 
     const int k_slices = a.K / EPS;
     const int n_steps = k_slices * a.n_src;
-    // two register sets (p, q) of one slice each; plain variables, filled and drained by macros
-    u32x4 pa0, pa1, pb0, pb1, pb2, pb3, qa0, qa1, qb0, qb1, qb2, qb3;
+    // Everything that lives across steps is a plain variable filled and drained by macros (arrays handed to
+    // helper functions ended up in scratch memory).  Two register sets (0, 1) hold the slices in flight from
+    // global memory, two fragment sets (f0, f1) hold the operands of the two halves of a slice.
+    u32x4 a0x0, a0x1, a1x0, a1x1;
+    u32x4 b0x0, b0x1, b0x2, b0x3, b1x0, b1x1, b1x2, b1x3;
+    u32x4 f0a0, f0a1, f0b0, f0b1, f0b2, f0b3, f1a0, f1a1, f1b0, f1b1, f1b2, f1b3;
+    f1a0 = f1a1 = f1b0 = f1b1 = f1b2 = f1b3 = (u32x4){0u, 0u, 0u, 0u};
+// a fetch beyond the last slice repeats the last one (a cache hit; what it brings is stashed but never multiplied)
 #define GNN_FETCH(S, step_)                                                        \
     {                                                                              \
-        const int st_ = (step_);                                                   \
+        const int st_ = (step_) < n_steps ? (step_) : n_steps - 1;                 \
         const int src_ = st_ >= k_slices ? 1 : 0;                                  \
         const int64_t kb_ = (int64_t)(st_ - src_ * k_slices) * 64;                 \
         const char* Ab_ = (const char*)(src_ ? a.A[1] : a.A[0]) + kb_;             \
         const char* Bb_ = (const char*)(src_ ? a.Bt[1] : a.Bt[0]) + kb_;           \
-        S##a0 = *(const u32x4*)(Ab_ + ao0);                                        \
-        S##a1 = *(const u32x4*)(Ab_ + ao1);                                        \
-        S##b0 = *(const u32x4*)(Bb_ + bo0);                                        \
-        if (B_CH > 1) S##b1 = *(const u32x4*)(Bb_ + bo1);                          \
+        a##S##x0 = *(const u32x4*)(Ab_ + ao0);                                     \
+        a##S##x1 = *(const u32x4*)(Ab_ + ao1);                                     \
+        b##S##x0 = *(const u32x4*)(Bb_ + bo0);                                     \
+        if (B_CH > 1) b##S##x1 = *(const u32x4*)(Bb_ + bo1);                       \
         if (B_CH > 2) {                                                            \
-            S##b2 = *(const u32x4*)(Bb_ + bo2);                                    \
-            S##b3 = *(const u32x4*)(Bb_ + bo3);                                    \
+            b##S##x2 = *(const u32x4*)(Bb_ + bo2);                                 \
+            b##S##x3 = *(const u32x4*)(Bb_ + bo3);                                 \
         }                                                                          \
     }
 #define GNN_STASH(buf_, S)                                                         \
     {                                                                              \
-        *(u32x4*)&(buf_)[st_off] = S##a0;                                          \
-        *(u32x4*)&(buf_)[1024 + st_off] = S##a1;                                   \
-        *(u32x4*)&(buf_)[BM * 16 + st_off] = S##b0;                                \
-        if (B_CH > 1) *(u32x4*)&(buf_)[BM * 16 + 1024 + st_off] = S##b1;           \
+        *(u32x4*)&(buf_)[st_off] = a##S##x0;                                       \
+        *(u32x4*)&(buf_)[1024 + st_off] = a##S##x1;                                \
+        *(u32x4*)&(buf_)[BM * 16 + st_off] = b##S##x0;                             \
+        if (B_CH > 1) *(u32x4*)&(buf_)[BM * 16 + 1024 + st_off] = b##S##x1;        \
         if (B_CH > 2) {                                                            \
-            *(u32x4*)&(buf_)[BM * 16 + 2048 + st_off] = S##b2;                     \
-            *(u32x4*)&(buf_)[BM * 16 + 3072 + st_off] = S##b3;                     \
+            *(u32x4*)&(buf_)[BM * 16 + 2048 + st_off] = b##S##x2;                  \
+            *(u32x4*)&(buf_)[BM * 16 + 3072 + st_off] = b##S##x3;                  \
         }                                                                          \
     }
-    // fragment addresses: row (.. + li), chunk g*2+q
+    // fragments: row (.. + li), chunk g*2+q of the slice
     const int sw = (li >> 1) & 3;
     const int fa_off = (wm * 64 + li) * 16, fb_off = BM * 16 + (wn * WTN + li) * 16;
-    auto compute = [&](const uint32_t* buf) {
+    const int slot0 = ((g * 2) ^ sw) << 2, slot1 = ((g * 2 + 1) ^ sw) << 2;
+#define GNN_READ(F, buf_, slot_)                                                   \
+    {                                                                              \
+        F##a0 = *(const u32x4*)&(buf_)[fa_off + (slot_)];                          \
+        F##a1 = *(const u32x4*)&(buf_)[fa_off + 512 + (slot_)];                    \
+        F##b0 = *(const u32x4*)&(buf_)[fb_off + (slot_)];                          \
+        if (NT > 1) F##b1 = *(const u32x4*)&(buf_)[fb_off + 512 + (slot_)];        \
+        if (NT > 2) {                                                              \
+            F##b2 = *(const u32x4*)&(buf_)[fb_off + 1024 + (slot_)];               \
+            F##b3 = *(const u32x4*)&(buf_)[fb_off + 1536 + (slot_)];               \
+        }                                                                          \
+    }
+    auto mma = [&](v16f& c, const u32x4& x, const u32x4& y) {
+        if (DT == GNN_F32) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int slot = ((g * 2 + q) ^ sw) << 2;
-            uint4 fa[MT], fb[NT];
-#pragma unroll
-            for (int i = 0; i < MT; ++i) fa[i] = *(const uint4*)&buf[fa_off + i * 512 + slot];
-#pragma unroll
-            for (int j = 0; j < NT; ++j) fb[j] = *(const uint4*)&buf[fb_off + j * 512 + slot];
-            if (DT == GNN_F32) {
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int i = 0; i < MT; ++i)
-#pragma unroll
-                        for (int j = 0; j < NT; ++j) {
-                            const uint32_t av = t == 0 ? fa[i].x : (t == 1 ? fa[i].y : (t == 2 ? fa[i].z : fa[i].w));
-                            const uint32_t bv = t == 0 ? fb[j].x : (t == 1 ? fb[j].y : (t == 2 ? fb[j].z : fb[j].w));
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av), __uint_as_float(bv), acc[i][j], 0, 0, 0);
-                        }
-            } else {
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-#pragma unroll
-                    for (int j = 0; j < NT; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fa[i]), __builtin_bit_cast(v8bf, fb[j]),
-                                                                             acc[i][j], 0, 0, 0);
-            }
+            for (int t = 0; t < 4; ++t) c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(x[t]), __uint_as_float(y[t]), c, 0, 0, 0);
+        } else {
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, x), __builtin_bit_cast(v8bf, y), c, 0, 0, 0);
         }
     };
-
+#define GNN_MMA(F)                                                                 \
+    {                                                                              \
+        mma(acc[0][0], F##a0, F##b0);                                              \
+        mma(acc[1][0], F##a1, F##b0);                                              \
+        if (NT > 1) {                                                              \
+            mma(acc[0][NT > 1 ? 1 : 0], F##a0, F##b1);                             \
+            mma(acc[1][NT > 1 ? 1 : 0], F##a1, F##b1);                             \
+        }                                                                          \
+        if (NT > 2) {                                                              \
+            mma(acc[0][NT > 2 ? 2 : 0], F##a0, F##b2);                             \
+            mma(acc[1][NT > 2 ? 2 : 0], F##a1, F##b2);                             \
+            mma(acc[0][NT > 2 ? 3 : 0], F##a0, F##b3);                             \
+            mma(acc[1][NT > 2 ? 3 : 0], F##a1, F##b3);                             \
+        }                                                                          \
+    }
+// One step on slice s_ (in ring buffer bufc_).  The second half of the previous slice is still waiting in f1: its
+// MFMAs run while the first half of this slice comes from LDS, and the MFMAs of the first half run while the second
+// half comes - LDS latency is hidden inside one wave.  Nothing here is conditional: with branches around the loads
+// or the LDS writes the compiler's wait-counter tracking loses the order of the outstanding loads.
+#define GNN_STEP(s_, bufc_, bufn_, SF, SS)                                         \
+    {                                                                              \
+        GNN_READ(f0, bufc_, slot0)                                                 \
+        GNN_FETCH(SF, (s_) + 2)                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_MMA(f1)                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_READ(f1, bufc_, slot1)                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_MMA(f0)                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_STASH(bufn_, SS)                                                       \
+        __syncthreads();                                                           \
+    }
     uint32_t* buf0 = smem;
     uint32_t* buf1 = smem + BUF;
-    // invariant at the top of an iteration for slice s: ring buffer s%2 holds slice s (visible to all waves),
-    // register set (s+1)%2 holds slice s+1 (possibly still in flight), register set s%2 is free
-    GNN_FETCH(p, 0);
-    if (n_steps > 1) GNN_FETCH(q, 1);
-    GNN_STASH(buf0, p);
+    // invariant at the top of step s: ring buffer s%2 holds slice s (visible to all waves), register set (s+1)%2 holds
+    // slice s+1 (possibly still in flight), register set s%2 is free, f1 holds the second half of slice s-1 (zeros at first)
+    GNN_FETCH(0, 0)
+    GNN_FETCH(1, 1)
+    GNN_STASH(buf0, 0)
     __syncthreads();
-    for (int step = 0; step < n_steps; step += 2) {
-        if (step + 2 < n_steps) GNN_FETCH(p, step + 2);
-        compute(buf0);
-        if (step + 1 < n_steps) GNN_STASH(buf1, q);
-        __syncthreads();
-        if (step + 1 < n_steps) {
-            if (step + 3 < n_steps) GNN_FETCH(q, step + 3);
-            compute(buf1);
-            if (step + 2 < n_steps) GNN_STASH(buf0, p);
-            __syncthreads();
-        }
+    const int n_pairs = n_steps >> 1;
+    for (int pr = 0; pr < n_pairs; ++pr) {
+        const int step = pr << 1;
+        GNN_STEP(step, buf0, buf1, 0, 1)
+        GNN_STEP(step + 1, buf1, buf0, 1, 0)
     }
+    if (n_steps & 1) GNN_STEP(n_steps - 1, buf0, buf1, 0, 1)
+    GNN_MMA(f1)
 #undef GNN_FETCH
 #undef GNN_STASH
+#undef GNN_READ
+#undef GNN_MMA
+#undef GNN_STEP
 
     // Epilogue.  acc[i][j][r] is C[row (r/4)*8 + g*4 + r%4][column li] of its 32x32 block: a piece of 32 rows x CW
     // columns is laid out row-major in the wave's part of LDS (bias, ReLU and rounding applied) and written with
