@@ -26,6 +26,14 @@ namespace gnnhot {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+// ds_read_b64_tr_b16: every lane hands in the LDS address of four 16-bit elements; within each group of 16 lanes
+// the 16 x 4 block is transposed (lane j receives element j%4 of the lanes 4e + j/4, e = 0..3).
+__device__ __forceinline__ v4s lds_tr16(const uint16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3)))*)p);
+}
 
 #ifndef GNN_NT_PF_BF16
 #define GNN_NT_PF_BF16 2
@@ -646,7 +654,9 @@ __global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
     constexpr int D_VPR = BN / EPV;
     constexpr int A_CH = BMR * A_VPR / 256;          // vectors per thread
     constexpr int D_CH = (BMR * D_VPR + 255) / 256;
-    constexpr int A_LDW = BKO * DTy<DT>::ES / 4, D_LDW = BN * DTy<DT>::ES / 4;  // LDS row strides in words
+    // LDS row strides in words: 32 bytes of padding put the four rows that one 16-lane group of a transpose read
+    // touches into different bank groups
+    constexpr int A_LDW = BKO * DTy<DT>::ES / 4 + 8, D_LDW = BN * DTy<DT>::ES / 4 + 8;
     __shared__ uint32_t sA[BMR * A_LDW];
     __shared__ uint32_t sD[BMR * D_LDW];
 
@@ -743,33 +753,30 @@ __global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], dv[j], acc[i][j], 0, 0, 0);
             }
         } else {
-            // step s (0, 1) multiplies tile rows s*16 + g*8 + e, e = 0..7, gathered down a column
-            const uint16_t* hA = (const uint16_t*)sA;
-            const uint16_t* hD = (const uint16_t*)sD;
+            // Step s (0, 1) multiplies tile rows s*16 + g*8 + e, e = 0..7: lane (li, g) needs those eight rows of
+            // ONE column, and the tiles are row-major.  The LDS transpose read of gfx950 does that gather: in every
+            // group of 16 lanes, lane 4e+q hands in the address of four consecutive columns (4q..4q+3) of row e and
+            // lane j gets back column j of rows 0..3 (measured: result[j][e] = source[4e + j/4][j%4]).  Two reads
+            // (rows +0..3, +4..7) make one operand.
+            const int tl = lane & 15, tb = lane >> 4;              // lane within its group, group
+            const int t_row = (tb >> 1) * 8 + (tl >> 2);           // g*8 + e
+            const int t_col = (tb & 1) * 16 + (tl & 3) * 4;        // first of the four columns, inside the 32-column block
+            const uint16_t* hA = (const uint16_t*)sA + t_row * (A_LDW * 2) + wk * WTK + t_col;
+            const uint16_t* hD = (const uint16_t*)sD + t_row * (D_LDW * 2) + wn * WTN + t_col;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                uint4 av[MT], dv[NT];
+                v8s av[MT], dv[NT];
 #pragma unroll
                 for (int i = 0; i < MT; ++i) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int r0 = s * 16 + g * 8 + 2 * e;
-                        const int col = wk * WTK + i * 32 + li;
-                        w[e] = (uint32_t)hA[r0 * (A_LDW * 2) + col] | ((uint32_t)hA[(r0 + 1) * (A_LDW * 2) + col] << 16);
-                    }
-                    av[i] = make_uint4(w[0], w[1], w[2], w[3]);
+                    const v4s lo = lds_tr16(hA + (s * 16) * (A_LDW * 2) + i * 32);
+                    const v4s hi = lds_tr16(hA + (s * 16 + 4) * (A_LDW * 2) + i * 32);
+                    av[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 }
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int r0 = s * 16 + g * 8 + 2 * e;
-                        const int col = wn * WTN + j * 32 + li;
-                        w[e] = (uint32_t)hD[r0 * (D_LDW * 2) + col] | ((uint32_t)hD[(r0 + 1) * (D_LDW * 2) + col] << 16);
-                    }
-                    dv[j] = make_uint4(w[0], w[1], w[2], w[3]);
+                    const v4s lo = lds_tr16(hD + (s * 16) * (D_LDW * 2) + j * 32);
+                    const v4s hi = lds_tr16(hD + (s * 16 + 4) * (D_LDW * 2) + j * 32);
+                    dv[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 }
 #pragma unroll
                 for (int i = 0; i < MT; ++i)
