@@ -156,7 +156,7 @@ def main():
         gdeg = None
         if w.model == "gcn":
             gdeg = dev(w.global_graph.degrees().astype(np.int32))[l2g.long()]
-        model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg)
+        model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg, prefix_numbered=True)
         # the host partition numbers its vertices by ascending id; its feature rows are permuted into ring order
         pos = torch.from_numpy(np.searchsorted(part.local_to_global, l2g.cpu().numpy().astype(np.int64)).astype(np.int32)).cuda()
         H0d = torch.zeros(n, ld0, dtype=dtype, device="cuda")
@@ -166,7 +166,8 @@ def main():
         G = sampled_graph if sampled_graph is not None else P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
         GT = G if part.graph_t is part.graph else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
         model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=dtype,
-                            global_degree=dev(part.global_degree) if w.model == "gcn" else None)
+                            global_degree=dev(part.global_degree) if w.model == "gcn" else None,
+                            prefix_numbered=sampled_graph is not None)   # the GPU extraction numbers by (distance, id)
         model.set_input(dev(H0).to(dtype))
     labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
     log(f"[bench] partition: n={n} nnz={part.graph.nnz} |T|={len(part.targets)} model={w.model} dims={w.dims} dtype={w.dtype}")
@@ -248,10 +249,20 @@ def main():
         tf, tb = call_ms.get(f"linear_fwd_{l}", 0.0) * 1e-3, call_ms.get(f"linear_bwd_{l}", 0.0) * 1e-3
         peak = MFMA_PEAK_TFLOPS[w.dtype]
         b_fwd = nl * (K * srcs + N) * es
+        # backward: dH and H in, dZ written and read back by both products, the layer inputs in, their gradients out
+        b_bwd = nl * (2 * N + 3 * N + K * srcs) * es + (nl * K * srcs * es if l > 1 else 0)
+        # the roof that binds a product this skinny: the slower of "operands at the HBM peak" and "flops at the MFMA peak"
+        roof_f = max(b_fwd / (HBM_PEAK_GBS * 1e9), f_fwd / (peak * 1e12))
+        roof_b = max(b_bwd / (HBM_PEAK_GBS * 1e9), f_bwd / (peak * 1e12))
         gemm[str(l)] = {"M": nl, "K": K * srcs, "N": N,
                         "fwd_TFLOPs": f_fwd / tf / 1e12 if tf > 0 else None, "fwd_frac_mfma": f_fwd / tf / 1e12 / peak if tf > 0 else None,
                         "fwd_GBs": b_fwd / tf / 1e9 if tf > 0 else None,
-                        "bwd_TFLOPs": f_bwd / tb / 1e12 if tb > 0 else None, "bwd_frac_mfma": f_bwd / tb / 1e12 / peak if tb > 0 else None}
+                        "fwd_binds": "hbm" if b_fwd / (HBM_PEAK_GBS * 1e9) > f_fwd / (peak * 1e12) else "mfma",
+                        "fwd_frac_roof": roof_f / tf if tf > 0 else None,
+                        "bwd_TFLOPs": f_bwd / tb / 1e12 if tb > 0 else None, "bwd_frac_mfma": f_bwd / tb / 1e12 / peak if tb > 0 else None,
+                        "bwd_GBs": b_bwd / tb / 1e9 if tb > 0 else None,
+                        "bwd_binds": "hbm" if b_bwd / (HBM_PEAK_GBS * 1e9) > f_bwd / (peak * 1e12) else "mfma",
+                        "bwd_frac_roof": roof_b / tb if tb > 0 else None}
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

@@ -27,11 +27,15 @@ class MaskedGNN:
     params           list of dicts with float32 device tensors W_neigh [K,N], W_self (sage), bias [N]
     dtype            torch.float32 or torch.bfloat16 (storage of activations and weights)
     global_degree    int32 device tensor: row lengths in the unpartitioned graph (GCN normalisation)
+    prefix_numbered  the caller's promise that the vertices are numbered by (distance from the targets, id), as
+                     gnn_extract_partition numbers them: every R_l is then the id range 0 .. |R_l|-1 and the calls
+                     get rows = NULL instead of an id list (checked once, when the active sets are first built)
     """
 
     def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, kind: str, params: list,
-                 dtype=torch.float32, global_degree: torch.Tensor | None = None):
+                 dtype=torch.float32, global_degree: torch.Tensor | None = None, prefix_numbered: bool = False):
         assert kind in ("gcn", "sage")
+        self.prefix_numbered, self._prefix_checked = prefix_numbered, False
         self.g, self.gt, self.targets, self.kind, self.dtype = graph, graph_t, targets, kind, dtype
         self.n = graph.n_rows
         self.L = len(params)
@@ -82,6 +86,13 @@ class MaskedGNN:
             self.rs, self.cs = s, s
         else:
             self.rs, self.cs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr), None
+        if self.prefix_numbered and not self._prefix_checked:
+            n_all = int(self.hop[-1])
+            ident = torch.arange(n_all, dtype=torch.int32, device=self.ring_ids.device)
+            if not torch.equal(self.ring_ids[:n_all], ident):
+                raise ValueError("prefix_numbered was promised but the ring-sorted ids are not 0 .. n-1")
+            self._prefix_checked = True
+        self.rows = None if self.prefix_numbered else self.ring_ids
         return self.hop
 
     def n_rows_of_layer(self, l: int) -> int:
@@ -99,11 +110,11 @@ class MaskedGNN:
             p = self.params[l - 1]
             K = self.dims[l - 1]
             nl = self.n_rows_of_layer(l)
-            self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, self.g, self.ring_ids, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs, ws=self.ws)
-            self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.ring_ids, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
+            self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, self.g, self.rows, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs, ws=self.ws)
+            self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
                              p["W_neigh"], p.get("W_self"), p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
         nt = self.n_rows_of_layer(self.L)
-        self._call("softmax_ce", B.gnn_softmax_ce, self.ring_ids, nt, self.H[self.L], self.dims[self.L], labels, self.dH[self.L], self.loss, ws=self.ws)
+        self._call("softmax_ce", B.gnn_softmax_ce, self.rows, nt, self.H[self.L], self.dims[self.L], labels, self.dH[self.L], self.loss, ws=self.ws)
         return self.loss
 
     # -- steps a5, a6 --------------------------------------------------------------------
@@ -115,7 +126,7 @@ class MaskedGNN:
             nl = self.n_rows_of_layer(l)
             sage = self.kind == "sage"
             need_in = l > 1
-            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.ring_ids, nl, self.dH[l], self.H[l] if l < L else None, l < L, self.A[l],
+            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], self.H[l] if l < L else None, l < L, self.A[l],
                              self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
                              gr["dW_neigh"], gr.get("dW_self"), gr["dbias"],
                              self.dA[l] if need_in else None, self.dH[l - 1] if (need_in and sage) else None, ws=self.ws)
@@ -127,13 +138,13 @@ class MaskedGNN:
                 ws_bwd = self.ws if 4 * nl >= self.n else None
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
-                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
                                           self.rs, self.cs, accumulate=True, ws=ws_bwd)
                     if n_prev > nl:
                         self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
                                               self.dH[l - 1], K, self.rs, self.cs, accumulate=False, ws=ws_bwd)
                 else:
-                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
                                           self.rs, self.cs, accumulate=False, ws=ws_bwd)
         return self.grads
 
