@@ -915,21 +915,21 @@ __global__ __launch_bounds__(256) void dz_kernel(const int32_t* __restrict__ row
     }
 }
 
-// out[n] = sum over the partial rows, in a fixed order: 8 row lanes x 32 columns per workgroup.
-__global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ part, int32_t n_blocks, int32_t N,
-                                                          float* __restrict__ out) {
-    __shared__ float s_sum[8][32];
+// out[n] = sum over the partial rows, in a fixed order: 32 row lanes x 32 columns per workgroup.
+__global__ __launch_bounds__(1024) void reduce_rows_kernel(const float* __restrict__ part, int32_t n_blocks, int32_t N,
+                                                           float* __restrict__ out) {
+    __shared__ float s_sum[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int n = blockIdx.x * 32 + tx;
     float s = 0.f;
     if (n < N)
-        for (int32_t b = ty; b < n_blocks; b += 8) s += part[(int64_t)b * N + n];
+        for (int32_t b = ty; b < n_blocks; b += 32) s += part[(int64_t)b * N + n];
     s_sum[ty][tx] = s;
     __syncthreads();
     if (ty == 0 && n < N) {
         float t = 0.f;
 #pragma unroll
-        for (int y = 0; y < 8; ++y) t += s_sum[y][tx];
+        for (int y = 0; y < 32; ++y) t += s_sum[y][tx];
         out[n] = t;
     }
 }
@@ -970,7 +970,7 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
     const int io_vec = vec_ok(dH, ld_out, ES) && (!relu || vec_ok(H, ld_out, ES));
     dz_kernel<DT><<<n_part, 256, 0, stream>>>(rows, M, dH, H, ld_out, io_vec, relu, N, dZ, ldz, part, cx);
     GNN_LAUNCH_CHECK("dz_kernel");
-    reduce_rows_kernel<<<(N + 31) / 32, 256, 0, stream>>>(part, n_part, N, dbias);
+    reduce_rows_kernel<<<(N + 31) / 32, 1024, 0, stream>>>(part, n_part, N, dbias);
     GNN_LAUNCH_CHECK("reduce_rows_kernel");
 
     GemmTN t;

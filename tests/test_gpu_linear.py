@@ -134,6 +134,28 @@ def test_softmax_cross_entropy(dtype, C):
     assert (got[rest] == sent).all() and (got[:, C:] == sent).all()
 
 
+def test_softmax_cross_entropy_many_rows_and_tiny_class_counts():
+    """More rows than one sweep of the launch covers; class counts below the lane-group width and C = 1."""
+    import paper_2311_06837_amd as P
+    for C, nt, dtype in ((32, 300001, torch.bfloat16), (5, 70001, torch.float32), (1, 100, torch.float32), (64, 3, torch.float32)):
+        print(f"softmax-ce: C={C} rows={nt} {dtype}", flush=True)
+        rng = np.random.default_rng(C + nt)
+        Z = as_stored(rng.standard_normal((nt, C)) * 2, dtype)
+        y = rng.integers(0, C, nt).astype(np.int32)
+        ld = _pad(C, 8)
+        Zd = padded(Z, ld, dtype, fill=float("nan") if ld > C else 0.0)
+        dZd = torch.full((nt, ld), SENT, dtype=dtype, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        P.gnn_softmax_ce(None, nt, Zd, C, dev(y), dZd, loss)
+        torch.cuda.synchronize()
+        dZ = np.zeros((nt, C))
+        want = oracle.softmax_ce(np.arange(nt, dtype=np.int32), Z, C, y, dZ)
+        assert abs(loss.item() - want) <= 1e-4 * max(abs(want), 1e-6)
+        got = host64(dZd)
+        check(got[:, :C], dZ, dtype, "dZ")
+        assert (got[:, C:] == host64(torch.tensor(SENT, dtype=dtype))).all()
+
+
 def test_norm_scales():
     import paper_2311_06837_amd as P
     deg = np.array([0, 1, 2, 3, 4, 9, 490, 10520], dtype=np.int32)
