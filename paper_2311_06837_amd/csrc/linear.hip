@@ -383,7 +383,23 @@ __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) 
 // rows and a reduction length that is a multiple of the slice; rows beyond M and columns beyond N
 // are computed from clamped addresses and discarded.
 // ------------------------------------------------------------------------------------------
-template <int DT, int NTW>
+// keeps the first n_valid elements of a 16-byte chunk, zeroes the rest (n_valid <= 0: all of it)
+template <int DT>
+__device__ __forceinline__ u32x4 mask_chunk(u32x4 r, int n_valid) {
+    if (DT == GNN_F32) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) r[t] = n_valid > t ? r[t] : 0u;
+    } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) r[t] &= (n_valid > 2 * t ? 0xffffu : 0u) | (n_valid > 2 * t + 1 ? 0xffff0000u : 0u);
+    }
+    return r;
+}
+
+// KTAIL: the reduction length is not a multiple of the slice.  The last slice of every source is then cut: chunks
+// that start at or beyond K are read from the start of their row instead (always addressable) and every chunk is
+// masked to its valid elements when it is moved to LDS, so neither padding nor a neighbouring row reaches the MFMAs.
+template <int DT, int NTW, bool KTAIL>
 __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
     constexpr int BM = 128, BN = 64 * NTW, MT = 2, NT = NTW, WTN = 32 * NTW;
     constexpr int ES = DTy<DT>::ES, EPV = DTy<DT>::EPV;
@@ -408,11 +424,11 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
     auto a_row = [&](int c) -> int64_t {
         const int m = m0 + ld_row + 64 * c;
         const int64_t r = m < a.M ? (a.a_rows ? (int64_t)a.a_rows[m] : (int64_t)m) : (a.a_rows ? (int64_t)a.a_rows[0] : 0);
-        return (r * a.lda + ld_c * EPV) * ES;
+        return (r * a.lda + (KTAIL ? 0 : ld_c * EPV)) * ES;
     };
     auto b_row = [&](int c) -> int64_t {
         const int n = n0 + ld_row + 64 * c;
-        return ((int64_t)(n < a.N ? n : 0) * a.ldb + ld_c * EPV) * ES;
+        return ((int64_t)(n < a.N ? n : 0) * a.ldb + (KTAIL ? 0 : ld_c * EPV)) * ES;
     };
     const int64_t ao0 = a_row(0), ao1 = a_row(1);
     const int64_t bo0 = b_row(0), bo1 = B_CH > 1 ? b_row(1) : 0, bo2 = B_CH > 2 ? b_row(2) : 0, bo3 = B_CH > 2 ? b_row(3) : 0;
@@ -425,7 +441,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int k_slices = a.K / EPS;
+    const int k_slices = KTAIL ? (a.K + EPS - 1) / EPS : a.K / EPS;
     const int n_steps = k_slices * a.n_src;
     // Everything that lives across steps is a plain variable filled and drained by macros (arrays handed to
     // helper functions ended up in scratch memory).  Two register sets (0, 1) hold the slices in flight from
@@ -439,7 +455,9 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
     {                                                                              \
         const int st_ = (step_) < n_steps ? (step_) : n_steps - 1;                 \
         const int src_ = st_ >= k_slices ? 1 : 0;                                  \
-        const int64_t kb_ = (int64_t)(st_ - src_ * k_slices) * 64;                 \
+        const int sl_ = st_ - src_ * k_slices;                                     \
+        int64_t kb_ = (int64_t)sl_ * 64;                                           \
+        if (KTAIL) kb_ = a.K - (sl_ * EPS + ld_c * EPV) > 0 ? kb_ + ld_c * 16 : 0; \
         const char* Ab_ = (const char*)(src_ ? a.A[1] : a.A[0]) + kb_;             \
         const char* Bb_ = (const char*)(src_ ? a.Bt[1] : a.Bt[0]) + kb_;           \
         a##S##x0 = *(const u32x4*)(Ab_ + ao0);                                     \
@@ -451,8 +469,20 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
             b##S##x3 = *(const u32x4*)(Bb_ + bo3);                                 \
         }                                                                          \
     }
-#define GNN_STASH(buf_, S)                                                         \
+#define GNN_STASH(buf_, S, step_)                                                  \
     {                                                                              \
+        if (KTAIL) {                                                               \
+            const int st_ = (step_) < n_steps ? (step_) : n_steps - 1;             \
+            const int nv_ = a.K - ((st_ - (st_ >= k_slices ? k_slices : 0)) * EPS + ld_c * EPV); \
+            a##S##x0 = mask_chunk<DT>(a##S##x0, nv_);                              \
+            a##S##x1 = mask_chunk<DT>(a##S##x1, nv_);                              \
+            b##S##x0 = mask_chunk<DT>(b##S##x0, nv_);                              \
+            if (B_CH > 1) b##S##x1 = mask_chunk<DT>(b##S##x1, nv_);                \
+            if (B_CH > 2) {                                                        \
+                b##S##x2 = mask_chunk<DT>(b##S##x2, nv_);                          \
+                b##S##x3 = mask_chunk<DT>(b##S##x3, nv_);                          \
+            }                                                                      \
+        }                                                                          \
         *(u32x4*)&(buf_)[st_off] = a##S##x0;                                       \
         *(u32x4*)&(buf_)[1024 + st_off] = a##S##x1;                                \
         *(u32x4*)&(buf_)[BM * 16 + st_off] = b##S##x0;                             \
@@ -515,7 +545,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
         __builtin_amdgcn_sched_barrier(0);                                         \
         GNN_MMA(f0)                                                                \
         __builtin_amdgcn_sched_barrier(0);                                         \
-        GNN_STASH(bufn_, SS)                                                       \
+        GNN_STASH(bufn_, SS, (s_) + 1)                                             \
         __syncthreads();                                                           \
     }
     uint32_t* buf0 = smem;
@@ -524,7 +554,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
     // slice s+1 (possibly still in flight), register set s%2 is free, f1 holds the second half of slice s-1 (zeros at first)
     GNN_FETCH(0, 0)
     GNN_FETCH(1, 1)
-    GNN_STASH(buf0, 0)
+    GNN_STASH(buf0, 0, 0)
     __syncthreads();
     const int n_pairs = n_steps >> 1;
     for (int pr = 0; pr < n_pairs; ++pr) {
@@ -597,15 +627,21 @@ static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
     if (a.M <= 0 || a.N <= 0) return GNN_OK;
     const int64_t tiles_m = ((int64_t)a.M + 127) / 128;
     const bool vec = a.a_vec && a.b_vec;  // both operands aligned: the branch-free loader
-    if (vec && a.N > 32 && a.K % (64 / DTy<DT>::ES) == 0 && a.K > 0) {
+    if (vec && a.N > 32 && a.K > 0) {
         // wide tile: the tile width that pads the output width least (256 on a tie)
         const int64_t p256 = ((int64_t)a.N + 255) / 256 * 256, p128 = ((int64_t)a.N + 127) / 128 * 128, p64 = ((int64_t)a.N + 63) / 64 * 64;
-        if (p256 <= p128 && p256 <= p64)
-            gemm_nt_wide_kernel<DT, 4><<<(unsigned)(tiles_m * (p256 / 256)), 256, 0, stream>>>(a);
-        else if (p128 <= p64)
-            gemm_nt_wide_kernel<DT, 2><<<(unsigned)(tiles_m * (p128 / 128)), 256, 0, stream>>>(a);
-        else
-            gemm_nt_wide_kernel<DT, 1><<<(unsigned)(tiles_m * (p64 / 64)), 256, 0, stream>>>(a);
+        const int ntw = (p256 <= p128 && p256 <= p64) ? 4 : (p128 <= p64 ? 2 : 1);
+        const unsigned grid = (unsigned)(tiles_m * (ntw == 4 ? p256 / 256 : (ntw == 2 ? p128 / 128 : p64 / 64)));
+        const bool ktail = a.K % (64 / DTy<DT>::ES) != 0;
+#define GNN_WIDE(NTW_)                                                                                  \
+    {                                                                                                   \
+        if (ktail) gemm_nt_wide_kernel<DT, NTW_, true><<<grid, 256, 0, stream>>>(a);                    \
+        else gemm_nt_wide_kernel<DT, NTW_, false><<<grid, 256, 0, stream>>>(a);                         \
+    }
+        if (ntw == 4) GNN_WIDE(4)
+        else if (ntw == 2) GNN_WIDE(2)
+        else GNN_WIDE(1)
+#undef GNN_WIDE
         GNN_LAUNCH_CHECK("gemm_nt_wide_kernel");
         return GNN_OK;
     }
