@@ -69,6 +69,9 @@ typedef struct gnn_csr {
     const int32_t *col_idx; /* device, [nnz], each in [0, n_cols) */
     int32_t flags;          /* OR of gnn_csr_flags; 0 promises nothing.  A promise that does not hold
                                gives wrong sums (never an out-of-bounds access). */
+    const uint32_t *edge_keep; /* device, nullable: one bit per entry of col_idx (bit p % 32 of word p / 32);
+                               entries whose bit is 0 are skipped by the aggregation calls - the per-layer mask of
+                               layer-wise sampling (section 5.2).  Read by gnn_masked_spmm_fwd / _bwd only. */
 } gnn_csr;
 
 int32_t gnn_version(void);
@@ -233,6 +236,33 @@ int32_t gnn_eas_traverse(const gnn_csr *g, const int32_t *targets, int32_t n_tar
                          int32_t fanout, int32_t rule, uint64_t seed,
                          int32_t *dist, int32_t *ring_ids, int64_t *hop_offsets, int64_t *hop_offsets_host,
                          void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Layer-wise sampling as a per-layer edge mask (section 5.2: for layer-wise sampling methods the maskings are
+ * generated per layer and the layer aggregates through them).  The one-hop graph stays as it is; layer `layer`
+ * keeps a subset of the entries of every listed row:
+ *   GNN_LAYER_MASK_THRESHOLD  entry (v <- u) is kept iff key(v, u) <= threshold (each edge on its own: a keep
+ *                             probability p is threshold = floor(p * 2^64) - 1; all ones keeps everything)
+ *   GNN_LAYER_MASK_FANOUT     a row keeps its min(fanout, length) entries with the smallest (key, id)
+ * key(v, u) = mix64(mix64(mix64(seed + layer) ^ v) ^ u), the seeded edge hash of gnn_sample_boundary.
+ * Outputs: edge_keep (bit p of the entry at position p of col_idx; words that hold bits of listed rows are
+ * written whole - clear the array before a call that lists only some rows), kept_len[v] (entries kept in row v,
+ * listed rows only; gnn_norm_scales(GNN_NORM_MEAN, kept_len) gives the mean over the kept neighbours).
+ * rows NULL => 0 .. n_active-1.  Rows must not repeat a column.  Bit-exact, independent of launch geometry.
+ */
+typedef enum gnn_layer_mask_rule { GNN_LAYER_MASK_THRESHOLD = 0, GNN_LAYER_MASK_FANOUT = 1 } gnn_layer_mask_rule;
+
+int32_t gnn_layer_edge_mask(const gnn_csr *g, const int32_t *rows, int32_t n_active, int32_t rule, int32_t fanout,
+                            uint64_t threshold, uint64_t seed, int32_t layer, uint32_t *edge_keep, int32_t *kept_len,
+                            void *stream);
+
+/*
+ * The same mask in the positions of the transposed graph, for the backward aggregation: bit q of keep_t (entry v
+ * of row u of gT) = bit p of keep, p = the position of u in row v of g.  Both graphs need GNN_CSR_SORTED_COLUMNS
+ * and rows without repeated columns; an entry of gT that g does not have gets 0.  keep_t: ceil(gT.nnz / 32) words,
+ * all written.
+ */
+int32_t gnn_transpose_edge_mask(const gnn_csr *g, const gnn_csr *gT, const uint32_t *keep, uint32_t *keep_t, void *stream);
 
 /*
  * Extraction of the partition's one-hop graph (section 6, figure 7c step 1: extract the multi-hop

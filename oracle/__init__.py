@@ -217,6 +217,62 @@ def eas_traverse(row_ptr, col_idx, targets, hops, fanout, rule, seed=0):
     return dist, ring[: off[-1]].copy(), off
 
 
+def keep_threshold(p: float) -> int:
+    """The 64-bit threshold that keeps an edge with probability p under the rule key <= threshold (p = 1: all ones)."""
+    assert 0.0 < p <= 1.0
+    return min((1 << 64) - 1, int(p * (1 << 64)) - 1) if p < 1.0 else (1 << 64) - 1
+
+
+def layer_edge_mask(row_ptr, col_idx, rows, rule, layer, seed=0, fanout=0, threshold=(1 << 64) - 1):
+    """Section 5.2: the mask of one layer over the one-hop graph.  rule "threshold" (every edge on its own, kept
+    iff its key <= threshold) or "fanout" (a row keeps its `fanout` entries with the smallest (key, id)).
+    -> keep uint8[nnz] (0 outside the listed rows), kept_len int32[n] (0 outside the listed rows)."""
+    row_ptr, col_idx, rows = _i32(row_ptr), _i32(col_idx), _i32(rows)
+    n = row_ptr.shape[0] - 1
+    n_active = rows.shape[0] if rows is not None else n
+    keep = np.zeros(max(col_idx.shape[0], 1), dtype=np.uint8)
+    kept_len = np.zeros(n, dtype=np.int32)
+    rc = lib().orc_layer_edge_mask(_p(row_ptr), _p(col_idx), _p(rows), C.c_int32(n_active), C.c_int32({"threshold": 0, "fanout": 1}[rule]),
+                                   C.c_int32(fanout), C.c_uint64(threshold), C.c_uint64(seed & (2**64 - 1)), C.c_int32(layer),
+                                   _p(keep), _p(kept_len))
+    if rc != 0:
+        raise ValueError("bad argument")
+    return keep[: col_idx.shape[0]], kept_len
+
+
+def transpose_mask(row_ptr, col_idx, keep, rpT, ciT):
+    """keep (positions of the graph) -> the same mask in the positions of the transposed graph."""
+    row_ptr, col_idx, rpT, ciT = _i32(row_ptr), _i32(col_idx), _i32(rpT), _i32(ciT)
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    out = np.zeros(max(ciT.shape[0], 1), dtype=np.uint8)
+    lib().orc_transpose_mask(_p(row_ptr), _p(col_idx), _p(keep), C.c_int32(rpT.shape[0] - 1), _p(rpT), _p(ciT), _p(out))
+    return out[: ciT.shape[0]]
+
+
+def spmm_fwd_em(row_ptr, col_idx, keep, rows, X, Y, F, rs=None, cs=None):
+    """spmm_fwd through a layer's edge mask (keep uint8[nnz])."""
+    row_ptr, col_idx, rows = _i32(row_ptr), _i32(col_idx), _i32(rows)
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    assert X.dtype == np.float64 and Y.dtype == np.float64 and X.flags.c_contiguous and Y.flags.c_contiguous
+    n_active = rows.shape[0] if rows is not None else row_ptr.shape[0] - 1
+    rs, cs = _f64(rs), _f64(cs)
+    lib().orc_spmm_fwd_em(_p(row_ptr), _p(col_idx), _p(keep), _p(rows), C.c_int32(n_active), _p(X), C.c_int64(X.shape[1]),
+                          _p(Y), C.c_int64(Y.shape[1]), C.c_int32(F), _p(rs), _p(cs))
+    return Y
+
+
+def spmm_bwd_em(row_ptr, col_idx, keep, rows, dY, dX, F, rs=None, cs=None):
+    """Adjoint of spmm_fwd_em; accumulates into dX."""
+    row_ptr, col_idx, rows = _i32(row_ptr), _i32(col_idx), _i32(rows)
+    keep = np.ascontiguousarray(keep, dtype=np.uint8)
+    assert dY.dtype == np.float64 and dX.dtype == np.float64 and dY.flags.c_contiguous and dX.flags.c_contiguous
+    n_active = rows.shape[0] if rows is not None else row_ptr.shape[0] - 1
+    rs, cs = _f64(rs), _f64(cs)
+    lib().orc_spmm_bwd_em(_p(row_ptr), _p(col_idx), _p(keep), _p(rows), C.c_int32(n_active), _p(dY), C.c_int64(dY.shape[1]),
+                          _p(dX), C.c_int64(dX.shape[1]), C.c_int32(F), _p(rs), _p(cs))
+    return dX
+
+
 def extract_from_ring(row_ptr, col_idx, ring):
     """The sub-graph induced by the listed vertices, renumbered in list order (section 5.3.1: a sub-graph is
     generated from the traversed vertices).  -> (local_row_ptr, local_col_idx)."""
@@ -289,9 +345,13 @@ class Model:
     bf16         round every stored tensor (inputs, A_l, H_l, W, and the
                  gradients dZ, dA, dH) to bfloat16
     all_rows     compute every row at every layer (the unmasked variant)
+    layer_sampling  None, or (rule, parameter, seed): layer-wise sampling as per-layer masking (section 5.2) -
+                 ("threshold", t, seed) or ("fanout", f, seed); layer l aggregates through layer_edge_mask(..., layer=l)
+                 over its rows R_l, and the mean is taken over the kept neighbours
     """
 
-    def __init__(self, row_ptr, col_idx, targets, kind, params, global_degree=None, bf16=False, all_rows=False):
+    def __init__(self, row_ptr, col_idx, targets, kind, params, global_degree=None, bf16=False, all_rows=False,
+                 layer_sampling=None):
         self.row_ptr, self.col_idx = _i32(row_ptr), _i32(col_idx)
         self.n = self.row_ptr.shape[0] - 1
         self.targets = _i32(targets)
@@ -314,6 +374,16 @@ class Model:
         else:
             self.rs, self.cs = norm_scales("mean", length), None
         self.all_rows = all_rows
+        self.keep, self.rs_l = None, None
+        if layer_sampling is not None:
+            rule, par, seed = layer_sampling
+            self.keep, self.rs_l = [None], [None]
+            for l in range(1, self.L + 1):
+                keep, kept_len = layer_edge_mask(self.row_ptr, self.col_idx, self.rows_of_layer(l), rule, l, seed,
+                                                 fanout=par if rule == "fanout" else 0,
+                                                 threshold=par if rule == "threshold" else (1 << 64) - 1)
+                self.keep.append(keep)
+                self.rs_l.append(self.rs if kind == "gcn" else norm_scales("mean", kept_len))
 
     def rows_of_layer(self, l: int) -> np.ndarray:
         """R_l = {dist <= L - l} as ring-sorted ids (l = 0 is the input set)."""
@@ -339,7 +409,10 @@ class Model:
                 assert (self.dist[need] >= 0).all() and (self.dist[need] <= self.L - l + 1).all()
             A = np.full((self.n, K), np.nan)
             assert self.H[l - 1].shape[1] == K
-            spmm_fwd(self.row_ptr, self.col_idx, rows, self.H[l - 1], A, K, self.rs, self.cs)
+            if self.keep is None:
+                spmm_fwd(self.row_ptr, self.col_idx, rows, self.H[l - 1], A, K, self.rs, self.cs)
+            else:
+                spmm_fwd_em(self.row_ptr, self.col_idx, self.keep[l], rows, self.H[l - 1], A, K, self.rs_l[l], self.cs)
             self._store(A)
             Hn = np.full((self.n, N), np.nan)
             Xs = self.H[l - 1] if self.kind == "sage" else None
@@ -375,6 +448,9 @@ class Model:
             if need_in:
                 self._store(dA)
                 dprev = dXs if dXs is not None else np.zeros((self.n, K))
-                spmm_bwd(self.row_ptr, self.col_idx, rows, dA, dprev, K, self.rs, self.cs)
+                if self.keep is None:
+                    spmm_bwd(self.row_ptr, self.col_idx, rows, dA, dprev, K, self.rs, self.cs)
+                else:
+                    spmm_bwd_em(self.row_ptr, self.col_idx, self.keep[l], rows, dA, dprev, K, self.rs_l[l], self.cs)
                 dH = self._store(dprev)
         return grads

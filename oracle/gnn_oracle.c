@@ -19,6 +19,8 @@
  *     the inner vertices, at most h hops outwards, at most f new vertices per
  *     traversed vertex and hop, preferring vertices with many connections to
  *     the vertices not selected so far;
+ *   - layer-wise sampling as per-layer masking (section 5.2): the one-hop
+ *     graph stays whole and every layer aggregates through its own edge mask;
  *   - extraction of the partition (section 6, step 1; section 5.3.1 "a
  *     subgraph is generated from the traversed vertices"): the vertices the
  *     traversal reached and every edge of the graph between two of them.
@@ -534,4 +536,115 @@ int orc_eas_traverse(int32_t n, const int32_t *row_ptr, const int32_t *col_idx,
     }
     free(cand); free(conn); free(was_selected);
     return 0;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Layer-wise sampling as per-layer masking (section 5.2: "for layer-wise   */
+/* samplings the maskings are generated per layer to conduct layer-wise     */
+/* aggregation of them").  The one-hop graph stays whole; layer `layer`     */
+/* aggregates only through the entries a rule keeps:                        */
+/*   rule 0  every entry (v <- u) on its own: kept iff key <= threshold     */
+/*   rule 1  a row keeps its min(fanout, length) entries with the smallest  */
+/*           (key, id)                                                      */
+/* with key = orc_edge_key(seed, v, u, layer).                              */
+/*   keep[e]      1/0 for every entry e of a listed row (others untouched)  */
+/*   kept_len[v]  kept entries of listed row v (others untouched)           */
+/* ---------------------------------------------------------------------- */
+int orc_layer_edge_mask(const int32_t *row_ptr, const int32_t *col_idx,
+                        const int32_t *rows, int32_t n_active, int32_t rule, int32_t fanout,
+                        uint64_t threshold, uint64_t seed, int32_t layer,
+                        uint8_t *keep, int32_t *kept_len)
+{
+    if ((rule != 0 && rule != 1) || fanout < 0) return 1;
+    orc_cand *cand = NULL;
+    int32_t cap = 0;
+    for (int32_t i = 0; i < n_active; ++i) {
+        const int32_t v = rows ? rows[i] : i;
+        const int32_t s = row_ptr[v], e = row_ptr[v + 1], len = e - s;
+        int32_t kept = 0;
+        if (rule == 0) {
+            for (int32_t p = s; p < e; ++p) {
+                keep[p] = orc_edge_key(seed, (uint64_t)v, (uint64_t)col_idx[p], (uint64_t)layer) <= threshold;
+                kept += keep[p];
+            }
+        } else {
+            if (len > cap) { cap = len; cand = (orc_cand *)realloc(cand, sizeof(orc_cand) * (size_t)cap); }
+            for (int32_t p = s; p < e; ++p) {
+                cand[p - s].key = orc_edge_key(seed, (uint64_t)v, (uint64_t)col_idx[p], (uint64_t)layer);
+                cand[p - s].u = col_idx[p];
+                keep[p] = 0;
+            }
+            qsort(cand, (size_t)len, sizeof(orc_cand), orc_cand_cmp);
+            kept = len < fanout ? len : fanout;
+            for (int32_t k = 0; k < kept; ++k)
+                for (int32_t p = s; p < e; ++p)
+                    if (col_idx[p] == cand[k].u) keep[p] = 1;
+        }
+        kept_len[v] = kept;
+    }
+    free(cand);
+    return 0;
+}
+
+/* The mask in the positions of the transposed graph: entry q of row u of   */
+/* (rpT, ciT) is the vertex v whose row lists u; keep_t[q] = keep[p] with p */
+/* the position of u in row v (0 if row v does not list u).                 */
+void orc_transpose_mask(const int32_t *row_ptr, const int32_t *col_idx, const uint8_t *keep,
+                        int32_t n_t, const int32_t *rpT, const int32_t *ciT, uint8_t *keep_t)
+{
+    for (int32_t u = 0; u < n_t; ++u)
+        for (int32_t q = rpT[u]; q < rpT[u + 1]; ++q) {
+            const int32_t v = ciT[q];
+            keep_t[q] = 0;
+            for (int32_t p = row_ptr[v]; p < row_ptr[v + 1]; ++p)
+                if (col_idx[p] == u) { keep_t[q] = keep[p]; break; }
+        }
+}
+
+/* orc_spmm_fwd / orc_spmm_bwd through a mask: the entries with keep[e] == 0 */
+/* do not exist for this layer.                                             */
+void orc_spmm_fwd_em(const int32_t *row_ptr, const int32_t *col_idx, const uint8_t *keep,
+                     const int32_t *rows, int32_t n_active,
+                     const double *X, int64_t ldx, double *Y, int64_t ldy, int32_t F,
+                     const double *rs, const double *cs)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int32_t i = 0; i < n_active; ++i) {
+        int32_t v = rows ? rows[i] : i;
+        double *y = Y + (int64_t)v * ldy;
+        for (int32_t f = 0; f < F; ++f) y[f] = 0.0;
+        for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+            if (!keep[e]) continue;
+            int32_t u = col_idx[e];
+            double w = cs ? cs[u] : 1.0;
+            const double *x = X + (int64_t)u * ldx;
+            for (int32_t f = 0; f < F; ++f) y[f] += w * x[f];
+        }
+        if (rs)
+            for (int32_t f = 0; f < F; ++f) y[f] *= rs[v];
+    }
+}
+
+void orc_spmm_bwd_em(const int32_t *row_ptr, const int32_t *col_idx, const uint8_t *keep,
+                     const int32_t *rows, int32_t n_active,
+                     const double *dY, int64_t lddy, double *dX, int64_t lddx, int32_t F,
+                     const double *rs, const double *cs)
+{
+    const int32_t CB = 16;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t f0 = 0; f0 < F; f0 += CB) {
+        int32_t f1 = f0 + CB < F ? f0 + CB : F;
+        for (int32_t i = 0; i < n_active; ++i) {
+            int32_t v = rows ? rows[i] : i;
+            const double *dy = dY + (int64_t)v * lddy;
+            double wv = rs ? rs[v] : 1.0;
+            for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                if (!keep[e]) continue;
+                int32_t u = col_idx[e];
+                double w = wv * (cs ? cs[u] : 1.0);
+                double *dx = dX + (int64_t)u * lddx;
+                for (int32_t f = f0; f < f1; ++f) dx[f] += w * dy[f];
+            }
+        }
+    }
 }

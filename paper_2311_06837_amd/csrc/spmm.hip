@@ -69,6 +69,7 @@ struct SpmmArgs {
     const float* nbr_scale;   // nullable, indexed by neighbour
     const int32_t* dist;      // nullable filter: keep u iff 0 <= dist[u] <= max_dist
     int32_t max_dist;
+    const uint32_t* edge_keep;  // nullable filter: keep the entry at position p iff bit p is set (layer-wise sampling mask)
     int32_t accumulate;
     int32_t rows_per_group;   // 1..kRowsPerGroup: rows of the list per LPR-lane group in one workgroup
     // column-blocked route only
@@ -182,6 +183,14 @@ __device__ __forceinline__ void store_part(float* p, int64_t off, const float (&
     } else {
         for (int k = 0; k < n_valid; ++k) p[off + k] = accumulate ? p[off + k] + v[k] : v[k];
     }
+}
+
+// The value the filter tests for the entry at position p with neighbour u: dist[u] (0 without a dist filter),
+// or -1 if the layer's edge mask drops the entry.
+__device__ __forceinline__ int32_t filter_probe(const SpmmArgs& a, int32_t u, int32_t p) {
+    int32_t d = a.dist ? a.dist[u] : 0;
+    if (a.edge_keep && !((a.edge_keep[p >> 5] >> (p & 31)) & 1u)) d = -1;
+    return d;
 }
 
 // Filter (backward: "was u an active row of the forward call"), compact and stage one tile of
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
     int32_t u_c = (have && pc + sl < ec) ? a.col_idx[pc + sl] : 0;
     int32_t u_n = (have_n && pn + sl < en) ? a.col_idx[pn + sl] : 0;
     int32_t d_c = 0;
-    if (FILTER) d_c = (have && pc + sl < ec) ? a.dist[u_c] : -1;
+    if (FILTER) d_c = (have && pc + sl < ec) ? filter_probe(a, u_c, pc + sl) : -1;
     while (__ballot(have) != 0ull) {  // uniform over the wave
         const bool row_done = have && pc + LPR >= ec;
         int jnn;
@@ -336,7 +345,7 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
         advance(jn, pn, en, have_n, jnn, pnn, enn, have_nn);
         const int32_t u_nn = (have_nn && pnn + sl < enn) ? a.col_idx[pnn + sl] : 0;  // two tiles ahead
         int32_t d_n = 0;
-        if (FILTER) d_n = (have_n && pn + sl < en) ? a.dist[u_n] : -1;               // one tile ahead
+        if (FILTER) d_n = (have_n && pn + sl < en) ? filter_probe(a, u_n, pn + sl) : -1;  // one tile ahead
 
         int left = have ? ec - pc : 0;
         left = left < 0 ? 0 : (left < LPR ? left : LPR);
@@ -389,7 +398,7 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
             int left = (int)((int64_t)he - p0 < 0 ? 0 : ((int64_t)he - p0 < LPR ? (int64_t)he - p0 : LPR));
             const int32_t u = sl < left ? a.col_idx[p0 + sl] : 0;
             int32_t d = 0;
-            if (FILTER) d = sl < left ? a.dist[u] : -1;
+            if (FILTER) d = sl < left ? filter_probe(a, u, (int32_t)(p0 + sl)) : -1;
             wave_lds_sync();
             const int cnt = commit_tile<LPR, FILTER>(a, sl < left, u, d, left, sub, sl, s_idx);
             int cnt_max = cnt;
@@ -929,6 +938,7 @@ static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, i
     // the stream kernel addresses the gathered matrix with 32-bit offsets in 16-byte units: 64 GB at most
     if ((int64_t)g->n_cols * row_bytes >= ((int64_t)1 << 36)) return p;
     if (!vec_ok || !(g->flags & GNN_CSR_SORTED_COLUMNS) || g->n_rows <= 0 || n_active < 4096) return p;
+    if (g->edge_keep != nullptr) return p;  // the per-layer edge mask is only known to the one-launch route
     const int64_t slab = (int64_t)g->n_cols * kSlabBytes;
     if (slab < (int64_t)GNN_SPMM_BLOCKED_MIN_SLAB) return p;
     const int passes = (int)((slab + kDies * (int64_t)GNN_SPMM_DIE_BYTES - 1) / (kDies * (int64_t)GNN_SPMM_DIE_BYTES));
@@ -1021,7 +1031,7 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     GNN_REQUIRE(ldx >= F && ldy >= F, GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
     const int ve = dtype == GNN_F32 ? 4 : 8;
     const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0;
-    const bool filter = dist != nullptr;
+    const bool filter = dist != nullptr || g->edge_keep != nullptr;
     BlockedPlan plan;
     if (ws_bytes != nullptr) {
         if (n_active > 0 && F > 0) plan = plan_blocked(g, n_active, F, ldx * (dtype == GNN_F32 ? 4 : 2), vec_ok, filter, nbr_scale != nullptr);
@@ -1046,7 +1056,8 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     SpmmArgs a;
     a.row_ptr = g->row_ptr; a.col_idx = g->col_idx; a.rows = rows; a.n_active = n_active;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
-    a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = max_dist;
+    a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = dist ? max_dist : INT32_MAX;
+    a.edge_keep = g->edge_keep;
     a.accumulate = accumulate;
     a.rows_per_group = 1;
     a.seg = nullptr; a.seg_end = nullptr; a.edge_w = nullptr; a.n_blocks = 0; a.block0 = 0;
