@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--extract-on-gpu", action="store_true",
                     help="build the partition on the GPU from the unpartitioned graph (active sets, extraction with "
                          "(distance, id) numbering, feature gather) instead of on the host; full-halo workloads only")
+    ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
+                    help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
+                         "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -169,6 +172,14 @@ def main():
                             global_degree=dev(part.global_degree) if w.model == "gcn" else None,
                             prefix_numbered=sampled_graph is not None)   # the GPU extraction numbers by (distance, id)
         model.set_input(dev(H0).to(dtype))
+    if args.layer_sampling:
+        f = args.layer_sampling.split(":")
+        seed_ls = int(f[2]) if len(f) > 2 else 1
+        if f[0] == "fanout":
+            model.layer_sampling = ("fanout", int(f[1]), seed_ls)
+        else:
+            pk = float(f[1])
+            model.layer_sampling = ("threshold", (1 << 64) - 1 if pk >= 1.0 else max(0, int(pk * (1 << 64)) - 1), seed_ls)
     labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
     log(f"[bench] partition: n={n} nnz={part.graph.nnz} |T|={len(part.targets)} model={w.model} dims={w.dims} dtype={w.dtype}")
 
@@ -293,6 +304,8 @@ def main():
         "partition_built_on": "gpu ((distance, id) numbering)" if (gpu_part is not None or sampled_graph is not None)
                               else "host (ascending-id numbering)",
         "aggregated_edges_per_step": total_edges,
+        "layer_sampling": args.layer_sampling,
+        "layer_mask_ms": sum(v for k, v in call_ms.items() if k.startswith("layer_mask")) if args.layer_sampling else None,
         "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,
         "call_ms": {k: round(v, 4) for k, v in call_ms.items()},
     }

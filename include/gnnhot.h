@@ -245,21 +245,33 @@ int32_t gnn_eas_traverse(const gnn_csr *g, const int32_t *targets, int32_t n_tar
  *                             probability p is threshold = floor(p * 2^64) - 1; all ones keeps everything)
  *   GNN_LAYER_MASK_FANOUT     a row keeps its min(fanout, length) entries with the smallest (key, id)
  * key(v, u) = mix64(mix64(mix64(seed + layer) ^ v) ^ u), the seeded edge hash of gnn_sample_boundary.
- * Outputs: edge_keep (bit p of the entry at position p of col_idx; words that hold bits of listed rows are
- * written whole - clear the array before a call that lists only some rows), kept_len[v] (entries kept in row v,
- * listed rows only; gnn_norm_scales(GNN_NORM_MEAN, kept_len) gives the mean over the kept neighbours).
+ * Outputs: edge_keep (ceil(nnz / 32) words, all written: bit p belongs to the entry at position p of col_idx, the
+ * bits of rows that are not listed are 0), kept_len[v] (entries kept in row v, listed rows only;
+ * gnn_norm_scales(GNN_NORM_MEAN, kept_len) gives the mean over the kept neighbours); optionally the threshold pair
+ * of every row (row_thr_key, row_thr_id: [n_rows] each, both or neither; an entry of row v is kept iff
+ * (key, id) <= (row_thr_key[v], row_thr_id[v]); rows that are not listed get a pair that keeps nothing), from
+ * which gnn_layer_edge_mask_transposed makes the backward mask.
  * rows NULL => 0 .. n_active-1.  Rows must not repeat a column.  Bit-exact, independent of launch geometry.
  */
 typedef enum gnn_layer_mask_rule { GNN_LAYER_MASK_THRESHOLD = 0, GNN_LAYER_MASK_FANOUT = 1 } gnn_layer_mask_rule;
 
 int32_t gnn_layer_edge_mask(const gnn_csr *g, const int32_t *rows, int32_t n_active, int32_t rule, int32_t fanout,
                             uint64_t threshold, uint64_t seed, int32_t layer, uint32_t *edge_keep, int32_t *kept_len,
-                            void *stream);
+                            uint64_t *row_thr_key, int32_t *row_thr_id, void *stream);
+
+/*
+ * The mask gnn_layer_edge_mask made for (seed, layer), in the positions of the transposed graph gT (the backward
+ * aggregation gathers over gT): entry (row u, column v) of gT is the forward entry (v <- u), kept iff
+ * (key(v, u), u) <= (row_thr_key[v], row_thr_id[v]).  keep_t: ceil(gT.nnz / 32) words, all written.  Same result
+ * as gnn_transpose_edge_mask on that mask, without the search.
+ */
+int32_t gnn_layer_edge_mask_transposed(const gnn_csr *gT, const uint64_t *row_thr_key, const int32_t *row_thr_id,
+                                       uint64_t seed, int32_t layer, uint32_t *keep_t, void *stream);
 
 /*
  * The same mask in the positions of the transposed graph, for the backward aggregation: bit q of keep_t (entry v
- * of row u of gT) = bit p of keep, p = the position of u in row v of g.  Both graphs need GNN_CSR_SORTED_COLUMNS
- * and rows without repeated columns; an entry of gT that g does not have gets 0.  keep_t: ceil(gT.nnz / 32) words,
+ * of row u of gT) = bit p of keep, p = the position of u in row v of g.  g needs GNN_CSR_SORTED_COLUMNS
+ * (only g's is used) and rows without repeated columns; an entry of gT that g does not have gets 0.  keep_t: ceil(gT.nnz / 32) words,
  * all written.
  */
 int32_t gnn_transpose_edge_mask(const gnn_csr *g, const gnn_csr *gT, const uint32_t *keep, uint32_t *keep_t, void *stream);

@@ -24,7 +24,8 @@ STATUS = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_SHAPE", 3: "GNN_ERR
 EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_scales", "gnn_masked_spmm_fwd",
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
-           "gnn_extract_sampled_partition", "gnn_eas_traverse"]
+           "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
+           "gnn_layer_edge_mask_transposed"]
 
 
 class GnnError(RuntimeError):
@@ -35,7 +36,7 @@ class GnnError(RuntimeError):
 
 class gnn_csr(C.Structure):
     _fields_ = [("n_rows", C.c_int32), ("n_cols", C.c_int32), ("nnz", C.c_int64),
-                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("flags", C.c_int32)]
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("flags", C.c_int32), ("edge_keep", C.c_void_p)]
 
 
 _lib = None
@@ -93,8 +94,11 @@ def _mat(t, name):
 class Graph:
     """Device CSR (int32) of a one-hop graph plus the host struct handed to the C ABI."""
 
-    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, n_cols: int | None = None, sorted_columns: bool = False):
-        """sorted_columns: the caller's promise that every row lists its columns in ascending order."""
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor, n_cols: int | None = None, sorted_columns: bool = False,
+                 edge_keep: torch.Tensor | None = None):
+        """sorted_columns: the caller's promise that every row lists its columns in ascending order.
+        edge_keep: optional int32 device tensor, one bit per entry of col_idx: the aggregation calls skip the
+        entries whose bit is 0 (per-layer mask of layer-wise sampling)."""
         _i32(row_ptr, "row_ptr"), _i32(col_idx, "col_idx")
         assert row_ptr.is_cuda and col_idx.is_cuda
         self.row_ptr, self.col_idx = row_ptr, col_idx
@@ -102,8 +106,16 @@ class Graph:
         self.n_cols = self.n_rows if n_cols is None else n_cols
         self.nnz = col_idx.numel()
         self.sorted_columns = bool(sorted_columns)
+        self.edge_keep = edge_keep
+        if edge_keep is not None:
+            assert edge_keep.is_cuda and edge_keep.dtype == torch.int32 and edge_keep.numel() * 32 >= self.nnz
         self.c = gnn_csr(self.n_rows, self.n_cols, self.nnz, row_ptr.data_ptr(), col_idx.data_ptr() if self.nnz else None,
-                         GNN_CSR_SORTED_COLUMNS if sorted_columns else 0)
+                         GNN_CSR_SORTED_COLUMNS if sorted_columns else 0,
+                         edge_keep.data_ptr() if edge_keep is not None else None)
+
+    def with_edge_keep(self, edge_keep: torch.Tensor | None) -> "Graph":
+        """The same graph (arrays shared) seen through a layer's edge mask."""
+        return Graph(self.row_ptr, self.col_idx, self.n_cols, self.sorted_columns, edge_keep)
 
     @staticmethod
     def from_numpy(row_ptr, col_idx, device="cuda", n_cols=None) -> "Graph":
@@ -177,6 +189,43 @@ def gnn_eas_traverse(g: Graph, targets: torch.Tensor, hops: int, fanout: int, ru
               _ptr(dist) if g.n_rows else None, _ptr(ring), _ptr(off), host),
              (_stream(),), ws)
     return dist, ring, off, (list(host) if sync else None)
+
+
+def gnn_layer_edge_mask(g: Graph, rows, n_active: int, rule: str, layer: int, seed: int = 0, fanout: int = 0,
+                        threshold: int = (1 << 64) - 1, with_thresholds: bool = False):
+    """rule "threshold" (an entry is kept iff its key <= threshold) or "fanout" (a row keeps its `fanout` entries with
+    the smallest (key, id)).  -> edge_keep int32[ceil(nnz / 32)] (bit p = entry p), kept_len int32[n_rows] (0 for rows
+    that are not listed) and, with_thresholds, the per-row threshold pairs (int64 keys, int32 ids)."""
+    dev = g.row_ptr.device
+    keep = torch.empty(max((g.nnz + 31) // 32, 1), dtype=torch.int32, device=dev)
+    kept_len = torch.zeros(max(g.n_rows, 1), dtype=torch.int32, device=dev)
+    thr_k = torch.empty(max(g.n_rows, 1), dtype=torch.int64, device=dev) if with_thresholds else None
+    thr_u = torch.empty(max(g.n_rows, 1), dtype=torch.int32, device=dev) if with_thresholds else None
+    assert rows is None or rows.numel() >= n_active
+    _check(lib().gnn_layer_edge_mask(C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active),
+                                     C.c_int32({"threshold": 0, "fanout": 1}[rule]), C.c_int32(fanout), C.c_uint64(threshold),
+                                     C.c_uint64(seed & (2 ** 64 - 1)), C.c_int32(layer), _ptr(keep), _ptr(kept_len),
+                                     _ptr(thr_k), _ptr(thr_u), _stream()))
+    if with_thresholds:
+        return keep, kept_len[: g.n_rows], thr_k, thr_u
+    return keep, kept_len[: g.n_rows]
+
+
+def gnn_layer_edge_mask_transposed(gT: Graph, thr_k: torch.Tensor, thr_u: torch.Tensor, layer: int, seed: int = 0) -> torch.Tensor:
+    """The layer's mask as a bit per entry of gT, from the threshold pairs of gnn_layer_edge_mask(with_thresholds=True)."""
+    assert thr_k.dtype == torch.int64 and thr_u.dtype == torch.int32 and thr_k.numel() >= gT.n_cols and thr_u.numel() >= gT.n_cols
+    keep_t = torch.empty(max((gT.nnz + 31) // 32, 1), dtype=torch.int32, device=thr_k.device)
+    _check(lib().gnn_layer_edge_mask_transposed(C.byref(gT.c), _ptr(thr_k), _ptr(thr_u), C.c_uint64(seed & (2 ** 64 - 1)),
+                                                C.c_int32(layer), _ptr(keep_t), _stream()))
+    return keep_t
+
+
+def gnn_transpose_edge_mask(g: Graph, gT: Graph, keep: torch.Tensor) -> torch.Tensor:
+    """keep (bit per entry of g) -> the same mask as a bit per entry of gT."""
+    assert keep.dtype == torch.int32 and keep.numel() * 32 >= g.nnz
+    keep_t = torch.empty(max((gT.nnz + 31) // 32, 1), dtype=torch.int32, device=keep.device)
+    _check(lib().gnn_transpose_edge_mask(C.byref(g.c), C.byref(gT.c), _ptr(keep), _ptr(keep_t), _stream()))
+    return keep_t
 
 
 def gnn_norm_scales(norm: int, n: int, length: torch.Tensor | None = None, row_ptr: torch.Tensor | None = None) -> torch.Tensor:

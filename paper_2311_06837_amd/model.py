@@ -30,11 +30,17 @@ class MaskedGNN:
     prefix_numbered  the caller's promise that the vertices are numbered by (distance from the targets, id), as
                      gnn_extract_partition numbers them: every R_l is then the id range 0 .. |R_l|-1 and the calls
                      get rows = NULL instead of an id list (checked once, when the active sets are first built)
+    layer_sampling   None, or (rule, parameter, seed): layer-wise sampling as per-layer masking - layer l aggregates
+                     through gnn_layer_edge_mask(rule, layer = l) over its rows, forward and backward; rule
+                     "threshold" (parameter = 64-bit key threshold) or "fanout" (parameter = neighbours kept per row).
+                     The masks are rebuilt in every step (a training run changes the seed per epoch).
     """
 
     def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, kind: str, params: list,
-                 dtype=torch.float32, global_degree: torch.Tensor | None = None, prefix_numbered: bool = False):
+                 dtype=torch.float32, global_degree: torch.Tensor | None = None, prefix_numbered: bool = False,
+                 layer_sampling=None):
         assert kind in ("gcn", "sage")
+        self.layer_sampling = layer_sampling
         self.prefix_numbered, self._prefix_checked = prefix_numbered, False
         self.g, self.gt, self.targets, self.kind, self.dtype = graph, graph_t, targets, kind, dtype
         self.n = graph.n_rows
@@ -95,6 +101,27 @@ class MaskedGNN:
         self.rows = None if self.prefix_numbered else self.ring_ids
         return self.hop
 
+    def build_layer_masks(self):
+        """Per-layer edge masks of layer-wise sampling: the graph seen through layer l's mask (forward), its transpose
+        seen through the same mask (backward), and the mean over the kept neighbours."""
+        rule, par, seed = self.layer_sampling
+        self.g_l, self.gt_l, self.rs_l, self.kept_l = [None], [None], [None], [None]
+        for l in range(1, self.L + 1):
+            nl = self.n_rows_of_layer(l)
+            # layer 1 has no backward aggregation: its threshold pairs are not needed
+            out = self._call(f"layer_mask_{l}", B.gnn_layer_edge_mask, self.g, self.rows, nl, rule, l, seed,
+                             fanout=par if rule == "fanout" else 0, threshold=par if rule == "threshold" else (1 << 64) - 1,
+                             with_thresholds=l > 1)
+            keep, kept_len = out[0], out[1]
+            self.g_l.append(self.g.with_edge_keep(keep))
+            self.kept_l.append(kept_len)
+            if l > 1:
+                keep_t = self._call(f"layer_mask_t_{l}", B.gnn_layer_edge_mask_transposed, self.gt, out[2], out[3], l, seed)
+                self.gt_l.append(self.gt.with_edge_keep(keep_t))
+            else:
+                self.gt_l.append(None)
+            self.rs_l.append(self.rs if self.kind == "gcn" else B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, length=kept_len))
+
     def n_rows_of_layer(self, l: int) -> int:
         """|R_l|, R_l = {dist <= L - l}: a prefix of the ring-sorted ids."""
         return int(self.hop[self.L - l + 1])
@@ -110,7 +137,8 @@ class MaskedGNN:
             p = self.params[l - 1]
             K = self.dims[l - 1]
             nl = self.n_rows_of_layer(l)
-            self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, self.g, self.rows, nl, self.H[l - 1], self.A[l], K, self.rs, self.cs, ws=self.ws)
+            g_l, rs_l = (self.g, self.rs) if self.layer_sampling is None else (self.g_l[l], self.rs_l[l])
+            self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, g_l, self.rows, nl, self.H[l - 1], self.A[l], K, rs_l, self.cs, ws=self.ws)
             self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
                              p["W_neigh"], p.get("W_self"), p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
         nt = self.n_rows_of_layer(self.L)
@@ -136,21 +164,24 @@ class MaskedGNN:
                 # few (the last layers: R_l is close to T), the column-blocked route would spend more on preparing
                 # every edge than the gathers cost: no workspace -> the one-launch route.
                 ws_bwd = self.ws if 4 * nl >= self.n else None
+                gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[l], self.rs_l[l])
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
-                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=True, ws=ws_bwd)
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                                          rs_l, self.cs, accumulate=True, ws=ws_bwd)
                     if n_prev > nl:
-                        self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
-                                              self.dH[l - 1], K, self.rs, self.cs, accumulate=False, ws=ws_bwd)
+                        self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, gt_l, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
+                                              self.dH[l - 1], K, rs_l, self.cs, accumulate=False, ws=ws_bwd)
                 else:
-                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
-                                          self.rs, self.cs, accumulate=False, ws=ws_bwd)
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                                          rs_l, self.cs, accumulate=False, ws=ws_bwd)
         return self.grads
 
     def step(self, labels: torch.Tensor):
         """One pass of the whole hot path: active sets, forward, loss, backward."""
         self.build_active_sets()
+        if self.layer_sampling is not None:
+            self.build_layer_masks()
         self.forward(labels)
         self.backward()
         return self.loss
@@ -163,7 +194,10 @@ class MaskedGNN:
         out = {}
         for l in range(1, self.L + 1):
             rows = ring[: self.n_rows_of_layer(l)]
-            fwd = int((rp[rows + 1] - rp[rows]).sum().item())
+            if self.layer_sampling is not None:      # only the entries the layer's mask keeps are aggregated
+                fwd = int(self.kept_l[l][rows].sum().item())
+            else:
+                fwd = int((rp[rows + 1] - rp[rows]).sum().item())
             bwd = 0
             if l > 1:
                 # transposed rows of R_{l-1}; entries v with dist(v) <= L - l are exactly the forward edges of R_l

@@ -1,0 +1,175 @@
+"""GPU parity of layer-wise sampling as per-layer masking (section 5.2): gnn_layer_edge_mask and
+gnn_transpose_edge_mask bit-exact against the oracle, the aggregation calls through gnn_csr.edge_keep against the
+oracle's masked aggregation (fp32 1e-4, bf16 2e-2), and one training step of the model with per-layer masks."""
+import numpy as np
+import pytest
+import torch
+
+import graphgen as gg
+import oracle
+from gpu_util import TOL, as_stored, check, dev, host64, padded
+
+pytestmark = pytest.mark.gpu
+
+M64 = (1 << 64) - 1
+SENT = 4321.0
+
+
+def _bits(words: torch.Tensor, nnz: int) -> np.ndarray:
+    w = words.cpu().numpy().view(np.uint32)
+    return ((w[np.arange(nnz) >> 5] >> (np.arange(nnz) & 31).astype(np.uint32)) & 1).astype(np.uint8)
+
+
+def _pack(keep: np.ndarray) -> torch.Tensor:
+    nnz = keep.shape[0]
+    w = np.zeros(max((nnz + 31) // 32, 1), dtype=np.uint32)
+    np.bitwise_or.at(w, np.arange(nnz) >> 5, keep.astype(np.uint32) << (np.arange(nnz) & 31).astype(np.uint32))
+    return torch.from_numpy(w.view(np.int32)).cuda()
+
+
+def _mask_case(g, rows, rule, par, layer, seed):
+    import paper_2311_06837_amd as P
+    print(f"layer mask: n={g.n_rows} nnz={g.nnz} rows={'all' if rows is None else len(rows)} rule={rule} par={par} layer={layer}", flush=True)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    n_active = g.n_rows if rows is None else len(rows)
+    kw = dict(fanout=par) if rule == "fanout" else dict(threshold=par)
+    keep, kept_len = P.gnn_layer_edge_mask(G, dev(np.asarray(rows, dtype=np.int32)) if rows is not None and len(rows) else None,
+                                           n_active, rule, layer, seed, **kw)
+    torch.cuda.synchronize()
+    okeep, olen = oracle.layer_edge_mask(g.row_ptr, g.col_idx, None if rows is None else np.asarray(rows, dtype=np.int32), rule, layer, seed, **kw)
+    assert np.array_equal(_bits(keep, g.nnz), okeep)
+    assert np.array_equal(kept_len.cpu().numpy(), olen)
+    return G, keep, okeep
+
+
+@pytest.mark.parametrize("rule,par", [("threshold", oracle.keep_threshold(0.5)), ("threshold", M64), ("threshold", 0),
+                                      ("fanout", 1), ("fanout", 5), ("fanout", 25), ("fanout", 0), ("fanout", 10**6)])
+def test_masks_power_law_graph(rule, par):
+    g = gg.chung_lu(30011, 22.0, 2.1, 3)
+    rng = np.random.default_rng(5)
+    _mask_case(g, None, rule, par, 1, 42)
+    _mask_case(g, np.sort(rng.choice(30011, 9000, replace=False)), rule, par, 3, 43)
+    _mask_case(g, rng.permutation(30011)[:777], rule, par, 2, 2 ** 63 + 5)          # unsorted list, large seed
+
+
+def test_masks_hub_rows_empty_rows_and_nothing_listed():
+    g = gg.chung_lu(12000, 150.0, 2.1, 12)
+    assert g.degrees().max() > 1024
+    _mask_case(g, None, "fanout", 15, 1, 1)
+    _mask_case(g, None, "threshold", oracle.keep_threshold(0.1), 2, 1)
+    d = gg.random_directed(5000, 1.5, 13)
+    assert (d.degrees() == 0).any()
+    _mask_case(d, None, "fanout", 2, 1, 9)
+    _mask_case(d, [], "fanout", 2, 1, 9)
+    empty = gg.CSR(40, 40, np.zeros(41, dtype=np.int32), np.zeros(0, dtype=np.int32))
+    _mask_case(empty, None, "threshold", M64, 1, 0)
+
+
+def test_transposed_mask():
+    import paper_2311_06837_amd as P
+    for g in (gg.random_directed(20000, 6.0, 4), gg.chung_lu(9000, 40.0, 2.1, 5)):
+        gt = gg.transpose(g)
+        G, keep, okeep = _mask_case(g, None, "threshold", oracle.keep_threshold(0.4), 2, 7)
+        GT = P.Graph.from_numpy(gt.row_ptr, gt.col_idx)
+        kt = P.gnn_transpose_edge_mask(G, GT, keep)
+        torch.cuda.synchronize()
+        want = oracle.transpose_mask(g.row_ptr, g.col_idx, okeep, gt.row_ptr, gt.col_idx)
+        assert np.array_equal(_bits(kt, gt.nnz), want)
+        # the same mask from the per-row threshold pairs, both rules, with only some rows listed
+        rows = np.sort(np.random.default_rng(1).choice(g.n_rows, g.n_rows // 3, replace=False)).astype(np.int32)
+        for rule, kw in (("threshold", dict(threshold=oracle.keep_threshold(0.4))), ("fanout", dict(fanout=3)), ("fanout", dict(fanout=0))):
+            keep2, _, tk, tu = P.gnn_layer_edge_mask(G, dev(rows), len(rows), rule, 2, 7, with_thresholds=True, **kw)
+            kt2 = P.gnn_layer_edge_mask_transposed(GT, tk, tu, 2, 7)
+            torch.cuda.synchronize()
+            ok2, _ = oracle.layer_edge_mask(g.row_ptr, g.col_idx, rows, rule, 2, 7, **kw)
+            assert np.array_equal(_bits(keep2, g.nnz), ok2)
+            assert np.array_equal(_bits(kt2, gt.nnz), oracle.transpose_mask(g.row_ptr, g.col_idx, ok2, gt.row_ptr, gt.col_idx)), rule
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("F,ld", [(64, 64), (128, 128), (256, 256), (602, 608), (100, 100), (7, 7)])
+def test_aggregation_through_a_mask_forward_and_backward(dtype, F, ld):
+    import paper_2311_06837_amd as P
+    g = gg.chung_lu(8000, 60.0, 2.1, 21)                      # symmetric, a few rows above 1024 neighbours
+    n = g.n_rows
+    rng = np.random.default_rng(F)
+    T = np.sort(rng.choice(n, 40, replace=False)).astype(np.int32)
+    dist, ring, off = oracle.active_sets(g.row_ptr, g.col_idx, T, 2)
+    rows = ring[: off[2]]                                      # R of a layer: targets and their neighbours
+    print(f"masked aggregation: F={F} ld={ld} {dtype} rows={len(rows)}", flush=True)
+    okeep, olen = oracle.layer_edge_mask(g.row_ptr, g.col_idx, rows, "fanout", 2, 3, fanout=6)
+    rs = oracle.norm_scales("mean", olen)
+    cs = (rng.random(n) + 0.5)
+    X = as_stored(rng.standard_normal((n, F)), dtype)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx).with_edge_keep(_pack(okeep))
+    Xd = padded(X, ld, dtype, fill=float("nan") if ld > F else 0.0)
+    Yd = torch.full((n, ld), SENT, dtype=dtype, device="cuda")
+    P.gnn_masked_spmm_fwd(G, dev(rows), len(rows), Xd, Yd, F, dev(rs.astype(np.float32)), dev(cs.astype(np.float32)), ws=P.Workspace())
+    torch.cuda.synchronize()
+    want = np.full((n, F), SENT)
+    oracle.spmm_fwd_em(g.row_ptr, g.col_idx, okeep, rows, X, want, F, rs.astype(np.float32).astype(np.float64), cs.astype(np.float32).astype(np.float64))
+    got = host64(Yd)
+    check(got[rows, :F], want[rows], dtype, "forward")
+    rest = np.setdiff1d(np.arange(n), rows)
+    sent = host64(torch.tensor(SENT, dtype=dtype))
+    assert (got[rest] == sent).all() and (got[:, F:] == sent).all()
+
+    # backward: gather over the transposed graph (the graph is symmetric: same arrays) with the transposed mask and the
+    # dist filter "v was a row of the forward call"
+    kt = oracle.transpose_mask(g.row_ptr, g.col_idx, okeep, g.row_ptr, g.col_idx)
+    GT = P.Graph.from_numpy(g.row_ptr, g.col_idx).with_edge_keep(_pack(kt))
+    dY = as_stored(rng.standard_normal((n, F)), dtype)
+    dYd = padded(dY, ld, dtype, fill=float("nan") if ld > F else 0.0)
+    out_rows = ring[: off[3]]
+    dXd = torch.full((n, ld), SENT, dtype=dtype, device="cuda")
+    P.gnn_masked_spmm_bwd(GT, dev(out_rows), len(out_rows), dev(dist), 1, dYd, dXd, F, dev(rs.astype(np.float32)), dev(cs.astype(np.float32)),
+                          accumulate=False)
+    torch.cuda.synchronize()
+    dX = np.zeros((n, F))
+    oracle.spmm_bwd_em(g.row_ptr, g.col_idx, okeep, rows, dY, dX, F, rs.astype(np.float32).astype(np.float64), cs.astype(np.float32).astype(np.float64))
+    got = host64(dXd)
+    check(got[out_rows, :F], dX[out_rows], dtype, "backward")
+    rest = np.setdiff1d(np.arange(n), out_rows)
+    assert (got[rest] == sent).all() and (got[:, F:] == sent).all()
+
+
+@pytest.mark.parametrize("kind,dtype,ls", [("sage", torch.float32, ("fanout", 4, 11)),
+                                           ("gcn", torch.float32, ("threshold", oracle.keep_threshold(0.5), 12)),
+                                           ("sage", torch.bfloat16, ("threshold", oracle.keep_threshold(0.7), 13)),
+                                           ("sage", torch.float32, ("threshold", M64, 14))])
+def test_training_step_with_per_layer_masks(kind, dtype, ls):
+    import paper_2311_06837_amd as P
+    w = gg.make_workload("cfg0", scale=0.5)
+    part = w.partition
+    dims = [32, 64, 48, 8]
+    print(f"model with layer sampling {ls[0]}: n={part.graph.n_rows} nnz={part.graph.nnz} {kind} {dtype}", flush=True)
+    L = len(dims) - 1
+    g = part.graph if kind == "sage" else part.graph
+    T = part.targets
+    # three layers over a 2-hop partition: the outermost active set simply repeats
+    params = gg.layer_weights(dims, kind == "sage", 5)
+    n = g.n_rows
+    H0 = as_stored(gg.features(n, dims[0], 5), dtype)
+    y = gg.labels(len(T), dims[-1], 5)
+    gdeg = part.global_degree if kind == "gcn" else None
+    om = oracle.Model(g.row_ptr, g.col_idx, T, kind, params, gdeg, bf16=dtype == torch.bfloat16, layer_sampling=ls)
+    loss_o = om.forward(H0, y)
+    grads_o = om.backward()
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    m = P.MaskedGNN(G, G, dev(T), kind, [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
+                    global_degree=dev(gdeg) if gdeg is not None else None, layer_sampling=ls)
+    m.set_input(padded(H0, P.row_stride(dims[0], dtype), dtype))
+    loss = m.step(dev(y))
+    torch.cuda.synchronize()
+    for l in range(1, L + 1):
+        assert np.array_equal(_bits(m.g_l[l].edge_keep, g.nnz), om.keep[l]), f"mask of layer {l}"
+    tol = TOL[dtype]
+    assert abs(loss.item() - loss_o) <= tol * L * abs(loss_o), (loss.item(), loss_o)
+    for l in range(L):
+        for k, want in grads_o[l].items():
+            got = host64(m.grads[l][k])
+            e = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+            assert e <= tol * (L + 1), (l, k, e)
+    if ls[1] == M64:       # everything kept: the plain model
+        plain = oracle.Model(g.row_ptr, g.col_idx, T, kind, params, gdeg, bf16=dtype == torch.bfloat16)
+        assert plain.forward(H0, y) == loss_o
