@@ -305,6 +305,18 @@ def layer_weights(dims: list[int], sage: bool, seed: int) -> list[dict]:
     return out
 
 
+def res_layer_weights(dims: list[int], seed: int) -> list[dict]:
+    """Parameters of the deep residual GraphSAGE: layer_weights(sage) plus, from the second layer on, the scale and
+    shift of the layer normalisation in front of it (ln_gamma ~ 1 + N(0, 0.01), ln_beta ~ N(0, 0.01), float32)."""
+    out = layer_weights(dims, True, seed)
+    rng = np.random.default_rng([seed, 0x4C4E])
+    for l in range(1, len(out)):
+        k = dims[l]
+        out[l]["ln_gamma"] = (1.0 + 0.1 * rng.standard_normal(k)).astype(np.float32)
+        out[l]["ln_beta"] = (0.1 * rng.standard_normal(k)).astype(np.float32)
+    return out
+
+
 def labels(n: int, n_classes: int, seed: int) -> np.ndarray:
     rng = np.random.default_rng([seed, 0x4C4142])
     return rng.integers(0, n_classes, size=n, dtype=np.int32)

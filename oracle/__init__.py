@@ -454,3 +454,124 @@ class Model:
                     spmm_bwd_em(self.row_ptr, self.col_idx, self.keep[l], rows, dA, dprev, K, self.rs_l[l], self.cs)
                 dH = self._store(dprev)
         return grads
+
+
+LN_EPS = 1e-5
+
+
+def ln_relu_fwd(rows, X, F, gamma, beta, Y, eps=LN_EPS):
+    """Y[rows] = ReLU(LayerNorm(X[rows])) over the first F columns; in place on Y."""
+    rows = _i32(rows)
+    gamma, beta = _f64(gamma), _f64(beta)
+    assert X.dtype == np.float64 and Y.dtype == np.float64 and X.flags.c_contiguous and Y.flags.c_contiguous
+    n_active = rows.shape[0] if rows is not None else X.shape[0]
+    lib().orc_ln_relu_fwd(_p(rows), C.c_int32(n_active), _p(X), C.c_int64(X.shape[1]), C.c_int32(F), _p(gamma), _p(beta),
+                          C.c_double(eps), _p(Y), C.c_int64(Y.shape[1]))
+    return Y
+
+
+def ln_relu_bwd(rows, dY, T, X, F, gamma, dX, eps=LN_EPS):
+    """-> (dgamma, dbeta); dX[rows] is overwritten.  T = the stored forward output (ReLU mask)."""
+    rows = _i32(rows)
+    gamma = _f64(gamma)
+    for a in (dY, T, X, dX):
+        assert a.dtype == np.float64 and a.flags.c_contiguous
+    n_active = rows.shape[0] if rows is not None else X.shape[0]
+    dg, db = np.zeros(F), np.zeros(F)
+    lib().orc_ln_relu_bwd(_p(rows), C.c_int32(n_active), _p(dY), C.c_int64(dY.shape[1]), _p(T), C.c_int64(T.shape[1]),
+                          _p(X), C.c_int64(X.shape[1]), C.c_int32(F), _p(gamma), C.c_double(eps), _p(dX), C.c_int64(dX.shape[1]),
+                          _p(dg), _p(db))
+    return dg, db
+
+
+class ResModel:
+    """The deep residual GraphSAGE the paper calls ResSAGE+ (section 8.1; residual connections and pre-activation):
+        h_1 = SAGE_1(h_0)
+        h_l = h_{l-1} + SAGE_l(ReLU(LN_l(h_{l-1})))      1 < l < L     (all hidden widths equal)
+        out = SAGE_L(ReLU(LN_L(h_{L-1})))
+    with SAGE_l(t)[v] = t[v] W_self + mean_{u in row(v)} t[u] W_neigh + b, under one-hop masking: layer l produces the
+    rows R_l, its pre-activation runs over R_{l-1}.  params[l-1]: W_neigh, W_self, bias and, for l > 1, ln_gamma, ln_beta.
+    bf16: every stored tensor is rounded (h_0, t_l, A_l, the layer's transform before the residual is added, h_l, W,
+    and the gradients)."""
+
+    def __init__(self, row_ptr, col_idx, targets, params, bf16=False, all_rows=False):
+        self.row_ptr, self.col_idx = _i32(row_ptr), _i32(col_idx)
+        self.n = self.row_ptr.shape[0] - 1
+        self.targets = _i32(targets)
+        self.L = len(params)
+        self.bf16 = bf16
+        self.params = []
+        for p in params:
+            q = {k: np.array(v, dtype=np.float64) for k, v in p.items()}
+            if bf16:
+                round_bf16(q["W_neigh"]), round_bf16(q["W_self"])
+            self.params.append(q)
+        self.dist, self.ring_ids, self.hop_offsets = active_sets(self.row_ptr, self.col_idx, self.targets, self.L)
+        self.rs = norm_scales("mean", np.diff(self.row_ptr))
+        self.all_rows = all_rows
+
+    def rows_of_layer(self, l):
+        if self.all_rows:
+            return np.arange(self.n, dtype=np.int32)
+        return self.ring_ids[: self.hop_offsets[self.L - l + 1]]
+
+    def _store(self, x):
+        return round_bf16(x) if self.bf16 else x
+
+    def forward(self, H0, labels):
+        self.H = [self._store(np.array(H0, dtype=np.float64, order="C"))]
+        self.T, self.A = [None, None], [None]
+        for l in range(1, self.L + 1):
+            p = self.params[l - 1]
+            K, N = p["W_neigh"].shape
+            rows = self.rows_of_layer(l)
+            if l == 1:
+                src = self.H[0]
+            else:
+                src = np.full((self.n, K), np.nan)
+                ln_relu_fwd(self.rows_of_layer(l - 1), self.H[l - 1], K, p["ln_gamma"], p["ln_beta"], src)
+                self._store(src)
+                self.T.append(src)
+            A = np.full((self.n, K), np.nan)
+            spmm_fwd(self.row_ptr, self.col_idx, rows, src, A, K, self.rs, None)
+            self._store(A)
+            Z = np.full((self.n, N), np.nan)
+            linear_fwd(rows, A, src, K, p["W_neigh"], p["W_self"], p["bias"], Z, relu=False)
+            self._store(Z)
+            if 1 < l < self.L:
+                Z[rows] = Z[rows] + self.H[l - 1][rows]
+                self._store(Z)
+            self.A.append(A)
+            self.H.append(Z)
+        self.labels = _i32(labels)
+        C_ = self.params[-1]["W_neigh"].shape[1]
+        self.dlogits = np.zeros((self.n, C_))
+        self.loss = softmax_ce(self.targets, self.H[-1], C_, self.labels, self.dlogits)
+        return self.loss
+
+    def backward(self):
+        grads = [None] * self.L
+        dH = self._store(self.dlogits.copy())
+        for l in range(self.L, 0, -1):
+            p = self.params[l - 1]
+            K, N = p["W_neigh"].shape
+            rows = self.rows_of_layer(l)
+            need_in = l > 1
+            src = self.H[0] if l == 1 else self.T[l]
+            dA = np.zeros((self.n, K)) if need_in else None
+            dT = np.zeros((self.n, K)) if need_in else None
+            dWn, dWs, db = linear_bwd(rows, dH, None, False, self.A[l], src, K, p["W_neigh"], p["W_self"], dA, dT)
+            g = {"dW_neigh": dWn, "dW_self": dWs, "dbias": db}
+            if need_in:
+                self._store(dA)
+                self._store(dT)       # the self part is stored before the aggregated part is added to it
+                spmm_bwd(self.row_ptr, self.col_idx, rows, dA, dT, K, self.rs, None)
+                self._store(dT)
+                rows_prev = self.rows_of_layer(l - 1)
+                dprev = np.zeros((self.n, K))
+                g["dln_gamma"], g["dln_beta"] = ln_relu_bwd(rows_prev, dT, self.T[l], self.H[l - 1], K, p["ln_gamma"], dprev)
+                if l < self.L:
+                    dprev[rows] += dH[rows]          # the residual connection
+                dH = self._store(dprev)
+            grads[l - 1] = g
+        return grads

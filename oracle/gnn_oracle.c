@@ -21,6 +21,8 @@
  *     the vertices not selected so far;
  *   - layer-wise sampling as per-layer masking (section 5.2): the one-hop
  *     graph stays whole and every layer aggregates through its own edge mask;
+ *   - the deep residual model the paper trains (ResSAGE+, section 8.1): GraphSAGE layers with residual
+ *     connections and pre-activation (layer normalisation, then ReLU);
  *   - extraction of the partition (section 6, step 1; section 5.3.1 "a
  *     subgraph is generated from the traversed vertices"): the vertices the
  *     traversal reached and every edge of the graph between two of them.
@@ -647,4 +649,75 @@ void orc_spmm_bwd_em(const int32_t *row_ptr, const int32_t *col_idx, const uint8
             }
         }
     }
+}
+
+/* ---------------------------------------------------------------------- */
+/* Pre-activation of the deep residual model (section 8.1 names ResSAGE+;   */
+/* the related-work section describes it as residual connections plus       */
+/* pre-activation): t = ReLU(LayerNorm(x)) per vertex, over its F features: */
+/*   mu = mean(x), var = mean((x - mu)^2), xhat = (x - mu) / sqrt(var + eps) */
+/*   t  = max(0, xhat * gamma + beta)                                        */
+/* Only the listed rows are read and written.                               */
+/* ---------------------------------------------------------------------- */
+void orc_ln_relu_fwd(const int32_t *rows, int32_t n_active, const double *X, int64_t ldx, int32_t F,
+                     const double *gamma, const double *beta, double eps, double *Y, int64_t ldy)
+{
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < n_active; ++i) {
+        const int32_t v = rows ? rows[i] : i;
+        const double *x = X + (int64_t)v * ldx;
+        double *y = Y + (int64_t)v * ldy;
+        double mu = 0.0, var = 0.0;
+        for (int32_t f = 0; f < F; ++f) mu += x[f];
+        mu /= (double)F;
+        for (int32_t f = 0; f < F; ++f) var += (x[f] - mu) * (x[f] - mu);
+        var /= (double)F;
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int32_t f = 0; f < F; ++f) {
+            const double t = (x[f] - mu) * rstd * gamma[f] + beta[f];
+            y[f] = t > 0.0 ? t : 0.0;
+        }
+    }
+}
+
+/* Backward of orc_ln_relu_fwd by the chain rule.  Tmask = the forward      */
+/* output as it was stored (the ReLU passes gradient where it is > 0).      */
+/*   g = dY where Tmask > 0, else 0;  dgamma += sum_rows g * xhat;          */
+/*   dbeta += sum_rows g;  gx = g * gamma;                                   */
+/*   dX = rstd * (gx - mean(gx) - xhat * mean(gx * xhat))   (overwrites)     */
+/* dgamma, dbeta are accumulated into (caller zeroes them).                 */
+void orc_ln_relu_bwd(const int32_t *rows, int32_t n_active, const double *dY, int64_t lddy,
+                     const double *Tmask, int64_t ldt, const double *X, int64_t ldx, int32_t F,
+                     const double *gamma, double eps, double *dX, int64_t lddx,
+                     double *dgamma, double *dbeta)
+{
+    double *xhat = (double *)malloc(sizeof(double) * (size_t)(F > 0 ? F : 1));
+    double *gx = (double *)malloc(sizeof(double) * (size_t)(F > 0 ? F : 1));
+    for (int32_t i = 0; i < n_active; ++i) {
+        const int32_t v = rows ? rows[i] : i;
+        const double *x = X + (int64_t)v * ldx;
+        const double *dy = dY + (int64_t)v * lddy;
+        const double *tm = Tmask + (int64_t)v * ldt;
+        double *dx = dX + (int64_t)v * lddx;
+        double mu = 0.0, var = 0.0;
+        for (int32_t f = 0; f < F; ++f) mu += x[f];
+        mu /= (double)F;
+        for (int32_t f = 0; f < F; ++f) var += (x[f] - mu) * (x[f] - mu);
+        var /= (double)F;
+        const double rstd = 1.0 / sqrt(var + eps);
+        double m1 = 0.0, m2 = 0.0;
+        for (int32_t f = 0; f < F; ++f) {
+            xhat[f] = (x[f] - mu) * rstd;
+            const double g = tm[f] > 0.0 ? dy[f] : 0.0;
+            dgamma[f] += g * xhat[f];
+            dbeta[f] += g;
+            gx[f] = g * gamma[f];
+            m1 += gx[f];
+            m2 += gx[f] * xhat[f];
+        }
+        m1 /= (double)F;
+        m2 /= (double)F;
+        for (int32_t f = 0; f < F; ++f) dx[f] = rstd * (gx[f] - m1 - xhat[f] * m2);
+    }
+    free(xhat); free(gx);
 }
