@@ -97,6 +97,10 @@ def main():
     ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
                     help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
                          "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
+    ap.add_argument("--res-layers", type=int, default=0, metavar="L",
+                    help="run the deep residual GraphSAGE (ResSAGE+) with L layers of the workload's hidden width on the "
+                         "workload's graph instead of its own model (GraphSAGE workloads); --recompute: activation recomputation")
+    ap.add_argument("--recompute", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -128,6 +132,9 @@ def main():
     ld0 = P.row_stride(w.dims[0], dtype)
     H0 = gg.features(n, w.dims[0], w.seed, ld=ld0)
     n_layers = len(w.dims) - 1
+
+    if args.res_layers:
+        return bench_res_model(args, w, part, sampled_graph, dtype)
 
     # Step (a-1) of the path, outside the timed step like the sampling: the partition's one-hop graph extracted on
     # the GPU from the unpartitioned graph, vertices renumbered by (distance, id).  Timed always (full-halo
@@ -308,6 +315,70 @@ def main():
         "layer_mask_ms": sum(v for k, v in call_ms.items() if k.startswith("layer_mask")) if args.layer_sampling else None,
         "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,
         "call_ms": {k: round(v, 4) for k, v in call_ms.items()},
+    }
+    print(json.dumps(out))
+
+
+def bench_res_model(args, w, part, sampled_graph, dtype):
+    """The deep residual GraphSAGE on the workload's partition (host-built numbering unless the partition was sampled
+    on the GPU): same metric, the forward aggregation of a middle layer as the dominant call."""
+    import torch
+    import graphgen as gg
+    import paper_2311_06837_amd as P
+    assert w.model == "sage" and args.res_layers >= 2
+    L, hid = args.res_layers, w.dims[1]
+    dims = [w.dims[0]] + [hid] * (L - 1) + [w.dims[-1]]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    # the partition's halo was cut for the workload's own depth: deeper models see the same vertices (the late active
+    # sets are the whole partition, as in configs[3])
+    G = sampled_graph if sampled_graph is not None else P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
+    params = [{k: dev(v) for k, v in p.items()} for p in gg.res_layer_weights(dims, w.seed)]
+    model = P.ResSAGEPlus(G, G, dev(part.targets), params, dtype=dtype, recompute=args.recompute,
+                          prefix_numbered=sampled_graph is not None)
+    n = part.graph.n_rows
+    model.set_input(dev(gg.features(n, w.dims[0], w.seed, ld=P.row_stride(w.dims[0], dtype))).to(dtype))
+    labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
+    for _ in range(args.warmup):
+        model.step(labels)
+    torch.cuda.synchronize()
+    model.trace = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.step(labels)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    trace, model.trace = model.trace, None
+    per_call = {}
+    for name, a, b in trace:
+        per_call.setdefault(name, []).append(a.elapsed_time(b))
+    call_ms = {k: float(np.mean(v)) for k, v in per_call.items()}
+    edges = model.aggregated_edges()
+    total_edges = sum(e["fwd"] + e["bwd"] + e["again"] for e in edges.values())
+    es = 4 if dtype == torch.float32 else 2
+    dom = max(range(2, L + 1), key=lambda l: call_ms.get(f"spmm_fwd_{l}", 0.0))
+    nd = model.n_rows_of_layer(dom)
+    alg_bytes = edges[dom]["fwd"] * (4 + hid * es) + nd * (8 + hid * es)
+    t_dom = call_ms[f"spmm_fwd_{dom}"] * 1e-3
+    group = lambda pre: sum(v for k, v in call_ms.items() if k.startswith(pre))
+    out = {
+        "metric": "aggregated_edges_per_sec", "value": total_edges / (wall / args.steps), "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"deep residual GraphSAGE (ResSAGE+), {L} layers, hidden {hid}, on the partition of "
+                               f"configs[{CONFIG_INDEX[args.workload]}]: {gg.WORKLOADS[args.workload]}",
+                   "scale": args.scale, "n_local": n, "nnz_local": part.graph.nnz, "targets": len(part.targets),
+                   "layers": L, "recompute": bool(args.recompute)},
+        "epoch_ms": sum(v for k, v in call_ms.items() if k != "active_sets"),
+        "activation_bytes": model.activation_bytes(),
+        "aggregated_edges_per_step": total_edges,
+        "ms_by_kind": {"spmm_fwd": group("spmm_fwd"), "spmm_bwd": group("spmm_bwd"), "linear_fwd": group("linear_fwd"),
+                       "linear_bwd": group("linear_bwd"), "layer_norm_fwd": group("ln_fwd"), "layer_norm_bwd": group("ln_bwd"),
+                       "residual": group("residual"), "active_sets": call_ms.get("active_sets"), "softmax_ce": call_ms.get("softmax_ce")},
+        "roofline": {"kernel": f"spmm_rows_kernel; gnn_masked_spmm_fwd, layer {dom}, F={hid}", "bound": "hbm",
+                     "achieved": alg_bytes / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": alg_bytes, "launch_ms": t_dom * 1e3},
+        "cpu_baseline": None,
     }
     print(json.dumps(out))
 

@@ -277,6 +277,32 @@ int32_t gnn_layer_edge_mask_transposed(const gnn_csr *gT, const uint64_t *row_th
 int32_t gnn_transpose_edge_mask(const gnn_csr *g, const gnn_csr *gT, const uint32_t *keep, uint32_t *keep_t, void *stream);
 
 /*
+ * Pre-activation of the deep residual GraphSAGE (ResSAGE+, section 8.1; the paper's related-work section: residual
+ * connections and pre-activation): for the listed rows, over the first F columns (1 <= F <= 1024),
+ *   Y[v] = max(0, (X[v] - mean) / sqrt(var + eps) * gamma + beta),   mean / var over the row (var = mean of squares
+ *   of the deviations).  gamma, beta: float [F], device.  Rows that are not listed are neither read nor written.
+ */
+int32_t gnn_layer_norm_relu_fwd(const int32_t *rows, int32_t n_active, const void *X, int64_t ldx, int32_t F,
+                                const float *gamma, const float *beta, float eps, void *Y, int64_t ldy, int32_t dtype,
+                                void *stream);
+
+/*
+ * Its backward.  T = the forward output as stored (the ReLU passes the gradient where T > 0), X = the forward input.
+ *   dX[v] = LayerNorm-backward(dY[v] where T[v] > 0)  (+ dRes[v] for the first n_res listed rows: the gradient that
+ *   arrives over the residual connection; dRes NULL: none).  dX is overwritten for the listed rows only.
+ *   dgamma, dbeta: float [F], overwritten with the sums over the listed rows (fixed order: bit-reproducible).
+ * Workspace: (ws, ws_bytes) size-query protocol.
+ */
+int32_t gnn_layer_norm_relu_bwd(const int32_t *rows, int32_t n_active, const void *dY, int64_t lddy, const void *T,
+                                int64_t ldt, const void *X, int64_t ldx, int32_t F, const float *gamma, float eps,
+                                const void *dRes, int64_t ldr, int32_t n_res, void *dX, int64_t lddx, float *dgamma,
+                                float *dbeta, int32_t dtype, void *ws, size_t *ws_bytes, void *stream);
+
+/* Y[v, 0:F] += X[v, 0:F] for the listed rows: the residual connection of the same model, forward. */
+int32_t gnn_add_rows(const int32_t *rows, int32_t n_active, const void *X, int64_t ldx, void *Y, int64_t ldy, int32_t F,
+                     int32_t dtype, void *stream);
+
+/*
  * Extraction of the partition's one-hop graph (section 6, figure 7c step 1: extract the multi-hop
  * dependency starting from the inner vertices; section 5.3.1: a subgraph is generated from the
  * traversed vertices).  g is the UNPARTITIONED graph (square); ring_ids[0 .. n_local) and dist are

@@ -25,7 +25,7 @@ EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_s
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
            "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
-           "gnn_layer_edge_mask_transposed"]
+           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows"]
 
 
 class GnnError(RuntimeError):
@@ -410,3 +410,43 @@ def gnn_gather_rows(src: torch.Tensor, ids: torch.Tensor, F: int, dst: torch.Ten
     assert src.dtype == dst.dtype and dst.shape[0] >= ids.numel()
     _check(lib().gnn_gather_rows(_ptr(src), C.c_int64(src.stride(0)), C.c_int32(src.shape[0]), _ptr(ids), C.c_int32(ids.numel()),
                                  C.c_int32(F), C.c_int32(_dtype_code(src)), _ptr(dst), C.c_int64(dst.stride(0)), _stream()))
+
+
+LN_EPS = 1e-5
+
+
+def gnn_layer_norm_relu_fwd(rows, n_active: int, X: torch.Tensor, F: int, gamma: torch.Tensor, beta: torch.Tensor, Y: torch.Tensor,
+                            eps: float = LN_EPS):
+    """Y[rows, :F] = ReLU(LayerNorm(X[rows, :F]) * gamma + beta)."""
+    _mat(X, "X"), _mat(Y, "Y")
+    assert X.dtype == Y.dtype and gamma.dtype == torch.float32 and beta.dtype == torch.float32 and gamma.numel() == F == beta.numel()
+    _check(lib().gnn_layer_norm_relu_fwd(_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), C.c_int32(F),
+                                         _ptr(gamma), _ptr(beta), C.c_float(eps), _ptr(Y), C.c_int64(Y.stride(0)),
+                                         C.c_int32(_dtype_code(X)), _stream()))
+
+
+def gnn_layer_norm_relu_bwd(rows, n_active: int, dY: torch.Tensor, T: torch.Tensor, X: torch.Tensor, F: int, gamma: torch.Tensor,
+                            dRes, n_res: int, dX: torch.Tensor, dgamma: torch.Tensor, dbeta: torch.Tensor, eps: float = LN_EPS,
+                            ws: Workspace | None = None):
+    """dX[rows] = LN-backward(dY where T > 0) (+ dRes for the first n_res listed rows); dgamma, dbeta overwritten."""
+    for t, nm in ((dY, "dY"), (T, "T"), (X, "X"), (dX, "dX")):
+        _mat(t, nm)
+        assert t.dtype == X.dtype
+    assert dgamma.dtype == torch.float32 and dbeta.dtype == torch.float32 and dgamma.numel() == F == dbeta.numel()
+    if dRes is not None:
+        _mat(dRes, "dRes")
+        assert dRes.dtype == X.dtype
+    _with_ws(lib().gnn_layer_norm_relu_bwd,
+             (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(dY), C.c_int64(dY.stride(0)), _ptr(T), C.c_int64(T.stride(0)),
+              _ptr(X), C.c_int64(X.stride(0)), C.c_int32(F), _ptr(gamma), C.c_float(eps), _ptr(dRes),
+              C.c_int64(dRes.stride(0) if dRes is not None else 0), C.c_int32(n_res), _ptr(dX), C.c_int64(dX.stride(0)),
+              _ptr(dgamma), _ptr(dbeta), C.c_int32(_dtype_code(X))),
+             (_stream(),), ws)
+
+
+def gnn_add_rows(rows, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int):
+    """Y[rows, :F] += X[rows, :F]."""
+    _mat(X, "X"), _mat(Y, "Y")
+    assert X.dtype == Y.dtype
+    _check(lib().gnn_add_rows(_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
+                              C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _stream()))

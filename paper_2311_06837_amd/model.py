@@ -204,3 +204,151 @@ class MaskedGNN:
                 bwd = fwd
             out[l] = {"fwd": fwd, "bwd": bwd}
         return out
+
+
+class ResSAGEPlus:
+    """The deep residual GraphSAGE of the paper's evaluation (ResSAGE+: GraphSAGE layers, residual connections,
+    pre-activation by layer normalisation and ReLU) over one partition under one-hop masking:
+        h_1 = SAGE_1(h_0);   h_l = h_{l-1} + SAGE_l(ReLU(LN_l(h_{l-1})))  (1 < l < L);   out = SAGE_L(ReLU(LN_L(h_{L-1})))
+    Layer l produces the rows R_l, its pre-activation runs over R_{l-1}.  Call order only; every step runs in the
+    library's kernels.
+
+    params       per layer W_neigh, W_self [K,N], bias [N]; from the second layer on ln_gamma, ln_beta [K]
+    recompute    activation recomputation: the forward pass keeps only h_l (one matrix per layer); the backward pass
+                 makes the pre-activation t_l and the aggregate A_l of a layer again (one more normalisation and one
+                 more forward aggregation per layer) in two buffers shared by all layers, instead of 3 matrices per layer
+    """
+
+    def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, params: list, dtype=torch.float32,
+                 prefix_numbered: bool = False, recompute: bool = False):
+        self.g, self.gt, self.targets, self.dtype = graph, graph_t, targets, dtype
+        self.n, self.L = graph.n_rows, len(params)
+        self.prefix_numbered, self.recompute = prefix_numbered, recompute
+        self.ws = B.Workspace()
+        self.dims = [params[0]["W_neigh"].shape[0]] + [p["W_neigh"].shape[1] for p in params]
+        assert all(d == self.dims[1] for d in self.dims[1:-1]), "the residual connection needs equal hidden widths"
+        self.params = []
+        for l, p in enumerate(params):
+            q = {"W_neigh": p["W_neigh"].to(dtype).contiguous(), "W_self": p["W_self"].to(dtype).contiguous(),
+                 "bias": p["bias"].float().contiguous()}
+            if l > 0:
+                q["ln_gamma"], q["ln_beta"] = p["ln_gamma"].float().contiguous(), p["ln_beta"].float().contiguous()
+            self.params.append(q)
+        self.ld = [row_stride(d, dtype) for d in self.dims]
+        dev, n, L = targets.device, self.n, self.L
+        z = lambda w: torch.zeros(n, w, dtype=dtype, device=dev)
+        self.H = [None] + [z(self.ld[l]) for l in range(1, L + 1)]
+        n_buf = min(2, L) if recompute else L        # with recomputation all layers share the buffers of layers 1 and 2
+        self.T = [None, None] + [z(self.ld[l - 1]) for l in range(2, n_buf + 1)]
+        self.A = [None] + [z(self.ld[l - 1]) for l in range(1, n_buf + 1)]
+        hid = self.ld[1] if L > 1 else self.ld[0]
+        # gradients: dH ping-pong (hidden width), the logits' gradient, dA and dT (shared by all layers)
+        self.dH = [z(hid), z(hid)]
+        self.dlogits = z(self.ld[L])
+        self.dA, self.dT = (z(hid), z(hid)) if L > 1 else (None, None)
+        self.grads = []
+        for l, p in enumerate(self.params):
+            gdict = {"dW_neigh": torch.zeros_like(p["W_neigh"], dtype=torch.float32), "dW_self": torch.zeros_like(p["W_self"], dtype=torch.float32),
+                     "dbias": torch.zeros_like(p["bias"])}
+            if l > 0:
+                gdict["dln_gamma"], gdict["dln_beta"] = torch.zeros_like(p["ln_gamma"]), torch.zeros_like(p["ln_beta"])
+            self.grads.append(gdict)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.trace = None
+
+    _call = MaskedGNN._call
+
+    def build_active_sets(self):
+        self.dist, self.ring_ids, self.hop_offsets, self.hop = self._call("active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws)
+        self.rs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr)
+        if self.prefix_numbered:
+            n_all = int(self.hop[-1])
+            if not torch.equal(self.ring_ids[:n_all], torch.arange(n_all, dtype=torch.int32, device=self.ring_ids.device)):
+                raise ValueError("prefix_numbered was promised but the ring-sorted ids are not 0 .. n-1")
+        self.rows = None if self.prefix_numbered else self.ring_ids
+        return self.hop
+
+    def n_rows_of_layer(self, l: int) -> int:
+        return int(self.hop[self.L - l + 1])
+
+    def set_input(self, H0: torch.Tensor):
+        assert H0.dtype == self.dtype and H0.shape[0] == self.n and H0.stride(0) == self.ld[0]
+        self.H[0] = H0
+
+    def _slot(self, l):
+        """index of the buffers that hold t_l / A_l"""
+        return l if not self.recompute else min(l, 2)
+
+    def _pre_and_aggregate(self, l, tag):
+        """t_l = ReLU(LN_l(h_{l-1})) over R_{l-1} (layer 1: the input itself), A_l = mean aggregation of t_l over R_l."""
+        p, K, nl = self.params[l - 1], self.dims[l - 1], self.n_rows_of_layer(l)
+        if l == 1:
+            src = self.H[0]
+        else:
+            src = self.T[self._slot(l)]
+            self._call(f"ln_fwd_{l}{tag}", B.gnn_layer_norm_relu_fwd, self.rows, self.n_rows_of_layer(l - 1), self.H[l - 1], K,
+                       p["ln_gamma"], p["ln_beta"], src)
+        A = self.A[self._slot(l)]
+        self._call(f"spmm_fwd_{l}{tag}", B.gnn_masked_spmm_fwd, self.g, self.rows, nl, src, A, K, self.rs, None, ws=self.ws)
+        return src, A
+
+    def forward(self, labels: torch.Tensor) -> torch.Tensor:
+        for l in range(1, self.L + 1):
+            p, K, nl = self.params[l - 1], self.dims[l - 1], self.n_rows_of_layer(l)
+            src, A = self._pre_and_aggregate(l, "")
+            self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, A, src, K, p["W_neigh"], p["W_self"], p["bias"], self.H[l],
+                       relu=False, ws=self.ws)
+            if 1 < l < self.L:
+                self._call(f"residual_{l}", B.gnn_add_rows, self.rows, nl, self.H[l - 1], self.H[l], self.dims[l])
+        nt = self.n_rows_of_layer(self.L)
+        self._call("softmax_ce", B.gnn_softmax_ce, self.rows, nt, self.H[self.L], self.dims[self.L], labels, self.dlogits, self.loss, ws=self.ws)
+        return self.loss
+
+    def backward(self):
+        L = self.L
+        dH = self.dlogits
+        for l in range(L, 0, -1):
+            p, gr, K, nl = self.params[l - 1], self.grads[l - 1], self.dims[l - 1], self.n_rows_of_layer(l)
+            need_in = l > 1
+            if self.recompute and l > 1:
+                src, A = self._pre_and_aggregate(l, "_again")
+            else:
+                src, A = (self.H[0] if l == 1 else self.T[self._slot(l)]), self.A[self._slot(l)]
+            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, dH, None, False, A, src, K, p["W_neigh"], p["W_self"],
+                       gr["dW_neigh"], gr["dW_self"], gr["dbias"], self.dA if need_in else None, self.dT if need_in else None, ws=self.ws)
+            if not need_in:
+                break
+            n_prev = self.n_rows_of_layer(l - 1)
+            # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
+            self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, nl, self.dist, L - l, self.dA, self.dT, K,
+                       self.rs, None, accumulate=True, ws=None)
+            if n_prev > nl:
+                self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA,
+                           self.dT, K, self.rs, None, accumulate=False, ws=None)
+            out = self.dH[l % 2]
+            self._call(f"ln_bwd_{l}", B.gnn_layer_norm_relu_bwd, self.rows, n_prev, self.dT, src, self.H[l - 1], K, p["ln_gamma"],
+                       dH if l < L else None, nl if l < L else 0, out, gr["dln_gamma"], gr["dln_beta"], ws=self.ws)
+            dH = out
+        return self.grads
+
+    def step(self, labels: torch.Tensor):
+        self.build_active_sets()
+        self.forward(labels)
+        self.backward()
+        return self.loss
+
+    def aggregated_edges(self) -> dict:
+        """Edges visited per layer by the forward and the backward aggregation (and by the recomputed forward)."""
+        rp = self.g.row_ptr.long()
+        ring = self.ring_ids.long()
+        out = {}
+        for l in range(1, self.L + 1):
+            rows = ring[: self.n_rows_of_layer(l)]
+            fwd = int((rp[rows + 1] - rp[rows]).sum().item())
+            out[l] = {"fwd": fwd, "bwd": fwd if l > 1 else 0, "again": fwd if (self.recompute and l > 1) else 0}
+        return out
+
+    def activation_bytes(self) -> int:
+        """Bytes of the per-layer activation and gradient buffers this model holds (the memory the recomputation saves)."""
+        ts = [t for lst in (self.H[1:], self.T, self.A, self.dH, [self.dlogits, self.dA, self.dT]) for t in lst if t is not None]
+        return sum(t.numel() * t.element_size() for t in ts)

@@ -1,0 +1,138 @@
+"""GPU parity of the deep residual GraphSAGE (ResSAGE+, section 8.1): the pre-activation kernels
+(gnn_layer_norm_relu_fwd / _bwd), the residual add, and whole training steps - with and without activation
+recomputation - against the oracle.  fp32: 1e-4, bf16: 2e-2 per call."""
+import numpy as np
+import pytest
+import torch
+
+import graphgen as gg
+import oracle
+from gpu_util import TOL, as_stored, check, dev, host64, padded
+
+pytestmark = pytest.mark.gpu
+
+SENT = 2468.0
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("F,ld", [(128, 128), (256, 256), (64, 64), (100, 104), (7, 8), (1, 8), (602, 608), (1024, 1024), (65, 72)])
+def test_pre_activation_forward_and_backward(dtype, F, ld):
+    import paper_2311_06837_amd as P
+    print(f"layer norm + relu: F={F} ld={ld} {dtype}", flush=True)
+    rng = np.random.default_rng(F)
+    n, na = 3000, 1777
+    rows = np.sort(rng.choice(n, na, replace=False)).astype(np.int32)
+    rest = np.setdiff1d(np.arange(n), rows)
+    X = as_stored(rng.standard_normal((n, F)) * 1.5 + 0.3, dtype)
+    gamma = (1 + 0.2 * rng.standard_normal(F)).astype(np.float32)
+    beta = (0.2 * rng.standard_normal(F)).astype(np.float32)
+    Xd = padded(X, ld, dtype, fill=float("nan") if ld > F else 0.0)
+    Yd = torch.full((n, ld), SENT, dtype=dtype, device="cuda")
+    P.gnn_layer_norm_relu_fwd(dev(rows), na, Xd, F, dev(gamma), dev(beta), Yd)
+    torch.cuda.synchronize()
+    Y = np.full((n, F), SENT)
+    oracle.ln_relu_fwd(rows, X, F, gamma, beta, Y)
+    got = host64(Yd)
+    sent = host64(torch.tensor(SENT, dtype=dtype))
+    if F > 1:
+        check(got[rows, :F], Y[rows], dtype, "forward")
+    assert (got[rest] == sent).all() and (got[:, F:] == sent).all()
+
+    # backward, masked by the oracle's stored output so both sides pass the same entries
+    Ts = as_stored(Y, dtype)
+    dY = as_stored(rng.standard_normal((n, F)), dtype)
+    dRes = as_stored(rng.standard_normal((n, F)), dtype)
+    n_res = 700
+    dXd = torch.full((n, ld), SENT, dtype=dtype, device="cuda")
+    dg_d, db_d = torch.full((F,), SENT, device="cuda"), torch.full((F,), SENT, device="cuda")
+    P.gnn_layer_norm_relu_bwd(dev(rows), na, padded(dY, ld, dtype, fill=float("nan") if ld > F else 0.0), padded(Ts, ld, dtype), Xd, F,
+                              dev(gamma), padded(dRes, ld, dtype), n_res, dXd, dg_d, db_d)
+    torch.cuda.synchronize()
+    dX = np.full((n, F), SENT)
+    dg, db = oracle.ln_relu_bwd(rows, dY, Ts, X, F, gamma, dX)
+    dX[rows[:n_res]] += dRes[rows[:n_res]]
+    got = host64(dXd)
+    if F > 1:
+        check(got[rows, :F], dX[rows], dtype, "dX")
+        check(host64(dg_d), dg, dtype, "dgamma")
+    check(host64(db_d), db, dtype, "dbeta")
+    assert (got[rest] == sent).all() and (got[:, F:] == sent).all()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_residual_add_and_edge_cases(dtype):
+    import paper_2311_06837_amd as P
+    rng = np.random.default_rng(3)
+    n, F, ld = 900, 100, 104
+    rows = rng.permutation(n)[:333].astype(np.int32)
+    X, Y = as_stored(rng.standard_normal((n, F)), dtype), as_stored(rng.standard_normal((n, F)), dtype)
+    Yd = padded(Y, ld, dtype, fill=SENT)
+    P.gnn_add_rows(dev(rows), len(rows), padded(X, ld, dtype, fill=float("nan")), Yd, F)
+    torch.cuda.synchronize()
+    want = Y.copy()
+    want[rows] = as_stored(Y[rows] + X[rows], dtype)
+    got = host64(Yd)
+    assert np.array_equal(got[:, :F], want) and (got[:, F:] == host64(torch.tensor(SENT, dtype=dtype))).all()
+    # nothing listed: gradients of the scale and shift become zero, nothing else is touched
+    g = torch.ones(F, device="cuda")
+    dg, db = torch.full((F,), 5.0, device="cuda"), torch.full((F,), 5.0, device="cuda")
+    Z = torch.full((n, ld), SENT, dtype=dtype, device="cuda")
+    P.gnn_layer_norm_relu_bwd(None, 0, Z, Z, Z, F, g, None, 0, Z, dg, db)
+    P.gnn_layer_norm_relu_fwd(None, 0, Z, F, g, g, Z)
+    P.gnn_add_rows(None, 0, Z, Z, F)
+    torch.cuda.synchronize()
+    assert not dg.any() and not db.any() and (Z == SENT).all()
+    with pytest.raises(P.GnnError):
+        P.gnn_layer_norm_relu_fwd(None, 1, torch.zeros(4, 2048, device="cuda"), 2048, torch.ones(2048, device="cuda"),
+                                  torch.ones(2048, device="cuda"), torch.zeros(4, 2048, device="cuda"))
+
+
+def _step(part, dims, dtype, seed, recompute, prefix=False):
+    import paper_2311_06837_amd as P
+    g, T = part.graph, part.targets
+    L = len(dims) - 1
+    print(f"res model: n={g.n_rows} nnz={g.nnz} |T|={len(T)} dims={dims} {dtype} recompute={recompute}", flush=True)
+    params = gg.res_layer_weights(dims, seed)
+    H0 = as_stored(gg.features(g.n_rows, dims[0], seed), dtype)
+    y = gg.labels(len(T), dims[-1], seed)
+    om = oracle.ResModel(g.row_ptr, g.col_idx, T, params, bf16=dtype == torch.bfloat16)
+    loss_o = om.forward(H0, y)
+    grads_o = om.backward()
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    m = P.ResSAGEPlus(G, G, dev(T), [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype, recompute=recompute,
+                      prefix_numbered=prefix)
+    m.set_input(padded(H0, P.row_stride(dims[0], dtype), dtype))
+    loss = m.step(dev(y))
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert abs(loss.item() - loss_o) <= tol * L * abs(loss_o), (loss.item(), loss_o)
+    for l in range(1, L + 1):
+        rows = om.rows_of_layer(l)
+        check(host64(m.H[l])[rows, : dims[l]], om.H[l][rows], dtype, f"h_{l}", calls=2 * l)
+    for l in range(L):
+        assert set(grads_o[l]) == set(m.grads[l])
+        for k, want in grads_o[l].items():
+            got = host64(m.grads[l][k])
+            e = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+            assert e <= tol * 2 * (L + 1), (l, k, e)
+    return m
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("recompute", [False, True])
+def test_training_step_against_the_oracle(dtype, recompute):
+    w = gg.make_workload("cfg3", scale=0.02)          # deep halo: the late active sets are the whole partition
+    dims = [w.dims[0]] + [64] * 5 + [w.dims[-1]]      # six layers
+    _step(w.partition, dims, dtype, 3, recompute)
+
+
+def test_recomputation_changes_nothing_and_saves_memory():
+    w = gg.make_workload("cfg0", scale=0.5)
+    dims = [32, 48, 48, 48, 8]
+    a = _step(w.partition, dims, torch.float32, 4, False)
+    b = _step(w.partition, dims, torch.float32, 4, True)
+    assert a.loss.item() == b.loss.item()
+    for ga, gb in zip(a.grads, b.grads):
+        for k in ga:
+            assert torch.equal(ga[k], gb[k]), k
+    assert b.activation_bytes() < a.activation_bytes()
