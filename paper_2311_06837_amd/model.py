@@ -165,15 +165,17 @@ class MaskedGNN:
                 # every edge than the gathers cost: no workspace -> the one-launch route.
                 ws_bwd = self.ws if 4 * nl >= self.n else None
                 gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[l], self.rs_l[l])
+                # when the forward call computed every vertex of the partition the filter keeps everything: leave it out
+                dist_l = None if nl == self.n else self.dist
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
-                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, nl, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, nl, dist_l, L - l, self.dA[l], self.dH[l - 1], K,
                                           rs_l, self.cs, accumulate=True, ws=ws_bwd)
                     if n_prev > nl:
-                        self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, gt_l, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA[l],
+                        self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, gt_l, self.ring_ids[nl:], n_prev - nl, dist_l, L - l, self.dA[l],
                                               self.dH[l - 1], K, rs_l, self.cs, accumulate=False, ws=ws_bwd)
                 else:
-                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, self.dist, L - l, self.dA[l], self.dH[l - 1], K,
+                    self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dA[l], self.dH[l - 1], K,
                                           rs_l, self.cs, accumulate=False, ws=ws_bwd)
         return self.grads
 
@@ -319,11 +321,12 @@ class ResSAGEPlus:
             if not need_in:
                 break
             n_prev = self.n_rows_of_layer(l - 1)
+            dist_l = None if nl == self.n else self.dist    # every vertex was a forward row: the filter keeps everything
             # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
-            self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, nl, self.dist, L - l, self.dA, self.dT, K,
+            self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, nl, dist_l, L - l, self.dA, self.dT, K,
                        self.rs, None, accumulate=True, ws=None)
             if n_prev > nl:
-                self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, self.dist, L - l, self.dA,
+                self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, dist_l, L - l, self.dA,
                            self.dT, K, self.rs, None, accumulate=False, ws=None)
             out = self.dH[l % 2]
             self._call(f"ln_bwd_{l}", B.gnn_layer_norm_relu_bwd, self.rows, n_prev, self.dT, src, self.H[l - 1], K, p["ln_gamma"],
