@@ -5,7 +5,7 @@ import torch
 import oracle
 from conftest import rel_err
 
-TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}   # the benchmark spec tolerances
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}   # relative-error bars: fp32 arithmetic, bf16 storage
 
 
 def dev(a, dtype=None):
