@@ -270,8 +270,8 @@ def main():
         tf, tb = call_ms.get(f"linear_fwd_{l}", 0.0) * 1e-3, call_ms.get(f"linear_bwd_{l}", 0.0) * 1e-3
         peak = MFMA_PEAK_TFLOPS[w.dtype]
         b_fwd = nl * (K * srcs + N) * es
-        # backward: dH and H in, dZ written and read back by both products, the layer inputs in, their gradients out
-        b_bwd = nl * (2 * N + 3 * N + K * srcs) * es + (nl * K * srcs * es if l > 1 else 0)
+        # backward, every operand once: the (already masked) output gradient and the layer inputs in, the input gradients out
+        b_bwd = nl * (N + K * srcs) * es + (nl * K * srcs * es if l > 1 else 0)
         # the roof that binds a product this skinny: the slower of "operands at the HBM peak" and "flops at the MFMA peak"
         roof_f = max(b_fwd / (HBM_PEAK_GBS * 1e9), f_fwd / (peak * 1e12))
         roof_b = max(b_bwd / (HBM_PEAK_GBS * 1e9), f_bwd / (peak * 1e12))

@@ -136,12 +136,18 @@ int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_act
  *     dX[u, 0:F] (+)= col_scale[u] * sum_{v in rowT(u), active(v)} row_scale[v] * dY[v, 0:F]   for u in out_rows
  *   active(v)   dist == NULL: always; else 0 <= dist[v] <= max_active_dist  (v was a row of the forward call)
  *   accumulate  0: overwrite dX rows, 1: add to them
+ *   relu_H      nullable: the activations H of the layer whose gradient dX is (same rows, F columns, leading
+ *               dimension ld_relu).  What is stored (after the addition of accumulate) is zeroed where H <= 0, i.e. dX
+ *               leaves the call as the gradient in front of that layer's ReLU (the chain rule's next factor), and
+ *               gnn_linear_bwd of that layer is then called with relu = 0.  The call that writes a row LAST must be the
+ *               one that masks it.
  * Same determinism and the same optional workspace as the forward call.
  */
 int32_t gnn_masked_spmm_bwd(const gnn_csr *gT, const int32_t *out_rows, int32_t n_out,
                             const int32_t *dist, int32_t max_active_dist,
                             const void *dY, int64_t lddy, void *dX, int64_t lddx, int32_t F, int32_t dtype,
                             const float *row_scale, const float *col_scale, int32_t accumulate,
+                            const void *relu_H, int64_t ld_relu,
                             void *ws, size_t *ws_bytes, void *stream);
 
 /*

@@ -678,6 +678,7 @@ struct GemmTN {
     int32_t rows_per_split; // multiple of 32
     int32_t n_splits;
     float* P;               // [splits][n_src*K][N]
+    float* Pb;              // nullable: [splits][N] column sums of D over each split (the bias gradient's partial sums)
 };
 
 template <int DT, int BN, bool VEC>
@@ -695,6 +696,7 @@ __global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
     constexpr int A_LDW = BKO * DTy<DT>::ES / 4 + 8, D_LDW = BN * DTy<DT>::ES / 4 + 8;
     __shared__ uint32_t sA[BMR * A_LDW];
     __shared__ uint32_t sD[BMR * D_LDW];
+    __shared__ float s_bs[BMR * D_VPR * EPV];   // column sums of D, per tile row, before they are added up
 
     const int ko_tiles = (a.K + BKO - 1) / BKO;
     const int n_tiles = (a.N + BN - 1) / BN;
@@ -723,6 +725,14 @@ __global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // the workgroups of the first k-tile of the first source also add up the columns of D (each thread keeps the sums
+    // of the chunk positions it loads; tile rows are added in order afterwards)
+    const bool do_bias = a.Pb != nullptr && src == 0 && tk == 0;
+    float bs[D_CH][EPV];
+#pragma unroll
+    for (int c = 0; c < D_CH; ++c)
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) bs[c][e] = 0.f;
     uint4 ra[A_CH], rd[D_CH];
     auto fetch = [&](int64_t mb) {
 #pragma unroll
@@ -761,6 +771,18 @@ __global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
             const int v = tid + 256 * c;
             if (VEC && edge) rd[c] = fix_chunk<DT>(rd[c], mb + v / D_VPR < m_end ? a.N - (n0 + (v % D_VPR) * EPV) : 0);
             if (v / D_VPR < BMR) *(uint4*)&sD[(v / D_VPR) * D_LDW + (v % D_VPR) * 4] = rd[c];
+            if (do_bias && v / D_VPR < BMR) {
+                const uint32_t w[4] = {rd[c].x, rd[c].y, rd[c].z, rd[c].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (DT == GNN_F32) {
+                        bs[c][q] += __uint_as_float(w[q]);
+                    } else {
+                        bs[c][2 * q] += bf16lo(w[q]);
+                        bs[c][2 * q + 1] += bf16hi(w[q]);
+                    }
+                }
+            }
         }
     };
 
@@ -829,6 +851,22 @@ __global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
         }
     }
 
+    if (do_bias) {   // uniform over the workgroup
+#pragma unroll
+        for (int c = 0; c < D_CH; ++c) {
+            const int v = tid + 256 * c;
+            if (v < BMR * D_VPR) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) s_bs[v * EPV + e] = bs[c][e];
+            }
+        }
+        __syncthreads();
+        for (int col = tid; col < BN; col += 256) {
+            float t = 0.f;
+            for (int r = 0; r < BMR; ++r) t += s_bs[(r * D_VPR + col / EPV) * EPV + col % EPV];
+            if (n0 + col < a.N) a.Pb[(int64_t)split * a.N + n0 + col] = t;
+        }
+    }
     float* P = a.P + ((int64_t)split * a.n_src + src) * (int64_t)a.K * a.N;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -998,22 +1036,32 @@ template <int DT>
 static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, const void* H, int64_t ld_out, int32_t relu,
                                const void* A, const void* Xs, int64_t ld_in, int32_t K, const void* Wn, const void* Ws, int32_t N,
                                float* dWn, float* dWs, float* dbias, void* dA, void* dXs, int64_t ld_din, void* dZ, int64_t ldz,
-                               float* part, int32_t n_part, float* P, int32_t splits, int32_t rows_per_split, hipStream_t stream) {
+                               float* part, int32_t n_part, float* P, float* Pb, int32_t splits, int32_t rows_per_split,
+                               hipStream_t stream) {
     constexpr int ES = DTy<DT>::ES;
-    const int n_vec = (N + DTy<DT>::EPV - 1) / DTy<DT>::EPV;
-    int cx = 4;
-    while (cx < n_vec && cx < 256) cx <<= 1;
-    const int io_vec = vec_ok(dH, ld_out, ES) && (!relu || vec_ok(H, ld_out, ES));
-    dz_kernel<DT><<<n_part, 256, 0, stream>>>(rows, M, dH, H, ld_out, io_vec, relu, N, dZ, ldz, part, cx);
-    GNN_LAUNCH_CHECK("dz_kernel");
-    reduce_rows_kernel<<<(N + 31) / 32, 1024, 0, stream>>>(part, n_part, N, dbias);
-    GNN_LAUNCH_CHECK("reduce_rows_kernel");
+    // Without an activation to undo and without a row list, dH IS the compact dZ: no copy is made, the products read
+    // dH in place and the weight-gradient kernel adds up the bias gradient on its way.
+    const bool in_place = rows == nullptr && !relu && vec_ok(dH, ld_out, ES);
+    if (in_place) {
+        dZ = const_cast<void*>(dH);
+        ldz = ld_out;
+    } else {
+        const int n_vec = (N + DTy<DT>::EPV - 1) / DTy<DT>::EPV;
+        int cx = 4;
+        while (cx < n_vec && cx < 256) cx <<= 1;
+        const int io_vec = vec_ok(dH, ld_out, ES) && (!relu || vec_ok(H, ld_out, ES));
+        dz_kernel<DT><<<n_part, 256, 0, stream>>>(rows, M, dH, H, ld_out, io_vec, relu, N, dZ, ldz, part, cx);
+        GNN_LAUNCH_CHECK("dz_kernel");
+        reduce_rows_kernel<<<(N + 31) / 32, 1024, 0, stream>>>(part, n_part, N, dbias);
+        GNN_LAUNCH_CHECK("reduce_rows_kernel");
+    }
 
     GemmTN t;
     t.A[0] = A; t.A[1] = Xs; t.n_src = Xs ? 2 : 1; t.lda = ld_in;
     t.a_vec = vec_ok(A, ld_in, ES) && (!Xs || vec_ok(Xs, ld_in, ES));
     t.a_rows = rows; t.D = dZ; t.ldd = ldz; t.d_vec = vec_ok(dZ, ldz, ES);
     t.M = M; t.N = N; t.K = K; t.rows_per_split = rows_per_split; t.n_splits = splits; t.P = P;
+    t.Pb = in_place ? Pb : nullptr;
     const int ko_tiles = (K + 127) / 128;
     if (N > 32) {
         const int64_t total = (int64_t)t.n_src * ko_tiles * ((N + 127) / 128) * splits;
@@ -1028,6 +1076,10 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
     reduce_partials_kernel<<<grid_for((int64_t)t.n_src * K * N, 256, 2048), 256, 0, stream>>>(P, splits, t.n_src, (int64_t)K * N, dWn,
                                                                                             dWs);
     GNN_LAUNCH_CHECK("reduce_partials_kernel");
+    if (in_place) {
+        reduce_rows_kernel<<<(N + 31) / 32, 1024, 0, stream>>>(Pb, splits, N, dbias);
+        GNN_LAUNCH_CHECK("reduce_rows_kernel");
+    }
 
     // input gradients: dA = dZ W_neigh^T, dX_self = dZ W_self^T   (Bt = W as stored: [K][N])
     for (int which = 0; which < 2; ++which) {
@@ -1114,6 +1166,7 @@ extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const v
     char* dZ = carve.take<char>((size_t)(n_active > 0 ? n_active : 1) * ldz * es);
     float* part = carve.take<float>((size_t)n_part * N);
     float* P = carve.take<float>((size_t)splits * n_src * K * N);
+    float* Pb = carve.take<float>((size_t)splits * N);
     bool query;
     GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
     if (query) return GNN_OK;
@@ -1129,9 +1182,9 @@ extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const v
     GNN_REQUIRE(!relu || H_out, GNN_ERR_INVALID_ARG, "relu backward needs H_out");
     if (dtype == GNN_F32)
         return linear_bwd_impl<GNN_F32>(rows, n_active, dH_out, H_out, ld_out, relu, A_neigh, X_self, ld_in, K, W_neigh, W_self, N,
-                                        dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, splits,
+                                        dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, Pb, splits,
                                         rows_per_split, stream);
     return linear_bwd_impl<GNN_BF16>(rows, n_active, dH_out, H_out, ld_out, relu, A_neigh, X_self, ld_in, K, W_neigh, W_self, N,
-                                     dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, splits,
+                                     dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, Pb, splits,
                                      rows_per_split, stream);
 }

@@ -71,6 +71,8 @@ struct SpmmArgs {
     int32_t max_dist;
     const uint32_t* edge_keep;  // nullable filter: keep the entry at position p iff bit p is set (layer-wise sampling mask)
     int32_t accumulate;
+    const void* relu_h;       // nullable: the stored result is zeroed where this matrix (same rows and columns as Y) is <= 0
+    int64_t ldh;
     int32_t rows_per_group;   // 1..kRowsPerGroup: rows of the list per LPR-lane group in one workgroup
     // column-blocked route only
     const int32_t* seg;       // [n_active][n_blocks + 1] cut points of every listed row: block j = [seg[j], seg[j+1])
@@ -95,17 +97,27 @@ struct Elem<GNN_F32, 4> {
         acc[2] = fmaf(w, __uint_as_float(r.z), acc[2]);
         acc[3] = fmaf(w, __uint_as_float(r.w), acc[3]);
     }
-    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[4], int n_valid, bool accumulate) {
+    // h (nullable): activation matrix of the same layout position hoff; what is stored is zeroed where h <= 0
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[4], int n_valid, bool accumulate,
+                                                 const void* h = nullptr, int64_t hoff = 0) {
         float* q = (float*)p + off;
+        const float* hq = (const float*)h + hoff;
         if (n_valid >= 4) {
             float4 o = make_float4(v[0], v[1], v[2], v[3]);
             if (accumulate) {
                 float4 old = *(const float4*)q;
                 o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
             }
+            if (h) {
+                const float4 m = *(const float4*)hq;
+                o.x = m.x > 0.f ? o.x : 0.f; o.y = m.y > 0.f ? o.y : 0.f; o.z = m.z > 0.f ? o.z : 0.f; o.w = m.w > 0.f ? o.w : 0.f;
+            }
             *(float4*)q = o;
         } else {
-            for (int e = 0; e < n_valid; ++e) q[e] = accumulate ? q[e] + v[e] : v[e];
+            for (int e = 0; e < n_valid; ++e) {
+                const float t = accumulate ? q[e] + v[e] : v[e];
+                q[e] = (h == nullptr || hq[e] > 0.f) ? t : 0.f;
+            }
         }
     }
 };
@@ -115,10 +127,15 @@ struct Elem<GNN_F32, 1> {
     static constexpr int VE = 1;
     using Raw = float;
     static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return ((const float*)p)[off]; }
+    static __device__ __forceinline__ float to_float(Raw r) { return r; }
     static __device__ __forceinline__ void fma(float (&acc)[1], float w, const Raw& r) { acc[0] = fmaf(w, r, acc[0]); }
-    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[1], int n_valid, bool accumulate) {
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[1], int n_valid, bool accumulate,
+                                                 const void* h = nullptr, int64_t hoff = 0) {
         float* q = (float*)p + off;
-        if (n_valid >= 1) q[0] = accumulate ? q[0] + v[0] : v[0];
+        if (n_valid >= 1) {
+            const float t = accumulate ? q[0] + v[0] : v[0];
+            q[0] = (h == nullptr || ((const float*)h)[hoff] > 0.f) ? t : 0.f;
+        }
     }
 };
 
@@ -133,8 +150,10 @@ struct Elem<GNN_BF16, 8> {
         acc[4] = fmaf(w, bf16lo(r.z), acc[4]); acc[5] = fmaf(w, bf16hi(r.z), acc[5]);
         acc[6] = fmaf(w, bf16lo(r.w), acc[6]); acc[7] = fmaf(w, bf16hi(r.w), acc[7]);
     }
-    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[8], int n_valid, bool accumulate) {
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[8], int n_valid, bool accumulate,
+                                                 const void* h = nullptr, int64_t hoff = 0) {
         uint16_t* q = (uint16_t*)p + off;
+        const uint16_t* hq = (const uint16_t*)h + hoff;
         if (n_valid >= 8) {
             float t[8];
 #pragma unroll
@@ -144,12 +163,22 @@ struct Elem<GNN_BF16, 8> {
                 t[0] += bf16lo(old.x); t[1] += bf16hi(old.x); t[2] += bf16lo(old.y); t[3] += bf16hi(old.y);
                 t[4] += bf16lo(old.z); t[5] += bf16hi(old.z); t[6] += bf16lo(old.w); t[7] += bf16hi(old.w);
             }
+            if (h) {
+                const uint4 m = *(const uint4*)hq;
+                t[0] = bf16lo(m.x) > 0.f ? t[0] : 0.f; t[1] = bf16hi(m.x) > 0.f ? t[1] : 0.f;
+                t[2] = bf16lo(m.y) > 0.f ? t[2] : 0.f; t[3] = bf16hi(m.y) > 0.f ? t[3] : 0.f;
+                t[4] = bf16lo(m.z) > 0.f ? t[4] : 0.f; t[5] = bf16hi(m.z) > 0.f ? t[5] : 0.f;
+                t[6] = bf16lo(m.w) > 0.f ? t[6] : 0.f; t[7] = bf16hi(m.w) > 0.f ? t[7] : 0.f;
+            }
             uint4 o;
             o.x = pack_bf16(t[0], t[1]); o.y = pack_bf16(t[2], t[3]);
             o.z = pack_bf16(t[4], t[5]); o.w = pack_bf16(t[6], t[7]);
             *(uint4*)q = o;
         } else {
-            for (int e = 0; e < n_valid; ++e) q[e] = f32_to_bf16(accumulate ? bf16_to_f32(q[e]) + v[e] : v[e]);
+            for (int e = 0; e < n_valid; ++e) {
+                const float t = accumulate ? bf16_to_f32(q[e]) + v[e] : v[e];
+                q[e] = f32_to_bf16((h == nullptr || bf16_to_f32(hq[e]) > 0.f) ? t : 0.f);
+            }
         }
     }
 };
@@ -159,10 +188,15 @@ struct Elem<GNN_BF16, 1> {
     static constexpr int VE = 1;
     using Raw = uint16_t;
     static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return ((const uint16_t*)p)[off]; }
+    static __device__ __forceinline__ float to_float(Raw r) { return bf16_to_f32(r); }
     static __device__ __forceinline__ void fma(float (&acc)[1], float w, const Raw& r) { acc[0] = fmaf(w, bf16_to_f32(r), acc[0]); }
-    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[1], int n_valid, bool accumulate) {
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[1], int n_valid, bool accumulate,
+                                                 const void* h = nullptr, int64_t hoff = 0) {
         uint16_t* q = (uint16_t*)p + off;
-        if (n_valid >= 1) q[0] = f32_to_bf16(accumulate ? bf16_to_f32(q[0]) + v[0] : v[0]);
+        if (n_valid >= 1) {
+            const float t = accumulate ? bf16_to_f32(q[0]) + v[0] : v[0];
+            q[0] = f32_to_bf16((h == nullptr || bf16_to_f32(((const uint16_t*)h)[hoff]) > 0.f) ? t : 0.f);
+        }
     }
 };
 
@@ -368,7 +402,8 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
 #pragma unroll
                         for (int k = 0; k < VE; ++k) o[k] = acc[c][k] * sc;
                         const int64_t rest = (int64_t)a.F - col_off[c];
-                        E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, rest >= VE ? VE : (int)rest, a.accumulate != 0);
+                        E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, rest >= VE ? VE : (int)rest, a.accumulate != 0, a.relu_h,
+                                 (int64_t)v * a.ldh + col_off[c]);
                     }
                 }
             }
@@ -420,7 +455,7 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
 #pragma unroll
                 for (int r = 0; r < NG; ++r) t += s_red[r][col];
                 float o[1] = {t * sc};
-                Elem<DT, 1>::store(a.Y, (int64_t)hv * a.ldy + gcol, o, 1, a.accumulate != 0);
+                Elem<DT, 1>::store(a.Y, (int64_t)hv * a.ldy + gcol, o, 1, a.accumulate != 0, a.relu_h, (int64_t)hv * a.ldh + gcol);
             }
         }
         __syncthreads();
@@ -563,7 +598,7 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
                     const int64_t rest = (int64_t)a.F - col_off[c];
                     const int n_valid = rest >= VE ? VE : (int)rest;
                     if (PART) store_part<VE>(part, (int64_t)v * a.ldy + col_off[c], o, n_valid, a.accumulate != 0);
-                    else E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, n_valid, a.accumulate != 0);
+                    else E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, n_valid, a.accumulate != 0, a.relu_h, (int64_t)v * a.ldh + col_off[c]);
                 }
             }
         } else {  // a piece: head (the row began in an earlier stretch) or tail (it goes on in the next one)
@@ -874,7 +909,7 @@ __global__ __launch_bounds__(256) void spmm_prepare_kernel(const int32_t* __rest
 template <int DT>
 __global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __restrict__ part, int64_t ldp, const int32_t* __restrict__ rows,
                                                               int32_t n_active, int32_t F, void* __restrict__ Y, int64_t ldy,
-                                                              const float* __restrict__ out_scale, int32_t accumulate) {
+                                                              const float* __restrict__ out_scale, int32_t accumulate, const void* __restrict__ relu_h, int64_t ldh) {
     const int32_t f4 = (F + 3) / 4;
     const int64_t total = (int64_t)n_active * f4;
     const int64_t plane = (int64_t)n_active * ldp;
@@ -891,6 +926,11 @@ __global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __rest
         float o[4] = {t.x * sc, t.y * sc, t.z * sc, t.w * sc};
         const int n_valid = F - c >= 4 ? 4 : F - c;
         const int64_t off = (int64_t)v * ldy + c;
+        // the stored value is zeroed where relu_h (same rows and columns as Y) is <= 0
+        bool pass[4] = {true, true, true, true};
+        if (relu_h) {
+            for (int k = 0; k < n_valid; ++k) pass[k] = Elem<DT, 1>::to_float(Elem<DT, 1>::load(relu_h, (int64_t)v * ldh + c + k)) > 0.f;
+        }
         if (DT == GNN_F32) {
             float* y = (float*)Y + off;
             if (n_valid == 4) {
@@ -899,9 +939,10 @@ __global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __rest
                     const float4 old = *(const float4*)y;
                     w.x += old.x; w.y += old.y; w.z += old.z; w.w += old.w;
                 }
+                w.x = pass[0] ? w.x : 0.f; w.y = pass[1] ? w.y : 0.f; w.z = pass[2] ? w.z : 0.f; w.w = pass[3] ? w.w : 0.f;
                 *(float4*)y = w;
             } else {
-                for (int k = 0; k < n_valid; ++k) y[k] = accumulate ? y[k] + o[k] : o[k];
+                for (int k = 0; k < n_valid; ++k) y[k] = pass[k] ? (accumulate ? y[k] + o[k] : o[k]) : 0.f;
             }
         } else {
             uint16_t* y = (uint16_t*)Y + off;
@@ -910,9 +951,11 @@ __global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __rest
                     const uint2 old = *(const uint2*)y;
                     o[0] += bf16lo(old.x); o[1] += bf16hi(old.x); o[2] += bf16lo(old.y); o[3] += bf16hi(old.y);
                 }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = pass[k] ? o[k] : 0.f;
                 *(uint2*)y = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
             } else {
-                for (int k = 0; k < n_valid; ++k) y[k] = f32_to_bf16(accumulate ? bf16_to_f32(y[k]) + o[k] : o[k]);
+                for (int k = 0; k < n_valid; ++k) y[k] = f32_to_bf16(pass[k] ? (accumulate ? bf16_to_f32(y[k]) + o[k] : o[k]) : 0.f);
             }
         }
     }
@@ -1001,7 +1044,7 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
         GNN_CHECK((launch_stream<DT, VE, 16, 1, true>(b, p.avg_seg, stream)));
     }
     spmm_sum_parts_kernel<DT><<<grid_for((int64_t)a.n_active * ((a.F + 3) / 4), 256, 1 << 16), 256, 0, stream>>>(
-        part, p.ldp, a.rows, a.n_active, a.F, a.Y, a.ldy, a.out_scale, a.accumulate);
+        part, p.ldp, a.rows, a.n_active, a.F, a.Y, a.ldy, a.out_scale, a.accumulate, a.relu_h, a.ldh);
     GNN_LAUNCH_CHECK("spmm_sum_parts_kernel");
     return GNN_OK;
 }
@@ -1021,8 +1064,8 @@ static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
 
 static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* rows, int32_t n_active, const int32_t* dist,
                            int32_t max_dist, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F, int32_t dtype,
-                           const float* out_scale, const float* nbr_scale, int32_t accumulate, void* ws, size_t* ws_bytes,
-                           hipStream_t stream) {
+                           const float* out_scale, const float* nbr_scale, int32_t accumulate, const void* relu_h, int64_t ldh,
+                           void* ws, size_t* ws_bytes, hipStream_t stream) {
     GNN_CHECK(check_csr(g, gname));
     GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative row count");
     GNN_REQUIRE(rows != nullptr || n_active <= g->n_rows, GNN_ERR_SHAPE, "n_active %d exceeds n_rows %d", n_active, g->n_rows);
@@ -1030,7 +1073,9 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     GNN_REQUIRE(F >= 0, GNN_ERR_INVALID_ARG, "F < 0");
     GNN_REQUIRE(ldx >= F && ldy >= F, GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
     const int ve = dtype == GNN_F32 ? 4 : 8;
-    const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0;
+    GNN_REQUIRE(relu_h == nullptr || ldh >= F, GNN_ERR_SHAPE, "ld_relu smaller than F = %d", F);
+    const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0 &&
+                        (relu_h == nullptr || ((uintptr_t)relu_h % 16 == 0 && ldh % ve == 0));
     const bool filter = dist != nullptr || g->edge_keep != nullptr;
     BlockedPlan plan;
     if (ws_bytes != nullptr) {
@@ -1059,6 +1104,7 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = dist ? max_dist : INT32_MAX;
     a.edge_keep = g->edge_keep;
     a.accumulate = accumulate;
+    a.relu_h = relu_h; a.ldh = ldh;
     a.rows_per_group = 1;
     a.seg = nullptr; a.seg_end = nullptr; a.edge_w = nullptr; a.n_blocks = 0; a.block0 = 0;
 
@@ -1077,15 +1123,15 @@ using namespace gnnhot;
 extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
                                        void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
                                        const float* col_scale, void* ws, size_t* ws_bytes, void* stream) {
-    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, ws, ws_bytes,
-                       (hipStream_t)stream);
+    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, nullptr, 0, ws,
+                       ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int32_t gnn_masked_spmm_bwd(const gnn_csr* gT, const int32_t* out_rows, int32_t n_out, const int32_t* dist,
                                        int32_t max_active_dist, const void* dY, int64_t lddy, void* dX, int64_t lddx, int32_t F,
                                        int32_t dtype, const float* row_scale, const float* col_scale, int32_t accumulate,
-                                       void* ws, size_t* ws_bytes, void* stream) {
+                                       const void* relu_H, int64_t ld_relu, void* ws, size_t* ws_bytes, void* stream) {
     GNN_REQUIRE(accumulate == 0 || accumulate == 1, GNN_ERR_INVALID_ARG, "accumulate must be 0 or 1");
     return spmm_common(gT, "gT", out_rows, n_out, dist, max_active_dist, dY, lddy, dX, lddx, F, dtype, col_scale, row_scale,
-                       accumulate, ws, ws_bytes, (hipStream_t)stream);
+                       accumulate, relu_H, ld_relu, ws, ws_bytes, (hipStream_t)stream);
 }

@@ -154,7 +154,8 @@ class MaskedGNN:
             nl = self.n_rows_of_layer(l)
             sage = self.kind == "sage"
             need_in = l > 1
-            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], self.H[l] if l < L else None, l < L, self.A[l],
+            # dH_l arrives with the ReLU of layer l already undone: the aggregation call that wrote it last masked it
+            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
                              self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
                              gr["dW_neigh"], gr.get("dW_self"), gr["dbias"],
                              self.dA[l] if need_in else None, self.dH[l - 1] if (need_in and sage) else None, ws=self.ws)
@@ -167,16 +168,17 @@ class MaskedGNN:
                 gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[l], self.rs_l[l])
                 # when the forward call computed every vertex of the partition the filter keeps everything: leave it out
                 dist_l = None if nl == self.n else self.dist
+                relu_h = self.H[l - 1]      # layer l-1 ends in a ReLU (l-1 < L): its gradient leaves the aggregation masked
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, nl, dist_l, L - l, self.dA[l], self.dH[l - 1], K,
-                                          rs_l, self.cs, accumulate=True, ws=ws_bwd)
+                                          rs_l, self.cs, accumulate=True, ws=ws_bwd, relu_H=relu_h)
                     if n_prev > nl:
                         self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, gt_l, self.ring_ids[nl:], n_prev - nl, dist_l, L - l, self.dA[l],
-                                              self.dH[l - 1], K, rs_l, self.cs, accumulate=False, ws=ws_bwd)
+                                              self.dH[l - 1], K, rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h)
                 else:
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dA[l], self.dH[l - 1], K,
-                                          rs_l, self.cs, accumulate=False, ws=ws_bwd)
+                                          rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h)
         return self.grads
 
     def step(self, labels: torch.Tensor):

@@ -95,6 +95,19 @@ def test_large_row_count_many_splits():
     _case(70000, 65537, 128, 128, torch.bfloat16, sage=True, relu=True, use_rows=True, aligned=True, seed=7)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_backward_without_activation_and_row_list_reads_the_gradient_in_place(dtype):
+    """No ReLU to undo and rows = NULL: no compact copy of the gradient is made and the bias gradient is summed inside
+    the weight-gradient kernel (many row splits, ragged last tile, narrow and unaligned widths)."""
+    _case(70000, 65537, 256, 256, dtype, sage=True, relu=False, use_rows=False, aligned=True, seed=21)
+    _case(9000, 8999, 128, 128, dtype, sage=True, relu=False, use_rows=False, aligned=True, seed=22)
+    _case(5000, 4097, 100, 256, dtype, sage=False, relu=False, use_rows=False, aligned=True, seed=23)
+    _case(5000, 3000, 256, 41, dtype, sage=True, relu=False, use_rows=False, aligned=True, seed=24)
+    _case(3000, 1234, 64, 16, dtype, sage=True, relu=False, use_rows=False, aligned=True, seed=25)
+    _case(900, 31, 64, 64, dtype, sage=False, relu=False, use_rows=False, aligned=True, seed=26)       # fewer rows than a tile
+    _case(500, 257, 602, 41, dtype, sage=True, relu=False, use_rows=False, aligned=False, seed=27)     # unaligned: copies after all
+
+
 def test_zero_active_rows_zeroes_the_weight_gradients():
     import paper_2311_06837_amd as P
     K, N = 16, 8

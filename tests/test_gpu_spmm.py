@@ -94,10 +94,11 @@ def test_fwd_is_bitwise_reproducible():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
-def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed, ws=None):
-    """Backward of layer `lyr` of an L-layer model: forward rows R_lyr, outputs for R_{lyr-1}."""
+def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed, ws=None, relu=False):
+    """Backward of layer `lyr` of an L-layer model: forward rows R_lyr, outputs for R_{lyr-1}.  relu: the call also
+    undoes the ReLU of the layer in front (what it stores is zeroed where that layer's activations are <= 0)."""
     import paper_2311_06837_amd as P
-    print(f"spmm bwd: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} L={L} layer={lyr} acc={accumulate}", flush=True)
+    print(f"spmm bwd: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} L={L} layer={lyr} acc={accumulate} relu={relu}", flush=True)
     rng = np.random.default_rng(seed)
     n = g.n_rows
     T = np.sort(rng.choice(n, max(1, n // 50), replace=False)).astype(np.int32)
@@ -112,8 +113,9 @@ def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed, ws=None):
     GT = P.Graph.from_numpy(gt.row_ptr, gt.col_idx)
     dYd = padded(dY, ld, dtype)
     dXd = padded(init, ld, dtype, fill=SENTINEL)
+    Hact = as_stored(np.maximum(rng.standard_normal((n, F)), 0), dtype) if relu else None     # about half of it is zero
     P.gnn_masked_spmm_bwd(GT, dev(rows_o), len(rows_o), dev(dist), L - lyr, dYd, dXd, F, dev(rs), dev(cs), accumulate=accumulate,
-                          ws=ws)
+                          ws=ws, relu_H=padded(Hact, ld, dtype, fill=float("nan") if ld > F else 0.0) if relu else None)
     torch.cuda.synchronize()
     want = np.zeros((n, F))
     oracle.spmm_bwd(g.row_ptr, g.col_idx, rows_f, dY, want, F, rs, cs)
@@ -122,6 +124,8 @@ def _bwd_case(g, F, ld, dtype, L, lyr, accumulate, seed, ws=None):
     assert not want[outside].any()
     if accumulate:
         want = want + init
+    if relu:
+        want = want * (Hact > 0)
     got = host64(dXd)
     check(got[rows_o, :F], want[rows_o], dtype, "bwd rows")
     assert (got[outside, :F] == host64(padded(init, ld, dtype, fill=SENTINEL))[outside, :F]).all(), "rows outside were written"
@@ -134,6 +138,18 @@ def test_bwd_directed_graph_with_filter(dtype, accumulate):
     _bwd_case(g, 128, 128, dtype, 3, 3, accumulate, 5)
     _bwd_case(g, 256, 256, dtype, 3, 2, accumulate, 6)
     _bwd_case(g, 602, 608, dtype, 2, 2, accumulate, 7)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_bwd_that_undoes_the_relu_in_front(dtype, accumulate):
+    g = gg.random_directed(8000, 6.0, 22)
+    _bwd_case(g, 128, 128, dtype, 3, 3, accumulate, 15, relu=True)
+    _bwd_case(g, 602, 608, dtype, 2, 2, accumulate, 16, relu=True)
+    _bwd_case(g, 100, 100, dtype, 2, 2, accumulate, 17, relu=True)       # unaligned for bf16: element route
+    _bwd_case(g, 7, 7, dtype, 2, 2, accumulate, 18, relu=True)
+    h = gg.chung_lu(12000, 150.0, 2.1, 12)                                # hub rows: reduced through LDS, then masked
+    _bwd_case(h, 64, 64, dtype, 2, 2, accumulate, 19, relu=True)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -198,6 +214,7 @@ def test_blocked_route_backward_with_filter(dtype, accumulate):
     ws = P.Workspace()
     _bwd_case(g, 136, 136, dtype, 2, 2, accumulate, 44, ws=ws)            # forward rows = targets only: most neighbours filtered out
     assert _used_blocked_route(ws)
+    _bwd_case(g, 136, 136, dtype, 2, 2, accumulate, 45, ws=ws, relu=True)  # the plane sum undoes the ReLU in front
 
 
 def test_blocked_route_falls_back_without_promise_or_density():
