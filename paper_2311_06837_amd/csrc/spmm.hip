@@ -961,6 +961,26 @@ __global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __rest
     }
 }
 
+// Xs[u, 0:F] = scale[u] * X[u, 0:F] for every row of the gathered matrix (16-byte aligned rows): with a neighbour scale
+// the column-blocked route gathers from this copy, so its inner loop needs no per-edge factor.
+template <int DT>
+__global__ __launch_bounds__(256) void spmm_scale_rows_kernel(const void* __restrict__ X, int64_t ldx, int32_t n_rows, int32_t F,
+                                                              const float* __restrict__ scale, void* __restrict__ Xs) {
+    using E = Elem<DT, DT == GNN_F32 ? 4 : 8>;
+    constexpr int VE = E::VE;
+    const int vpr = (F + VE - 1) / VE;
+    const int64_t total = (int64_t)n_rows * vpr;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t u = t / vpr;
+        const int64_t off = u * ldx + (t % vpr) * VE;
+        float acc[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) acc[e] = 0.f;
+        E::fma(acc, scale[u], E::load(X, off));
+        E::store(Xs, off, acc, VE, false);
+    }
+}
+
 // The column-blocked route's shape for one call; passes == 0: the route does not apply.
 struct BlockedPlan {
     int passes = 0;
@@ -969,14 +989,15 @@ struct BlockedPlan {
     int64_t ldp = 0;          // leading dimension of a partial plane, in floats
     size_t seg_bytes = 0, part_bytes = 0;
     size_t end_bytes = 0, ids_bytes = 0;   // with a filter or a neighbour scale: segment ends and the (compacted) copy of the ids
-    size_t w_bytes = 0;                    // with a neighbour scale: the factor of every copied id
+    size_t xs_bytes = 0;                   // fp32 with a neighbour scale: the gathered matrix with its rows scaled
+    size_t w_bytes = 0;                    // bf16 with a neighbour scale: the factor of every copied id
     int64_t avg_seg = 0;      // average neighbours of a row inside one column block
     int32_t n_cols = 0;
     size_t bounds_bytes = 0;  // with a filter: the column-block boundaries (balanced over the active vertices)
 };
 
 static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, int64_t row_bytes, bool vec_ok, bool filter,
-                                bool scaled) {
+                                bool scaled, bool f32) {
     BlockedPlan p;
     // the stream kernel addresses the gathered matrix with 32-bit offsets in 16-byte units: 64 GB at most
     if ((int64_t)g->n_cols * row_bytes >= ((int64_t)1 << 36)) return p;
@@ -994,11 +1015,14 @@ static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, i
     p.ldp = ((int64_t)F + 7) / 8 * 8;
     p.seg_bytes = (size_t)n_active * (n_blocks + 1) * sizeof(int32_t);
     p.part_bytes = (size_t)kDies * n_active * p.ldp * sizeof(float);
-    if (filter || scaled) {
+    // A neighbour scale: fp32 gathers from a copy of the matrix with scaled rows (one rounding more per element,
+    // far inside the fp32 tolerance); bf16 would lose too much in a rounded copy and keeps a factor per edge.
+    if (filter || (scaled && !f32)) {
         p.end_bytes = (size_t)n_active * n_blocks * sizeof(int32_t);
         p.ids_bytes = (size_t)g->nnz * sizeof(int32_t);
     }
-    if (scaled) p.w_bytes = (size_t)g->nnz * sizeof(float);
+    if (scaled && f32) p.xs_bytes = (size_t)g->n_cols * (size_t)row_bytes;
+    if (scaled && !f32) p.w_bytes = (size_t)g->nnz * sizeof(float);
     if (filter) p.bounds_bytes = ((size_t)n_blocks + 1) * sizeof(int32_t);
     p.n_cols = g->n_cols;
     return p;
@@ -1010,10 +1034,12 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
     WsCarver carve(ws);
     int32_t* seg = carve.take<int32_t>(p.seg_bytes / sizeof(int32_t));
     float* part = carve.take<float>(p.part_bytes / sizeof(float));
-    const bool prepare = FILTER || a.nbr_scale != nullptr;
+    const bool prescale = a.nbr_scale != nullptr && DT == GNN_F32, per_edge = a.nbr_scale != nullptr && DT != GNN_F32;
+    const bool prepare = FILTER || per_edge;
     int32_t* seg_end = prepare ? carve.take<int32_t>(p.end_bytes / sizeof(int32_t)) : nullptr;
     int32_t* ids = prepare ? carve.take<int32_t>(p.ids_bytes / sizeof(int32_t)) : nullptr;
-    float* edge_w = a.nbr_scale ? carve.take<float>(p.w_bytes / sizeof(float)) : nullptr;
+    char* xs = prescale ? carve.take<char>(p.xs_bytes) : nullptr;
+    float* edge_w = per_edge ? carve.take<float>(p.w_bytes / sizeof(float)) : nullptr;
     int32_t* bounds = FILTER ? carve.take<int32_t>((size_t)p.n_blocks + 1) : nullptr;
     if (FILTER) {
         spmm_bounds_kernel<<<1, 1024, 0, stream>>>(a.dist, a.max_dist, p.n_cols, p.n_blocks, bounds);
@@ -1023,10 +1049,19 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
         a.row_ptr, a.col_idx, a.rows, a.n_active, p.n_blocks, p.block_size, bounds, seg);
     GNN_LAUNCH_CHECK("spmm_seg_kernel");
     SpmmArgs b = a;
+    if (prescale) {
+        // the neighbour scale is applied once per row of the gathered matrix, not once per edge and slab
+        spmm_scale_rows_kernel<DT><<<grid_for((int64_t)p.n_cols * ((a.F + VE - 1) / VE), 256, 1 << 16), 256, 0, stream>>>(
+            a.X, a.ldx, p.n_cols, a.F, a.nbr_scale, xs);
+        GNN_LAUNCH_CHECK("spmm_scale_rows_kernel");
+        b.X = xs;
+        b.nbr_scale = nullptr;
+    }
     if (prepare) {
         const int64_t n_segments = (int64_t)a.n_active * p.n_blocks;
         spmm_prepare_kernel<<<grid_for(n_segments * 16, 256, 1 << 18), 256, 0, stream>>>(
-            a.col_idx, seg, FILTER ? a.dist : nullptr, a.max_dist, a.nbr_scale, n_segments, p.n_blocks, ids, edge_w, seg_end);
+            a.col_idx, seg, FILTER ? a.dist : nullptr, a.max_dist, per_edge ? a.nbr_scale : nullptr, n_segments, p.n_blocks, ids, edge_w,
+            seg_end);
         GNN_LAUNCH_CHECK("spmm_prepare_kernel");
         b.col_idx = ids;
         b.seg_end = seg_end;
@@ -1079,7 +1114,8 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     const bool filter = dist != nullptr || g->edge_keep != nullptr;
     BlockedPlan plan;
     if (ws_bytes != nullptr) {
-        if (n_active > 0 && F > 0) plan = plan_blocked(g, n_active, F, ldx * (dtype == GNN_F32 ? 4 : 2), vec_ok, filter, nbr_scale != nullptr);
+        if (n_active > 0 && F > 0) plan = plan_blocked(g, n_active, F, ldx * (dtype == GNN_F32 ? 4 : 2), vec_ok, filter, nbr_scale != nullptr,
+                                                            dtype == GNN_F32);
         WsCarver measure(nullptr);
         if (plan.passes > 0) {
             measure.take<char>(plan.seg_bytes);
@@ -1088,6 +1124,7 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
                 measure.take<char>(plan.end_bytes);
                 measure.take<char>(plan.ids_bytes);
             }
+            if (plan.xs_bytes) measure.take<char>(plan.xs_bytes);
             if (plan.w_bytes) measure.take<char>(plan.w_bytes);
             if (plan.bounds_bytes) measure.take<char>(plan.bounds_bytes);
         }
