@@ -92,9 +92,11 @@ def main():
     ap.add_argument("--workload", default="cfg1", choices=sorted(CONFIG_INDEX))
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the vertex count (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extract-on-gpu", action="store_true",
-                    help="build the partition on the GPU from the unpartitioned graph (active sets, extraction with "
-                         "(distance, id) numbering, feature gather) instead of on the host; full-halo workloads only")
+    ap.add_argument("--host-partition", action="store_true",
+                    help="run the step on the host-built partition (ascending-id numbering, every call gets a row list) "
+                         "instead of the one built on the GPU from the unpartitioned graph (active sets, extraction with "
+                         "(distance, id) numbering, feature gather: every R_l is an id prefix); full-halo workloads only")
+    ap.add_argument("--extract-on-gpu", action="store_true", help="the default; kept for old command lines")
     ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
                     help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
                          "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
@@ -105,6 +107,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
+    args.extract_on_gpu = not args.host_partition
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding or collectives are part of it); "
               "run with --gpus 1", file=sys.stderr)

@@ -95,9 +95,11 @@ def _spmm_fwd_sampled(w, G, rows_all, F, dtype, kind, seed, n_sample=1500):
     return X, Xd, Yd, (rs, cs, rs_d, cs_d)
 
 
-def _spmm_bwd_sampled(w, G, dist, rows_out, max_dist, F, dtype, scales, seed, n_sample=1500):
+def _spmm_bwd_sampled(w, G, dist, rows_out, max_dist, F, dtype, scales, seed, n_sample=1500, whole=False):
     """Backward aggregation for every row of rows_out; the oracle recomputes a sample in gather form over
-    the (symmetric) graph with the activity filter folded into the per-neighbour scale."""
+    the (symmetric) graph with the activity filter folded into the per-neighbour scale.
+    whole: the form the model uses when every vertex was a forward row - no row list, no filter, and the call undoes
+    the ReLU of the layer in front (relu_H)."""
     import paper_2311_06837_amd as P
     part = w.partition
     n = part.graph.n_rows
@@ -107,21 +109,31 @@ def _spmm_bwd_sampled(w, G, dist, rows_out, max_dist, F, dtype, scales, seed, n_
     dY = as_stored(gg.features(n, F, seed + 100), dtype)
     dYd = padded(dY, ld, dtype)
     dXd = torch.zeros(n, ld, dtype=dtype, device="cuda")
-    P.gnn_masked_spmm_bwd(G, dev(rows_out), rows_out.size, dev(dist), max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False, ws=_ws())
+    Hact = None
+    if whole:
+        assert rows_out.size == n and np.array_equal(rows_out, np.arange(n)) and ((dist >= 0) & (dist <= max_dist)).all()
+        Hact = as_stored(np.maximum(gg.features(n, F, seed + 200), 0), dtype)
+        P.gnn_masked_spmm_bwd(G, None, n, None, max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False, ws=_ws(), relu_H=padded(Hact, ld, dtype))
+    else:
+        P.gnn_masked_spmm_bwd(G, dev(rows_out), rows_out.size, dev(dist), max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False, ws=_ws())
     torch.cuda.synchronize()
     sample = _sample_rows(part, rows_out, n_sample, seed + 1)
     active = ((dist >= 0) & (dist <= max_dist)).astype(np.float64)
     nbr = active * (rs if rs is not None else 1.0)           # per contributing row v: rs[v] * [v active]
     want = np.zeros((n, F))
     oracle.spmm_fwd(part.graph.row_ptr, part.graph.col_idx, sample, dY, want, F, cs, nbr)   # symmetric: gT = g
+    if whole:
+        want = want * (Hact > 0)
     got = host64(dXd[dev(sample).long()])[:, :F]
     check(got, want[sample], dtype, "sampled rows of the backward aggregation")
 
 
-def _linear_sampled(w, rows_all, K, N, dtype, sage, seed, n_sample=2000, n_cols=8):
+def _linear_sampled(w, rows_all, K, N, dtype, sage, seed, n_sample=2000, n_cols=8, in_place=False):
     """Forward + backward feature transform over ALL rows on the GPU.  The oracle recomputes sampled output
     rows (forward, dA, dX_self) and, for the weight gradients, n_cols whole columns of dW / dbias
-    (a column of dW depends on that column of dZ only)."""
+    (a column of dW depends on that column of dZ only).
+    in_place: the form the model uses on a (distance, id)-numbered partition - no row list (rows_all must be
+    0 .. m-1) and, in the backward call, no activation to undo (the gradient arrives masked)."""
     import paper_2311_06837_amd as P
     n = w.partition.graph.n_rows
     ld_in, ld_out = P.row_stride(K, dtype), P.row_stride(N, dtype)
@@ -136,6 +148,10 @@ def _linear_sampled(w, rows_all, K, N, dtype, sage, seed, n_sample=2000, n_cols=
     Wnd, Wsd = dev(Wn, dtype), (dev(Ws, dtype) if sage else None)
     Hd = torch.zeros(n, ld_out, dtype=dtype, device="cuda")
     rows_d = dev(rows_all)
+    relu_b = True
+    if in_place:
+        assert np.array_equal(rows_all, np.arange(rows_all.size))
+        rows_d, relu_b = None, False
     P.gnn_linear_fwd(rows_d, rows_all.size, Ad, Xd, K, Wnd, Wsd, dev(b), Hd, True)
     torch.cuda.synchronize()
     rng = np.random.default_rng(seed)
@@ -152,19 +168,19 @@ def _linear_sampled(w, rows_all, K, N, dtype, sage, seed, n_sample=2000, n_cols=
     db_d = torch.zeros(N, device="cuda")
     dA_d = torch.zeros(n, ld_in, dtype=dtype, device="cuda")
     dX_d = torch.zeros(n, ld_in, dtype=dtype, device="cuda") if sage else None
-    P.gnn_linear_bwd(rows_d, rows_all.size, padded(dH, ld_out, dtype), padded(Hs, ld_out, dtype), True, Ad, Xd, K, Wnd, Wsd,
-                     dWn_d, dWs_d, db_d, dA_d, dX_d)
+    P.gnn_linear_bwd(rows_d, rows_all.size, padded(dH, ld_out, dtype), padded(Hs, ld_out, dtype) if relu_b else None, relu_b, Ad, Xd, K,
+                     Wnd, Wsd, dWn_d, dWs_d, db_d, dA_d, dX_d)
     torch.cuda.synchronize()
     # (a) input gradients on sampled rows
     dA = np.zeros((n, K))
     dX = np.zeros((n, K)) if sage else None
-    oracle.linear_bwd(sample, dH, Hs, True, A, Xs, K, Wn, Ws, dA, dX)
+    oracle.linear_bwd(sample, dH, Hs if relu_b else None, relu_b, A, Xs, K, Wn, Ws, dA, dX)
     check(host64(dA_d[dev(sample).long()])[:, :K], dA[sample], dtype, "sampled rows of dA")
     if sage:
         check(host64(dX_d[dev(sample).long()])[:, :K], dX[sample], dtype, "sampled rows of dX_self")
     # (b) n_cols full columns of the weight and bias gradients, reduced over ALL rows by the oracle
     cols = np.sort(rng.choice(N, size=min(n_cols, N), replace=False))
-    dWn, dWs, db = oracle.linear_bwd(rows_all, np.ascontiguousarray(dH[:, cols]), np.ascontiguousarray(Hs[:, cols]), True, A, Xs, K,
+    dWn, dWs, db = oracle.linear_bwd(rows_all, np.ascontiguousarray(dH[:, cols]), np.ascontiguousarray(Hs[:, cols]) if relu_b else None, relu_b, A, Xs, K,
                                      np.ascontiguousarray(Wn[:, cols]), np.ascontiguousarray(Ws[:, cols]) if sage else None)
     check(host64(dWn_d)[:, cols], dWn, dtype, "columns of dW_neigh")
     check(host64(db_d)[cols], db, dtype, "entries of dbias")
@@ -184,6 +200,13 @@ def test_cfg1_full_size(cfg1):
     _spmm_bwd_sampled(w, G, dist, R2, L - 3, 256, torch.float32, sc, 14, n_sample=600)      # backward of layer 3
     _linear_sampled(w, R1, 602, 256, torch.float32, True, 15, n_sample=1500, n_cols=4)
     _linear_sampled(w, R3, 256, 41, torch.float32, True, 16, n_sample=1500, n_cols=8)
+    # the forms the model uses where every vertex is a row (layers 1 and 2 here): no row list, no filter, the ReLU in
+    # front undone by the aggregation, the gradient read in place by the feature transform
+    n = w.partition.graph.n_rows
+    assert R1.size == n
+    allrows = np.arange(n, dtype=np.int32)
+    _spmm_bwd_sampled(w, G, dist, allrows, L - 2, 256, torch.float32, sc, 17, n_sample=600, whole=True)
+    _linear_sampled(w, allrows, 256, 256, torch.float32, True, 18, n_sample=1500, n_cols=4, in_place=True)
 
 
 def test_cfg1_sum_of_ones_is_degree_at_full_size(cfg1):
@@ -211,6 +234,11 @@ def test_cfg3_full_size_bf16(cfg3):
     _spmm_bwd_sampled(w, G, dist, R1, L - 2, 128, torch.bfloat16, sc, 24)                   # backward of layer 2
     _linear_sampled(w, R1, 128, 128, torch.bfloat16, True, 25)
     _linear_sampled(w, R8, 128, 16, torch.bfloat16, True, 26)
+    n = w.partition.graph.n_rows
+    assert R1.size == n
+    allrows = np.arange(n, dtype=np.int32)
+    _spmm_bwd_sampled(w, G, dist, allrows, L - 2, 128, torch.bfloat16, sc, 27, whole=True)
+    _linear_sampled(w, allrows, 128, 128, torch.bfloat16, True, 28, in_place=True)
 
 
 def test_cfg4_sampling_and_active_sets_full_size():
