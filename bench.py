@@ -97,6 +97,9 @@ def main():
                          "instead of the one built on the GPU from the unpartitioned graph (active sets, extraction with "
                          "(distance, id) numbering, feature gather: every R_l is an id prefix); full-halo workloads only")
     ap.add_argument("--extract-on-gpu", action="store_true", help="the default; kept for old command lines")
+    ap.add_argument("--aggregate-first", action="store_true",
+                    help="keep the paper's order (aggregate, then weights) in a first layer that narrows its input; by default "
+                         "such a layer multiplies by the weights first and gathers the narrower rows")
     ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
                     help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
                          "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
@@ -170,7 +173,8 @@ def main():
         gdeg = None
         if w.model == "gcn":
             gdeg = dev(w.global_graph.degrees().astype(np.int32))[l2g.long()]
-        model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg, prefix_numbered=True)
+        model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg, prefix_numbered=True,
+                            transform_first=False if args.aggregate_first else "auto")
         # the host partition numbers its vertices by ascending id; its feature rows are permuted into ring order
         pos = torch.from_numpy(np.searchsorted(part.local_to_global, l2g.cpu().numpy().astype(np.int64)).astype(np.int32)).cuda()
         H0d = torch.zeros(n, ld0, dtype=dtype, device="cuda")
@@ -181,7 +185,8 @@ def main():
         GT = G if part.graph_t is part.graph else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
         model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=dtype,
                             global_degree=dev(part.global_degree) if w.model == "gcn" else None,
-                            prefix_numbered=sampled_graph is not None)   # the GPU extraction numbers by (distance, id)
+                            prefix_numbered=sampled_graph is not None,   # the GPU extraction numbers by (distance, id)
+                            transform_first=False if args.aggregate_first else "auto")
         model.set_input(dev(H0).to(dtype))
     if args.layer_sampling:
         f = args.layer_sampling.split(":")
@@ -216,33 +221,38 @@ def main():
     L = model.L
     es = 4 if dtype == torch.float32 else 2
 
+    # a first layer in the exchanged order splits its feature transform into two calls each way
+    lin_f = lambda l: call_ms.get(f"linear_fwd_{l}", 0.0) + call_ms.get(f"linear_pre_{l}", 0.0)
+    lin_b = lambda l: call_ms.get(f"linear_bwd_{l}", 0.0) + call_ms.get(f"linear_bwd_{l}_neigh", 0.0)
+
     # per-layer report
     layers = {}
     for l in range(1, L + 1):
         t_f = call_ms.get(f"spmm_fwd_{l}", 0.0)
         t_b = call_ms.get(f"spmm_bwd_{l}", 0.0) + call_ms.get(f"spmm_bwd_{l}_ring", 0.0)
         e = edges[l]
-        F = w.dims[l - 1]
+        F = model.agg_width(l)
         nl = model.n_rows_of_layer(l)
         gather_bytes = e["fwd"] * (4 + F * es) + nl * (8 + F * es)
         layers[str(l)] = {
             "rows": nl, "edges_fwd": e["fwd"], "edges_bwd": e["bwd"], "F": F,
             "spmm_fwd_ms": round(t_f, 4), "spmm_bwd_ms": round(t_b, 4),
-            "linear_fwd_ms": round(call_ms.get(f"linear_fwd_{l}", 0.0), 4),
-            "linear_bwd_ms": round(call_ms.get(f"linear_bwd_{l}", 0.0), 4),
+            "linear_fwd_ms": round(lin_f(l), 4), "linear_bwd_ms": round(lin_b(l), 4),
             "edges_per_s_spmm": (e["fwd"] + e["bwd"]) / ((t_f + t_b) * 1e-3) if t_f + t_b > 0 else None,
             "spmm_fwd_gather_GBs": gather_bytes / (t_f * 1e-3) / 1e9 if t_f > 0 else None,
         }
 
-    # roofline of the dominant kernel: the forward aggregation with the largest time
-    dom = max(range(1, L + 1), key=lambda l: call_ms.get(f"spmm_fwd_{l}", 0.0))
-    Fd = w.dims[dom - 1]
+    # roofline of the dominant kernel: the forward aggregation that gathers the most bytes (the later layer on a tie:
+    # the plain call rather than the first layer's add-on-top form)
+    dom = max(range(1, L + 1), key=lambda l: (edges[l]["fwd"] * model.agg_width(l), l))
+    Fd = model.agg_width(dom)
     nd = model.n_rows_of_layer(dom)
     n_in = model.n_rows_of_layer(dom - 1) if dom > 1 else int(hop[L + 1])
     alg_bytes = edges[dom]["fwd"] * (4 + Fd * es) + nd * (8 + Fd * es)           # gather model
     compulsory = edges[dom]["fwd"] * 4 + n_in * Fd * es + nd * (8 + Fd * es)     # every input row read once
     t_dom = call_ms[f"spmm_fwd_{dom}"] * 1e-3
-    blocked = P.binding.spmm_workspace_bytes(G, nd, model.H[dom - 1], model.A[dom], Fd) > 0
+    src_dom, dst_dom = (model.P, model.H[1]) if (dom == 1 and model.transform_first) else (model.H[dom - 1], model.A[dom])
+    blocked = P.binding.spmm_workspace_bytes(G, nd, src_dom, dst_dom, Fd) > 0
     kernels = ("spmm_stream_kernel (+ spmm_seg_kernel before and spmm_sum_parts_kernel after it: column-blocked route)"
                if blocked else "spmm_rows_kernel")
     kib = MEASURED_TRAFFIC_KIB.get(args.workload) if args.scale == 1.0 else None
@@ -270,7 +280,7 @@ def main():
         srcs = 2 if sage else 1
         f_fwd = 2.0 * nl * K * N * srcs
         f_bwd = f_fwd * (2 if l > 1 else 1)
-        tf, tb = call_ms.get(f"linear_fwd_{l}", 0.0) * 1e-3, call_ms.get(f"linear_bwd_{l}", 0.0) * 1e-3
+        tf, tb = lin_f(l) * 1e-3, lin_b(l) * 1e-3
         peak = MFMA_PEAK_TFLOPS[w.dtype]
         b_fwd = nl * (K * srcs + N) * es
         # backward, every operand once: the (already masked) output gradient and the layer inputs in, the input gradients out
@@ -317,6 +327,7 @@ def main():
         "partition_built_on": "gpu ((distance, id) numbering)" if (gpu_part is not None or sampled_graph is not None)
                               else "host (ascending-id numbering)",
         "aggregated_edges_per_step": total_edges,
+        "first_layer_order": "weights, then aggregation" if model.transform_first else "aggregation, then weights",
         "layer_sampling": args.layer_sampling,
         "layer_mask_ms": sum(v for k, v in call_ms.items() if k.startswith("layer_mask")) if args.layer_sampling else None,
         "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,

@@ -130,6 +130,20 @@ int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_act
                             void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * Masked aggregation added onto the output (section 2.1's layer equation with the neighbour sum and the weight
+ * product exchanged: sum_u (x_u W) instead of (sum_u x_u) W, the cheaper order when the layer narrows its input):
+ *     Y[v, 0:F] = act( Y[v, 0:F] + row_scale[v] * sum_{u in row(v)} col_scale[u] * X[u, 0:F] )     for v in rows
+ *   X     the already transformed rows (x_u W_neigh), Y on entry the self term (x_v W_self + bias) of the same rows
+ *   relu  1: act = max(., 0), 0: identity
+ * Everything else (row list, scales, determinism, workspace, errors) as in gnn_masked_spmm_fwd; a row without
+ * entries still gets its activation.
+ */
+int32_t gnn_masked_spmm_fwd_add(const gnn_csr *g, const int32_t *rows, int32_t n_active,
+                                const void *X, int64_t ldx, void *Y, int64_t ldy, int32_t F, int32_t dtype,
+                                const float *row_scale, const float *col_scale, int32_t relu,
+                                void *ws, size_t *ws_bytes, void *stream);
+
+/*
  * Masked aggregation, backward = the adjoint of the forward map, in gather form over the
  * TRANSPOSED graph gT (row u of gT lists every v that aggregates u; for a symmetric graph pass
  * the same arrays):

@@ -21,7 +21,7 @@ GNN_CSR_SORTED_COLUMNS = 1
 STATUS = {0: "GNN_OK", 1: "GNN_ERR_INVALID_ARG", 2: "GNN_ERR_SHAPE", 3: "GNN_ERR_WORKSPACE",
           4: "GNN_ERR_UNSUPPORTED", 5: "GNN_ERR_HIP"}
 
-EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_scales", "gnn_masked_spmm_fwd",
+EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_scales", "gnn_masked_spmm_fwd", "gnn_masked_spmm_fwd_add",
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
            "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
@@ -252,6 +252,18 @@ def gnn_masked_spmm_fwd(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch
     _with_optional_ws(lib().gnn_masked_spmm_fwd, (
         C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
         C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale)), (_stream(),), ws)
+
+
+def gnn_masked_spmm_fwd_add(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int,
+                            row_scale=None, col_scale=None, relu: bool = False, ws: Workspace | None = None):
+    """Y[rows] = act(Y[rows] + aggregation of X): the transform-before-aggregate order of a layer."""
+    _mat(X, "X"), _mat(Y, "Y")
+    assert X.dtype == Y.dtype and X.shape[0] >= g.n_cols and Y.shape[0] >= g.n_rows
+    assert rows is None or rows.numel() >= n_active
+    _with_optional_ws(lib().gnn_masked_spmm_fwd_add, (
+        C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
+        C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale),
+        C.c_int32(1 if relu else 0)), (_stream(),), ws)
 
 
 def spmm_workspace_bytes(g: Graph, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int) -> int:

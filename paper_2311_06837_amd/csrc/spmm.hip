@@ -97,7 +97,8 @@ struct Elem<GNN_F32, 4> {
         acc[2] = fmaf(w, __uint_as_float(r.z), acc[2]);
         acc[3] = fmaf(w, __uint_as_float(r.w), acc[3]);
     }
-    // h (nullable): activation matrix of the same layout position hoff; what is stored is zeroed where h <= 0
+    // h (nullable): activation matrix of the same layout position hoff; what is stored is zeroed where h <= 0.
+    // h == p stands for "the value being stored itself": the store applies a ReLU.
     static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[4], int n_valid, bool accumulate,
                                                  const void* h = nullptr, int64_t hoff = 0) {
         float* q = (float*)p + off;
@@ -109,14 +110,14 @@ struct Elem<GNN_F32, 4> {
                 o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
             }
             if (h) {
-                const float4 m = *(const float4*)hq;
+                const float4 m = h == p ? o : *(const float4*)hq;
                 o.x = m.x > 0.f ? o.x : 0.f; o.y = m.y > 0.f ? o.y : 0.f; o.z = m.z > 0.f ? o.z : 0.f; o.w = m.w > 0.f ? o.w : 0.f;
             }
             *(float4*)q = o;
         } else {
             for (int e = 0; e < n_valid; ++e) {
                 const float t = accumulate ? q[e] + v[e] : v[e];
-                q[e] = (h == nullptr || hq[e] > 0.f) ? t : 0.f;
+                q[e] = (h == nullptr || (h == p ? t : hq[e]) > 0.f) ? t : 0.f;
             }
         }
     }
@@ -134,7 +135,7 @@ struct Elem<GNN_F32, 1> {
         float* q = (float*)p + off;
         if (n_valid >= 1) {
             const float t = accumulate ? q[0] + v[0] : v[0];
-            q[0] = (h == nullptr || ((const float*)h)[hoff] > 0.f) ? t : 0.f;
+            q[0] = (h == nullptr || (h == p ? t : ((const float*)h)[hoff]) > 0.f) ? t : 0.f;
         }
     }
 };
@@ -163,7 +164,10 @@ struct Elem<GNN_BF16, 8> {
                 t[0] += bf16lo(old.x); t[1] += bf16hi(old.x); t[2] += bf16lo(old.y); t[3] += bf16hi(old.y);
                 t[4] += bf16lo(old.z); t[5] += bf16hi(old.z); t[6] += bf16lo(old.w); t[7] += bf16hi(old.w);
             }
-            if (h) {
+            if (h == p) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t[e] = t[e] > 0.f ? t[e] : 0.f;
+            } else if (h) {
                 const uint4 m = *(const uint4*)hq;
                 t[0] = bf16lo(m.x) > 0.f ? t[0] : 0.f; t[1] = bf16hi(m.x) > 0.f ? t[1] : 0.f;
                 t[2] = bf16lo(m.y) > 0.f ? t[2] : 0.f; t[3] = bf16hi(m.y) > 0.f ? t[3] : 0.f;
@@ -177,7 +181,7 @@ struct Elem<GNN_BF16, 8> {
         } else {
             for (int e = 0; e < n_valid; ++e) {
                 const float t = accumulate ? bf16_to_f32(q[e]) + v[e] : v[e];
-                q[e] = f32_to_bf16((h == nullptr || bf16_to_f32(hq[e]) > 0.f) ? t : 0.f);
+                q[e] = f32_to_bf16((h == nullptr || (h == p ? t : bf16_to_f32(hq[e])) > 0.f) ? t : 0.f);
             }
         }
     }
@@ -195,7 +199,7 @@ struct Elem<GNN_BF16, 1> {
         uint16_t* q = (uint16_t*)p + off;
         if (n_valid >= 1) {
             const float t = accumulate ? bf16_to_f32(q[0]) + v[0] : v[0];
-            q[0] = f32_to_bf16((h == nullptr || bf16_to_f32(((const uint16_t*)h)[hoff]) > 0.f) ? t : 0.f);
+            q[0] = f32_to_bf16((h == nullptr || (h == p ? t : bf16_to_f32(((const uint16_t*)h)[hoff])) > 0.f) ? t : 0.f);
         }
     }
 };
@@ -926,37 +930,33 @@ __global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __rest
         float o[4] = {t.x * sc, t.y * sc, t.z * sc, t.w * sc};
         const int n_valid = F - c >= 4 ? 4 : F - c;
         const int64_t off = (int64_t)v * ldy + c;
-        // the stored value is zeroed where relu_h (same rows and columns as Y) is <= 0
+        // the stored value is zeroed where relu_h (same rows and columns as Y) is <= 0; relu_h == Y: where it is <= 0 itself
+        const bool self = relu_h == (const void*)Y;
         bool pass[4] = {true, true, true, true};
-        if (relu_h) {
+        if (relu_h && !self) {
             for (int k = 0; k < n_valid; ++k) pass[k] = Elem<DT, 1>::to_float(Elem<DT, 1>::load(relu_h, (int64_t)v * ldh + c + k)) > 0.f;
         }
+        if (accumulate) {
+            if (DT == GNN_F32) {
+                const float* y = (const float*)Y + off;
+                for (int k = 0; k < n_valid; ++k) o[k] += y[k];
+            } else {
+                const uint16_t* y = (const uint16_t*)Y + off;
+                for (int k = 0; k < n_valid; ++k) o[k] += bf16_to_f32(y[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (self ? o[k] > 0.f : pass[k]) ? o[k] : 0.f;
         if (DT == GNN_F32) {
             float* y = (float*)Y + off;
-            if (n_valid == 4) {
-                float4 w = make_float4(o[0], o[1], o[2], o[3]);
-                if (accumulate) {
-                    const float4 old = *(const float4*)y;
-                    w.x += old.x; w.y += old.y; w.z += old.z; w.w += old.w;
-                }
-                w.x = pass[0] ? w.x : 0.f; w.y = pass[1] ? w.y : 0.f; w.z = pass[2] ? w.z : 0.f; w.w = pass[3] ? w.w : 0.f;
-                *(float4*)y = w;
-            } else {
-                for (int k = 0; k < n_valid; ++k) y[k] = pass[k] ? (accumulate ? y[k] + o[k] : o[k]) : 0.f;
-            }
+            if (n_valid == 4) *(float4*)y = make_float4(o[0], o[1], o[2], o[3]);
+            else
+                for (int k = 0; k < n_valid; ++k) y[k] = o[k];
         } else {
             uint16_t* y = (uint16_t*)Y + off;
-            if (n_valid == 4) {
-                if (accumulate) {
-                    const uint2 old = *(const uint2*)y;
-                    o[0] += bf16lo(old.x); o[1] += bf16hi(old.x); o[2] += bf16lo(old.y); o[3] += bf16hi(old.y);
-                }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) o[k] = pass[k] ? o[k] : 0.f;
-                *(uint2*)y = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
-            } else {
-                for (int k = 0; k < n_valid; ++k) y[k] = f32_to_bf16(pass[k] ? (accumulate ? bf16_to_f32(y[k]) + o[k] : o[k]) : 0.f);
-            }
+            if (n_valid == 4) *(uint2*)y = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
+            else
+                for (int k = 0; k < n_valid; ++k) y[k] = f32_to_bf16(o[k]);
         }
     }
 }
@@ -1161,6 +1161,15 @@ extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, in
                                        void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
                                        const float* col_scale, void* ws, size_t* ws_bytes, void* stream) {
     return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, nullptr, 0, ws,
+                       ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int32_t gnn_masked_spmm_fwd_add(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
+                                           void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
+                                           const float* col_scale, int32_t relu, void* ws, size_t* ws_bytes, void* stream) {
+    GNN_REQUIRE(relu == 0 || relu == 1, GNN_ERR_INVALID_ARG, "relu must be 0 or 1");
+    // the output matrix as its own mask stands for a ReLU of what is stored
+    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 1, relu ? Y : nullptr, ldy, ws,
                        ws_bytes, (hipStream_t)stream);
 }
 

@@ -34,12 +34,20 @@ class MaskedGNN:
                      through gnn_layer_edge_mask(rule, layer = l) over its rows, forward and backward; rule
                      "threshold" (parameter = 64-bit key threshold) or "fanout" (parameter = neighbours kept per row).
                      The masks are rebuilt in every step (a training run changes the seed per epoch).
+    transform_first  the order of the first layer's two halves.  False: aggregate the input features, then multiply by
+                     the weights (the paper's order).  True: multiply first, P = H_0 W_neigh, then aggregate P on top
+                     of the self term (gnn_masked_spmm_fwd_add) - the same sum, gathered dims[1] instead of dims[0]
+                     columns wide; the backward pass then needs one aggregation of the layer's output gradient
+                     (dP, dims[1] wide) for dW_neigh = H_0^T dP.  "auto" (default): True for a GraphSAGE model
+                     whose first layer narrows its input (dims[0] > dims[1]).  Only the first layer: it needs no
+                     input gradient.
     """
 
     def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, kind: str, params: list,
                  dtype=torch.float32, global_degree: torch.Tensor | None = None, prefix_numbered: bool = False,
-                 layer_sampling=None):
+                 layer_sampling=None, transform_first="auto"):
         assert kind in ("gcn", "sage")
+        assert transform_first in (True, False, "auto")
         self.layer_sampling = layer_sampling
         self.prefix_numbered, self._prefix_checked = prefix_numbered, False
         self.g, self.gt, self.targets, self.kind, self.dtype = graph, graph_t, targets, kind, dtype
@@ -56,8 +64,18 @@ class MaskedGNN:
         self.global_degree = global_degree
         self.ld = [row_stride(d, dtype) for d in self.dims]
         dev = targets.device
+        if transform_first == "auto":
+            transform_first = kind == "sage" and self.dims[0] > self.dims[1]
+        assert not transform_first or kind == "sage", "the exchanged order is built for the GraphSAGE layer only"
+        self.transform_first = bool(transform_first)
         # activations A_l, H_l and their gradients; rows outside the active sets are never touched
         self.A = [None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
+        if self.transform_first:
+            # no aggregate of the input features; instead the transformed rows P and the gradient that reaches them
+            self.A[1] = None
+            self.P = torch.zeros(self.n, self.ld[1], dtype=dtype, device=dev)
+            self.dP = torch.zeros(self.n, self.ld[1], dtype=dtype, device=dev)
+            self._dbias_unused = torch.zeros(self.dims[1], dtype=torch.float32, device=dev)
         self.H = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
         self.dH = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
         self.dA = [None, None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(2, self.L + 1)]
@@ -108,14 +126,15 @@ class MaskedGNN:
         self.g_l, self.gt_l, self.rs_l, self.kept_l = [None], [None], [None], [None]
         for l in range(1, self.L + 1):
             nl = self.n_rows_of_layer(l)
-            # layer 1 has no backward aggregation: its threshold pairs are not needed
+            # layer 1 has no backward aggregation in the paper's order: its threshold pairs are not needed then
+            need_t = l > 1 or self.transform_first
             out = self._call(f"layer_mask_{l}", B.gnn_layer_edge_mask, self.g, self.rows, nl, rule, l, seed,
                              fanout=par if rule == "fanout" else 0, threshold=par if rule == "threshold" else (1 << 64) - 1,
-                             with_thresholds=l > 1)
+                             with_thresholds=need_t)
             keep, kept_len = out[0], out[1]
             self.g_l.append(self.g.with_edge_keep(keep))
             self.kept_l.append(kept_len)
-            if l > 1:
+            if need_t:
                 keep_t = self._call(f"layer_mask_t_{l}", B.gnn_layer_edge_mask_transposed, self.gt, out[2], out[3], l, seed)
                 self.gt_l.append(self.gt.with_edge_keep(keep_t))
             else:
@@ -125,6 +144,10 @@ class MaskedGNN:
     def n_rows_of_layer(self, l: int) -> int:
         """|R_l|, R_l = {dist <= L - l}: a prefix of the ring-sorted ids."""
         return int(self.hop[self.L - l + 1])
+
+    def agg_width(self, l: int) -> int:
+        """Columns of the matrix that layer l's forward aggregation gathers."""
+        return self.dims[1] if (l == 1 and self.transform_first) else self.dims[l - 1]
 
     def set_input(self, H0: torch.Tensor):
         """H0: [n, row_stride(F0, dtype)] of the model dtype, row-major; used in place."""
@@ -138,6 +161,15 @@ class MaskedGNN:
             K = self.dims[l - 1]
             nl = self.n_rows_of_layer(l)
             g_l, rs_l = (self.g, self.rs) if self.layer_sampling is None else (self.g_l[l], self.rs_l[l])
+            if l == 1 and self.transform_first:
+                n0 = int(self.hop[self.L + 1])      # every vertex within L hops can be a neighbour of a row of R_1
+                self._call("linear_pre_1", B.gnn_linear_fwd, self.rows, n0, self.H[0], None, K, p["W_neigh"], None, None, self.P,
+                           relu=False, ws=self.ws)
+                self._call("linear_fwd_1", B.gnn_linear_fwd, self.rows, nl, self.H[0], None, K, p["W_self"], None, p["bias"], self.H[1],
+                           relu=False, ws=self.ws)
+                self._call("spmm_fwd_1", B.gnn_masked_spmm_fwd_add, g_l, self.rows, nl, self.P, self.H[1], self.dims[1], rs_l, self.cs,
+                           relu=(l < self.L), ws=self.ws)
+                continue
             self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, g_l, self.rows, nl, self.H[l - 1], self.A[l], K, rs_l, self.cs, ws=self.ws)
             self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
                              p["W_neigh"], p.get("W_self"), p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
@@ -154,6 +186,9 @@ class MaskedGNN:
             nl = self.n_rows_of_layer(l)
             sage = self.kind == "sage"
             need_in = l > 1
+            if l == 1 and self.transform_first:
+                self._backward_transform_first()
+                continue
             # dH_l arrives with the ReLU of layer l already undone: the aggregation call that wrote it last masked it
             self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
                              self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
@@ -181,6 +216,20 @@ class MaskedGNN:
                                           rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h)
         return self.grads
 
+    def _backward_transform_first(self):
+        """First layer in the exchanged order, Z = rs * Agg(H_0 W_neigh) + H_0 W_self + b: the self half takes dZ as it
+        is, the neighbour half takes dP = Agg^T(rs * dZ) (one backward aggregation, dims[1] wide)."""
+        L, p, gr, K = self.L, self.params[0], self.grads[0], self.dims[0]
+        n1, n0 = self.n_rows_of_layer(1), int(self.hop[L + 1])
+        gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[1], self.rs_l[1])
+        dist_l = None if n1 == self.n else self.dist
+        self._call("spmm_bwd_1", B.gnn_masked_spmm_bwd, gt_l, self.rows, n0, dist_l, L - 1, self.dH[1], self.dP, self.dims[1],
+                   rs_l, self.cs, accumulate=False, ws=self.ws if 4 * n1 >= self.n else None)
+        self._call("linear_bwd_1", B.gnn_linear_bwd, self.rows, n1, self.dH[1], None, False, self.H[0], None, K, p["W_self"], None,
+                   gr["dW_self"], None, gr["dbias"], None, None, ws=self.ws)
+        self._call("linear_bwd_1_neigh", B.gnn_linear_bwd, self.rows, n0, self.dP, None, False, self.H[0], None, K, p["W_neigh"], None,
+                   gr["dW_neigh"], None, self._dbias_unused, None, None, ws=self.ws)
+
     def step(self, labels: torch.Tensor):
         """One pass of the whole hot path: active sets, forward, loss, backward."""
         self.build_active_sets()
@@ -191,8 +240,9 @@ class MaskedGNN:
         return self.loss
 
     def aggregated_edges(self) -> dict:
-        """Edges visited per layer by the forward and the backward aggregation (host-side bookkeeping
-        from row_ptr; used by the benchmark's edges/s metric)."""
+        """Edges visited per layer by the forward and the backward aggregation of the paper's order (host-side
+        bookkeeping from row_ptr; used by the benchmark's edges/s metric).  The first layer's extra backward aggregation
+        under transform_first is NOT counted: the exchanged order must not raise the metric by doing more, narrower sums."""
         rp = self.g.row_ptr.long()
         ring = self.ring_ids.long()
         out = {}
@@ -274,6 +324,10 @@ class ResSAGEPlus:
 
     def n_rows_of_layer(self, l: int) -> int:
         return int(self.hop[self.L - l + 1])
+
+    def agg_width(self, l: int) -> int:
+        """Columns of the matrix that layer l's forward aggregation gathers."""
+        return self.dims[1] if (l == 1 and self.transform_first) else self.dims[l - 1]
 
     def set_input(self, H0: torch.Tensor):
         assert H0.dtype == self.dtype and H0.shape[0] == self.n and H0.stride(0) == self.ld[0]

@@ -133,15 +133,19 @@ def test_aggregation_through_a_mask_forward_and_backward(dtype, F, ld):
     assert (got[rest] == sent).all() and (got[:, F:] == sent).all()
 
 
-@pytest.mark.parametrize("kind,dtype,ls", [("sage", torch.float32, ("fanout", 4, 11)),
-                                           ("gcn", torch.float32, ("threshold", oracle.keep_threshold(0.5), 12)),
-                                           ("sage", torch.bfloat16, ("threshold", oracle.keep_threshold(0.7), 13)),
-                                           ("sage", torch.float32, ("threshold", M64, 14))])
-def test_training_step_with_per_layer_masks(kind, dtype, ls):
+@pytest.mark.parametrize("kind,dtype,ls,dims", [
+    ("sage", torch.float32, ("fanout", 4, 11), [32, 64, 48, 8]),
+    ("gcn", torch.float32, ("threshold", oracle.keep_threshold(0.5), 12), [32, 64, 48, 8]),
+    ("sage", torch.bfloat16, ("threshold", oracle.keep_threshold(0.7), 13), [32, 64, 48, 8]),
+    ("sage", torch.float32, ("threshold", M64, 14), [32, 64, 48, 8]),
+    # a first layer that narrows its input: the model multiplies by the weights first and aggregates the layer-1 mask
+    # backward as well (its transposed mask is built too)
+    ("sage", torch.float32, ("fanout", 4, 15), [64, 32, 48, 8]),
+    ("sage", torch.float32, ("threshold", oracle.keep_threshold(0.5), 16), [64, 32, 48, 8])])
+def test_training_step_with_per_layer_masks(kind, dtype, ls, dims):
     import paper_2311_06837_amd as P
     w = gg.make_workload("cfg0", scale=0.5)
     part = w.partition
-    dims = [32, 64, 48, 8]
     print(f"model with layer sampling {ls[0]}: n={part.graph.n_rows} nnz={part.graph.nnz} {kind} {dtype}", flush=True)
     L = len(dims) - 1
     g = part.graph if kind == "sage" else part.graph
@@ -158,6 +162,7 @@ def test_training_step_with_per_layer_masks(kind, dtype, ls):
     G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
     m = P.MaskedGNN(G, G, dev(T), kind, [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
                     global_degree=dev(gdeg) if gdeg is not None else None, layer_sampling=ls)
+    assert m.transform_first == (kind == "sage" and dims[0] > dims[1])
     m.set_input(padded(H0, P.row_stride(dims[0], dtype), dtype))
     loss = m.step(dev(y))
     torch.cuda.synchronize()

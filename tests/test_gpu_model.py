@@ -11,19 +11,21 @@ from gpu_util import TOL, as_stored, check, dev, host64, padded
 pytestmark = pytest.mark.gpu
 
 
-def _gpu_model(part, kind, params, dtype):
+def _gpu_model(part, kind, params, dtype, transform_first="auto"):
     import paper_2311_06837_amd as P
     G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
     same = part.graph_t is part.graph
     GT = G if same else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
     dparams = [{k: dev(v) for k, v in p.items()} for p in params]
     return P.MaskedGNN(G, GT, dev(part.targets), kind, dparams, dtype=dtype,
-                       global_degree=dev(part.global_degree) if kind == "gcn" else None)
+                       global_degree=dev(part.global_degree) if kind == "gcn" else None, transform_first=transform_first)
 
 
-def _parity(name, part, kind, dims, dtype, seed):
-    print(f"model {name}: n={part.graph.n_rows} nnz={part.graph.nnz} |T|={len(part.targets)} {kind} dims={dims} {dtype}",
-          flush=True)
+def _parity(name, part, kind, dims, dtype, seed, transform_first="auto"):
+    """transform_first: the order of the first layer's halves on the GPU ("auto": weights first where the layer narrows
+    its input).  The oracle always aggregates first; the two orders are the same sums up to rounding."""
+    print(f"model {name}: n={part.graph.n_rows} nnz={part.graph.nnz} |T|={len(part.targets)} {kind} dims={dims} {dtype} "
+          f"transform_first={transform_first}", flush=True)
     import paper_2311_06837_amd as P
     L = len(dims) - 1
     params = gg.layer_weights(dims, kind == "sage", seed)
@@ -37,7 +39,9 @@ def _parity(name, part, kind, dims, dtype, seed):
     loss_o = om.forward(H0, y)
     grads_o = om.backward()
 
-    m = _gpu_model(part, kind, params, dtype)
+    m = _gpu_model(part, kind, params, dtype, transform_first)
+    if transform_first != "auto":
+        assert m.transform_first == transform_first
     hop = m.build_active_sets()
     assert list(hop) == list(om.hop_offsets)
     assert np.array_equal(m.dist.cpu().numpy(), om.dist)
@@ -51,7 +55,8 @@ def _parity(name, part, kind, dims, dtype, seed):
     assert abs(loss.item() - loss_o) <= tol * abs(loss_o), (loss.item(), loss_o)
     for l in range(1, L + 1):
         rows = om.rows_of_layer(l)
-        check(host64(m.A[l])[rows, : dims[l - 1]], om.A[l][rows], dtype, f"A_{l}", calls=l)
+        if m.A[l] is not None:          # (the exchanged order never forms the aggregate of the input features)
+            check(host64(m.A[l])[rows, : dims[l - 1]], om.A[l][rows], dtype, f"A_{l}", calls=l)
         check(host64(m.H[l])[rows, : dims[l]], om.H[l][rows], dtype, f"H_{l}", calls=l)
     # gradients accumulate rounding over L layers; the bound is per GEMM/SpMM call, so allow L of them
     for l in range(L):
@@ -67,9 +72,22 @@ def test_cfg0_full_size():
     _parity("cfg0", w.partition, w.model, w.dims, torch.float32, 0)
 
 
-def test_cfg1_scaled():
+@pytest.mark.parametrize("transform_first", [False, True])
+def test_cfg1_scaled(transform_first):
     w = gg.make_workload("cfg1", scale=0.02)
-    _parity("cfg1@0.02", w.partition, w.model, w.dims, torch.float32, 1)
+    assert w.dims[0] > w.dims[1]
+    _parity("cfg1@0.02", w.partition, w.model, w.dims, torch.float32, 1, transform_first)
+
+
+@pytest.mark.parametrize("dims", [[96, 64, 64, 7], [40, 12]])
+def test_transform_first_bf16_and_single_layer(dims):
+    """The exchanged first layer in bf16 storage, and as the only layer (its output is the logits: no ReLU, the
+    gradient comes straight from the loss)."""
+    g = gg.chung_lu(5000, 9.0, 2.2, 61)
+    T = np.sort(np.random.default_rng(61).choice(5000, 300, replace=False)).astype(np.int64)
+    part = gg.halo_partition(g, T, len(dims) - 1)
+    _parity("narrowing", part, "sage", dims, torch.bfloat16, 61, True)
+    _parity("narrowing", part, "sage", dims, torch.float32, 62, True)
 
 
 def test_cfg2_scaled():
@@ -104,7 +122,8 @@ def test_directed_graph_uses_the_transpose():
     T = np.sort(np.random.default_rng(41).choice(6000, 200, replace=False)).astype(np.int64)
     part = gg.halo_partition(g, T, 3, symmetric=False)
     assert part.graph_t is not part.graph
-    _parity("directed", part, "sage", [32, 24, 16, 5], torch.float32, 41)
+    _parity("directed", part, "sage", [32, 24, 16, 5], torch.float32, 41, False)
+    _parity("directed", part, "sage", [32, 24, 16, 5], torch.float32, 41, True)    # layer 1 aggregates backward too
 
 
 def test_masked_equals_unmasked_on_targets_on_the_gpu():

@@ -47,6 +47,56 @@ def _fwd_case(g, F, ld, dtype, rows, scales, seed, ws=None):
         assert (got[:, F:] == host64(torch.tensor(SENTINEL, dtype=dtype))).all(), "pad columns were written"
 
 
+def _fwd_add_case(g, F, ld, dtype, rows, relu, seed, ws=None):
+    """gnn_masked_spmm_fwd_add: Y = act(Y + aggregation).  The oracle aggregates into a zeroed matrix; the sum with
+    the self term and the ReLU are written out here (in the storage precision of the self term)."""
+    import paper_2311_06837_amd as P
+    print(f"spmm fwd_add: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} rows={'list' if rows is not None else 'all'} relu={relu}",
+          flush=True)
+    rng = np.random.default_rng(seed)
+    n = g.n_rows
+    X = as_stored(rng.standard_normal((n, F)), dtype)
+    S = as_stored(rng.standard_normal((n, F)), dtype)
+    rs = (1.0 / np.maximum(g.degrees(), 1)).astype(np.float32)
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    Xd = padded(X, ld, dtype)
+    Yd = torch.full((n, ld), SENTINEL, dtype=dtype, device="cuda")
+    Yd[:, :F] = padded(S, F, dtype)
+    rows_d = dev(rows) if rows is not None else None
+    n_active = len(rows) if rows is not None else n
+    P.gnn_masked_spmm_fwd_add(G, rows_d, n_active, Xd, Yd, F, dev(rs), None, relu=relu, ws=ws)
+    torch.cuda.synchronize()
+    agg = np.zeros((n, F))
+    oracle.spmm_fwd(g.row_ptr, g.col_idx, rows, X, agg, F, rs, None)
+    want = S + agg
+    if relu:
+        want = np.maximum(want, 0.0)
+    got = host64(Yd)
+    sel = np.asarray(rows if rows is not None else np.arange(n))
+    check(got[sel, :F], want[sel], dtype, "active rows")
+    if relu:
+        assert (got[sel, :F] >= 0).all()
+        # a row without neighbours still gets its activation
+        empty = sel[g.degrees()[sel] == 0]
+        assert np.array_equal(got[empty, :F], np.maximum(S[empty], 0.0))
+    rest = np.setdiff1d(np.arange(n), sel)
+    assert np.array_equal(got[rest, :F], S[rest]), "masked rows were written"
+    if ld > F:
+        assert (got[:, F:] == host64(torch.tensor(SENTINEL, dtype=dtype))).all(), "pad columns were written"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("relu", [False, True])
+def test_fwd_add_on_top_of_the_self_term(dtype, relu):
+    g = gg.chung_lu(3000, 6.0, 2.1, 13)
+    assert (g.degrees() == 0).any()
+    rng = np.random.default_rng(3)
+    rows = np.sort(rng.choice(3000, 1777, replace=False)).astype(np.int32)
+    _fwd_add_case(g, 256, 256, dtype, None, relu, 51)
+    _fwd_add_case(g, 100, 104, dtype, rows, relu, 52)
+    _fwd_add_case(g, 7, 7, dtype, rows, relu, 53)            # element-wise lanes
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("F,ld", [(64, 64), (100, 100), (128, 128), (256, 256), (602, 608), (602, 602), (7, 7), (1, 8),
                                   (300, 304), (1000, 1000)])
@@ -204,6 +254,18 @@ def test_blocked_route_forward(dtype):
         rows[17] = 0
     _fwd_case(g, 602, 608, dtype, rows, False, 42, ws=ws)
     _fwd_case(g, 64, 64, dtype, rows, True, 43, ws=ws)                    # a single slab
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_blocked_route_forward_add(dtype):
+    import paper_2311_06837_amd as P
+    g = _dense_graph()
+    ws = P.Workspace()
+    _fwd_add_case(g, 200, 200, dtype, None, True, 44, ws=ws)
+    assert _used_blocked_route(ws)
+    rows = np.random.default_rng(6).permutation(g.n_rows)[:40001].astype(np.int32)
+    _fwd_add_case(g, 256, 256, dtype, rows, False, 45, ws=ws)
+    _fwd_add_case(g, 90, 96, dtype, rows, True, 46, ws=ws)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
