@@ -148,7 +148,12 @@ int32_t gnn_masked_spmm_fwd_add(const gnn_csr *g, const int32_t *rows, int32_t n
  * TRANSPOSED graph gT (row u of gT lists every v that aggregates u; for a symmetric graph pass
  * the same arrays):
  *     dX[u, 0:F] (+)= col_scale[u] * sum_{v in rowT(u), active(v)} row_scale[v] * dY[v, 0:F]   for u in out_rows
- *   active(v)   dist == NULL: always; else 0 <= dist[v] <= max_active_dist  (v was a row of the forward call)
+ *   active(v)   (dist == NULL or 0 <= dist[v] <= max_active_dist) and (src_prefix < 0 or v < src_prefix): v was a
+ *               row of the forward call.  src_prefix is the form of the test for a partition numbered by (distance,
+ *               id) (gnn_extract_partition): the forward rows were the ids 0 .. src_prefix-1, so dist can stay NULL;
+ *               when gT promises GNN_CSR_SORTED_COLUMNS every row is simply cut at its first entry >= src_prefix
+ *               (a binary search per row instead of a test per entry), otherwise the entries are tested one by one.
+ *               -1: no such test.
  *   accumulate  0: overwrite dX rows, 1: add to them
  *   relu_H      nullable: the activations H of the layer whose gradient dX is (same rows, F columns, leading
  *               dimension ld_relu).  What is stored (after the addition of accumulate) is zeroed where H <= 0, i.e. dX
@@ -158,7 +163,7 @@ int32_t gnn_masked_spmm_fwd_add(const gnn_csr *g, const int32_t *rows, int32_t n
  * Same determinism and the same optional workspace as the forward call.
  */
 int32_t gnn_masked_spmm_bwd(const gnn_csr *gT, const int32_t *out_rows, int32_t n_out,
-                            const int32_t *dist, int32_t max_active_dist,
+                            const int32_t *dist, int32_t max_active_dist, int32_t src_prefix,
                             const void *dY, int64_t lddy, void *dX, int64_t lddx, int32_t F, int32_t dtype,
                             const float *row_scale, const float *col_scale, int32_t accumulate,
                             const void *relu_H, int64_t ld_relu,

@@ -278,8 +278,10 @@ def spmm_workspace_bytes(g: Graph, n_active: int, X: torch.Tensor, Y: torch.Tens
 
 def gnn_masked_spmm_bwd(gT: Graph, out_rows, n_out: int, dist, max_active_dist: int, dY: torch.Tensor, dX: torch.Tensor,
                         F: int, row_scale=None, col_scale=None, accumulate: bool = False, ws: Workspace | None = None,
-                        relu_H: torch.Tensor | None = None):
-    """relu_H: activations of the layer whose gradient dX is; the stored rows are zeroed where relu_H <= 0."""
+                        relu_H: torch.Tensor | None = None, src_prefix: int = -1):
+    """relu_H: activations of the layer whose gradient dX is; the stored rows are zeroed where relu_H <= 0.
+    src_prefix: >= 0: only the entries v < src_prefix of a row of gT are gathered (the forward rows of a (distance, id)-
+    numbered partition)."""
     _mat(dY, "dY"), _mat(dX, "dX")
     if relu_H is not None:
         _mat(relu_H, "relu_H")
@@ -288,7 +290,7 @@ def gnn_masked_spmm_bwd(gT: Graph, out_rows, n_out: int, dist, max_active_dist: 
     assert out_rows is None or out_rows.numel() >= n_out
     _with_optional_ws(lib().gnn_masked_spmm_bwd, (
         C.byref(gT.c), _ptr(_i32(out_rows, "out_rows")), C.c_int32(n_out), _ptr(_i32(dist, "dist")),
-        C.c_int32(max_active_dist), _ptr(dY), C.c_int64(dY.stride(0)), _ptr(dX), C.c_int64(dX.stride(0)), C.c_int32(F),
+        C.c_int32(max_active_dist), C.c_int32(src_prefix), _ptr(dY), C.c_int64(dY.stride(0)), _ptr(dX), C.c_int64(dX.stride(0)), C.c_int32(F),
         C.c_int32(_dtype_code(dY)), _ptr(row_scale), _ptr(col_scale), C.c_int32(1 if accumulate else 0), _ptr(relu_H),
         C.c_int64(relu_H.stride(0) if relu_H is not None else 0)), (_stream(),), ws)
 

@@ -70,6 +70,8 @@ struct SpmmArgs {
     const int32_t* dist;      // nullable filter: keep u iff 0 <= dist[u] <= max_dist
     int32_t max_dist;
     const uint32_t* edge_keep;  // nullable filter: keep the entry at position p iff bit p is set (layer-wise sampling mask)
+    int32_t cut_id;           // -1, or (rows sorted by column): every row ends at its first entry >= cut_id
+    int32_t id_limit;         // -1, or (rows in any order): the filter drops the entries >= id_limit
     int32_t accumulate;
     const void* relu_h;       // nullable: the stored result is zeroed where this matrix (same rows and columns as Y) is <= 0
     int64_t ldh;
@@ -228,7 +230,18 @@ __device__ __forceinline__ void store_part(float* p, int64_t off, const float (&
 __device__ __forceinline__ int32_t filter_probe(const SpmmArgs& a, int32_t u, int32_t p) {
     int32_t d = a.dist ? a.dist[u] : 0;
     if (a.edge_keep && !((a.edge_keep[p >> 5] >> (p & 31)) & 1u)) d = -1;
+    if (a.id_limit >= 0 && u >= a.id_limit) d = -1;
     return d;
+}
+
+// First position in [lo, hi) of a row sorted by column whose entry is >= bound (hi if none).
+__device__ __forceinline__ int32_t row_lower_bound(const int32_t* __restrict__ col_idx, int32_t lo, int32_t hi, int64_t bound) {
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if ((int64_t)col_idx[mid] < bound) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
 }
 
 // Filter (backward: "was u an active row of the forward call"), compact and stage one tile of
@@ -303,7 +316,7 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
     constexpr int RPB = NG * kRowsPerGroup;  // largest chunk, <= 128
     constexpr int W = LPR * NCH * VE;        // feature columns per workgroup (grid.y blocks cover F)
     __shared__ int32_t s_idx_all[4][kWave];
-    __shared__ int32_t s_row_v[RPB], s_row_s[RPB], s_row_e[RPB], s_row_hub[RPB];
+    __shared__ int32_t s_row_v[RPB], s_row_s[RPB], s_row_e[RPB], s_row_hub[RPB], s_row_he[RPB];
     __shared__ float s_row_sc[RPB];
     __shared__ int32_t s_next;
     __shared__ float s_red[NG][W];
@@ -319,11 +332,14 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
     if ((int)threadIdx.x < n_chunk) {
         const int r = threadIdx.x;
         const int32_t v = a.rows ? a.rows[chunk0 + r] : (int32_t)(chunk0 + r);
-        const int32_t s = a.row_ptr[v], e = a.row_ptr[v + 1];
+        const int32_t s = a.row_ptr[v];
+        int32_t e = a.row_ptr[v + 1];
+        if (a.cut_id >= 0) e = row_lower_bound(a.col_idx, s, e, a.cut_id);   // the entries past it can never pass the filter
         const bool hub = e - s > kHubDegree;
         s_row_v[r] = v;
         s_row_s[r] = s;
         s_row_e[r] = hub ? s : e;
+        s_row_he[r] = e;
         s_row_hub[r] = hub ? 1 : 0;
         s_row_sc[r] = a.out_scale ? a.out_scale[v] : 1.f;
     }
@@ -426,7 +442,7 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
     for (int q = 0; q < n_chunk; ++q) {
         if (!s_row_hub[q]) continue;  // uniform over the workgroup
         const int32_t hv = s_row_v[q];
-        const int32_t hs = s_row_s[q], he = a.row_ptr[hv + 1];
+        const int32_t hs = s_row_s[q], he = s_row_he[q];
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
@@ -834,25 +850,23 @@ __global__ __launch_bounds__(1024) void spmm_bounds_kernel(const int32_t* __rest
 
 // Cut points of every listed row at the column-block boundaries (rows sorted by column): seg[r][j] = first position
 // of row r whose column is >= the j-th boundary (bounds[j] if given, else j * block_size); seg[r][0] = start,
-// seg[r][n_blocks] = end.
+// seg[r][n_blocks] = end - or, with limit < n_cols, the first position whose column is >= limit (the entries past it
+// are never gathered), and no boundary lies above limit.
 __global__ __launch_bounds__(256) void spmm_seg_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                         const int32_t* __restrict__ rows, int32_t n_active, int32_t n_blocks,
-                                                        int32_t block_size, const int32_t* __restrict__ bounds,
-                                                        int32_t* __restrict__ seg) {
+                                                        int32_t block_size, const int32_t* __restrict__ bounds, int32_t limit,
+                                                        int32_t n_cols, int32_t* __restrict__ seg) {
     const int64_t total = (int64_t)n_active * (n_blocks + 1);
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
         const int32_t r = (int32_t)(i / (n_blocks + 1)), j = (int32_t)(i % (n_blocks + 1));
         const int32_t v = rows ? rows[r] : r;
         int32_t lo = row_ptr[v], hi = row_ptr[v + 1];
         if (j == n_blocks) {
-            lo = hi;
+            lo = limit < n_cols ? row_lower_bound(col_idx, lo, hi, limit) : hi;
         } else if (j > 0) {
-            const int64_t bound = bounds ? (int64_t)bounds[j] : (int64_t)j * block_size;
-            while (lo < hi) {  // lower bound
-                const int32_t mid = lo + ((hi - lo) >> 1);
-                if ((int64_t)col_idx[mid] < bound) lo = mid + 1;
-                else hi = mid;
-            }
+            int64_t bound = bounds ? (int64_t)bounds[j] : (int64_t)j * block_size;
+            bound = bound < limit ? bound : limit;
+            lo = row_lower_bound(col_idx, lo, hi, bound);
         }
         seg[i] = lo;
     }
@@ -993,25 +1007,31 @@ struct BlockedPlan {
     size_t w_bytes = 0;                    // bf16 with a neighbour scale: the factor of every copied id
     int64_t avg_seg = 0;      // average neighbours of a row inside one column block
     int32_t n_cols = 0;
+    int32_t limit = 0;        // neighbour ids >= limit are never gathered (n_cols without a source prefix)
     size_t bounds_bytes = 0;  // with a filter: the column-block boundaries (balanced over the active vertices)
 };
 
 static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, int64_t row_bytes, bool vec_ok, bool filter,
-                                bool scaled, bool f32) {
+                                bool scaled, bool f32, int32_t src_prefix) {
     BlockedPlan p;
+    // with a source prefix only the rows [0, src_prefix) of the gathered matrix are ever read
+    const int32_t n_src = (src_prefix >= 0 && src_prefix < g->n_cols) ? src_prefix : g->n_cols;
     // the stream kernel addresses the gathered matrix with 32-bit offsets in 16-byte units: 64 GB at most
     if ((int64_t)g->n_cols * row_bytes >= ((int64_t)1 << 36)) return p;
     if (!vec_ok || !(g->flags & GNN_CSR_SORTED_COLUMNS) || g->n_rows <= 0 || n_active < 4096) return p;
     if (g->edge_keep != nullptr) return p;  // the per-layer edge mask is only known to the one-launch route
-    const int64_t slab = (int64_t)g->n_cols * kSlabBytes;
+    const int64_t slab = (int64_t)n_src * kSlabBytes;
     if (slab < (int64_t)GNN_SPMM_BLOCKED_MIN_SLAB) return p;
     const int passes = (int)((slab + kDies * (int64_t)GNN_SPMM_DIE_BYTES - 1) / (kDies * (int64_t)GNN_SPMM_DIE_BYTES));
     const int n_blocks = kDies * passes;
-    if (g->nnz / g->n_rows < (int64_t)GNN_SPMM_BLOCKED_MIN_SEG * n_blocks) return p;
+    // average kept length of a row: its entries spread over the id range like the vertices do
+    const int64_t avg_row = (int64_t)((double)g->nnz / g->n_rows * ((double)n_src / g->n_cols));
+    if (avg_row < (int64_t)GNN_SPMM_BLOCKED_MIN_SEG * n_blocks) return p;
     p.passes = passes;
     p.n_blocks = n_blocks;
-    p.avg_seg = g->nnz / g->n_rows / n_blocks;
-    p.block_size = (int32_t)(((int64_t)g->n_cols + n_blocks - 1) / n_blocks);
+    p.avg_seg = avg_row / n_blocks;
+    p.block_size = (int32_t)(((int64_t)n_src + n_blocks - 1) / n_blocks);
+    p.limit = n_src;
     p.ldp = ((int64_t)F + 7) / 8 * 8;
     p.seg_bytes = (size_t)n_active * (n_blocks + 1) * sizeof(int32_t);
     p.part_bytes = (size_t)kDies * n_active * p.ldp * sizeof(float);
@@ -1021,7 +1041,7 @@ static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, i
         p.end_bytes = (size_t)n_active * n_blocks * sizeof(int32_t);
         p.ids_bytes = (size_t)g->nnz * sizeof(int32_t);
     }
-    if (scaled && f32) p.xs_bytes = (size_t)g->n_cols * (size_t)row_bytes;
+    if (scaled && f32) p.xs_bytes = (size_t)n_src * (size_t)row_bytes;
     if (scaled && !f32) p.w_bytes = (size_t)g->nnz * sizeof(float);
     if (filter) p.bounds_bytes = ((size_t)n_blocks + 1) * sizeof(int32_t);
     p.n_cols = g->n_cols;
@@ -1046,13 +1066,13 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
         GNN_LAUNCH_CHECK("spmm_bounds_kernel");
     }
     spmm_seg_kernel<<<grid_for((int64_t)a.n_active * (p.n_blocks + 1), 256, 1 << 16), 256, 0, stream>>>(
-        a.row_ptr, a.col_idx, a.rows, a.n_active, p.n_blocks, p.block_size, bounds, seg);
+        a.row_ptr, a.col_idx, a.rows, a.n_active, p.n_blocks, p.block_size, bounds, p.limit, p.n_cols, seg);
     GNN_LAUNCH_CHECK("spmm_seg_kernel");
     SpmmArgs b = a;
     if (prescale) {
         // the neighbour scale is applied once per row of the gathered matrix, not once per edge and slab
-        spmm_scale_rows_kernel<DT><<<grid_for((int64_t)p.n_cols * ((a.F + VE - 1) / VE), 256, 1 << 16), 256, 0, stream>>>(
-            a.X, a.ldx, p.n_cols, a.F, a.nbr_scale, xs);
+        spmm_scale_rows_kernel<DT><<<grid_for((int64_t)p.limit * ((a.F + VE - 1) / VE), 256, 1 << 16), 256, 0, stream>>>(
+            a.X, a.ldx, p.limit, a.F, a.nbr_scale, xs);
         GNN_LAUNCH_CHECK("spmm_scale_rows_kernel");
         b.X = xs;
         b.nbr_scale = nullptr;
@@ -1098,7 +1118,7 @@ static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
 }
 
 static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* rows, int32_t n_active, const int32_t* dist,
-                           int32_t max_dist, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F, int32_t dtype,
+                           int32_t max_dist, int32_t src_prefix, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F, int32_t dtype,
                            const float* out_scale, const float* nbr_scale, int32_t accumulate, const void* relu_h, int64_t ldh,
                            void* ws, size_t* ws_bytes, hipStream_t stream) {
     GNN_CHECK(check_csr(g, gname));
@@ -1111,11 +1131,17 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     GNN_REQUIRE(relu_h == nullptr || ldh >= F, GNN_ERR_SHAPE, "ld_relu smaller than F = %d", F);
     const bool vec_ok = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && ldx % ve == 0 && ldy % ve == 0 &&
                         (relu_h == nullptr || ((uintptr_t)relu_h % 16 == 0 && ldh % ve == 0));
-    const bool filter = dist != nullptr || g->edge_keep != nullptr;
+    GNN_REQUIRE(src_prefix >= -1, GNN_ERR_INVALID_ARG, "src_prefix %d: -1 or a vertex count", src_prefix);
+    // A source prefix that leaves something out: rows sorted by column are cut at that id (no test per entry), rows in
+    // any order get the test in the filter.
+    const bool use_prefix = src_prefix >= 0 && src_prefix < g->n_cols;
+    const bool sorted = (g->flags & GNN_CSR_SORTED_COLUMNS) != 0;
+    const int32_t cut_id = (use_prefix && sorted) ? src_prefix : -1, id_limit = (use_prefix && !sorted) ? src_prefix : -1;
+    const bool filter = dist != nullptr || g->edge_keep != nullptr || id_limit >= 0;
     BlockedPlan plan;
     if (ws_bytes != nullptr) {
         if (n_active > 0 && F > 0) plan = plan_blocked(g, n_active, F, ldx * (dtype == GNN_F32 ? 4 : 2), vec_ok, filter, nbr_scale != nullptr,
-                                                            dtype == GNN_F32);
+                                                            dtype == GNN_F32, cut_id);
         WsCarver measure(nullptr);
         if (plan.passes > 0) {
             measure.take<char>(plan.seg_bytes);
@@ -1140,6 +1166,7 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
     a.out_scale = out_scale; a.nbr_scale = nbr_scale; a.dist = dist; a.max_dist = dist ? max_dist : INT32_MAX;
     a.edge_keep = g->edge_keep;
+    a.cut_id = cut_id; a.id_limit = id_limit;
     a.accumulate = accumulate;
     a.relu_h = relu_h; a.ldh = ldh;
     a.rows_per_group = 1;
@@ -1160,7 +1187,7 @@ using namespace gnnhot;
 extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
                                        void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
                                        const float* col_scale, void* ws, size_t* ws_bytes, void* stream) {
-    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, nullptr, 0, ws,
+    return spmm_common(g, "g", rows, n_active, nullptr, 0, -1, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 0, nullptr, 0, ws,
                        ws_bytes, (hipStream_t)stream);
 }
 
@@ -1169,15 +1196,15 @@ extern "C" int32_t gnn_masked_spmm_fwd_add(const gnn_csr* g, const int32_t* rows
                                            const float* col_scale, int32_t relu, void* ws, size_t* ws_bytes, void* stream) {
     GNN_REQUIRE(relu == 0 || relu == 1, GNN_ERR_INVALID_ARG, "relu must be 0 or 1");
     // the output matrix as its own mask stands for a ReLU of what is stored
-    return spmm_common(g, "g", rows, n_active, nullptr, 0, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 1, relu ? Y : nullptr, ldy, ws,
+    return spmm_common(g, "g", rows, n_active, nullptr, 0, -1, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 1, relu ? Y : nullptr, ldy, ws,
                        ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int32_t gnn_masked_spmm_bwd(const gnn_csr* gT, const int32_t* out_rows, int32_t n_out, const int32_t* dist,
-                                       int32_t max_active_dist, const void* dY, int64_t lddy, void* dX, int64_t lddx, int32_t F,
+                                       int32_t max_active_dist, int32_t src_prefix, const void* dY, int64_t lddy, void* dX, int64_t lddx, int32_t F,
                                        int32_t dtype, const float* row_scale, const float* col_scale, int32_t accumulate,
                                        const void* relu_H, int64_t ld_relu, void* ws, size_t* ws_bytes, void* stream) {
     GNN_REQUIRE(accumulate == 0 || accumulate == 1, GNN_ERR_INVALID_ARG, "accumulate must be 0 or 1");
-    return spmm_common(gT, "gT", out_rows, n_out, dist, max_active_dist, dY, lddy, dX, lddx, F, dtype, col_scale, row_scale,
+    return spmm_common(gT, "gT", out_rows, n_out, dist, max_active_dist, src_prefix, dY, lddy, dX, lddx, F, dtype, col_scale, row_scale,
                        accumulate, relu_H, ld_relu, ws, ws_bytes, (hipStream_t)stream);
 }

@@ -202,19 +202,28 @@ class MaskedGNN:
                 ws_bwd = self.ws if 4 * nl >= self.n else None
                 gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[l], self.rs_l[l])
                 # when the forward call computed every vertex of the partition the filter keeps everything: leave it out
-                dist_l = None if nl == self.n else self.dist
+                dist_l, pre_l = self._source_filter(nl)
                 relu_h = self.H[l - 1]      # layer l-1 ends in a ReLU (l-1 < L): its gradient leaves the aggregation masked
                 if sage:
                     # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, nl, dist_l, L - l, self.dA[l], self.dH[l - 1], K,
-                                          rs_l, self.cs, accumulate=True, ws=ws_bwd, relu_H=relu_h)
+                                          rs_l, self.cs, accumulate=True, ws=ws_bwd, relu_H=relu_h, src_prefix=pre_l)
                     if n_prev > nl:
                         self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, gt_l, self.ring_ids[nl:], n_prev - nl, dist_l, L - l, self.dA[l],
-                                              self.dH[l - 1], K, rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h)
+                                              self.dH[l - 1], K, rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h, src_prefix=pre_l)
                 else:
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dA[l], self.dH[l - 1], K,
-                                          rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h)
+                                          rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h, src_prefix=pre_l)
         return self.grads
+
+    def _source_filter(self, n_fwd: int):
+        """(dist, src_prefix) of a backward aggregation whose forward call computed the first n_fwd ring-sorted vertices:
+        nothing when those are all vertices, the id prefix on a (distance, id)-numbered partition, else the distances."""
+        if n_fwd == self.n:
+            return None, -1
+        if self.prefix_numbered:
+            return None, n_fwd
+        return self.dist, -1
 
     def _backward_transform_first(self):
         """First layer in the exchanged order, Z = rs * Agg(H_0 W_neigh) + H_0 W_self + b: the self half takes dZ as it
@@ -222,9 +231,9 @@ class MaskedGNN:
         L, p, gr, K = self.L, self.params[0], self.grads[0], self.dims[0]
         n1, n0 = self.n_rows_of_layer(1), int(self.hop[L + 1])
         gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[1], self.rs_l[1])
-        dist_l = None if n1 == self.n else self.dist
+        dist_l, pre_l = self._source_filter(n1)
         self._call("spmm_bwd_1", B.gnn_masked_spmm_bwd, gt_l, self.rows, n0, dist_l, L - 1, self.dH[1], self.dP, self.dims[1],
-                   rs_l, self.cs, accumulate=False, ws=self.ws if 4 * n1 >= self.n else None)
+                   rs_l, self.cs, accumulate=False, ws=self.ws if 4 * n1 >= self.n else None, src_prefix=pre_l)
         self._call("linear_bwd_1", B.gnn_linear_bwd, self.rows, n1, self.dH[1], None, False, self.H[0], None, K, p["W_self"], None,
                    gr["dW_self"], None, gr["dbias"], None, None, ws=self.ws)
         self._call("linear_bwd_1_neigh", B.gnn_linear_bwd, self.rows, n0, self.dP, None, False, self.H[0], None, K, p["W_neigh"], None,
@@ -377,13 +386,15 @@ class ResSAGEPlus:
             if not need_in:
                 break
             n_prev = self.n_rows_of_layer(l - 1)
-            dist_l = None if nl == self.n else self.dist    # every vertex was a forward row: the filter keeps everything
+            # every vertex was a forward row: the filter keeps everything; on a (distance, id)-numbered partition the
+            # forward rows are an id prefix; else their distances decide
+            dist_l, pre_l = (None, -1) if nl == self.n else ((None, nl) if self.prefix_numbered else (self.dist, -1))
             # rows of R_l already hold dZ W_self^T: add the aggregated part; the next ring starts from zero
             self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, self.gt, self.rows, nl, dist_l, L - l, self.dA, self.dT, K,
-                       self.rs, None, accumulate=True, ws=None)
+                       self.rs, None, accumulate=True, ws=None, src_prefix=pre_l)
             if n_prev > nl:
                 self._call(f"spmm_bwd_{l}_ring", B.gnn_masked_spmm_bwd, self.gt, self.ring_ids[nl:], n_prev - nl, dist_l, L - l, self.dA,
-                           self.dT, K, self.rs, None, accumulate=False, ws=None)
+                           self.dT, K, self.rs, None, accumulate=False, ws=None, src_prefix=pre_l)
             out = self.dH[l % 2]
             self._call(f"ln_bwd_{l}", B.gnn_layer_norm_relu_bwd, self.rows, n_prev, self.dT, src, self.H[l - 1], K, p["ln_gamma"],
                        dH if l < L else None, nl if l < L else 0, out, gr["dln_gamma"], gr["dln_beta"], ws=self.ws)

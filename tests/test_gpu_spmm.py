@@ -322,3 +322,69 @@ def test_blocked_route_backward_with_prefix_active_sources():
     want = np.zeros((n, F))
     oracle.spmm_bwd(g.row_ptr, g.col_idx, np.arange(n_fwd, dtype=np.int32), dY, want, F, rs, cs)
     check(host64(dX), want, torch.float32, "prefix-active backward")
+
+
+def _prefix_case(g, n_fwd, F, dtype, seed, sorted_promise=True, ws=None, accumulate=False, relu=False, out_rows=None):
+    """Backward aggregation whose forward rows were the ids 0 .. n_fwd-1, told through src_prefix instead of a
+    distance array.  The oracle gets the same thing as an explicit row list."""
+    import paper_2311_06837_amd as P
+    print(f"spmm bwd src_prefix: n={g.n_rows} nnz={g.nnz} n_fwd={n_fwd} F={F} {dtype} sorted={sorted_promise} acc={accumulate} "
+          f"relu={relu}", flush=True)
+    rng = np.random.default_rng(seed)
+    n = g.n_rows
+    gt = gg.transpose(g)
+    dY = as_stored(rng.standard_normal((n, F)), dtype)
+    rs = (rng.random(n) + 0.5).astype(np.float32)
+    cs = (rng.random(n) + 0.5).astype(np.float32)
+    init = as_stored(rng.standard_normal((n, F)), dtype) if accumulate else np.full((n, F), SENTINEL)
+    Hact = as_stored(np.maximum(rng.standard_normal((n, F)), 0), dtype) if relu else None
+    GT = P.Graph.from_numpy(gt.row_ptr, gt.col_idx)
+    assert GT.sorted_columns
+    if not sorted_promise:
+        GT = P.Graph(GT.row_ptr, GT.col_idx, None, sorted_columns=False)     # same arrays, no promise: tested entry by entry
+    rows_o = np.arange(n, dtype=np.int32) if out_rows is None else out_rows
+    dXd = padded(init, F, dtype)
+    P.gnn_masked_spmm_bwd(GT, None if out_rows is None else dev(rows_o), len(rows_o), None, 0, padded(dY, F, dtype), dXd, F, dev(rs),
+                          dev(cs), accumulate=accumulate, ws=ws, relu_H=padded(Hact, F, dtype) if relu else None, src_prefix=n_fwd)
+    torch.cuda.synchronize()
+    want = np.zeros((n, F))
+    oracle.spmm_bwd(g.row_ptr, g.col_idx, np.arange(n_fwd, dtype=np.int32), dY, want, F, rs, cs)
+    if accumulate:
+        want = want + init
+    if relu:
+        want = want * (Hact > 0)
+    got = host64(dXd)
+    check(got[rows_o], want[rows_o], dtype, "bwd rows")
+    outside = np.setdiff1d(np.arange(n), rows_o)
+    assert (got[outside] == host64(padded(init, F, dtype))[outside]).all(), "rows outside were written"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("sorted_promise", [True, False])
+def test_bwd_source_prefix(dtype, sorted_promise):
+    g = gg.random_directed(8000, 6.0, 23)
+    _prefix_case(g, 1500, 128, dtype, 31, sorted_promise)
+    _prefix_case(g, 1, 64, dtype, 32, sorted_promise, accumulate=True)                 # a single forward row
+    _prefix_case(g, 0, 64, dtype, 33, sorted_promise)                                  # none: every row sums to zero
+    _prefix_case(g, 8000, 64, dtype, 34, sorted_promise, relu=True)                    # all: no cut at all
+    _prefix_case(g, 7999, 100, dtype, 35, sorted_promise, accumulate=True, relu=True)
+    rows = np.random.default_rng(36).permutation(8000)[:3001].astype(np.int32)
+    _prefix_case(g, 4000, 7, dtype, 37, sorted_promise, out_rows=rows)
+    h = gg.chung_lu(12000, 150.0, 2.1, 12)                                             # hub rows, cut inside the hub
+    assert h.degrees().max() > 1200                                                    # (hub rows: longer than 1024)
+    _prefix_case(h, 11000, 64, dtype, 38, sorted_promise, relu=True)                   # still hubs after the cut
+    _prefix_case(h, 6000, 64, dtype, 39, sorted_promise)                               # hubs that stop being hubs after the cut
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_blocked_route_backward_with_source_prefix(dtype):
+    """The column-blocked route cuts its blocks out of [0, src_prefix) only."""
+    import paper_2311_06837_amd as P
+    g = _dense_graph()
+    ws = P.Workspace()
+    _prefix_case(g, 68001, 96, dtype, 78, ws=ws, relu=True)          # 68001 * 256 B is still above the route's threshold
+    assert _used_blocked_route(ws)
+    _prefix_case(g, 66000, 200, dtype, 79, ws=ws, accumulate=True)
+    ws2 = P.Workspace()
+    _prefix_case(g, 9000, 96, dtype, 80, ws=ws2)                     # a short prefix fits the caches: one launch
+    assert not _used_blocked_route(ws2)
