@@ -34,12 +34,13 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 CONFIG_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}
 
 # Traffic between L2 and the memory fabric of the dominant call per launch, from the two rocprofv3 --pmc runs
-# summarised in profiles/spmm_fwd_layer1_cfg1.md and profiles/spmm_rows_and_gemm_cfg4.md (FETCH_SIZE and WRITE_SIZE in KiB, summed over the call's
-# three kernels, scaled by what the same counters read for a 1 GiB copy: 2.0 and 1.0).  Known for configs[1] and
-# configs[4] at full scale.
-MEASURED_TRAFFIC_KIB = {"cfg1": {"layer": 1, "fetch": 40302620 + 2297897 + 231169,   # stream + sum_parts + seg kernels
-                                 "write": 4427085 + 562475 + 8192},
-                        "cfg4": {"layer": 2, "fetch": 7994684, "write": 1742670}}     # one spmm_rows_kernel launch
+# summarised in profiles/spmm_blocked_fwd_cfg1.md and profiles/spmm_rows_and_gemm_cfg4.md (FETCH_SIZE and WRITE_SIZE in
+# KiB, summed over the call's kernels, scaled by what the same counters read for a 1 GiB copy: 2.0 and 1.0).  Known
+# for configs[1] (layer 2; layer 1 in the paper's order, --aggregate-first) and configs[4] at full scale.
+MEASURED_TRAFFIC_KIB = {"cfg1": {2: {"fetch": 232480 + 15956789 + 935673,       # seg + stream + sum_parts kernels
+                                     "write": 8191 + 1864000 + 233000},
+                                 1: {"fetch": 231169 + 40302620 + 2297897, "write": 8192 + 4427085 + 562475}},
+                        "cfg4": {2: {"fetch": 7995125, "write": 1742670}}}       # one spmm_rows_kernel launch
 FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 
 
@@ -255,11 +256,11 @@ def main():
     blocked = P.binding.spmm_workspace_bytes(G, nd, src_dom, dst_dom, Fd) > 0
     kernels = ("spmm_stream_kernel (+ spmm_seg_kernel before and spmm_sum_parts_kernel after it: column-blocked route)"
                if blocked else "spmm_rows_kernel")
-    kib = MEASURED_TRAFFIC_KIB.get(args.workload) if args.scale == 1.0 else None
-    if kib is not None and kib["layer"] != dom:
+    kib = MEASURED_TRAFFIC_KIB.get(args.workload, {}).get(dom) if args.scale == 1.0 else None
+    if dom == 1 and model.transform_first:       # (the layer-1 figures are those of the 602-wide gather)
         kib = None
     traffic = None
-    if kib and kib["fetch"] is not None:
+    if kib:
         traffic = (kib["fetch"] * FETCH_SCALE + kib["write"] * WRITE_SCALE) * 1024
     # `achieved` counts the ALGORITHMIC bytes of the gather model (every neighbour row of every edge); on the
     # column-blocked route most of them are served by the L2 of the compute die, so it can exceed the HBM peak.
