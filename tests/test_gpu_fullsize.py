@@ -95,15 +95,42 @@ def _spmm_fwd_sampled(w, G, rows_all, F, dtype, kind, seed, n_sample=1500):
     return X, Xd, Yd, (rs, cs, rs_d, cs_d)
 
 
-def _spmm_bwd_sampled(w, G, dist, rows_out, max_dist, F, dtype, scales, seed, n_sample=1500, whole=False):
+def _spmm_fwd_add_sampled(w, G, F, dtype, seed, n_sample=600):
+    """The add-on-top form of the forward aggregation (a first layer that multiplies by its weights first), every
+    vertex a row, ReLU in the store; the oracle recomputes the plain aggregation of a sample, the sum with the self
+    term and the ReLU are written out here."""
+    import paper_2311_06837_amd as P
+    part = w.partition
+    n = part.graph.n_rows
+    ld = P.row_stride(F, dtype)
+    print(f"{w.name}: spmm fwd_add rows={n} F={F} {dtype}", flush=True)
+    X = as_stored(gg.features(n, F, seed), dtype)
+    S = as_stored(gg.features(n, F, seed + 300), dtype)
+    rs = oracle.norm_scales("mean", np.diff(part.graph.row_ptr).astype(np.int32))
+    rs_d = P.gnn_norm_scales(P.GNN_NORM_MEAN, n, row_ptr=G.row_ptr)
+    Yd = padded(S, ld, dtype)
+    P.gnn_masked_spmm_fwd_add(G, None, n, padded(X, ld, dtype), Yd, F, rs_d, None, relu=True, ws=_ws())
+    torch.cuda.synchronize()
+    sample = _sample_rows(part, np.arange(n, dtype=np.int32), n_sample, seed)
+    agg = np.zeros((n, F))
+    oracle.spmm_fwd(part.graph.row_ptr, part.graph.col_idx, sample, X, agg, F, rs, None)
+    want = np.maximum(S[sample] + agg[sample], 0.0)
+    check(host64(Yd[dev(sample).long()])[:, :F], want, dtype, "sampled rows of the aggregation on top of the self term")
+
+
+def _spmm_bwd_sampled(w, G, dist, rows_out, max_dist, F, dtype, scales, seed, n_sample=1500, whole=False, src_prefix=-1):
     """Backward aggregation for every row of rows_out; the oracle recomputes a sample in gather form over
     the (symmetric) graph with the activity filter folded into the per-neighbour scale.
     whole: the form the model uses when every vertex was a forward row - no row list, no filter, and the call undoes
-    the ReLU of the layer in front (relu_H)."""
+    the ReLU of the layer in front (relu_H).
+    src_prefix >= 0: the contributing rows are the ids below it, told through src_prefix instead of the distances
+    (the form of the call on a (distance, id)-numbered partition; any graph will do to check it)."""
     import paper_2311_06837_amd as P
     part = w.partition
     n = part.graph.n_rows
     rs, cs, rs_d, cs_d = scales
+    if src_prefix >= 0:
+        dist = np.where(np.arange(n) < src_prefix, 0, max_dist + 1).astype(np.int32)
     ld = P.row_stride(F, dtype)                       # the layout the model (and so bench.py) uses
     print(f"{w.name}: spmm bwd rows={rows_out.size} F={F} {dtype} max_dist={max_dist}", flush=True)
     dY = as_stored(gg.features(n, F, seed + 100), dtype)
@@ -114,6 +141,9 @@ def _spmm_bwd_sampled(w, G, dist, rows_out, max_dist, F, dtype, scales, seed, n_
         assert rows_out.size == n and np.array_equal(rows_out, np.arange(n)) and ((dist >= 0) & (dist <= max_dist)).all()
         Hact = as_stored(np.maximum(gg.features(n, F, seed + 200), 0), dtype)
         P.gnn_masked_spmm_bwd(G, None, n, None, max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False, ws=_ws(), relu_H=padded(Hact, ld, dtype))
+    elif src_prefix >= 0:
+        P.gnn_masked_spmm_bwd(G, dev(rows_out), rows_out.size, None, max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False, ws=_ws(),
+                              src_prefix=src_prefix)
     else:
         P.gnn_masked_spmm_bwd(G, dev(rows_out), rows_out.size, dev(dist), max_dist, dYd, dXd, F, rs_d, cs_d, accumulate=False, ws=_ws())
     torch.cuda.synchronize()
@@ -206,6 +236,9 @@ def test_cfg1_full_size(cfg1):
     assert R1.size == n
     allrows = np.arange(n, dtype=np.int32)
     _spmm_bwd_sampled(w, G, dist, allrows, L - 2, 256, torch.float32, sc, 17, n_sample=600, whole=True)
+    _spmm_fwd_add_sampled(w, G, 256, torch.float32, 19)
+    _spmm_bwd_sampled(w, G, dist, allrows, 0, 256, torch.float32, sc, 20, n_sample=600, src_prefix=29125)      # one launch, rows cut
+    _spmm_bwd_sampled(w, G, dist, allrows, 0, 256, torch.float32, sc, 21, n_sample=600, src_prefix=200001)     # column-blocked route
     _linear_sampled(w, allrows, 256, 256, torch.float32, True, 18, n_sample=1500, n_cols=4, in_place=True)
 
 

@@ -148,3 +148,47 @@ def test_bf16_model_stays_close_to_fp64_model():
     for H in b.H:
         fin = H[np.isfinite(H)]
         assert np.array_equal(oracle.round_bf16(fin.copy()), fin)
+
+
+@pytest.mark.parametrize("directed", [False, True])
+def test_first_layer_in_the_exchanged_order_is_the_same_layer(directed):
+    """Section 2.1's layer is linear in front of the activation, so a first layer may multiply by its weights before it
+    aggregates: Agg(H_0 W_n) + H_0 W_s + b = Agg(H_0) W_n + H_0 W_s + b, and then dW_n = H_0^T Agg^T(dZ_1).  The exchanged
+    order written out with dense matrices against the oracle's aggregate-first model; dZ_1 comes from central
+    differences of the dense brute-force loss (a shift of Z_1[v, c] is emulated by a one-hot extra input column that
+    only the self weights of column c see)."""
+    g, T, params, H0, y = _setup("sage", 71, n=48, L=3, dims=(9, 5, 4, 3), directed=directed)
+    m = oracle.Model(g.row_ptr, g.col_idx, T, "sage", params)
+    m.forward(H0, y)
+    grads = m.backward()
+    n = g.n_rows
+    A = g.to_scipy().toarray().astype(np.float64)
+    deg = A.sum(1)
+    Ahat = np.where(deg > 0, 1 / np.maximum(deg, 1), 0)[:, None] * A
+    R1 = m.rows_of_layer(1)
+    base = [{k: np.array(v, dtype=np.float64) for k, v in pp.items()} for pp in params]
+    Wn, Ws, b = base[0]["W_neigh"], base[0]["W_self"], base[0]["bias"]
+    N1 = Wn.shape[1]
+    # forward
+    H1 = np.maximum(Ahat @ (H0 @ Wn) + H0 @ Ws + b, 0)
+    assert np.allclose(H1[R1], m.H[1][R1], rtol=1e-12, atol=1e-12)
+
+    # backward: dZ_1 by central differences
+    def loss_with_shift(v, c, d):
+        H0x = np.concatenate([H0, np.zeros((n, 1))], axis=1)
+        H0x[v, -1] = d
+        col = np.zeros((1, N1))
+        col[0, c] = 1.0
+        q = [dict(pp) for pp in base]
+        q[0] = {"W_neigh": np.concatenate([Wn, np.zeros_like(col)]), "W_self": np.concatenate([Ws, col]), "bias": b}
+        return _dense_forward(g, T, "sage", q, H0x, y)[1]
+
+    eps = 1e-6
+    dZ1 = np.zeros((n, N1))
+    for v in R1:
+        for c in range(N1):
+            dZ1[v, c] = (loss_with_shift(v, c, eps) - loss_with_shift(v, c, -eps)) / (2 * eps)
+    dP = Ahat.T @ dZ1                                         # what reaches the transformed rows: Agg^T(dZ_1)
+    for name, want in (("dW_neigh", H0.T @ dP), ("dW_self", H0.T @ dZ1), ("dbias", dZ1.sum(0))):
+        got = grads[0][name]
+        assert np.abs(got - want).max() <= 1e-7 * max(1.0, np.abs(want).max()), name
