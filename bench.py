@@ -99,8 +99,8 @@ def main():
                          "(distance, id) numbering, feature gather: every R_l is an id prefix); full-halo workloads only")
     ap.add_argument("--extract-on-gpu", action="store_true", help="the default; kept for old command lines")
     ap.add_argument("--aggregate-first", action="store_true",
-                    help="keep the paper's order (aggregate, then weights) in a first layer that narrows its input; by default "
-                         "such a layer multiplies by the weights first and gathers the narrower rows")
+                    help="keep the paper's order (aggregate, then weights) in every layer; by default a GraphSAGE layer that "
+                         "narrows its input multiplies by the weights first and gathers the narrower rows")
     ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
                     help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
                          "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
@@ -252,12 +252,12 @@ def main():
     alg_bytes = edges[dom]["fwd"] * (4 + Fd * es) + nd * (8 + Fd * es)           # gather model
     compulsory = edges[dom]["fwd"] * 4 + n_in * Fd * es + nd * (8 + Fd * es)     # every input row read once
     t_dom = call_ms[f"spmm_fwd_{dom}"] * 1e-3
-    src_dom, dst_dom = (model.P, model.H[1]) if (dom == 1 and model.transform_first) else (model.H[dom - 1], model.A[dom])
+    src_dom, dst_dom = (model.P[dom], model.H[dom]) if dom in model.tf_layers else (model.H[dom - 1], model.A[dom])
     blocked = P.binding.spmm_workspace_bytes(G, nd, src_dom, dst_dom, Fd) > 0
     kernels = ("spmm_stream_kernel (+ spmm_seg_kernel before and spmm_sum_parts_kernel after it: column-blocked route)"
                if blocked else "spmm_rows_kernel")
     kib = MEASURED_TRAFFIC_KIB.get(args.workload, {}).get(dom) if args.scale == 1.0 else None
-    if dom == 1 and model.transform_first:       # (the layer-1 figures are those of the 602-wide gather)
+    if dom == 1 and 1 in model.tf_layers:        # (the layer-1 figures are those of the 602-wide gather)
         kib = None
     traffic = None
     if kib:
@@ -328,7 +328,7 @@ def main():
         "partition_built_on": "gpu ((distance, id) numbering)" if (gpu_part is not None or sampled_graph is not None)
                               else "host (ascending-id numbering)",
         "aggregated_edges_per_step": total_edges,
-        "first_layer_order": "weights, then aggregation" if model.transform_first else "aggregation, then weights",
+        "layers_weights_first": sorted(model.tf_layers),
         "layer_sampling": args.layer_sampling,
         "layer_mask_ms": sum(v for k, v in call_ms.items() if k.startswith("layer_mask")) if args.layer_sampling else None,
         "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,

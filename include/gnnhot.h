@@ -328,6 +328,16 @@ int32_t gnn_add_rows(const int32_t *rows, int32_t n_active, const void *X, int64
                      int32_t dtype, void *stream);
 
 /*
+ * Two gradient contributions meet in front of a ReLU (backward of a layer in the exchanged order of
+ * gnn_masked_spmm_fwd_add: the neighbour half reaches every listed row, the self half only the first n_add of them):
+ *     Y[v, 0:F] = [H[v, 0:F] > 0] * (Y[v, 0:F] + (i < n_add ? X[v, 0:F] : 0))      v = rows[i], i < n_active
+ *   H   the activations behind that ReLU (same rows and columns, leading dimension ldh), not NULL
+ *   X   may be NULL when n_add == 0
+ */
+int32_t gnn_add_rows_masked(const int32_t *rows, int32_t n_active, const void *X, int64_t ldx, int32_t n_add, void *Y,
+                            int64_t ldy, int32_t F, const void *H, int64_t ldh, int32_t dtype, void *stream);
+
+/*
  * Extraction of the partition's one-hop graph (section 6, figure 7c step 1: extract the multi-hop
  * dependency starting from the inner vertices; section 5.3.1: a subgraph is generated from the
  * traversed vertices).  g is the UNPARTITIONED graph (square); ring_ids[0 .. n_local) and dist are

@@ -25,7 +25,7 @@ EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_s
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
            "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
-           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows"]
+           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked"]
 
 
 class GnnError(RuntimeError):
@@ -470,3 +470,18 @@ def gnn_add_rows(rows, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int):
     assert X.dtype == Y.dtype
     _check(lib().gnn_add_rows(_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
                               C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _stream()))
+
+
+def gnn_add_rows_masked(rows, n_active: int, X, n_add: int, Y: torch.Tensor, F: int, H: torch.Tensor):
+    """Y[rows, :F] = (Y[rows, :F] + X[rows, :F] for the first n_add listed rows) where H > 0, else 0."""
+    _mat(Y, "Y"), _mat(H, "H")
+    assert H.dtype == Y.dtype
+    assert rows is None or rows.numel() >= n_active
+    if X is not None:
+        _mat(X, "X")
+        assert X.dtype == Y.dtype
+    else:
+        assert n_add == 0
+    _check(lib().gnn_add_rows_masked(_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0) if X is not None else 0),
+                                     C.c_int32(n_add), _ptr(Y), C.c_int64(Y.stride(0)), C.c_int32(F), _ptr(H), C.c_int64(H.stride(0)),
+                                     C.c_int32(_dtype_code(Y)), _stream()))

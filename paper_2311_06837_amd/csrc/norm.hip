@@ -373,11 +373,14 @@ __global__ __launch_bounds__(1024) void ln_reduce_kernel(const float* __restrict
     }
 }
 
-// Y[v, 0:F] += X[v, 0:F] for the listed rows (the residual connection, forward).  VEC: 16-byte aligned rows and F a
-// multiple of the vector - a lane adds one 16-byte vector, consecutive lanes walk along the row and on to the next rows.
+// Y[v, 0:F] += X[v, 0:F] for the listed rows (the residual connection, forward).  Only the first n_add listed rows take
+// the addition; with H (nullable, same rows and columns as Y) what is stored is zeroed where H <= 0 - for every listed
+// row.  VEC: 16-byte aligned rows and F a multiple of the vector - a lane adds one 16-byte vector, consecutive lanes walk
+// along the row and on to the next rows.
 template <int DT, bool VEC>
 __global__ __launch_bounds__(256) void add_rows_kernel(const int32_t* __restrict__ rows, int32_t n_active, const void* __restrict__ X,
-                                                       int64_t ldx, void* __restrict__ Y, int64_t ldy, int32_t F) {
+                                                       int64_t ldx, int32_t n_add, void* __restrict__ Y, int64_t ldy, int32_t F,
+                                                       const void* __restrict__ H, int64_t ldh) {
     if (VEC) {
         constexpr int VE = LnVec<DT>::VE;
         const int vpr = F / VE;
@@ -388,9 +391,16 @@ __global__ __launch_bounds__(256) void add_rows_kernel(const int32_t* __restrict
             const int64_t v = rows ? (int64_t)rows[i] : i;
             float a[VE], b[VE];
             LnVec<DT>::load(Y, v * ldy + c0, a);
-            LnVec<DT>::load(X, v * ldx + c0, b);
+            if (i < n_add) {
+                LnVec<DT>::load(X, v * ldx + c0, b);
 #pragma unroll
-            for (int e = 0; e < VE; ++e) a[e] += b[e];
+                for (int e = 0; e < VE; ++e) a[e] += b[e];
+            }
+            if (H) {
+                LnVec<DT>::load(H, v * ldh + c0, b);
+#pragma unroll
+                for (int e = 0; e < VE; ++e) a[e] = b[e] > 0.f ? a[e] : 0.f;
+            }
             LnVec<DT>::store(Y, v * ldy + c0, a, VE);
         }
         return;
@@ -399,7 +409,12 @@ __global__ __launch_bounds__(256) void add_rows_kernel(const int32_t* __restrict
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     for (int64_t i = wave; i < n_active; i += n_waves) {
         const int64_t v = rows ? (int64_t)rows[i] : i;
-        for (int c = lane; c < F; c += 64) ln_store<DT>(Y, v * ldy + c, ln_load<DT>(Y, v * ldy + c) + ln_load<DT>(X, v * ldx + c));
+        for (int c = lane; c < F; c += 64) {
+            float a = ln_load<DT>(Y, v * ldy + c);
+            if (i < n_add) a += ln_load<DT>(X, v * ldx + c);
+            if (H && !(ln_load<DT>(H, v * ldh + c) > 0.f)) a = 0.f;
+            ln_store<DT>(Y, v * ldy + c, a);
+        }
     }
 }
 
@@ -496,24 +511,37 @@ extern "C" int32_t gnn_layer_norm_relu_bwd(const int32_t* rows, int32_t n_active
     return GNN_OK;
 }
 
-extern "C" int32_t gnn_add_rows(const int32_t* rows, int32_t n_active, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F,
-                                int32_t dtype, void* stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
+static int32_t add_rows_impl(const int32_t* rows, int32_t n_active, const void* X, int64_t ldx, int32_t n_add, void* Y, int64_t ldy,
+                             int32_t F, const void* H, int64_t ldh, int32_t dtype, hipStream_t stream) {
     GNN_REQUIRE(n_active >= 0 && F >= 0, GNN_ERR_INVALID_ARG, "negative size");
+    GNN_REQUIRE(n_add >= 0 && n_add <= n_active, GNN_ERR_INVALID_ARG, "n_add = %d outside [0, n_active = %d]", n_add, n_active);
     GNN_REQUIRE(dtype == GNN_F32 || dtype == GNN_BF16, GNN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
-    GNN_REQUIRE(ldx >= F && ldy >= F, GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
+    GNN_REQUIRE((n_add == 0 || ldx >= F) && ldy >= F && (H == nullptr || ldh >= F), GNN_ERR_SHAPE, "leading dimension smaller than F = %d", F);
     if (n_active == 0 || F == 0) return GNN_OK;
-    GNN_REQUIRE(X && Y, GNN_ERR_INVALID_ARG, "X or Y is NULL");
+    GNN_REQUIRE((X || n_add == 0) && Y, GNN_ERR_INVALID_ARG, "X or Y is NULL");
     const int es = dtype == GNN_F32 ? 4 : 2, ve = 16 / es;
-    const bool vec = ((uintptr_t)X % 16 == 0) && ((uintptr_t)Y % 16 == 0) && (ldx * es) % 16 == 0 && (ldy * es) % 16 == 0 && F % ve == 0;
+    const bool vec = (n_add == 0 || ((uintptr_t)X % 16 == 0 && (ldx * es) % 16 == 0)) && ((uintptr_t)Y % 16 == 0) && (ldy * es) % 16 == 0 &&
+                     (H == nullptr || ((uintptr_t)H % 16 == 0 && (ldh * es) % 16 == 0)) && F % ve == 0;
     const int grid = vec ? grid_for((int64_t)n_active * (F / ve), 256, 1 << 14) : grid_for((int64_t)n_active * 64, 256, 1 << 14);
     if (dtype == GNN_F32) {
-        if (vec) add_rows_kernel<GNN_F32, true><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, Y, ldy, F);
-        else add_rows_kernel<GNN_F32, false><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, Y, ldy, F);
+        if (vec) add_rows_kernel<GNN_F32, true><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, n_add, Y, ldy, F, H, ldh);
+        else add_rows_kernel<GNN_F32, false><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, n_add, Y, ldy, F, H, ldh);
     } else {
-        if (vec) add_rows_kernel<GNN_BF16, true><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, Y, ldy, F);
-        else add_rows_kernel<GNN_BF16, false><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, Y, ldy, F);
+        if (vec) add_rows_kernel<GNN_BF16, true><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, n_add, Y, ldy, F, H, ldh);
+        else add_rows_kernel<GNN_BF16, false><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, n_add, Y, ldy, F, H, ldh);
     }
     GNN_LAUNCH_CHECK("add_rows_kernel");
     return GNN_OK;
+}
+
+extern "C" int32_t gnn_add_rows(const int32_t* rows, int32_t n_active, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F,
+                                int32_t dtype, void* stream_) {
+    GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative size");
+    return add_rows_impl(rows, n_active, X, ldx, n_active, Y, ldy, F, nullptr, 0, dtype, (hipStream_t)stream_);
+}
+
+extern "C" int32_t gnn_add_rows_masked(const int32_t* rows, int32_t n_active, const void* X, int64_t ldx, int32_t n_add, void* Y,
+                                       int64_t ldy, int32_t F, const void* H, int64_t ldh, int32_t dtype, void* stream_) {
+    GNN_REQUIRE(H != nullptr || n_active == 0 || F == 0, GNN_ERR_INVALID_ARG, "H is NULL");
+    return add_rows_impl(rows, n_active, X, ldx, n_add, Y, ldy, F, H, ldh, dtype, (hipStream_t)stream_);
 }

@@ -789,7 +789,7 @@ static int32_t launch_stream(const SpmmArgs& a, int64_t avg_row, hipStream_t str
 
 template <int DT, int VE, int LPR, int NCH, bool FILTER>
 static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
-    constexpr int U = NCH == 1 ? (LPR < 64 ? GNN_SPMM_U_NARROW : GNN_SPMM_U_WIDE) : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
+    constexpr int U = NCH == 1 ? (LPR < 16 ? 4 : (LPR < 64 ? GNN_SPMM_U_NARROW : GNN_SPMM_U_WIDE)) : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
     constexpr int NG = 4 * (kWave / LPR);
     constexpr int W = LPR * NCH * VE;
     // chunk size: as large as possible (better balance inside a workgroup) while the launch still
@@ -1110,6 +1110,8 @@ static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
     const int F = a.F;
     // any alignment / leading dimension: element-wise lanes, 256 columns per workgroup
     if (!vec_ok) return launch_rows<DT, 1, 64, 4, FILTER>(a, stream);
+    // narrow outputs (class scores, a layer in the exchanged order): fewer lanes per row, more rows per wavefront
+    if (F <= 8 * VE) return launch_rows<DT, VE, 8, 1, FILTER>(a, stream);
     if (F <= 16 * VE) return launch_rows<DT, VE, 16, 1, FILTER>(a, stream);
     if (F <= 32 * VE) return launch_rows<DT, VE, 32, 1, FILTER>(a, stream);
     if (F <= 64 * VE) return launch_rows<DT, VE, 64, 1, FILTER>(a, stream);

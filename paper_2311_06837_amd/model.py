@@ -34,20 +34,22 @@ class MaskedGNN:
                      through gnn_layer_edge_mask(rule, layer = l) over its rows, forward and backward; rule
                      "threshold" (parameter = 64-bit key threshold) or "fanout" (parameter = neighbours kept per row).
                      The masks are rebuilt in every step (a training run changes the seed per epoch).
-    transform_first  the order of the first layer's two halves.  False: aggregate the input features, then multiply by
-                     the weights (the paper's order).  True: multiply first, P = H_0 W_neigh, then aggregate P on top
-                     of the self term (gnn_masked_spmm_fwd_add) - the same sum, gathered dims[1] instead of dims[0]
-                     columns wide; the backward pass then needs one aggregation of the layer's output gradient
-                     (dP, dims[1] wide) for dW_neigh = H_0^T dP.  "auto" (default): True for a GraphSAGE model
-                     whose first layer narrows its input (dims[0] > dims[1]).  Only the first layer: it needs no
-                     input gradient.
+    transform_first  the order of a layer's two halves.  The paper's order: aggregate the layer's input, then multiply by
+                     the weights.  Exchanged: multiply first, P = H_{l-1} W_neigh, then aggregate P on top of the self
+                     term (gnn_masked_spmm_fwd_add) - the same sum, gathered dims[l] instead of dims[l-1] columns wide;
+                     the backward pass aggregates the layer's output gradient (dP = Agg^T(dZ), dims[l] wide) and gets
+                     dW_neigh = H_{l-1}^T dP and the input gradient dP W_neigh^T + dZ W_self^T (two products, met in
+                     front of the previous ReLU by gnn_add_rows_masked).  True: every layer of a GraphSAGE model that
+                     narrows its input (dims[l-1] > dims[l]); "auto" (default): those of them whose input rows are at
+                     least 512 bytes long (shorter rows are gathered at a rate set by their number, not their bytes:
+                     narrowing them further buys nothing and the two extra products cost); False: none; or a
+                     collection of layer numbers.
     """
 
     def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, kind: str, params: list,
                  dtype=torch.float32, global_degree: torch.Tensor | None = None, prefix_numbered: bool = False,
                  layer_sampling=None, transform_first="auto"):
         assert kind in ("gcn", "sage")
-        assert transform_first in (True, False, "auto")
         self.layer_sampling = layer_sampling
         self.prefix_numbered, self._prefix_checked = prefix_numbered, False
         self.g, self.gt, self.targets, self.kind, self.dtype = graph, graph_t, targets, kind, dtype
@@ -64,18 +66,25 @@ class MaskedGNN:
         self.global_degree = global_degree
         self.ld = [row_stride(d, dtype) for d in self.dims]
         dev = targets.device
-        if transform_first == "auto":
-            transform_first = kind == "sage" and self.dims[0] > self.dims[1]
-        assert not transform_first or kind == "sage", "the exchanged order is built for the GraphSAGE layer only"
-        self.transform_first = bool(transform_first)
+        if transform_first is True or (isinstance(transform_first, str) and transform_first == "auto"):
+            es = 4 if dtype == torch.float32 else 2
+            min_bytes = 0 if transform_first is True else 512
+            self.tf_layers = frozenset(l for l in range(1, self.L + 1) if kind == "sage" and self.dims[l - 1] > self.dims[l]
+                                       and self.dims[l - 1] * es >= min_bytes)
+        elif transform_first is False:
+            self.tf_layers = frozenset()
+        else:
+            self.tf_layers = frozenset(int(l) for l in transform_first)
+            assert all(1 <= l <= self.L for l in self.tf_layers)
+        assert not self.tf_layers or kind == "sage", "the exchanged order is built for the GraphSAGE layer only"
         # activations A_l, H_l and their gradients; rows outside the active sets are never touched
-        self.A = [None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
-        if self.transform_first:
-            # no aggregate of the input features; instead the transformed rows P and the gradient that reaches them
-            self.A[1] = None
-            self.P = torch.zeros(self.n, self.ld[1], dtype=dtype, device=dev)
-            self.dP = torch.zeros(self.n, self.ld[1], dtype=dtype, device=dev)
-            self._dbias_unused = torch.zeros(self.dims[1], dtype=torch.float32, device=dev)
+        self.A = [None] + [None if l in self.tf_layers else torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev)
+                           for l in range(1, self.L + 1)]
+        # a layer in the exchanged order keeps no aggregate of its input; instead its transformed rows P_l and the
+        # gradient dP_l that reaches them
+        self.P = {l: torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in self.tf_layers}
+        self.dP = {l: torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in self.tf_layers}
+        self._dbias_unused = torch.zeros(max(self.dims), dtype=torch.float32, device=dev)
         self.H = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
         self.dH = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
         self.dA = [None, None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(2, self.L + 1)]
@@ -127,7 +136,7 @@ class MaskedGNN:
         for l in range(1, self.L + 1):
             nl = self.n_rows_of_layer(l)
             # layer 1 has no backward aggregation in the paper's order: its threshold pairs are not needed then
-            need_t = l > 1 or self.transform_first
+            need_t = l > 1 or l in self.tf_layers
             out = self._call(f"layer_mask_{l}", B.gnn_layer_edge_mask, self.g, self.rows, nl, rule, l, seed,
                              fanout=par if rule == "fanout" else 0, threshold=par if rule == "threshold" else (1 << 64) - 1,
                              with_thresholds=need_t)
@@ -145,9 +154,13 @@ class MaskedGNN:
         """|R_l|, R_l = {dist <= L - l}: a prefix of the ring-sorted ids."""
         return int(self.hop[self.L - l + 1])
 
+    @property
+    def transform_first(self) -> bool:
+        return bool(self.tf_layers)
+
     def agg_width(self, l: int) -> int:
         """Columns of the matrix that layer l's forward aggregation gathers."""
-        return self.dims[1] if (l == 1 and self.transform_first) else self.dims[l - 1]
+        return self.dims[l] if l in self.tf_layers else self.dims[l - 1]
 
     def set_input(self, H0: torch.Tensor):
         """H0: [n, row_stride(F0, dtype)] of the model dtype, row-major; used in place."""
@@ -161,14 +174,14 @@ class MaskedGNN:
             K = self.dims[l - 1]
             nl = self.n_rows_of_layer(l)
             g_l, rs_l = (self.g, self.rs) if self.layer_sampling is None else (self.g_l[l], self.rs_l[l])
-            if l == 1 and self.transform_first:
-                n0 = int(self.hop[self.L + 1])      # every vertex within L hops can be a neighbour of a row of R_1
-                self._call("linear_pre_1", B.gnn_linear_fwd, self.rows, n0, self.H[0], None, K, p["W_neigh"], None, None, self.P,
-                           relu=False, ws=self.ws)
-                self._call("linear_fwd_1", B.gnn_linear_fwd, self.rows, nl, self.H[0], None, K, p["W_self"], None, p["bias"], self.H[1],
-                           relu=False, ws=self.ws)
-                self._call("spmm_fwd_1", B.gnn_masked_spmm_fwd_add, g_l, self.rows, nl, self.P, self.H[1], self.dims[1], rs_l, self.cs,
-                           relu=(l < self.L), ws=self.ws)
+            if l in self.tf_layers:
+                n_prev = self.n_rows_of_layer(l - 1)    # every row of R_{l-1} can be a neighbour of a row of R_l
+                self._call(f"linear_pre_{l}", B.gnn_linear_fwd, self.rows, n_prev, self.H[l - 1], None, K, p["W_neigh"], None, None,
+                           self.P[l], relu=False, ws=self.ws)
+                self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.H[l - 1], None, K, p["W_self"], None, p["bias"],
+                           self.H[l], relu=False, ws=self.ws)
+                self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd_add, g_l, self.rows, nl, self.P[l], self.H[l], self.dims[l], rs_l,
+                           self.cs, relu=(l < self.L), ws=self.ws)
                 continue
             self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, g_l, self.rows, nl, self.H[l - 1], self.A[l], K, rs_l, self.cs, ws=self.ws)
             self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
@@ -186,8 +199,8 @@ class MaskedGNN:
             nl = self.n_rows_of_layer(l)
             sage = self.kind == "sage"
             need_in = l > 1
-            if l == 1 and self.transform_first:
-                self._backward_transform_first()
+            if l in self.tf_layers:
+                self._backward_transform_first(l)
                 continue
             # dH_l arrives with the ReLU of layer l already undone: the aggregation call that wrote it last masked it
             self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
@@ -225,19 +238,26 @@ class MaskedGNN:
             return None, n_fwd
         return self.dist, -1
 
-    def _backward_transform_first(self):
-        """First layer in the exchanged order, Z = rs * Agg(H_0 W_neigh) + H_0 W_self + b: the self half takes dZ as it
-        is, the neighbour half takes dP = Agg^T(rs * dZ) (one backward aggregation, dims[1] wide)."""
-        L, p, gr, K = self.L, self.params[0], self.grads[0], self.dims[0]
-        n1, n0 = self.n_rows_of_layer(1), int(self.hop[L + 1])
-        gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[1], self.rs_l[1])
-        dist_l, pre_l = self._source_filter(n1)
-        self._call("spmm_bwd_1", B.gnn_masked_spmm_bwd, gt_l, self.rows, n0, dist_l, L - 1, self.dH[1], self.dP, self.dims[1],
-                   rs_l, self.cs, accumulate=False, ws=self.ws if 4 * n1 >= self.n else None, src_prefix=pre_l)
-        self._call("linear_bwd_1", B.gnn_linear_bwd, self.rows, n1, self.dH[1], None, False, self.H[0], None, K, p["W_self"], None,
-                   gr["dW_self"], None, gr["dbias"], None, None, ws=self.ws)
-        self._call("linear_bwd_1_neigh", B.gnn_linear_bwd, self.rows, n0, self.dP, None, False, self.H[0], None, K, p["W_neigh"], None,
-                   gr["dW_neigh"], None, self._dbias_unused, None, None, ws=self.ws)
+    def _backward_transform_first(self, l: int):
+        """Layer l in the exchanged order, Z = rs * Agg(H_{l-1} W_neigh) + H_{l-1} W_self + b: the self half takes dZ as
+        it is, the neighbour half takes dP = Agg^T(rs * dZ) (one backward aggregation, dims[l] wide); the two input
+        gradients meet in front of the previous layer's ReLU."""
+        L, p, gr, K, N = self.L, self.params[l - 1], self.grads[l - 1], self.dims[l - 1], self.dims[l]
+        nl, n_prev = self.n_rows_of_layer(l), self.n_rows_of_layer(l - 1)
+        need_in = l > 1
+        gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[l], self.rs_l[l])
+        dist_l, pre_l = self._source_filter(nl)
+        self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dH[l], self.dP[l], N,
+                   rs_l, self.cs, accumulate=False, ws=self.ws if 4 * nl >= self.n else None, src_prefix=pre_l)
+        self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.H[l - 1], None, K, p["W_self"], None,
+                   gr["dW_self"], None, gr["dbias"], self.dH[l - 1] if need_in else None, None, ws=self.ws)
+        self._call(f"linear_bwd_{l}_neigh", B.gnn_linear_bwd, self.rows, n_prev, self.dP[l], None, False, self.H[l - 1], None, K,
+                   p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], self.dA[l] if need_in else None, None, ws=self.ws)
+        if need_in:
+            # dA_l holds dP W_neigh^T for R_{l-1}, dH_{l-1} holds dZ W_self^T for R_l: sum and mask into dA_l, which
+            # then IS the gradient of layer l-1's output (same shape: the two buffers trade places)
+            self._call(f"add_rows_{l}", B.gnn_add_rows_masked, self.rows, n_prev, self.dH[l - 1], nl, self.dA[l], K, self.H[l - 1])
+            self.dH[l - 1], self.dA[l] = self.dA[l], self.dH[l - 1]
 
     def step(self, labels: torch.Tensor):
         """One pass of the whole hot path: active sets, forward, loss, backward."""
@@ -250,8 +270,8 @@ class MaskedGNN:
 
     def aggregated_edges(self) -> dict:
         """Edges visited per layer by the forward and the backward aggregation of the paper's order (host-side
-        bookkeeping from row_ptr; used by the benchmark's edges/s metric).  The first layer's extra backward aggregation
-        under transform_first is NOT counted: the exchanged order must not raise the metric by doing more, narrower sums."""
+        bookkeeping from row_ptr; used by the benchmark's edges/s metric).  A first layer in the exchanged order aggregates
+        backward as well; that is NOT counted: the exchanged order must not raise the metric by doing more, narrower sums."""
         rp = self.g.row_ptr.long()
         ring = self.ring_ids.long()
         out = {}
@@ -333,10 +353,6 @@ class ResSAGEPlus:
 
     def n_rows_of_layer(self, l: int) -> int:
         return int(self.hop[self.L - l + 1])
-
-    def agg_width(self, l: int) -> int:
-        """Columns of the matrix that layer l's forward aggregation gathers."""
-        return self.dims[1] if (l == 1 and self.transform_first) else self.dims[l - 1]
 
     def set_input(self, H0: torch.Tensor):
         assert H0.dtype == self.dtype and H0.shape[0] == self.n and H0.stride(0) == self.ld[0]

@@ -105,7 +105,8 @@ def test_training_step_on_the_extracted_graph(kind, dtype):
     m = P.MaskedGNN(local, local, torch.arange(len(T), dtype=torch.int32, device="cuda"), kind,
                     [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
                     global_degree=dev(g.degrees()[l2g].astype(np.int32)) if kind == "gcn" else None,
-                    prefix_numbered=True)     # the extraction numbers by (distance, id): the calls get rows = NULL
+                    prefix_numbered=True,     # the extraction numbers by (distance, id): the calls get rows = NULL
+                    transform_first=kind == "sage")   # and the narrowing GraphSAGE layers run in the exchanged order
     m.set_input(H0d)
     loss = m.step(dev(y))
     torch.cuda.synchronize()
@@ -185,7 +186,8 @@ def test_training_step_after_sampling_and_extraction():
     H0d = torch.zeros(n_local, P.row_stride(dims[0], dtype), dtype=dtype, device="cuda")
     P.gnn_gather_rows(dev(H0g).to(dtype), l2g_d, dims[0], H0d)
     m = P.MaskedGNN(local, local, torch.arange(len(T), dtype=torch.int32, device="cuda"), "sage",
-                    [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype, prefix_numbered=True)
+                    [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype, prefix_numbered=True,
+                    transform_first=True)
     m.set_input(H0d)
     loss = m.step(dev(y))
     torch.cuda.synchronize()

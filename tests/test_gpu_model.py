@@ -41,7 +41,8 @@ def _parity(name, part, kind, dims, dtype, seed, transform_first="auto"):
 
     m = _gpu_model(part, kind, params, dtype, transform_first)
     if transform_first != "auto":
-        assert m.transform_first == transform_first
+        narrowing = {l for l in range(1, len(dims)) if dims[l - 1] > dims[l]}
+        assert m.tf_layers == (narrowing if transform_first else set())
     hop = m.build_active_sets()
     assert list(hop) == list(om.hop_offsets)
     assert np.array_equal(m.dist.cpu().numpy(), om.dist)
@@ -79,10 +80,11 @@ def test_cfg1_scaled(transform_first):
     _parity("cfg1@0.02", w.partition, w.model, w.dims, torch.float32, 1, transform_first)
 
 
-@pytest.mark.parametrize("dims", [[96, 64, 64, 7], [40, 12]])
+@pytest.mark.parametrize("dims", [[96, 64, 64, 7], [40, 12], [64, 48, 32, 16, 5], [16, 32, 8]])
 def test_transform_first_bf16_and_single_layer(dims):
-    """The exchanged first layer in bf16 storage, and as the only layer (its output is the logits: no ReLU, the
-    gradient comes straight from the loss)."""
+    """Layers in the exchanged order in both storage types: first and last layer with a plain one between, the only
+    layer (its output is the logits: no ReLU, the gradient comes straight from the loss), every layer (their input
+    gradients hand over masked from one to the next), only the last."""
     g = gg.chung_lu(5000, 9.0, 2.2, 61)
     T = np.sort(np.random.default_rng(61).choice(5000, 300, replace=False)).astype(np.int64)
     part = gg.halo_partition(g, T, len(dims) - 1)
@@ -123,7 +125,7 @@ def test_directed_graph_uses_the_transpose():
     part = gg.halo_partition(g, T, 3, symmetric=False)
     assert part.graph_t is not part.graph
     _parity("directed", part, "sage", [32, 24, 16, 5], torch.float32, 41, False)
-    _parity("directed", part, "sage", [32, 24, 16, 5], torch.float32, 41, True)    # layer 1 aggregates backward too
+    _parity("directed", part, "sage", [32, 24, 16, 5], torch.float32, 41, True)    # every layer aggregates backward through gT
 
 
 def test_masked_equals_unmasked_on_targets_on_the_gpu():
@@ -150,3 +152,34 @@ def test_masked_equals_unmasked_on_targets_on_the_gpu():
     t = dev(part.targets).long()
     a, b = masked.H[-1][t][:, : w.dims[-1]], full.H[-1][t][:, : w.dims[-1]]
     assert torch.allclose(a, b, rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("F,ld", [(256, 256), (100, 104), (41, 44), (7, 7)])
+def test_add_rows_masked(dtype, F, ld):
+    """gnn_add_rows_masked: the two input gradients of a layer in the exchanged order meet in front of a ReLU.
+    Elementwise, so the expected values are the definition written out (one rounding of the sum in storage precision)."""
+    import paper_2311_06837_amd as P
+    SENT = 777.0
+    rng = np.random.default_rng(F)
+    n = 2000
+    rows = rng.permutation(n)[:1234].astype(np.int32)
+    n_add = 400
+    X, Y = as_stored(rng.standard_normal((n, F)), dtype), as_stored(rng.standard_normal((n, F)), dtype)
+    H = as_stored(np.maximum(rng.standard_normal((n, F)), 0), dtype)
+    for rws, n_act, n_a in ((rows, len(rows), n_add), (None, 1500, 1500), (rows, len(rows), 0)):
+        print(f"add_rows_masked: F={F} ld={ld} {dtype} rows={'list' if rws is not None else 'prefix'} n={n_act} n_add={n_a}", flush=True)
+        Yd = padded(Y, ld, dtype, fill=SENT)
+        Xd = padded(X, ld, dtype, fill=float("nan")) if n_a else None
+        P.gnn_add_rows_masked(dev(rws) if rws is not None else None, n_act, Xd, n_a, Yd, F, padded(H, ld, dtype, fill=float("nan")))
+        torch.cuda.synchronize()
+        sel = rws if rws is not None else np.arange(n_act)
+        want = Y.copy()
+        t = Y[sel].copy()
+        t[:n_a] += X[sel[:n_a]]
+        want[sel] = as_stored(t, dtype) * (H[sel] > 0)
+        got = host64(Yd)
+        assert np.array_equal(got[:, :F], want)
+        assert (got[:, F:] == host64(torch.tensor(SENT, dtype=dtype))).all()
+    with pytest.raises(P.GnnError):
+        P.gnn_add_rows_masked(None, 10, padded(X, ld, dtype), 11, padded(Y, ld, dtype), F, padded(H, ld, dtype))

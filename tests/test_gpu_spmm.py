@@ -95,11 +95,13 @@ def test_fwd_add_on_top_of_the_self_term(dtype, relu):
     _fwd_add_case(g, 256, 256, dtype, None, relu, 51)
     _fwd_add_case(g, 100, 104, dtype, rows, relu, 52)
     _fwd_add_case(g, 7, 7, dtype, rows, relu, 53)            # element-wise lanes
+    _fwd_add_case(g, 16, 16, dtype, rows, relu, 54)          # narrow rows
+    _fwd_add_case(g, 41, 48, dtype, None, relu, 55)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("F,ld", [(64, 64), (100, 100), (128, 128), (256, 256), (602, 608), (602, 602), (7, 7), (1, 8),
-                                  (300, 304), (1000, 1000)])
+                                  (300, 304), (1000, 1000), (16, 16), (32, 32), (41, 44), (47, 48)])
 def test_fwd_widths(dtype, F, ld):
     g = gg.chung_lu(3000, 20.0, 2.1, 11)
     rng = np.random.default_rng(F)
@@ -188,6 +190,8 @@ def test_bwd_directed_graph_with_filter(dtype, accumulate):
     _bwd_case(g, 128, 128, dtype, 3, 3, accumulate, 5)
     _bwd_case(g, 256, 256, dtype, 3, 2, accumulate, 6)
     _bwd_case(g, 602, 608, dtype, 2, 2, accumulate, 7)
+    _bwd_case(g, 16, 16, dtype, 3, 2, accumulate, 8)                     # narrow rows: 4 / 8 lanes per row
+    _bwd_case(g, 41, 48, dtype, 3, 3, accumulate, 9)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -207,6 +211,8 @@ def test_bwd_power_law_hubs(dtype):
     g = gg.chung_lu(12000, 150.0, 2.1, 12)
     _bwd_case(g, 64, 64, dtype, 2, 2, False, 8)
     _bwd_case(g, 100, 100, dtype, 3, 2, True, 9)
+    _bwd_case(g, 16, 16, dtype, 2, 2, True, 10, relu=True)               # hub rows reduced by 64 narrow lane groups
+    _bwd_case(g, 32, 32, dtype, 2, 2, False, 11)
 
 
 def test_empty_calls_are_noops():
@@ -373,6 +379,7 @@ def test_bwd_source_prefix(dtype, sorted_promise):
     h = gg.chung_lu(12000, 150.0, 2.1, 12)                                             # hub rows, cut inside the hub
     assert h.degrees().max() > 1200                                                    # (hub rows: longer than 1024)
     _prefix_case(h, 11000, 64, dtype, 38, sorted_promise, relu=True)                   # still hubs after the cut
+    _prefix_case(h, 11000, 16, dtype, 40, sorted_promise)
     _prefix_case(h, 6000, 64, dtype, 39, sorted_promise)                               # hubs that stop being hubs after the cut
 
 
