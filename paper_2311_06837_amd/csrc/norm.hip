@@ -382,26 +382,32 @@ __global__ __launch_bounds__(256) void add_rows_kernel(const int32_t* __restrict
                                                        int64_t ldx, int32_t n_add, void* __restrict__ Y, int64_t ldy, int32_t F,
                                                        const void* __restrict__ H, int64_t ldh) {
     if (VEC) {
+        // a thread keeps its column vector and walks down the rows: the workgroup covers `rb` rows x `vpr` vectors at a
+        // time (or, for rows of more than 256 vectors, one row in several sweeps) - no division inside the loop
         constexpr int VE = LnVec<DT>::VE;
         const int vpr = F / VE;
-        const int64_t total = (int64_t)n_active * vpr;
-        for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
-            const int64_t i = t / vpr;
-            const int c0 = (int)(t % vpr) * VE;
+        const int rb = vpr < 256 ? 256 / vpr : 1;
+        const int r0 = vpr < 256 ? (int)threadIdx.x / vpr : 0;
+        const int cstart = vpr < 256 ? (int)threadIdx.x % vpr : (int)threadIdx.x;
+        if (r0 >= rb) return;
+        for (int64_t i = (int64_t)blockIdx.x * rb + r0; i < n_active; i += (int64_t)gridDim.x * rb) {
             const int64_t v = rows ? (int64_t)rows[i] : i;
-            float a[VE], b[VE];
-            LnVec<DT>::load(Y, v * ldy + c0, a);
-            if (i < n_add) {
-                LnVec<DT>::load(X, v * ldx + c0, b);
+            for (int cv = cstart; cv < vpr; cv += 256) {
+                const int c0 = cv * VE;
+                float a[VE], b[VE];
+                LnVec<DT>::load(Y, v * ldy + c0, a);
+                if (i < n_add) {
+                    LnVec<DT>::load(X, v * ldx + c0, b);
 #pragma unroll
-                for (int e = 0; e < VE; ++e) a[e] += b[e];
-            }
-            if (H) {
-                LnVec<DT>::load(H, v * ldh + c0, b);
+                    for (int e = 0; e < VE; ++e) a[e] += b[e];
+                }
+                if (H) {
+                    LnVec<DT>::load(H, v * ldh + c0, b);
 #pragma unroll
-                for (int e = 0; e < VE; ++e) a[e] = b[e] > 0.f ? a[e] : 0.f;
+                    for (int e = 0; e < VE; ++e) a[e] = b[e] > 0.f ? a[e] : 0.f;
+                }
+                LnVec<DT>::store(Y, v * ldy + c0, a, VE);
             }
-            LnVec<DT>::store(Y, v * ldy + c0, a, VE);
         }
         return;
     }
@@ -522,7 +528,8 @@ static int32_t add_rows_impl(const int32_t* rows, int32_t n_active, const void* 
     const int es = dtype == GNN_F32 ? 4 : 2, ve = 16 / es;
     const bool vec = (n_add == 0 || ((uintptr_t)X % 16 == 0 && (ldx * es) % 16 == 0)) && ((uintptr_t)Y % 16 == 0) && (ldy * es) % 16 == 0 &&
                      (H == nullptr || ((uintptr_t)H % 16 == 0 && (ldh * es) % 16 == 0)) && F % ve == 0;
-    const int grid = vec ? grid_for((int64_t)n_active * (F / ve), 256, 1 << 14) : grid_for((int64_t)n_active * 64, 256, 1 << 14);
+    const int vpr = F / ve, rb = (vec && vpr < 256) ? 256 / vpr : 1;       // rows one workgroup covers per sweep (vector route)
+    const int grid = vec ? grid_for(((int64_t)n_active + rb - 1) / rb * 256, 256, 1 << 14) : grid_for((int64_t)n_active * 64, 256, 1 << 14);
     if (dtype == GNN_F32) {
         if (vec) add_rows_kernel<GNN_F32, true><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, n_add, Y, ldy, F, H, ldh);
         else add_rows_kernel<GNN_F32, false><<<grid, 256, 0, stream>>>(rows, n_active, X, ldx, n_add, Y, ldy, F, H, ldh);
