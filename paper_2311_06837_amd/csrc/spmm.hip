@@ -491,9 +491,9 @@ __global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_k
 // its pieces in LDS ("carry" slots: at most a head piece and a tail piece per group), and after a barrier the
 // pieces are added in stream order and stored.  So power-law rows cost no imbalance inside the workgroup,
 // tiles are always full, and the result is a fixed-order sum (bit-reproducible).
-//   PART (column-blocked route): the workgroup id carries (chunk, die) = (id / 8, id % 8); every row is cut to
-//   the die's column block through `seg`, and the unscaled float sums go to plane `die` of the partial buffer
-//   (a.Y, row index = position in the row list) instead of the output matrix.
+// It serves the column-blocked route: the workgroup id carries (chunk, die) = (id / 8, id % 8); every row is cut to
+// the die's column block through `seg`, and the unscaled float sums go to plane `die` of the partial buffer
+// (a.Y, row index = position in the row list), not to the output matrix.
 constexpr int kStreamMaxRows = 256;
 #ifndef GNN_SPMM_STREAM_U
 #define GNN_SPMM_STREAM_U 4        // row loads in flight per lane when a lane owns one 16-byte chunk of the row
@@ -506,14 +506,13 @@ constexpr int kStreamMaxRows = 256;
 #define GNN_SPMM_WG_EDGES 8192     // edges one workgroup aims for when the host picks its row count
 #endif
 
-template <int DT, int VE, int LPR, int NCH, int U, bool PART, bool SCALED>
+template <int DT, int VE, int LPR, int NCH, int U, bool SCALED>
 __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm_stream_kernel(SpmmArgs a) {
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
     constexpr int NG = 4 * RPW;
     constexpr int W = LPR * NCH * VE;  // feature columns per workgroup (grid.y blocks cover F)
     __shared__ int32_t s_start[kStreamMaxRows], s_voff[kStreamMaxRows + 1], s_v[kStreamMaxRows];
-    __shared__ float s_sc[kStreamMaxRows];
     __shared__ int32_t s_u_all[4][kWave], s_r_all[4][kWave];   // neighbour id and row slot of every staged edge
     __shared__ float s_w_all[4][kWave];                        // its scale factor (only with a neighbour scale)
     __shared__ float s_carry[NG * 2][W];
@@ -528,28 +527,18 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
 
     // ---- phase 0: row descriptors and the exclusive prefix of the row lengths
     const int rpw = a.rows_per_group;  // rows of the list per workgroup, <= kStreamMaxRows
-    const int die = PART ? (int)(blockIdx.x % kDies) : 0;
-    const int64_t chunk0 = (int64_t)(PART ? blockIdx.x / kDies : blockIdx.x) * rpw;
+    const int die = (int)(blockIdx.x % kDies);
+    const int64_t chunk0 = (int64_t)(blockIdx.x / kDies) * rpw;
     const int n_chunk = (int)(((int64_t)a.n_active - chunk0) < rpw ? ((int64_t)a.n_active - chunk0) : rpw);
-    float* const part = PART ? (float*)a.Y + (int64_t)die * a.n_active * a.ldy : nullptr;
+    float* const part = (float*)a.Y + (int64_t)die * a.n_active * a.ldy;
     int len = 0;
     if (tid < n_chunk) {
-        int32_t v, s, e;
-        float sc = 1.f;
-        if (PART) {
-            v = (int32_t)(chunk0 + tid);
-            const int32_t* cut = a.seg + (int64_t)v * (a.n_blocks + 1) + a.block0 + die;
-            s = cut[0];
-            e = a.seg_end ? a.seg_end[(int64_t)v * a.n_blocks + a.block0 + die] : cut[1];
-        } else {
-            v = a.rows ? a.rows[chunk0 + tid] : (int32_t)(chunk0 + tid);
-            s = a.row_ptr[v];
-            e = a.row_ptr[v + 1];
-            if (a.out_scale) sc = a.out_scale[v];
-        }
+        const int32_t v = (int32_t)(chunk0 + tid);
+        const int32_t* cut = a.seg + (int64_t)v * (a.n_blocks + 1) + a.block0 + die;
+        const int32_t s = cut[0];
+        const int32_t e = a.seg_end ? a.seg_end[(int64_t)v * a.n_blocks + a.block0 + die] : cut[1];
         s_v[tid] = v;
         s_start[tid] = s;
-        s_sc[tid] = sc;
         len = e - s;
     }
     if (tid < NG * 2) s_ctag[tid] = -1;
@@ -608,17 +597,12 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
         const int b0 = s_voff[cur], b1 = s_voff[cur + 1];
         if (b0 >= lo && b1 <= hi) {  // the whole row lies in this stretch
             const int32_t v = s_v[cur];
-            const float sc = s_sc[cur];
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 if (col_ok[c]) {
-                    float o[VE];
-#pragma unroll
-                    for (int k = 0; k < VE; ++k) o[k] = acc[c][k] * sc;
                     const int64_t rest = (int64_t)a.F - col_off[c];
                     const int n_valid = rest >= VE ? VE : (int)rest;
-                    if (PART) store_part<VE>(part, (int64_t)v * a.ldy + col_off[c], o, n_valid, a.accumulate != 0);
-                    else E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, n_valid, a.accumulate != 0, a.relu_h, (int64_t)v * a.ldh + col_off[c]);
+                    store_part<VE>(part, (int64_t)v * a.ldy + col_off[c], acc[c], n_valid, a.accumulate != 0);
                 }
             }
         } else {  // a piece: head (the row began in an earlier stretch) or tail (it goes on in the next one)
@@ -737,10 +721,9 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
             if (tq == -1) continue;
             if (tq != tag) {
                 if (tag >= 0) {
-                    float o[1] = {sum * s_sc[tag]};
+                    float o[1] = {sum};
                     const int64_t off = (int64_t)s_v[tag] * a.ldy + gcol;
-                    if (PART) store_part<1>(part, off, o, 1, a.accumulate != 0);
-                    else Elem<DT, 1>::store(a.Y, off, o, 1, a.accumulate != 0);
+                    store_part<1>(part, off, o, 1, a.accumulate != 0);
                 }
                 tag = tq;
                 sum = 0.f;
@@ -761,28 +744,27 @@ __global__ __launch_bounds__(256, NCH == 1 ? GNN_SPMM_STREAM_MINB : 4) void spmm
                     for (int k = 0; k < VE; ++k) o[k] = 0.f;
                     const int64_t rest = (int64_t)a.F - col_off[c];
                     const int n_valid = rest >= VE ? VE : (int)rest;
-                    if (PART) store_part<VE>(part, (int64_t)v * a.ldy + col_off[c], o, n_valid, false);
-                    else E::store(a.Y, (int64_t)v * a.ldy + col_off[c], o, n_valid, false);
+                    store_part<VE>(part, (int64_t)v * a.ldy + col_off[c], o, n_valid, false);
                 }
             }
         }
     }
 }
 
-template <int DT, int VE, int LPR, int NCH, bool PART>
+template <int DT, int VE, int LPR, int NCH>
 static int32_t launch_stream(const SpmmArgs& a, int64_t avg_row, hipStream_t stream) {
     constexpr int U = NCH == 1 ? GNN_SPMM_STREAM_U : (NCH == 2 ? 4 : (NCH == 3 ? 3 : 2));
     constexpr int W = LPR * NCH * VE;
     // rows per workgroup: about GNN_SPMM_WG_EDGES edges, while the launch keeps a few thousand workgroups
     SpmmArgs b = a;
     int64_t rows = (int64_t)GNN_SPMM_WG_EDGES / (avg_row < 1 ? 1 : avg_row);
-    const int64_t cap = (int64_t)a.n_active * (PART ? kDies : 1) / 4096;
+    const int64_t cap = (int64_t)a.n_active * kDies / 4096;
     if (rows > cap) rows = cap;
     b.rows_per_group = (int32_t)(rows < 16 ? 16 : (rows > kStreamMaxRows ? kStreamMaxRows : rows));
     const int64_t n_chunks = ((int64_t)a.n_active + b.rows_per_group - 1) / b.rows_per_group;
-    dim3 grid((unsigned)(n_chunks * (PART ? kDies : 1)), (unsigned)((a.F + W - 1) / W));
-    if (a.edge_w) spmm_stream_kernel<DT, VE, LPR, NCH, U, PART, true><<<grid, 256, 0, stream>>>(b);
-    else spmm_stream_kernel<DT, VE, LPR, NCH, U, PART, false><<<grid, 256, 0, stream>>>(b);
+    dim3 grid((unsigned)(n_chunks * kDies), (unsigned)((a.F + W - 1) / W));
+    if (a.edge_w) spmm_stream_kernel<DT, VE, LPR, NCH, U, true><<<grid, 256, 0, stream>>>(b);
+    else spmm_stream_kernel<DT, VE, LPR, NCH, U, false><<<grid, 256, 0, stream>>>(b);
     GNN_LAUNCH_CHECK("spmm_stream_kernel");
     return GNN_OK;
 }
@@ -1096,7 +1078,7 @@ static int32_t run_blocked(const SpmmArgs& a, const BlockedPlan& p, void* ws, hi
     for (int pass = 0; pass < p.passes; ++pass) {
         b.block0 = pass * kDies;
         b.accumulate = pass > 0;
-        GNN_CHECK((launch_stream<DT, VE, 16, 1, true>(b, p.avg_seg, stream)));
+        GNN_CHECK((launch_stream<DT, VE, 16, 1>(b, p.avg_seg, stream)));
     }
     spmm_sum_parts_kernel<DT><<<grid_for((int64_t)a.n_active * ((a.F + 3) / 4), 256, 1 << 16), 256, 0, stream>>>(
         part, p.ldp, a.rows, a.n_active, a.F, a.Y, a.ldy, a.out_scale, a.accumulate, a.relu_h, a.ldh);
