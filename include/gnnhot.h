@@ -134,13 +134,15 @@ int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_act
  * product exchanged: sum_u (x_u W) instead of (sum_u x_u) W, the cheaper order when the layer narrows its input):
  *     Y[v, 0:F] = act( Y[v, 0:F] + row_scale[v] * sum_{u in row(v)} col_scale[u] * X[u, 0:F] )     for v in rows
  *   X     the already transformed rows (x_u W_neigh), Y on entry the self term (x_v W_self + bias) of the same rows
+ *   bias  float [F] or NULL.  Non-NULL: the layer has no self term (GCN); what Y holds on entry is ignored and the
+ *         listed rows start from bias instead
  *   relu  1: act = max(., 0), 0: identity
  * Everything else (row list, scales, determinism, workspace, errors) as in gnn_masked_spmm_fwd; a row without
  * entries still gets its activation.
  */
 int32_t gnn_masked_spmm_fwd_add(const gnn_csr *g, const int32_t *rows, int32_t n_active,
                                 const void *X, int64_t ldx, void *Y, int64_t ldy, int32_t F, int32_t dtype,
-                                const float *row_scale, const float *col_scale, int32_t relu,
+                                const float *row_scale, const float *col_scale, const float *bias, int32_t relu,
                                 void *ws, size_t *ws_bytes, void *stream);
 
 /*
@@ -202,6 +204,14 @@ int32_t gnn_linear_bwd(const int32_t *rows, int32_t n_active,
                        float *dW_neigh, float *dW_self, float *dbias,
                        void *dA_neigh, void *dX_self, int64_t ld_din, int32_t dtype,
                        void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Bias gradient alone: dbias[0:N] = sum over the listed rows of dZ[v, 0:N] (fixed order, no atomics) - for a layer in
+ * the exchanged order without a self term, whose gnn_linear_bwd call runs on another matrix (dP) than dZ.
+ * Workspace: (ws, ws_bytes) size-query protocol.  N <= 4096.
+ */
+int32_t gnn_bias_grad(const int32_t *rows, int32_t n_active, const void *dZ, int64_t lddz, int32_t N, int32_t dtype,
+                      float *dbias, void *ws, size_t *ws_bytes, void *stream);
 
 /*
  * Node-classification loss on the targets (section 8.1): mean softmax cross-entropy.

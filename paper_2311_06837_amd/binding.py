@@ -25,7 +25,7 @@ EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_s
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
            "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
-           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked"]
+           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked", "gnn_bias_grad"]
 
 
 class GnnError(RuntimeError):
@@ -255,14 +255,15 @@ def gnn_masked_spmm_fwd(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch
 
 
 def gnn_masked_spmm_fwd_add(g: Graph, rows, n_active: int, X: torch.Tensor, Y: torch.Tensor, F: int,
-                            row_scale=None, col_scale=None, relu: bool = False, ws: Workspace | None = None):
-    """Y[rows] = act(Y[rows] + aggregation of X): the transform-before-aggregate order of a layer."""
+                            row_scale=None, col_scale=None, relu: bool = False, ws: Workspace | None = None, bias=None):
+    """Y[rows] = act(Y[rows] + aggregation of X): the transform-before-aggregate order of a layer.  bias (float [F]):
+    no self term - the rows start from bias instead of what Y holds."""
     _mat(X, "X"), _mat(Y, "Y")
     assert X.dtype == Y.dtype and X.shape[0] >= g.n_cols and Y.shape[0] >= g.n_rows
     assert rows is None or rows.numel() >= n_active
     _with_optional_ws(lib().gnn_masked_spmm_fwd_add, (
         C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), _ptr(Y),
-        C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale),
+        C.c_int64(Y.stride(0)), C.c_int32(F), C.c_int32(_dtype_code(X)), _ptr(row_scale), _ptr(col_scale), _ptr(bias),
         C.c_int32(1 if relu else 0)), (_stream(),), ws)
 
 
@@ -485,3 +486,12 @@ def gnn_add_rows_masked(rows, n_active: int, X, n_add: int, Y: torch.Tensor, F: 
     _check(lib().gnn_add_rows_masked(_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0) if X is not None else 0),
                                      C.c_int32(n_add), _ptr(Y), C.c_int64(Y.stride(0)), C.c_int32(F), _ptr(H), C.c_int64(H.stride(0)),
                                      C.c_int32(_dtype_code(Y)), _stream()))
+
+
+def gnn_bias_grad(rows, n_active: int, dZ: torch.Tensor, N: int, dbias: torch.Tensor, ws: Workspace | None = None):
+    """dbias[:N] = sum of dZ[rows, :N]."""
+    _mat(dZ, "dZ")
+    assert dbias.dtype == torch.float32 and dbias.numel() >= N and dbias.is_contiguous()
+    assert rows is None or rows.numel() >= n_active
+    _with_ws(lib().gnn_bias_grad, (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(dZ), C.c_int64(dZ.stride(0)), C.c_int32(N),
+                                   C.c_int32(_dtype_code(dZ)), _ptr(dbias)), (_stream(),), ws)

@@ -918,7 +918,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const void* __restrict__
 }
 
 // dZ[i][0:N] = relu ? dH[row(i)] * [H[row(i)] > 0] : dH[row(i)], rows compacted (pad columns of dZ
-// are written as zero); column sums of each block of kDzRows rows go to part[block][0:N].
+// are written as zero; dZ == NULL: nothing is stored); column sums of each block of kDzRows rows go to part[block][0:N].
 // Threads: cx 16-byte column vectors x 256/cx row lanes.
 constexpr int kDzRows = 1024;
 
@@ -970,6 +970,7 @@ __global__ __launch_bounds__(256) void dz_kernel(const int32_t* __restrict__ row
                     }
                     o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
                 }
+                if (dZ == nullptr) continue;          // only the column sums are wanted
                 if (DT == GNN_F32) *(uint4*)((float*)dZ + m * ldz + n0) = o;
                 else *(uint4*)((uint16_t*)dZ + m * ldz + n0) = o;
             }
@@ -986,6 +987,17 @@ __global__ __launch_bounds__(256) void dz_kernel(const int32_t* __restrict__ row
             }
         }
         __syncthreads();
+    }
+}
+
+// Wp[k][0:ldp] = W[k][0:N] followed by zeros: rows of an unaligned width become 16-byte aligned.
+template <int DT>
+__global__ __launch_bounds__(256) void pad_rows_kernel(const void* __restrict__ W, int32_t K, int32_t N, void* __restrict__ Wp, int32_t ldp) {
+    const int64_t total = (int64_t)K * ldp;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t k = (int32_t)(t / ldp), c = (int32_t)(t % ldp);
+        if (DT == GNN_F32) ((float*)Wp)[t] = c < N ? ((const float*)W)[(int64_t)k * N + c] : 0.f;
+        else ((uint16_t*)Wp)[t] = c < N ? ((const uint16_t*)W)[(int64_t)k * N + c] : (uint16_t)0;
     }
 }
 
@@ -1037,7 +1049,7 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
                                const void* A, const void* Xs, int64_t ld_in, int32_t K, const void* Wn, const void* Ws, int32_t N,
                                float* dWn, float* dWs, float* dbias, void* dA, void* dXs, int64_t ld_din, void* dZ, int64_t ldz,
                                float* part, int32_t n_part, float* P, float* Pb, int32_t splits, int32_t rows_per_split,
-                               hipStream_t stream) {
+                               void* Wpad0, void* Wpad1, int32_t ldwp, hipStream_t stream) {
     constexpr int ES = DTy<DT>::ES;
     // Without an activation to undo and without a row list, dH IS the compact dZ: no copy is made, the products read
     // dH in place and the weight-gradient kernel adds up the bias gradient on its way.
@@ -1063,7 +1075,11 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
     t.M = M; t.N = N; t.K = K; t.rows_per_split = rows_per_split; t.n_splits = splits; t.P = P;
     t.Pb = in_place ? Pb : nullptr;
     const int ko_tiles = (K + 127) / 128;
-    if (N > 32) {
+    if (N > 32 && N <= 64) {      // class-score widths (41, 47): a 128-column tile would be two thirds padding
+        const int64_t total = (int64_t)t.n_src * ko_tiles * splits;
+        if (t.a_vec && t.d_vec) gemm_tn_kernel<DT, 64, true><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
+        else gemm_tn_kernel<DT, 64, false><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
+    } else if (N > 32) {
         const int64_t total = (int64_t)t.n_src * ko_tiles * ((N + 127) / 128) * splits;
         if (t.a_vec && t.d_vec) gemm_tn_kernel<DT, 128, true><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
         else gemm_tn_kernel<DT, 128, false><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
@@ -1086,9 +1102,18 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
         void* out = which == 0 ? dA : dXs;
         const void* W = which == 0 ? Wn : Ws;
         if (!out) continue;
+        int64_t ldw = N;
+        void* Wpad = which == 0 ? Wpad0 : Wpad1;
+        if (Wpad != nullptr) {
+            // rows of N elements are not 16-byte aligned (41 or 47 classes): the product reads a padded copy with vector loads
+            pad_rows_kernel<DT><<<grid_for((int64_t)K * ldwp, 256, 1024), 256, 0, stream>>>(W, K, N, Wpad, ldwp);
+            GNN_LAUNCH_CHECK("pad_rows_kernel");
+            W = Wpad;
+            ldw = ldwp;
+        }
         GemmNT g;
         g.A[0] = dZ; g.A[1] = nullptr; g.Bt[0] = W; g.Bt[1] = nullptr; g.n_src = 1;
-        g.lda = ldz; g.ldb = N; g.a_vec = vec_ok(dZ, ldz, ES); g.b_vec = vec_ok(W, N, ES);
+        g.lda = ldz; g.ldb = ldw; g.a_vec = vec_ok(dZ, ldz, ES); g.b_vec = vec_ok(W, ldw, ES);
         g.a_rows = nullptr; g.c_rows = rows; g.M = M; g.N = K; g.K = N;
         g.bias = nullptr; g.relu = 0; g.C = out; g.ldc = ld_din; g.c_vec = vec_ok(out, ld_din, ES);
         GNN_CHECK(launch_gemm_nt<DT>(g, stream));
@@ -1167,6 +1192,12 @@ extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const v
     float* part = carve.take<float>((size_t)n_part * N);
     float* P = carve.take<float>((size_t)splits * n_src * K * N);
     float* Pb = carve.take<float>((size_t)splits * N);
+    // padded copies of the weights for the input-gradient products when a weight row is not a whole number of 16-byte vectors
+    const bool pad_w = ((int64_t)N * es) % 16 != 0;
+    const int32_t ldwp = (int32_t)ldz;
+    char* Wpad0 = carve.take<char>(pad_w ? (size_t)K * ldwp * es : 0);
+    char* Wpad1 = carve.take<char>(pad_w ? (size_t)K * ldwp * es : 0);
+    if (!pad_w || ws == nullptr) Wpad0 = Wpad1 = nullptr;
     bool query;
     GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
     if (query) return GNN_OK;
@@ -1183,8 +1214,41 @@ extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const v
     if (dtype == GNN_F32)
         return linear_bwd_impl<GNN_F32>(rows, n_active, dH_out, H_out, ld_out, relu, A_neigh, X_self, ld_in, K, W_neigh, W_self, N,
                                         dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, Pb, splits,
-                                        rows_per_split, stream);
+                                        rows_per_split, Wpad0, Wpad1, ldwp, stream);
     return linear_bwd_impl<GNN_BF16>(rows, n_active, dH_out, H_out, ld_out, relu, A_neigh, X_self, ld_in, K, W_neigh, W_self, N,
                                      dW_neigh, dW_self, dbias, dA_neigh, dX_self, ld_din, dZ, ldz, part, n_part, P, Pb, splits,
-                                     rows_per_split, stream);
+                                     rows_per_split, Wpad0, Wpad1, ldwp, stream);
+}
+
+extern "C" int32_t gnn_bias_grad(const int32_t* rows, int32_t n_active, const void* dZ, int64_t ldz, int32_t N, int32_t dtype,
+                                 float* dbias, void* ws, size_t* ws_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative row count");
+    GNN_REQUIRE(dtype == GNN_F32 || dtype == GNN_BF16, GNN_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    GNN_REQUIRE(N >= 1 && N <= 4096, GNN_ERR_UNSUPPORTED, "N = %d out of range [1, 4096]", N);
+    GNN_REQUIRE(ldz >= N, GNN_ERR_SHAPE, "leading dimension smaller than N = %d", N);
+    const int32_t n_part = n_active > 0 ? (n_active + kDzRows - 1) / kDzRows : 1;
+    WsCarver carve(ws);
+    float* part = carve.take<float>((size_t)n_part * N);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+    GNN_REQUIRE(dbias, GNN_ERR_INVALID_ARG, "dbias is NULL");
+    if (n_active == 0) {
+        fill_kernel<float><<<1, 256, 0, stream>>>(dbias, (int64_t)N, 0.f);
+        GNN_LAUNCH_CHECK("fill_kernel");
+        return GNN_OK;
+    }
+    GNN_REQUIRE(dZ, GNN_ERR_INVALID_ARG, "dZ is NULL");
+    const int es = dtype == GNN_F32 ? 4 : 2, epv = 16 / es;
+    const int n_vec = (N + epv - 1) / epv;
+    int cx = 4;
+    while (cx < n_vec && cx < 256) cx <<= 1;
+    const int io_vec = ((uintptr_t)dZ % 16 == 0) && (ldz * es) % 16 == 0;
+    if (dtype == GNN_F32) dz_kernel<GNN_F32><<<n_part, 256, 0, stream>>>(rows, n_active, dZ, nullptr, ldz, io_vec, 0, N, nullptr, 0, part, cx);
+    else dz_kernel<GNN_BF16><<<n_part, 256, 0, stream>>>(rows, n_active, dZ, nullptr, ldz, io_vec, 0, N, nullptr, 0, part, cx);
+    GNN_LAUNCH_CHECK("dz_kernel");
+    reduce_rows_kernel<<<(N + 31) / 32, 1024, 0, stream>>>(part, n_part, N, dbias);
+    GNN_LAUNCH_CHECK("reduce_rows_kernel");
+    return GNN_OK;
 }

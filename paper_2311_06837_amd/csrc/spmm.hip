@@ -957,6 +957,19 @@ __global__ __launch_bounds__(256) void spmm_sum_parts_kernel(const float* __rest
     }
 }
 
+// Y[v, 0:F] = bias[0:F] for the listed rows: the starting value of an aggregation that has no self term under it.
+template <int DT>
+__global__ __launch_bounds__(256) void spmm_bias_rows_kernel(const int32_t* __restrict__ rows, int32_t n_active, const float* __restrict__ bias,
+                                                              void* __restrict__ Y, int64_t ldy, int32_t F) {
+    const int64_t total = (int64_t)n_active * F;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t i = (int32_t)(t / F), c = (int32_t)(t % F);
+        const int64_t v = rows ? (int64_t)rows[i] : i;
+        if (DT == GNN_F32) ((float*)Y)[v * ldy + c] = bias[c];
+        else ((uint16_t*)Y)[v * ldy + c] = f32_to_bf16(bias[c]);
+    }
+}
+
 // Xs[u, 0:F] = scale[u] * X[u, 0:F] for every row of the gathered matrix (16-byte aligned rows): with a neighbour scale
 // the column-blocked route gathers from this copy, so its inner loop needs no per-edge factor.
 template <int DT>
@@ -1104,7 +1117,7 @@ static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
 static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* rows, int32_t n_active, const int32_t* dist,
                            int32_t max_dist, int32_t src_prefix, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t F, int32_t dtype,
                            const float* out_scale, const float* nbr_scale, int32_t accumulate, const void* relu_h, int64_t ldh,
-                           void* ws, size_t* ws_bytes, hipStream_t stream) {
+                           void* ws, size_t* ws_bytes, hipStream_t stream, const float* start_bias = nullptr) {
     GNN_CHECK(check_csr(g, gname));
     GNN_REQUIRE(n_active >= 0, GNN_ERR_INVALID_ARG, "negative row count");
     GNN_REQUIRE(rows != nullptr || n_active <= g->n_rows, GNN_ERR_SHAPE, "n_active %d exceeds n_rows %d", n_active, g->n_rows);
@@ -1144,6 +1157,13 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     }
     if (n_active == 0 || F == 0) return GNN_OK;
     GNN_REQUIRE(X != nullptr && Y != nullptr, GNN_ERR_INVALID_ARG, "X or Y is NULL");
+    if (start_bias != nullptr) {
+        // no self term under the sum (GCN in the exchanged order): the listed rows start from the bias
+        const int grid = grid_for((int64_t)n_active * F, 256, 1 << 14);
+        if (dtype == GNN_F32) spmm_bias_rows_kernel<GNN_F32><<<grid, 256, 0, stream>>>(rows, n_active, start_bias, Y, ldy, F);
+        else spmm_bias_rows_kernel<GNN_BF16><<<grid, 256, 0, stream>>>(rows, n_active, start_bias, Y, ldy, F);
+        GNN_LAUNCH_CHECK("spmm_bias_rows_kernel");
+    }
 
     SpmmArgs a;
     a.row_ptr = g->row_ptr; a.col_idx = g->col_idx; a.rows = rows; a.n_active = n_active;
@@ -1177,11 +1197,12 @@ extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, in
 
 extern "C" int32_t gnn_masked_spmm_fwd_add(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
                                            void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,
-                                           const float* col_scale, int32_t relu, void* ws, size_t* ws_bytes, void* stream) {
+                                           const float* col_scale, const float* bias, int32_t relu, void* ws, size_t* ws_bytes,
+                                           void* stream) {
     GNN_REQUIRE(relu == 0 || relu == 1, GNN_ERR_INVALID_ARG, "relu must be 0 or 1");
     // the output matrix as its own mask stands for a ReLU of what is stored
     return spmm_common(g, "g", rows, n_active, nullptr, 0, -1, X, ldx, Y, ldy, F, dtype, row_scale, col_scale, 1, relu ? Y : nullptr, ldy, ws,
-                       ws_bytes, (hipStream_t)stream);
+                       ws_bytes, (hipStream_t)stream, bias);
 }
 
 extern "C" int32_t gnn_masked_spmm_bwd(const gnn_csr* gT, const int32_t* out_rows, int32_t n_out, const int32_t* dist,

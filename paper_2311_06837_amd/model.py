@@ -39,8 +39,9 @@ class MaskedGNN:
                      term (gnn_masked_spmm_fwd_add) - the same sum, gathered dims[l] instead of dims[l-1] columns wide;
                      the backward pass aggregates the layer's output gradient (dP = Agg^T(dZ), dims[l] wide) and gets
                      dW_neigh = H_{l-1}^T dP and the input gradient dP W_neigh^T + dZ W_self^T (two products, met in
-                     front of the previous ReLU by gnn_add_rows_masked).  True: every layer of a GraphSAGE model that
-                     narrows its input (dims[l-1] > dims[l]); "auto" (default): those of them whose input rows are at
+                     front of the previous ReLU by gnn_add_rows_masked).  A GCN layer has no self term: its sum starts
+                     from the bias, its bias gradient comes from gnn_bias_grad.  True: every layer that narrows its
+                     input (dims[l-1] > dims[l]); "auto" (default): those of them whose input rows are at
                      least 512 bytes long (shorter rows are gathered at a rate set by their number, not their bytes:
                      narrowing them further buys nothing and the two extra products cost); False: none; or a
                      collection of layer numbers.
@@ -69,14 +70,13 @@ class MaskedGNN:
         if transform_first is True or (isinstance(transform_first, str) and transform_first == "auto"):
             es = 4 if dtype == torch.float32 else 2
             min_bytes = 0 if transform_first is True else 512
-            self.tf_layers = frozenset(l for l in range(1, self.L + 1) if kind == "sage" and self.dims[l - 1] > self.dims[l]
+            self.tf_layers = frozenset(l for l in range(1, self.L + 1) if self.dims[l - 1] > self.dims[l]
                                        and self.dims[l - 1] * es >= min_bytes)
         elif transform_first is False:
             self.tf_layers = frozenset()
         else:
             self.tf_layers = frozenset(int(l) for l in transform_first)
             assert all(1 <= l <= self.L for l in self.tf_layers)
-        assert not self.tf_layers or kind == "sage", "the exchanged order is built for the GraphSAGE layer only"
         # activations A_l, H_l and their gradients; rows outside the active sets are never touched
         self.A = [None] + [None if l in self.tf_layers else torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev)
                            for l in range(1, self.L + 1)]
@@ -178,10 +178,11 @@ class MaskedGNN:
                 n_prev = self.n_rows_of_layer(l - 1)    # every row of R_{l-1} can be a neighbour of a row of R_l
                 self._call(f"linear_pre_{l}", B.gnn_linear_fwd, self.rows, n_prev, self.H[l - 1], None, K, p["W_neigh"], None, None,
                            self.P[l], relu=False, ws=self.ws)
-                self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.H[l - 1], None, K, p["W_self"], None, p["bias"],
-                           self.H[l], relu=False, ws=self.ws)
+                if self.kind == "sage":
+                    self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.H[l - 1], None, K, p["W_self"], None, p["bias"],
+                               self.H[l], relu=False, ws=self.ws)
                 self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd_add, g_l, self.rows, nl, self.P[l], self.H[l], self.dims[l], rs_l,
-                           self.cs, relu=(l < self.L), ws=self.ws)
+                           self.cs, relu=(l < self.L), ws=self.ws, bias=None if self.kind == "sage" else p["bias"])
                 continue
             self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, g_l, self.rows, nl, self.H[l - 1], self.A[l], K, rs_l, self.cs, ws=self.ws)
             self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
@@ -249,14 +250,19 @@ class MaskedGNN:
         dist_l, pre_l = self._source_filter(nl)
         self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dH[l], self.dP[l], N,
                    rs_l, self.cs, accumulate=False, ws=self.ws if 4 * nl >= self.n else None, src_prefix=pre_l)
-        self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.H[l - 1], None, K, p["W_self"], None,
-                   gr["dW_self"], None, gr["dbias"], self.dH[l - 1] if need_in else None, None, ws=self.ws)
+        sage = self.kind == "sage"
+        if sage:
+            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.H[l - 1], None, K, p["W_self"],
+                       None, gr["dW_self"], None, gr["dbias"], self.dH[l - 1] if need_in else None, None, ws=self.ws)
+        else:
+            self._call(f"linear_bwd_{l}", B.gnn_bias_grad, self.rows, nl, self.dH[l], N, gr["dbias"], ws=self.ws)
         self._call(f"linear_bwd_{l}_neigh", B.gnn_linear_bwd, self.rows, n_prev, self.dP[l], None, False, self.H[l - 1], None, K,
                    p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], self.dA[l] if need_in else None, None, ws=self.ws)
         if need_in:
-            # dA_l holds dP W_neigh^T for R_{l-1}, dH_{l-1} holds dZ W_self^T for R_l: sum and mask into dA_l, which
-            # then IS the gradient of layer l-1's output (same shape: the two buffers trade places)
-            self._call(f"add_rows_{l}", B.gnn_add_rows_masked, self.rows, n_prev, self.dH[l - 1], nl, self.dA[l], K, self.H[l - 1])
+            # dA_l holds dP W_neigh^T for R_{l-1}, dH_{l-1} (GraphSAGE) holds dZ W_self^T for R_l: sum and mask into dA_l,
+            # which then IS the gradient of layer l-1's output (same shape: the two buffers trade places)
+            self._call(f"add_rows_{l}", B.gnn_add_rows_masked, self.rows, n_prev, self.dH[l - 1] if sage else None, nl if sage else 0,
+                       self.dA[l], K, self.H[l - 1])
             self.dH[l - 1], self.dA[l] = self.dA[l], self.dH[l - 1]
 
     def step(self, labels: torch.Tensor):

@@ -162,8 +162,8 @@ def test_training_step_with_per_layer_masks(kind, dtype, ls, dims):
     G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
     m = P.MaskedGNN(G, G, dev(T), kind, [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
                     global_degree=dev(gdeg) if gdeg is not None else None, layer_sampling=ls,
-                    transform_first=kind == "sage")      # every narrowing layer in the exchanged order
-    assert m.tf_layers == ({l for l in range(1, L + 1) if dims[l - 1] > dims[l]} if kind == "sage" else set())   # (asked for below)
+                    transform_first=True)      # every narrowing layer in the exchanged order
+    assert m.tf_layers == {l for l in range(1, L + 1) if dims[l - 1] > dims[l]}   # (asked for below)
     m.set_input(padded(H0, P.row_stride(dims[0], dtype), dtype))
     loss = m.step(dev(y))
     torch.cuda.synchronize()

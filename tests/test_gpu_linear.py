@@ -179,3 +179,23 @@ def test_norm_scales():
     rp = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
     got = P.gnn_norm_scales(P.GNN_NORM_MEAN, len(deg), row_ptr=dev(rp)).cpu().numpy()
     assert np.allclose(got, oracle.norm_scales("mean", deg), rtol=2e-7)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("N,ld", [(47, 48), (256, 256), (7, 7), (100, 104)])
+def test_bias_grad(dtype, N, ld):
+    """gnn_bias_grad: column sums of the listed rows (the definition, summed in fp64 here)."""
+    import paper_2311_06837_amd as P
+    rng = np.random.default_rng(N)
+    n = 5000
+    dZ = as_stored(rng.standard_normal((n, N)), dtype)
+    rows = rng.permutation(n)[:3333].astype(np.int32)
+    for rws, cnt in ((rows, len(rows)), (None, 4097), (rows, 1), (None, 0)):
+        print(f"bias_grad: N={N} ld={ld} {dtype} rows={'list' if rws is not None else 'prefix'} n={cnt}", flush=True)
+        db = torch.full((N,), 9.0, device="cuda")
+        P.gnn_bias_grad(dev(rws) if rws is not None else None, cnt, padded(dZ, ld, dtype, fill=float("nan")), N, db)
+        torch.cuda.synchronize()
+        sel = rws[:cnt] if rws is not None else np.arange(cnt)
+        want = dZ[sel].sum(0)
+        got = db.double().cpu().numpy()
+        assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(dZ[sel]).sum(0).max()), (got, want)

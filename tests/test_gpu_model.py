@@ -68,9 +68,10 @@ def _parity(name, part, kind, dims, dtype, seed, transform_first="auto"):
     return m, om
 
 
-def test_cfg0_full_size():
+@pytest.mark.parametrize("transform_first", [False, True])
+def test_cfg0_full_size(transform_first):
     w = gg.make_workload("cfg0")
-    _parity("cfg0", w.partition, w.model, w.dims, torch.float32, 0)
+    _parity("cfg0", w.partition, w.model, w.dims, torch.float32, 0, transform_first)      # GCN 64-64-8: the last layer narrows
 
 
 @pytest.mark.parametrize("transform_first", [False, True])
@@ -92,9 +93,19 @@ def test_transform_first_bf16_and_single_layer(dims):
     _parity("narrowing", part, "sage", dims, torch.float32, 62, True)
 
 
-def test_cfg2_scaled():
+@pytest.mark.parametrize("transform_first", [False, True])
+def test_cfg2_scaled(transform_first):
     w = gg.make_workload("cfg2", scale=0.01)
-    _parity("cfg2@0.01", w.partition, w.model, w.dims, torch.float32, 2)
+    _parity("cfg2@0.01", w.partition, w.model, w.dims, torch.float32, 2, transform_first)  # GCN 100-256-256-47
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_gcn_every_layer_in_the_exchanged_order(dtype):
+    """GCN layers have no self term: the aggregation starts from the bias, the bias gradient is summed on its own."""
+    g = gg.add_self_loops(gg.chung_lu(5000, 9.0, 2.2, 63))
+    T = np.sort(np.random.default_rng(63).choice(5000, 300, replace=False)).astype(np.int64)
+    part = gg.halo_partition(g, T, 3)
+    _parity("gcn narrowing", part, "gcn", [64, 48, 24, 6], dtype, 63, True)
 
 
 def test_cfg3_scaled_deep_bf16():

@@ -47,9 +47,10 @@ def _fwd_case(g, F, ld, dtype, rows, scales, seed, ws=None):
         assert (got[:, F:] == host64(torch.tensor(SENTINEL, dtype=dtype))).all(), "pad columns were written"
 
 
-def _fwd_add_case(g, F, ld, dtype, rows, relu, seed, ws=None):
+def _fwd_add_case(g, F, ld, dtype, rows, relu, seed, ws=None, bias=False):
     """gnn_masked_spmm_fwd_add: Y = act(Y + aggregation).  The oracle aggregates into a zeroed matrix; the sum with
-    the self term and the ReLU are written out here (in the storage precision of the self term)."""
+    the self term and the ReLU are written out here (in the storage precision of the self term).  bias: the form
+    without a self term - the listed rows start from a bias vector, whatever the output matrix held."""
     import paper_2311_06837_amd as P
     print(f"spmm fwd_add: n={g.n_rows} nnz={g.nnz} F={F} ld={ld} {dtype} rows={'list' if rows is not None else 'all'} relu={relu}",
           flush=True)
@@ -64,11 +65,13 @@ def _fwd_add_case(g, F, ld, dtype, rows, relu, seed, ws=None):
     Yd[:, :F] = padded(S, F, dtype)
     rows_d = dev(rows) if rows is not None else None
     n_active = len(rows) if rows is not None else n
-    P.gnn_masked_spmm_fwd_add(G, rows_d, n_active, Xd, Yd, F, dev(rs), None, relu=relu, ws=ws)
+    b = (rng.standard_normal(F) * 0.5).astype(np.float32) if bias else None
+    P.gnn_masked_spmm_fwd_add(G, rows_d, n_active, Xd, Yd, F, dev(rs), None, relu=relu, ws=ws, bias=dev(b) if bias else None)
     torch.cuda.synchronize()
     agg = np.zeros((n, F))
     oracle.spmm_fwd(g.row_ptr, g.col_idx, rows, X, agg, F, rs, None)
-    want = S + agg
+    start = np.broadcast_to(as_stored(b.astype(np.float64), dtype), (n, F)) if bias else S
+    want = start + agg
     if relu:
         want = np.maximum(want, 0.0)
     got = host64(Yd)
@@ -78,7 +81,7 @@ def _fwd_add_case(g, F, ld, dtype, rows, relu, seed, ws=None):
         assert (got[sel, :F] >= 0).all()
         # a row without neighbours still gets its activation
         empty = sel[g.degrees()[sel] == 0]
-        assert np.array_equal(got[empty, :F], np.maximum(S[empty], 0.0))
+        assert np.array_equal(got[empty, :F], np.maximum(start[empty], 0.0))
     rest = np.setdiff1d(np.arange(n), sel)
     assert np.array_equal(got[rest, :F], S[rest]), "masked rows were written"
     if ld > F:
@@ -97,6 +100,8 @@ def test_fwd_add_on_top_of_the_self_term(dtype, relu):
     _fwd_add_case(g, 7, 7, dtype, rows, relu, 53)            # element-wise lanes
     _fwd_add_case(g, 16, 16, dtype, rows, relu, 54)          # narrow rows
     _fwd_add_case(g, 41, 48, dtype, None, relu, 55)
+    _fwd_add_case(g, 47, 48, dtype, rows, relu, 56, bias=True)     # no self term: the rows start from the bias
+    _fwd_add_case(g, 256, 256, dtype, None, relu, 57, bias=True)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -272,6 +277,7 @@ def test_blocked_route_forward_add(dtype):
     rows = np.random.default_rng(6).permutation(g.n_rows)[:40001].astype(np.int32)
     _fwd_add_case(g, 256, 256, dtype, rows, False, 45, ws=ws)
     _fwd_add_case(g, 90, 96, dtype, rows, True, 46, ws=ws)
+    _fwd_add_case(g, 200, 200, dtype, rows, True, 47, ws=ws, bias=True)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
