@@ -224,7 +224,8 @@ def main():
 
     # a first layer in the exchanged order splits its feature transform into two calls each way
     lin_f = lambda l: call_ms.get(f"linear_fwd_{l}", 0.0) + call_ms.get(f"linear_pre_{l}", 0.0)
-    lin_b = lambda l: call_ms.get(f"linear_bwd_{l}", 0.0) + call_ms.get(f"linear_bwd_{l}_neigh", 0.0)
+    lin_b = lambda l: (call_ms.get(f"linear_bwd_{l}", 0.0) + call_ms.get(f"linear_bwd_{l}_neigh", 0.0) +
+                       call_ms.get(f"linear_bwd_{l}_input", 0.0))
 
     # per-layer report
     layers = {}

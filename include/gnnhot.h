@@ -206,6 +206,18 @@ int32_t gnn_linear_bwd(const int32_t *rows, int32_t n_active,
                        void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * Input gradient of one half of a layer in the exchanged order, finished in the product's own store:
+ *     dX[v, 0:K] = [relu_H[v, 0:K] > 0] * ( dZ[v, 0:N] W^T  +  (i < n_accumulate ? dX[v, 0:K] : 0) )      v = rows[i]
+ * (the neighbour half dP W_neigh^T reaches every row of R_{l-1}; the rows of R_l, listed first, already hold the self
+ * half dZ W_self^T; relu_H = H_{l-1} puts the sum in front of the previous layer's ReLU).
+ *   W        [K, N] as in gnn_linear_fwd;  relu_H NULL: no mask, then n_accumulate must be 0
+ * Workspace: (ws, ws_bytes) size-query protocol.
+ */
+int32_t gnn_linear_bwd_input(const int32_t *rows, int32_t n_active, const void *dZ, int64_t lddz, int32_t N, const void *W,
+                             int32_t K, int32_t n_accumulate, const void *relu_H, int64_t ld_relu, void *dX, int64_t lddx,
+                             int32_t dtype, void *ws, size_t *ws_bytes, void *stream);
+
+/*
  * Bias gradient alone: dbias[0:N] = sum over the listed rows of dZ[v, 0:N] (fixed order, no atomics) - for a layer in
  * the exchanged order without a self term, whose gnn_linear_bwd call runs on another matrix (dP) than dZ.
  * Workspace: (ws, ws_bytes) size-query protocol.  N <= 4096.

@@ -25,7 +25,7 @@ EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_s
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
            "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
-           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked", "gnn_bias_grad"]
+           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked", "gnn_bias_grad", "gnn_linear_bwd_input"]
 
 
 class GnnError(RuntimeError):
@@ -495,3 +495,18 @@ def gnn_bias_grad(rows, n_active: int, dZ: torch.Tensor, N: int, dbias: torch.Te
     assert rows is None or rows.numel() >= n_active
     _with_ws(lib().gnn_bias_grad, (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(dZ), C.c_int64(dZ.stride(0)), C.c_int32(N),
                                    C.c_int32(_dtype_code(dZ)), _ptr(dbias)), (_stream(),), ws)
+
+
+def gnn_linear_bwd_input(rows, n_active: int, dZ: torch.Tensor, N: int, W: torch.Tensor, K: int, n_accumulate: int, relu_H, dX: torch.Tensor,
+                         ws: Workspace | None = None):
+    """dX[rows] = (dZ[rows] W^T + dX[rows] for the first n_accumulate listed rows) where relu_H > 0, else 0."""
+    _mat(dZ, "dZ"), _mat(dX, "dX")
+    assert W.shape == (K, N) and W.is_contiguous() and W.dtype == dZ.dtype == dX.dtype
+    assert rows is None or rows.numel() >= n_active
+    if relu_H is not None:
+        _mat(relu_H, "relu_H")
+        assert relu_H.dtype == dX.dtype
+    _with_ws(lib().gnn_linear_bwd_input,
+             (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(dZ), C.c_int64(dZ.stride(0)), C.c_int32(N), _ptr(W), C.c_int32(K),
+              C.c_int32(n_accumulate), _ptr(relu_H), C.c_int64(relu_H.stride(0) if relu_H is not None else 0), _ptr(dX),
+              C.c_int64(dX.stride(0)), C.c_int32(_dtype_code(dZ))), (_stream(),), ws)

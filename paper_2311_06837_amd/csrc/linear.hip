@@ -149,7 +149,63 @@ struct GemmNT {
     void* C;
     int64_t ldc;
     int32_t c_vec;             // 16-byte stores to C rows allowed
+    // input gradient of a layer in the exchanged order: what is stored is (product + what C held, for the first n_acc
+    // rows) where mask > 0, else 0.  mask: nullable, same rows and columns as C
+    const void* mask;
+    int64_t ldm;
+    int32_t m_vec;             // 16-byte loads from mask rows allowed
+    int32_t n_acc;
 };
+
+// The post-processing of that input gradient on one stored 16-byte vector / one element.
+template <int DT>
+__device__ __forceinline__ uint4 post_vec(uint4 v, const void* C, int64_t coff, bool acc, const void* mask, int64_t moff) {
+    if (DT == GNN_F32) {
+        float x[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+        if (acc) {
+            const float4 o = *(const float4*)((const float*)C + coff);
+            x[0] += o.x; x[1] += o.y; x[2] += o.z; x[3] += o.w;
+        }
+        const float4 h = *(const float4*)((const float*)mask + moff);
+        return make_uint4(__float_as_uint(h.x > 0.f ? x[0] : 0.f), __float_as_uint(h.y > 0.f ? x[1] : 0.f),
+                          __float_as_uint(h.z > 0.f ? x[2] : 0.f), __float_as_uint(h.w > 0.f ? x[3] : 0.f));
+    }
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = bf16lo(w[e]);
+        x[2 * e + 1] = bf16hi(w[e]);
+    }
+    if (acc) {
+        const uint4 o4 = *(const uint4*)((const uint16_t*)C + coff);
+        const uint32_t o[4] = {o4.x, o4.y, o4.z, o4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[2 * e] += bf16lo(o[e]);
+            x[2 * e + 1] += bf16hi(o[e]);
+        }
+    }
+    const uint4 h4 = *(const uint4*)((const uint16_t*)mask + moff);
+    const uint32_t h[4] = {h4.x, h4.y, h4.z, h4.w};
+    uint32_t r[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = pack_bf16(bf16lo(h[e]) > 0.f ? x[2 * e] : 0.f, bf16hi(h[e]) > 0.f ? x[2 * e + 1] : 0.f);
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+template <int DT>
+__device__ __forceinline__ float post_elem(float v, const void* C, int64_t coff, bool acc, const void* mask, int64_t moff) {
+    float h;
+    if (DT == GNN_F32) {
+        if (acc) v += ((const float*)C)[coff];
+        h = ((const float*)mask)[moff];
+    } else {
+        if (acc) v += bf16_to_f32(((const uint16_t*)C)[coff]);
+        h = bf16_to_f32(((const uint16_t*)mask)[moff]);
+    }
+    return h > 0.f ? v : 0.f;
+}
 
 template <int DT, int BN, int WM, int WN, bool VEC>
 __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) void gemm_nt_kernel(GemmNT a) {
@@ -335,13 +391,18 @@ __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) 
             const int m = m0 + row, n = n0 + ch * 8;
             if (m < a.M && n < a.N) {
                 const int64_t crow = a.c_rows ? (int64_t)a.c_rows[m] : (int64_t)m;
-                const uint4 v = *(const uint4*)&smem[row * RS + ch * 4];
+                uint4 v = *(const uint4*)&smem[row * RS + ch * 4];
                 uint16_t* dst = (uint16_t*)a.C + crow * a.ldc + n;
-                if (n + 8 <= a.N && a.c_vec) {
+                if (n + 8 <= a.N && a.c_vec && (!a.mask || a.m_vec)) {
+                    if (a.mask) v = post_vec<DT>(v, a.C, crow * a.ldc + n, m < a.n_acc, a.mask, crow * a.ldm + n);
                     *(uint4*)dst = v;
                 } else {
                     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-                    for (int e = 0; e < 8 && n + e < a.N; ++e) dst[e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                    for (int e = 0; e < 8 && n + e < a.N; ++e) {
+                        uint16_t o = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                        if (a.mask) o = f32_to_bf16(post_elem<DT>(bf16_to_f32(o), a.C, crow * a.ldc + n + e, m < a.n_acc, a.mask, crow * a.ldm + n + e));
+                        dst[e] = o;
+                    }
                 }
             }
         }
@@ -363,6 +424,7 @@ __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) 
                     float v = acc[i][j][r];
                     if (a.bias) v += a.bias[n];
                     if (a.relu) v = v > 0.f ? v : 0.f;
+                    if (a.mask) v = post_elem<DT>(v, a.C, crow * a.ldc + n, m < a.n_acc, a.mask, crow * a.ldm + n);
                     store_elem<DT>(a.C, crow * a.ldc + n, v);
                 }
             }
@@ -603,16 +665,25 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
                 const int n = n0 + wn * WTN + p * CW + ch * EPV;
                 if (m < a.M && n < a.N) {
                     const int64_t crow = a.c_rows ? (int64_t)a.c_rows[m] : (int64_t)m;
-                    const uint4 v = *(const uint4*)&stg[row * CROW + ch * 4];
+                    uint4 v = *(const uint4*)&stg[row * CROW + ch * 4];
                     char* dst = (char*)a.C + (crow * a.ldc + n) * ES;
-                    if (n + EPV <= a.N && a.c_vec) {
+                    if (n + EPV <= a.N && a.c_vec && (!a.mask || a.m_vec)) {
+                        if (a.mask) v = post_vec<DT>(v, a.C, crow * a.ldc + n, m < a.n_acc, a.mask, crow * a.ldm + n);
                         *(uint4*)dst = v;
                     } else {
                         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
                         if (DT == GNN_F32) {
-                            for (int e = 0; e < 4 && n + e < a.N; ++e) ((uint32_t*)dst)[e] = w[e];
+                            for (int e = 0; e < 4 && n + e < a.N; ++e) {
+                                float o = __uint_as_float(w[e]);
+                                if (a.mask) o = post_elem<DT>(o, a.C, crow * a.ldc + n + e, m < a.n_acc, a.mask, crow * a.ldm + n + e);
+                                ((float*)dst)[e] = o;
+                            }
                         } else {
-                            for (int e = 0; e < 8 && n + e < a.N; ++e) ((uint16_t*)dst)[e] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                            for (int e = 0; e < 8 && n + e < a.N; ++e) {
+                                uint16_t o = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                                if (a.mask) o = f32_to_bf16(post_elem<DT>(bf16_to_f32(o), a.C, crow * a.ldc + n + e, m < a.n_acc, a.mask, crow * a.ldm + n + e));
+                                ((uint16_t*)dst)[e] = o;
+                            }
                         }
                     }
                 }
@@ -1041,6 +1112,7 @@ static int32_t linear_fwd_impl(const int32_t* rows, int32_t n_active, const void
     g.b_vec = 1;
     g.a_rows = rows; g.c_rows = rows; g.M = n_active; g.N = N; g.K = K;
     g.bias = bias; g.relu = relu; g.C = H; g.ldc = ld_out; g.c_vec = vec_ok(H, ld_out, ES);
+    g.mask = nullptr; g.ldm = 0; g.m_vec = 0; g.n_acc = 0;
     return launch_gemm_nt<DT>(g, stream);
 }
 
@@ -1116,6 +1188,7 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
         g.lda = ldz; g.ldb = ldw; g.a_vec = vec_ok(dZ, ldz, ES); g.b_vec = vec_ok(W, ldw, ES);
         g.a_rows = nullptr; g.c_rows = rows; g.M = M; g.N = K; g.K = N;
         g.bias = nullptr; g.relu = 0; g.C = out; g.ldc = ld_din; g.c_vec = vec_ok(out, ld_din, ES);
+        g.mask = nullptr; g.ldm = 0; g.m_vec = 0; g.n_acc = 0;
         GNN_CHECK(launch_gemm_nt<DT>(g, stream));
     }
     return GNN_OK;
@@ -1251,4 +1324,41 @@ extern "C" int32_t gnn_bias_grad(const int32_t* rows, int32_t n_active, const vo
     reduce_rows_kernel<<<(N + 31) / 32, 1024, 0, stream>>>(part, n_part, N, dbias);
     GNN_LAUNCH_CHECK("reduce_rows_kernel");
     return GNN_OK;
+}
+
+extern "C" int32_t gnn_linear_bwd_input(const int32_t* rows, int32_t n_active, const void* dZ, int64_t lddz, int32_t N, const void* W,
+                                        int32_t K, int32_t n_accumulate, const void* relu_H, int64_t ld_relu, void* dX, int64_t lddx,
+                                        int32_t dtype, void* ws, size_t* ws_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_linear_common(n_active, K, N, dtype));
+    GNN_REQUIRE(lddz >= N && lddx >= K, GNN_ERR_SHAPE, "leading dimension smaller than the width");
+    GNN_REQUIRE(n_accumulate >= 0 && n_accumulate <= n_active, GNN_ERR_INVALID_ARG, "n_accumulate = %d outside [0, n_active = %d]",
+                n_accumulate, n_active);
+    GNN_REQUIRE(relu_H == nullptr ? n_accumulate == 0 : ld_relu >= K, GNN_ERR_SHAPE,
+                "relu_H: leading dimension smaller than K, or rows to accumulate without it");
+    const int es = dtype == GNN_F32 ? 4 : 2;
+    const bool pad_w = ((int64_t)N * es) % 16 != 0;
+    const int32_t ldwp = (int32_t)align_up((size_t)N, 16 / es);
+    WsCarver carve(ws);
+    char* Wpad = carve.take<char>(pad_w ? (size_t)K * ldwp * es : 0);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+    if (n_active == 0) return GNN_OK;
+    GNN_REQUIRE(dZ && W && dX, GNN_ERR_INVALID_ARG, "dZ, W or dX is NULL");
+    int64_t ldw = N;
+    if (pad_w) {
+        if (dtype == GNN_F32) pad_rows_kernel<GNN_F32><<<grid_for((int64_t)K * ldwp, 256, 1024), 256, 0, stream>>>(W, K, N, Wpad, ldwp);
+        else pad_rows_kernel<GNN_BF16><<<grid_for((int64_t)K * ldwp, 256, 1024), 256, 0, stream>>>(W, K, N, Wpad, ldwp);
+        GNN_LAUNCH_CHECK("pad_rows_kernel");
+        W = Wpad;
+        ldw = ldwp;
+    }
+    GemmNT g;
+    g.A[0] = dZ; g.A[1] = nullptr; g.Bt[0] = W; g.Bt[1] = nullptr; g.n_src = 1;
+    g.lda = lddz; g.ldb = ldw; g.a_vec = vec_ok(dZ, lddz, es); g.b_vec = vec_ok(W, ldw, es);
+    g.a_rows = rows; g.c_rows = rows; g.M = n_active; g.N = K; g.K = N;
+    g.bias = nullptr; g.relu = 0; g.C = dX; g.ldc = lddx; g.c_vec = vec_ok(dX, lddx, es);
+    g.mask = relu_H; g.ldm = ld_relu; g.m_vec = relu_H ? vec_ok(relu_H, ld_relu, es) : 0; g.n_acc = n_accumulate;
+    return dtype == GNN_F32 ? launch_gemm_nt<GNN_F32>(g, stream) : launch_gemm_nt<GNN_BF16>(g, stream);
 }

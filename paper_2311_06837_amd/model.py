@@ -38,8 +38,8 @@ class MaskedGNN:
                      the weights.  Exchanged: multiply first, P = H_{l-1} W_neigh, then aggregate P on top of the self
                      term (gnn_masked_spmm_fwd_add) - the same sum, gathered dims[l] instead of dims[l-1] columns wide;
                      the backward pass aggregates the layer's output gradient (dP = Agg^T(dZ), dims[l] wide) and gets
-                     dW_neigh = H_{l-1}^T dP and the input gradient dP W_neigh^T + dZ W_self^T (two products, met in
-                     front of the previous ReLU by gnn_add_rows_masked).  A GCN layer has no self term: its sum starts
+                     dW_neigh = H_{l-1}^T dP and the input gradient dP W_neigh^T + dZ W_self^T (two products; the
+                     second one adds onto the first and masks in front of the previous ReLU: gnn_linear_bwd_input).  A GCN layer has no self term: its sum starts
                      from the bias, its bias gradient comes from gnn_bias_grad.  True: every layer that narrows its
                      input (dims[l-1] > dims[l]); "auto" (default): those of them whose input rows are at
                      least 512 bytes long (shorter rows are gathered at a rate set by their number, not their bytes:
@@ -87,7 +87,8 @@ class MaskedGNN:
         self._dbias_unused = torch.zeros(max(self.dims), dtype=torch.float32, device=dev)
         self.H = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
         self.dH = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
-        self.dA = [None, None] + [torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(2, self.L + 1)]
+        self.dA = [None, None] + [None if l in self.tf_layers else torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev)
+                                  for l in range(2, self.L + 1)]
         self.grads = []
         for p in self.params:
             gdict = {"dW_neigh": torch.zeros_like(p["W_neigh"], dtype=torch.float32), "dbias": torch.zeros_like(p["bias"])}
@@ -257,13 +258,12 @@ class MaskedGNN:
         else:
             self._call(f"linear_bwd_{l}", B.gnn_bias_grad, self.rows, nl, self.dH[l], N, gr["dbias"], ws=self.ws)
         self._call(f"linear_bwd_{l}_neigh", B.gnn_linear_bwd, self.rows, n_prev, self.dP[l], None, False, self.H[l - 1], None, K,
-                   p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], self.dA[l] if need_in else None, None, ws=self.ws)
+                   p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], None, None, ws=self.ws)
         if need_in:
-            # dA_l holds dP W_neigh^T for R_{l-1}, dH_{l-1} (GraphSAGE) holds dZ W_self^T for R_l: sum and mask into dA_l,
-            # which then IS the gradient of layer l-1's output (same shape: the two buffers trade places)
-            self._call(f"add_rows_{l}", B.gnn_add_rows_masked, self.rows, n_prev, self.dH[l - 1] if sage else None, nl if sage else 0,
-                       self.dA[l], K, self.H[l - 1])
-            self.dH[l - 1], self.dA[l] = self.dA[l], self.dH[l - 1]
+            # dP W_neigh^T for every row of R_{l-1}, added (GraphSAGE) to the dZ W_self^T that the rows of R_l already
+            # hold and masked in front of layer l-1's ReLU, all in the product's store: dH_{l-1} leaves masked
+            self._call(f"linear_bwd_{l}_input", B.gnn_linear_bwd_input, self.rows, n_prev, self.dP[l], N, p["W_neigh"], K,
+                       nl if sage else 0, self.H[l - 1], self.dH[l - 1], ws=self.ws)
 
     def step(self, labels: torch.Tensor):
         """One pass of the whole hot path: active sets, forward, loss, backward."""

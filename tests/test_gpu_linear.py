@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 import torch
 
+import graphgen as gg
 import oracle
 from gpu_util import as_stored, check, dev, host64, padded
 
@@ -199,3 +200,39 @@ def test_bias_grad(dtype, N, ld):
         want = dZ[sel].sum(0)
         got = db.double().cpu().numpy()
         assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(dZ[sel]).sum(0).max()), (got, want)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K,N", [(256, 41), (256, 32), (128, 16), (256, 256), (96, 47), (40, 7)])
+def test_input_gradient_product_with_sum_and_mask_in_its_store(dtype, K, N):
+    """gnn_linear_bwd_input: dX = [H > 0] * (dZ W^T + dX on the first n_accumulate listed rows).  The product comes from
+    the oracle's feature-transform backward, the sum and the mask are written out here."""
+    import paper_2311_06837_amd as P
+    rng = np.random.default_rng(K * 1000 + N)
+    n = 3000
+    params = gg.layer_weights([K, N], False, K + N)[0]
+    W = as_stored(params["W_neigh"], dtype)
+    dZ = as_stored(rng.standard_normal((n, N)), dtype)
+    old = as_stored(rng.standard_normal((n, K)), dtype)
+    H = as_stored(np.maximum(rng.standard_normal((n, K)), 0), dtype)
+    rows = rng.permutation(n)[:1777].astype(np.int32)
+    ld_in, ld_out = P.row_stride(K, dtype), P.row_stride(N, dtype)
+    for rws, cnt, n_acc, mask in ((rows, len(rows), 600, True), (None, 2049, 2049, True), (rows, len(rows), 0, True), (rows, 129, 0, False)):
+        print(f"linear_bwd_input: K={K} N={N} {dtype} rows={'list' if rws is not None else 'prefix'} n={cnt} n_acc={n_acc} mask={mask}", flush=True)
+        dXd = padded(old, ld_in, dtype, fill=SENT)
+        P.gnn_linear_bwd_input(dev(rws) if rws is not None else None, cnt, padded(dZ, ld_out, dtype), N, dev(W).to(dtype), K, n_acc,
+                               padded(H, ld_in, dtype) if mask else None, dXd)
+        torch.cuda.synchronize()
+        sel = rws[:cnt] if rws is not None else np.arange(cnt, dtype=np.int32)
+        prod = np.zeros((n, K))
+        oracle.linear_bwd(sel, dZ, None, False, np.zeros((n, K)), None, K, W, None, prod, None)
+        want = old.copy()
+        t = prod[sel]
+        t[:n_acc] += old[sel[:n_acc]]
+        want[sel] = t * (H[sel] > 0) if mask else t
+        got = host64(dXd)
+        check(got[sel, :K], want[sel], dtype, "listed rows")
+        rest = np.setdiff1d(np.arange(n), sel)
+        assert np.array_equal(got[rest, :K], old[rest]), "rows outside the list were written"
+        if ld_in > K:
+            assert (got[:, K:] == host64(torch.tensor(SENT, dtype=dtype))).all()
