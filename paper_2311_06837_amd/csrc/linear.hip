@@ -701,7 +701,10 @@ static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
     if (vec && a.N > 32 && a.K > 0) {
         // wide tile: the tile width that pads the output width least (256 on a tie)
         const int64_t p256 = ((int64_t)a.N + 255) / 256 * 256, p128 = ((int64_t)a.N + 127) / 128 * 128, p64 = ((int64_t)a.N + 63) / 64 * 64;
-        const int ntw = (p256 <= p128 && p256 <= p64) ? 4 : (p128 <= p64 ? 2 : 1);
+        int ntw = (p256 <= p128 && p256 <= p64) ? 4 : (p128 <= p64 ? 2 : 1);
+        // a reduction of one or two slices (an input gradient from 32 or 41 class scores) is all prologue and epilogue:
+        // narrow tiles keep more workgroups on a CU to hide those latencies, and re-reading the short rows costs little
+        if ((int64_t)a.K * a.n_src * DTy<DT>::ES <= 128) ntw = 1;
         const unsigned grid = (unsigned)(tiles_m * (ntw == 4 ? p256 / 256 : (ntw == 2 ? p128 / 128 : p64 / 64)));
         const bool ktail = a.K % (64 / DTy<DT>::ES) != 0;
 #define GNN_WIDE(NTW_)                                                                                  \
