@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--aggregate-first", action="store_true",
                     help="keep the paper's order (aggregate, then weights) in every layer; by default a GraphSAGE layer that "
                          "narrows its input multiplies by the weights first and gathers the narrower rows")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="enqueue the weight-gradient products on the step's stream instead of a second one")
     ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
                     help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
                          "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
@@ -175,7 +177,7 @@ def main():
         if w.model == "gcn":
             gdeg = dev(w.global_graph.degrees().astype(np.int32))[l2g.long()]
         model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg, prefix_numbered=True,
-                            transform_first=False if args.aggregate_first else "auto")
+                            transform_first=False if args.aggregate_first else "auto", side_stream=not args.one_stream)
         # the host partition numbers its vertices by ascending id; its feature rows are permuted into ring order
         pos = torch.from_numpy(np.searchsorted(part.local_to_global, l2g.cpu().numpy().astype(np.int64)).astype(np.int32)).cuda()
         H0d = torch.zeros(n, ld0, dtype=dtype, device="cuda")
@@ -187,7 +189,7 @@ def main():
         model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=dtype,
                             global_degree=dev(part.global_degree) if w.model == "gcn" else None,
                             prefix_numbered=sampled_graph is not None,   # the GPU extraction numbers by (distance, id)
-                            transform_first=False if args.aggregate_first else "auto")
+                            transform_first=False if args.aggregate_first else "auto", side_stream=not args.one_stream)
         model.set_input(dev(H0).to(dtype))
     if args.layer_sampling:
         f = args.layer_sampling.split(":")
@@ -225,7 +227,7 @@ def main():
     # a first layer in the exchanged order splits its feature transform into two calls each way
     lin_f = lambda l: call_ms.get(f"linear_fwd_{l}", 0.0) + call_ms.get(f"linear_pre_{l}", 0.0)
     lin_b = lambda l: (call_ms.get(f"linear_bwd_{l}", 0.0) + call_ms.get(f"linear_bwd_{l}_neigh", 0.0) +
-                       call_ms.get(f"linear_bwd_{l}_input", 0.0))
+                       call_ms.get(f"linear_bwd_{l}_input", 0.0) + call_ms.get(f"linear_bwd_{l}_input_self", 0.0))
 
     # per-layer report
     layers = {}

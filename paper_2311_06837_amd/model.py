@@ -45,11 +45,15 @@ class MaskedGNN:
                      least 512 bytes long (shorter rows are gathered at a rate set by their number, not their bytes:
                      narrowing them further buys nothing and the two extra products cost); False: none; or a
                      collection of layer numbers.
+    side_stream      True (default): the weight-gradient products of the backward pass - nothing in the step waits for
+                     them - are enqueued on a second HIP stream (default priority, a workspace of its own), so they
+                     run beside the backward aggregations, which leave the matrix cores idle; the step's stream
+                     waits for that stream when the backward pass ends.  False: everything on the caller's stream.
     """
 
     def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, kind: str, params: list,
                  dtype=torch.float32, global_degree: torch.Tensor | None = None, prefix_numbered: bool = False,
-                 layer_sampling=None, transform_first="auto"):
+                 layer_sampling=None, transform_first="auto", side_stream: bool = True):
         assert kind in ("gcn", "sage")
         self.layer_sampling = layer_sampling
         self.prefix_numbered, self._prefix_checked = prefix_numbered, False
@@ -57,6 +61,8 @@ class MaskedGNN:
         self.n = graph.n_rows
         self.L = len(params)
         self.ws = B.Workspace()
+        self.side = torch.cuda.Stream(device=targets.device) if side_stream else None
+        self.ws_side = B.Workspace()
         self.dims = [params[0]["W_neigh"].shape[0]] + [p["W_neigh"].shape[1] for p in params]
         self.params = []
         for p in params:
@@ -109,6 +115,21 @@ class MaskedGNN:
         b.record()
         self.trace.append((name, a, b))
         return out
+
+    def _call_beside(self, name, fn, *args, **kw):
+        """A call whose inputs are final by now and whose outputs nobody reads before the backward pass ends (weight
+        and bias gradients): on the side stream, after everything enqueued so far on the step's stream."""
+        if self.side is None:
+            return self._call(name, fn, *args, ws=self.ws, **kw)
+        ready = torch.cuda.Event()
+        ready.record()
+        with torch.cuda.stream(self.side):
+            self.side.wait_event(ready)
+            return self._call(name, fn, *args, ws=self.ws_side, **kw)
+
+    def _join_side(self):
+        if self.side is not None:
+            torch.cuda.current_stream().wait_stream(self.side)
 
     # -- step a1 -------------------------------------------------------------------------
     def build_active_sets(self):
@@ -205,10 +226,22 @@ class MaskedGNN:
                 self._backward_transform_first(l)
                 continue
             # dH_l arrives with the ReLU of layer l already undone: the aggregation call that wrote it last masked it
-            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
-                             self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
-                             gr["dW_neigh"], gr.get("dW_self"), gr["dbias"],
-                             self.dA[l] if need_in else None, self.dH[l - 1] if (need_in and sage) else None, ws=self.ws)
+            N = self.dims[l]
+            if need_in and self.side is not None:
+                # weight and bias gradients beside the rest; the input gradients, which the aggregation waits for, here
+                self._call_beside(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
+                                  self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
+                                  gr["dW_neigh"], gr.get("dW_self"), gr["dbias"], None, None)
+                self._call(f"linear_bwd_{l}_input", B.gnn_linear_bwd_input, self.rows, nl, self.dH[l], N, p["W_neigh"], K, 0, None,
+                           self.dA[l], ws=self.ws)
+                if sage:
+                    self._call(f"linear_bwd_{l}_input_self", B.gnn_linear_bwd_input, self.rows, nl, self.dH[l], N, p["W_self"], K, 0,
+                               None, self.dH[l - 1], ws=self.ws)
+            else:
+                self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
+                           self.H[l - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
+                           gr["dW_neigh"], gr.get("dW_self"), gr["dbias"],
+                           self.dA[l] if need_in else None, self.dH[l - 1] if (need_in and sage) else None, ws=self.ws)
             if need_in:
                 n_prev = self.n_rows_of_layer(l - 1)
                 # The backward gather only keeps the neighbours that were rows of the forward call.  When those are
@@ -229,6 +262,7 @@ class MaskedGNN:
                 else:
                     self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dA[l], self.dH[l - 1], K,
                                           rs_l, self.cs, accumulate=False, ws=ws_bwd, relu_H=relu_h, src_prefix=pre_l)
+        self._join_side()
         return self.grads
 
     def _source_filter(self, n_fwd: int):
@@ -249,16 +283,20 @@ class MaskedGNN:
         need_in = l > 1
         gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[l], self.rs_l[l])
         dist_l, pre_l = self._source_filter(nl)
+        sage = self.kind == "sage"
+        # the gradients of the self half (or, GCN, of the bias) need dZ only: beside the backward aggregation
+        if sage:
+            self._call_beside(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.H[l - 1], None, K,
+                              p["W_self"], None, gr["dW_self"], None, gr["dbias"], None, None)
+            if need_in:
+                self._call(f"linear_bwd_{l}_input_self", B.gnn_linear_bwd_input, self.rows, nl, self.dH[l], N, p["W_self"], K, 0, None,
+                           self.dH[l - 1], ws=self.ws)
+        else:
+            self._call_beside(f"linear_bwd_{l}", B.gnn_bias_grad, self.rows, nl, self.dH[l], N, gr["dbias"])
         self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dH[l], self.dP[l], N,
                    rs_l, self.cs, accumulate=False, ws=self.ws if 4 * nl >= self.n else None, src_prefix=pre_l)
-        sage = self.kind == "sage"
-        if sage:
-            self._call(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.H[l - 1], None, K, p["W_self"],
-                       None, gr["dW_self"], None, gr["dbias"], self.dH[l - 1] if need_in else None, None, ws=self.ws)
-        else:
-            self._call(f"linear_bwd_{l}", B.gnn_bias_grad, self.rows, nl, self.dH[l], N, gr["dbias"], ws=self.ws)
-        self._call(f"linear_bwd_{l}_neigh", B.gnn_linear_bwd, self.rows, n_prev, self.dP[l], None, False, self.H[l - 1], None, K,
-                   p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], None, None, ws=self.ws)
+        self._call_beside(f"linear_bwd_{l}_neigh", B.gnn_linear_bwd, self.rows, n_prev, self.dP[l], None, False, self.H[l - 1], None, K,
+                          p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], None, None)
         if need_in:
             # dP W_neigh^T for every row of R_{l-1}, added (GraphSAGE) to the dZ W_self^T that the rows of R_l already
             # hold and masked in front of layer l-1's ReLU, all in the product's store: dH_{l-1} leaves masked

@@ -194,3 +194,32 @@ def test_add_rows_masked(dtype, F, ld):
         assert (got[:, F:] == host64(torch.tensor(SENT, dtype=dtype))).all()
     with pytest.raises(P.GnnError):
         P.gnn_add_rows_masked(None, 10, padded(X, ld, dtype), 11, padded(Y, ld, dtype), F, padded(H, ld, dtype))
+
+
+@pytest.mark.parametrize("kind,dims", [("sage", [96, 64, 64, 7]), ("gcn", [64, 48, 24, 6]), ("sage", [16, 32, 32, 8])])
+def test_side_stream_changes_nothing(kind, dims):
+    """The weight-gradient products run on a second stream by default; with everything on one stream the step gives the
+    same bits (same kernels, same inputs - only the order in time differs)."""
+    import paper_2311_06837_amd as P
+    g = gg.chung_lu(6000, 9.0, 2.2, 71)
+    if kind == "gcn":
+        g = gg.add_self_loops(g)
+    T = np.sort(np.random.default_rng(71).choice(6000, 400, replace=False)).astype(np.int64)
+    part = gg.halo_partition(g, T, 3)
+    params = gg.layer_weights(dims, kind == "sage", 71)
+    H0 = padded(gg.features(part.graph.n_rows, dims[0], 71), P.row_stride(dims[0], torch.float32), torch.float32)
+    y = dev(gg.labels(len(part.targets), dims[-1], 71))
+    out = []
+    for side in (True, False):
+        G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
+        m = P.MaskedGNN(G, G, dev(part.targets), kind, [{k: dev(v) for k, v in p.items()} for p in params],
+                        global_degree=dev(part.global_degree) if kind == "gcn" else None, transform_first=True, side_stream=side)
+        m.set_input(H0)
+        for _ in range(2):                      # twice: the second step reuses every buffer while the side stream may still run
+            loss = m.step(y)
+        torch.cuda.synchronize()
+        out.append((loss.item(), [{k: v.clone() for k, v in gr.items()} for gr in m.grads]))
+    assert out[0][0] == out[1][0]
+    for ga, gb in zip(out[0][1], out[1][1]):
+        for k in ga:
+            assert torch.equal(ga[k], gb[k]), k
