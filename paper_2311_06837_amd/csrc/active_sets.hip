@@ -49,24 +49,27 @@ __global__ __launch_bounds__(256) void as_seed_kernel(const int32_t* __restrict_
     }
 }
 
-// One wave per frontier vertex, lanes across its row.
+// LPV lanes per frontier vertex, lanes across its row: a whole wavefront for long rows, 16 lanes (four vertices per
+// wavefront) where rows are short - a vertex costs a chain of dependent loads (id, row bounds, neighbours, bitmap
+// words), and with short rows that latency, not the bytes, is what the expansion pays for.
+template <int LPV>
 __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                         const int32_t* __restrict__ ring_ids,
                                                         const int64_t* __restrict__ hop_offsets, int32_t ring,
                                                         const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
                                                         int32_t* __restrict__ hubq, AsCtrl* ctrl) {
     const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
-    const int lane = lane_id();
-    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    for (int64_t i = begin + wave; i < end; i += n_waves) {
+    const int sl = lane_id() % LPV;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPV;
+    const int64_t n_groups = ((int64_t)gridDim.x * blockDim.x) / LPV;
+    for (int64_t i = begin + group; i < end; i += n_groups) {
         const int32_t v = ring_ids[i];
         const int32_t s = row_ptr[v], e = row_ptr[v + 1];
         if (e - s > kAsHubDegree) {
-            if (lane == 0) hubq[atomicAdd(&ctrl->n_hubs, 1)] = v;
+            if (sl == 0) hubq[atomicAdd(&ctrl->n_hubs, 1)] = v;
             continue;
         }
-        for (int32_t p = s + lane; p < e; p += kWave) {
+        for (int32_t p = s + sl; p < e; p += LPV) {
             const int32_t u = col_idx[p];
             const uint32_t bit = 1u << (u & 31);
             if (!(visited[u >> 5] & bit) && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
@@ -290,8 +293,14 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* target
         const int expand_grid = 2048;  // 8 waves per CU-slot; bounds are read on the device
         for (int32_t ring = 0; ring <= L; ++ring) {
             if (ring > 0) {
-                as_expand_kernel<<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited,
-                                                                  next, hubq, ctrl);
+                // rows shorter than 16 entries on average: four vertices per wavefront (measured: better at 10 per
+                // row, worse at 20 and 50)
+                if (g->nnz < (int64_t)16 * g->n_rows)
+                    as_expand_kernel<16><<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited,
+                                                                          next, hubq, ctrl);
+                else
+                    as_expand_kernel<64><<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited,
+                                                                          next, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_kernel");
                 as_expand_hubs_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, visited, next, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_hubs_kernel");
