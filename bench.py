@@ -37,10 +37,10 @@ CONFIG_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}
 # summarised in profiles/spmm_blocked_fwd_cfg1.md and profiles/spmm_rows_and_gemm_cfg4.md (FETCH_SIZE and WRITE_SIZE in
 # KiB, summed over the call's kernels, scaled by what the same counters read for a 1 GiB copy: 2.0 and 1.0).  Known
 # for configs[1] (layer 2; layer 1 in the paper's order, --aggregate-first) and configs[4] at full scale.
-MEASURED_TRAFFIC_KIB = {"cfg1": {2: {"fetch": 230520 + 15973796 + 935668,       # seg + stream + sum_parts kernels
+MEASURED_TRAFFIC_KIB = {"cfg1": {2: {"fetch": 230305 + 15972532 + 935683,       # seg + stream + sum_parts kernels
                                      "write": 8191 + 1864000 + 233000},
                                  1: {"fetch": 231169 + 40302620 + 2297897, "write": 8192 + 4427085 + 562475}},
-                        "cfg4": {2: {"fetch": 7994841, "write": 1742670}}}       # one spmm_rows_kernel launch
+                        "cfg4": {2: {"fetch": 7994937, "write": 1742670}}}       # one spmm_rows_kernel launch
 FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 
 
