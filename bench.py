@@ -6,9 +6,12 @@ A step is one pass of the whole hot path over one synthetic partition: active-se
 matching backward pass.  Inputs are resident in HBM before the timed region.  One JSON line on
 stdout:
   value     aggregated edges per second = (edges visited by all forward and backward aggregations
-            of a step) / (wall time of a step)
-  roofline  the dominant kernel (the layer-1 forward aggregation): algorithmic bytes per launch
-            over the launch's duration from HIP events recorded on the launch stream in the timed steps
+            of a step, counted for the paper's order of a layer's halves) / (wall time of a step)
+  roofline  the dominant kernel (the forward aggregation that gathers the most bytes): algorithmic bytes
+            per launch over the launch's duration from HIP events recorded on the launch stream in the timed steps
+  call_ms   every C-ABI call between two events on the stream it is enqueued on; the weight-gradient
+            products run on a second stream beside the backward aggregations, so the sum of the entries
+            exceeds the step (ms_per_step is the wall time)
   cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample (reported for
             context; it is not the target)
 
