@@ -104,6 +104,8 @@ def main():
     ap.add_argument("--aggregate-first", action="store_true",
                     help="keep the paper's order (aggregate, then weights) in every layer; by default a GraphSAGE layer that "
                          "narrows its input multiplies by the weights first and gathers the narrower rows")
+    ap.add_argument("--weights-first-all", action="store_true",
+                    help="every narrowing layer in the exchanged order, also those whose input rows are shorter than 512 bytes")
     ap.add_argument("--one-stream", action="store_true",
                     help="enqueue the weight-gradient products on the step's stream instead of a second one")
     ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
@@ -180,7 +182,7 @@ def main():
         if w.model == "gcn":
             gdeg = dev(w.global_graph.degrees().astype(np.int32))[l2g.long()]
         model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg, prefix_numbered=True,
-                            transform_first=False if args.aggregate_first else "auto", side_stream=not args.one_stream)
+                            transform_first=False if args.aggregate_first else (True if args.weights_first_all else "auto"), side_stream=not args.one_stream)
         # the host partition numbers its vertices by ascending id; its feature rows are permuted into ring order
         pos = torch.from_numpy(np.searchsorted(part.local_to_global, l2g.cpu().numpy().astype(np.int64)).astype(np.int32)).cuda()
         H0d = torch.zeros(n, ld0, dtype=dtype, device="cuda")
@@ -192,7 +194,7 @@ def main():
         model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=dtype,
                             global_degree=dev(part.global_degree) if w.model == "gcn" else None,
                             prefix_numbered=sampled_graph is not None,   # the GPU extraction numbers by (distance, id)
-                            transform_first=False if args.aggregate_first else "auto", side_stream=not args.one_stream)
+                            transform_first=False if args.aggregate_first else (True if args.weights_first_all else "auto"), side_stream=not args.one_stream)
         model.set_input(dev(H0).to(dtype))
     if args.layer_sampling:
         f = args.layer_sampling.split(":")

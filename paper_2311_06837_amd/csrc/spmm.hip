@@ -189,6 +189,74 @@ struct Elem<GNN_BF16, 8> {
     }
 };
 
+// two bf16 per lane: narrow rows (up to 32 columns) spread over 16 lanes, so that a tile still holds 16 neighbours
+template <>
+struct Elem<GNN_BF16, 2> {
+    static constexpr int VE = 2;
+    using Raw = uint32_t;
+    static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return *(const uint32_t*)((const uint16_t*)p + off); }
+    static __device__ __forceinline__ void fma(float (&acc)[2], float w, const Raw& r) {
+        acc[0] = fmaf(w, bf16lo(r), acc[0]);
+        acc[1] = fmaf(w, bf16hi(r), acc[1]);
+    }
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[2], int n_valid, bool accumulate,
+                                                 const void* h = nullptr, int64_t hoff = 0) {
+        uint16_t* q = (uint16_t*)p + off;
+        const uint16_t* hq = (const uint16_t*)h + hoff;
+        for (int e = 0; e < 2; ++e) {
+            if (e >= n_valid) break;
+            const float t = accumulate ? bf16_to_f32(q[e]) + v[e] : v[e];
+            q[e] = f32_to_bf16((h == nullptr || (h == p ? t : bf16_to_f32(hq[e])) > 0.f) ? t : 0.f);
+        }
+    }
+};
+
+// four bf16 per lane (33 to 64 columns over 16 lanes)
+template <>
+struct Elem<GNN_BF16, 4> {
+    static constexpr int VE = 4;
+    using Raw = uint2;
+    static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return *(const uint2*)((const uint16_t*)p + off); }
+    static __device__ __forceinline__ void fma(float (&acc)[4], float w, const Raw& r) {
+        acc[0] = fmaf(w, bf16lo(r.x), acc[0]);
+        acc[1] = fmaf(w, bf16hi(r.x), acc[1]);
+        acc[2] = fmaf(w, bf16lo(r.y), acc[2]);
+        acc[3] = fmaf(w, bf16hi(r.y), acc[3]);
+    }
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[4], int n_valid, bool accumulate,
+                                                 const void* h = nullptr, int64_t hoff = 0) {
+        uint16_t* q = (uint16_t*)p + off;
+        const uint16_t* hq = (const uint16_t*)h + hoff;
+        for (int e = 0; e < 4; ++e) {
+            if (e >= n_valid) break;
+            const float t = accumulate ? bf16_to_f32(q[e]) + v[e] : v[e];
+            q[e] = f32_to_bf16((h == nullptr || (h == p ? t : bf16_to_f32(hq[e])) > 0.f) ? t : 0.f);
+        }
+    }
+};
+
+// two floats per lane (17 to 32 columns over 16 lanes)
+template <>
+struct Elem<GNN_F32, 2> {
+    static constexpr int VE = 2;
+    using Raw = float2;
+    static __device__ __forceinline__ Raw load(const void* p, int64_t off) { return *(const float2*)((const float*)p + off); }
+    static __device__ __forceinline__ void fma(float (&acc)[2], float w, const Raw& r) {
+        acc[0] = fmaf(w, r.x, acc[0]);
+        acc[1] = fmaf(w, r.y, acc[1]);
+    }
+    static __device__ __forceinline__ void store(void* p, int64_t off, const float (&v)[2], int n_valid, bool accumulate,
+                                                 const void* h = nullptr, int64_t hoff = 0) {
+        float* q = (float*)p + off;
+        const float* hq = (const float*)h + hoff;
+        for (int e = 0; e < 2; ++e) {
+            if (e >= n_valid) break;
+            const float t = accumulate ? q[e] + v[e] : v[e];
+            q[e] = (h == nullptr || (h == p ? t : hq[e]) > 0.f) ? t : 0.f;
+        }
+    }
+};
+
 template <>
 struct Elem<GNN_BF16, 1> {
     static constexpr int VE = 1;
@@ -1105,8 +1173,18 @@ static int32_t dispatch(const SpmmArgs& a, bool vec_ok, hipStream_t stream) {
     const int F = a.F;
     // any alignment / leading dimension: element-wise lanes, 256 columns per workgroup
     if (!vec_ok) return launch_rows<DT, 1, 64, 4, FILTER>(a, stream);
-    // narrow outputs (class scores, a layer in the exchanged order): fewer lanes per row, more rows per wavefront
-    if (F <= 8 * VE) return launch_rows<DT, VE, 8, 1, FILTER>(a, stream);
+    // Narrow outputs (class scores, a layer in the exchanged order).  A tile of the row kernel is as long as the lanes
+    // that span a row, and a short tile pays the per-tile work (staging, ballots, row claims) for few neighbours: rows
+    // narrower than 16 vectors of 16 bytes keep their 16 lanes and 16-neighbour tiles and take fewer bytes per lane
+    // instead (measured on 64-byte rows: 8 lanes x 16 bytes 2.45 ms, 16 lanes x 4 bytes 1.81 ms).
+    if (DT == GNN_BF16) {
+        if (F <= 16) return launch_rows<GNN_BF16, 1, 16, 1, FILTER>(a, stream);
+        if (F <= 32) return launch_rows<GNN_BF16, 2, 16, 1, FILTER>(a, stream);
+        if (F <= 64) return launch_rows<GNN_BF16, 4, 16, 1, FILTER>(a, stream);
+    } else {
+        if (F <= 16) return launch_rows<GNN_F32, 1, 16, 1, FILTER>(a, stream);
+        if (F <= 32) return launch_rows<GNN_F32, 2, 16, 1, FILTER>(a, stream);
+    }
     if (F <= 16 * VE) return launch_rows<DT, VE, 16, 1, FILTER>(a, stream);
     if (F <= 32 * VE) return launch_rows<DT, VE, 32, 1, FILTER>(a, stream);
     if (F <= 64 * VE) return launch_rows<DT, VE, 64, 1, FILTER>(a, stream);
