@@ -117,7 +117,7 @@ int32_t gnn_norm_scales(int32_t norm, const int32_t *len, const int32_t *row_ptr
  *
  * Workspace (optional).  ws_bytes == NULL: no workspace, one kernel launch that gathers whole rows.
  * With a workspace the call may take the column-blocked route for dense graphs whose gathered
- * matrix is far larger than a cache (average row length >= 64 per column block, columns sorted:
+ * matrix is far larger than a cache (on average at least 8 entries of a row per column block, columns sorted:
  * GNN_CSR_SORTED_COLUMNS, 16-byte aligned operands): the neighbour-id range is cut into 8 blocks
  * per pass, workgroup i works on block i mod 8 (the compute die it runs on), so each die's L2
  * only ever holds one eighth of a 256-byte-wide feature slab; the per-block partial sums (float)
