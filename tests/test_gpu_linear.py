@@ -236,3 +236,8 @@ def test_input_gradient_product_with_sum_and_mask_in_its_store(dtype, K, N):
         assert np.array_equal(got[rest, :K], old[rest]), "rows outside the list were written"
         if ld_in > K:
             assert (got[:, K:] == host64(torch.tensor(SENT, dtype=dtype))).all()
+    # rows to accumulate need the activations of the ReLU they are summed in front of; counts must fit
+    with pytest.raises(P.GnnError):
+        P.gnn_linear_bwd_input(None, 10, padded(dZ, ld_out, dtype), N, dev(W).to(dtype), K, 5, None, padded(old, ld_in, dtype))
+    with pytest.raises(P.GnnError):
+        P.gnn_linear_bwd_input(None, 10, padded(dZ, ld_out, dtype), N, dev(W).to(dtype), K, 11, padded(H, ld_in, dtype), padded(old, ld_in, dtype))

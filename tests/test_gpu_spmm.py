@@ -224,6 +224,9 @@ def test_empty_calls_are_noops():
     import paper_2311_06837_amd as P
     g = gg.erdos_renyi(100, 3.0, 1)
     G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    with pytest.raises(P.GnnError):             # a source prefix is -1 (none) or a vertex count
+        z = torch.zeros(100, 8, device="cuda")
+        P.gnn_masked_spmm_bwd(G, None, 100, None, 0, z, torch.zeros_like(z), 8, src_prefix=-2)
     X = torch.randn(100, 8, device="cuda")
     Y = torch.full((100, 8), 3.0, device="cuda")
     P.gnn_masked_spmm_fwd(G, None, 0, X, Y, 8)
