@@ -187,6 +187,26 @@ int32_t gnn_linear_fwd(const int32_t *rows, int32_t n_active,
                        void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * gnn_linear_fwd for callers that cannot allocate device memory and so have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
+ * (ws, ws_bytes), same kernels, same bits.  The two transposed weight copies go to an array that the library
+ * holds in device memory on every GPU it runs on until the process ends (8 MiB); no hipMalloc / hipFree or other
+ * allocating call is made.
+ *   limit      N * round_up(K, 16 bytes) * element size <= 4 MiB per weight matrix (1024 x 1024 floats,
+ *              2048 x 1024 bf16); beyond it GNN_ERR_UNSUPPORTED - use gnn_linear_fwd
+ *   set-up     the first call on a device looks up the array's address on that device (the device must be
+ *              current, as for every call); a call with n_active == 0 does only that and can serve as set-up
+ *              before a capture starts
+ *   sharing    all calls on one GPU use the same array: calls that overlap there (two streams, two threads)
+ *              race; calls on one stream are ordered and safe.  Nothing has to be cleared between calls: every
+ *              call rewrites what it reads.
+ */
+int32_t gnn_linear_fwd_static(const int32_t *rows, int32_t n_active,
+                              const void *A_neigh, const void *X_self, int64_t ld_in, int32_t K,
+                              const void *W_neigh, const void *W_self, const float *bias, int32_t N,
+                              void *H_out, int64_t ld_out, int32_t relu, int32_t dtype, void *stream);
+
+/*
  * Feature transform, backward (chain rule of the above), for v in rows:
  *     dZ[v]    = relu ? dH_out[v] * [H_out[v] > 0] : dH_out[v]
  *     dW_neigh = sum_v A_neigh[v]^T dZ[v]      dW_self = sum_v X_self[v]^T dZ[v]      dbias = sum_v dZ[v]

@@ -25,7 +25,8 @@ EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_s
            "gnn_masked_spmm_bwd", "gnn_linear_fwd", "gnn_linear_bwd", "gnn_softmax_ce", "gnn_make_bitmap",
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
            "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
-           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked", "gnn_bias_grad", "gnn_linear_bwd_input"]
+           "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked", "gnn_bias_grad", "gnn_linear_bwd_input",
+           "gnn_linear_fwd_static"]
 
 
 class GnnError(RuntimeError):
@@ -311,6 +312,23 @@ def gnn_linear_fwd(rows, n_active: int, A_neigh: torch.Tensor, X_self, K: int, W
               C.c_int32(K), _ptr(W_neigh), _ptr(W_self), _ptr(bias), C.c_int32(N), _ptr(H_out), C.c_int64(H_out.stride(0)),
               C.c_int32(1 if relu else 0), C.c_int32(_dtype_code(A_neigh))),
              (_stream(),), ws)
+
+
+def gnn_linear_fwd_static(rows, n_active: int, A_neigh: torch.Tensor, X_self, K: int, W_neigh: torch.Tensor, W_self, bias,
+                          H_out: torch.Tensor, relu: bool):
+    """gnn_linear_fwd without a workspace: the library's own static device array takes its place (no allocation)."""
+    _mat(A_neigh, "A_neigh"), _mat(H_out, "H_out")
+    N = W_neigh.shape[1]
+    assert W_neigh.shape == (K, N) and W_neigh.is_contiguous() and W_neigh.dtype == A_neigh.dtype == H_out.dtype
+    if X_self is not None:
+        _mat(X_self, "X_self")
+        assert X_self.stride(0) == A_neigh.stride(0) and X_self.dtype == A_neigh.dtype
+        assert W_self.shape == (K, N) and W_self.is_contiguous() and W_self.dtype == W_neigh.dtype
+    assert bias is None or (bias.dtype == torch.float32 and bias.numel() == N)
+    _check(lib().gnn_linear_fwd_static(
+        _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(A_neigh), _ptr(X_self), C.c_int64(A_neigh.stride(0)),
+        C.c_int32(K), _ptr(W_neigh), _ptr(W_self), _ptr(bias), C.c_int32(N), _ptr(H_out), C.c_int64(H_out.stride(0)),
+        C.c_int32(1 if relu else 0), C.c_int32(_dtype_code(A_neigh)), _stream()))
 
 
 def gnn_linear_bwd(rows, n_active: int, dH_out: torch.Tensor, H_out, relu: bool, A_neigh: torch.Tensor, X_self, K: int,

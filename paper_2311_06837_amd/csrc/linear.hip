@@ -20,6 +20,7 @@
 // The next tile is prefetched into registers while the current one feeds the MFMAs.
 // Workgroup ids are remapped so that consecutive tiles share an XCD (and its L2).
 #include "common.h"
+#include <mutex>
 
 namespace gnnhot {
 
@@ -1226,6 +1227,57 @@ extern "C" int32_t gnn_linear_fwd(const int32_t* rows, int32_t n_active, const v
     if (query) return GNN_OK;
     if (n_active == 0) return GNN_OK;
     GNN_REQUIRE(A_neigh && W_neigh && H_out, GNN_ERR_INVALID_ARG, "A_neigh, W_neigh or H_out is NULL");
+    if (dtype == GNN_F32)
+        return linear_fwd_impl<GNN_F32>(rows, n_active, A_neigh, X_self, ld_in, K, W_neigh, W_self, bias, N, H_out, ld_out, relu, Wt0,
+                                        Wt1, ldt, stream);
+    return linear_fwd_impl<GNN_BF16>(rows, n_active, A_neigh, X_self, ld_in, K, W_neigh, W_self, bias, N, H_out, ld_out, relu, Wt0,
+                                     Wt1, ldt, stream);
+}
+
+// ---- the forward transform for callers that cannot allocate ---------------------------------
+// Same kernels as gnn_linear_fwd; the two transposed weight copies live in a file-scope device array instead of a
+// caller's workspace.  Every GPU holds its own copy of the array at its own address: the address is looked up once
+// per device (with that device current) and only that pointer is ever handed to kernels.
+constexpr size_t kStaticWtBytes = (size_t)4 << 20;   // one transposed weight matrix: N * round_up(K) elements
+static __device__ __align__(256) unsigned char scratch[2 * kStaticWtBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static int32_t static_scratch(void** out) {
+    int dev = -1;
+    GNN_HIP(hipGetDevice(&dev));
+    GNN_REQUIRE(dev >= 0 && dev < kMaxDevices, GNN_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        GNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        GNN_REQUIRE(p != nullptr, GNN_ERR_HIP, "the scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return GNN_OK;
+}
+
+extern "C" int32_t gnn_linear_fwd_static(const int32_t* rows, int32_t n_active, const void* A_neigh, const void* X_self,
+                                         int64_t ld_in, int32_t K, const void* W_neigh, const void* W_self, const float* bias,
+                                         int32_t N, void* H_out, int64_t ld_out, int32_t relu, int32_t dtype, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_linear_common(n_active, K, N, dtype));
+    GNN_REQUIRE(ld_in >= K && ld_out >= N, GNN_ERR_SHAPE, "leading dimension smaller than the width");
+    GNN_REQUIRE((X_self == nullptr) == (W_self == nullptr), GNN_ERR_INVALID_ARG, "X_self and W_self must be given together");
+    const int es = dtype == GNN_F32 ? 4 : 2;
+    const int64_t ldt = (int64_t)align_up((size_t)K, 16 / es);
+    const size_t wt_bytes = (size_t)N * ldt * es;
+    GNN_REQUIRE(wt_bytes <= kStaticWtBytes, GNN_ERR_UNSUPPORTED,
+                "weights of %d x %d elements of %d bytes need %zu bytes of scratch per matrix, the static array holds %zu: "
+                "use gnn_linear_fwd with a workspace", K, N, es, wt_bytes, kStaticWtBytes);
+    void* base = nullptr;
+    GNN_CHECK(static_scratch(&base));     // also the set-up call: n_active == 0 resolves the address and returns
+    if (n_active == 0) return GNN_OK;
+    GNN_REQUIRE(A_neigh && W_neigh && H_out, GNN_ERR_INVALID_ARG, "A_neigh, W_neigh or H_out is NULL");
+    char* Wt0 = (char*)base;
+    char* Wt1 = (char*)base + kStaticWtBytes;
     if (dtype == GNN_F32)
         return linear_fwd_impl<GNN_F32>(rows, n_active, A_neigh, X_self, ld_in, K, W_neigh, W_self, bias, N, H_out, ld_out, relu, Wt0,
                                         Wt1, ldt, stream);

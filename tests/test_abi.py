@@ -69,6 +69,10 @@ def test_bad_arguments_return_codes_without_touching_the_gpu(lib):
                               None, C.byref(need), None) == 1
     assert lib.gnn_linear_fwd(None, 0, None, None, C.c_int64(5000), 5000, None, None, None, 4, None, C.c_int64(4), 0, 0, None,
                               C.byref(need), None) == 4
+    # the forward transform without a workspace: weights beyond what the library's static array holds
+    assert lib.gnn_linear_fwd_static(None, 0, None, None, C.c_int64(2048), 2048, None, None, None, 1024, None, C.c_int64(1024), 0, 0,
+                                     None) == 4
+    assert b"static array" in lib.gnn_last_error()
     # sampling: negative fanout, hops != 1
     assert lib.gnn_sample_boundary(C.byref(g), None, None, 0, -1, 1, C.c_uint64(0), None, None, C.c_int64(0), None, None, None,
                                    C.byref(need), None) == 1
