@@ -353,12 +353,77 @@ WORKLOADS = {
 }
 
 
+def _cache_path(name: str, scale: float, seed) -> str | None:
+    import os
+    d = os.environ.get("GRAPHGEN_CACHE")
+    if not d:
+        return None
+    os.makedirs(d, exist_ok=True)
+    return os.path.join(d, f"{name}_s{scale:g}_seed{'d' if seed is None else seed}.npz")
+
+
+def _save_workload(path: str, w: Workload) -> None:
+    """Plain arrays only (numpy's own container, no pickled objects)."""
+    a = {"meta": np.array([w.n_layers, w.fanout, w.seed, w.sample_seed, 1 if w.partition is not None else 0], dtype=np.int64),
+         "dims": np.array(w.dims, dtype=np.int64), "g_rp": w.global_graph.row_ptr, "g_ci": w.global_graph.col_idx,
+         "g_shape": np.array([w.global_graph.n_rows, w.global_graph.n_cols], dtype=np.int64), "tg": w.targets_global}
+    if w.partition is not None:
+        p = w.partition
+        sym = p.graph_t is p.graph
+        a.update({"p_rp": p.graph.row_ptr, "p_ci": p.graph.col_idx, "p_l2g": p.local_to_global, "p_t": p.targets,
+                  "p_deg": p.global_degree, "p_sym": np.array([1 if sym else 0], dtype=np.int64)})
+        if p.graph is w.global_graph:           # the halo is the whole graph: keep one copy
+            a.pop("p_rp"), a.pop("p_ci")
+            a["p_same"] = np.array([1], dtype=np.int64)
+        if not sym:
+            a.update({"pt_rp": p.graph_t.row_ptr, "pt_ci": p.graph_t.col_idx})
+    tmp = path + ".tmp.npz"
+    np.savez(tmp, **a)
+    import os
+    os.replace(tmp, path)
+
+
+def _load_workload(path: str, name: str, model: str, dtype: str) -> Workload:
+    z = np.load(path, allow_pickle=False)
+    n_layers, fanout, seed, sample_seed, has_part = (int(x) for x in z["meta"])
+    g = CSR(int(z["g_shape"][0]), int(z["g_shape"][1]), z["g_rp"], z["g_ci"])
+    part = None
+    if has_part:
+        if "p_same" in z.files:
+            lg = g
+        else:
+            n_loc = z["p_l2g"].shape[0]
+            lg = CSR(n_loc, n_loc, z["p_rp"], z["p_ci"])
+        lt = lg if int(z["p_sym"][0]) else CSR(lg.n_rows, lg.n_cols, z["pt_rp"], z["pt_ci"])
+        part = Partition(lg, lt, z["p_l2g"], z["p_t"], z["p_deg"])
+    return Workload(name, model, dtype, [int(d) for d in z["dims"]], n_layers, part, g, z["tg"], fanout=fanout, seed=seed,
+                    sample_seed=sample_seed)
+
+
+_MODEL_OF = {"cfg0": ("gcn", "f32"), "cfg1": ("sage", "f32"), "cfg2": ("gcn", "f32"), "cfg3": ("sage", "bf16"), "cfg4": ("sage", "bf16")}
+
+
 def make_workload(name: str, scale: float = 1.0, seed: int | None = None) -> Workload:
     """Build the named workload; ``scale`` < 1 shrinks the vertex count (tests).
 
     For cfg4 only the global graph and the target list are made here: the
     local partition depends on the method's boundary sampling.
+
+    With the environment variable GRAPHGEN_CACHE naming a directory, the
+    arrays of a workload are kept there after the first build and read back
+    on later calls (the generators are deterministic, so this only saves time).
     """
+    import os
+    path = _cache_path(name, scale, seed)
+    if path and os.path.exists(path):
+        return _load_workload(path, name, *_MODEL_OF[name])
+    w = _make_workload(name, scale, seed)
+    if path:
+        _save_workload(path, w)
+    return w
+
+
+def _make_workload(name: str, scale: float = 1.0, seed: int | None = None) -> Workload:
     if name == "cfg0":
         s = 0 if seed is None else seed
         n = max(50, int(10_000 * scale))
