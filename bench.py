@@ -7,22 +7,30 @@ matching backward pass.  Inputs are resident in HBM before the timed region.  On
 stdout:
   value     aggregated edges per second = (edges visited by all forward and backward aggregations
             of a step, counted for the paper's order of a layer's halves) / (wall time of a step)
-  roofline  the dominant kernel (the forward aggregation that gathers the most bytes): algorithmic bytes
-            per launch over the launch's duration from HIP events recorded on the launch stream in the timed steps
+  roofline  the dominant kernel (the forward aggregation that gathers the most bytes), against the HBM
+            peak; `frac` is never above 1 by construction, see roofline_of_call()
+  roofline_gemm / roofline_sets / roofline_sampling / roofline_extract   the other steps of the path
   call_ms   every C-ABI call between two events on the stream it is enqueued on; the weight-gradient
             products run on a second stream beside the backward aggregations, so the sum of the entries
             exceeds the step (ms_per_step is the wall time)
   cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample (reported for
             context; it is not the target)
+  others    the same record for the other single-GPU workloads (configs[2], [3], [4]), fewer steps
 
-python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1] [--scale s]
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1] [--others cfg2,cfg3,cfg4 | --no-others]
+
+Counter-derived figures (`traffic`, `mfma_busy`) come from profiles/counters_sidecar.json, which
+bench_counters.py writes from rocprofv3 --pmc runs of this file's --pmc-probe mode; they are used only
+when the sidecar was measured on the same kernel sources (hash of csrc/ and include/), else null.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
+import threading
 import time
 
 import numpy as np
@@ -33,22 +41,36 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
-
+SIDECAR = os.path.join(ROOT, "profiles", "counters_sidecar.json")
 CONFIG_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}
-
-# Traffic between L2 and the memory fabric of the dominant call per launch, from the two rocprofv3 --pmc runs
-# summarised in profiles/spmm_blocked_fwd_cfg1.md and profiles/spmm_rows_and_gemm_cfg4.md (FETCH_SIZE and WRITE_SIZE in
-# KiB, summed over the call's kernels, scaled by what the same counters read for a 1 GiB copy: 2.0 and 1.0).  Known
-# for configs[1] (layer 2; layer 1 in the paper's order, --aggregate-first) and configs[4] at full scale.
-MEASURED_TRAFFIC_KIB = {"cfg1": {2: {"fetch": 230305 + 15972532 + 935683,       # seg + stream + sum_parts kernels
-                                     "write": 8191 + 1864000 + 233000},
-                                 1: {"fetch": 231169 + 40302620 + 2297897, "write": 8192 + 4427085 + 562475}},
-                        "cfg4": {2: {"fetch": 7994957, "write": 1742670}}}       # one spmm_rows_kernel launch
-FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def source_sha() -> str:
+    """Hash of the kernel sources and the header: identifies the build a counter sidecar belongs to."""
+    h = hashlib.sha256()
+    files = [os.path.join(ROOT, "include", "gnnhot.h")]
+    csrc = os.path.join(ROOT, "paper_2311_06837_amd", "csrc")
+    files += sorted(os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def load_sidecar():
+    """The counter sidecar if it exists AND was measured on these sources; else None (figures become null)."""
+    try:
+        d = json.load(open(SIDECAR))
+    except (OSError, ValueError):
+        return None
+    if d.get("source_sha") != source_sha():
+        log(f"[bench] {SIDECAR} was measured on other kernel sources ({d.get('source_sha')}): counter figures are null")
+        return None
+    return d
 
 
 def build_partition(name, scale):
@@ -63,7 +85,8 @@ def build_partition(name, scale):
 
 def sampled_partition_cfg4(w):
     """configs[4], steps a0 and a-1 on the GPU: boundary sampling, then extraction of the local one-hop graph with
-    (distance, id) numbering.  Returns a host-side Partition (for the CPU baseline), the device graph and the two times."""
+    (distance, id) numbering.  Returns a host-side Partition (for the CPU baseline), the device graph and the two times
+    (best of three passes each; the first pass also warms the allocator)."""
     import torch
     import graphgen as gg
     import paper_2311_06837_amd as P
@@ -72,15 +95,17 @@ def sampled_partition_cfg4(w):
     Td = torch.from_numpy(T).cuda()
     ws = P.Workspace()
     bits = P.gnn_make_bitmap(Td, g.n_rows)
-    for _ in range(2):                                                 # first pass warms the allocator, second is timed
+    t_sample, t_extract = float("inf"), float("inf")
+    for _ in range(4):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         rp, ci = P.gnn_sample_boundary(G, bits, Td, w.fanout, w.sample_seed, ws=ws)
         torch.cuda.synchronize()
-        t_sample = time.perf_counter() - t0
+        t1 = time.perf_counter()
         local, l2g, hop = P.gnn_extract_sampled_partition(G, Td, rp, ci, ws=ws)     # symmetric graph: gT = g
         torch.cuda.synchronize()
-        t_extract = time.perf_counter() - t0 - t_sample
+        t2 = time.perf_counter()
+        t_sample, t_extract = min(t_sample, t1 - t0), min(t_extract, t2 - t1)
     kept = int(ci.numel())
     l2g_h = l2g.cpu().numpy().astype(np.int64)
     lg = gg.CSR(local.n_rows, local.n_rows, local.row_ptr.cpu().numpy(), local.col_idx.cpu().numpy())
@@ -88,114 +113,132 @@ def sampled_partition_cfg4(w):
     return part, local, t_sample, t_extract, kept
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg1", choices=sorted(CONFIG_INDEX))
-    ap.add_argument("--scale", type=float, default=1.0, help="shrink the vertex count (debugging only)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--host-partition", action="store_true",
-                    help="run the step on the host-built partition (ascending-id numbering, every call gets a row list) "
-                         "instead of the one built on the GPU from the unpartitioned graph (active sets, extraction with "
-                         "(distance, id) numbering, feature gather: every R_l is an id prefix); full-halo workloads only")
-    ap.add_argument("--extract-on-gpu", action="store_true", help="the default; kept for old command lines")
-    ap.add_argument("--aggregate-first", action="store_true",
-                    help="keep the paper's order (aggregate, then weights) in every layer; by default a GraphSAGE layer that "
-                         "narrows its input multiplies by the weights first and gathers the narrower rows")
-    ap.add_argument("--weights-first-all", action="store_true",
-                    help="every narrowing layer in the exchanged order, also those whose input rows are shorter than 512 bytes")
-    ap.add_argument("--one-stream", action="store_true",
-                    help="enqueue the weight-gradient products on the step's stream instead of a second one")
-    ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
-                    help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
-                         "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
-    ap.add_argument("--res-layers", type=int, default=0, metavar="L",
-                    help="run the deep residual GraphSAGE (ResSAGE+) with L layers of the workload's hidden width on the "
-                         "workload's graph instead of its own model (GraphSAGE workloads); --recompute: activation recomputation")
-    ap.add_argument("--recompute", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    args = ap.parse_args()
-    args.extract_on_gpu = not args.host_partition
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (no sharding or collectives are part of it); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def roofline_of_call(kernels, what, t_s, gather_bytes, compulsory_bytes, blocked, counters):
+    """HBM roofline record of one aggregation call.
 
+    gather model   every neighbour row of every edge comes from memory (no reuse): index + row per edge, row_ptr +
+                   output row per active row.  What a gather kernel WITHOUT designed reuse must move.
+    compulsory     every input row, index and output row exactly once (perfect reuse): the lower bound.
+    `achieved` / `frac` (never above 1):
+      one-launch route   gather-model bytes / time, capped at what the counters say crossed the fabric when a same-build
+                         counter reading exists and is smaller (reuse the caches found on their own)
+      column-blocked     its point is reuse inside the compute dies' L2s, so gather-model bytes are not memory bytes:
+                         counter bytes (L2 <-> fabric) / time when a same-build reading exists, else the compulsory bytes
+                         / time (a floor).  The gather-model rate is reported separately as gather_GBs.
+    """
+    traffic = None
+    extra = {}
+    if counters:
+        traffic = counters.get("traffic_bytes")
+        extra = {k: counters[k] for k in ("fetch_bytes_by_request_size", "write_bytes", "fetch_size_KiB", "write_size_KiB",
+                                          "tcc_hit", "tcc_miss", "l2_hit_rate") if k in counters}
+    if blocked:
+        basis = "counters (L2<->fabric bytes of the same build)" if traffic else "compulsory bytes (no same-build counter reading)"
+        ach_bytes = traffic if traffic else compulsory_bytes
+    else:
+        ach_bytes, basis = gather_bytes, "gather model"
+        if traffic and traffic < gather_bytes:
+            ach_bytes, basis = traffic, "counters (below the gather model: cache reuse)"
+    ach = ach_bytes / t_s / 1e9
+    return {
+        "kernel": f"{kernels}; {what}", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": ach / HBM_PEAK_GBS, "frac_basis": basis,
+        "traffic": traffic, "traffic_GBs": None if traffic is None else traffic / t_s / 1e9,
+        "bytes_per_launch": ach_bytes, "launch_ms": t_s * 1e3,
+        "gather_bytes_per_launch": gather_bytes, "gather_GBs": gather_bytes / t_s / 1e9,
+        "compulsory_bytes_per_launch": compulsory_bytes, "compulsory_GBs": compulsory_bytes / t_s / 1e9,
+        "frac_compulsory": compulsory_bytes / t_s / 1e9 / HBM_PEAK_GBS, **extra,
+    }
+
+
+def simple_roofline(kernel, t_s, alg_bytes, counters=None, note=None):
+    out = {"kernel": kernel, "bound": "hbm", "achieved": alg_bytes / t_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": alg_bytes / t_s / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": alg_bytes, "launch_ms": t_s * 1e3,
+           "traffic": counters.get("traffic_bytes") if counters else None}
+    if note:
+        out["note"] = note
+    return out
+
+
+class Setup:
+    """Everything of one workload that lives on the GPU before the timed region."""
+    pass
+
+
+def setup_workload(args, name):
     import torch
     import graphgen as gg
     import paper_2311_06837_amd as P
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    w = build_partition(args.workload, args.scale)
-    t_sample, kept, t_extract, sampled_graph = None, None, None, None
+    w = build_partition(name, args.scale)
+    S = Setup()
+    S.w, S.name = w, name
+    S.t_sample = S.kept = S.t_extract = S.sampled_graph = None
     if w.partition is None:
-        part, sampled_graph, t_sample, t_extract, kept = sampled_partition_cfg4(w)
-        log(f"[bench] GPU sampling {t_sample * 1e3:.2f} ms, GPU extraction of the sampled partition {t_extract * 1e3:.2f} ms")
+        S.part, S.sampled_graph, S.t_sample, S.t_extract, S.kept = sampled_partition_cfg4(w)
+        log(f"[bench] GPU sampling {S.t_sample * 1e3:.2f} ms, GPU extraction of the sampled partition {S.t_extract * 1e3:.2f} ms")
     else:
-        part = w.partition
-    dtype = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    sage = w.model == "sage"
-    n = part.graph.n_rows
+        S.part = w.partition
+    part = S.part
+    S.dtype = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    S.sage = w.model == "sage"
+    S.n = n = part.graph.n_rows
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-
-    params = gg.layer_weights(w.dims, sage, w.seed)
-    dparams = [{k: dev(v) for k, v in p.items()} for p in params]
-    ld0 = P.row_stride(w.dims[0], dtype)
-    H0 = gg.features(n, w.dims[0], w.seed, ld=ld0)
-    n_layers = len(w.dims) - 1
-
+    S.params = gg.layer_weights(w.dims, S.sage, w.seed)
+    dparams = [{k: dev(v) for k, v in p.items()} for p in S.params]
+    ld0 = P.row_stride(w.dims[0], S.dtype)
+    S.H0 = gg.features(n, w.dims[0], w.seed, ld=ld0)
+    S.n_layers = len(w.dims) - 1
+    S.edges_traversed = None
     if args.res_layers:
-        return bench_res_model(args, w, part, sampled_graph, dtype)
+        return S
 
     # Step (a-1) of the path, outside the timed step like the sampling: the partition's one-hop graph extracted on
-    # the GPU from the unpartitioned graph, vertices renumbered by (distance, id).  Timed always (full-halo
-    # workloads); used for the run with --extract-on-gpu.
-    gpu_part = None
+    # the GPU from the unpartitioned graph, vertices renumbered by (distance, id).
+    S.gpu_part, S.pos = None, None
     if w.partition is not None:
         Gg = P.Graph.from_numpy(w.global_graph.row_ptr, w.global_graph.col_idx)
         Tg = dev(w.targets_global.astype(np.int32))
         ews = P.Workspace()
-        for rep_i in range(2):       # first pass warms the allocator, second is timed
+        S.t_extract = float("inf")
+        for rep_i in range(3):       # first pass warms the allocator
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            gdist, gring, _, ghop = P.gnn_build_active_sets(Gg, Tg, n_layers, ws=ews)
-            local, new_id = P.gnn_extract_partition(Gg, gring, int(ghop[-1]), gdist, n_layers, ws=ews)
+            gdist, gring, _, ghop = P.gnn_build_active_sets(Gg, Tg, S.n_layers, ws=ews)
+            local, new_id = P.gnn_extract_partition(Gg, gring, int(ghop[-1]), gdist, S.n_layers, ws=ews)
             torch.cuda.synchronize()
-            t_extract = time.perf_counter() - t0
+            S.t_extract = min(S.t_extract, time.perf_counter() - t0)
         assert local.n_rows == n and local.nnz == part.graph.nnz, "GPU extraction disagrees with the host-built partition"
-        log(f"[bench] GPU extraction of the partition (active sets of the unpartitioned graph + sub-graph): {t_extract * 1e3:.2f} ms")
-        if args.extract_on_gpu:
-            gpu_part = (local, gring[:n].clone())
-        del Gg, gdist, new_id
-        if not args.extract_on_gpu:
-            del local, gring
+        log(f"[bench] GPU extraction of the partition (active sets of the unpartitioned graph + sub-graph): {S.t_extract * 1e3:.2f} ms")
+        S.edges_traversed = int(w.global_graph.degrees()[part.local_to_global].astype(np.int64).sum())
+        if not args.host_partition:
+            S.gpu_part = (local, gring[:n].clone())
+        del Gg, gdist, new_id, local, gring
 
-    if gpu_part is not None:
-        G, l2g = gpu_part
-        GT = G                                   # the workloads' graphs are symmetric
+    tf = False if args.aggregate_first else (True if args.weights_first_all else "auto")
+    if S.gpu_part is not None:
+        G, l2g = S.gpu_part
         t_dev = torch.arange(len(part.targets), dtype=torch.int32, device="cuda")
         gdeg = None
         if w.model == "gcn":
             gdeg = dev(w.global_graph.degrees().astype(np.int32))[l2g.long()]
-        model = P.MaskedGNN(G, GT, t_dev, w.model, dparams, dtype=dtype, global_degree=gdeg, prefix_numbered=True,
-                            transform_first=False if args.aggregate_first else (True if args.weights_first_all else "auto"), side_stream=not args.one_stream)
+        model = P.MaskedGNN(G, G, t_dev, w.model, dparams, dtype=S.dtype, global_degree=gdeg, prefix_numbered=True,
+                            transform_first=tf, side_stream=not args.one_stream, fused_forward=args.fused,
+                            grad_first=False if args.chain_rule_order else "auto")
         # the host partition numbers its vertices by ascending id; its feature rows are permuted into ring order
-        pos = torch.from_numpy(np.searchsorted(part.local_to_global, l2g.cpu().numpy().astype(np.int64)).astype(np.int32)).cuda()
-        H0d = torch.zeros(n, ld0, dtype=dtype, device="cuda")
-        P.gnn_gather_rows(dev(H0).to(dtype), pos, w.dims[0], H0d)
+        S.pos = torch.from_numpy(np.searchsorted(part.local_to_global, l2g.cpu().numpy().astype(np.int64)).astype(np.int32)).cuda()
+        H0d = torch.zeros(n, ld0, dtype=S.dtype, device="cuda")
+        P.gnn_gather_rows(dev(S.H0).to(S.dtype), S.pos, w.dims[0], H0d)
         model.set_input(H0d)
     else:
-        G = sampled_graph if sampled_graph is not None else P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
+        G = S.sampled_graph if S.sampled_graph is not None else P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
         GT = G if part.graph_t is part.graph else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
-        model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=dtype,
+        model = P.MaskedGNN(G, GT, dev(part.targets), w.model, dparams, dtype=S.dtype,
                             global_degree=dev(part.global_degree) if w.model == "gcn" else None,
-                            prefix_numbered=sampled_graph is not None,   # the GPU extraction numbers by (distance, id)
-                            transform_first=False if args.aggregate_first else (True if args.weights_first_all else "auto"), side_stream=not args.one_stream)
-        model.set_input(dev(H0).to(dtype))
+                            prefix_numbered=S.sampled_graph is not None,   # the GPU extraction numbers by (distance, id)
+                            transform_first=tf, side_stream=not args.one_stream, fused_forward=args.fused,
+                            grad_first=False if args.chain_rule_order else "auto")
+        model.set_input(dev(S.H0).to(S.dtype))
     if args.layer_sampling:
         f = args.layer_sampling.split(":")
         seed_ls = int(f[2]) if len(f) > 2 else 1
@@ -204,40 +247,61 @@ def main():
         else:
             pk = float(f[1])
             model.layer_sampling = ("threshold", (1 << 64) - 1 if pk >= 1.0 else max(0, int(pk * (1 << 64)) - 1), seed_ls)
-    labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
+    S.G, S.model = G, model
+    S.labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
     log(f"[bench] partition: n={n} nnz={part.graph.nnz} |T|={len(part.targets)} model={w.model} dims={w.dims} dtype={w.dtype}")
+    return S
 
-    for _ in range(args.warmup):
-        model.step(labels)
+
+def dominant_layer(model, edges):
+    """The forward aggregation that gathers the most bytes (the later layer on a tie: the plain call rather than the
+    first layer's add-on-top form)."""
+    return max(range(1, model.L + 1), key=lambda l: (edges[l]["fwd"] * model.agg_width(l), l))
+
+
+def run_workload(args, name, steps, warmup, cpu_flops):
+    import torch
+    import graphgen as gg
+    import paper_2311_06837_amd as P
+
+    S = setup_workload(args, name)
+    w, part, model, dtype = S.w, S.part, getattr(S, "model", None), S.dtype
+    if args.res_layers:
+        return bench_res_model(args, w, part, S.sampled_graph, dtype, steps, warmup)
+    n, G = S.n, S.G
+
+    for _ in range(warmup):
+        model.step(S.labels)
     torch.cuda.synchronize()
     model.trace = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        model.step(labels)
+    for _ in range(steps):
+        model.step(S.labels)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     trace, model.trace = model.trace, None
-    ms_per_step = wall / args.steps * 1e3
+    ms_per_step = wall / steps * 1e3
 
     per_call = {}
-    for name, a, b in trace:
-        per_call.setdefault(name, []).append(a.elapsed_time(b))
+    for nm, a, b in trace:
+        per_call.setdefault(nm, []).append(a.elapsed_time(b))
     call_ms = {k: float(np.mean(v)) for k, v in per_call.items()}
     edges = model.aggregated_edges()
     total_edges = sum(e["fwd"] + e["bwd"] for e in edges.values())
     hop = [int(x) for x in model.hop]
     L = model.L
     es = 4 if dtype == torch.float32 else 2
+    sidecar = load_sidecar()
+    side = (sidecar or {}).get("workloads", {}).get(name, {}) if args.scale == 1.0 else {}
 
-    # a first layer in the exchanged order splits its feature transform into two calls each way
+    # a layer in the exchanged order splits its feature transform into two calls each way
     lin_f = lambda l: call_ms.get(f"linear_fwd_{l}", 0.0) + call_ms.get(f"linear_pre_{l}", 0.0)
     lin_b = lambda l: (call_ms.get(f"linear_bwd_{l}", 0.0) + call_ms.get(f"linear_bwd_{l}_neigh", 0.0) +
                        call_ms.get(f"linear_bwd_{l}_input", 0.0) + call_ms.get(f"linear_bwd_{l}_input_self", 0.0))
 
-    # per-layer report
     layers = {}
     for l in range(1, L + 1):
-        t_f = call_ms.get(f"spmm_fwd_{l}", 0.0)
+        t_f = call_ms.get(f"spmm_fwd_{l}", 0.0) + call_ms.get(f"fused_fwd_{l}", 0.0)   # fused: aggregation and transform together
         t_b = call_ms.get(f"spmm_bwd_{l}", 0.0) + call_ms.get(f"spmm_bwd_{l}_ring", 0.0)
         e = edges[l]
         F = model.agg_width(l)
@@ -251,42 +315,30 @@ def main():
             "spmm_fwd_gather_GBs": gather_bytes / (t_f * 1e-3) / 1e9 if t_f > 0 else None,
         }
 
-    # roofline of the dominant kernel: the forward aggregation that gathers the most bytes (the later layer on a tie:
-    # the plain call rather than the first layer's add-on-top form)
-    dom = max(range(1, L + 1), key=lambda l: (edges[l]["fwd"] * model.agg_width(l), l))
+    # ---- roofline of the dominant kernel
+    dom = dominant_layer(model, edges)
     Fd = model.agg_width(dom)
     nd = model.n_rows_of_layer(dom)
     n_in = model.n_rows_of_layer(dom - 1) if dom > 1 else int(hop[L + 1])
-    alg_bytes = edges[dom]["fwd"] * (4 + Fd * es) + nd * (8 + Fd * es)           # gather model
-    compulsory = edges[dom]["fwd"] * 4 + n_in * Fd * es + nd * (8 + Fd * es)     # every input row read once
-    t_dom = call_ms[f"spmm_fwd_{dom}"] * 1e-3
-    src_dom, dst_dom = (model.P[dom], model.H[dom]) if dom in model.tf_layers else (model.H[dom - 1], model.A[dom])
-    blocked = P.binding.spmm_workspace_bytes(G, nd, src_dom, dst_dom, Fd) > 0
-    kernels = ("spmm_stream_kernel (+ spmm_seg_kernel before and spmm_sum_parts_kernel after it: column-blocked route)"
-               if blocked else "spmm_rows_kernel")
-    kib = MEASURED_TRAFFIC_KIB.get(args.workload, {}).get(dom) if args.scale == 1.0 else None
-    if dom == 1 and 1 in model.tf_layers:        # (the layer-1 figures are those of the 602-wide gather)
-        kib = None
-    traffic = None
-    if kib:
-        traffic = (kib["fetch"] * FETCH_SCALE + kib["write"] * WRITE_SCALE) * 1024
-    # `achieved` counts the ALGORITHMIC bytes of the gather model (every neighbour row of every edge); on the
-    # column-blocked route most of them are served by the L2 of the compute die, so it can exceed the HBM peak.
-    # `traffic` is what actually crossed from L2 to the memory fabric, `traffic_GBs` the same per second.
-    roofline = {
-        "kernel": f"{kernels}; gnn_masked_spmm_fwd, layer {dom}, F={Fd}",
-        "bound": "hbm", "achieved": alg_bytes / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS,
-        "traffic": traffic, "traffic_GBs": None if traffic is None else traffic / t_dom / 1e9,
-        "bytes_per_launch": alg_bytes, "launch_ms": t_dom * 1e3,
-        "compulsory_bytes_per_launch": compulsory, "compulsory_GBs": compulsory / t_dom / 1e9,
-    }
-    # the feature-transform GEMMs against the MFMA peak of their data type
+    gather_bytes = edges[dom]["fwd"] * (4 + Fd * es) + nd * (8 + Fd * es)
+    compulsory = edges[dom]["fwd"] * 4 + n_in * Fd * es + nd * (8 + Fd * es)
+    t_dom = (call_ms.get(f"spmm_fwd_{dom}") or call_ms[f"fused_fwd_{dom}"]) * 1e-3
+    if dom in model.fused_layers:
+        blocked, kernels = False, "fused_agg_linear_kernel (aggregation and feature transform in one kernel)"
+    else:
+        src_dom, dst_dom = (model.P[dom], model.H[dom]) if dom in model.tf_layers else (model.H[dom - 1], model.A[dom])
+        blocked = P.binding.spmm_workspace_bytes(G, nd, src_dom, dst_dom, Fd) > 0
+        kernels = ("spmm_stream_kernel (+ spmm_seg_kernel before and spmm_sum_parts_kernel after it: column-blocked route)"
+                   if blocked else "spmm_rows_kernel")
+    c_dom = side.get("spmm_fwd_dom") if side.get("dominant_layer") == dom else None
+    roofline = roofline_of_call(kernels, f"gnn_masked_spmm_fwd, layer {dom}, F={Fd}", t_dom, gather_bytes, compulsory, blocked, c_dom)
+
+    # ---- the feature-transform GEMMs against the MFMA peak of their data type and the roof that binds
     gemm = {}
     for l in range(1, L + 1):
         K, N = w.dims[l - 1], w.dims[l]
         nl = model.n_rows_of_layer(l)
-        srcs = 2 if sage else 1
+        srcs = 2 if S.sage else 1
         f_fwd = 2.0 * nl * K * N * srcs
         f_bwd = f_fwd * (2 if l > 1 else 1)
         tf, tb = lin_f(l) * 1e-3, lin_b(l) * 1e-3
@@ -305,54 +357,283 @@ def main():
                         "bwd_TFLOPs": f_bwd / tb / 1e12 if tb > 0 else None, "bwd_frac_mfma": f_bwd / tb / 1e12 / peak if tb > 0 else None,
                         "bwd_GBs": b_bwd / tb / 1e9 if tb > 0 else None,
                         "bwd_binds": "hbm" if b_bwd / (HBM_PEAK_GBS * 1e9) > f_bwd / (peak * 1e12) else "mfma",
-                        "bwd_frac_roof": roof_b / tb if tb > 0 else None}
+                        "bwd_frac_roof": roof_b / tb if tb > 0 else None,
+                        "bwd_timing": "sum of the layer's backward product calls; the weight-gradient product shares the GPU with an "
+                                      "aggregation on the other stream unless --one-stream" if not args.one_stream else "one stream"}
+        if l == dom:
+            for key in ("linear_fwd_dom", "linear_bwd_dom"):
+                if key in side:
+                    gemm[str(l)][key + "_counters"] = side[key]
 
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    # ---- set expansion: 4 B per frontier edge (rows of rings 0 .. L-1), 8 B row bounds per frontier vertex, 8 B (distance and
+    # ring-list entry) per reached vertex
+    rp = model.g.row_ptr.long()
+    ring = model.ring_ids.long()
+    n_front = int(hop[L])
+    frontier_edges = int((rp[ring[:n_front] + 1] - rp[ring[:n_front]]).sum().item())
+    reached = int(hop[L + 1])
+    sets_bytes = 4 * frontier_edges + 8 * n_front + 8 * reached
+    t_sets = call_ms["active_sets"] * 1e-3
+    roof_sets = simple_roofline(f"as_expand / as_count / as_emit kernels; gnn_build_active_sets, L={L}", t_sets, sets_bytes,
+                                side.get("active_sets"))
+    roof_sets.update({"frontier_edges": frontier_edges, "reached_vertices": reached, "levels": L,
+                      "edges_per_s": frontier_edges / t_sets})
+    roof_sampling = None
+    if S.t_sample is not None:
+        deg_t = w.global_graph.degrees()[w.targets_global].astype(np.int64)
+        cand = int(deg_t.sum())
+        nt = int(w.targets_global.size)
+        samp_bytes = 4 * cand + 8 * nt + 4 * S.kept + 4 * (nt + 1)
+        roof_sampling = simple_roofline("sb_count_kernel + sb_fill_kernel; gnn_sample_boundary (count and fill pass, host "
+                                        "allocation of the output between them)", S.t_sample, samp_bytes, side.get("sampling"))
+        roof_sampling.update({"candidate_edges": cand, "kept_edges": S.kept, "targets": nt, "edges_per_s": cand / S.t_sample})
+    roof_extract = None
+    if S.t_extract is not None:
+        if S.edges_traversed is not None:      # full halo: active sets of the unpartitioned graph + induced sub-graph
+            ex_bytes = 4 * S.edges_traversed + 8 * n + 4 * part.graph.nnz + 8 * n
+            what = "gnn_build_active_sets on the unpartitioned graph + gnn_extract_partition (count and fill pass)"
+        else:                                  # sampled: kept rows -> rings -> local rows
+            ex_bytes = 4 * S.kept + 8 * n + 4 * part.graph.nnz + 8 * n
+            what = "gnn_expand_row_ptr + gnn_build_active_sets + gnn_extract_sampled_partition (count and fill pass)"
+        roof_extract = simple_roofline(what, S.t_extract, ex_bytes, None,
+                                       note="wall time of the whole chain incl. two host round trips for output sizes")
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_flops > 0:
         rows1 = model.ring_ids[: model.n_rows_of_layer(1)]
-        if gpu_part is not None:     # same vertices in the host partition's numbering (H0 and part.graph use it)
-            rows1 = pos[rows1.long()]
-        cpu = cpu_baseline(part, w, params, H0, rows1.cpu().numpy())
+        if S.pos is not None:     # same vertices in the host partition's numbering (H0 and part.graph use it)
+            rows1 = S.pos[rows1.long()]
+        cpu = cpu_baseline(part, w, S.params, S.H0, rows1.cpu().numpy(), cpu_flops)
 
     out = {
-        "metric": "aggregated_edges_per_sec", "value": total_edges / (wall / args.steps), "unit": "edges/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "aggregated_edges_per_sec", "value": total_edges / (wall / steps), "unit": "edges/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{CONFIG_INDEX[args.workload]}]: {gg.WORKLOADS[args.workload]}",
+        "config": {"workload": f"configs[{CONFIG_INDEX[name]}]: {gg.WORKLOADS[name]}",
                    "scale": args.scale, "n_local": n, "nnz_local": part.graph.nnz, "targets": len(part.targets),
                    "hop_offsets": hop, "layers": L},
         "epoch_ms": sum(v for k, v in call_ms.items() if k != "active_sets"),
         "active_sets_ms": call_ms.get("active_sets"),
-        "sampling_ms": None if t_sample is None else t_sample * 1e3, "sampled_edges": kept,
-        "extract_ms": None if t_extract is None else t_extract * 1e3,
-        "partition_built_on": "gpu ((distance, id) numbering)" if (gpu_part is not None or sampled_graph is not None)
+        "sampling_ms": None if S.t_sample is None else S.t_sample * 1e3, "sampled_edges": S.kept,
+        "extract_ms": None if S.t_extract is None else S.t_extract * 1e3,
+        "partition_built_on": "gpu ((distance, id) numbering)" if (S.gpu_part is not None or S.sampled_graph is not None)
                               else "host (ascending-id numbering)",
         "aggregated_edges_per_step": total_edges,
-        "layers_weights_first": sorted(model.tf_layers),
+        "layers_weights_first": sorted(model.tf_layers), "layers_gradient_aggregated_first": sorted(model.gf_layers),
+        "layers_fused_forward": sorted(model.fused_layers),
         "layer_sampling": args.layer_sampling,
         "layer_mask_ms": sum(v for k, v in call_ms.items() if k.startswith("layer_mask")) if args.layer_sampling else None,
-        "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "cpu_baseline": cpu,
+        "per_layer": layers, "roofline": roofline, "roofline_gemm": gemm, "roofline_sets": roof_sets,
+        "roofline_sampling": roof_sampling, "roofline_extract": roof_extract, "cpu_baseline": cpu,
+        "counters_sidecar": None if not side else {"source_sha": sidecar["source_sha"], "file": "profiles/counters_sidecar.json"},
         "call_ms": {k: round(v, 4) for k, v in call_ms.items()},
     }
+    del model, S
+    torch.cuda.empty_cache()
+    return out
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# counter probe: the calls whose counters profiles/ reports, each repeated a few times from a thread of its own, so
+# that a rocprofv3 --pmc run of this mode can be split by the Thread_Id column (see bench_counters.py)
+# ---------------------------------------------------------------------------------------------------------------
+def pmc_probe(args, name, manifest_path, repeats=3):
+    import torch
+    import paper_2311_06837_amd as P
+
+    args.one_stream = True
+    S = setup_workload(args, name)
+    model, w = S.model, S.w
+    model.step(S.labels)            # every buffer of the step holds real values; also the lazy module loads
+    torch.cuda.synchronize()
+    edges = model.aggregated_edges()
+    dom = dominant_layer(model, edges)
+    L = model.L
+    groups = {}
+
+    def in_thread(tag, fn):
+        box = {}
+
+        def body():
+            torch.cuda.set_device(0)
+            box["tid"] = threading.get_native_id()
+            for _ in range(repeats):
+                fn()
+            torch.cuda.synchronize()
+        th = threading.Thread(target=body)
+        th.start()
+        th.join()
+        groups[tag] = {"thread_id": box["tid"], "repeats": repeats}
+
+    p = model.params[dom - 1]
+    K, N = model.dims[dom - 1], model.dims[dom]
+    nl = model.n_rows_of_layer(dom)
+    sage = model.kind == "sage"
+    assert dom not in model.tf_layers, "the probe expects the dominant call in the paper's order"
+    in_thread("active_sets", lambda: model.build_active_sets())
+    in_thread("spmm_fwd_dom", lambda: P.gnn_masked_spmm_fwd(model.g, model.rows, nl, model.H[dom - 1], model.A[dom], K, model.rs,
+                                                            model.cs, ws=model.ws))
+    in_thread("linear_fwd_dom", lambda: P.gnn_linear_fwd(model.rows, nl, model.A[dom], model.H[dom - 1] if sage else None, K,
+                                                         p["W_neigh"], p.get("W_self"), p["bias"], model.H[dom], relu=(dom < L),
+                                                         ws=model.ws))
+    gr = model.grads[dom - 1]
+    if dom > 1:
+        in_thread("linear_bwd_dom", lambda: P.gnn_linear_bwd(model.rows, nl, model.dH[dom], None, False, model.A[dom],
+                                                             model.H[dom - 1] if sage else None, K, p["W_neigh"], p.get("W_self"),
+                                                             gr["dW_neigh"], gr.get("dW_self"), gr["dbias"], model.dA[dom],
+                                                             model.dH[dom - 1] if sage else None, ws=model.ws))
+    if w.partition is None:        # configs[4]: the sampler
+        g = w.global_graph
+        Gg = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+        Td = torch.from_numpy(w.targets_global.astype(np.int32)).cuda()
+        bits = P.gnn_make_bitmap(Td, g.n_rows)
+        sws = P.Workspace()
+        P.gnn_sample_boundary(Gg, bits, Td, w.fanout, w.sample_seed, ws=sws)
+        in_thread("sampling", lambda: P.gnn_sample_boundary(Gg, bits, Td, w.fanout, w.sample_seed, ws=sws))
+    # a plain copy of known size: what the byte counters read for it scales the readings of the other groups
+    n_copy, f_copy = 1 << 20, 256
+    src = torch.empty(n_copy, f_copy, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    ids = torch.arange(n_copy, dtype=torch.int32, device="cuda")
+    P.gnn_gather_rows(src, ids, f_copy, dst)
+    in_thread("copy_calibration", lambda: P.gnn_gather_rows(src, ids, f_copy, dst))
+    groups["copy_calibration"].update({"bytes_read": n_copy * f_copy * 4 + n_copy * 4, "bytes_written": n_copy * f_copy * 4})
+    json.dump({"workload": name, "source_sha": source_sha(), "dominant_layer": dom, "groups": groups,
+               "shapes": {"rows": nl, "K": K, "N": N, "edges_fwd": edges[dom]["fwd"], "sage": sage, "dtype": w.dtype}},
+              open(manifest_path, "w"))
+    log(f"[bench] probe manifest -> {manifest_path}")
+
+
+def eas_bench(args, name):
+    """The paper's expansion-aware traversal (section 5.3.1) on the workload's unpartitioned graph, one cell (hops, fanout,
+    rule) of its sensitivity grid per entry of --eas: traversal and extraction times and the size of the halo."""
+    import torch
+    import paper_2311_06837_amd as P
+    w = build_partition(name, args.scale)
+    g = w.global_graph
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    Td = torch.from_numpy(w.targets_global.astype(np.int32)).cuda()
+    ws = P.Workspace()
+    cells = []
+    for cell in args.eas.split(","):
+        f = cell.split(":")
+        hops, fanout, rule = int(f[0]), int(f[1]), (f[2] if len(f) > 2 else "degree")
+        best_t, best_e = float("inf"), float("inf")
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            dist, ring, off, hop = P.gnn_eas_traverse(G, Td, hops, fanout, rule=rule, seed=w.sample_seed, ws=ws)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            local, _ = P.gnn_extract_partition(G, ring, int(hop[-1]), dist, hops, ws=ws)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            best_t, best_e = min(best_t, t1 - t0), min(best_e, t2 - t1)
+        deg = g.degrees().astype(np.int64)
+        ring_h = ring[: int(hop[-1])].cpu().numpy()
+        front = ring_h[: int(hop[hops])]
+        e_front = int(deg[front].sum())
+        # the degree rule reads the whole graph once per hop (connection counts); both rules read the frontier rows
+        alg = 4 * e_front + (4 * g.nnz * hops if rule == "degree" else 0) + 8 * int(hop[-1])
+        cells.append({"hops": hops, "fanout": fanout, "rule": rule, "traverse_ms": best_t * 1e3, "extract_ms": best_e * 1e3,
+                      "halo_vertices": int(hop[-1]) - int(hop[1]), "local_vertices": int(hop[-1]), "local_edges": local.nnz,
+                      "ring_sizes": [int(hop[j + 1]) - int(hop[j]) for j in range(hops + 1)],
+                      "frontier_edges": e_front, "algorithmic_GBs": alg / best_t / 1e9,
+                      "frac_hbm_peak": alg / best_t / 1e9 / HBM_PEAK_GBS})
+        log(f"[bench] eas {cell}: traverse {best_t * 1e3:.2f} ms, extract {best_e * 1e3:.2f} ms, local n={int(hop[-1])} nnz={local.nnz}")
+    return {"metric": "eas_traversal_ms", "unit": "ms", "n_gpus": 1, "data": "synthetic",
+            "config": {"workload": f"expansion-aware traversal on the unpartitioned graph of configs[{CONFIG_INDEX[name]}]",
+                       "n": g.n_rows, "nnz": g.nnz, "targets": int(w.targets_global.size)},
+            "cells": cells}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg1", choices=sorted(CONFIG_INDEX))
+    ap.add_argument("--others", default=None, metavar="cfgA,cfgB",
+                    help="workloads reported under the `others` key of the same JSON line (default: cfg2,cfg3,cfg4 when the "
+                         "headline is cfg1 and no special mode is on; each with at most 5 timed steps and a smaller CPU sample)")
+    ap.add_argument("--no-others", action="store_true")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the vertex count (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--host-partition", action="store_true",
+                    help="run the step on the host-built partition (ascending-id numbering, every call gets a row list) "
+                         "instead of the one built on the GPU from the unpartitioned graph (active sets, extraction with "
+                         "(distance, id) numbering, feature gather: every R_l is an id prefix); full-halo workloads only")
+    ap.add_argument("--extract-on-gpu", action="store_true", help="the default; kept for old command lines")
+    ap.add_argument("--aggregate-first", action="store_true",
+                    help="keep the paper's order (aggregate, then weights) in every layer; by default a GraphSAGE layer that "
+                         "narrows its input multiplies by the weights first and gathers the narrower rows")
+    ap.add_argument("--weights-first-all", action="store_true",
+                    help="every narrowing layer in the exchanged order, also those whose input rows are shorter than 512 bytes")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="enqueue the weight-gradient products on the step's stream instead of a second one (then every "
+                         "call_ms entry is that call alone on the GPU)")
+    ap.add_argument("--fused", action="store_true",
+                    help="GraphSAGE layers of a shape gnn_fused_layer_fwd takes run aggregation and feature transform as one kernel "
+                         "(the aggregate never leaves the chip); off by default")
+    ap.add_argument("--chain-rule-order", action="store_true",
+                    help="backward pass: input gradients per half and an accumulating aggregation (the order the chain rule gives) "
+                         "instead of one product from the aggregated output gradient")
+    ap.add_argument("--layer-sampling", default=None, metavar="RULE:PARAM[:SEED]",
+                    help="layer-wise sampling as per-layer edge masks, rebuilt every step: fanout:F (neighbours kept per "
+                         "row and layer) or dropedge:P (every edge kept with probability P per layer); off by default")
+    ap.add_argument("--res-layers", type=int, default=0, metavar="L",
+                    help="run the deep residual GraphSAGE (ResSAGE+) with L layers on the workload's graph instead of its own "
+                         "model (GraphSAGE workloads); --res-hidden: its hidden width (default: the workload's); "
+                         "--recompute: activation recomputation")
+    ap.add_argument("--res-hidden", type=int, default=0)
+    ap.add_argument("--recompute", action="store_true")
+    ap.add_argument("--eas", default=None, metavar="H:F[:RULE],...",
+                    help="time the expansion-aware traversal (hops H, fanout F, rule degree|hash) and the extraction of its "
+                         "sub-graph on the workload's unpartitioned graph, one JSON line with a record per cell")
+    ap.add_argument("--pmc-probe", default=None, metavar="MANIFEST.json",
+                    help="counter probe for rocprofv3 --pmc runs (driven by bench_counters.py): the dominant aggregation, its "
+                         "layer's feature transforms, set expansion, sampling and a plain copy, each from a thread of its own")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding or collectives are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.pmc_probe:
+        return pmc_probe(args, args.workload, args.pmc_probe)
+    if args.eas:
+        print(json.dumps(eas_bench(args, args.workload)))
+        return
+    special = bool(args.res_layers or args.layer_sampling or args.host_partition or args.aggregate_first or
+                   args.weights_first_all or args.scale != 1.0 or args.fused or args.chain_rule_order)
+    others = []
+    if not args.no_others:
+        if args.others:
+            others = [o for o in args.others.split(",") if o]
+        elif args.workload == "cfg1" and not special:
+            others = ["cfg2", "cfg3", "cfg4"]
+    out = run_workload(args, args.workload, args.steps, args.warmup, 0.0 if args.no_cpu_baseline else 2.0e11)
+    if others:
+        out["others"] = {}
+        for o in others:
+            assert o in CONFIG_INDEX and o != args.workload
+            r = run_workload(args, o, min(args.steps, 5), min(args.warmup, 2), 0.0 if args.no_cpu_baseline else 5.0e10)
+            r.pop("call_ms", None)
+            out["others"][o] = r
     print(json.dumps(out))
 
 
-def bench_res_model(args, w, part, sampled_graph, dtype):
+def bench_res_model(args, w, part, sampled_graph, dtype, steps, warmup):
     """The deep residual GraphSAGE on the workload's partition (host-built numbering unless the partition was sampled
     on the GPU): same metric, the forward aggregation of a middle layer as the dominant call."""
     import torch
     import graphgen as gg
     import paper_2311_06837_amd as P
     assert w.model == "sage" and args.res_layers >= 2
-    L, hid = args.res_layers, w.dims[1]
+    L, hid = args.res_layers, (args.res_hidden or w.dims[1])
     dims = [w.dims[0]] + [hid] * (L - 1) + [w.dims[-1]]
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     # the partition's halo was cut for the workload's own depth: deeper models see the same vertices (the late active
@@ -364,12 +645,12 @@ def bench_res_model(args, w, part, sampled_graph, dtype):
     n = part.graph.n_rows
     model.set_input(dev(gg.features(n, w.dims[0], w.seed, ld=P.row_stride(w.dims[0], dtype))).to(dtype))
     labels = dev(gg.labels(len(part.targets), w.dims[-1], w.seed))
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         model.step(labels)
     torch.cuda.synchronize()
     model.trace = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         model.step(labels)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -384,16 +665,16 @@ def bench_res_model(args, w, part, sampled_graph, dtype):
     dom = max(range(2, L + 1), key=lambda l: call_ms.get(f"spmm_fwd_{l}", 0.0))
     nd = model.n_rows_of_layer(dom)
     alg_bytes = edges[dom]["fwd"] * (4 + hid * es) + nd * (8 + hid * es)
-    t_dom = call_ms[f"spmm_fwd_{dom}"] * 1e-3
+    t_dom = (call_ms.get(f"spmm_fwd_{dom}") or call_ms[f"fused_fwd_{dom}"]) * 1e-3
     group = lambda pre: sum(v for k, v in call_ms.items() if k.startswith(pre))
-    out = {
-        "metric": "aggregated_edges_per_sec", "value": total_edges / (wall / args.steps), "unit": "edges/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
+    return {
+        "metric": "aggregated_edges_per_sec", "value": total_edges / (wall / steps), "unit": "edges/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall / steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"deep residual GraphSAGE (ResSAGE+), {L} layers, hidden {hid}, on the partition of "
                                f"configs[{CONFIG_INDEX[args.workload]}]: {gg.WORKLOADS[args.workload]}",
                    "scale": args.scale, "n_local": n, "nnz_local": part.graph.nnz, "targets": len(part.targets),
-                   "layers": L, "recompute": bool(args.recompute)},
+                   "layers": L, "hidden": hid, "recompute": bool(args.recompute)},
         "epoch_ms": sum(v for k, v in call_ms.items() if k != "active_sets"),
         "activation_bytes": model.activation_bytes(),
         "aggregated_edges_per_step": total_edges,
@@ -402,22 +683,20 @@ def bench_res_model(args, w, part, sampled_graph, dtype):
                        "residual": group("residual"), "active_sets": call_ms.get("active_sets"), "softmax_ce": call_ms.get("softmax_ce")},
         "roofline": {"kernel": f"spmm_rows_kernel; gnn_masked_spmm_fwd, layer {dom}, F={hid}", "bound": "hbm",
                      "achieved": alg_bytes / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS, "frac_basis": "gather model", "traffic": None,
                      "bytes_per_launch": alg_bytes, "launch_ms": t_dom * 1e3},
         "cpu_baseline": None,
     }
-    print(json.dumps(out))
 
 
-def cpu_baseline(part, w, params, H0, rows_all):
+def cpu_baseline(part, w, params, H0, rows_all, flops_budget):
     """The oracle as it stands, on this machine's host cores: layer-1 masked aggregation + feature transform
-    (forward) on a seeded sample of the layer's rows (rows_all, local ids of the host partition), sized for
-    about 10-30 s."""
+    (forward) on a seeded sample of the layer's rows (rows_all, local ids of the host partition), sized by a budget of
+    fp64 multiply-adds of aggregation (2e11: roughly 10-20 s on 16 cores with the gathers)."""
     import oracle
     K, N = w.dims[0], w.dims[1]
     deg = np.diff(part.graph.row_ptr)[rows_all].astype(np.int64)
-    # budget: about 2e11 fp64 multiply-adds of aggregation (roughly 10-20 s on 16 cores with the gathers)
-    budget = 2.0e11 / max(K, 1)
+    budget = flops_budget / max(K, 1)
     rng = np.random.default_rng(12345)
     order = rng.permutation(rows_all.size)
     take = int(np.searchsorted(np.cumsum(deg[order]), budget)) + 1

@@ -130,6 +130,16 @@ int32_t gnn_masked_spmm_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_act
                             void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * (Helper; no passage of the paper.)  The compute die (XCC id, 0..7) that each of the first n_ids <= 64 workgroups of a
+ * 16 x 4 probe grid ran on, in dispatch order (x fastest), to xcc_ids_host (HOST memory); *holds_host (nullable, host) = 1
+ * if workgroup i ran on the die of workgroup i mod 8 and the first eight dies are all different - the dispatch order the
+ * column-blocked route of the aggregation calls is built on.  The library asks the same question once per device before
+ * it takes that route for the first time (the size query then reports 0 if the answer is no).  Launches on the null
+ * stream and waits.
+ */
+int32_t gnn_die_mapping(int32_t *xcc_ids_host, int32_t n_ids, int32_t *holds_host);
+
+/*
  * Masked aggregation added onto the output (section 2.1's layer equation with the neighbour sum and the weight
  * product exchanged: sum_u (x_u W) instead of (sum_u x_u) W, the cheaper order when the layer narrows its input):
  *     Y[v, 0:F] = act( Y[v, 0:F] + row_scale[v] * sum_{u in row(v)} col_scale[u] * X[u, 0:F] )     for v in rows
@@ -187,6 +197,23 @@ int32_t gnn_linear_fwd(const int32_t *rows, int32_t n_active,
                        void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * A layer's forward pass in ONE kernel (section 2.1, both halves of the layer equation; the mask of section 6 through the
+ * row list): the aggregate of a tile of rows is formed in on-chip memory and multiplied by the weights there,
+ *     H_out[v, 0:N] = act( (row_scale[v] * sum_{u in row(v)} col_scale[u] * X[u, 0:K]) W_neigh (+ X[v, 0:K] W_self) + bias )
+ * for v in rows, so the aggregate A_l of gnn_masked_spmm_fwd is neither written nor read back.  The aggregate is rounded
+ * to `dtype` before the product, exactly as if it had been stored: the result equals that of the two calls up to the
+ * order of additions.  Arguments as in gnn_masked_spmm_fwd and gnn_linear_fwd (W_self NULL: no self term).
+ * Limits: input rows of 128 to 512 bytes (K rounded up to 32 bytes), output rows of at most 512 bytes, X rows 16-byte
+ * aligned, no per-layer edge mask; anything else returns GNN_ERR_UNSUPPORTED (use the two calls).
+ * A backward pass cannot rely on A_l then: dW_neigh = X^T Agg^T(dZ) (gnn_masked_spmm_bwd of dZ, then gnn_linear_bwd with X).
+ * Workspace: (ws, ws_bytes) protocol (transposed, zero-padded weights).
+ */
+int32_t gnn_fused_layer_fwd(const gnn_csr *g, const int32_t *rows, int32_t n_active, const void *X, int64_t ldx, int32_t K,
+                            const float *row_scale, const float *col_scale, const void *W_neigh, const void *W_self,
+                            const float *bias, int32_t N, void *H_out, int64_t ld_out, int32_t relu, int32_t dtype,
+                            void *ws, size_t *ws_bytes, void *stream);
+
+/*
  * gnn_linear_fwd for callers that cannot allocate device memory and so have no workspace to hand over: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
  * (ws, ws_bytes), same kernels, same bits.  The two transposed weight copies go to an array that the library
@@ -238,7 +265,26 @@ int32_t gnn_linear_bwd_input(const int32_t *rows, int32_t n_active, const void *
                              int32_t dtype, void *ws, size_t *ws_bytes, void *stream);
 
 /*
- * Bias gradient alone: dbias[0:N] = sum over the listed rows of dZ[v, 0:N] (fixed order, no atomics) - for a layer in
+ * Input gradient of a GraphSAGE layer from its AGGREGATED output gradient (chain rule of section 2.1's layer equation
+ * with the linear steps of the neighbour half exchanged: Agg^T(dZ W_neigh^T) = Agg^T(dZ) W_neigh^T), one product:
+ *     dX[v, 0:K] = [relu_H[v, 0:K] > 0] * ( dG[v, 0:N] W_neigh^T  +  (i < n_self ? dZ[v, 0:N] W_self^T : 0) )     v = rows[i]
+ *   dG       the layer's output gradient aggregated backwards (gnn_masked_spmm_bwd of dZ): one row for every vertex of
+ *            R_{l-1}, listed in `rows`
+ *   dZ       the layer's output gradient itself; only the first n_self listed rows (those of R_l) have one.  dG and dZ
+ *            share the leading dimension ldd; the rows of dZ past the first n_self listed ones must be addressable
+ *            (they are fetched and discarded)
+ *   W_neigh, W_self   [K, N] as in gnn_linear_fwd;  n_self == 0: no self half (dZ, W_self may be NULL)
+ *   relu_H   nullable: no mask
+ * Against gnn_linear_bwd's two input gradients plus an accumulating backward aggregation this saves one product pass
+ * over dZ, the aggregation's re-read of dX, and gathers N instead of K columns.  Workspace: (ws, ws_bytes) protocol.
+ */
+int32_t gnn_linear_bwd_input2(const int32_t *rows, int32_t n_active, const void *dG, const void *W_neigh, const void *dZ,
+                              const void *W_self, int32_t n_self, int64_t ldd, int32_t N, int32_t K, const void *relu_H,
+                              int64_t ld_relu, void *dX, int64_t lddx, int32_t dtype, void *ws, size_t *ws_bytes, void *stream);
+
+/*
+ * Bias gradient alone (chain rule of section 2.1's layer equation, the bias term):
+ * dbias[0:N] = sum over the listed rows of dZ[v, 0:N] (fixed order, no atomics) - for a layer in
  * the exchanged order without a self term, whose gnn_linear_bwd call runs on another matrix (dP) than dZ.
  * Workspace: (ws, ws_bytes) size-query protocol.  N <= 4096.
  */
@@ -256,7 +302,7 @@ int32_t gnn_softmax_ce(const int32_t *rows, int32_t n_active, const void *Z, int
                        void *ws, size_t *ws_bytes, void *stream);
 
 /*
- * Bitmap of a vertex set: bit (v & 31) of word v >> 5 is set iff v is in `ids`.
+ * (Helper; no passage of the paper.)  Bitmap of a vertex set: bit (v & 31) of word v >> 5 is set iff v is in `ids`.
  * bitmap has (n + 31) / 32 words and is overwritten.
  */
 int32_t gnn_make_bitmap(const int32_t *ids, int32_t n_ids, int32_t n, uint32_t *bitmap, void *stream);
@@ -275,7 +321,9 @@ int32_t gnn_make_bitmap(const int32_t *ids, int32_t n_ids, int32_t n, uint32_t *
  *   fill pass   out_col_idx != NULL: reads out_row_ptr as written by the count pass with the
  *               same arguments and writes the kept ids; entries at or beyond out_capacity
  *               are not written.
- * hops must be 1.  Bit-exact and independent of the order of `targets`.
+ * hops must be 1.  Rows must not repeat a column (a repeated outside neighbour would be counted once per
+ * appearance by the count pass but share one key in the fill pass: the two passes would disagree).
+ * Bit-exact and independent of the order of `targets`.
  */
 int32_t gnn_sample_boundary(const gnn_csr *g, const uint32_t *target_bitmap,
                             const int32_t *targets, int32_t n_targets,
@@ -288,7 +336,7 @@ int32_t gnn_sample_boundary(const gnn_csr *g, const uint32_t *target_bitmap,
  * Traversal of expansion-aware sampling (section 5.3.1): from the inner vertices (targets, hop 0) at
  * most `hops` hops outwards; in hop j every vertex selected in hop j-1 keeps at most `fanout` of its
  * neighbours that had not been selected when the hop started - those with the smallest (key, id):
- *   GNN_EAS_DEGREE  the paper's rule, vertices with many connections to unselected vertices first:
+ *   GNN_EAS_DEGREE  the paper's rule, the best-connected candidates (towards the unselected part) first:
  *                   key(u) = -(entries of row u that were unselected when the hop started)
  *   GNN_EAS_HASH    key(v, u) = mix64(mix64(mix64(seed + j) ^ v) ^ u), as in gnn_sample_boundary
  * A vertex is selected in hop j if some vertex of hop j-1 kept it.  Outputs as for
@@ -365,7 +413,7 @@ int32_t gnn_layer_norm_relu_bwd(const int32_t *rows, int32_t n_active, const voi
                                 const void *dRes, int64_t ldr, int32_t n_res, void *dX, int64_t lddx, float *dgamma,
                                 float *dbeta, int32_t dtype, void *ws, size_t *ws_bytes, void *stream);
 
-/* Y[v, 0:F] += X[v, 0:F] for the listed rows: the residual connection of the same model, forward. */
+/* Y[v, 0:F] += X[v, 0:F] for the listed rows: the residual connection of the same model (section 8.1, ResSAGE+), forward. */
 int32_t gnn_add_rows(const int32_t *rows, int32_t n_active, const void *X, int64_t ldx, void *Y, int64_t ldy, int32_t F,
                      int32_t dtype, void *stream);
 
@@ -380,9 +428,8 @@ int32_t gnn_add_rows_masked(const int32_t *rows, int32_t n_active, const void *X
                             int64_t ldy, int32_t F, const void *H, int64_t ldh, int32_t dtype, void *stream);
 
 /*
- * Extraction of the partition's one-hop graph (section 6, figure 7c step 1: extract the multi-hop
- * dependency starting from the inner vertices; section 5.3.1: a subgraph is generated from the
- * traversed vertices).  g is the UNPARTITIONED graph (square); ring_ids[0 .. n_local) and dist are
+ * Extraction of the partition's one-hop graph (section 6, figure 7c step 1; section 5.3.1: the sub-graph
+ * on the vertices a traversal from the partition's own vertices reached).  g is the UNPARTITIONED graph (square); ring_ids[0 .. n_local) and dist are
  * what gnn_build_active_sets wrote for it (traversed vertices sorted by (distance, id)).  The
  * traversed vertices become the local vertices 0 .. n_local-1 in that order - so the rows of layer l
  * are the PREFIX 0 .. hop_offsets[L-l+1]-1 of the local numbering, targets first - and the local
@@ -404,7 +451,7 @@ int32_t gnn_extract_partition(const gnn_csr *g, const int32_t *ring_ids, int32_t
                               void *ws, size_t *ws_bytes, void *stream);
 
 /*
- * out_row_ptr[0 .. n] over the full id range from a row list: row ids[i] gets the length
+ * (Helper; no passage of the paper.)  out_row_ptr[0 .. n] over the full id range from a row list: row ids[i] gets the length
  * list_row_ptr[i+1] - list_row_ptr[i] of listed row i, every other row is empty.  With ids ascending,
  * (out_row_ptr, the list's col_idx) is the row list as an n-row CSR - this is how the kept rows of
  * gnn_sample_boundary become the graph `gs` below.  Ids outside [0, n) are ignored.
@@ -413,8 +460,8 @@ int32_t gnn_expand_row_ptr(int32_t n, const int32_t *ids, int32_t n_ids, const i
                            int32_t *out_row_ptr, void *ws, size_t *ws_bytes, void *stream);
 
 /*
- * Extraction after boundary sampling (section 5.3.1: when the traversal is finished a subgraph is
- * generated from the traversed vertices; the dependencies between inner vertices stay whole).
+ * Extraction after boundary sampling (section 5.3.1: the local graph is built on what the sampler's
+ * traversal reached, and no edge between two inner vertices is dropped).
  *   gs   the kept rows as an n-row CSR (rows of non-targets empty, columns ascending)
  *   gT   the transposed unpartitioned graph (the same arrays as the graph itself if it is symmetric)
  *   ring_ids, dist   gnn_build_active_sets(gs, targets, L = 1): targets (distance 0), then every
@@ -431,6 +478,7 @@ int32_t gnn_extract_sampled_partition(const gnn_csr *gT, const gnn_csr *gs, cons
                                       void *ws, size_t *ws_bytes, void *stream);
 
 /*
+ * (Helper; no passage of the paper: section 6 only says that a partition holds the features of its vertices.)
  * Row gather (the features of the extracted vertices, in local order):
  *     dst[i, 0:F] = src[ids[i], 0:F]    for i in [0, n);  rows with ids[i] outside [0, n_src) are skipped
  * src [n_src, ld_src], dst [n, ld_dst] of `dtype`; columns F..ld_dst of dst are not written.

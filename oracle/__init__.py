@@ -202,7 +202,7 @@ def sampled_local_edges(targets, out_row_ptr, out_col_idx):
 
 
 def eas_traverse(row_ptr, col_idx, targets, hops, fanout, rule, seed=0):
-    """Section 5.3.1 traversal.  rule: "degree" (the paper's: many connections to unselected vertices first) or
+    """Section 5.3.1 traversal.  rule: "degree" (the paper's: best-connected candidates first) or
     "hash" (seeded).  -> dist int32[n] (hop of selection or -1), ring_ids, hop_offsets int64[hops+2]."""
     row_ptr, col_idx, targets = _i32(row_ptr), _i32(col_idx), _i32(targets)
     n = row_ptr.shape[0] - 1

@@ -17,8 +17,8 @@
  *     `fanout` per boundary vertex;
  *   - the traversal of expansion-aware sampling itself (section 5.3.1): from
  *     the inner vertices, at most h hops outwards, at most f new vertices per
- *     traversed vertex and hop, preferring vertices with many connections to
- *     the vertices not selected so far;
+ *     traversed vertex and hop, high-degree-first with respect to the part of
+ *     the graph not yet selected;
  *   - layer-wise sampling as per-layer masking (section 5.2): the one-hop
  *     graph stays whole and every layer aggregates through its own edge mask;
  *   - the deep residual model the paper trains (ResSAGE+, section 8.1): GraphSAGE layers with residual
@@ -78,8 +78,8 @@ int orc_active_sets(int32_t n, const int32_t *row_ptr, const int32_t *col_idx,
 }
 
 /* ---------------------------------------------------------------------- */
-/* Normalisation factors (reading of "AGGREGATE ... usually the summation" */
-/* for the two named models).  mode 1: mean, 1/len (0 for an empty row).   */
+/* Normalisation factors (section 2.1 leaves the aggregator open beyond a   */
+/* sum; these are the two named models').  mode 1: mean, 1/len (0 if empty).*/
 /* mode 2: symmetric GCN, len^-1/2 (len counts the self loop in the graph).*/
 /* ---------------------------------------------------------------------- */
 void orc_norm_scales(int32_t mode, const int32_t *len, int32_t n, double *out)
@@ -318,7 +318,7 @@ static int orc_i32_cmp(const void *a, const void *b)
 
 /*
  * For every target v (in the order given): keep every neighbour that is a
- * target ("all other dependencies untouched"); of the neighbours outside T
+ * target (section 5.3: only the boundary is sampled); of the neighbours outside T
  * keep the min(fanout, count) with the smallest (key, id).  The kept row is
  * emitted in ascending id order.  Two-call use: out_col_idx == NULL only
  * fills out_row_ptr[0..n_targets] (so the caller can size the second call).
@@ -402,9 +402,9 @@ int64_t orc_extract_partition(int32_t n, const int32_t *row_ptr, const int32_t *
 }
 
 /* ---------------------------------------------------------------------- */
-/* Extraction after boundary sampling (section 5.3.1: "when the traversal   */
-/* is finished, a subgraph is generated from the traversed vertices, and    */
-/* the internal dependencies of the inner vertices remain unsampled").      */
+/* Extraction after boundary sampling (section 5.3.1: the sub-graph is      */
+/* built on the vertices the traversal reached; edges between two inner     */
+/* vertices are never dropped).                                             */
 /* Traversed vertices = the targets (distance 0) and every outside vertex   */
 /* that some target kept (distance 1); local numbering by (distance, id):   */
 /* targets first.  Edges: the kept row of every target, plus the reverse    */
@@ -469,8 +469,8 @@ int64_t orc_extract_sampled(int32_t n, const int32_t *targets, int32_t n_targets
 /* every vertex v selected in hop j-1 looks at its neighbours that have not */
 /* been selected before this hop started and keeps at most `fanout` of them */
 /* - those with the smallest (key, id):                                     */
-/*   rule 1 (the paper's): key = -(connections of u to vertices that were   */
-/*           unselected when the hop started), i.e. many connections first; */
+/*   rule 1 (the paper's): key = -(entries of row u that were unselected    */
+/*           when the hop started), i.e. the best-connected candidate first;*/
 /*   rule 0 (seeded hash, as in orc_sample_boundary): key = orc_edge_key(   */
 /*           seed, v, u, j).                                                */
 /* A vertex is selected in hop j if some v kept it.  Outputs are those of   */

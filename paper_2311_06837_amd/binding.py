@@ -26,7 +26,7 @@ EXPORTS = ["gnn_version", "gnn_last_error", "gnn_build_active_sets", "gnn_norm_s
            "gnn_sample_boundary", "gnn_extract_partition", "gnn_gather_rows", "gnn_expand_row_ptr",
            "gnn_extract_sampled_partition", "gnn_eas_traverse", "gnn_layer_edge_mask", "gnn_transpose_edge_mask",
            "gnn_layer_edge_mask_transposed", "gnn_layer_norm_relu_fwd", "gnn_layer_norm_relu_bwd", "gnn_add_rows", "gnn_add_rows_masked", "gnn_bias_grad", "gnn_linear_bwd_input",
-           "gnn_linear_fwd_static"]
+           "gnn_linear_fwd_static", "gnn_linear_bwd_input2", "gnn_die_mapping", "gnn_fused_layer_fwd"]
 
 
 class GnnError(RuntimeError):
@@ -176,7 +176,7 @@ def gnn_build_active_sets(g: Graph, targets: torch.Tensor, L: int, sync: bool = 
 
 def gnn_eas_traverse(g: Graph, targets: torch.Tensor, hops: int, fanout: int, rule: str = "degree", seed: int = 0,
                      sync: bool = True, ws: Workspace | None = None):
-    """rule: "degree" (many connections to unselected vertices first) or "hash" (seeded).  Outputs as for
+    """rule: "degree" (best-connected candidates first, the paper's rule) or "hash" (seeded).  Outputs as for
     gnn_build_active_sets with L = hops."""
     _i32(targets, "targets")
     dev = g.row_ptr.device
@@ -528,3 +528,54 @@ def gnn_linear_bwd_input(rows, n_active: int, dZ: torch.Tensor, N: int, W: torch
              (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(dZ), C.c_int64(dZ.stride(0)), C.c_int32(N), _ptr(W), C.c_int32(K),
               C.c_int32(n_accumulate), _ptr(relu_H), C.c_int64(relu_H.stride(0) if relu_H is not None else 0), _ptr(dX),
               C.c_int64(dX.stride(0)), C.c_int32(_dtype_code(dZ))), (_stream(),), ws)
+
+
+def gnn_linear_bwd_input2(rows, n_active: int, dG: torch.Tensor, W_neigh: torch.Tensor, dZ, W_self, n_self: int, N: int, K: int,
+                          relu_H, dX: torch.Tensor, ws: Workspace | None = None):
+    """dX[rows] = (dG[rows] W_neigh^T + dZ[rows] W_self^T for the first n_self listed rows) where relu_H > 0, else 0."""
+    _mat(dG, "dG"), _mat(dX, "dX")
+    assert W_neigh.shape == (K, N) and W_neigh.is_contiguous() and W_neigh.dtype == dG.dtype == dX.dtype
+    assert rows is None or rows.numel() >= n_active
+    if n_self > 0:
+        _mat(dZ, "dZ")
+        assert dZ.dtype == dG.dtype and dZ.stride(0) == dG.stride(0) and dZ.shape[0] >= dG.shape[0]
+        assert W_self.shape == (K, N) and W_self.is_contiguous() and W_self.dtype == dG.dtype
+    if relu_H is not None:
+        _mat(relu_H, "relu_H")
+        assert relu_H.dtype == dX.dtype
+    _with_ws(lib().gnn_linear_bwd_input2,
+             (_ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(dG), _ptr(W_neigh), _ptr(dZ) if n_self > 0 else None,
+              _ptr(W_self) if n_self > 0 else None, C.c_int32(n_self), C.c_int64(dG.stride(0)), C.c_int32(N), C.c_int32(K),
+              _ptr(relu_H), C.c_int64(relu_H.stride(0) if relu_H is not None else 0), _ptr(dX), C.c_int64(dX.stride(0)),
+              C.c_int32(_dtype_code(dG))), (_stream(),), ws)
+
+
+def gnn_die_mapping():
+    """-> (list of the compute-die ids the 64 workgroups of the probe grid ran on, whether workgroup i ran on die i mod 8)."""
+    ids = (C.c_int32 * 64)()
+    holds = C.c_int32(0)
+    _check(lib().gnn_die_mapping(ids, C.c_int32(64), C.byref(holds)))
+    return list(ids), bool(holds.value)
+
+
+def fused_layer_supported(K: int, N: int, dtype) -> bool:
+    """Shapes gnn_fused_layer_fwd takes: input rows of 128 to 512 bytes (K rounded up to 32 bytes), output rows up to 512."""
+    es = torch.empty(0, dtype=dtype).element_size()
+    kp = (K * es + 31) // 32 * 32
+    return 128 <= kp <= 512 and N * es <= 512
+
+
+def gnn_fused_layer_fwd(g: Graph, rows, n_active: int, X: torch.Tensor, K: int, row_scale, col_scale, W_neigh: torch.Tensor,
+                        W_self, bias, H_out: torch.Tensor, relu: bool, ws: Workspace | None = None):
+    """H_out[rows] = act(aggregate(X)[rows] W_neigh (+ X[rows] W_self) + bias) in one kernel; the aggregate stays on chip."""
+    _mat(X, "X"), _mat(H_out, "H_out")
+    N = W_neigh.shape[1]
+    assert W_neigh.shape == (K, N) and W_neigh.is_contiguous() and W_neigh.dtype == X.dtype == H_out.dtype
+    assert X.shape[0] >= g.n_cols and H_out.shape[0] >= g.n_rows
+    assert W_self is None or (W_self.shape == (K, N) and W_self.is_contiguous() and W_self.dtype == X.dtype)
+    assert bias is None or (bias.dtype == torch.float32 and bias.numel() == N)
+    assert rows is None or rows.numel() >= n_active
+    _with_ws(lib().gnn_fused_layer_fwd,
+             (C.byref(g.c), _ptr(_i32(rows, "rows")), C.c_int32(n_active), _ptr(X), C.c_int64(X.stride(0)), C.c_int32(K),
+              _ptr(row_scale), _ptr(col_scale), _ptr(W_neigh), _ptr(W_self), _ptr(bias), C.c_int32(N), _ptr(H_out),
+              C.c_int64(H_out.stride(0)), C.c_int32(1 if relu else 0), C.c_int32(_dtype_code(X))), (_stream(),), ws)

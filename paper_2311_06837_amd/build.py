@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgnnhot.so")
-SOURCES = ["core.hip", "active_sets.hip", "spmm.hip", "linear.hip", "loss.hip", "sample.hip", "extract.hip", "layer_mask.hip", "norm.hip"]
+SOURCES = ["core.hip", "active_sets.hip", "spmm.hip", "linear.hip", "loss.hip", "sample.hip", "extract.hip", "layer_mask.hip", "norm.hip", "fused.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -3,12 +3,22 @@
 // vertices, step 4 generates the per-layer mask).
 //
 // Data layout.  Two bitmaps of n bits live in the workspace: `visited` (everything reached
-// so far, read-only while a level expands) and `next` (candidates found by the level being
-// expanded).  A level is: expand (edge gather + bit probes) -> count / scan / emit, a
-// bitmap compaction that lists the new ring in ascending id order without any sort, so the
-// output does not depend on which wave found a vertex first.  Ring sizes stay on the
-// device (hop_offsets); every kernel has a fixed grid and reads its bounds from there, so
-// the whole construction is enqueued without a host round trip.
+// by the levels before the one being expanded, read-only while it expands) and `seen`
+// (`visited` plus what the level has found so far: the only word an edge probes, and sets
+// if its bit is still clear).  A level is: expand (edge gather + one bit probe per edge) ->
+// count / scan / emit, a compaction of seen & ~visited that lists the new ring in ascending
+// id order without any sort, so the output does not depend on which wave found a vertex
+// first; emit then makes visited equal to seen.  Ring sizes stay on the device
+// (hop_offsets); every kernel has a fixed grid and reads its bounds from there, so the
+// whole construction is enqueued without a host round trip.
+//
+// The expansion is EDGE-parallel: a wavefront takes 64 frontier vertices, reads their row
+// bounds in one sweep, and then walks the concatenation of their rows 256 edges at a time
+// (each lane finds the row of its edge by a binary search over the 64 prefix sums in LDS),
+// so rows of 5 and rows of 500 entries keep all lanes busy alike and every lane has four
+// independent index loads and four bitmap probes in flight.  (A lane group per vertex, the
+// first form of this kernel, paid a chain of dependent loads per vertex: 0.9 ms for the
+// 20M edges of the 8-level workload.)
 //
 // Bound: HBM bandwidth.  Per level the algorithm reads each edge of the frontier once
 // (4 B) and writes 8 B per newly reached vertex; the bit probes hit a bitmap of n/8 bytes
@@ -28,78 +38,122 @@ struct AsCtrl {
 };
 
 __global__ __launch_bounds__(256) void as_init_kernel(int32_t* __restrict__ dist, int32_t n, uint32_t* __restrict__ visited,
-                                                      uint32_t* __restrict__ next, int64_t nw, AsCtrl* ctrl,
+                                                      uint32_t* __restrict__ seen, int64_t nw, AsCtrl* ctrl,
                                                       int64_t* __restrict__ hop_offsets, int32_t L) {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t v = tid; v < n; v += stride) dist[v] = -1;
     for (int64_t w = tid; w < nw; w += stride) {
         visited[w] = 0u;
-        next[w] = 0u;
+        seen[w] = 0u;
     }
     if (tid == 0) ctrl->n_hubs = 0;
     if (tid <= L + 1) hop_offsets[tid] = 0;
 }
 
 __global__ __launch_bounds__(256) void as_seed_kernel(const int32_t* __restrict__ targets, int32_t n_targets, int32_t n,
-                                                      uint32_t* __restrict__ next) {
+                                                      uint32_t* __restrict__ seen) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_targets; i += (int64_t)gridDim.x * blockDim.x) {
         int32_t v = targets[i];
-        if (v >= 0 && v < n) atomicOr(&next[v >> 5], 1u << (v & 31));
+        if (v >= 0 && v < n) atomicOr(&seen[v >> 5], 1u << (v & 31));
     }
 }
 
-// LPV lanes per frontier vertex, lanes across its row: a whole wavefront for long rows, 16 lanes (four vertices per
-// wavefront) where rows are short - a vertex costs a chain of dependent loads (id, row bounds, neighbours, bitmap
-// words), and with short rows that latency, not the bytes, is what the expansion pays for.
-template <int LPV>
+constexpr int kAsU = 4;   // edges per lane and step: their index loads, then their bitmap probes, are issued together
+
+// One wavefront per 64 entries of the frontier list (grid-stride), edge-parallel inside (see the head of the file).
 __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                         const int32_t* __restrict__ ring_ids,
                                                         const int64_t* __restrict__ hop_offsets, int32_t ring,
-                                                        const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
-                                                        int32_t* __restrict__ hubq, AsCtrl* ctrl) {
+                                                        uint32_t* __restrict__ seen, int32_t* __restrict__ hubq, AsCtrl* ctrl) {
+    __shared__ int32_t s_start[4][kWave];
+    __shared__ int32_t s_excl[4][kWave + 1];
     const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
-    const int sl = lane_id() % LPV;
-    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPV;
-    const int64_t n_groups = ((int64_t)gridDim.x * blockDim.x) / LPV;
-    for (int64_t i = begin + group; i < end; i += n_groups) {
-        const int32_t v = ring_ids[i];
-        const int32_t s = row_ptr[v], e = row_ptr[v + 1];
-        if (e - s > kAsHubDegree) {
-            if (sl == 0) hubq[atomicAdd(&ctrl->n_hubs, 1)] = v;
-            continue;
+    const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
+    int32_t* st = s_start[wave];
+    int32_t* ex = s_excl[wave];
+    const int64_t wave_g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t b = begin + wave_g * kWave; b < end; b += n_waves * kWave) {   // uniform over the wavefront
+        const int64_t i = b + lane;
+        int32_t s = 0, len = 0;
+        if (i < end) {
+            const int32_t v = ring_ids[i];
+            s = row_ptr[v];
+            len = row_ptr[v + 1] - s;
+            if (len > kAsHubDegree) {   // a whole workgroup of the next launch takes this row
+                hubq[atomicAdd(&ctrl->n_hubs, 1)] = v;
+                len = 0;
+            }
         }
-        for (int32_t p = s + sl; p < e; p += LPV) {
-            const int32_t u = col_idx[p];
-            const uint32_t bit = 1u << (u & 31);
-            if (!(visited[u >> 5] & bit) && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
+        const int incl = wave_inclusive_scan(len);
+        const int total = __shfl(incl, kWave - 1, kWave);
+        wave_lds_sync();   // the previous batch has been read
+        st[lane] = s;
+        ex[lane] = incl - len;
+        if (lane == kWave - 1) ex[kWave] = total;
+        wave_lds_sync();
+        for (int t0 = 0; t0 < total; t0 += kWave * kAsU) {
+            int32_t u[kAsU];
+            bool ok[kAsU];
+#pragma unroll
+            for (int j = 0; j < kAsU; ++j) {
+                const int t = t0 + j * kWave + lane;
+                ok[j] = t < total;
+                int lo = 0, hi = kWave;   // ex[lo] <= t < ex[hi]: the row that holds edge t (empty rows are stepped over)
+                if (ok[j]) {
+#pragma unroll
+                    for (int k = 0; k < 6; ++k) {
+                        const int mid = (lo + hi) >> 1;
+                        if (ex[mid] <= t) lo = mid;
+                        else hi = mid;
+                    }
+                }
+                u[j] = ok[j] ? col_idx[st[lo] + (t - ex[lo])] : 0;
+            }
+            uint32_t w[kAsU];
+#pragma unroll
+            for (int j = 0; j < kAsU; ++j) w[j] = seen[u[j] >> 5];   // u = 0 where the lane has no edge: a valid word
+#pragma unroll
+            for (int j = 0; j < kAsU; ++j) {
+                const uint32_t bit = 1u << (u[j] & 31);
+                if (ok[j] && !(w[j] & bit)) atomicOr(&seen[u[j] >> 5], bit);
+            }
         }
     }
 }
 
-// Hub rows: one workgroup per queued row (grid-stride over the queue), threads across the row.
+// Hub rows: one workgroup per queued row (grid-stride over the queue), threads across the row, four entries per step.
 __global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-                                                             const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
-                                                             const int32_t* __restrict__ hubq, const AsCtrl* ctrl) {
+                                                             uint32_t* __restrict__ seen, const int32_t* __restrict__ hubq,
+                                                             const AsCtrl* ctrl) {
     const int32_t n_hubs = ctrl->n_hubs;
     for (int32_t h = blockIdx.x; h < n_hubs; h += gridDim.x) {
         const int32_t v = hubq[h];
         const int32_t s = row_ptr[v], e = row_ptr[v + 1];
-        for (int32_t p = s + (int32_t)threadIdx.x; p < e; p += 256) {
-            const int32_t u = col_idx[p];
-            const uint32_t bit = 1u << (u & 31);
-            if (!(visited[u >> 5] & bit) && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
+        for (int32_t base = s + (int32_t)threadIdx.x; base < e; base += 256 * kAsU) {
+            int32_t u[kAsU];
+            uint32_t w[kAsU];
+#pragma unroll
+            for (int j = 0; j < kAsU; ++j) u[j] = base + j * 256 < e ? col_idx[base + j * 256] : 0;
+#pragma unroll
+            for (int j = 0; j < kAsU; ++j) w[j] = seen[u[j] >> 5];
+#pragma unroll
+            for (int j = 0; j < kAsU; ++j) {
+                const uint32_t bit = 1u << (u[j] & 31);
+                if (base + j * 256 < e && !(w[j] & bit)) atomicOr(&seen[u[j] >> 5], bit);
+            }
         }
     }
 }
 
-__global__ __launch_bounds__(kAsWordsPerBlock) void as_count_kernel(const uint32_t* __restrict__ next,
+__global__ __launch_bounds__(kAsWordsPerBlock) void as_count_kernel(const uint32_t* __restrict__ seen,
                                                                     const uint32_t* __restrict__ visited, int64_t nw,
                                                                     int32_t* __restrict__ blk_cnt) {
     __shared__ int s_part[kAsWordsPerBlock / kWave];
     const int64_t w = (int64_t)blockIdx.x * kAsWordsPerBlock + threadIdx.x;
     int c = 0;
-    if (w < nw) c = __popc(next[w] & ~visited[w]);
+    if (w < nw) c = __popc(seen[w] & ~visited[w]);
     int total;
     block_exclusive_scan<kAsWordsPerBlock>(c, s_part, &total);
     if (threadIdx.x == 0) blk_cnt[blockIdx.x] = total;
@@ -115,7 +169,7 @@ __global__ __launch_bounds__(1024) void as_scan_kernel(int32_t* __restrict__ blk
     }
 }
 
-__global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(uint32_t* __restrict__ next, uint32_t* __restrict__ visited,
+__global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(const uint32_t* __restrict__ seen, uint32_t* __restrict__ visited,
                                                                    int64_t nw, const int32_t* __restrict__ blk_cnt,
                                                                    const int64_t* __restrict__ hop_offsets, int32_t ring,
                                                                    int32_t* __restrict__ ring_ids, int32_t* __restrict__ dist) {
@@ -123,13 +177,9 @@ __global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(uint32_t* __r
     const int64_t w = (int64_t)blockIdx.x * kAsWordsPerBlock + threadIdx.x;
     uint32_t fresh = 0u;
     if (w < nw) {
-        const uint32_t nx = next[w];
-        if (nx) {
-            const uint32_t vis = visited[w];
-            fresh = nx & ~vis;
-            visited[w] = vis | fresh;
-            next[w] = 0u;
-        }
+        const uint32_t sn = seen[w], vis = visited[w];
+        fresh = sn & ~vis;
+        if (fresh) visited[w] = sn;
     }
     int total;
     const int before = block_exclusive_scan<kAsWordsPerBlock>(__popc(fresh), s_part, &total);
@@ -176,7 +226,7 @@ __device__ __forceinline__ uint64_t eas_key(int32_t rule, uint64_t seed_hop_mixe
 // (key, id) by `fanout` rounds of "smallest pair above the previous one" (the row is re-read from cache).
 __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                           const int32_t* __restrict__ ring_ids, const int64_t* __restrict__ hop_offsets,
-                                                          int32_t ring, const uint32_t* __restrict__ visited, uint32_t* __restrict__ next,
+                                                          int32_t ring, const uint32_t* __restrict__ visited, uint32_t* __restrict__ seen,
                                                           int32_t fanout, int32_t rule, uint64_t seed_hop_mixed,
                                                           const int32_t* __restrict__ conn) {
     const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
@@ -248,7 +298,7 @@ __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restri
             if (need) keep = !pair_less(thr_k, thr_u, eas_key(rule, seed_hop_mixed, conn, v, u), u);
             if (fanout == 0) keep = false;
             const uint32_t bit = 1u << (u & 31);
-            if (keep && !(next[u >> 5] & bit)) atomicOr(&next[u >> 5], bit);
+            if (keep && !(seen[u >> 5] & bit)) atomicOr(&seen[u >> 5], bit);
         }
     }
 }
@@ -271,7 +321,7 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* target
 
     WsCarver carve(ws);
     uint32_t* visited = carve.take<uint32_t>((size_t)nw + 1);
-    uint32_t* next = carve.take<uint32_t>((size_t)nw + 1);
+    uint32_t* seen = carve.take<uint32_t>((size_t)nw + 1);
     int32_t* blk_cnt = carve.take<int32_t>((size_t)nb + 1);
     int32_t* hubq = carve.take<int32_t>((size_t)n + 1);
     AsCtrl* ctrl = carve.take<AsCtrl>(1);
@@ -283,33 +333,26 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* target
     GNN_REQUIRE(n == 0 || (dist != nullptr && ring_ids != nullptr), GNN_ERR_INVALID_ARG, "dist / ring_ids is NULL");
     GNN_REQUIRE(n_targets == 0 || targets != nullptr, GNN_ERR_INVALID_ARG, "targets is NULL");
 
-    as_init_kernel<<<grid_for(n > L + 2 ? n : L + 2, 256, 2048), 256, 0, stream>>>(dist, n, visited, next, nw, ctrl, hop_offsets, L);
+    as_init_kernel<<<grid_for(n > L + 2 ? n : L + 2, 256, 2048), 256, 0, stream>>>(dist, n, visited, seen, nw, ctrl, hop_offsets, L);
     GNN_LAUNCH_CHECK("as_init_kernel");
     if (n > 0) {
         if (n_targets > 0) {
-            as_seed_kernel<<<grid_for(n_targets, 256, 2048), 256, 0, stream>>>(targets, n_targets, n, next);
+            as_seed_kernel<<<grid_for(n_targets, 256, 2048), 256, 0, stream>>>(targets, n_targets, n, seen);
             GNN_LAUNCH_CHECK("as_seed_kernel");
         }
         const int expand_grid = 2048;  // 8 waves per CU-slot; bounds are read on the device
         for (int32_t ring = 0; ring <= L; ++ring) {
             if (ring > 0) {
-                // rows shorter than 16 entries on average: four vertices per wavefront (measured: better at 10 per
-                // row, worse at 20 and 50)
-                if (g->nnz < (int64_t)16 * g->n_rows)
-                    as_expand_kernel<16><<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited,
-                                                                          next, hubq, ctrl);
-                else
-                    as_expand_kernel<64><<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited,
-                                                                          next, hubq, ctrl);
+                as_expand_kernel<<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, seen, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_kernel");
-                as_expand_hubs_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, visited, next, hubq, ctrl);
+                as_expand_hubs_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, seen, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_hubs_kernel");
             }
-            as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt);
+            as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt);
             GNN_LAUNCH_CHECK("as_count_kernel");
             as_scan_kernel<<<1, 1024, 0, stream>>>(blk_cnt, nb, hop_offsets, ring, ctrl);
             GNN_LAUNCH_CHECK("as_scan_kernel");
-            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
+            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
             GNN_LAUNCH_CHECK("as_emit_kernel");
         }
     }
@@ -336,7 +379,7 @@ extern "C" int32_t gnn_eas_traverse(const gnn_csr* g, const int32_t* targets, in
 
     WsCarver carve(ws);
     uint32_t* visited = carve.take<uint32_t>((size_t)nw + 1);
-    uint32_t* next = carve.take<uint32_t>((size_t)nw + 1);
+    uint32_t* seen = carve.take<uint32_t>((size_t)nw + 1);
     int32_t* blk_cnt = carve.take<int32_t>((size_t)nb + 1);
     int32_t* conn = carve.take<int32_t>(rule == GNN_EAS_DEGREE ? (size_t)n + 1 : 1);
     AsCtrl* ctrl = carve.take<AsCtrl>(1);
@@ -348,11 +391,11 @@ extern "C" int32_t gnn_eas_traverse(const gnn_csr* g, const int32_t* targets, in
     GNN_REQUIRE(n == 0 || (dist != nullptr && ring_ids != nullptr), GNN_ERR_INVALID_ARG, "dist / ring_ids is NULL");
     GNN_REQUIRE(n_targets == 0 || targets != nullptr, GNN_ERR_INVALID_ARG, "targets is NULL");
 
-    as_init_kernel<<<grid_for(n > hops + 2 ? n : hops + 2, 256, 2048), 256, 0, stream>>>(dist, n, visited, next, nw, ctrl, hop_offsets, hops);
+    as_init_kernel<<<grid_for(n > hops + 2 ? n : hops + 2, 256, 2048), 256, 0, stream>>>(dist, n, visited, seen, nw, ctrl, hop_offsets, hops);
     GNN_LAUNCH_CHECK("as_init_kernel");
     if (n > 0) {
         if (n_targets > 0) {
-            as_seed_kernel<<<grid_for(n_targets, 256, 2048), 256, 0, stream>>>(targets, n_targets, n, next);
+            as_seed_kernel<<<grid_for(n_targets, 256, 2048), 256, 0, stream>>>(targets, n_targets, n, seen);
             GNN_LAUNCH_CHECK("as_seed_kernel");
         }
         for (int32_t ring = 0; ring <= hops; ++ring) {
@@ -361,15 +404,15 @@ extern "C" int32_t gnn_eas_traverse(const gnn_csr* g, const int32_t* targets, in
                     eas_connections_kernel<<<grid_for((int64_t)n * 16, 256, 1 << 16), 256, 0, stream>>>(g->row_ptr, g->col_idx, n, visited, conn);
                     GNN_LAUNCH_CHECK("eas_connections_kernel");
                 }
-                eas_expand_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited, next, fanout,
+                eas_expand_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited, seen, fanout,
                                                             rule, mix64(seed + (uint64_t)ring), conn);
                 GNN_LAUNCH_CHECK("eas_expand_kernel");
             }
-            as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt);
+            as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt);
             GNN_LAUNCH_CHECK("as_count_kernel");
             as_scan_kernel<<<1, 1024, 0, stream>>>(blk_cnt, nb, hop_offsets, ring, ctrl);
             GNN_LAUNCH_CHECK("as_scan_kernel");
-            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(next, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
+            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
             GNN_LAUNCH_CHECK("as_emit_kernel");
         }
     }

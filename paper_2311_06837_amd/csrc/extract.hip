@@ -1,6 +1,6 @@
-// Extraction of the partition's one-hop graph (paper section 6, figure 7c step 1: "extract the selected
-// neighbours from the multi-hop dependency starting from the inner vertices"; section 5.3.1: "a subgraph is
-// generated from the traversed vertices"), and the matching gather of the feature rows.
+// Extraction of the partition's one-hop graph (paper section 6, figure 7c step 1: the vertices the partition
+// depends on are collected outwards from its own vertices; section 5.3.1: the sub-graph is then built on what the
+// traversal reached), and the matching gather of the feature rows.
 //
 // Input is what gnn_build_active_sets leaves for the UNPARTITIONED graph: the traversed vertices in ring order
 // (sorted by (distance from the targets, id)) and dist[].  They become the local vertices 0 .. n_local-1 in that

@@ -156,6 +156,7 @@ struct GemmNT {
     int64_t ldm;
     int32_t m_vec;             // 16-byte loads from mask rows allowed
     int32_t n_acc;
+    int32_t M1;                // n_src == 2: only the rows m < M1 have a second source (INT32_MAX: all of them)
 };
 
 // The post-processing of that input gradient on one stored 16-byte vector / one element.
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) 
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int k_tiles = (a.K + BK - 1) / BK;
-    const int n_steps = k_tiles * a.n_src;
+    const int n_steps = k_tiles * ((a.n_src == 2 && m0 >= a.M1) ? 1 : a.n_src);   // a tile past M1 has one source only
     uint4 ra0[A_CH], rb0[B_CH], ra1[A_CH], rb1[B_CH];
 
     auto fetch = [&](int step, uint4 (&ra)[A_CH], uint4 (&rb)[B_CH]) {
@@ -289,6 +290,11 @@ __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) 
             for (int c = 0; c < A_CH; ++c) ra[c] = fix_chunk<DT>(ra[c], a_ok[c] ? nv : 0);
 #pragma unroll
             for (int c = 0; c < B_CH; ++c) rb[c] = fix_chunk<DT>(rb[c], b_ok[c] ? nv : 0);
+        }
+        if (step >= k_tiles) {   // second source: rows at or past M1 contribute nothing
+#pragma unroll
+            for (int c = 0; c < A_CH; ++c)
+                if (m0 + ld_row + 32 * c >= a.M1) ra[c] = make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
         for (int c = 0; c < A_CH; ++c) *(uint4*)&sA[(ld_row + 32 * c) * kLdsRowWords + ld_kc * 4] = ra[c];
@@ -505,7 +511,9 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int k_slices = KTAIL ? (a.K + EPS - 1) / EPS : a.K / EPS;
-    const int n_steps = k_slices * a.n_src;
+    const int n_steps = k_slices * ((a.n_src == 2 && m0 >= a.M1) ? 1 : a.n_src);   // a tile past M1 has one source only
+    // rows of this thread's two chunks that lie at or past M1: their second-source data is zeroed on its way to LDS
+    const bool z0 = m0 + ld_row >= a.M1, z1 = m0 + ld_row + 64 >= a.M1;
     // Everything that lives across steps is a plain variable filled and drained by macros (arrays handed to
     // helper functions ended up in scratch memory).  Two register sets (0, 1) hold the slices in flight from
     // global memory, two fragment sets (f0, f1) hold the operands of the two halves of a slice.
@@ -545,6 +553,12 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
                 b##S##x2 = mask_chunk<DT>(b##S##x2, nv_);                          \
                 b##S##x3 = mask_chunk<DT>(b##S##x3, nv_);                          \
             }                                                                      \
+        }                                                                          \
+        {                                                                          \
+            const int sq_ = (step_) < n_steps ? (step_) : n_steps - 1;             \
+            const bool s1_ = sq_ >= k_slices;                                      \
+            a##S##x0 = (s1_ && z0) ? (u32x4){0u, 0u, 0u, 0u} : a##S##x0;           \
+            a##S##x1 = (s1_ && z1) ? (u32x4){0u, 0u, 0u, 0u} : a##S##x1;           \
         }                                                                          \
         *(u32x4*)&(buf_)[st_off] = a##S##x0;                                       \
         *(u32x4*)&(buf_)[1024 + st_off] = a##S##x1;                                \
@@ -957,15 +971,29 @@ __global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
         }
 }
 
-// out_src[k][n] = sum over splits, in split order
+// out_src[k][n] = sum over the row splits.  64 outputs x 4 split lanes per workgroup: lane y adds the splits y, y+4, ... in
+// order and the four sums are added in lane order - a fixed tree (bit-reproducible) with four times the loads in flight
+// of one chain over all splits (which took 72 us for 256 splits of a 128 x 256 gradient: as long as half the product).
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ P, int32_t splits, int32_t n_src,
                                                               int64_t kn, float* __restrict__ out0, float* __restrict__ out1) {
+    __shared__ float s_sum[4][64];
+    const int x = (int)(threadIdx.x & 63), y = (int)(threadIdx.x >> 6);
     const int64_t total = (int64_t)n_src * kn;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    for (int64_t base = (int64_t)blockIdx.x * 64; base < total; base += (int64_t)gridDim.x * 64) {   // uniform over the workgroup
+        const int64_t i = base + x;
         float s = 0.f;
-        for (int32_t sp = 0; sp < splits; ++sp) s += P[(int64_t)sp * total + i];
-        if (i < kn) out0[i] = s;
-        else out1[i - kn] = s;
+        if (i < total) {
+#pragma unroll 8
+            for (int32_t sp = y; sp < splits; sp += 4) s += P[(int64_t)sp * total + i];
+        }
+        s_sum[y][x] = s;
+        __syncthreads();
+        if (y == 0 && i < total) {
+            const float t = ((s_sum[0][x] + s_sum[1][x]) + s_sum[2][x]) + s_sum[3][x];
+            if (i < kn) out0[i] = t;
+            else out1[i - kn] = t;
+        }
+        __syncthreads();
     }
 }
 
@@ -1116,7 +1144,7 @@ static int32_t linear_fwd_impl(const int32_t* rows, int32_t n_active, const void
     g.b_vec = 1;
     g.a_rows = rows; g.c_rows = rows; g.M = n_active; g.N = N; g.K = K;
     g.bias = bias; g.relu = relu; g.C = H; g.ldc = ld_out; g.c_vec = vec_ok(H, ld_out, ES);
-    g.mask = nullptr; g.ldm = 0; g.m_vec = 0; g.n_acc = 0;
+    g.mask = nullptr; g.ldm = 0; g.m_vec = 0; g.n_acc = 0; g.M1 = INT32_MAX;
     return launch_gemm_nt<DT>(g, stream);
 }
 
@@ -1165,8 +1193,8 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
         else gemm_tn_kernel<DT, 32, false><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
     }
     GNN_LAUNCH_CHECK("gemm_tn_kernel");
-    reduce_partials_kernel<<<grid_for((int64_t)t.n_src * K * N, 256, 2048), 256, 0, stream>>>(P, splits, t.n_src, (int64_t)K * N, dWn,
-                                                                                            dWs);
+    reduce_partials_kernel<<<grid_for((int64_t)t.n_src * K * N, 64, 8192), 256, 0, stream>>>(P, splits, t.n_src, (int64_t)K * N, dWn,
+                                                                                           dWs);
     GNN_LAUNCH_CHECK("reduce_partials_kernel");
     if (in_place) {
         reduce_rows_kernel<<<(N + 31) / 32, 1024, 0, stream>>>(Pb, splits, N, dbias);
@@ -1192,7 +1220,7 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
         g.lda = ldz; g.ldb = ldw; g.a_vec = vec_ok(dZ, ldz, ES); g.b_vec = vec_ok(W, ldw, ES);
         g.a_rows = nullptr; g.c_rows = rows; g.M = M; g.N = K; g.K = N;
         g.bias = nullptr; g.relu = 0; g.C = out; g.ldc = ld_din; g.c_vec = vec_ok(out, ld_din, ES);
-        g.mask = nullptr; g.ldm = 0; g.m_vec = 0; g.n_acc = 0;
+        g.mask = nullptr; g.ldm = 0; g.m_vec = 0; g.n_acc = 0; g.M1 = INT32_MAX;
         GNN_CHECK(launch_gemm_nt<DT>(g, stream));
     }
     return GNN_OK;
@@ -1414,6 +1442,53 @@ extern "C" int32_t gnn_linear_bwd_input(const int32_t* rows, int32_t n_active, c
     g.lda = lddz; g.ldb = ldw; g.a_vec = vec_ok(dZ, lddz, es); g.b_vec = vec_ok(W, ldw, es);
     g.a_rows = rows; g.c_rows = rows; g.M = n_active; g.N = K; g.K = N;
     g.bias = nullptr; g.relu = 0; g.C = dX; g.ldc = lddx; g.c_vec = vec_ok(dX, lddx, es);
-    g.mask = relu_H; g.ldm = ld_relu; g.m_vec = relu_H ? vec_ok(relu_H, ld_relu, es) : 0; g.n_acc = n_accumulate;
+    g.mask = relu_H; g.ldm = ld_relu; g.m_vec = relu_H ? vec_ok(relu_H, ld_relu, es) : 0; g.n_acc = n_accumulate; g.M1 = INT32_MAX;
+    return dtype == GNN_F32 ? launch_gemm_nt<GNN_F32>(g, stream) : launch_gemm_nt<GNN_BF16>(g, stream);
+}
+
+extern "C" int32_t gnn_linear_bwd_input2(const int32_t* rows, int32_t n_active, const void* dG, const void* W_neigh, const void* dZ,
+                                         const void* W_self, int32_t n_self, int64_t ldd, int32_t N, int32_t K, const void* relu_H,
+                                         int64_t ld_relu, void* dX, int64_t lddx, int32_t dtype, void* ws, size_t* ws_bytes,
+                                         void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    GNN_CHECK(check_linear_common(n_active, K, N, dtype));
+    GNN_REQUIRE(ldd >= N && lddx >= K, GNN_ERR_SHAPE, "leading dimension smaller than the width");
+    GNN_REQUIRE(n_self >= 0 && n_self <= n_active, GNN_ERR_INVALID_ARG, "n_self = %d outside [0, n_active = %d]", n_self, n_active);
+    GNN_REQUIRE(relu_H == nullptr || ld_relu >= K, GNN_ERR_SHAPE, "relu_H: leading dimension smaller than K");
+    const int es = dtype == GNN_F32 ? 4 : 2;
+    const bool pad_w = ((int64_t)N * es) % 16 != 0;
+    const int32_t ldwp = (int32_t)align_up((size_t)N, 16 / es);
+    WsCarver carve(ws);
+    char* Wpad0 = carve.take<char>(pad_w ? (size_t)K * ldwp * es : 0);
+    char* Wpad1 = carve.take<char>(pad_w ? (size_t)K * ldwp * es : 0);
+    bool query;
+    GNN_CHECK(ws_protocol(ws, ws_bytes, carve.used, &query));
+    if (query) return GNN_OK;
+    if (n_active == 0) return GNN_OK;
+    GNN_REQUIRE(dG && W_neigh && dX, GNN_ERR_INVALID_ARG, "dG, W_neigh or dX is NULL");
+    GNN_REQUIRE(n_self == 0 || (dZ && W_self), GNN_ERR_INVALID_ARG, "dZ or W_self is NULL with n_self > 0");
+    const bool two = n_self > 0;
+    int64_t ldw = N;
+    if (pad_w) {   // weight rows of an unaligned width (41 or 47 classes): the product reads padded copies with vector loads
+        for (int which = 0; which < (two ? 2 : 1); ++which) {
+            const void* W = which == 0 ? W_neigh : W_self;
+            char* Wp = which == 0 ? Wpad0 : Wpad1;
+            if (dtype == GNN_F32) pad_rows_kernel<GNN_F32><<<grid_for((int64_t)K * ldwp, 256, 1024), 256, 0, stream>>>(W, K, N, Wp, ldwp);
+            else pad_rows_kernel<GNN_BF16><<<grid_for((int64_t)K * ldwp, 256, 1024), 256, 0, stream>>>(W, K, N, Wp, ldwp);
+            GNN_LAUNCH_CHECK("pad_rows_kernel");
+        }
+        W_neigh = Wpad0;
+        W_self = Wpad1;
+        ldw = ldwp;
+    }
+    GemmNT g;
+    g.A[0] = dG; g.A[1] = two ? dZ : nullptr; g.Bt[0] = W_neigh; g.Bt[1] = two ? W_self : nullptr; g.n_src = two ? 2 : 1;
+    g.lda = ldd; g.ldb = ldw;
+    g.a_vec = vec_ok(dG, ldd, es) && (!two || vec_ok(dZ, ldd, es));
+    g.b_vec = vec_ok(W_neigh, ldw, es) && (!two || vec_ok(W_self, ldw, es));
+    g.a_rows = rows; g.c_rows = rows; g.M = n_active; g.N = K; g.K = N;
+    g.bias = nullptr; g.relu = 0; g.C = dX; g.ldc = lddx; g.c_vec = vec_ok(dX, lddx, es);
+    g.mask = relu_H; g.ldm = ld_relu; g.m_vec = relu_H ? vec_ok(relu_H, ld_relu, es) : 0; g.n_acc = 0;
+    g.M1 = two ? n_self : INT32_MAX;
     return dtype == GNN_F32 ? launch_gemm_nt<GNN_F32>(g, stream) : launch_gemm_nt<GNN_BF16>(g, stream);
 }

@@ -19,6 +19,7 @@
 // reduced through LDS in a fixed order, inside the same launch.
 #include "common.h"
 #include "scan.h"
+#include <mutex>
 
 namespace gnnhot {
 
@@ -1058,6 +1059,55 @@ __global__ __launch_bounds__(256) void spmm_scale_rows_kernel(const void* __rest
     }
 }
 
+// ---- does workgroup i run on compute die i mod 8? --------------------------------------------------------------
+// The column-blocked route rests on it (correctness does not: with another dispatch order the sums are the same, only
+// the reason for the route is gone).  Checked once per device, at the first call that would take the route: a 16 x 4
+// grid of one-wave workgroups records the die (XCC) id each of them ran on; the route is taken only if the first eight
+// ids are eight different dies and workgroup i (in dispatch order: x fastest) repeats the die of workgroup i mod 8.
+constexpr int kProbeX = 16, kProbeY = 4;
+static __device__ int32_t g_die_probe[kProbeX * kProbeY];
+
+__global__ __launch_bounds__(64) void die_probe_kernel(int32_t* __restrict__ out) {
+    uint32_t x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));   // bits 3:0: the die this wavefront runs on
+    if (threadIdx.x == 0) out[blockIdx.y * gridDim.x + blockIdx.x] = (int32_t)(x & 0xfu);
+}
+
+static int32_t probe_die_ids(int32_t* ids_host) {
+    void* p = nullptr;
+    GNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_die_probe)));
+    die_probe_kernel<<<dim3(kProbeX, kProbeY), 64, 0, (hipStream_t)0>>>((int32_t*)p);
+    GNN_LAUNCH_CHECK("die_probe_kernel");
+    GNN_HIP(hipMemcpy(ids_host, p, sizeof(int32_t) * kProbeX * kProbeY, hipMemcpyDeviceToHost));   // waits for the kernel
+    return GNN_OK;
+}
+
+static bool die_ids_round_robin(const int32_t* ids) {
+    uint32_t seen = 0;
+    for (int i = 0; i < kDies; ++i) {
+        if (ids[i] < 0 || ids[i] >= kDies) return false;
+        seen |= 1u << ids[i];
+    }
+    if (seen != (1u << kDies) - 1u) return false;
+    for (int i = kDies; i < kProbeX * kProbeY; ++i)
+        if (ids[i] != ids[i % kDies]) return false;
+    return true;
+}
+
+// 1: the mapping holds on the current device, 0: it does not (or could not be probed); probed at the first question
+static int die_mapping_holds() {
+    static std::mutex mu;
+    static int state[64];   // per device: 0 unknown, 1 holds, 2 does not
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    std::lock_guard<std::mutex> lock(mu);
+    if (state[dev] == 0) {
+        int32_t ids[kProbeX * kProbeY];
+        state[dev] = (probe_die_ids(ids) == GNN_OK && die_ids_round_robin(ids)) ? 1 : 2;
+    }
+    return state[dev] == 1;
+}
+
 // The column-blocked route's shape for one call; passes == 0: the route does not apply.
 struct BlockedPlan {
     int passes = 0;
@@ -1090,6 +1140,7 @@ static BlockedPlan plan_blocked(const gnn_csr* g, int32_t n_active, int32_t F, i
     // average kept length of a row: its entries spread over the id range like the vertices do
     const int64_t avg_row = (int64_t)((double)g->nnz / g->n_rows * ((double)n_src / g->n_cols));
     if (avg_row < (int64_t)GNN_SPMM_BLOCKED_MIN_SEG * n_blocks) return p;
+    if (!die_mapping_holds()) return p;     // workgroup i is not on die i mod 8 here: the route has lost its reason
     p.passes = passes;
     p.n_blocks = n_blocks;
     p.avg_seg = avg_row / n_blocks;
@@ -1265,6 +1316,15 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
 }  // namespace gnnhot
 
 using namespace gnnhot;
+
+extern "C" int32_t gnn_die_mapping(int32_t* xcc_ids_host, int32_t n_ids, int32_t* holds_host) {
+    GNN_REQUIRE(n_ids >= 0 && (xcc_ids_host != nullptr || n_ids == 0), GNN_ERR_INVALID_ARG, "xcc_ids_host is NULL");
+    int32_t ids[kProbeX * kProbeY];
+    GNN_CHECK(probe_die_ids(ids));
+    for (int i = 0; i < n_ids && i < kProbeX * kProbeY; ++i) xcc_ids_host[i] = ids[i];
+    if (holds_host != nullptr) *holds_host = die_ids_round_robin(ids) ? 1 : 0;
+    return GNN_OK;
+}
 
 extern "C" int32_t gnn_masked_spmm_fwd(const gnn_csr* g, const int32_t* rows, int32_t n_active, const void* X, int64_t ldx,
                                        void* Y, int64_t ldy, int32_t F, int32_t dtype, const float* row_scale,

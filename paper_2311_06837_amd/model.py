@@ -45,6 +45,15 @@ class MaskedGNN:
                      least 512 bytes long (shorter rows are gathered at a rate set by their number, not their bytes:
                      narrowing them further buys nothing and the two extra products cost); False: none; or a
                      collection of layer numbers.
+    grad_first       the order of the two linear steps of a GraphSAGE layer's neighbour half in the BACKWARD pass.  The
+                     chain rule gives dA_l = dZ W_neigh^T, then the backward aggregation of dA_l added onto dZ W_self^T.
+                     True ("auto": where dims[l] <= dims[l-1], the default): aggregate the output gradient first,
+                     G = Agg^T(dZ) (dims[l] columns, plain store), then ONE product dH_{l-1} = mask(G W_neigh^T + dZ W_self^T)
+                     (gnn_linear_bwd_input2) - one pass over dZ and one over dH_{l-1} fewer.  False: the chain rule's order.
+    fused_forward    True: the GraphSAGE layers whose backward pass aggregates first (grad_first), in the paper's order and
+                     of a shape the kernel takes run their forward pass as ONE kernel (gnn_fused_layer_fwd): the aggregate
+                     A_l stays on chip and is never stored; the backward pass then gets dW_neigh = H_{l-1}^T Agg^T(dZ) from
+                     the aggregated gradient it forms anyway.  False (default): two calls per layer.
     side_stream      True (default): the weight-gradient products of the backward pass - nothing in the step waits for
                      them - are enqueued on a second HIP stream (default priority, a workspace of its own), so they
                      run beside the backward aggregations, which leave the matrix cores idle; the step's stream
@@ -53,7 +62,8 @@ class MaskedGNN:
 
     def __init__(self, graph: B.Graph, graph_t: B.Graph, targets: torch.Tensor, kind: str, params: list,
                  dtype=torch.float32, global_degree: torch.Tensor | None = None, prefix_numbered: bool = False,
-                 layer_sampling=None, transform_first="auto", side_stream: bool = True):
+                 layer_sampling=None, transform_first="auto", side_stream: bool = True, grad_first="auto",
+                 fused_forward: bool = False):
         assert kind in ("gcn", "sage")
         self.layer_sampling = layer_sampling
         self.prefix_numbered, self._prefix_checked = prefix_numbered, False
@@ -83,9 +93,16 @@ class MaskedGNN:
         else:
             self.tf_layers = frozenset(int(l) for l in transform_first)
             assert all(1 <= l <= self.L for l in self.tf_layers)
+        if kind != "sage" or grad_first is False:
+            self.gf_layers = frozenset()
+        else:
+            self.gf_layers = frozenset(l for l in range(2, self.L + 1)
+                                       if grad_first is True or self.dims[l] <= self.dims[l - 1])
+        self.fused_layers = frozenset(l for l in self.gf_layers if fused_forward and l not in self.tf_layers and layer_sampling is None
+                                      and B.fused_layer_supported(self.dims[l - 1], self.dims[l], dtype))
         # activations A_l, H_l and their gradients; rows outside the active sets are never touched
-        self.A = [None] + [None if l in self.tf_layers else torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev)
-                           for l in range(1, self.L + 1)]
+        self.A = [None] + [None if (l in self.tf_layers or l in self.fused_layers)
+                           else torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
         # a layer in the exchanged order keeps no aggregate of its input; instead its transformed rows P_l and the
         # gradient dP_l that reaches them
         self.P = {l: torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in self.tf_layers}
@@ -93,8 +110,10 @@ class MaskedGNN:
         self._dbias_unused = torch.zeros(max(self.dims), dtype=torch.float32, device=dev)
         self.H = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
         self.dH = [None] + [torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in range(1, self.L + 1)]
-        self.dA = [None, None] + [None if l in self.tf_layers else torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev)
-                                  for l in range(2, self.L + 1)]
+        self.dA = [None, None] + [None if (l in self.tf_layers or l in self.gf_layers)
+                                  else torch.zeros(self.n, self.ld[l - 1], dtype=dtype, device=dev) for l in range(2, self.L + 1)]
+        # the output gradient of a layer aggregated backwards (layers whose backward pass aggregates first)
+        self.dG = {l: torch.zeros(self.n, self.ld[l], dtype=dtype, device=dev) for l in self.gf_layers if l not in self.tf_layers}
         self.grads = []
         for p in self.params:
             gdict = {"dW_neigh": torch.zeros_like(p["W_neigh"], dtype=torch.float32), "dbias": torch.zeros_like(p["bias"])}
@@ -206,6 +225,10 @@ class MaskedGNN:
                 self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd_add, g_l, self.rows, nl, self.P[l], self.H[l], self.dims[l], rs_l,
                            self.cs, relu=(l < self.L), ws=self.ws, bias=None if self.kind == "sage" else p["bias"])
                 continue
+            if l in self.fused_layers:
+                self._call(f"fused_fwd_{l}", B.gnn_fused_layer_fwd, g_l, self.rows, nl, self.H[l - 1], K, rs_l, self.cs, p["W_neigh"],
+                           p["W_self"], p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
+                continue
             self._call(f"spmm_fwd_{l}", B.gnn_masked_spmm_fwd, g_l, self.rows, nl, self.H[l - 1], self.A[l], K, rs_l, self.cs, ws=self.ws)
             self._call(f"linear_fwd_{l}", B.gnn_linear_fwd, self.rows, nl, self.A[l], self.H[l - 1] if self.kind == "sage" else None, K,
                              p["W_neigh"], p.get("W_self"), p["bias"], self.H[l], relu=(l < self.L), ws=self.ws)
@@ -225,8 +248,29 @@ class MaskedGNN:
             if l in self.tf_layers:
                 self._backward_transform_first(l)
                 continue
-            # dH_l arrives with the ReLU of layer l already undone: the aggregation call that wrote it last masked it
+            # dH_l arrives with the ReLU of layer l already undone: the call that wrote it last masked it
             N = self.dims[l]
+            if l in self.gf_layers:
+                # weight and bias gradients beside the rest (they need A_l, H_{l-1} and dZ only); the input gradient from the
+                # aggregated output gradient: G = Agg^T(dZ) over every row of R_{l-1}, then one product for both halves
+                fused = l in self.fused_layers
+                if fused:   # no A_l: the self half's gradients from dZ now, the neighbour half's from the aggregated gradient below
+                    self._call_beside(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.H[l - 1], None, K,
+                                      p["W_self"], None, gr["dW_self"], None, gr["dbias"], None, None)
+                else:
+                    self._call_beside(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
+                                      self.H[l - 1], K, p["W_neigh"], p["W_self"], gr["dW_neigh"], gr["dW_self"], gr["dbias"], None, None)
+                n_prev = self.n_rows_of_layer(l - 1)
+                gt_l, rs_l = (self.gt, self.rs) if self.layer_sampling is None else (self.gt_l[l], self.rs_l[l])
+                dist_l, pre_l = self._source_filter(nl)
+                self._call(f"spmm_bwd_{l}", B.gnn_masked_spmm_bwd, gt_l, self.rows, n_prev, dist_l, L - l, self.dH[l], self.dG[l], N,
+                           rs_l, self.cs, accumulate=False, ws=self.ws if 4 * nl >= self.n else None, src_prefix=pre_l)
+                if fused:
+                    self._call_beside(f"linear_bwd_{l}_neigh", B.gnn_linear_bwd, self.rows, n_prev, self.dG[l], None, False, self.H[l - 1],
+                                      None, K, p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], None, None)
+                self._call(f"linear_bwd_{l}_input", B.gnn_linear_bwd_input2, self.rows, n_prev, self.dG[l], p["W_neigh"], self.dH[l],
+                           p["W_self"], nl, N, K, self.H[l - 1], self.dH[l - 1], ws=self.ws)
+                continue
             if need_in and self.side is not None:
                 # weight and bias gradients beside the rest; the input gradients, which the aggregation waits for, here
                 self._call_beside(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.A[l],
@@ -288,7 +332,7 @@ class MaskedGNN:
         if sage:
             self._call_beside(f"linear_bwd_{l}", B.gnn_linear_bwd, self.rows, nl, self.dH[l], None, False, self.H[l - 1], None, K,
                               p["W_self"], None, gr["dW_self"], None, gr["dbias"], None, None)
-            if need_in:
+            if need_in and l not in self.gf_layers:
                 self._call(f"linear_bwd_{l}_input_self", B.gnn_linear_bwd_input, self.rows, nl, self.dH[l], N, p["W_self"], K, 0, None,
                            self.dH[l - 1], ws=self.ws)
         else:
@@ -297,7 +341,12 @@ class MaskedGNN:
                    rs_l, self.cs, accumulate=False, ws=self.ws if 4 * nl >= self.n else None, src_prefix=pre_l)
         self._call_beside(f"linear_bwd_{l}_neigh", B.gnn_linear_bwd, self.rows, n_prev, self.dP[l], None, False, self.H[l - 1], None, K,
                           p["W_neigh"], None, gr["dW_neigh"], None, self._dbias_unused[:N], None, None)
-        if need_in:
+        if need_in and l in self.gf_layers:
+            # both halves in one product: dP W_neigh^T for every row of R_{l-1} plus dZ W_self^T for the rows of R_l, masked in
+            # front of layer l-1's ReLU in the store
+            self._call(f"linear_bwd_{l}_input", B.gnn_linear_bwd_input2, self.rows, n_prev, self.dP[l], p["W_neigh"], self.dH[l],
+                       p["W_self"], nl, N, K, self.H[l - 1], self.dH[l - 1], ws=self.ws)
+        elif need_in:
             # dP W_neigh^T for every row of R_{l-1}, added (GraphSAGE) to the dZ W_self^T that the rows of R_l already
             # hold and masked in front of layer l-1's ReLU, all in the product's store: dH_{l-1} leaves masked
             self._call(f"linear_bwd_{l}_input", B.gnn_linear_bwd_input, self.rows, n_prev, self.dP[l], N, p["W_neigh"], K,

@@ -6,7 +6,7 @@ import torch
 
 import graphgen as gg
 import oracle
-from gpu_util import TOL, dev
+from gpu_util import TOL, backward_at_the_oracles_point, check, dev
 
 pytestmark = pytest.mark.gpu
 
@@ -114,11 +114,10 @@ def test_training_step_on_the_extracted_graph(kind, dtype):
     assert torch.equal(m.ring_ids[:n_local].cpu(), torch.arange(n_local, dtype=torch.int32))   # the numbering IS the ring order
     tol = TOL[dtype] * 2 * L
     assert abs(loss.item() - loss_o) <= tol * abs(loss_o), (loss.item(), loss_o)
+    backward_at_the_oracles_point(m, om, dims, dtype, dev(y))     # same ReLU decisions on both sides, then element by element
     for l, gr in enumerate(grads_o):
         for k, want in gr.items():
-            got = m.grads[l][k].double().cpu().numpy()
-            err = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
-            assert err <= tol, (l, k, err)
+            check(m.grads[l][k].double().cpu().numpy(), want, dtype, f"layer {l + 1} {k}", calls=L - l)
 
 
 # ---- extraction after boundary sampling ----------------------------------------------------------------------
@@ -194,8 +193,7 @@ def test_training_step_after_sampling_and_extraction():
     assert [int(x) for x in m.hop] == [0, len(T), n_local, n_local, n_local]      # dist is 0 or 1: every later ring is empty
     tol = TOL[dtype] * 2 * L
     assert abs(loss.item() - loss_o) <= tol * abs(loss_o), (loss.item(), loss_o)
+    backward_at_the_oracles_point(m, om, dims, dtype, dev(y))     # same ReLU decisions on both sides, then element by element
     for l, gr in enumerate(grads_o):
         for k, want in gr.items():
-            got = m.grads[l][k].double().cpu().numpy()
-            err = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
-            assert err <= tol, (l, k, err)
+            check(m.grads[l][k].double().cpu().numpy(), want, dtype, f"layer {l + 1} {k}", calls=L - l)

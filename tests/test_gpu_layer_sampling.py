@@ -7,7 +7,7 @@ import torch
 
 import graphgen as gg
 import oracle
-from gpu_util import TOL, as_stored, check, dev, host64, padded
+from gpu_util import TOL, as_stored, backward_at_the_oracles_point, check, dev, host64, padded
 
 pytestmark = pytest.mark.gpu
 
@@ -171,11 +171,10 @@ def test_training_step_with_per_layer_masks(kind, dtype, ls, dims):
         assert np.array_equal(_bits(m.g_l[l].edge_keep, g.nnz), om.keep[l]), f"mask of layer {l}"
     tol = TOL[dtype]
     assert abs(loss.item() - loss_o) <= tol * L * abs(loss_o), (loss.item(), loss_o)
+    backward_at_the_oracles_point(m, om, dims, dtype, dev(y))     # same ReLU decisions on both sides, then element by element
     for l in range(L):
         for k, want in grads_o[l].items():
-            got = host64(m.grads[l][k])
-            e = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
-            assert e <= tol * (L + 1), (l, k, e)
+            check(host64(m.grads[l][k]), want, dtype, f"layer {l + 1} {k}", calls=L - l)
     if ls[1] == M64:       # everything kept: the plain model
         plain = oracle.Model(g.row_ptr, g.col_idx, T, kind, params, gdeg, bf16=dtype == torch.bfloat16)
         assert plain.forward(H0, y) == loss_o

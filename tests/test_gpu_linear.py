@@ -241,3 +241,52 @@ def test_input_gradient_product_with_sum_and_mask_in_its_store(dtype, K, N):
         P.gnn_linear_bwd_input(None, 10, padded(dZ, ld_out, dtype), N, dev(W).to(dtype), K, 5, None, padded(old, ld_in, dtype))
     with pytest.raises(P.GnnError):
         P.gnn_linear_bwd_input(None, 10, padded(dZ, ld_out, dtype), N, dev(W).to(dtype), K, 11, padded(H, ld_in, dtype), padded(old, ld_in, dtype))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K,N", [(128, 128), (256, 256), (256, 41), (128, 16), (96, 47), (40, 7), (602, 256)])
+def test_input_gradient_from_the_aggregated_gradient(dtype, K, N):
+    """gnn_linear_bwd_input2: dX = [H > 0] * (dG W_neigh^T + dZ W_self^T on the first n_self listed rows).  Both products
+    come from the oracle's feature-transform backward; the sum, the row limit and the mask are written out here.  The rows
+    of dZ past n_self hold NaN: they are fetched by the kernel and must not reach the result."""
+    import paper_2311_06837_amd as P
+    rng = np.random.default_rng(K * 1000 + N + 7)
+    n = 3000
+    params = gg.layer_weights([K, N], True, K + N)[0]
+    Wn, Ws = as_stored(params["W_neigh"], dtype), as_stored(params["W_self"], dtype)
+    dG = as_stored(rng.standard_normal((n, N)), dtype)
+    dZ = as_stored(rng.standard_normal((n, N)), dtype)
+    H = as_stored(np.maximum(rng.standard_normal((n, K)), 0), dtype)
+    rows = rng.permutation(n)[:1777].astype(np.int32)
+    ld_in, ld_out = P.row_stride(K, dtype), P.row_stride(N, dtype)
+    # (row list or prefix, listed rows, rows with a self half, mask): limits inside a 128-row tile, at a tile edge, none, all
+    for rws, cnt, n_self, mask in ((rows, len(rows), 600, True), (None, 2049, 2049, True), (rows, len(rows), 0, True),
+                                   (None, 1500, 1280, False), (rows, 130, 1, True), (None, 700, 129, True)):
+        print(f"linear_bwd_input2: K={K} N={N} {dtype} rows={'list' if rws is not None else 'prefix'} n={cnt} n_self={n_self} "
+              f"mask={mask}", flush=True)
+        sel = rws[:cnt] if rws is not None else np.arange(cnt, dtype=np.int32)
+        dZ_poisoned = dZ.copy()
+        no_self = np.setdiff1d(np.arange(n), sel[:n_self])
+        dZd = padded(dZ_poisoned, ld_out, dtype)
+        dZd[dev(no_self.astype(np.int64))] = float("nan")
+        dXd = torch.full((n, ld_in), SENT, dtype=dtype, device="cuda")
+        P.gnn_linear_bwd_input2(dev(rws) if rws is not None else None, cnt, padded(dG, ld_out, dtype), dev(Wn).to(dtype), dZd,
+                                dev(Ws).to(dtype), n_self, N, K, padded(H, ld_in, dtype) if mask else None, dXd)
+        torch.cuda.synchronize()
+        p1, p2 = np.zeros((n, K)), np.zeros((n, K))
+        oracle.linear_bwd(sel, dG, None, False, np.zeros((n, K)), None, K, Wn, None, p1, None)
+        if n_self:
+            oracle.linear_bwd(sel[:n_self], dZ, None, False, np.zeros((n, K)), None, K, Ws, None, p2, None)
+        want = p1[sel] + p2[sel]
+        if mask:
+            want = want * (H[sel] > 0)
+        got = host64(dXd)
+        check(got[sel, :K], want, dtype, "listed rows")
+        rest = np.setdiff1d(np.arange(n), sel)
+        sent = host64(torch.tensor(SENT, dtype=dtype))
+        assert (got[rest] == sent).all(), "rows outside the list were written"
+        if ld_in > K:
+            assert (got[:, K:] == sent).all()
+    with pytest.raises(P.GnnError):      # more rows with a self half than rows
+        P.gnn_linear_bwd_input2(None, 10, padded(dG, ld_out, dtype), dev(Wn).to(dtype), padded(dZ, ld_out, dtype), dev(Ws).to(dtype), 11,
+                                N, K, None, torch.zeros(n, ld_in, dtype=dtype, device="cuda"))

@@ -6,22 +6,23 @@ import torch
 
 import graphgen as gg
 import oracle
-from gpu_util import TOL, as_stored, check, dev, host64, padded
+from gpu_util import TOL, as_stored, backward_at_the_oracles_point, check, dev, host64, padded
 
 pytestmark = pytest.mark.gpu
 
 
-def _gpu_model(part, kind, params, dtype, transform_first="auto"):
+def _gpu_model(part, kind, params, dtype, transform_first="auto", grad_first="auto"):
     import paper_2311_06837_amd as P
     G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
     same = part.graph_t is part.graph
     GT = G if same else P.Graph.from_numpy(part.graph_t.row_ptr, part.graph_t.col_idx)
     dparams = [{k: dev(v) for k, v in p.items()} for p in params]
     return P.MaskedGNN(G, GT, dev(part.targets), kind, dparams, dtype=dtype,
-                       global_degree=dev(part.global_degree) if kind == "gcn" else None, transform_first=transform_first)
+                       global_degree=dev(part.global_degree) if kind == "gcn" else None, transform_first=transform_first,
+                       grad_first=grad_first)
 
 
-def _parity(name, part, kind, dims, dtype, seed, transform_first="auto"):
+def _parity(name, part, kind, dims, dtype, seed, transform_first="auto", grad_first="auto"):
     """transform_first: the order of the first layer's halves on the GPU ("auto": weights first where the layer narrows
     its input).  The oracle always aggregates first; the two orders are the same sums up to rounding."""
     print(f"model {name}: n={part.graph.n_rows} nnz={part.graph.nnz} |T|={len(part.targets)} {kind} dims={dims} {dtype} "
@@ -39,7 +40,7 @@ def _parity(name, part, kind, dims, dtype, seed, transform_first="auto"):
     loss_o = om.forward(H0, y)
     grads_o = om.backward()
 
-    m = _gpu_model(part, kind, params, dtype, transform_first)
+    m = _gpu_model(part, kind, params, dtype, transform_first, grad_first)
     if transform_first != "auto":
         narrowing = {l for l in range(1, len(dims)) if dims[l - 1] > dims[l]}
         assert m.tf_layers == (narrowing if transform_first else set())
@@ -57,14 +58,13 @@ def _parity(name, part, kind, dims, dtype, seed, transform_first="auto"):
     for l in range(1, L + 1):
         rows = om.rows_of_layer(l)
         if m.A[l] is not None:          # (the exchanged order never forms the aggregate of the input features)
-            check(host64(m.A[l])[rows, : dims[l - 1]], om.A[l][rows], dtype, f"A_{l}", calls=l)
-        check(host64(m.H[l])[rows, : dims[l]], om.H[l][rows], dtype, f"H_{l}", calls=l)
-    # gradients accumulate rounding over L layers; the bound is per GEMM/SpMM call, so allow L of them
+            check(host64(m.A[l])[rows, : dims[l - 1]], om.A[l][rows], dtype, f"{name} A_{l}", calls=l)
+        check(host64(m.H[l])[rows, : dims[l]], om.H[l][rows], dtype, f"{name} H_{l}", calls=l)
+    # every gradient element by element: the backward pass again from the oracle's forward point (gpu_util explains why)
+    backward_at_the_oracles_point(m, om, dims, dtype, dev(y))
     for l in range(L):
         for k, want in grads_o[l].items():
-            got = host64(m.grads[l][k])
-            e = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
-            assert e <= tol * (L - l + 1), f"layer {l + 1} {k}: {e:.3e}"
+            check(host64(m.grads[l][k]), want, dtype, f"{name} layer {l + 1} {k}", calls=L - l)
     return m, om
 
 
@@ -223,3 +223,51 @@ def test_side_stream_changes_nothing(kind, dims):
     for ga, gb in zip(out[0][1], out[1][1]):
         for k in ga:
             assert torch.equal(ga[k], gb[k]), k
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("transform_first", [False, True])
+def test_backward_in_the_chain_rules_order(dtype, transform_first):
+    """grad_first=False: input gradients per half (dA = dZ W_neigh^T, aggregated onto dZ W_self^T) instead of the default
+    one product from the aggregated output gradient; a widening layer keeps this order under "auto" as well."""
+    g = gg.chung_lu(5000, 9.0, 2.2, 71)
+    T = np.sort(np.random.default_rng(71).choice(5000, 300, replace=False)).astype(np.int64)
+    part = gg.halo_partition(g, T, 3)
+    m, _ = _parity("chain-rule order", part, "sage", [64, 48, 48, 6], dtype, 71, transform_first, grad_first=False)
+    assert not m.gf_layers
+    m, _ = _parity("widening", part, "sage", [32, 48, 64, 6], dtype, 72, transform_first)
+    assert m.gf_layers == {3}
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fused_forward_layers(dtype):
+    """fused_forward=True: the layers of a shape the one-kernel layer takes keep no aggregate; their weight gradient comes
+    from the aggregated output gradient.  Same results as the two-call path up to rounding."""
+    g = gg.chung_lu(6000, 10.0, 2.2, 73)
+    T = np.sort(np.random.default_rng(73).choice(6000, 400, replace=False)).astype(np.int64)
+    part = gg.halo_partition(g, T, 3)
+    dims = [64, 64, 64, 6]
+    print(f"fused model: {dtype}", flush=True)
+    import paper_2311_06837_amd as P
+    params = gg.layer_weights(dims, True, 73)
+    n = part.graph.n_rows
+    H0 = as_stored(gg.features(n, dims[0], 73), dtype)
+    y = gg.labels(len(part.targets), dims[-1], 73)
+    om = oracle.Model(part.graph.row_ptr, part.graph.col_idx, part.targets, "sage", params, None, bf16=dtype == torch.bfloat16)
+    loss_o = om.forward(H0, y)
+    grads_o = om.backward()
+    G = P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
+    m = P.MaskedGNN(G, G, dev(part.targets), "sage", [{k: dev(v) for k, v in p.items()} for p in params], dtype=dtype,
+                    transform_first=False, fused_forward=True)
+    assert m.fused_layers == {2, 3} and m.A[2] is None and m.A[3] is None and m.A[1] is not None
+    m.set_input(padded(H0, P.row_stride(dims[0], dtype), dtype))
+    loss = m.step(dev(y))
+    torch.cuda.synchronize()
+    assert abs(loss.item() - loss_o) <= TOL[dtype] * abs(loss_o)
+    for l in range(1, 4):
+        rows = om.rows_of_layer(l)
+        check(host64(m.H[l])[rows, : dims[l]], om.H[l][rows], dtype, f"fused H_{l}", calls=l)
+    backward_at_the_oracles_point(m, om, dims, dtype, dev(y))
+    for l in range(3):
+        for k, want in grads_o[l].items():
+            check(host64(m.grads[l][k]), want, dtype, f"fused layer {l + 1} {k}", calls=3 - l)

@@ -53,3 +53,21 @@ def test_unsorted_targets_and_edge_cases():
     _compare(g, T, 2, 9)
     _compare(g, np.zeros(0, dtype=np.int32), 2, 9)        # no targets
     _compare(g, np.arange(3000, dtype=np.int32), 2, 9)    # no outside neighbours at all
+
+
+def test_row_lengths_around_the_sixteen_lane_limit():
+    """Rows of 63 / 64 / 65 entries (the last one leaves its sixteen lanes for a workgroup), of 1023 / 1024 / 1025 (one step
+    of that workgroup's sweep, then two) and an empty one, targets and outside vertices mixed in every row."""
+    rng = np.random.default_rng(35)
+    n = 5000
+    lens = [63, 64, 65, 0, 1023, 1024, 1025, 1, 256, 257]
+    rows, cols = [], []
+    for r, ln in enumerate(lens):
+        c = rng.choice(n, size=ln, replace=False)
+        rows.append(np.full(ln, r, dtype=np.int64))
+        cols.append(c.astype(np.int64))
+    g = gg.csr_from_edges(n, n, np.concatenate(rows), np.concatenate(cols))
+    assert list(g.degrees()[: len(lens)]) == lens
+    T = np.concatenate([np.arange(len(lens)), np.arange(100, n, 2)]).astype(np.int32)   # about half of every row is inside
+    for fanout in (0, 3, 40, 600):
+        _compare(g, T, fanout, 0xABCDEF)

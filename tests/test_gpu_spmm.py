@@ -404,3 +404,19 @@ def test_blocked_route_backward_with_source_prefix(dtype):
     ws2 = P.Workspace()
     _prefix_case(g, 9000, 96, dtype, 80, ws=ws2)                     # a short prefix fits the caches: one launch
     assert not _used_blocked_route(ws2)
+
+
+def test_die_mapping_probe_and_the_route_that_depends_on_it():
+    """Workgroup i on compute die i mod 8: the probe's raw ids are checked here on the CPU, and the size query of a call the
+    column-blocked route is made for offers the route exactly when the pattern holds."""
+    import paper_2311_06837_amd as P
+    ids, holds = P.gnn_die_mapping()
+    print("die ids of the probe grid:", ids, flush=True)
+    assert len(ids) == 64 and all(0 <= i < 8 for i in ids)
+    pattern = len(set(ids[:8])) == 8 and all(ids[i] == ids[i % 8] for i in range(64))
+    assert holds == pattern
+    g = gg.chung_lu(80_000, 160.0, 2.1, 17)       # dense enough: 20 entries of a row per column block, an 20 MB slab
+    G = P.Graph.from_numpy(g.row_ptr, g.col_idx)
+    X = torch.zeros(g.n_rows, 64, device="cuda")
+    need = P.binding.spmm_workspace_bytes(G, g.n_rows, X, X.clone(), 64)
+    assert (need > 0) == pattern
