@@ -45,6 +45,9 @@ PASSES = {
            "SQ_WAVES", "SQ_LDS_BANK_CONFLICT", "SQ_LDS_IDX_ACTIVE", "GRBM_GUI_ACTIVE"],
 }
 N_SIMD = 256 * 4       # MI355X: 256 compute units, 4 SIMDs each
+N_XCC = 8              # GRBM_GUI_ACTIVE comes summed over the eight compute dies (16 "cycles" per ns on a long kernel), so
+                       # the cycles of ONE die's clock are a eighth of it.  Cross-check: SQ_INSTS_VALU_MFMA_MOPS_BF16 * 512 flop /
+                       # 32768 flop per 32x32x16 instruction * 32 cycles equals SQ_VALU_MFMA_BUSY_CYCLES to three digits.
 
 
 def log(*a):
@@ -84,10 +87,18 @@ def read_pass(csv_dir, manifest):
         sums = collections.defaultdict(float)
         kern = collections.OrderedDict()
         seen = set()
+        # a counter may come as one row per hardware instance (one per compute die): block counters are summed over the
+        # instances, the clock-like GRBM_* counters take the largest instance (every die counts the same cycles)
+        per = collections.OrderedDict()
         for r in rs:
-            sums[r["Counter_Name"]] += float(r["Counter_Value"])
+            per.setdefault((r["Dispatch_Id"], r["Counter_Name"]), []).append(r)
+        for (did, cname), lst in per.items():
+            vals = [float(x["Counter_Value"]) for x in lst]
+            val = max(vals) if cname.startswith("GRBM_") else sum(vals)
+            r = lst[0]
+            sums[cname] += val
             k = kern.setdefault(r["Kernel_Name"], {"dispatches": 0, "ns": 0.0, "counters": collections.defaultdict(float)})
-            k["counters"][r["Counter_Name"]] += float(r["Counter_Value"])
+            k["counters"][cname] += val
             if r["Dispatch_Id"] not in seen:
                 seen.add(r["Dispatch_Id"])
                 k["dispatches"] += 1
@@ -135,12 +146,13 @@ def derive(groups, manifest):
                 cc = kv["counters_per_dispatch"]
                 act = cc.get("GRBM_GUI_ACTIVE", 0.0)
                 if act > 0 and "SQ_VALU_MFMA_BUSY_CYCLES" in cc:
-                    per_k[kn] = {"mfma_busy": cc["SQ_VALU_MFMA_BUSY_CYCLES"] / (act * N_SIMD),
+                    per_k[kn] = {"mfma_busy": cc["SQ_VALU_MFMA_BUSY_CYCLES"] / (act / N_XCC * N_SIMD),
                                  "mfma_mops_bf16": cc.get("SQ_INSTS_VALU_MFMA_MOPS_BF16", 0.0),
                                  "mfma_mops_f32": cc.get("SQ_INSTS_VALU_MFMA_MOPS_F32", 0.0),
                                  "lds_bank_conflict_frac": (cc.get("SQ_LDS_BANK_CONFLICT", 0.0) / cc["SQ_LDS_IDX_ACTIVE"]
                                                             if cc.get("SQ_LDS_IDX_ACTIVE") else None),
-                                 "waves": cc.get("SQ_WAVES", 0.0), "gui_active_cycles": act}
+                                 "lds_busy": (cc.get("SQ_LDS_IDX_ACTIVE", 0.0) / (act / N_XCC * 256) if cc.get("SQ_LDS_IDX_ACTIVE") else None),
+                                 "waves": cc.get("SQ_WAVES", 0.0), "gui_active_cycles_one_die": act / N_XCC}
             r["sq_per_kernel"] = per_k
         res[g] = r
     return res

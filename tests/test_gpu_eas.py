@@ -1,5 +1,5 @@
 """GPU parity: gnn_eas_traverse against the oracle's expansion-aware traversal, bit-exact (section 5.3.1: at most h
-hops from the inner vertices, at most f kept neighbours per traversed vertex; many-connections-first or seeded hash),
+hops from the inner vertices, at most f kept neighbours per traversed vertex; best-connected-first or seeded hash),
 and the sub-graph of the traversed vertices (gnn_extract_partition on the traversal's outputs)."""
 import numpy as np
 import pytest
@@ -41,7 +41,8 @@ def test_hand_worked_example():
 
 
 @pytest.mark.parametrize("rule", ["degree", "hash"])
-@pytest.mark.parametrize("hops,fanout", [(1, 5), (2, 3), (3, 15), (3, 25), (2, 1)])
+@pytest.mark.parametrize("hops,fanout", [(1, 15), (1, 25), (2, 15), (2, 25), (3, 15), (3, 25),     # the paper's sensitivity grid (section 8.5)
+                                         (1, 5), (2, 3), (2, 1)])
 def test_power_law_graph(rule, hops, fanout):
     g = gg.chung_lu(40000, 18.0, 2.1, 11)
     T = np.sort(np.random.default_rng(hops * 100 + fanout).choice(40000, 700, replace=False))
@@ -71,8 +72,8 @@ def test_edge_cases(rule):
 
 
 def test_induced_subgraph_of_the_traversed_vertices():
-    """Section 5.3.1: a sub-graph is generated from the traversed vertices - the extraction call takes the traversal's
-    outputs as it takes those of the plain active sets."""
+    """Section 5.3.1: the local graph is the sub-graph on the vertices the traversal reached - the extraction call takes
+    the traversal's outputs as it takes those of the plain active sets."""
     import paper_2311_06837_amd as P
     g = gg.chung_lu(20000, 15.0, 2.1, 6)
     T = np.sort(np.random.default_rng(1).choice(20000, 2500, replace=False))
