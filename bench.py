@@ -139,6 +139,8 @@ def roofline_of_call(kernels, what, t_s, gather_bytes, compulsory_bytes, blocked
         ach_bytes, basis = gather_bytes, "gather model"
         if traffic and traffic < gather_bytes:
             ach_bytes, basis = traffic, "counters (below the gather model: cache reuse)"
+        if ach_bytes / t_s / 1e9 > HBM_PEAK_GBS:    # rows re-read from L2: only the lower bound can be claimed
+            ach_bytes, basis = compulsory_bytes, "compulsory bytes (the gather model exceeds the HBM peak and no counter reading says less)"
     ach = ach_bytes / t_s / 1e9
     return {
         "kernel": f"{kernels}; {what}", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -204,7 +206,7 @@ def setup_workload(args, name):
         for rep_i in range(3):       # first pass warms the allocator
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            gdist, gring, _, ghop = P.gnn_build_active_sets(Gg, Tg, S.n_layers, ws=ews)
+            gdist, gring, _, ghop = P.gnn_build_active_sets(Gg, Tg, S.n_layers, ws=ews, gt=Gg)   # symmetric: its own transpose
             local, new_id = P.gnn_extract_partition(Gg, gring, int(ghop[-1]), gdist, S.n_layers, ws=ews)
             torch.cuda.synchronize()
             S.t_extract = min(S.t_extract, time.perf_counter() - t0)
@@ -282,10 +284,24 @@ def run_workload(args, name, steps, warmup, cpu_flops):
     trace, model.trace = model.trace, None
     ms_per_step = wall / steps * 1e3
 
-    per_call = {}
-    for nm, a, b in trace:
-        per_call.setdefault(nm, []).append(a.elapsed_time(b))
-    call_ms = {k: float(np.mean(v)) for k, v in per_call.items()}
+    def mean_ms(tr):
+        per_call = {}
+        for nm, a, b in tr:
+            per_call.setdefault(nm, []).append(a.elapsed_time(b))
+        return {k: float(np.mean(v)) for k, v in per_call.items()}
+    call_ms = mean_ms(trace)
+    # Outside the timed region: two more steps with every call on the one stream, so that the events around a weight-
+    # gradient product time that product alone (in the timed steps it shares the GPU with an aggregation).
+    alone_ms = call_ms
+    if model.side is not None:
+        side_stream, model.side = model.side, None
+        model.step(S.labels)
+        model.trace = []
+        for _ in range(2):
+            model.step(S.labels)
+        torch.cuda.synchronize()
+        alone_ms, model.trace = mean_ms(model.trace), None
+        model.side = side_stream
     edges = model.aggregated_edges()
     total_edges = sum(e["fwd"] + e["bwd"] for e in edges.values())
     hop = [int(x) for x in model.hop]
@@ -333,37 +349,43 @@ def run_workload(args, name, steps, warmup, cpu_flops):
     c_dom = side.get("spmm_fwd_dom") if side.get("dominant_layer") == dom else None
     roofline = roofline_of_call(kernels, f"gnn_masked_spmm_fwd, layer {dom}, F={Fd}", t_dom, gather_bytes, compulsory, blocked, c_dom)
 
-    # ---- the feature-transform GEMMs against the MFMA peak of their data type and the roof that binds
-    gemm = {}
+    # ---- the feature-transform products against the roof that binds each of them: the slower of "operands once at
+    # the HBM peak" and "flops at the MFMA peak of the data type".  Timed alone on the GPU (see above).
+    peak = MFMA_PEAK_TFLOPS[w.dtype]
+    costs = model.product_costs()
+    gemm_calls = {}
+    for nm, c in costs.items():
+        t = alone_ms.get(nm, 0.0) * 1e-3
+        if t <= 0:
+            continue
+        t_hbm, t_mfma = c["bytes"] / (HBM_PEAK_GBS * 1e9), c["flops"] / (peak * 1e12)
+        gemm_calls[nm] = {"layer": c["layer"], "direction": c["direction"], "ms": t * 1e3, "TFLOPs": c["flops"] / t / 1e12,
+                          "GBs": c["bytes"] / t / 1e9, "binds": "hbm" if t_hbm > t_mfma else "mfma",
+                          "roof_ms": max(t_hbm, t_mfma) * 1e3, "frac_roof": max(t_hbm, t_mfma) / t,
+                          "frac_mfma": c["flops"] / t / 1e12 / peak}
+    gemm = {"timing": "HIP events around each product call with the call alone on the GPU (extra one-stream steps after the "
+                      "timed region); a layer's figure = sum of its calls' roof times / sum of their durations",
+            "calls": gemm_calls}
     for l in range(1, L + 1):
-        K, N = w.dims[l - 1], w.dims[l]
-        nl = model.n_rows_of_layer(l)
-        srcs = 2 if S.sage else 1
-        f_fwd = 2.0 * nl * K * N * srcs
-        f_bwd = f_fwd * (2 if l > 1 else 1)
-        tf, tb = lin_f(l) * 1e-3, lin_b(l) * 1e-3
-        peak = MFMA_PEAK_TFLOPS[w.dtype]
-        b_fwd = nl * (K * srcs + N) * es
-        # backward, every operand once: the (already masked) output gradient and the layer inputs in, the input gradients out
-        b_bwd = nl * (N + K * srcs) * es + (nl * K * srcs * es if l > 1 else 0)
-        # the roof that binds a product this skinny: the slower of "operands at the HBM peak" and "flops at the MFMA peak"
-        roof_f = max(b_fwd / (HBM_PEAK_GBS * 1e9), f_fwd / (peak * 1e12))
-        roof_b = max(b_bwd / (HBM_PEAK_GBS * 1e9), f_bwd / (peak * 1e12))
-        gemm[str(l)] = {"M": nl, "K": K * srcs, "N": N,
-                        "fwd_TFLOPs": f_fwd / tf / 1e12 if tf > 0 else None, "fwd_frac_mfma": f_fwd / tf / 1e12 / peak if tf > 0 else None,
-                        "fwd_GBs": b_fwd / tf / 1e9 if tf > 0 else None,
-                        "fwd_binds": "hbm" if b_fwd / (HBM_PEAK_GBS * 1e9) > f_fwd / (peak * 1e12) else "mfma",
-                        "fwd_frac_roof": roof_f / tf if tf > 0 else None,
-                        "bwd_TFLOPs": f_bwd / tb / 1e12 if tb > 0 else None, "bwd_frac_mfma": f_bwd / tb / 1e12 / peak if tb > 0 else None,
-                        "bwd_GBs": b_bwd / tb / 1e9 if tb > 0 else None,
-                        "bwd_binds": "hbm" if b_bwd / (HBM_PEAK_GBS * 1e9) > f_bwd / (peak * 1e12) else "mfma",
-                        "bwd_frac_roof": roof_b / tb if tb > 0 else None,
-                        "bwd_timing": "sum of the layer's backward product calls; the weight-gradient product shares the GPU with an "
-                                      "aggregation on the other stream unless --one-stream" if not args.one_stream else "one stream"}
+        rec = {"K": w.dims[l - 1], "N": w.dims[l], "rows": model.n_rows_of_layer(l),
+               "order": "transform first" if l in model.tf_layers else "aggregate first",
+               "input_gradient": "from the aggregated output gradient, one two-source product" if l in model.gf_layers else
+                                 ("none" if l == 1 else "per source, then aggregated")}
+        for d in ("fwd", "bwd"):
+            sel = [c for c in gemm_calls.values() if c["layer"] == l and c["direction"] == d]
+            if sel:
+                tt, rr = sum(c["ms"] for c in sel), sum(c["roof_ms"] for c in sel)
+                ff = sum(c["TFLOPs"] * c["ms"] for c in sel)
+                rec[f"{d}_ms"] = tt
+                rec[f"{d}_frac_roof"] = rr / tt
+                rec[f"{d}_TFLOPs"] = ff / tt
+                rec[f"{d}_frac_mfma"] = ff / tt / peak
+                rec[f"{d}_binds"] = max(sel, key=lambda c: c["roof_ms"])["binds"]
         if l == dom:
             for key in ("linear_fwd_dom", "linear_bwd_dom"):
                 if key in side:
-                    gemm[str(l)][key + "_counters"] = side[key]
+                    rec[key + "_counters"] = side[key]
+        gemm[str(l)] = rec
 
     # ---- set expansion: 4 B per frontier edge (rows of rings 0 .. L-1), 8 B row bounds per frontier vertex, 8 B (distance and
     # ring-list entry) per reached vertex
@@ -638,6 +660,15 @@ def bench_res_model(args, w, part, sampled_graph, dtype, steps, warmup):
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     # the partition's halo was cut for the workload's own depth: deeper models see the same vertices (the late active
     # sets are the whole partition, as in configs[3])
+    es = 4 if dtype == torch.float32 else 2
+    need = part.graph.n_rows * P.row_stride(hid, dtype) * es * (L * (1 if args.recompute else 3) + 8)
+    have = torch.cuda.get_device_properties(0).total_memory
+    if need > 0.9 * have:       # say so instead of driving the allocator into the wall
+        return {"metric": "aggregated_edges_per_sec", "value": None, "unit": "edges/s", "n_gpus": 1,
+                "config": {"workload": f"deep residual GraphSAGE (ResSAGE+), {L} layers, hidden {hid}, on the partition of "
+                                       f"configs[{CONFIG_INDEX[args.workload]}]", "layers": L, "hidden": hid,
+                           "recompute": bool(args.recompute), "n_local": part.graph.n_rows},
+                "does_not_fit": {"needed_bytes": int(need), "device_bytes": int(have)}}
     G = sampled_graph if sampled_graph is not None else P.Graph.from_numpy(part.graph.row_ptr, part.graph.col_idx)
     params = [{k: dev(v) for k, v in p.items()} for p in gg.res_layer_weights(dims, w.seed)]
     model = P.ResSAGEPlus(G, G, dev(part.targets), params, dtype=dtype, recompute=args.recompute,
@@ -661,7 +692,6 @@ def bench_res_model(args, w, part, sampled_graph, dtype, steps, warmup):
     call_ms = {k: float(np.mean(v)) for k, v in per_call.items()}
     edges = model.aggregated_edges()
     total_edges = sum(e["fwd"] + e["bwd"] + e["again"] for e in edges.values())
-    es = 4 if dtype == torch.float32 else 2
     dom = max(range(2, L + 1), key=lambda l: call_ms.get(f"spmm_fwd_{l}", 0.0))
     nd = model.n_rows_of_layer(dom)
     alg_bytes = edges[dom]["fwd"] * (4 + hid * es) + nd * (8 + hid * es)
@@ -681,12 +711,24 @@ def bench_res_model(args, w, part, sampled_graph, dtype, steps, warmup):
         "ms_by_kind": {"spmm_fwd": group("spmm_fwd"), "spmm_bwd": group("spmm_bwd"), "linear_fwd": group("linear_fwd"),
                        "linear_bwd": group("linear_bwd"), "layer_norm_fwd": group("ln_fwd"), "layer_norm_bwd": group("ln_bwd"),
                        "residual": group("residual"), "active_sets": call_ms.get("active_sets"), "softmax_ce": call_ms.get("softmax_ce")},
-        "roofline": {"kernel": f"spmm_rows_kernel; gnn_masked_spmm_fwd, layer {dom}, F={hid}", "bound": "hbm",
-                     "achieved": alg_bytes / t_dom / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": alg_bytes / t_dom / 1e9 / HBM_PEAK_GBS, "frac_basis": "gather model", "traffic": None,
-                     "bytes_per_launch": alg_bytes, "launch_ms": t_dom * 1e3},
+        "roofline": res_roofline(f"spmm_rows_kernel; gnn_masked_spmm_fwd, layer {dom}, F={hid}", alg_bytes,
+                                 edges[dom]["fwd"] * 4 + model.n_rows_of_layer(dom - 1) * hid * es + nd * (8 + hid * es), t_dom),
         "cpu_baseline": None,
     }
+
+
+def res_roofline(kernel, gather_bytes, compulsory_bytes, t_s):
+    """No counter reading exists for these shapes.  The gather model (every neighbour row from memory) is what the
+    launch is priced on while it stays below the HBM peak; wide rows are re-read from L2 often enough that the model
+    overshoots the peak - then only the lower bound (every operand once) can be claimed."""
+    g = gather_bytes / t_s / 1e9
+    over = g > HBM_PEAK_GBS
+    ach = compulsory_bytes / t_s / 1e9 if over else g
+    return {"kernel": kernel, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "frac_basis": "compulsory bytes (the gather model exceeds the HBM peak: neighbour rows come from L2)" if over
+                          else "gather model",
+            "traffic": None, "bytes_per_launch": compulsory_bytes if over else gather_bytes, "launch_ms": t_s * 1e3,
+            "gather_GBs": g, "compulsory_GBs": compulsory_bytes / t_s / 1e9}
 
 
 def cpu_baseline(part, w, params, H0, rows_all, flops_budget):

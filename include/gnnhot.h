@@ -81,6 +81,13 @@ const char *gnn_last_error(void);
  * Per-layer active vertex sets (section 6: step 1 extracts the multi-hop dependency starting
  * from the inner vertices; step 4 generates the per-layer mask).  Level-synchronous frontier
  * expansion from T over CSR rows, L levels deep.
+ *   gt               nullable: the transpose of g (same sizes; entry (u, v) for every entry (v, u) of g;
+ *                    g itself for a symmetric graph).  With it a level may run from the unreached
+ *                    vertices instead of from the frontier (each looks through its row of gt for a
+ *                    frontier vertex and stops at the first), chosen on the device per level from
+ *                    the exact edge counts of the two directions.  The outputs are the same with and
+ *                    without it; a gt that is not the transpose gives wrong sets (never an
+ *                    out-of-bounds access).
  *   targets          [n_targets] vertex ids; repeats are allowed (set semantics);
  *                    ids outside [0, n_rows) are ignored
  *   dist             out [n_rows]: hop distance, -1 if farther than L hops or unreachable
@@ -92,8 +99,8 @@ const char *gnn_last_error(void);
  *                    stream before returning
  * Requires g->n_rows == g->n_cols.  All outputs are bit-exact functions of the inputs.
  */
-int32_t gnn_build_active_sets(const gnn_csr *g, const int32_t *targets, int32_t n_targets, int32_t L,
-                              int32_t *dist, int32_t *ring_ids, int64_t *hop_offsets,
+int32_t gnn_build_active_sets(const gnn_csr *g, const gnn_csr *gt, const int32_t *targets, int32_t n_targets,
+                              int32_t L, int32_t *dist, int32_t *ring_ids, int64_t *hop_offsets,
                               int64_t *hop_offsets_host, void *ws, size_t *ws_bytes, void *stream);
 
 /*

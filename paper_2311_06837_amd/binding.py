@@ -158,9 +158,10 @@ def gnn_version() -> int:
     return int(lib().gnn_version())
 
 
-def gnn_build_active_sets(g: Graph, targets: torch.Tensor, L: int, sync: bool = True, ws: Workspace | None = None):
+def gnn_build_active_sets(g: Graph, targets: torch.Tensor, L: int, sync: bool = True, ws: Workspace | None = None,
+                          gt: Graph | None = None):
     """-> dist int32[n], ring_ids int32[n] (first hop_offsets[L+1] valid), hop_offsets int64[L+2] (device),
-    and the host copy of hop_offsets as a list (None when sync is False)."""
+    and the host copy of hop_offsets as a list (None when sync is False).  gt: the transposed graph (optional)."""
     _i32(targets, "targets")
     dev = g.row_ptr.device
     dist = torch.empty(g.n_rows, dtype=torch.int32, device=dev)
@@ -168,7 +169,7 @@ def gnn_build_active_sets(g: Graph, targets: torch.Tensor, L: int, sync: bool = 
     off = torch.empty(L + 2, dtype=torch.int64, device=dev)
     host = (C.c_int64 * (L + 2))() if sync else None
     _with_ws(lib().gnn_build_active_sets,
-             (C.byref(g.c), _ptr(targets) if targets.numel() else None, C.c_int32(targets.numel()), C.c_int32(L),
+             (C.byref(g.c), C.byref(gt.c) if gt is not None else None, _ptr(targets) if targets.numel() else None, C.c_int32(targets.numel()), C.c_int32(L),
               _ptr(dist) if g.n_rows else None, _ptr(ring), _ptr(off), host),
              (_stream(),), ws)
     return dist, ring, off, (list(host) if sync else None)

@@ -2,27 +2,35 @@
 // (paper section 6, figure 7c: step 1 extracts the multi-hop dependency from the inner
 // vertices, step 4 generates the per-layer mask).
 //
-// Data layout.  Two bitmaps of n bits live in the workspace: `visited` (everything reached
-// by the levels before the one being expanded, read-only while it expands) and `seen`
-// (`visited` plus what the level has found so far: the only word an edge probes, and sets
-// if its bit is still clear).  A level is: expand (edge gather + one bit probe per edge) ->
-// count / scan / emit, a compaction of seen & ~visited that lists the new ring in ascending
-// id order without any sort, so the output does not depend on which wave found a vertex
-// first; emit then makes visited equal to seen.  Ring sizes stay on the device
-// (hop_offsets); every kernel has a fixed grid and reads its bounds from there, so the
-// whole construction is enqueued without a host round trip.
+// Data layout.  Three bitmaps of n bits live in the workspace: `visited` (everything reached
+// by the levels before the one being expanded, read-only while it expands), `seen`
+// (`visited` plus what the level has found so far) and `frontier` (the ring the last level
+// found).  A level is: expand -> count / scan / emit, a compaction of seen & ~visited that
+// lists the new ring in ascending id order without any sort, so the output does not depend on
+// which wave found a vertex first; emit then makes visited equal to seen.  Ring sizes stay on
+// the device (hop_offsets); every kernel has a fixed grid and reads its bounds from there, so
+// the whole construction is enqueued without a host round trip.
 //
-// The expansion is EDGE-parallel: a wavefront takes 64 frontier vertices, reads their row
-// bounds in one sweep, and then walks the concatenation of their rows 256 edges at a time
-// (each lane finds the row of its edge by a binary search over the 64 prefix sums in LDS),
-// so rows of 5 and rows of 500 entries keep all lanes busy alike and every lane has four
-// independent index loads and four bitmap probes in flight.  (A lane group per vertex, the
-// first form of this kernel, paid a chain of dependent loads per vertex: 0.9 ms for the
-// 20M edges of the 8-level workload.)
+// A level expands in one of two directions; the sets are the same either way.
+//   push  (from the frontier)  EDGE-parallel: a wavefront takes 64 frontier vertices, reads
+//         their row bounds in one sweep, and then walks the concatenation of their rows 256
+//         edges at a time (each lane finds the row of its edge by a binary search over the 64
+//         prefix sums in LDS), so rows of 5 and rows of 500 entries keep all lanes busy alike
+//         and every lane has four independent index loads and four bitmap probes in flight.
+//         One probe of `seen` per edge; the bit is set if still clear.
+//   pull  (from the unreached vertices; needs the transposed graph)  sixteen lanes per
+//         unreached vertex scan its row of the transposed graph - the vertices that would
+//         reach it - and stop at the first one that is in `frontier`.  Once the frontier is
+//         most of the graph, nearly every edge of a push level points at a vertex that is
+//         already in the set; the pull level only touches the few vertices still outside.
+// The direction is chosen on the device, per level, from exact integer sums (as_plan_kernel):
+// pull when the frontier's edges outnumber what a pull can touch at most, the transposed
+// rows of the unreached vertices plus sixteen lanes for each of them.  Both kernels of a level
+// are enqueued; the one whose turn it is not returns at once.
 //
-// Bound: HBM bandwidth.  Per level the algorithm reads each edge of the frontier once
-// (4 B) and writes 8 B per newly reached vertex; the bit probes hit a bitmap of n/8 bytes
-// that stays in L2.
+// Bound: a push level reads each edge of the frontier once (4 B, streaming) and makes one
+// 4-byte probe per edge into a bitmap of n/8 bytes that stays in L2: the probes, not the
+// bytes, are what limits it (the L2s serve a fixed number of requests per clock).
 #include "common.h"
 #include "hashkey.h"
 #include "scan.h"
@@ -34,8 +42,20 @@ constexpr int kAsHubDegree = 2048;      // longer rows are queued and expanded b
 
 struct AsCtrl {
     int32_t n_hubs;
-    int32_t pad[7];
+    int32_t pad;
+    unsigned long long frontier_edges;   // entries of the frontier's rows (graph), this level
+    unsigned long long reached_edges_t;  // entries of the transposed rows of everything reached so far
+    unsigned long long pad2;
 };
+
+// True when this level runs in the pull direction.  frontier = ring `ring_prev`.  A pull touches at most the transposed
+// rows of the unreached vertices, sixteen lanes at a time.
+__device__ __forceinline__ bool as_pull_level(const AsCtrl* ctrl, const int64_t* __restrict__ hop_offsets, int32_t ring_prev,
+                                              int64_t n, int64_t nnz_t) {
+    const int64_t unreached = n - hop_offsets[ring_prev + 1];
+    const int64_t unreached_edges = nnz_t - (int64_t)ctrl->reached_edges_t;
+    return (int64_t)ctrl->frontier_edges > unreached_edges + 16 * unreached;
+}
 
 __global__ __launch_bounds__(256) void as_init_kernel(int32_t* __restrict__ dist, int32_t n, uint32_t* __restrict__ visited,
                                                       uint32_t* __restrict__ seen, int64_t nw, AsCtrl* ctrl,
@@ -47,7 +67,11 @@ __global__ __launch_bounds__(256) void as_init_kernel(int32_t* __restrict__ dist
         visited[w] = 0u;
         seen[w] = 0u;
     }
-    if (tid == 0) ctrl->n_hubs = 0;
+    if (tid == 0) {
+        ctrl->n_hubs = 0;
+        ctrl->frontier_edges = 0ull;
+        ctrl->reached_edges_t = 0ull;
+    }
     if (tid <= L + 1) hop_offsets[tid] = 0;
 }
 
@@ -61,13 +85,16 @@ __global__ __launch_bounds__(256) void as_seed_kernel(const int32_t* __restrict_
 
 constexpr int kAsU = 4;   // edges per lane and step: their index loads, then their bitmap probes, are issued together
 
-// One wavefront per 64 entries of the frontier list (grid-stride), edge-parallel inside (see the head of the file).
+// Push level.  One wavefront per 64 entries of the frontier list (grid-stride), edge-parallel inside (see the head of
+// the file).  nnz_t < 0: no transposed graph was given, every level is a push level.
 __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                         const int32_t* __restrict__ ring_ids,
                                                         const int64_t* __restrict__ hop_offsets, int32_t ring,
-                                                        uint32_t* __restrict__ seen, int32_t* __restrict__ hubq, AsCtrl* ctrl) {
+                                                        uint32_t* __restrict__ seen, int32_t* __restrict__ hubq, AsCtrl* ctrl,
+                                                        int32_t n, int64_t nnz_t) {
     __shared__ int32_t s_start[4][kWave];
     __shared__ int32_t s_excl[4][kWave + 1];
+    if (nnz_t >= 0 && as_pull_level(ctrl, hop_offsets, ring, n, nnz_t)) return;   // uniform over the grid
     const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
     const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
     int32_t* st = s_start[wave];
@@ -123,7 +150,8 @@ __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restric
     }
 }
 
-// Hub rows: one workgroup per queued row (grid-stride over the queue), threads across the row, four entries per step.
+// Hub rows of a push level: one workgroup per queued row (grid-stride over the queue), threads across the row, four
+// entries per step.  (In a pull level the queue is empty when this kernel runs.)
 __global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                              uint32_t* __restrict__ seen, const int32_t* __restrict__ hubq,
                                                              const AsCtrl* ctrl) {
@@ -142,6 +170,99 @@ __global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __re
             for (int j = 0; j < kAsU; ++j) {
                 const uint32_t bit = 1u << (u[j] & 31);
                 if (base + j * 256 < e && !(w[j] & bit)) atomicOr(&seen[u[j] >> 5], bit);
+            }
+        }
+    }
+}
+
+// Exact sums the direction switch needs, over the ring the next level expands: entries of its rows (what a push
+// reads) and entries of its transposed rows (added to the running total of everything reached).  Integer atomics:
+// the totals do not depend on the order of the additions.
+__global__ __launch_bounds__(256) void as_plan_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ row_ptr_t,
+                                                      const int32_t* __restrict__ ring_ids, const int64_t* __restrict__ hop_offsets,
+                                                      int32_t ring, AsCtrl* ctrl) {
+    __shared__ unsigned long long s_a[4], s_b[4];
+    const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
+    unsigned long long a = 0ull, b = 0ull;
+    for (int64_t i = begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < end; i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t v = ring_ids[i];
+        a += (unsigned long long)(row_ptr[v + 1] - row_ptr[v]);
+        b += (unsigned long long)(row_ptr_t[v + 1] - row_ptr_t[v]);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        a += __shfl_xor(a, d, kWave);
+        b += __shfl_xor(b, d, kWave);
+    }
+    if (lane_id() == 0) {
+        s_a[threadIdx.x >> 6] = a;
+        s_b[threadIdx.x >> 6] = b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = s_a[0] + s_a[1] + s_a[2] + s_a[3];
+        b = s_b[0] + s_b[1] + s_b[2] + s_b[3];
+        if (a) atomicAdd(&ctrl->frontier_edges, a);
+        if (b) atomicAdd(&ctrl->reached_edges_t, b);
+    }
+}
+
+// Pull level.  Sixteen lanes per bitmap word (grid-stride): for each vertex of the word that is not in the set yet,
+// scan its transposed row 64 entries at a time and stop at the first entry that is in the frontier.  A lane group
+// is the only writer of its word in this kernel.  Rows longer than kAsHubDegree go to the queue.
+__global__ __launch_bounds__(256) void as_pull_kernel(const int32_t* __restrict__ row_ptr_t, const int32_t* __restrict__ col_idx_t,
+                                                      int32_t n, int64_t nw, const uint32_t* __restrict__ visited,
+                                                      uint32_t* __restrict__ seen, const uint32_t* __restrict__ frontier,
+                                                      const int64_t* __restrict__ hop_offsets, int32_t ring, int64_t nnz_t,
+                                                      int32_t* __restrict__ hubq, AsCtrl* ctrl) {
+    if (!as_pull_level(ctrl, hop_offsets, ring, n, nnz_t)) return;   // uniform over the grid
+    const int lane = lane_id(), sub = lane / 16, sl = lane % 16;
+    const int64_t groups = ((int64_t)gridDim.x * blockDim.x) / 16;
+    for (int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 16; w < nw; w += groups) {
+        uint32_t open = ~visited[w];
+        if (w == nw - 1 && (n & 31)) open &= (1u << (n & 31)) - 1u;
+        uint32_t add = 0u;
+        while (open) {   // uniform over the lane group
+            const int b = __ffs(open) - 1;
+            open &= open - 1u;
+            const int32_t v = (int32_t)(w * 32 + b);
+            const int32_t s = row_ptr_t[v], e = row_ptr_t[v + 1];
+            if (e - s > kAsHubDegree) {
+                if (sl == 0) hubq[atomicAdd(&ctrl->n_hubs, 1)] = v;
+                continue;
+            }
+            bool found = false;
+            for (int32_t p = s; p < e && !found; p += 64) {
+                int32_t u[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) u[j] = p + j * 16 + sl < e ? col_idx_t[p + j * 16 + sl] : -1;
+                bool hit = false;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) hit |= u[j] >= 0 && in_set(frontier, u[j]);
+                found = ((__ballot(hit) >> (sub * 16)) & 0xffffull) != 0ull;
+            }
+            if (found) add |= 1u << b;
+        }
+        if (add && sl == 0) atomicOr(&seen[w], add);
+    }
+}
+
+// Long rows of a pull level: one workgroup per queued vertex, 256 entries per step, until one is in the frontier.
+__global__ __launch_bounds__(256) void as_pull_hubs_kernel(const int32_t* __restrict__ row_ptr_t, const int32_t* __restrict__ col_idx_t,
+                                                           uint32_t* __restrict__ seen, const uint32_t* __restrict__ frontier,
+                                                           const int64_t* __restrict__ hop_offsets, int32_t ring, int32_t n,
+                                                           int64_t nnz_t, const int32_t* __restrict__ hubq, const AsCtrl* ctrl) {
+    if (!as_pull_level(ctrl, hop_offsets, ring, n, nnz_t)) return;
+    const int32_t n_hubs = ctrl->n_hubs;
+    for (int32_t h = blockIdx.x; h < n_hubs; h += gridDim.x) {   // uniform over the workgroup
+        const int32_t v = hubq[h];
+        const int32_t s = row_ptr_t[v], e = row_ptr_t[v + 1];
+        for (int32_t base = s; base < e; base += 256) {
+            const int32_t p = base + (int32_t)threadIdx.x;
+            const int hit = p < e && in_set(frontier, col_idx_t[p]);
+            if (__syncthreads_or(hit)) {
+                if (threadIdx.x == 0) atomicOr(&seen[v >> 5], 1u << (v & 31));
+                break;
             }
         }
     }
@@ -166,13 +287,15 @@ __global__ __launch_bounds__(1024) void as_scan_kernel(int32_t* __restrict__ blk
     if (threadIdx.x == 0) {
         hop_offsets[ring + 1] = hop_offsets[ring] + total;
         ctrl->n_hubs = 0;
+        ctrl->frontier_edges = 0ull;
     }
 }
 
 __global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(const uint32_t* __restrict__ seen, uint32_t* __restrict__ visited,
                                                                    int64_t nw, const int32_t* __restrict__ blk_cnt,
                                                                    const int64_t* __restrict__ hop_offsets, int32_t ring,
-                                                                   int32_t* __restrict__ ring_ids, int32_t* __restrict__ dist) {
+                                                                   int32_t* __restrict__ ring_ids, int32_t* __restrict__ dist,
+                                                                   uint32_t* __restrict__ frontier) {
     __shared__ int s_part[kAsWordsPerBlock / kWave];
     const int64_t w = (int64_t)blockIdx.x * kAsWordsPerBlock + threadIdx.x;
     uint32_t fresh = 0u;
@@ -180,6 +303,7 @@ __global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(const uint32_
         const uint32_t sn = seen[w], vis = visited[w];
         fresh = sn & ~vis;
         if (fresh) visited[w] = sn;
+        if (frontier != nullptr) frontier[w] = fresh;   // the ring a pull level looks for
     }
     int total;
     const int before = block_exclusive_scan<kAsWordsPerBlock>(__popc(fresh), s_part, &total);
@@ -221,6 +345,10 @@ __device__ __forceinline__ uint64_t eas_key(int32_t rule, uint64_t seed_hop_mixe
     return rule == 1 ? (uint64_t)(0xffffffffu - (uint32_t)conn[u]) : edge_key(seed_hop_mixed, (uint64_t)v, (uint64_t)u);
 }
 
+constexpr int kEasShortRow = 64;    // rows up to this length: sixteen lanes each; longer rows: a wavefront each
+constexpr int kEasListCap = 1024;   // candidates of one long row that a wavefront keeps in LDS
+
+// Rows of at most kEasShortRow entries.
 // Sixteen lanes per frontier vertex, four vertices per wavefront; loops run to the longest row of the wavefront so
 // that ballots and shuffles stay convergent.  A row with more than `fanout` candidates finds the fanout-th smallest
 // (key, id) by `fanout` rounds of "smallest pair above the previous one" (the row is re-read from cache).
@@ -239,6 +367,7 @@ __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restri
             v = ring_ids[i];
             s = row_ptr[v];
             e = row_ptr[v + 1];
+            if (e - s > kEasShortRow) e = s;   // eas_expand_long_kernel takes this row
         }
         int len_max = e - s;
         len_max = max(len_max, __shfl_xor(len_max, 16, kWave));
@@ -303,16 +432,123 @@ __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restri
     }
 }
 
+// Rows longer than kEasShortRow: one wavefront per frontier vertex.  The row is read once; its candidates (neighbours
+// not selected when the hop started) go to a list in LDS with their keys (one key computation and, for the
+// best-connected-first rule, one read of conn[] per candidate).  With more than `fanout` candidates the fanout-th
+// smallest (key, id) is found by `fanout` rounds of "smallest pair above the previous one" over the list.  A row with
+// more candidates than the list holds runs the same rounds over the row itself.
+__global__ __launch_bounds__(256) void eas_expand_long_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                               const int32_t* __restrict__ ring_ids,
+                                                               const int64_t* __restrict__ hop_offsets, int32_t ring,
+                                                               const uint32_t* __restrict__ visited, uint32_t* __restrict__ seen,
+                                                               int32_t fanout, int32_t rule, uint64_t seed_hop_mixed,
+                                                               const int32_t* __restrict__ conn) {
+    __shared__ uint64_t s_key[4][kEasListCap];
+    __shared__ int32_t s_id[4][kEasListCap];
+    const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
+    const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
+    uint64_t* key = s_key[wave];
+    int32_t* id = s_id[wave];
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    if (fanout == 0) return;   // nothing is selected
+    for (int64_t i = begin + (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6); i < end; i += waves) {   // uniform over the wave
+        const int32_t v = ring_ids[i];
+        const int32_t s = row_ptr[v], e = row_ptr[v + 1];
+        if (e - s <= kEasShortRow) continue;
+        int32_t n_cand = 0;
+        for (int32_t p = s; p < e; p += kWave) {
+            const int32_t q = p + lane;
+            const int32_t u = q < e ? col_idx[q] : 0;
+            const bool cand = q < e && !in_set(visited, u);
+            const uint64_t mask = __ballot(cand);
+            const int32_t pos = n_cand + __popcll(mask & lanes_below);
+            if (cand && pos < kEasListCap) {
+                key[pos] = eas_key(rule, seed_hop_mixed, conn, v, u);
+                id[pos] = u;
+            }
+            n_cand += __popcll(mask);
+        }
+        wave_lds_sync();
+        const bool listed = n_cand <= kEasListCap;
+        uint64_t thr_k = ~0ull;   // candidates with (key, id) <= (thr_k, thr_u) are kept
+        int32_t thr_u = 0x7fffffff;
+        if (n_cand > fanout) {
+            uint64_t prev_k = 0ull;
+            int32_t prev_u = -1;
+            for (int32_t round = 0; round < fanout; ++round) {
+                uint64_t best_k = ~0ull;
+                int32_t best_u = 0x7fffffff;
+                if (listed) {
+                    for (int32_t j = lane; j < n_cand; j += kWave) {
+                        const uint64_t k = key[j];
+                        const int32_t u = id[j];
+                        if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
+                            best_k = k;
+                            best_u = u;
+                        }
+                    }
+                } else {
+                    for (int32_t p = s + lane; p < e; p += kWave) {
+                        const int32_t u = col_idx[p];
+                        if (in_set(visited, u)) continue;
+                        const uint64_t k = eas_key(rule, seed_hop_mixed, conn, v, u);
+                        if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
+                            best_k = k;
+                            best_u = u;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const uint64_t ok = __shfl_xor(best_k, d, kWave);
+                    const int32_t ou = __shfl_xor(best_u, d, kWave);
+                    if (pair_less(ok, ou, best_k, best_u)) {
+                        best_k = ok;
+                        best_u = ou;
+                    }
+                }
+                prev_k = best_k;
+                prev_u = best_u;
+            }
+            thr_k = prev_k;
+            thr_u = prev_u;
+        }
+        if (listed) {
+            for (int32_t j = lane; j < n_cand; j += kWave) {
+                const int32_t u = id[j];
+                const uint32_t bit = 1u << (u & 31);
+                if (!pair_less(thr_k, thr_u, key[j], u) && !(seen[u >> 5] & bit)) atomicOr(&seen[u >> 5], bit);
+            }
+        } else {
+            for (int32_t p = s + lane; p < e; p += kWave) {
+                const int32_t u = col_idx[p];
+                if (in_set(visited, u)) continue;
+                const uint32_t bit = 1u << (u & 31);
+                if (!pair_less(thr_k, thr_u, eas_key(rule, seed_hop_mixed, conn, v, u), u) && !(seen[u >> 5] & bit))
+                    atomicOr(&seen[u >> 5], bit);
+            }
+        }
+        wave_lds_sync();   // the lists are read before the next row overwrites them
+    }
+}
+
 }  // namespace gnnhot
 
 using namespace gnnhot;
 
-extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* targets, int32_t n_targets, int32_t L,
+extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const gnn_csr* gt, const int32_t* targets, int32_t n_targets, int32_t L,
                                          int32_t* dist, int32_t* ring_ids, int64_t* hop_offsets, int64_t* hop_offsets_host,
                                          void* ws, size_t* ws_bytes, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     GNN_CHECK(check_csr(g, "g"));
     GNN_REQUIRE(g->n_rows == g->n_cols, GNN_ERR_SHAPE, "active sets need a square graph (%d x %d)", g->n_rows, g->n_cols);
+    if (gt != nullptr) {
+        GNN_CHECK(check_csr(gt, "gt"));
+        GNN_REQUIRE(gt->n_rows == g->n_rows && gt->n_cols == g->n_cols && gt->nnz == g->nnz, GNN_ERR_SHAPE,
+                    "gt (%d x %d, %lld entries) is not the transpose of g (%d x %d, %lld entries)", gt->n_rows, gt->n_cols,
+                    (long long)gt->nnz, g->n_rows, g->n_cols, (long long)g->nnz);
+    }
     GNN_REQUIRE(L >= 1 && L <= 1024, GNN_ERR_INVALID_ARG, "L = %d out of range [1, 1024]", L);
     GNN_REQUIRE(n_targets >= 0, GNN_ERR_INVALID_ARG, "n_targets < 0");
     const int32_t n = g->n_rows;
@@ -322,6 +558,7 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* target
     WsCarver carve(ws);
     uint32_t* visited = carve.take<uint32_t>((size_t)nw + 1);
     uint32_t* seen = carve.take<uint32_t>((size_t)nw + 1);
+    uint32_t* frontier = carve.take<uint32_t>((size_t)nw + 1);
     int32_t* blk_cnt = carve.take<int32_t>((size_t)nb + 1);
     int32_t* hubq = carve.take<int32_t>((size_t)n + 1);
     AsCtrl* ctrl = carve.take<AsCtrl>(1);
@@ -341,18 +578,33 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const int32_t* target
             GNN_LAUNCH_CHECK("as_seed_kernel");
         }
         const int expand_grid = 2048;  // 8 waves per CU-slot; bounds are read on the device
+        const int64_t nnz_t = gt != nullptr ? gt->nnz : -1;   // < 0: every level pushes
         for (int32_t ring = 0; ring <= L; ++ring) {
             if (ring > 0) {
-                as_expand_kernel<<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, seen, hubq, ctrl);
+                if (gt != nullptr) {
+                    as_plan_kernel<<<512, 256, 0, stream>>>(g->row_ptr, gt->row_ptr, ring_ids, hop_offsets, ring - 1, ctrl);
+                    GNN_LAUNCH_CHECK("as_plan_kernel");
+                }
+                as_expand_kernel<<<expand_grid, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, seen, hubq, ctrl,
+                                                                  n, nnz_t);
                 GNN_LAUNCH_CHECK("as_expand_kernel");
                 as_expand_hubs_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, seen, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_hubs_kernel");
+                if (gt != nullptr) {
+                    as_pull_kernel<<<grid_for(nw * 16, 256, expand_grid), 256, 0, stream>>>(gt->row_ptr, gt->col_idx, n, nw, visited, seen,
+                                                                                           frontier, hop_offsets, ring - 1, nnz_t, hubq, ctrl);
+                    GNN_LAUNCH_CHECK("as_pull_kernel");
+                    as_pull_hubs_kernel<<<1024, 256, 0, stream>>>(gt->row_ptr, gt->col_idx, seen, frontier, hop_offsets, ring - 1, n, nnz_t,
+                                                                  hubq, ctrl);
+                    GNN_LAUNCH_CHECK("as_pull_hubs_kernel");
+                }
             }
             as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt);
             GNN_LAUNCH_CHECK("as_count_kernel");
             as_scan_kernel<<<1, 1024, 0, stream>>>(blk_cnt, nb, hop_offsets, ring, ctrl);
             GNN_LAUNCH_CHECK("as_scan_kernel");
-            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
+            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist,
+                                                                     gt != nullptr ? frontier : nullptr);
             GNN_LAUNCH_CHECK("as_emit_kernel");
         }
     }
@@ -407,12 +659,15 @@ extern "C" int32_t gnn_eas_traverse(const gnn_csr* g, const int32_t* targets, in
                 eas_expand_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited, seen, fanout,
                                                             rule, mix64(seed + (uint64_t)ring), conn);
                 GNN_LAUNCH_CHECK("eas_expand_kernel");
+                eas_expand_long_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, ring_ids, hop_offsets, ring - 1, visited, seen, fanout,
+                                                                 rule, mix64(seed + (uint64_t)ring), conn);
+                GNN_LAUNCH_CHECK("eas_expand_long_kernel");
             }
             as_count_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt);
             GNN_LAUNCH_CHECK("as_count_kernel");
             as_scan_kernel<<<1, 1024, 0, stream>>>(blk_cnt, nb, hop_offsets, ring, ctrl);
             GNN_LAUNCH_CHECK("as_scan_kernel");
-            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist);
+            as_emit_kernel<<<(int)nb, kAsWordsPerBlock, 0, stream>>>(seen, visited, nw, blk_cnt, hop_offsets, ring, ring_ids, dist, nullptr);
             GNN_LAUNCH_CHECK("as_emit_kernel");
         }
     }

@@ -153,7 +153,7 @@ class MaskedGNN:
     # -- step a1 -------------------------------------------------------------------------
     def build_active_sets(self):
         self.dist, self.ring_ids, self.hop_offsets, self.hop = self._call(
-            "active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws)
+            "active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws, gt=self.gt)
         if self.kind == "gcn":
             s = B.gnn_norm_scales(B.GNN_NORM_SYM, self.n, length=self.global_degree,
                                   row_ptr=None if self.global_degree is not None else self.g.row_ptr)
@@ -361,6 +361,58 @@ class MaskedGNN:
         self.backward()
         return self.loss
 
+    def product_costs(self) -> dict:
+        """call name -> (layer, direction, flops, operand bytes with every operand read or written once) of each
+        feature-transform product of a step, in the order this model runs them (host-side bookkeeping for the benchmark's
+        rooflines; the bias-only calls are left out)."""
+        es = torch.empty(0, dtype=self.dtype).element_size()
+        sage = self.kind == "sage"
+        srcs = 2 if sage else 1
+        out = {}
+
+        def put(name, l, direction, flops, nbytes):
+            out[name] = {"layer": l, "direction": direction, "flops": float(flops), "bytes": float(nbytes) * es}
+
+        for l in range(1, self.L + 1):
+            K, N = self.dims[l - 1], self.dims[l]
+            nl = self.n_rows_of_layer(l)
+            n_prev = self.n_rows_of_layer(l - 1) if l > 1 else self.n
+            need_in = l > 1
+            one = lambda m: (2.0 * m * K * N, m * (K + N))      # one product over m rows: flops, elements moved
+            both_in = (2.0 * N * K * (n_prev + (nl if sage else 0)),          # the two-source input gradient: G and dZ in,
+                       n_prev * N + (nl * N if sage else 0) + 2 * n_prev * K)   # the ReLU mask in, dH_{l-1} out
+            if l in self.tf_layers:
+                put(f"linear_pre_{l}", l, "fwd", *one(n_prev))
+                if sage:
+                    put(f"linear_fwd_{l}", l, "fwd", *one(nl))
+                    put(f"linear_bwd_{l}", l, "bwd", *one(nl))
+                    if need_in and l not in self.gf_layers:
+                        put(f"linear_bwd_{l}_input_self", l, "bwd", *one(nl))
+                put(f"linear_bwd_{l}_neigh", l, "bwd", *one(n_prev))
+                if need_in and l in self.gf_layers:
+                    put(f"linear_bwd_{l}_input", l, "bwd", *both_in)
+                elif need_in:
+                    put(f"linear_bwd_{l}_input", l, "bwd", 2.0 * n_prev * N * K, n_prev * (N + 2 * K) + (nl * K if sage else 0))
+                continue
+            if l not in self.fused_layers:
+                put(f"linear_fwd_{l}", l, "fwd", 2.0 * nl * K * N * srcs, nl * (K * srcs + N))
+            if l in self.gf_layers:
+                if l in self.fused_layers:
+                    put(f"linear_bwd_{l}", l, "bwd", *one(nl))
+                    put(f"linear_bwd_{l}_neigh", l, "bwd", *one(n_prev))
+                else:
+                    put(f"linear_bwd_{l}", l, "bwd", 2.0 * nl * K * N * srcs, nl * (N + K * srcs))
+                put(f"linear_bwd_{l}_input", l, "bwd", *both_in)
+            elif need_in and self.side is not None:
+                put(f"linear_bwd_{l}", l, "bwd", 2.0 * nl * K * N * srcs, nl * (N + K * srcs))
+                put(f"linear_bwd_{l}_input", l, "bwd", *one(nl))
+                if sage:
+                    put(f"linear_bwd_{l}_input_self", l, "bwd", *one(nl))
+            else:
+                f = 2.0 * nl * K * N * srcs
+                put(f"linear_bwd_{l}", l, "bwd", f * (2 if need_in else 1), nl * (N + K * srcs) + (nl * K * srcs if need_in else 0))
+        return out
+
     def aggregated_edges(self) -> dict:
         """Edges visited per layer by the forward and the backward aggregation of the paper's order (host-side
         bookkeeping from row_ptr; used by the benchmark's edges/s metric).  A first layer in the exchanged order aggregates
@@ -435,7 +487,7 @@ class ResSAGEPlus:
     _call = MaskedGNN._call
 
     def build_active_sets(self):
-        self.dist, self.ring_ids, self.hop_offsets, self.hop = self._call("active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws)
+        self.dist, self.ring_ids, self.hop_offsets, self.hop = self._call("active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws, gt=self.gt)
         self.rs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr)
         if self.prefix_numbered:
             n_all = int(self.hop[-1])

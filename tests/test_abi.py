@@ -41,19 +41,19 @@ def _csr(n_rows=4, n_cols=4, nnz=0, rp=1, ci=None):
 def test_bad_arguments_return_codes_without_touching_the_gpu(lib):
     need = C.c_size_t(0)
     # NULL graph
-    assert lib.gnn_build_active_sets(None, None, 0, 2, None, None, None, None, None, C.byref(need), None) == 1
+    assert lib.gnn_build_active_sets(None, None, None, 0, 2, None, None, None, None, None, C.byref(need), None) == 1
     assert b"NULL" in lib.gnn_last_error()
     g = _csr()
     # L < 1
-    assert lib.gnn_build_active_sets(C.byref(g), None, 0, 0, None, None, None, None, None, C.byref(need), None) == 1
+    assert lib.gnn_build_active_sets(C.byref(g), None, None, 0, 0, None, None, None, None, None, C.byref(need), None) == 1
     # non-square graph
     g2 = _csr(n_rows=4, n_cols=5)
-    assert lib.gnn_build_active_sets(C.byref(g2), None, 0, 2, None, None, None, None, None, C.byref(need), None) == 2
+    assert lib.gnn_build_active_sets(C.byref(g2), None, None, 0, 2, None, None, None, None, None, C.byref(need), None) == 2
     # nnz >= 2^31
     g3 = _csr(nnz=2**31, ci=1)
     assert lib.gnn_masked_spmm_fwd(C.byref(g3), None, 0, None, C.c_int64(4), None, C.c_int64(4), 4, 0, None, None, None, None, None) == 4
     # ws_bytes NULL
-    assert lib.gnn_build_active_sets(C.byref(g), None, 0, 2, None, None, None, None, None, None, None) == 1
+    assert lib.gnn_build_active_sets(C.byref(g), None, None, 0, 2, None, None, None, None, None, None, None) == 1
     # leading dimension smaller than F
     assert lib.gnn_masked_spmm_fwd(C.byref(g), None, 0, None, C.c_int64(3), None, C.c_int64(4), 4, 0, None, None, None, None, None) == 2
     # unknown dtype
@@ -86,14 +86,14 @@ def test_bad_arguments_return_codes_without_touching_the_gpu(lib):
 def test_workspace_query_and_too_small_workspace(lib):
     g = _csr(n_rows=1000, n_cols=1000)
     need = C.c_size_t(0)
-    assert lib.gnn_build_active_sets(C.byref(g), None, 0, 3, None, None, None, None, None, C.byref(need), None) == 0
+    assert lib.gnn_build_active_sets(C.byref(g), None, None, 0, 3, None, None, None, None, None, C.byref(need), None) == 0
     assert need.value >= 1000 * 4 and need.value % 256 == 0
     small = C.c_size_t(256)
-    assert lib.gnn_build_active_sets(C.byref(g), None, 0, 3, None, None, None, None, C.c_void_p(4096), C.byref(small), None) == 3
+    assert lib.gnn_build_active_sets(C.byref(g), None, None, 0, 3, None, None, None, None, C.c_void_p(4096), C.byref(small), None) == 3
     assert b"workspace too small" in lib.gnn_last_error()
     # misaligned workspace
     big = C.c_size_t(1 << 30)
-    assert lib.gnn_build_active_sets(C.byref(g), None, 0, 3, None, None, None, None, C.c_void_p(4100), C.byref(big), None) == 1
+    assert lib.gnn_build_active_sets(C.byref(g), None, None, 0, 3, None, None, None, None, C.c_void_p(4100), C.byref(big), None) == 1
     need2 = C.c_size_t(0)
     assert lib.gnn_linear_bwd(None, 100000, None, None, C.c_int64(256), 1, None, None, C.c_int64(608), 602, None, None, 256, None,
                               None, None, None, None, C.c_int64(0), 0, None, C.byref(need2), None) == 0

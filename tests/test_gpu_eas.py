@@ -57,6 +57,10 @@ def test_long_rows_and_ragged_sizes(rule):
     _compare(g, T, 2, 7, rule, seed=9)
     d = gg.random_directed(10007, 6.0, 2)                       # directed: rows are what a vertex aggregates
     _compare(d, np.arange(0, 10007, 37), 3, 2, rule, seed=4)
+    big = gg.chung_lu(20000, 1500.0, 2.1, 8)                    # rows with more candidates than a wavefront lists in LDS
+    assert big.degrees().max() > 4096
+    _compare(big, np.arange(0, 20000, 501), 2, 30, rule, seed=2)
+    _compare(big, np.arange(0, 20000, 501), 1, 1500, rule, seed=3)     # a fanout above the list size
 
 
 @pytest.mark.parametrize("rule", ["degree", "hash"])
