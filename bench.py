@@ -292,9 +292,10 @@ def run_workload(args, name, steps, warmup, cpu_flops):
     call_ms = mean_ms(trace)
     # Outside the timed region: two more steps with every call on the one stream, so that the events around a weight-
     # gradient product time that product alone (in the timed steps it shares the GPU with an aggregation).
-    alone_ms = call_ms
+    alone_ms, costs = call_ms, model.product_costs()
     if model.side is not None:
         side_stream, model.side = model.side, None
+        costs = model.product_costs()      # the one-stream step forms some gradients in fewer, larger calls
         model.step(S.labels)
         model.trace = []
         for _ in range(2):
@@ -352,7 +353,6 @@ def run_workload(args, name, steps, warmup, cpu_flops):
     # ---- the feature-transform products against the roof that binds each of them: the slower of "operands once at
     # the HBM peak" and "flops at the MFMA peak of the data type".  Timed alone on the GPU (see above).
     peak = MFMA_PEAK_TFLOPS[w.dtype]
-    costs = model.product_costs()
     gemm_calls = {}
     for nm, c in costs.items():
         t = alone_ms.get(nm, 0.0) * 1e-3

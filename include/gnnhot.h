@@ -265,6 +265,9 @@ int32_t gnn_linear_bwd(const int32_t *rows, int32_t n_active,
  * (the neighbour half dP W_neigh^T reaches every row of R_{l-1}; the rows of R_l, listed first, already hold the self
  * half dZ W_self^T; relu_H = H_{l-1} puts the sum in front of the previous layer's ReLU).
  *   W        [K, N] as in gnn_linear_fwd;  relu_H NULL: no mask, then n_accumulate must be 0
+ * Rounding with bf16 storage: the product is rounded to bf16, added to the stored dX in float and the sum rounded again -
+ * the bits that storing the two halves separately and adding them would give (gnn_linear_bwd_input2 below forms both
+ * halves in one float accumulator and rounds once).
  * Workspace: (ws, ws_bytes) size-query protocol.
  */
 int32_t gnn_linear_bwd_input(const int32_t *rows, int32_t n_active, const void *dZ, int64_t lddz, int32_t N, const void *W,

@@ -2,12 +2,16 @@
 // (paper section 6, figure 7c: step 1 extracts the multi-hop dependency from the inner
 // vertices, step 4 generates the per-layer mask).
 //
-// Data layout.  Three bitmaps of n bits live in the workspace: `visited` (everything reached
-// by the levels before the one being expanded, read-only while it expands), `seen`
-// (`visited` plus what the level has found so far) and `frontier` (the ring the last level
-// found).  A level is: expand -> count / scan / emit, a compaction of seen & ~visited that
-// lists the new ring in ascending id order without any sort, so the output does not depend on
-// which wave found a vertex first; emit then makes visited equal to seen.  Ring sizes stay on
+// Data layout.  In the workspace: two bitmaps of n bits, `visited` (everything reached by the
+// levels before the one being expanded, read-only while it expands) and `frontier` (the ring
+// the last level found), and `seen`, ONE BYTE per vertex (`visited` plus what the level has
+// found so far).  `seen` is bytes because every lane that finds a vertex marks it: a byte takes
+// a plain store of 1 - whoever comes first, the byte ends up the same - where a bit needs an
+// atomic OR, and a ring of a few million new vertices packs those atomics onto a few thousand
+// cache lines (measured: 0.60 ms of atomics for 24 M edges that discover 2.2 M vertices).
+// A level is: expand -> count / scan / emit, a compaction of seen & ~visited that lists the
+// new ring in ascending id order without any sort, so the output does not depend on which
+// wave found a vertex first; emit then brings visited up to seen.  Ring sizes stay on
 // the device (hop_offsets); every kernel has a fixed grid and reads its bounds from there, so
 // the whole construction is enqueued without a host round trip.
 //
@@ -17,7 +21,7 @@
 //         edges at a time (each lane finds the row of its edge by a binary search over the 64
 //         prefix sums in LDS), so rows of 5 and rows of 500 entries keep all lanes busy alike
 //         and every lane has four independent index loads and four bitmap probes in flight.
-//         One probe of `seen` per edge; the bit is set if still clear.
+//         One probe of `seen` per edge; the byte is set if still clear.
 //   pull  (from the unreached vertices; needs the transposed graph)  sixteen lanes per
 //         unreached vertex scan its row of the transposed graph - the vertices that would
 //         reach it - and stop at the first one that is in `frontier`.  Once the frontier is
@@ -29,8 +33,8 @@
 // are enqueued; the one whose turn it is not returns at once.
 //
 // Bound: a push level reads each edge of the frontier once (4 B, streaming) and makes one
-// 4-byte probe per edge into a bitmap of n/8 bytes that stays in L2: the probes, not the
-// bytes, are what limits it (the L2s serve a fixed number of requests per clock).
+// 1-byte probe per edge into n bytes that stay in L2: the probes, not the bytes, are what
+// limits it (the L2s serve a fixed number of requests per clock).
 #include "common.h"
 #include "hashkey.h"
 #include "scan.h"
@@ -57,15 +61,27 @@ __device__ __forceinline__ bool as_pull_level(const AsCtrl* ctrl, const int64_t*
     return (int64_t)ctrl->frontier_edges > unreached_edges + 16 * unreached;
 }
 
+// Bit b of the result = byte b of the 32 bytes at p (each 0 or 1); p is 32-byte aligned.
+__device__ __forceinline__ uint32_t as_mask_of_bytes(const uint8_t* __restrict__ p) {
+    const uint4 a = *(const uint4*)p, b = *(const uint4*)(p + 16);
+    const uint32_t x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    uint32_t m = 0u;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        m |= ((x[k] & 1u) | ((x[k] >> 7) & 2u) | ((x[k] >> 14) & 4u) | ((x[k] >> 21) & 8u)) << (4 * k);
+    return m;
+}
+
 __global__ __launch_bounds__(256) void as_init_kernel(int32_t* __restrict__ dist, int32_t n, uint32_t* __restrict__ visited,
-                                                      uint32_t* __restrict__ seen, int64_t nw, AsCtrl* ctrl,
+                                                      uint8_t* __restrict__ seen, int64_t nw, AsCtrl* ctrl,
                                                       int64_t* __restrict__ hop_offsets, int32_t L) {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t v = tid; v < n; v += stride) dist[v] = -1;
     for (int64_t w = tid; w < nw; w += stride) {
         visited[w] = 0u;
-        seen[w] = 0u;
+        ((uint4*)seen)[2 * w] = make_uint4(0u, 0u, 0u, 0u);   // 32 bytes per bitmap word, the tail of the last word included
+        ((uint4*)seen)[2 * w + 1] = make_uint4(0u, 0u, 0u, 0u);
     }
     if (tid == 0) {
         ctrl->n_hubs = 0;
@@ -76,10 +92,10 @@ __global__ __launch_bounds__(256) void as_init_kernel(int32_t* __restrict__ dist
 }
 
 __global__ __launch_bounds__(256) void as_seed_kernel(const int32_t* __restrict__ targets, int32_t n_targets, int32_t n,
-                                                      uint32_t* __restrict__ seen) {
+                                                      uint8_t* __restrict__ seen) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_targets; i += (int64_t)gridDim.x * blockDim.x) {
         int32_t v = targets[i];
-        if (v >= 0 && v < n) atomicOr(&seen[v >> 5], 1u << (v & 31));
+        if (v >= 0 && v < n) seen[v] = 1;
     }
 }
 
@@ -90,7 +106,7 @@ constexpr int kAsU = 4;   // edges per lane and step: their index loads, then th
 __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                         const int32_t* __restrict__ ring_ids,
                                                         const int64_t* __restrict__ hop_offsets, int32_t ring,
-                                                        uint32_t* __restrict__ seen, int32_t* __restrict__ hubq, AsCtrl* ctrl,
+                                                        uint8_t* __restrict__ seen, int32_t* __restrict__ hubq, AsCtrl* ctrl,
                                                         int32_t n, int64_t nnz_t) {
     __shared__ int32_t s_start[4][kWave];
     __shared__ int32_t s_excl[4][kWave + 1];
@@ -138,14 +154,12 @@ __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restric
                 }
                 u[j] = ok[j] ? col_idx[st[lo] + (t - ex[lo])] : 0;
             }
-            uint32_t w[kAsU];
+            uint8_t w[kAsU];
 #pragma unroll
-            for (int j = 0; j < kAsU; ++j) w[j] = seen[u[j] >> 5];   // u = 0 where the lane has no edge: a valid word
+            for (int j = 0; j < kAsU; ++j) w[j] = seen[u[j]];   // u = 0 where the lane has no edge: a valid byte
 #pragma unroll
-            for (int j = 0; j < kAsU; ++j) {
-                const uint32_t bit = 1u << (u[j] & 31);
-                if (ok[j] && !(w[j] & bit)) atomicOr(&seen[u[j] >> 5], bit);
-            }
+            for (int j = 0; j < kAsU; ++j)
+                if (ok[j] && !w[j]) seen[u[j]] = 1;
         }
     }
 }
@@ -153,7 +167,7 @@ __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restric
 // Hub rows of a push level: one workgroup per queued row (grid-stride over the queue), threads across the row, four
 // entries per step.  (In a pull level the queue is empty when this kernel runs.)
 __global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-                                                             uint32_t* __restrict__ seen, const int32_t* __restrict__ hubq,
+                                                             uint8_t* __restrict__ seen, const int32_t* __restrict__ hubq,
                                                              const AsCtrl* ctrl) {
     const int32_t n_hubs = ctrl->n_hubs;
     for (int32_t h = blockIdx.x; h < n_hubs; h += gridDim.x) {
@@ -161,16 +175,14 @@ __global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __re
         const int32_t s = row_ptr[v], e = row_ptr[v + 1];
         for (int32_t base = s + (int32_t)threadIdx.x; base < e; base += 256 * kAsU) {
             int32_t u[kAsU];
-            uint32_t w[kAsU];
+            uint8_t w[kAsU];
 #pragma unroll
             for (int j = 0; j < kAsU; ++j) u[j] = base + j * 256 < e ? col_idx[base + j * 256] : 0;
 #pragma unroll
-            for (int j = 0; j < kAsU; ++j) w[j] = seen[u[j] >> 5];
+            for (int j = 0; j < kAsU; ++j) w[j] = seen[u[j]];
 #pragma unroll
-            for (int j = 0; j < kAsU; ++j) {
-                const uint32_t bit = 1u << (u[j] & 31);
-                if (base + j * 256 < e && !(w[j] & bit)) atomicOr(&seen[u[j] >> 5], bit);
-            }
+            for (int j = 0; j < kAsU; ++j)
+                if (base + j * 256 < e && !w[j]) seen[u[j]] = 1;
         }
     }
 }
@@ -209,10 +221,10 @@ __global__ __launch_bounds__(256) void as_plan_kernel(const int32_t* __restrict_
 
 // Pull level.  Sixteen lanes per bitmap word (grid-stride): for each vertex of the word that is not in the set yet,
 // scan its transposed row 64 entries at a time and stop at the first entry that is in the frontier.  A lane group
-// is the only writer of its word in this kernel.  Rows longer than kAsHubDegree go to the queue.
+// is the only writer of its vertices' bytes in this kernel.  Rows longer than kAsHubDegree go to the queue.
 __global__ __launch_bounds__(256) void as_pull_kernel(const int32_t* __restrict__ row_ptr_t, const int32_t* __restrict__ col_idx_t,
                                                       int32_t n, int64_t nw, const uint32_t* __restrict__ visited,
-                                                      uint32_t* __restrict__ seen, const uint32_t* __restrict__ frontier,
+                                                      uint8_t* __restrict__ seen, const uint32_t* __restrict__ frontier,
                                                       const int64_t* __restrict__ hop_offsets, int32_t ring, int64_t nnz_t,
                                                       int32_t* __restrict__ hubq, AsCtrl* ctrl) {
     if (!as_pull_level(ctrl, hop_offsets, ring, n, nnz_t)) return;   // uniform over the grid
@@ -221,7 +233,6 @@ __global__ __launch_bounds__(256) void as_pull_kernel(const int32_t* __restrict_
     for (int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 16; w < nw; w += groups) {
         uint32_t open = ~visited[w];
         if (w == nw - 1 && (n & 31)) open &= (1u << (n & 31)) - 1u;
-        uint32_t add = 0u;
         while (open) {   // uniform over the lane group
             const int b = __ffs(open) - 1;
             open &= open - 1u;
@@ -241,15 +252,14 @@ __global__ __launch_bounds__(256) void as_pull_kernel(const int32_t* __restrict_
                 for (int j = 0; j < 4; ++j) hit |= u[j] >= 0 && in_set(frontier, u[j]);
                 found = ((__ballot(hit) >> (sub * 16)) & 0xffffull) != 0ull;
             }
-            if (found) add |= 1u << b;
+            if (found && sl == 0) seen[v] = 1;
         }
-        if (add && sl == 0) atomicOr(&seen[w], add);
     }
 }
 
 // Long rows of a pull level: one workgroup per queued vertex, 256 entries per step, until one is in the frontier.
 __global__ __launch_bounds__(256) void as_pull_hubs_kernel(const int32_t* __restrict__ row_ptr_t, const int32_t* __restrict__ col_idx_t,
-                                                           uint32_t* __restrict__ seen, const uint32_t* __restrict__ frontier,
+                                                           uint8_t* __restrict__ seen, const uint32_t* __restrict__ frontier,
                                                            const int64_t* __restrict__ hop_offsets, int32_t ring, int32_t n,
                                                            int64_t nnz_t, const int32_t* __restrict__ hubq, const AsCtrl* ctrl) {
     if (!as_pull_level(ctrl, hop_offsets, ring, n, nnz_t)) return;
@@ -261,20 +271,20 @@ __global__ __launch_bounds__(256) void as_pull_hubs_kernel(const int32_t* __rest
             const int32_t p = base + (int32_t)threadIdx.x;
             const int hit = p < e && in_set(frontier, col_idx_t[p]);
             if (__syncthreads_or(hit)) {
-                if (threadIdx.x == 0) atomicOr(&seen[v >> 5], 1u << (v & 31));
+                if (threadIdx.x == 0) seen[v] = 1;
                 break;
             }
         }
     }
 }
 
-__global__ __launch_bounds__(kAsWordsPerBlock) void as_count_kernel(const uint32_t* __restrict__ seen,
+__global__ __launch_bounds__(kAsWordsPerBlock) void as_count_kernel(const uint8_t* __restrict__ seen,
                                                                     const uint32_t* __restrict__ visited, int64_t nw,
                                                                     int32_t* __restrict__ blk_cnt) {
     __shared__ int s_part[kAsWordsPerBlock / kWave];
     const int64_t w = (int64_t)blockIdx.x * kAsWordsPerBlock + threadIdx.x;
     int c = 0;
-    if (w < nw) c = __popc(seen[w] & ~visited[w]);
+    if (w < nw) c = __popc(as_mask_of_bytes(seen + 32 * w) & ~visited[w]);
     int total;
     block_exclusive_scan<kAsWordsPerBlock>(c, s_part, &total);
     if (threadIdx.x == 0) blk_cnt[blockIdx.x] = total;
@@ -291,7 +301,7 @@ __global__ __launch_bounds__(1024) void as_scan_kernel(int32_t* __restrict__ blk
     }
 }
 
-__global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(const uint32_t* __restrict__ seen, uint32_t* __restrict__ visited,
+__global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(const uint8_t* __restrict__ seen, uint32_t* __restrict__ visited,
                                                                    int64_t nw, const int32_t* __restrict__ blk_cnt,
                                                                    const int64_t* __restrict__ hop_offsets, int32_t ring,
                                                                    int32_t* __restrict__ ring_ids, int32_t* __restrict__ dist,
@@ -300,9 +310,9 @@ __global__ __launch_bounds__(kAsWordsPerBlock) void as_emit_kernel(const uint32_
     const int64_t w = (int64_t)blockIdx.x * kAsWordsPerBlock + threadIdx.x;
     uint32_t fresh = 0u;
     if (w < nw) {
-        const uint32_t sn = seen[w], vis = visited[w];
+        const uint32_t sn = as_mask_of_bytes(seen + 32 * w), vis = visited[w];
         fresh = sn & ~vis;
-        if (fresh) visited[w] = sn;
+        if (fresh) visited[w] = vis | sn;
         if (frontier != nullptr) frontier[w] = fresh;   // the ring a pull level looks for
     }
     int total;
@@ -348,18 +358,20 @@ __device__ __forceinline__ uint64_t eas_key(int32_t rule, uint64_t seed_hop_mixe
 constexpr int kEasShortRow = 64;    // rows up to this length: sixteen lanes each; longer rows: a wavefront each
 constexpr int kEasListCap = 1024;   // candidates of one long row that a wavefront keeps in LDS
 
-// Rows of at most kEasShortRow entries.
-// Sixteen lanes per frontier vertex, four vertices per wavefront; loops run to the longest row of the wavefront so
-// that ballots and shuffles stay convergent.  A row with more than `fanout` candidates finds the fanout-th smallest
-// (key, id) by `fanout` rounds of "smallest pair above the previous one" (the row is re-read from cache).
+// Rows of at most kEasShortRow entries: sixteen lanes per frontier vertex, four vertices per wavefront, up to four
+// entries of the row per lane.  Entries, candidate flags and keys are read once and stay in registers; a row with
+// more than `fanout` candidates finds the fanout-th smallest (key, id) by `fanout` rounds of "smallest pair above the
+// previous one" over those registers.  Every lane runs every ballot and shuffle (no lane leaves early).
 __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                           const int32_t* __restrict__ ring_ids, const int64_t* __restrict__ hop_offsets,
-                                                          int32_t ring, const uint32_t* __restrict__ visited, uint32_t* __restrict__ seen,
+                                                          int32_t ring, const uint32_t* __restrict__ visited, uint8_t* __restrict__ seen,
                                                           int32_t fanout, int32_t rule, uint64_t seed_hop_mixed,
                                                           const int32_t* __restrict__ conn) {
+    constexpr int kPerLane = kEasShortRow / 16;
     const int64_t begin = hop_offsets[ring], end = hop_offsets[ring + 1];
     const int lane = lane_id(), sub = lane / 16, sl = lane % 16;
     const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    if (fanout == 0) return;   // nothing is selected
     for (int64_t base = begin + 4 * (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6); base < end; base += 4 * waves) {  // uniform over the wave
         const int64_t i = base + sub;
         int32_t v = 0, s = 0, e = 0;
@@ -369,38 +381,34 @@ __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restri
             e = row_ptr[v + 1];
             if (e - s > kEasShortRow) e = s;   // eas_expand_long_kernel takes this row
         }
-        int len_max = e - s;
-        len_max = max(len_max, __shfl_xor(len_max, 16, kWave));
-        len_max = max(len_max, __shfl_xor(len_max, 32, kWave));
+        int32_t u[kPerLane];
+        bool cand[kPerLane];
+        uint64_t key[kPerLane];
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) u[j] = s + j * 16 + sl < e ? col_idx[s + j * 16 + sl] : -1;
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) cand[j] = u[j] >= 0 && !in_set(visited, u[j]);
         int32_t n_cand = 0;
-        for (int32_t off = 0; off < len_max; off += 16) {
-            const int32_t p = s + off + sl;
-            const bool cand = p < e && !in_set(visited, col_idx[p]);
-            n_cand += __popcll((__ballot(cand) >> (sub * 16)) & 0xffffull);
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            key[j] = cand[j] ? eas_key(rule, seed_hop_mixed, conn, v, u[j]) : ~0ull;
+            n_cand += __popcll((__ballot(cand[j]) >> (sub * 16)) & 0xffffull);
         }
         // threshold pair: candidates with (key, id) <= (thr_k, thr_u) are kept
         uint64_t thr_k = ~0ull;
         int32_t thr_u = 0x7fffffff;
-        if (fanout == 0) {
-            thr_k = 0ull;
-            thr_u = -1;  // nothing is <= (0, -1): ids are non-negative
-        }
-        const bool need = fanout > 0 && n_cand > fanout;  // uniform over the 16-lane group
-        if (__ballot(need) != 0ull) {                      // uniform over the wavefront
+        const bool need = n_cand > fanout;   // uniform over the 16-lane group
+        if (__ballot(need) != 0ull) {        // uniform over the wavefront
             uint64_t prev_k = 0ull;
             int32_t prev_u = -1;
             for (int32_t round = 0; round < fanout; ++round) {
                 uint64_t best_k = ~0ull;
                 int32_t best_u = 0x7fffffff;
-                if (need) {
-                    for (int32_t p = s + sl; p < e; p += 16) {
-                        const int32_t u = col_idx[p];
-                        if (in_set(visited, u)) continue;
-                        const uint64_t k = eas_key(rule, seed_hop_mixed, conn, v, u);
-                        if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
-                            best_k = k;
-                            best_u = u;
-                        }
+#pragma unroll
+                for (int j = 0; j < kPerLane; ++j) {
+                    if (cand[j] && pair_less(prev_k, prev_u, key[j], u[j]) && pair_less(key[j], u[j], best_k, best_u)) {
+                        best_k = key[j];
+                        best_u = u[j];
                     }
                 }
 #pragma unroll
@@ -420,27 +428,57 @@ __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restri
                 thr_u = prev_u;
             }
         }
-        for (int32_t p = s + sl; p < e; p += 16) {
-            const int32_t u = col_idx[p];
-            if (in_set(visited, u)) continue;
-            bool keep = !need;
-            if (need) keep = !pair_less(thr_k, thr_u, eas_key(rule, seed_hop_mixed, conn, v, u), u);
-            if (fanout == 0) keep = false;
-            const uint32_t bit = 1u << (u & 31);
-            if (keep && !(seen[u >> 5] & bit)) atomicOr(&seen[u >> 5], bit);
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            if (cand[j] && !pair_less(thr_k, thr_u, key[j], u[j]) && !seen[u[j]]) seen[u[j]] = 1;
         }
     }
 }
 
-// Rows longer than kEasShortRow: one wavefront per frontier vertex.  The row is read once; its candidates (neighbours
+// The fanout-th smallest (key, id) of a wavefront's LDS list of n (> fanout) distinct pairs: `fanout` rounds of
+// "smallest pair above the previous one".  Every lane returns the same pair.
+__device__ __forceinline__ void eas_list_select(const uint64_t* key, const int32_t* id, int32_t n, int32_t fanout, int lane,
+                                                uint64_t& thr_k, int32_t& thr_u) {
+    uint64_t prev_k = 0ull;
+    int32_t prev_u = -1;
+    for (int32_t round = 0; round < fanout; ++round) {
+        uint64_t best_k = ~0ull;
+        int32_t best_u = 0x7fffffff;
+        for (int32_t j = lane; j < n; j += kWave) {
+            const uint64_t k = key[j];
+            const int32_t u = id[j];
+            if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
+                best_k = k;
+                best_u = u;
+            }
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const uint64_t ok = __shfl_xor(best_k, d, kWave);
+            const int32_t ou = __shfl_xor(best_u, d, kWave);
+            if (pair_less(ok, ou, best_k, best_u)) {
+                best_k = ok;
+                best_u = ou;
+            }
+        }
+        prev_k = best_k;
+        prev_u = best_u;
+    }
+    thr_k = prev_k;
+    thr_u = prev_u;
+}
+
+// Rows longer than kEasShortRow: one wavefront per frontier vertex.  The row is read ONCE; its candidates (neighbours
 // not selected when the hop started) go to a list in LDS with their keys (one key computation and, for the
-// best-connected-first rule, one read of conn[] per candidate).  With more than `fanout` candidates the fanout-th
-// smallest (key, id) is found by `fanout` rounds of "smallest pair above the previous one" over the list.  A row with
-// more candidates than the list holds runs the same rounds over the row itself.
+// best-connected-first rule, one read of conn[] per candidate).  When the list is full it is cut down to its `fanout`
+// smallest (key, id) pairs, and from then on only candidates below the largest of those are listed: a pair that is
+// not among the fanout smallest of what has been read so far cannot be among the fanout smallest of the row.  At the
+// end the fanout smallest pairs of the list are the row's.  (A fanout too large for this - within 64 of the list's
+// capacity - takes the rounds over the row itself, re-reading it once per kept neighbour.)
 __global__ __launch_bounds__(256) void eas_expand_long_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                                const int32_t* __restrict__ ring_ids,
                                                                const int64_t* __restrict__ hop_offsets, int32_t ring,
-                                                               const uint32_t* __restrict__ visited, uint32_t* __restrict__ seen,
+                                                               const uint32_t* __restrict__ visited, uint8_t* __restrict__ seen,
                                                                int32_t fanout, int32_t rule, uint64_t seed_hop_mixed,
                                                                const int32_t* __restrict__ conn) {
     __shared__ uint64_t s_key[4][kEasListCap];
@@ -452,43 +490,68 @@ __global__ __launch_bounds__(256) void eas_expand_long_kernel(const int32_t* __r
     const uint64_t lanes_below = (1ull << lane) - 1ull;
     const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     if (fanout == 0) return;   // nothing is selected
+    const bool streaming = fanout <= kEasListCap - kWave;   // the list can always be cut down far enough to take a chunk
     for (int64_t i = begin + (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6); i < end; i += waves) {   // uniform over the wave
         const int32_t v = ring_ids[i];
         const int32_t s = row_ptr[v], e = row_ptr[v + 1];
         if (e - s <= kEasShortRow) continue;
-        int32_t n_cand = 0;
+        uint64_t thr_k = ~0ull;   // pairs above (thr_k, thr_u) are out
+        int32_t thr_u = 0x7fffffff;
+        int32_t n_list = 0;       // pairs in the list
+        int32_t n_cand = 0;       // candidates of the row (only needed when not streaming)
         for (int32_t p = s; p < e; p += kWave) {
             const int32_t q = p + lane;
             const int32_t u = q < e ? col_idx[q] : 0;
             const bool cand = q < e && !in_set(visited, u);
-            const uint64_t mask = __ballot(cand);
-            const int32_t pos = n_cand + __popcll(mask & lanes_below);
-            if (cand && pos < kEasListCap) {
-                key[pos] = eas_key(rule, seed_hop_mixed, conn, v, u);
+            const uint64_t k = cand ? eas_key(rule, seed_hop_mixed, conn, v, u) : 0ull;
+            bool take = cand && !pair_less(thr_k, thr_u, k, u);
+            uint64_t mask = __ballot(take);
+            n_cand += __popcll(__ballot(cand));
+            if (streaming && n_list + __popcll(mask) > kEasListCap) {   // uniform: cut the list down to its fanout smallest
+                wave_lds_sync();
+                eas_list_select(key, id, n_list, fanout, lane, thr_k, thr_u);
+                int32_t out = 0;
+                for (int32_t base = 0; base < n_list; base += kWave) {   // in-place compaction, front to back
+                    const int32_t j = base + lane;
+                    const uint64_t kj = j < n_list ? key[j] : 0ull;
+                    const int32_t uj = j < n_list ? id[j] : 0;
+                    const bool keep = j < n_list && !pair_less(thr_k, thr_u, kj, uj);
+                    const uint64_t km = __ballot(keep);
+                    wave_lds_sync();   // the chunk has been read by every lane; targets lie at or before it
+                    if (keep) {
+                        const int32_t pos = out + __popcll(km & lanes_below);
+                        key[pos] = kj;
+                        id[pos] = uj;
+                    }
+                    out += __popcll(km);
+                    wave_lds_sync();
+                }
+                n_list = out;
+                take = cand && !pair_less(thr_k, thr_u, k, u);
+                mask = __ballot(take);
+            }
+            const int32_t pos = n_list + __popcll(mask & lanes_below);
+            if (take && pos < kEasListCap) {
+                key[pos] = k;
                 id[pos] = u;
             }
-            n_cand += __popcll(mask);
+            n_list += __popcll(mask);
         }
         wave_lds_sync();
-        const bool listed = n_cand <= kEasListCap;
-        uint64_t thr_k = ~0ull;   // candidates with (key, id) <= (thr_k, thr_u) are kept
-        int32_t thr_u = 0x7fffffff;
-        if (n_cand > fanout) {
-            uint64_t prev_k = 0ull;
-            int32_t prev_u = -1;
-            for (int32_t round = 0; round < fanout; ++round) {
-                uint64_t best_k = ~0ull;
-                int32_t best_u = 0x7fffffff;
-                if (listed) {
-                    for (int32_t j = lane; j < n_cand; j += kWave) {
-                        const uint64_t k = key[j];
-                        const int32_t u = id[j];
-                        if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
-                            best_k = k;
-                            best_u = u;
-                        }
-                    }
-                } else {
+        if (streaming || n_list <= kEasListCap) {
+            if (n_list > fanout) eas_list_select(key, id, n_list, fanout, lane, thr_k, thr_u);
+            for (int32_t j = lane; j < n_list; j += kWave) {
+                const int32_t u = id[j];
+                if (!pair_less(thr_k, thr_u, key[j], u) && !seen[u]) seen[u] = 1;
+            }
+        } else {
+            // more candidates than the list holds and a fanout too large to cut it down: rounds over the row itself
+            if (n_cand > fanout) {
+                uint64_t prev_k = 0ull;
+                int32_t prev_u = -1;
+                for (int32_t round = 0; round < fanout; ++round) {
+                    uint64_t best_k = ~0ull;
+                    int32_t best_u = 0x7fffffff;
                     for (int32_t p = s + lane; p < e; p += kWave) {
                         const int32_t u = col_idx[p];
                         if (in_set(visited, u)) continue;
@@ -498,35 +561,25 @@ __global__ __launch_bounds__(256) void eas_expand_long_kernel(const int32_t* __r
                             best_u = u;
                         }
                     }
-                }
 #pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) {
-                    const uint64_t ok = __shfl_xor(best_k, d, kWave);
-                    const int32_t ou = __shfl_xor(best_u, d, kWave);
-                    if (pair_less(ok, ou, best_k, best_u)) {
-                        best_k = ok;
-                        best_u = ou;
+                    for (int d = 32; d >= 1; d >>= 1) {
+                        const uint64_t ok = __shfl_xor(best_k, d, kWave);
+                        const int32_t ou = __shfl_xor(best_u, d, kWave);
+                        if (pair_less(ok, ou, best_k, best_u)) {
+                            best_k = ok;
+                            best_u = ou;
+                        }
                     }
+                    prev_k = best_k;
+                    prev_u = best_u;
                 }
-                prev_k = best_k;
-                prev_u = best_u;
+                thr_k = prev_k;
+                thr_u = prev_u;
             }
-            thr_k = prev_k;
-            thr_u = prev_u;
-        }
-        if (listed) {
-            for (int32_t j = lane; j < n_cand; j += kWave) {
-                const int32_t u = id[j];
-                const uint32_t bit = 1u << (u & 31);
-                if (!pair_less(thr_k, thr_u, key[j], u) && !(seen[u >> 5] & bit)) atomicOr(&seen[u >> 5], bit);
-            }
-        } else {
             for (int32_t p = s + lane; p < e; p += kWave) {
                 const int32_t u = col_idx[p];
                 if (in_set(visited, u)) continue;
-                const uint32_t bit = 1u << (u & 31);
-                if (!pair_less(thr_k, thr_u, eas_key(rule, seed_hop_mixed, conn, v, u), u) && !(seen[u >> 5] & bit))
-                    atomicOr(&seen[u >> 5], bit);
+                if (!pair_less(thr_k, thr_u, eas_key(rule, seed_hop_mixed, conn, v, u), u) && !seen[u]) seen[u] = 1;
             }
         }
         wave_lds_sync();   // the lists are read before the next row overwrites them
@@ -557,7 +610,7 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const gnn_csr* gt, co
 
     WsCarver carve(ws);
     uint32_t* visited = carve.take<uint32_t>((size_t)nw + 1);
-    uint32_t* seen = carve.take<uint32_t>((size_t)nw + 1);
+    uint8_t* seen = carve.take<uint8_t>((size_t)nw * 32 + 32);
     uint32_t* frontier = carve.take<uint32_t>((size_t)nw + 1);
     int32_t* blk_cnt = carve.take<int32_t>((size_t)nb + 1);
     int32_t* hubq = carve.take<int32_t>((size_t)n + 1);
@@ -631,7 +684,7 @@ extern "C" int32_t gnn_eas_traverse(const gnn_csr* g, const int32_t* targets, in
 
     WsCarver carve(ws);
     uint32_t* visited = carve.take<uint32_t>((size_t)nw + 1);
-    uint32_t* seen = carve.take<uint32_t>((size_t)nw + 1);
+    uint8_t* seen = carve.take<uint8_t>((size_t)nw * 32 + 32);
     int32_t* blk_cnt = carve.take<int32_t>((size_t)nb + 1);
     int32_t* conn = carve.take<int32_t>(rule == GNN_EAS_DEGREE ? (size_t)n + 1 : 1);
     AsCtrl* ctrl = carve.take<AsCtrl>(1);
