@@ -435,39 +435,6 @@ __global__ __launch_bounds__(256) void eas_expand_kernel(const int32_t* __restri
     }
 }
 
-// The fanout-th smallest (key, id) of a wavefront's LDS list of n (> fanout) distinct pairs: `fanout` rounds of
-// "smallest pair above the previous one".  Every lane returns the same pair.
-__device__ __forceinline__ void eas_list_select(const uint64_t* key, const int32_t* id, int32_t n, int32_t fanout, int lane,
-                                                uint64_t& thr_k, int32_t& thr_u) {
-    uint64_t prev_k = 0ull;
-    int32_t prev_u = -1;
-    for (int32_t round = 0; round < fanout; ++round) {
-        uint64_t best_k = ~0ull;
-        int32_t best_u = 0x7fffffff;
-        for (int32_t j = lane; j < n; j += kWave) {
-            const uint64_t k = key[j];
-            const int32_t u = id[j];
-            if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
-                best_k = k;
-                best_u = u;
-            }
-        }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            const uint64_t ok = __shfl_xor(best_k, d, kWave);
-            const int32_t ou = __shfl_xor(best_u, d, kWave);
-            if (pair_less(ok, ou, best_k, best_u)) {
-                best_k = ok;
-                best_u = ou;
-            }
-        }
-        prev_k = best_k;
-        prev_u = best_u;
-    }
-    thr_k = prev_k;
-    thr_u = prev_u;
-}
-
 // Rows longer than kEasShortRow: one wavefront per frontier vertex.  The row is read ONCE; its candidates (neighbours
 // not selected when the hop started) go to a list in LDS with their keys (one key computation and, for the
 // best-connected-first rule, one read of conn[] per candidate).  When the list is full it is cut down to its `fanout`
@@ -509,24 +476,8 @@ __global__ __launch_bounds__(256) void eas_expand_long_kernel(const int32_t* __r
             n_cand += __popcll(__ballot(cand));
             if (streaming && n_list + __popcll(mask) > kEasListCap) {   // uniform: cut the list down to its fanout smallest
                 wave_lds_sync();
-                eas_list_select(key, id, n_list, fanout, lane, thr_k, thr_u);
-                int32_t out = 0;
-                for (int32_t base = 0; base < n_list; base += kWave) {   // in-place compaction, front to back
-                    const int32_t j = base + lane;
-                    const uint64_t kj = j < n_list ? key[j] : 0ull;
-                    const int32_t uj = j < n_list ? id[j] : 0;
-                    const bool keep = j < n_list && !pair_less(thr_k, thr_u, kj, uj);
-                    const uint64_t km = __ballot(keep);
-                    wave_lds_sync();   // the chunk has been read by every lane; targets lie at or before it
-                    if (keep) {
-                        const int32_t pos = out + __popcll(km & lanes_below);
-                        key[pos] = kj;
-                        id[pos] = uj;
-                    }
-                    out += __popcll(km);
-                    wave_lds_sync();
-                }
-                n_list = out;
+                wave_list_kth(key, id, n_list, fanout, lane, thr_k, thr_u);
+                n_list = wave_list_keep_below(key, id, n_list, thr_k, thr_u, lane);
                 take = cand && !pair_less(thr_k, thr_u, k, u);
                 mask = __ballot(take);
             }
@@ -539,7 +490,7 @@ __global__ __launch_bounds__(256) void eas_expand_long_kernel(const int32_t* __r
         }
         wave_lds_sync();
         if (streaming || n_list <= kEasListCap) {
-            if (n_list > fanout) eas_list_select(key, id, n_list, fanout, lane, thr_k, thr_u);
+            if (n_list > fanout) wave_list_kth(key, id, n_list, fanout, lane, thr_k, thr_u);
             for (int32_t j = lane; j < n_list; j += kWave) {
                 const int32_t u = id[j];
                 if (!pair_less(thr_k, thr_u, key[j], u) && !seen[u]) seen[u] = 1;

@@ -3,10 +3,14 @@
 // one bit per CSR entry, which the aggregation kernels test next to their dist filter.
 //
 //   lm_mask_kernel       sixteen lanes per listed row (the boundary sampler's scheme): a row's keep decision is
-//                        "(key, id) <= threshold pair"; the threshold rule has a fixed pair, the fanout rule finds
-//                        the fanout-th smallest pair by `fanout` rounds of min-above-previous.  A tile of sixteen
-//                        consecutive entries becomes one 16-bit ballot that lane 0 ORs into the bitmap (at most two
-//                        words), so the result does not depend on which group runs first.
+//                        "(key, id) <= threshold pair".  A tile of sixteen consecutive entries becomes one 16-bit
+//                        ballot that lane 0 ORs into the bitmap (at most two words), so the result does not depend
+//                        on which group runs first.  The threshold rule has a fixed pair and takes this kernel for
+//                        every row; the fanout rule takes it for rows of up to 64 entries, whose ids and keys stay in
+//                        registers (four per lane) while `fanout` rounds of min-above-previous find the row's pair.
+//   lm_fanout_long_kernel  the fanout rule for longer rows, a wavefront per row: one pass over the row with a bounded
+//                        list of pairs in LDS (when it is full it is cut down to its `fanout` smallest, and from then
+//                        on only pairs below the largest of those are listed), then one more pass that writes the bits.
 //   lm_transpose_kernel  the same mask in the positions of the transposed graph (backward aggregation): entry q =
 //                        (row u, column v) of the transposed graph looks up u in row v of the graph by binary search.
 //   lm_mask_t_kernel     the fast way to the same transposed mask: both rules are "(key, id) <= the row's threshold
@@ -30,33 +34,48 @@ __device__ __forceinline__ void lm_or_bits(uint32_t* __restrict__ bits, int64_t 
     if (sh > 16 && (m >> (32 - sh)) != 0u) atomicOr(&bits[(p0 >> 5) + 1], m >> (32 - sh));
 }
 
+constexpr int kLmShortRow = 64;    // fanout rule: rows up to this length stay in registers, longer ones get a wavefront
+constexpr int kLmListCap = 1024;   // pairs a wavefront lists in LDS
+
 __global__ __launch_bounds__(256) void lm_mask_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                       const int32_t* __restrict__ rows, int32_t n_active, int32_t rule, int32_t fanout,
                                                       uint64_t threshold, uint64_t seed_layer_mixed, uint32_t* __restrict__ bits,
                                                       int32_t* __restrict__ kept_len, uint64_t* __restrict__ row_thr_key,
                                                       int32_t* __restrict__ row_thr_id) {
+    constexpr int kPerLane = kLmShortRow / kLmLanes;
     const int lane = lane_id(), sub = lane / kLmLanes, sl = lane % kLmLanes;
     const int64_t groups = ((int64_t)gridDim.x * blockDim.x) / kLmLanes;
     // the loop bound is uniform over the wavefront: its four groups take consecutive rows
     for (int64_t base = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) * 4; base < n_active; base += groups) {
         const int64_t i = base + sub;
         int32_t v = 0, s = 0, e = 0;
-        if (i < n_active) {
+        bool mine = i < n_active;
+        if (mine) {
             v = rows ? rows[i] : (int32_t)i;
             s = row_ptr[v];
             e = row_ptr[v + 1];
         }
-        int len_max = e - s;
-        len_max = max(len_max, __shfl_xor(len_max, 16, kWave));
-        len_max = max(len_max, __shfl_xor(len_max, 32, kWave));
         // pairs (key, id) <= (thr_k, thr_u) are kept
         uint64_t thr_k = threshold;
         int32_t thr_u = 0x7fffffff;
-        if (rule == GNN_LAYER_MASK_FANOUT) {
+        int32_t kept = 0;
+        if (rule == GNN_LAYER_MASK_FANOUT) {   // uniform over the grid
+            if (e - s > kLmShortRow) {         // lm_fanout_long_kernel takes this row
+                mine = false;
+                e = s;
+            }
             thr_k = ~0ull;
             if (fanout == 0) {
                 thr_k = 0ull;
                 thr_u = -1;  // nothing is <= (0, -1): ids are non-negative
+            }
+            int32_t u[kPerLane];
+            uint64_t key[kPerLane];
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                const int32_t p = s + j * kLmLanes + sl;
+                u[j] = p < e ? col_idx[p] : -1;
+                key[j] = u[j] >= 0 ? edge_key(seed_layer_mixed, (uint64_t)v, (uint64_t)u[j]) : ~0ull;
             }
             const bool need = fanout > 0 && e - s > fanout;  // uniform over the 16-lane group
             if (__ballot(need) != 0ull) {                     // uniform over the wavefront
@@ -65,14 +84,11 @@ __global__ __launch_bounds__(256) void lm_mask_kernel(const int32_t* __restrict_
                 for (int32_t round = 0; round < fanout; ++round) {
                     uint64_t best_k = ~0ull;
                     int32_t best_u = 0x7fffffff;
-                    if (need) {
-                        for (int32_t p = s + sl; p < e; p += kLmLanes) {
-                            const int32_t u = col_idx[p];
-                            const uint64_t k = edge_key(seed_layer_mixed, (uint64_t)v, (uint64_t)u);
-                            if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
-                                best_k = k;
-                                best_u = u;
-                            }
+#pragma unroll
+                    for (int j = 0; j < kPerLane; ++j) {
+                        if (u[j] >= 0 && pair_less(prev_k, prev_u, key[j], u[j]) && pair_less(key[j], u[j], best_k, best_u)) {
+                            best_k = key[j];
+                            best_u = u[j];
                         }
                     }
 #pragma unroll
@@ -92,20 +108,132 @@ __global__ __launch_bounds__(256) void lm_mask_kernel(const int32_t* __restrict_
                     thr_u = prev_u;
                 }
             }
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                const bool keep = u[j] >= 0 && !pair_less(thr_k, thr_u, key[j], u[j]);
+                const uint32_t m = lm_group_ballot(keep, sub);
+                kept += __popc(m);
+                if (sl == 0) lm_or_bits(bits, (int64_t)s + j * kLmLanes, m);
+            }
+        } else {
+            int len_max = e - s;
+            len_max = max(len_max, __shfl_xor(len_max, 16, kWave));
+            len_max = max(len_max, __shfl_xor(len_max, 32, kWave));
+            for (int32_t off = 0; off < len_max; off += kLmLanes) {
+                const int32_t p = s + off + sl;
+                bool keep = false;
+                if (p < e) {
+                    const int32_t u = col_idx[p];
+                    keep = !pair_less(thr_k, thr_u, edge_key(seed_layer_mixed, (uint64_t)v, (uint64_t)u), u);
+                }
+                const uint32_t m = lm_group_ballot(keep, sub);
+                kept += __popc(m);
+                if (sl == 0) lm_or_bits(bits, (int64_t)s + off, m);
+            }
+        }
+        if (sl == 0 && mine) {
+            kept_len[v] = kept;
+            if (row_thr_key) {
+                row_thr_key[v] = thr_k;
+                row_thr_id[v] = thr_u;
+            }
+        }
+    }
+}
+
+// Fanout rule, rows longer than kLmShortRow: one wavefront per listed row.  Pass 1 finds the row's threshold pair
+// with a bounded list (see the head of the file; a fanout within 64 of the list's capacity - the list could not be
+// cut down far enough to take the next 64 entries - finds it by `fanout` rounds over the row itself); pass 2 reads
+// the row again and writes its bits, sixteen entries per atomic.
+__global__ __launch_bounds__(256) void lm_fanout_long_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                             const int32_t* __restrict__ rows, int32_t n_active, int32_t fanout,
+                                                             uint64_t seed_layer_mixed, uint32_t* __restrict__ bits,
+                                                             int32_t* __restrict__ kept_len, uint64_t* __restrict__ row_thr_key,
+                                                             int32_t* __restrict__ row_thr_id) {
+    __shared__ uint64_t s_key[4][kLmListCap];
+    __shared__ int32_t s_id[4][kLmListCap];
+    const int lane = lane_id(), wave = (int)(threadIdx.x >> 6);
+    uint64_t* key = s_key[wave];
+    int32_t* id = s_id[wave];
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const bool streaming = fanout <= kLmListCap - kWave;
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; i < n_active; i += waves) {   // uniform over the wave
+        const int32_t v = rows ? rows[i] : (int32_t)i;
+        const int32_t s = row_ptr[v], e = row_ptr[v + 1];
+        if (e - s <= kLmShortRow) continue;
+        uint64_t thr_k = ~0ull;   // pairs above (thr_k, thr_u) are out
+        int32_t thr_u = 0x7fffffff;
+        if (fanout == 0) {
+            thr_k = 0ull;
+            thr_u = -1;
+        } else if (e - s > fanout && streaming) {
+            int32_t n_list = 0;
+            for (int32_t p = s; p < e; p += kWave) {
+                const int32_t q = p + lane;
+                const int32_t u = q < e ? col_idx[q] : 0;
+                const uint64_t k = q < e ? edge_key(seed_layer_mixed, (uint64_t)v, (uint64_t)u) : 0ull;
+                bool take = q < e && !pair_less(thr_k, thr_u, k, u);
+                uint64_t mask = __ballot(take);
+                if (n_list + __popcll(mask) > kLmListCap) {   // uniform: cut the list down to its fanout smallest
+                    wave_lds_sync();
+                    wave_list_kth(key, id, n_list, fanout, lane, thr_k, thr_u);
+                    n_list = wave_list_keep_below(key, id, n_list, thr_k, thr_u, lane);
+                    take = q < e && !pair_less(thr_k, thr_u, k, u);
+                    mask = __ballot(take);
+                }
+                if (take) {
+                    const int32_t pos = n_list + __popcll(mask & lanes_below);
+                    key[pos] = k;
+                    id[pos] = u;
+                }
+                n_list += __popcll(mask);
+            }
+            wave_lds_sync();
+            if (n_list > fanout) wave_list_kth(key, id, n_list, fanout, lane, thr_k, thr_u);
+            wave_lds_sync();   // the list is read before the next row overwrites it
+        } else if (e - s > fanout) {
+            uint64_t prev_k = 0ull;
+            int32_t prev_u = -1;
+            for (int32_t round = 0; round < fanout; ++round) {
+                uint64_t best_k = ~0ull;
+                int32_t best_u = 0x7fffffff;
+                for (int32_t p = s + lane; p < e; p += kWave) {
+                    const int32_t u = col_idx[p];
+                    const uint64_t k = edge_key(seed_layer_mixed, (uint64_t)v, (uint64_t)u);
+                    if (pair_less(prev_k, prev_u, k, u) && pair_less(k, u, best_k, best_u)) {
+                        best_k = k;
+                        best_u = u;
+                    }
+                }
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const uint64_t ok = __shfl_xor(best_k, d, kWave);
+                    const int32_t ou = __shfl_xor(best_u, d, kWave);
+                    if (pair_less(ok, ou, best_k, best_u)) {
+                        best_k = ok;
+                        best_u = ou;
+                    }
+                }
+                prev_k = best_k;
+                prev_u = best_u;
+            }
+            thr_k = prev_k;
+            thr_u = prev_u;
         }
         int32_t kept = 0;
-        for (int32_t off = 0; off < len_max; off += kLmLanes) {
-            const int32_t p = s + off + sl;
+        for (int32_t p = s; p < e; p += kWave) {
+            const int32_t q = p + lane;
             bool keep = false;
-            if (p < e) {
-                const int32_t u = col_idx[p];
+            if (q < e) {
+                const int32_t u = col_idx[q];
                 keep = !pair_less(thr_k, thr_u, edge_key(seed_layer_mixed, (uint64_t)v, (uint64_t)u), u);
             }
-            const uint32_t m = lm_group_ballot(keep, sub);
-            kept += __popc(m);
-            if (sl == 0) lm_or_bits(bits, (int64_t)s + off, m);
+            const uint64_t m = __ballot(keep);
+            kept += __popcll(m);
+            if (lane < 4) lm_or_bits(bits, (int64_t)p + 16 * lane, (uint32_t)((m >> (16 * lane)) & 0xffffull));
         }
-        if (sl == 0 && i < n_active) {
+        if (lane == 0) {
             kept_len[v] = kept;
             if (row_thr_key) {
                 row_thr_key[v] = thr_k;
@@ -220,6 +348,11 @@ extern "C" int32_t gnn_layer_edge_mask(const gnn_csr* g, const int32_t* rows, in
             g->row_ptr, g->col_idx, rows, n_active, rule, fanout, threshold, mix64(seed + (uint64_t)layer), edge_keep, kept_len, row_thr_key,
             row_thr_id);
         GNN_LAUNCH_CHECK("lm_mask_kernel");
+        if (rule == GNN_LAYER_MASK_FANOUT) {
+            lm_fanout_long_kernel<<<grid_for((int64_t)n_active * kWave, 256, 4096), 256, 0, stream>>>(
+                g->row_ptr, g->col_idx, rows, n_active, fanout, mix64(seed + (uint64_t)layer), edge_keep, kept_len, row_thr_key, row_thr_id);
+            GNN_LAUNCH_CHECK("lm_fanout_long_kernel");
+        }
     }
     return GNN_OK;
 }

@@ -57,6 +57,12 @@ def test_masks_hub_rows_empty_rows_and_nothing_listed():
     assert g.degrees().max() > 1024
     _mask_case(g, None, "fanout", 15, 1, 1)
     _mask_case(g, None, "threshold", oracle.keep_threshold(0.1), 2, 1)
+    big = gg.chung_lu(20000, 1500.0, 2.1, 8)                  # rows with several times the entries a wavefront lists in LDS
+    assert big.degrees().max() > 4096
+    _mask_case(big, None, "fanout", 30, 1, 2)
+    _mask_case(big, np.arange(0, 20000, 7), "fanout", 1, 2, 3)
+    _mask_case(big, np.arange(0, 20000, 3), "fanout", 990, 1, 4)     # too large a fanout for the bounded list: rounds over the row
+    _mask_case(big, np.arange(0, 20000, 3), "fanout", 960, 1, 5)     # the largest fanout the bounded list takes
     d = gg.random_directed(5000, 1.5, 13)
     assert (d.degrees() == 0).any()
     _mask_case(d, None, "fanout", 2, 1, 9)
