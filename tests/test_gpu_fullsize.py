@@ -57,11 +57,14 @@ def _active_sets_full(w):
     part = w.partition
     print(f"{w.name}: active sets n={part.graph.n_rows} nnz={part.graph.nnz} L={w.n_layers}", flush=True)
     G = _graph(part)
-    dist, ring, off, hop = P.gnn_build_active_sets(G, dev(part.targets), w.n_layers)
     od, oring, ooff = oracle.active_sets(part.graph.row_ptr, part.graph.col_idx, part.targets, w.n_layers)
-    assert list(hop) == list(ooff)
-    assert np.array_equal(dist.cpu().numpy(), od)
-    assert np.array_equal(ring.cpu().numpy()[: ooff[-1]], oring)
+    # every level from the frontier, then with the transposed graph (the workloads are symmetric: the graph itself),
+    # the form the model calls, whose levels may run from the unreached vertices
+    for gt in (None, G):
+        dist, ring, off, hop = P.gnn_build_active_sets(G, dev(part.targets), w.n_layers, gt=gt)
+        assert list(hop) == list(ooff)
+        assert np.array_equal(dist.cpu().numpy(), od)
+        assert np.array_equal(ring.cpu().numpy()[: ooff[-1]], oring)
     return G, od, oring, ooff
 
 
