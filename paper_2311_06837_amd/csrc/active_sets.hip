@@ -16,7 +16,7 @@
 // the whole construction is enqueued without a host round trip.
 //
 // A level expands in one of two directions; the sets are the same either way.
-//   push  (from the frontier)  EDGE-parallel: a wavefront takes 64 frontier vertices, reads
+//   push  (from the frontier)  EDGE-parallel: a wavefront takes up to 64 frontier vertices, reads
 //         their row bounds in one sweep, and then walks the concatenation of their rows 256
 //         edges at a time (each lane finds the row of its edge by a binary search over the 64
 //         prefix sums in LDS), so rows of 5 and rows of 500 entries keep all lanes busy alike
@@ -99,10 +99,15 @@ __global__ __launch_bounds__(256) void as_seed_kernel(const int32_t* __restrict_
     }
 }
 
-constexpr int kAsU = 4;   // edges per lane and step: their index loads, then their bitmap probes, are issued together
+constexpr int kAsU = 8;   // edges per lane and step: their index loads, then their probes, are issued together
 
-// Push level.  One wavefront per 64 entries of the frontier list (grid-stride), edge-parallel inside (see the head of
-// the file).  nnz_t < 0: no transposed graph was given, every level is a push level.
+// Push level.  One wavefront per batch of up to 64 entries of the frontier list (grid-stride), edge-parallel inside
+// (see the head of the file).  A step of a wavefront is a chain of dependent loads (row bounds, ids, probes: about
+// 3 us), so what a level costs is the number of steps of its busiest wavefront: the batch is made as small as it can be
+// while every batch still finds a wavefront of its own (a power of two, at least 1) - 29 000 frontier vertices of
+// 490 entries each are 122 steps per wavefront in batches of 64 and 4 in batches of 4 (measured on the 8-level
+// workload, 62 500 frontier vertices of 27 entries: 0.28 -> 0.08 ms for the level).
+// nnz_t < 0: no transposed graph was given, every level is a push level.
 __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                         const int32_t* __restrict__ ring_ids,
                                                         const int64_t* __restrict__ hop_offsets, int32_t ring,
@@ -117,10 +122,12 @@ __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restric
     int32_t* ex = s_excl[wave];
     const int64_t wave_g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    for (int64_t b = begin + wave_g * kWave; b < end; b += n_waves * kWave) {   // uniform over the wavefront
+    int batch = kWave;
+    while (batch > 1 && (int64_t)(batch >> 1) * n_waves >= end - begin) batch >>= 1;
+    for (int64_t b = begin + wave_g * batch; b < end; b += n_waves * batch) {   // uniform over the wavefront
         const int64_t i = b + lane;
         int32_t s = 0, len = 0;
-        if (i < end) {
+        if (lane < batch && i < end) {
             const int32_t v = ring_ids[i];
             s = row_ptr[v];
             len = row_ptr[v + 1] - s;
@@ -164,15 +171,20 @@ __global__ __launch_bounds__(256) void as_expand_kernel(const int32_t* __restric
     }
 }
 
-// Hub rows of a push level: one workgroup per queued row (grid-stride over the queue), threads across the row, four
-// entries per step.  (In a pull level the queue is empty when this kernel runs.)
+// Hub rows of a push level: the queued rows are cut into as many equal pieces as the grid has workgroups per row, a
+// workgroup per piece (grid-stride), threads across the piece, kAsU entries per thread and step.  (In a pull level the
+// queue is empty when this kernel runs.)
 __global__ __launch_bounds__(256) void as_expand_hubs_kernel(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
                                                              uint8_t* __restrict__ seen, const int32_t* __restrict__ hubq,
                                                              const AsCtrl* ctrl) {
     const int32_t n_hubs = ctrl->n_hubs;
-    for (int32_t h = blockIdx.x; h < n_hubs; h += gridDim.x) {
-        const int32_t v = hubq[h];
-        const int32_t s = row_ptr[v], e = row_ptr[v + 1];
+    if (n_hubs <= 0) return;
+    const int32_t parts = (int32_t)gridDim.x / n_hubs > 1 ? (int32_t)gridDim.x / n_hubs : 1;
+    for (int64_t job = blockIdx.x; job < (int64_t)n_hubs * parts; job += gridDim.x) {   // uniform over the workgroup
+        const int32_t v = hubq[job / parts];
+        const int32_t part = (int32_t)(job % parts);
+        const int64_t s0 = row_ptr[v], len = row_ptr[v + 1] - s0;
+        const int32_t s = (int32_t)(s0 + len * part / parts), e = (int32_t)(s0 + len * (part + 1) / parts);
         for (int32_t base = s + (int32_t)threadIdx.x; base < e; base += 256 * kAsU) {
             int32_t u[kAsU];
             uint8_t w[kAsU];
@@ -219,8 +231,8 @@ __global__ __launch_bounds__(256) void as_plan_kernel(const int32_t* __restrict_
     }
 }
 
-// Pull level.  Sixteen lanes per bitmap word (grid-stride): for each vertex of the word that is not in the set yet,
-// scan its transposed row 64 entries at a time and stop at the first entry that is in the frontier.  A lane group
+// Pull level.  A wavefront per bitmap word (grid-stride), sixteen lanes per vertex: for each vertex of the word that is
+// not in the set yet, scan its transposed row 64 entries at a time and stop at the first entry that is in the frontier.  A lane group
 // is the only writer of its vertices' bytes in this kernel.  Rows longer than kAsHubDegree go to the queue.
 __global__ __launch_bounds__(256) void as_pull_kernel(const int32_t* __restrict__ row_ptr_t, const int32_t* __restrict__ col_idx_t,
                                                       int32_t n, int64_t nw, const uint32_t* __restrict__ visited,
@@ -229,13 +241,21 @@ __global__ __launch_bounds__(256) void as_pull_kernel(const int32_t* __restrict_
                                                       int32_t* __restrict__ hubq, AsCtrl* ctrl) {
     if (!as_pull_level(ctrl, hop_offsets, ring, n, nnz_t)) return;   // uniform over the grid
     const int lane = lane_id(), sub = lane / 16, sl = lane % 16;
-    const int64_t groups = ((int64_t)gridDim.x * blockDim.x) / 16;
-    for (int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 16; w < nw; w += groups) {
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; w < nw; w += waves) {   // uniform over the wave
         uint32_t open = ~visited[w];
         if (w == nw - 1 && (n & 31)) open &= (1u << (n & 31)) - 1u;
-        while (open) {   // uniform over the lane group
-            const int b = __ffs(open) - 1;
-            open &= open - 1u;
+        // the wavefront's four lane groups share the word: group k takes its k-th, (k+4)-th, ... unreached vertex (a
+        // vertex is a chain of dependent loads; four chains run side by side)
+        uint32_t mine = 0u;
+        for (int k = 0; open; ++k) {   // uniform over the wave
+            const uint32_t lowest = open & (0u - open);
+            open ^= lowest;
+            if ((k & 3) == sub) mine |= lowest;
+        }
+        while (mine) {   // uniform over the lane group
+            const int b = __ffs(mine) - 1;
+            mine &= mine - 1u;
             const int32_t v = (int32_t)(w * 32 + b);
             const int32_t s = row_ptr_t[v], e = row_ptr_t[v + 1];
             if (e - s > kAsHubDegree) {
@@ -595,7 +615,7 @@ extern "C" int32_t gnn_build_active_sets(const gnn_csr* g, const gnn_csr* gt, co
                 as_expand_hubs_kernel<<<2048, 256, 0, stream>>>(g->row_ptr, g->col_idx, seen, hubq, ctrl);
                 GNN_LAUNCH_CHECK("as_expand_hubs_kernel");
                 if (gt != nullptr) {
-                    as_pull_kernel<<<grid_for(nw * 16, 256, expand_grid), 256, 0, stream>>>(gt->row_ptr, gt->col_idx, n, nw, visited, seen,
+                    as_pull_kernel<<<grid_for(nw * kWave, 256, 8192), 256, 0, stream>>>(gt->row_ptr, gt->col_idx, n, nw, visited, seen,
                                                                                            frontier, hop_offsets, ring - 1, nnz_t, hubq, ctrl);
                     GNN_LAUNCH_CHECK("as_pull_kernel");
                     as_pull_hubs_kernel<<<1024, 256, 0, stream>>>(gt->row_ptr, gt->col_idx, seen, frontier, hop_offsets, ring - 1, n, nnz_t,

@@ -67,6 +67,7 @@ class MaskedGNN:
         assert kind in ("gcn", "sage")
         self.layer_sampling = layer_sampling
         self.prefix_numbered, self._prefix_checked = prefix_numbered, False
+        self.rs = self.cs = None
         self.g, self.gt, self.targets, self.kind, self.dtype = graph, graph_t, targets, kind, dtype
         self.n = graph.n_rows
         self.L = len(params)
@@ -154,12 +155,13 @@ class MaskedGNN:
     def build_active_sets(self):
         self.dist, self.ring_ids, self.hop_offsets, self.hop = self._call(
             "active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws, gt=self.gt)
-        if self.kind == "gcn":
-            s = B.gnn_norm_scales(B.GNN_NORM_SYM, self.n, length=self.global_degree,
-                                  row_ptr=None if self.global_degree is not None else self.g.row_ptr)
-            self.rs, self.cs = s, s
-        else:
-            self.rs, self.cs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr), None
+        if self.rs is None:      # the normalisation factors depend on the graph alone: made once, not per step
+            if self.kind == "gcn":
+                s = B.gnn_norm_scales(B.GNN_NORM_SYM, self.n, length=self.global_degree,
+                                      row_ptr=None if self.global_degree is not None else self.g.row_ptr)
+                self.rs, self.cs = s, s
+            else:
+                self.rs, self.cs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr), None
         if self.prefix_numbered and not self._prefix_checked:
             n_all = int(self.hop[-1])
             ident = torch.arange(n_all, dtype=torch.int32, device=self.ring_ids.device)
@@ -452,6 +454,7 @@ class ResSAGEPlus:
         self.g, self.gt, self.targets, self.dtype = graph, graph_t, targets, dtype
         self.n, self.L = graph.n_rows, len(params)
         self.prefix_numbered, self.recompute = prefix_numbered, recompute
+        self._prefix_checked, self.rs = False, None
         self.ws = B.Workspace()
         self.dims = [params[0]["W_neigh"].shape[0]] + [p["W_neigh"].shape[1] for p in params]
         assert all(d == self.dims[1] for d in self.dims[1:-1]), "the residual connection needs equal hidden widths"
@@ -488,8 +491,10 @@ class ResSAGEPlus:
 
     def build_active_sets(self):
         self.dist, self.ring_ids, self.hop_offsets, self.hop = self._call("active_sets", B.gnn_build_active_sets, self.g, self.targets, self.L, ws=self.ws, gt=self.gt)
-        self.rs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr)
-        if self.prefix_numbered:
+        if self.rs is None:      # depends on the graph alone: made once, not per step
+            self.rs = B.gnn_norm_scales(B.GNN_NORM_MEAN, self.n, row_ptr=self.g.row_ptr)
+        if self.prefix_numbered and not self._prefix_checked:
+            self._prefix_checked = True
             n_all = int(self.hop[-1])
             if not torch.equal(self.ring_ids[:n_all], torch.arange(n_all, dtype=torch.int32, device=self.ring_ids.device)):
                 raise ValueError("prefix_numbered was promised but the ring-sorted ids are not 0 .. n-1")
