@@ -9,6 +9,9 @@
 // a plain store of 1 - whoever comes first, the byte ends up the same - where a bit needs an
 // atomic OR, and a ring of a few million new vertices packs those atomics onto a few thousand
 // cache lines (measured: 0.60 ms of atomics for 24 M edges that discover 2.2 M vertices).
+// The byte accesses are ordinary loads and stores on purpose: a stale 0 from the vector cache
+// only means one more store of the same 1 (relaxed atomic loads, which bypass that cache, were
+// measured 15 to 50 % slower per construction); kernel boundaries order the levels.
 // A level is: expand -> count / scan / emit, a compaction of seen & ~visited that lists the
 // new ring in ascending id order without any sort, so the output does not depend on which
 // wave found a vertex first; emit then brings visited up to seen.  Ring sizes stay on
