@@ -333,24 +333,39 @@ __device__ __forceinline__ int commit_tile(const SpmmArgs& a, bool in_row, int32
 
 // acc += sum over the staged tile.  `cnt` (this group's entries) may differ between the groups
 // of a wave; `cnt_max` is uniform over the wave.  Each round issues U x NCH independent row loads
-// (plus U broadcast loads of the neighbour scale) before the first multiply-add.
+// (plus U broadcast loads of the neighbour scale) before the first multiply-add.  The issue part has
+// no branch that depends on a lane: a slot past the group's count repeats the group's last entry (a
+// cache hit) and a lane past the row's width reads the row's start; only the multiply-adds are
+// predicated.  (With a branch around every load the compiler put a wait for the id's LDS read and
+// two mask updates between any two loads: sixteen loads took longer to issue than to arrive.)
 template <typename E, int LPR, int NCH, int U>
 __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt_max, int sub, const int64_t (&col_off)[NCH],
                                              const bool (&col_ok)[NCH], const int32_t* s_idx, float (&acc)[NCH][E::VE]) {
+    int64_t col_ld[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) col_ld[c] = col_ok[c] ? col_off[c] : 0;
+    const int last = cnt > 0 ? cnt - 1 : 0;
     for (int k = 0; k < cnt_max; k += U) {
         typename E::Raw x[U][NCH];
         float w[U];
+        int32_t u[U];
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            w[j] = 1.f;
-            if (k + j < cnt) {
-                const int32_t u = s_idx[sub * LPR + k + j];
-                if (a.nbr_scale) w[j] = a.nbr_scale[u];
-                const int64_t base = (int64_t)u * a.ldx;
+            const int32_t staged = s_idx[sub * LPR + (k + j < cnt ? k + j : last)];
+            u[j] = cnt > 0 ? staged : 0;   // nothing staged for this group: the slot may hold anything, row 0 always exists
+        }
+        if (a.nbr_scale) {   // uniform
 #pragma unroll
-                for (int c = 0; c < NCH; ++c)
-                    if (col_ok[c]) x[j][c] = E::load(a.X, base + col_off[c]);
-            }
+            for (int j = 0; j < U; ++j) w[j] = a.nbr_scale[u[j]];
+        } else {
+#pragma unroll
+            for (int j = 0; j < U; ++j) w[j] = 1.f;
+        }
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            const int64_t base = (int64_t)u[j] * a.ldx;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) x[j][c] = E::load(a.X, base + col_ld[c]);
         }
 #pragma unroll
         for (int j = 0; j < U; ++j) {
