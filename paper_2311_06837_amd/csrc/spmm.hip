@@ -23,12 +23,25 @@
 
 namespace gnnhot {
 
-// independent row loads in flight per lane-chunk when a lane owns one 16-byte chunk of the row
+// Independent row loads in flight per lane (a round), and workgroups per CU, when a lane owns one 16-byte chunk of
+// the row.  A round must divide the tile (16, 32 or 64 entries): 6, 10 or 12 loads were all slower than 8.  Measured
+// as the step time of the 8-level bf16 workload / the sampled-partition workload (ms; rows of 256 and 512 bytes, 10
+// to 20 neighbours, partitions numbered by (distance, id)): rounds of 16 at 4 workgroups per CU 17.5 / 23.7, 8 at 6
+// 17.5 / 24.2, 8 at 5 or 4 16.5 / 23.4, 4 at 8 19.5 / 24.8 - slots of a round past the end of a tile are wasted issue
+// slots of the vector cache, but eight workgroups of short rounds lose more to the caches than they gain.  (On the
+// same graph numbered by global id the order is the reverse, 4 at 8 being 18 % faster than 16 at 4: the setting
+// follows the numbering the extraction produces.)  Rows of 1 KB (64 lanes per row): 8 at 5 (8 at 6: +2 %).
 #ifndef GNN_SPMM_U_NARROW
-#define GNN_SPMM_U_NARROW 16
+#define GNN_SPMM_U_NARROW 8
 #endif
 #ifndef GNN_SPMM_U_WIDE
 #define GNN_SPMM_U_WIDE 8
+#endif
+#ifndef GNN_SPMM_MINB_NARROW
+#define GNN_SPMM_MINB_NARROW 5
+#endif
+#ifndef GNN_SPMM_MINB_WIDE
+#define GNN_SPMM_MINB_WIDE 5
 #endif
 
 #ifndef GNN_SPMM_RPG
@@ -77,6 +90,8 @@ struct SpmmArgs {
     const void* relu_h;       // nullable: the stored result is zeroed where this matrix (same rows and columns as Y) is <= 0
     int64_t ldh;
     int32_t rows_per_group;   // 1..kRowsPerGroup: rows of the list per LPR-lane group in one workgroup
+    uint32_t x_row_bytes;     // > 0: X holds fewer than 2^24 rows and less than 4 GB, a row starts every x_row_bytes bytes - the
+                              // row kernel then forms a gather address with one 24-bit multiply-add instead of a 64-bit product
     // column-blocked route only
     const int32_t* seg;       // [n_active][n_blocks + 1] cut points of every listed row: block j = [seg[j], seg[j+1])
     const int32_t* seg_end;   // nullable, [n_active][n_blocks]: block j ends here instead (filtered, compacted copy of the ids)
@@ -344,6 +359,9 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
     int64_t col_ld[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) col_ld[c] = col_ok[c] ? col_off[c] : 0;
+    uint32_t col_ld_bytes[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) col_ld_bytes[c] = (uint32_t)col_ld[c] * (uint32_t)(sizeof(typename E::Raw) / E::VE);
     const int last = cnt > 0 ? cnt - 1 : 0;
     for (int k = 0; k < cnt_max; k += U) {
         typename E::Raw x[U][NCH];
@@ -361,11 +379,20 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
 #pragma unroll
             for (int j = 0; j < U; ++j) w[j] = 1.f;
         }
+        if (a.x_row_bytes) {   // uniform
 #pragma unroll
-        for (int j = 0; j < U; ++j) {
-            const int64_t base = (int64_t)u[j] * a.ldx;
+            for (int j = 0; j < U; ++j) {
+                const uint32_t base = __umul24((uint32_t)u[j], a.x_row_bytes);
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) x[j][c] = E::load(a.X, base + col_ld[c]);
+                for (int c = 0; c < NCH; ++c) x[j][c] = *(const typename E::Raw*)((const char*)a.X + (base + col_ld_bytes[c]));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                const int64_t base = (int64_t)u[j] * a.ldx;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) x[j][c] = E::load(a.X, base + col_ld[c]);
+            }
         }
 #pragma unroll
         for (int j = 0; j < U; ++j) {
@@ -390,10 +417,9 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
 //   phase 2  hub rows (longer than kHubDegree) are taken one at a time by ALL groups (group q takes
 //            tiles q, q+NG, ...); the partial sums meet in LDS and are added in group order.
 // Which group handles a row does not change the order of its additions: results are bit-reproducible.
-// At least four workgroups per CU (six when a lane holds a single chunk and eight loads): the gather is
-// latency-bound, so resident wavefronts matter more than a few registers.
+// Workgroups per CU: see the tuning constants at the head of the file.
 template <int DT, int VE, int LPR, int NCH, int U, bool FILTER>
-__global__ __launch_bounds__(256, (NCH == 1 && U <= 8) ? 6 : 4) void spmm_rows_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(256, NCH == 1 ? (LPR == 64 ? GNN_SPMM_MINB_WIDE : GNN_SPMM_MINB_NARROW) : 4) void spmm_rows_kernel(SpmmArgs a) {
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
     constexpr int NG = 4 * RPW;
@@ -1318,6 +1344,11 @@ static int32_t spmm_common(const gnn_csr* g, const char* gname, const int32_t* r
     a.accumulate = accumulate;
     a.relu_h = relu_h; a.ldh = ldh;
     a.rows_per_group = 1;
+    {
+        const int64_t row_bytes = ldx * (dtype == GNN_F32 ? 4 : 2);
+        const bool small = g->n_cols < (1 << 24) && row_bytes < (1 << 24) && (int64_t)g->n_cols * row_bytes < ((int64_t)1 << 32);
+        a.x_row_bytes = small ? (uint32_t)row_bytes : 0u;
+    }
     a.seg = nullptr; a.seg_end = nullptr; a.edge_w = nullptr; a.n_blocks = 0; a.block0 = 0;
 
     if (plan.passes > 0) {

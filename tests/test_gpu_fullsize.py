@@ -314,9 +314,10 @@ def test_cfg3_full_size_bf16(cfg3):
     _linear_sampled(w, allrows, 128, 128, torch.bfloat16, True, 28, in_place=True)
 
 
-def test_cfg4_sampling_and_active_sets_full_size():
-    """configs[4]: boundary sampling over the 10M-vertex graph and the extraction of the sampled partition, both
-    bit-exact in full; then the active sets of the sampled partition."""
+@pytest.fixture(scope="module")
+def cfg4_sampled():
+    """configs[4] through sampling and extraction on the GPU and in the oracle, once for the tests below (the 10M-vertex
+    graph takes a minute to generate).  Everything the later tests use on the host side is the ORACLE's."""
     import paper_2311_06837_amd as P
     print("generating cfg4 at full size", flush=True)
     w = gg.make_workload("cfg4")
@@ -329,29 +330,50 @@ def test_cfg4_sampling_and_active_sets_full_size():
     is_t = np.zeros(g.n_rows, dtype=np.uint8)
     is_t[T] = 1
     orp, oci = oracle.sample_boundary(g.row_ptr, g.col_idx, is_t, T, w.fanout, w.sample_seed)
-    assert np.array_equal(rp.cpu().numpy(), orp)
-    assert np.array_equal(ci.cpu().numpy(), oci)
     print("cfg4: extraction of the sampled partition", flush=True)
     local, l2g_d, hop = P.gnn_extract_sampled_partition(G, Td, rp, ci)
     torch.cuda.synchronize()
     xrp, xci, xl2g, xoff, _ = oracle.extract_sampled(g.n_rows, T, orp, oci)
-    assert [int(x) for x in hop] == [int(x) for x in xoff]
-    assert np.array_equal(l2g_d.cpu().numpy(), xl2g)
-    assert np.array_equal(local.row_ptr.cpu().numpy(), xrp)
-    assert np.array_equal(local.col_idx.cpu().numpy(), xci)
     del G
+    return dict(w=w, g=g, T=T, gpu=(rp.cpu().numpy(), ci.cpu().numpy(), [int(x) for x in hop], l2g_d.cpu().numpy(),
+                                    local.row_ptr.cpu().numpy(), local.col_idx.cpu().numpy()),
+                oracle=(orp, oci, xrp, xci, xl2g, xoff), local=local)
+
+
+def test_cfg4_sampling_and_extraction_full_size(cfg4_sampled):
+    """configs[4]: boundary sampling over the 10M-vertex graph and the extraction of the sampled partition, both
+    bit-exact in full; then the active sets of the sampled partition."""
+    c = cfg4_sampled
+    rp, ci, hop, l2g_gpu, lrp, lci = c["gpu"]
+    orp, oci, xrp, xci, xl2g, xoff = c["oracle"]
+    assert np.array_equal(rp, orp)
+    assert np.array_equal(ci, oci)
+    assert hop == [int(x) for x in xoff]
+    assert np.array_equal(l2g_gpu, xl2g)
+    assert np.array_equal(lrp, xrp)
+    assert np.array_equal(lci, xci)
+    w, g, T = c["w"], c["g"], c["T"]
     l2g, er, ec = oracle.sampled_local_edges(T, orp, oci)
-    part = gg.partition_from_edges(g.n_rows, l2g, er, ec, T, g.degrees())
-    w.partition = part
+    w.partition = gg.partition_from_edges(g.n_rows, l2g, er, ec, T, g.degrees())
     _active_sets_full(w)
 
-    # The floating-point calls of the step on the extracted partition, in the forms bench.py's model issues them:
-    # bf16, rows as id prefixes (no lists), the backward filter as a source prefix, 128 / 256 / 32 columns.  The host
-    # copy of the graph is the ORACLE's extraction (the GPU's was just shown to equal it bit for bit).
+
+def _cfg4_local_partition(c):
+    """The extracted partition as a host workload (the oracle's extraction, which the GPU's equals bit for bit)."""
+    w, g, T = c["w"], c["g"], c["T"]
+    orp, oci, xrp, xci, xl2g, xoff = c["oracle"]
     n_loc, nt = int(xoff[-1]), int(T.size)
     lg = gg.CSR(n_loc, n_loc, xrp, xci)
     w.partition = gg.Partition(lg, lg, xl2g.astype(np.int64), np.arange(nt, dtype=np.int32), g.degrees()[xl2g].astype(np.int32))
-    allrows, trows = np.arange(n_loc, dtype=np.int32), np.arange(nt, dtype=np.int32)
+    return w, n_loc, nt
+
+
+def test_cfg4_aggregations_full_size(cfg4_sampled):
+    """The aggregation calls of the step on the extracted partition of configs[4], in the forms bench.py's model issues
+    them: bf16, rows as id prefixes (no lists), the backward filter as a source prefix, 128 / 256 / 32 columns."""
+    w, n_loc, nt = _cfg4_local_partition(cfg4_sampled)
+    local = cfg4_sampled["local"]
+    allrows = np.arange(n_loc, dtype=np.int32)
     bf = torch.bfloat16
     _, _, _, sc = _spmm_fwd_sampled(w, local, allrows, 128, bf, "sage", 41, n_sample=1200, as_prefix=True)     # layer 1
     _spmm_fwd_sampled(w, local, allrows, 256, bf, "sage", 42, n_sample=1200, as_prefix=True)                    # layer 2 (dominant call)
@@ -361,7 +383,14 @@ def test_cfg4_sampling_and_active_sets_full_size():
     # backward of layer 2: every vertex was a forward row, sums added onto the self half, ReLU of layer 1 undone
     _spmm_bwd_sampled(w, local, None, allrows, 0, 256, bf, sc, 45, n_sample=1200, src_prefix=n_loc, as_prefix=True,
                       accumulate=True, relu=True)
-    del local
+
+
+def test_cfg4_feature_transforms_full_size(cfg4_sampled):
+    """The feature transforms of configs[4] on the extracted partition: bf16, 128 -> 256, 256 -> 256, 256 -> 32."""
+    w, n_loc, nt = _cfg4_local_partition(cfg4_sampled)
+    cfg4_sampled["local"] = None        # the device copy of the graph is not needed any more
+    allrows, trows = np.arange(n_loc, dtype=np.int32), np.arange(nt, dtype=np.int32)
+    bf = torch.bfloat16
     _linear_sampled(w, allrows, 128, 256, bf, True, 46, n_sample=1000, n_cols=4, in_place=True)
     _linear_sampled(w, allrows, 256, 256, bf, True, 47, n_sample=1000, n_cols=4, in_place=True)
     _linear_sampled(w, trows, 256, 32, bf, True, 48, n_sample=1000, n_cols=4, in_place=True)
