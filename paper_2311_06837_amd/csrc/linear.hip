@@ -1329,10 +1329,12 @@ extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const v
     const int n_src = X_self ? 2 : 1;
     const int64_t ldz = (int64_t)align_up((size_t)N, 16 / es);
     const int32_t n_part = n_active > 0 ? (n_active + kDzRows - 1) / kDzRows : 1;
-    // row splits of the weight-gradient reduction: about four workgroups per CU, at least 256 rows each,
-    // at most 256 splits and 128 MB of partial tiles
+    // Row splits of the weight-gradient reduction: as many as give every CU the three workgroups it can hold at once
+    // and no more (256 CUs: 768 workgroups; the splits are equally long, so a second, partly filled round of workgroups
+    // would cost a whole round: 1024 workgroups took 2 rounds where 768 take 1.33 of the old round's length), at least
+    // 256 rows each, at most 256 splits and 128 MB of partial tiles
     const int tiles = n_src * ((K + 127) / 128) * (N > 32 ? (N + 127) / 128 : 1);
-    int32_t splits = (1024 + tiles - 1) / tiles;
+    int32_t splits = 768 / tiles;
     const int32_t max_splits = n_active > 0 ? (n_active + 255) / 256 : 1;
     const int64_t split_bytes = (int64_t)n_src * K * N * 4;
     if (splits > max_splits) splits = max_splits;
