@@ -14,7 +14,7 @@
 // row read; 64/LPR rows share a wavefront when rows are narrow.  Neighbour ids are fetched one
 // tile ahead, coalesced, filtered, compacted and staged in an LDS tile private to the
 // wavefront; the inner loop then reads the tile by broadcast and keeps U x NCH independent
-// 16-byte loads in flight per lane.  Groups claim rows dynamically inside a workgroup's chunk.  Rows longer than kHubDegree
+// 16-byte loads in flight per lane.  Groups claim rows dynamically inside a workgroup's chunk.  Rows of more than kHubTiles tiles
 // (power-law hubs) are split over all wavefronts of the workgroup and the partial sums are
 // reduced through LDS in a fixed order, inside the same launch.
 #include "common.h"
@@ -44,11 +44,24 @@ namespace gnnhot {
 #define GNN_SPMM_MINB_WIDE 5
 #endif
 
+// Rows of the list per lane group in one workgroup, and the length (in tiles of LPR entries) from which a row is
+// split over all groups of the workgroup.  A group walks a row alone, tile by tile; with power-law rows one long row
+// keeps its group - and the workgroup's registers and LDS - busy long after the other groups have run out of rows
+// (simulated on the 8-level workload's graph: the groups of a 64-row workgroup are busy 35 % of its lifetime when only
+// rows above 1024 entries are split).  Small chunks let the hardware's workgroup dispatch do the balancing, and a low
+// split length bounds what one group can be left with.  Measured as the step time of the 8-level / the
+// sampled-partition workload (ms): 4 rows per group and rows split above 1024 entries 16.5 / 23.4; 4 and 16 tiles
+// 15.9 / 22.6; 2 and 16 tiles 15.2 / 21.4; 2 and 4 tiles 14.1 / 20.7; 3 and 4..12 tiles 14.0 / 21.4; 1 row per group
+// 17.4 / 22.5; 8 or 16 rows per group 21.6 .. 31 / 24.4 .. 28.
 #ifndef GNN_SPMM_RPG
-#define GNN_SPMM_RPG 4
+#define GNN_SPMM_RPG 2
 #endif
 constexpr int kRowsPerGroup = GNN_SPMM_RPG;   // largest chunk: this many rows of the list per group
-constexpr int kHubDegree = 1024;   // rows longer than this are split over the whole workgroup
+#ifndef GNN_SPMM_HUB_TILES
+#define GNN_SPMM_HUB_TILES 4
+#endif
+constexpr int kHubTiles = GNN_SPMM_HUB_TILES;   // rows of more tiles (of LPR entries) than this are split over the whole workgroup
+constexpr int kMaxChunk = 256;                  // rows of the list per workgroup, at most (one descriptor per thread)
 
 // Column-blocked route (dense graphs, gathered matrix far larger than an L2).  The neighbour-id
 // range [0, n_cols) is cut into 8 * passes equal blocks; in pass p workgroup i gathers, for its
@@ -414,7 +427,7 @@ __device__ __forceinline__ void consume_tile(const SpmmArgs& a, int cnt, int cnt
 //            step; a group that finishes a row claims the next unclaimed one from an LDS counter,
 //            so short and long rows mix without idle groups, and the ids of the NEXT tile are
 //            fetched while the current tile's rows are being gathered;
-//   phase 2  hub rows (longer than kHubDegree) are taken one at a time by ALL groups (group q takes
+//   phase 2  hub rows (more than kHubTiles tiles) are taken one at a time by ALL groups (group q takes
 //            tiles q, q+NG, ...); the partial sums meet in LDS and are added in group order.
 // Which group handles a row does not change the order of its additions: results are bit-reproducible.
 // Workgroups per CU: see the tuning constants at the head of the file.
@@ -423,7 +436,7 @@ __global__ __launch_bounds__(256, NCH == 1 ? (LPR == 64 ? GNN_SPMM_MINB_WIDE : G
     using E = Elem<DT, VE>;
     constexpr int RPW = kWave / LPR;
     constexpr int NG = 4 * RPW;
-    constexpr int RPB = NG * kRowsPerGroup;  // largest chunk, <= 128
+    constexpr int RPB = NG * kRowsPerGroup < kMaxChunk ? NG * kRowsPerGroup : kMaxChunk;  // largest chunk
     constexpr int W = LPR * NCH * VE;        // feature columns per workgroup (grid.y blocks cover F)
     __shared__ int32_t s_idx_all[4][kWave];
     __shared__ int32_t s_row_v[RPB], s_row_s[RPB], s_row_e[RPB], s_row_hub[RPB], s_row_he[RPB];
@@ -445,7 +458,7 @@ __global__ __launch_bounds__(256, NCH == 1 ? (LPR == 64 ? GNN_SPMM_MINB_WIDE : G
         const int32_t s = a.row_ptr[v];
         int32_t e = a.row_ptr[v + 1];
         if (a.cut_id >= 0) e = row_lower_bound(a.col_idx, s, e, a.cut_id);   // the entries past it can never pass the filter
-        const bool hub = e - s > kHubDegree;
+        const bool hub = e - s > kHubTiles * LPR;
         s_row_v[r] = v;
         s_row_s[r] = s;
         s_row_e[r] = hub ? s : e;
@@ -888,7 +901,8 @@ static int32_t launch_rows(const SpmmArgs& a, hipStream_t stream) {
     // has about 16 workgroups per CU
     SpmmArgs b = a;
     int rpg = (int)((int64_t)a.n_active / ((int64_t)NG * 4096));
-    b.rows_per_group = rpg < 1 ? 1 : (rpg > kRowsPerGroup ? kRowsPerGroup : rpg);
+    constexpr int kMaxRpg = kRowsPerGroup * NG <= kMaxChunk ? kRowsPerGroup : kMaxChunk / NG;
+    b.rows_per_group = rpg < 1 ? 1 : (rpg > kMaxRpg ? kMaxRpg : rpg);
     const int rpb = NG * b.rows_per_group;
     dim3 grid((unsigned)(((int64_t)a.n_active + rpb - 1) / rpb), (unsigned)((a.F + W - 1) / W));
     spmm_rows_kernel<DT, VE, LPR, NCH, U, FILTER><<<grid, 256, 0, stream>>>(b);
