@@ -209,6 +209,33 @@ __device__ __forceinline__ float post_elem(float v, const void* C, int64_t coff,
     return h > 0.f ? v : 0.f;
 }
 
+// post_vec with its two loads already done: v + old (where has_old) where h > 0, else 0.
+template <int DT>
+__device__ __forceinline__ uint4 post_apply(uint4 v, uint4 old, bool has_old, uint4 h4) {
+    if (DT == GNN_F32) {
+        float x[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+        if (has_old) {
+            x[0] += __uint_as_float(old.x); x[1] += __uint_as_float(old.y); x[2] += __uint_as_float(old.z); x[3] += __uint_as_float(old.w);
+        }
+        return make_uint4(__float_as_uint(__uint_as_float(h4.x) > 0.f ? x[0] : 0.f), __float_as_uint(__uint_as_float(h4.y) > 0.f ? x[1] : 0.f),
+                          __float_as_uint(__uint_as_float(h4.z) > 0.f ? x[2] : 0.f), __float_as_uint(__uint_as_float(h4.w) > 0.f ? x[3] : 0.f));
+    }
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t o[4] = {old.x, old.y, old.z, old.w};
+    const uint32_t h[4] = {h4.x, h4.y, h4.z, h4.w};
+    uint32_t r[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float lo = bf16lo(w[e]), hi = bf16hi(w[e]);
+        if (has_old) {
+            lo += bf16lo(o[e]);
+            hi += bf16hi(o[e]);
+        }
+        r[e] = pack_bf16(bf16lo(h[e]) > 0.f ? lo : 0.f, bf16hi(h[e]) > 0.f ? hi : 0.f);
+    }
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
 template <int DT, int BN, int WM, int WN, bool VEC>
 __global__ __launch_bounds__(256, BN == 128 ? GNN_NT_MINB : GNN_NT_MINB_NARROW) void gemm_nt_kernel(GemmNT a) {
     constexpr int BM = 128;
@@ -708,6 +735,292 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// gemm_nt, line tile.  Same tile as the wide variant (128 rows x the whole output width, a wave
+// 64 x 32*NTW), two things done differently.
+// (1) The reduction moves in slices of 128 bytes - one whole cache line of every operand row.  With
+// 64-byte slices every line is asked for twice, one step apart, and by then it has left the CU's
+// vector cache: the L2 sees two requests per line.  A slice of this size leaves room for ONE copy in
+// LDS (48 KB at 256 columns, two workgroups per CU), so a step has two barriers: slice s feeds the
+// MFMAs while slice s+1 is in flight into registers; barrier; the registers go to LDS; barrier.  The
+// other workgroup of the CU computes meanwhile, and the last quarter of a slice is multiplied while
+// the first quarter of the next one comes from LDS.  LDS rows are 128 bytes without padding; the
+// 16-byte chunk c of row r sits at slot c ^ ((r >> 1) & 7): sixteen consecutive rows read with the
+// same c touch all 64 banks once.
+// (2) The epilogue never waits for memory.  A short reduction (2 .. 8 steps at the paper's widths)
+// leaves the epilogue a third of a tile's time, and most of that was waiting: loads and stores share
+// one counter on this chip, so any load inside the epilogue (a bias value, an output row index, and
+// the wait the compiler puts where a branch around such a load rejoins) stalls until the stores
+// before it have landed.  Here the bias and the output rows are put in LDS when the tile starts, LDS
+// reads are issued in batches ahead of their use, the activation mask of a fused input gradient is
+// loaded for all rows of a pass before the first store of that pass, and the MFMAs run with the
+// operands exchanged so that a lane holds four CONSECUTIVE columns of one row (8- or 16-byte LDS
+// writes instead of 2-byte ones).
+// Preconditions (checked by the launcher, which sends everything else to the wide variant): 16-byte
+// aligned operand, output and mask rows, a reduction length that is a multiple of the slice, an
+// output width that is a multiple of the tile width.
+// ------------------------------------------------------------------------------------------
+template <int DT, int NTW>
+__global__ __launch_bounds__(256, NTW == 4 ? 2 : 3) void gemm_nt_line_kernel(GemmNT a) {
+    constexpr int BM = 128, BN = 64 * NTW, MT = 2, NT = NTW, WTN = 32 * NTW;
+    constexpr int ES = DTy<DT>::ES, EPV = DTy<DT>::EPV;
+    constexpr int EPS = 128 / ES;                  // reduction elements per slice
+    constexpr int B_CH = BN / 32;                  // 16-byte chunks of the second operand per thread and slice (first: 4)
+    constexpr int BUF = (BM + BN) * 32;            // words of the slice buffer
+    constexpr int CW = (256 / ES) < WTN ? (256 / ES) : WTN;  // columns of one staged output piece (<= 256 bytes)
+    constexpr int CROW = CW * ES / 4 + 4;          // words per staged row (16 bytes of padding)
+    constexpr int STAGE = 32 * CROW;               // words per wave
+    constexpr int SMEM = BUF > 4 * STAGE ? BUF : 4 * STAGE;
+    __shared__ __attribute__((aligned(16))) uint32_t smem[SMEM];
+    // The tile's bias values and output rows wait in LDS: read from global memory inside the epilogue, each of them
+    // would make the wave wait for EVERY vector-memory operation it has in flight - that is, for the stores of the rows
+    // before - because one counter covers loads and stores alike.
+    __shared__ float s_bias[BN];
+    __shared__ int32_t s_crow[BM];
+
+    const int tiles_n = a.N / BN;
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, g = lane >> 5;
+    const int ld_row = tid >> 3, ld_c = tid & 7;   // loader: row within a 32-row band, 16-byte chunk of the slice
+    const int st_off = ld_row * 32 + ((ld_c ^ ((ld_row >> 1) & 7)) << 2);  // word offset of that chunk inside a band
+    const int k_slices = a.K / EPS;
+    // the tile's rows of the second operand are all in range (N is a multiple of BN): band c lies c * 32 rows further
+    const int64_t b_band = 32 * a.ldb * ES;
+
+    const int m0 = (int)(blockIdx.x / tiles_n) * BM, n0 = (int)(blockIdx.x % tiles_n) * BN;
+    // operand row of the loader's band c (rows past M read an addressable row; their results are never stored)
+    auto a_row = [&](int c) -> int64_t {
+        const int m = m0 + ld_row + 32 * c;
+        const int64_t r = m < a.M ? (a.a_rows ? (int64_t)a.a_rows[m] : (int64_t)m) : (a.a_rows ? (int64_t)a.a_rows[0] : 0);
+        return (r * a.lda + ld_c * EPV) * ES;
+    };
+    const int64_t ao0 = a_row(0), ao1 = a_row(1), ao2 = a_row(2), ao3 = a_row(3);
+    const int64_t bo0 = ((int64_t)(n0 + ld_row) * a.ldb + ld_c * EPV) * ES;
+    const int n_steps = k_slices * ((a.n_src == 2 && m0 >= a.M1) ? 1 : a.n_src);   // a tile past M1 has one source only
+    // rows of this thread's chunks that lie at or past M1: their second-source data is zeroed on its way to LDS
+    const bool z0 = m0 + ld_row >= a.M1, z1 = m0 + ld_row + 32 >= a.M1, z2 = m0 + ld_row + 64 >= a.M1, z3 = m0 + ld_row + 96 >= a.M1;
+
+    v16f acc[MT][NT];
+    // plain variables filled and drained by macros, as in the wide variant: one register set for the slice in flight,
+    // two fragment sets (f0, f1) for alternating quarters of a slice
+    u32x4 ax0, ax1, ax2, ax3;
+    u32x4 bx0, bx1, bx2, bx3, bx4, bx5, bx6, bx7;
+    u32x4 f0a0, f0a1, f0b0, f0b1, f0b2, f0b3, f1a0, f1a1, f1b0, f1b1, f1b2, f1b3;
+    f0b1 = f0b2 = f0b3 = (u32x4){0u, 0u, 0u, 0u};
+    f1a0 = f1a1 = f1b0 = f1b1 = f1b2 = f1b3 = (u32x4){0u, 0u, 0u, 0u};
+    bx4 = bx5 = bx6 = bx7 = (u32x4){0u, 0u, 0u, 0u};
+// a fetch beyond the last slice repeats the last one (a cache hit; what it brings is stashed but never multiplied)
+#define GNN_FETCH(step_)                                                           \
+    {                                                                              \
+        const int st_ = (step_) < n_steps ? (step_) : n_steps - 1;                 \
+        const int src_ = st_ >= k_slices ? 1 : 0;                                  \
+        const int64_t kb_ = (int64_t)(st_ - src_ * k_slices) * 128;                \
+        const char* Ab_ = (const char*)(src_ ? a.A[1] : a.A[0]) + kb_;             \
+        const char* Bb_ = (const char*)(src_ ? a.Bt[1] : a.Bt[0]) + kb_ + bo0;     \
+        ax0 = *(const u32x4*)(Ab_ + ao0);                                          \
+        ax1 = *(const u32x4*)(Ab_ + ao1);                                          \
+        ax2 = *(const u32x4*)(Ab_ + ao2);                                          \
+        ax3 = *(const u32x4*)(Ab_ + ao3);                                          \
+        bx0 = *(const u32x4*)(Bb_);                                                \
+        bx1 = *(const u32x4*)(Bb_ + b_band);                                       \
+        bx2 = *(const u32x4*)(Bb_ + 2 * b_band);                                   \
+        bx3 = *(const u32x4*)(Bb_ + 3 * b_band);                                   \
+        if (B_CH > 4) {                                                            \
+            bx4 = *(const u32x4*)(Bb_ + 4 * b_band);                               \
+            bx5 = *(const u32x4*)(Bb_ + 5 * b_band);                               \
+            bx6 = *(const u32x4*)(Bb_ + 6 * b_band);                               \
+            bx7 = *(const u32x4*)(Bb_ + 7 * b_band);                               \
+        }                                                                          \
+    }
+#define GNN_STASH(step_)                                                           \
+    {                                                                              \
+        const int sq_ = (step_) < n_steps ? (step_) : n_steps - 1;                 \
+        const bool s1_ = sq_ >= k_slices;                                          \
+        *(u32x4*)&smem[st_off] = (s1_ && z0) ? (u32x4){0u, 0u, 0u, 0u} : ax0;      \
+        *(u32x4*)&smem[1024 + st_off] = (s1_ && z1) ? (u32x4){0u, 0u, 0u, 0u} : ax1; \
+        *(u32x4*)&smem[2048 + st_off] = (s1_ && z2) ? (u32x4){0u, 0u, 0u, 0u} : ax2; \
+        *(u32x4*)&smem[3072 + st_off] = (s1_ && z3) ? (u32x4){0u, 0u, 0u, 0u} : ax3; \
+        *(u32x4*)&smem[BM * 32 + st_off] = bx0;                                    \
+        *(u32x4*)&smem[BM * 32 + 1024 + st_off] = bx1;                             \
+        *(u32x4*)&smem[BM * 32 + 2048 + st_off] = bx2;                             \
+        *(u32x4*)&smem[BM * 32 + 3072 + st_off] = bx3;                             \
+        if (B_CH > 4) {                                                            \
+            *(u32x4*)&smem[BM * 32 + 4096 + st_off] = bx4;                         \
+            *(u32x4*)&smem[BM * 32 + 5120 + st_off] = bx5;                         \
+            *(u32x4*)&smem[BM * 32 + 6144 + st_off] = bx6;                         \
+            *(u32x4*)&smem[BM * 32 + 7168 + st_off] = bx7;                         \
+        }                                                                          \
+    }
+    // fragments: row (.. + li), chunk g*4 + q of the slice for quarter q (the same permutation of the reduction index
+    // in both operands, which leaves the product unchanged)
+    const int sw = (li >> 1) & 7;
+    const int fa_off = (wm * 64 + li) * 32, fb_off = BM * 32 + (wn * WTN + li) * 32;
+#define GNN_READ(F, q_)                                                            \
+    {                                                                              \
+        const int slot_ = ((g * 4 + (q_)) ^ sw) << 2;                              \
+        F##a0 = *(const u32x4*)&smem[fa_off + slot_];                              \
+        F##a1 = *(const u32x4*)&smem[fa_off + 1024 + slot_];                       \
+        F##b0 = *(const u32x4*)&smem[fb_off + slot_];                              \
+        if (NT > 1) F##b1 = *(const u32x4*)&smem[fb_off + 1024 + slot_];           \
+        if (NT > 2) {                                                              \
+            F##b2 = *(const u32x4*)&smem[fb_off + 2048 + slot_];                   \
+            F##b3 = *(const u32x4*)&smem[fb_off + 3072 + slot_];                   \
+        }                                                                          \
+    }
+    auto mma = [&](v16f& c, const u32x4& x, const u32x4& y) {
+        if (DT == GNN_F32) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(x[t]), __uint_as_float(y[t]), c, 0, 0, 0);
+        } else {
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, x), __builtin_bit_cast(v8bf, y), c, 0, 0, 0);
+        }
+    };
+#define GNN_MMA(F)                                                                 \
+    {                                                                              \
+        mma(acc[0][0], F##b0, F##a0);                                              \
+        mma(acc[1][0], F##b0, F##a1);                                              \
+        if (NT > 1) {                                                              \
+            mma(acc[0][NT > 1 ? 1 : 0], F##b1, F##a0);                             \
+            mma(acc[1][NT > 1 ? 1 : 0], F##b1, F##a1);                             \
+        }                                                                          \
+        if (NT > 2) {                                                              \
+            mma(acc[0][NT > 2 ? 2 : 0], F##b2, F##a0);                             \
+            mma(acc[1][NT > 2 ? 2 : 0], F##b2, F##a1);                             \
+            mma(acc[0][NT > 2 ? 3 : 0], F##b3, F##a0);                             \
+            mma(acc[1][NT > 2 ? 3 : 0], F##b3, F##a1);                             \
+        }                                                                          \
+    }
+// the four quarters of the slice in LDS: the first fragments (f0) are on their way; f1 still holds the last quarter
+// of the slice before
+#define GNN_QUARTERS                                                               \
+    {                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_MMA(f1)                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_READ(f1, 1)                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_MMA(f0)                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_READ(f0, 2)                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_MMA(f1)                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_READ(f1, 3)                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+        GNN_MMA(f0)                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                         \
+    }
+    // invariant at the top of step s: LDS holds slice s (visible to all waves), the register set is free, f1 holds the
+    // last quarter of slice s-1 (zeros at first).  Nothing in a step is conditional (see the wide variant).
+    GNN_FETCH(0)
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    f1a0 = f1a1 = f1b0 = f1b1 = f1b2 = f1b3 = (u32x4){0u, 0u, 0u, 0u};
+    s_bias[tid & (BN - 1)] = a.bias ? a.bias[n0 + (tid & (BN - 1))] : 0.f;   // arrives with the slice the stash waits for
+    {
+        const int m = m0 + (tid & (BM - 1));
+        s_crow[tid & (BM - 1)] = m < a.M ? (a.c_rows ? a.c_rows[m] : m) : -1;   // -1: a row past M, never stored
+    }
+    GNN_STASH(0)
+    __syncthreads();
+    for (int s = 0; s < n_steps; ++s) {
+        GNN_READ(f0, 0)
+        GNN_FETCH(s + 1)
+        GNN_QUARTERS
+        __syncthreads();          // every wave has taken its fragments of slice s
+        GNN_STASH(s + 1)
+        __syncthreads();
+    }
+    GNN_MMA(f1)
+
+    // Epilogue.  The MFMAs ran with the operands exchanged (the weights' rows as the first operand): acc[i][j][r] is
+    // C[row li][column (r/4)*8 + g*4 + r%4] of its 32x32 block, four consecutive columns per lane and r/4.  A piece of
+    // 32 rows x CW columns is laid out row-major in the wave's part of LDS with 8- or 16-byte writes (bias, ReLU and
+    // rounding applied) and written to memory with 16-byte stores, up to 256 contiguous bytes per row.
+    uint32_t* stg = smem + wave * STAGE;
+    constexpr int JP = CW / 32;            // 32-column blocks per piece
+    constexpr int CPR = CW * ES / 16;      // 16-byte chunks per staged row
+    constexpr int RPP = 64 / CPR;          // rows written per pass of the wave
+    // what the epilogue needs from LDS is asked for in batches ahead of its use: a read issued right before its
+    // use costs one LDS round trip each time, and sixteen of those in a row were most of the epilogue
+    float4 bvs[NT][4];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bvs[j][q] = *(const float4*)&s_bias[wn * WTN + j * 32 + q * 8 + g * 4];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int p = 0; p < NT / JP; ++p) {
+#pragma unroll
+            for (int jj = 0; jj < JP; ++jj) {
+                const int j = p * JP + jj;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c = q * 8 + g * 4;     // first of this lane's four consecutive columns of the block
+                    const float4 bv = bvs[j][q];
+                    float v0 = acc[i][j][q * 4 + 0] + bv.x, v1 = acc[i][j][q * 4 + 1] + bv.y;
+                    float v2 = acc[i][j][q * 4 + 2] + bv.z, v3 = acc[i][j][q * 4 + 3] + bv.w;
+                    if (a.relu) {
+                        v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
+                    }
+                    if (DT == GNN_F32) {
+                        *(uint4*)&stg[li * CROW + jj * 32 + c] = make_uint4(__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3));
+                    } else {
+                        *(uint2*)&stg[li * CROW + jj * 16 + (c >> 1)] = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+                    }
+                }
+            }
+            __syncthreads();
+            constexpr int NP = 32 / RPP;   // passes of the wave over the piece
+            const int n = n0 + wn * WTN + p * CW + (lane % CPR) * EPV;
+            int32_t crs[NP];
+            uint4 vs[NP];
+#pragma unroll
+            for (int pass = 0; pass < NP; ++pass) {
+                const int row = pass * RPP + lane / CPR;
+                crs[pass] = s_crow[wm * 64 + i * 32 + row];
+                vs[pass] = *(const uint4*)&stg[row * CROW + (lane % CPR) * 4];
+            }
+            // 16-byte stores only: the launcher sends other layouts to the wide variant
+            if (a.mask) {
+                // the activation mask (and, for the rows that accumulate, what C holds) of all passes first, then the
+                // stores: a load between two stores would wait for the store before it
+                uint4 hs[NP], os[NP];
+#pragma unroll
+                for (int pass = 0; pass < NP; ++pass) {
+                    const int64_t crow = crs[pass] >= 0 ? crs[pass] : 0;      // a row past M reads an addressable row
+                    const int m = m0 + wm * 64 + i * 32 + pass * RPP + lane / CPR;
+                    hs[pass] = *(const uint4*)((const char*)a.mask + (crow * a.ldm + n) * ES);
+                    os[pass] = make_uint4(0u, 0u, 0u, 0u);
+                    if (m < a.n_acc) os[pass] = *(const uint4*)((const char*)a.C + (crow * a.ldc + n) * ES);
+                }
+#pragma unroll
+                for (int pass = 0; pass < NP; ++pass) {
+                    const int m = m0 + wm * 64 + i * 32 + pass * RPP + lane / CPR;
+                    vs[pass] = post_apply<DT>(vs[pass], os[pass], m < a.n_acc, hs[pass]);
+                }
+            }
+#pragma unroll
+            for (int pass = 0; pass < NP; ++pass) {
+                const int64_t crow = crs[pass];
+                if (crow >= 0) *(uint4*)((char*)a.C + (crow * a.ldc + n) * ES) = vs[pass];
+            }
+            __syncthreads();
+        }
+    }
+#undef GNN_FETCH
+#undef GNN_STASH
+#undef GNN_READ
+#undef GNN_MMA
+#undef GNN_QUARTERS
+}
+
 template <int DT>
 static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
     if (a.M <= 0 || a.N <= 0) return GNN_OK;
@@ -720,6 +1033,23 @@ static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
         // a reduction of one or two slices (an input gradient from 32 or 41 class scores) is all prologue and epilogue:
         // narrow tiles keep more workgroups on a CU to hide those latencies, and re-reading the short rows costs little
         if ((int64_t)a.K * a.n_src * DTy<DT>::ES <= 128) ntw = 1;
+        // whole cache lines per step where the shapes allow it (see gemm_nt_line_kernel)
+#ifndef GNN_NT_LINE
+#define GNN_NT_LINE 1
+#endif
+// fp32 products are bound by the fp32 MFMA rate, not by requests or the epilogue: the line tile changed none of
+// their durations (configs[1] and [2]), so they stay on the wide variant
+#ifndef GNN_NT_LINE_F32
+#define GNN_NT_LINE_F32 0
+#endif
+        if constexpr (GNN_NT_LINE && (DT == GNN_BF16 || GNN_NT_LINE_F32))
+        if ((int64_t)a.K * DTy<DT>::ES % 128 == 0 && ntw > 1 && a.N % (64 * ntw) == 0 && a.c_vec && (!a.mask || a.m_vec)) {
+            const unsigned lgrid = (unsigned)(tiles_m * (a.N / (64 * ntw)));
+            if (ntw == 4) gemm_nt_line_kernel<DT, 4><<<lgrid, 256, 0, stream>>>(a);
+            else gemm_nt_line_kernel<DT, 2><<<lgrid, 256, 0, stream>>>(a);
+            GNN_LAUNCH_CHECK("gemm_nt_line_kernel");
+            return GNN_OK;
+        }
         const unsigned grid = (unsigned)(tiles_m * (ntw == 4 ? p256 / 256 : (ntw == 2 ? p128 / 128 : p64 / 64)));
         const bool ktail = a.K % (64 / DTy<DT>::ES) != 0;
 #define GNN_WIDE(NTW_)                                                                                  \

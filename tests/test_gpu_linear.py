@@ -77,7 +77,7 @@ def _case(M_total, n_active, K, N, dtype, sage, relu, use_rows, aligned, seed, n
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("K,N", [(64, 64), (64, 8), (602, 256), (100, 256), (256, 47), (128, 16), (256, 41), (33, 5), (128, 128),
-                                 (256, 256), (128, 256), (96, 160), (608, 256)])
+                                 (256, 256), (128, 256), (96, 160), (608, 256), (512, 512), (192, 128), (64, 256)])
 def test_shapes_of_the_workloads(dtype, K, N):
     _case(3000, 1777, K, N, dtype, sage=(K != 100 and K != 64), relu=(N > 50), use_rows=True, aligned=True, seed=K + N)
 
