@@ -507,6 +507,10 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
     constexpr int STAGE = 32 * CROW;               // words per wave
     constexpr int SMEM = 2 * BUF > 4 * STAGE ? 2 * BUF : 4 * STAGE;
     __shared__ __attribute__((aligned(16))) uint32_t smem[SMEM];
+    // bias values and output rows of the tile, put here at the start: a load from global memory inside the epilogue
+    // waits for the stores issued before it (see the line variant)
+    __shared__ float s_bias[BN];
+    __shared__ int32_t s_crow[BM];
 
     const int tiles_n = (a.N + BN - 1) / BN;
     const int m0 = (int)(blockIdx.x / tiles_n) * BM, n0 = (int)(blockIdx.x % tiles_n) * BN;
@@ -658,6 +662,11 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
     // slice s+1 (possibly still in flight), register set s%2 is free, f1 holds the second half of slice s-1 (zeros at first)
     GNN_FETCH(0, 0)
     GNN_FETCH(1, 1)
+    {
+        const int n = n0 + (tid & (BN - 1)), m = m0 + (tid & (BM - 1));
+        s_bias[tid & (BN - 1)] = (a.bias && n < a.N) ? a.bias[n] : 0.f;
+        s_crow[tid & (BM - 1)] = m < a.M ? (a.c_rows ? a.c_rows[m] : m) : -1;   // -1: a row past M, never stored
+    }
     GNN_STASH(buf0, 0, 0)
     __syncthreads();
     const int n_pairs = n_steps >> 1;
@@ -688,8 +697,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
 #pragma unroll
             for (int jj = 0; jj < JP; ++jj) {
                 const int j = p * JP + jj;
-                const int n = n0 + wn * WTN + j * 32 + li;
-                const float bv = (a.bias && n < a.N) ? a.bias[n] : 0.f;
+                const float bv = s_bias[wn * WTN + j * 32 + li];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = (r >> 2) * 8 + g * 4 + (r & 3);
@@ -705,8 +713,8 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_wide_kernel(GemmNT a) {
                 const int row = pass * RPP + lane / CPR, ch = lane % CPR;
                 const int m = m0 + wm * 64 + i * 32 + row;
                 const int n = n0 + wn * WTN + p * CW + ch * EPV;
-                if (m < a.M && n < a.N) {
-                    const int64_t crow = a.c_rows ? (int64_t)a.c_rows[m] : (int64_t)m;
+                const int64_t crow = s_crow[wm * 64 + i * 32 + row];
+                if (crow >= 0 && n < a.N) {
                     uint4 v = *(const uint4*)&stg[row * CROW + ch * 4];
                     char* dst = (char*)a.C + (crow * a.ldc + n) * ES;
                     if (n + EPV <= a.N && a.c_vec && (!a.mask || a.m_vec)) {
