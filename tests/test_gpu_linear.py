@@ -203,7 +203,7 @@ def test_bias_grad(dtype, N, ld):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("K,N", [(256, 41), (256, 32), (128, 16), (256, 256), (96, 47), (40, 7)])
+@pytest.mark.parametrize("K,N", [(256, 41), (256, 32), (128, 16), (256, 256), (96, 47), (40, 7), (512, 128), (128, 64)])
 def test_input_gradient_product_with_sum_and_mask_in_its_store(dtype, K, N):
     """gnn_linear_bwd_input: dX = [H > 0] * (dZ W^T + dX on the first n_accumulate listed rows).  The product comes from
     the oracle's feature-transform backward, the sum and the mask are written out here."""
@@ -244,7 +244,7 @@ def test_input_gradient_product_with_sum_and_mask_in_its_store(dtype, K, N):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("K,N", [(128, 128), (256, 256), (256, 41), (128, 16), (96, 47), (40, 7), (602, 256)])
+@pytest.mark.parametrize("K,N", [(128, 128), (256, 256), (256, 41), (128, 16), (96, 47), (40, 7), (602, 256), (512, 256), (128, 192)])
 def test_input_gradient_from_the_aggregated_gradient(dtype, K, N):
     """gnn_linear_bwd_input2: dX = [H > 0] * (dG W_neigh^T + dZ W_self^T on the first n_self listed rows).  Both products
     come from the oracle's feature-transform backward; the sum, the row limit and the mask are written out here.  The rows
