@@ -1092,6 +1092,11 @@ static int32_t launch_gemm_nt(const GemmNT& a, hipStream_t stream) {
 // ------------------------------------------------------------------------------------------
 // gemm_tn : P[split][src*K + k][n] = sum_{m in split} A_src[row(m)][k] * D[m][n]
 // ------------------------------------------------------------------------------------------
+// Output tiles of the weight-gradient product are 128 x 256 instead of 128 x 128 where the width allows it (bf16: the
+// fp32 product is bound by its MFMAs): the kernel runs at the rate its operand slabs come from L2 - 9.3 TB/s at every
+// shape measured - and a slab of A is then fetched by one workgroup per split instead of two.
+static inline bool tn_wide_columns(int dtype, int32_t N) { return dtype == GNN_BF16 && N >= 256 && N % 256 == 0; }
+
 struct GemmTN {
     const void* A[2];
     int32_t n_src;
@@ -1109,10 +1114,10 @@ struct GemmTN {
 };
 
 template <int DT, int BN, bool VEC>
-__global__ __launch_bounds__(256, 3) void gemm_tn_kernel(GemmTN a) {
+__global__ __launch_bounds__(256, BN == 256 ? 2 : 3) void gemm_tn_kernel(GemmTN a) {
     constexpr int BKO = 128, BMR = 32;
     constexpr int EPV = DTy<DT>::EPV;
-    constexpr int WKO = BN == 128 ? 2 : 4, WNN = 4 / WKO;      // waves along k-out and n
+    constexpr int WKO = BN >= 128 ? 2 : 4, WNN = 4 / WKO;      // waves along k-out and n
     constexpr int WTK = BKO / WKO, WTN = BN / WNN, MT = WTK / 32, NT = WTN / 32;
     constexpr int A_VPR = BKO / EPV;                 // 16-byte vectors per tile row
     constexpr int D_VPR = BN / EPV;
@@ -1521,6 +1526,11 @@ static int32_t linear_bwd_impl(const int32_t* rows, int32_t M, const void* dH, c
         const int64_t total = (int64_t)t.n_src * ko_tiles * splits;
         if (t.a_vec && t.d_vec) gemm_tn_kernel<DT, 64, true><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
         else gemm_tn_kernel<DT, 64, false><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
+    } else if (tn_wide_columns(DT, N) && t.a_vec && t.d_vec) {
+        if constexpr (DT == GNN_BF16) {
+            const int64_t total = (int64_t)t.n_src * ko_tiles * (N / 256) * splits;
+            gemm_tn_kernel<DT, 256, true><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
+        }
     } else if (N > 32) {
         const int64_t total = (int64_t)t.n_src * ko_tiles * ((N + 127) / 128) * splits;
         if (t.a_vec && t.d_vec) gemm_tn_kernel<DT, 128, true><<<(unsigned)((total + 7) / 8 * 8), 256, 0, stream>>>(t);
@@ -1671,8 +1681,9 @@ extern "C" int32_t gnn_linear_bwd(const int32_t* rows, int32_t n_active, const v
     // and no more (256 CUs: 768 workgroups; the splits are equally long, so a second, partly filled round of workgroups
     // would cost a whole round: 1024 workgroups took 2 rounds where 768 take 1.33 of the old round's length), at least
     // 256 rows each, at most 256 splits and 128 MB of partial tiles
-    const int tiles = n_src * ((K + 127) / 128) * (N > 32 ? (N + 127) / 128 : 1);
-    int32_t splits = 768 / tiles;
+    const bool wide_n = tn_wide_columns(dtype, N) && vec_ok(A_neigh, ld_in, es) && (!X_self || vec_ok(X_self, ld_in, es));
+    const int tiles = n_src * ((K + 127) / 128) * (wide_n ? N / 256 : (N > 32 ? (N + 127) / 128 : 1));
+    int32_t splits = (wide_n ? 512 : 768) / tiles;   // two workgroups of the 256-column tile fit a CU, three of the others
     const int32_t max_splits = n_active > 0 ? (n_active + 255) / 256 : 1;
     const int64_t split_bytes = (int64_t)n_src * K * N * 4;
     if (splits > max_splits) splits = max_splits;
